@@ -1,0 +1,247 @@
+"""CPU oracle: operator-at-a-time evaluation of one `for` loop over zipped columns.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
+fused loop must return.  It is imported by the tests, by the smoke check and by
+the benchmark's cpu_baseline leg, never by the product library, and it shares
+no code with the HIP path.
+
+What it follows (paper, Sec. 3.2 and Table 1; Sec. 3.3 for the macros):
+  * `for(vectors, builders, func)` applies func to every index i and the
+    struct of the i-th elements of the zipped vectors.
+  * each expression of the body is evaluated here for ALL rows before the next
+    one starts, producing a full intermediate column: this is the unfused
+    `map` / `filter` / `reduce` form which the fused loop must equal
+    (Listing "combined program" == Listing "after loop fusion", Sec. 4.5).
+  * `if (p) merge(b, v) else b`  ==  merge of the rows where column p is true.
+  * merger[T,func,id]: fold of the merged values with func, starting at id.
+  * vecbuilder[T]: the merged values appended, i.e. the selected subsequence
+    in index order (all three printed examples keep index order).
+  * dictmerger[K,V,func]: first merge of a key stores the value, later ones
+    combine with func, field by field when V is a struct.
+
+Readings where the paper is silent: integers wrap modulo 2^w; integer div/mod
+truncate toward zero (C); no implicit promotion (a `cast` op is required); f64
+is IEEE round-to-nearest with one rounding per operator and no contraction;
+dictionary entries are returned sorted by key (the paper leaves them
+unordered, so callers compare sorted).
+
+Parity pins live in tests/test_oracle_pins.py (paper-printed results, closed
+forms, brute force against oracle/rowwise.py, library routines, exact sums).
+Black-Scholes prices have no printed value in the paper: they are pinned by
+put-call parity, bounds and a decimal-arithmetic evaluation of the formula;
+agreement of erf/exp/log with higher precision is checked on samples only.
+"""
+import math
+
+import numpy as np
+from scipy import special as _special
+
+NP_TYPE = {"bool": np.bool_, "i8": np.int8, "i32": np.int32, "i64": np.int64,
+           "f64": np.float64}
+INT_TYPES = ("i8", "i32", "i64")
+
+_COMPARE = {"lt": np.less, "le": np.less_equal, "gt": np.greater,
+            "ge": np.greater_equal, "eq": np.equal, "ne": np.not_equal}
+
+
+def identity(func, t):
+    """Identity element of a merger function for type t (Sec. 3.2: merger[T,func,id])."""
+    dt = NP_TYPE[t]
+    if func == "add":
+        return dt(0)
+    if func == "mul":
+        return dt(1)
+    if t == "f64":
+        return dt(np.inf) if func == "min" else dt(-np.inf)
+    info = np.iinfo(dt)
+    return dt(info.max) if func == "min" else dt(info.min)
+
+
+def _trunc_div(a, b):
+    """Integer quotient rounded toward zero, exact in the operand type."""
+    r = np.fmod(a, b)
+    return (a - r) // b
+
+
+def eval_columns(program, columns):
+    """Materialise every body expression as a full column (one operator at a time)."""
+    n = len(columns[0]) if columns else 0
+    for k, c in enumerate(columns):
+        assert c.dtype == NP_TYPE[program.columns[k]], (k, c.dtype)
+        assert len(c) == n
+    val = []
+    with np.errstate(all="ignore"):
+        for op in program.ops:
+            code, t = op[0], op[1]
+            dt = NP_TYPE[t]
+            a = [val[j] for j in op[2:]] if code not in ("col", "const", "index") else None
+            if code == "col":
+                out = columns[op[2]]
+            elif code == "const":
+                out = np.full(n, op[2], dtype=dt)
+            elif code == "index":
+                out = np.arange(n, dtype=np.int64)
+            elif code == "neg":
+                out = np.negative(a[0])
+            elif code == "not":
+                out = np.logical_not(a[0])
+            elif code == "cast":
+                src = a[0]
+                if src.dtype == np.float64 and t in INT_TYPES:
+                    out = np.trunc(src).astype(np.int64).astype(dt)
+                else:
+                    out = src.astype(dt)
+            elif code == "exp":
+                out = np.exp(a[0])
+            elif code == "log":
+                out = np.log(a[0])
+            elif code == "sqrt":
+                out = np.sqrt(a[0])
+            elif code == "erf":
+                out = _special.erf(a[0])
+            elif code == "add":
+                out = np.add(a[0], a[1])
+            elif code == "sub":
+                out = np.subtract(a[0], a[1])
+            elif code == "mul":
+                out = np.multiply(a[0], a[1])
+            elif code == "div":
+                out = np.divide(a[0], a[1]) if t == "f64" else _trunc_div(a[0], a[1])
+            elif code == "mod":
+                out = np.fmod(a[0], a[1])
+            elif code == "min":
+                out = np.minimum(a[0], a[1])
+            elif code == "max":
+                out = np.maximum(a[0], a[1])
+            elif code in _COMPARE:
+                assert a[0].dtype == a[1].dtype, "compare needs equal types"
+                out = _COMPARE[code](a[0], a[1])
+            elif code == "and":
+                out = np.logical_and(a[0], a[1])
+            elif code == "or":
+                out = np.logical_or(a[0], a[1])
+            elif code == "select":
+                out = np.where(a[0], a[1], a[2])
+            else:
+                raise ValueError("unknown op " + code)
+            out = np.asarray(out)
+            assert out.dtype == dt, (code, t, out.dtype)
+            val.append(out)
+    return val
+
+
+def exact_sum(v):
+    """The real-number sum of the doubles in v, rounded once to f64.
+
+    math.fsum is exactly rounded.  For very long inputs an extended-precision
+    (x87 80-bit) pairwise sum is used instead; its error, about log2(n) * 2^-64
+    relative to sum|v|, is far below one f64 rounding for the positive data used
+    here (pinned against math.fsum in the tests).
+    """
+    if v.size <= 20_000_000:
+        return np.float64(math.fsum(v.tolist() if v.size < 1_000_000 else v))
+    return np.float64(np.sum(v, dtype=np.longdouble))
+
+
+def _fold(func, t, v, sums):
+    """merger: acc = func(acc, v[i]) over the merged values in index order."""
+    ident = identity(func, t)
+    if v.size == 0:
+        return ident
+    with np.errstate(all="ignore"):
+        if func == "add":
+            if t == "f64":
+                if sums == "exact":
+                    return exact_sum(v)
+                return np.float64(np.cumsum(v)[-1])
+            return np.add.reduce(v, dtype=v.dtype)
+        if func == "mul":
+            return np.multiply.accumulate(v, dtype=v.dtype)[-1]
+        if func == "min":
+            return np.minimum.reduce(v)
+        return np.maximum.reduce(v)
+
+
+_REDUCEAT = {"add": np.add, "mul": np.multiply, "min": np.minimum, "max": np.maximum}
+
+
+def _group(func, key_cols, val_cols, val_types, sums):
+    """dictmerger: combine values of equal keys; entries returned sorted by key."""
+    m = len(key_cols[0])
+    if m == 0:
+        return ([k[:0] for k in key_cols], [v[:0] for v in val_cols])
+    order = np.lexsort(tuple(reversed(key_cols)))          # stable: index order within a key
+    ks = [k[order] for k in key_cols]
+    change = np.zeros(m, dtype=bool)
+    change[0] = True
+    for k in ks:
+        change[1:] |= k[1:] != k[:-1]
+    starts = np.flatnonzero(change)
+    ends = np.append(starts[1:], m)
+    out_keys = [k[starts] for k in ks]
+    out_vals = []
+    with np.errstate(all="ignore"):
+        for v, t in zip(val_cols, val_types):
+            vs = v[order]
+            if func == "add" and t == "f64":
+                if sums == "exact":
+                    out_vals.append(np.array([exact_sum(vs[s:e]) for s, e in zip(starts, ends)],
+                                             dtype=np.float64))
+                else:
+                    out_vals.append(np.array([np.cumsum(vs[s:e])[-1] for s, e in zip(starts, ends)],
+                                             dtype=np.float64))
+            else:
+                out_vals.append(_REDUCEAT[func].reduceat(vs, starts, dtype=v.dtype))
+    return (out_keys, out_vals)
+
+
+def run(program, columns, sums="exact"):
+    """Evaluate the loop; returns one result per builder, in builder order.
+
+    merger      -> numpy scalar of its type
+    vecbuilder  -> 1-d numpy array
+    dictmerger  -> (list of key columns, list of value columns), sorted by key
+
+    sums = "exact": an f64 `add` returns the correctly rounded real sum (any
+    merge order is legal, Sec. 3.2, so this is the value every order
+    approximates);  sums = "fold": the literal left-to-right f64 fold.
+    """
+    val = eval_columns(program, columns)
+    n = len(columns[0]) if columns else 0
+    results = [None] * len(program.builders)
+    merged = set()
+    for m in program.merges:
+        b = m["builder"]
+        assert b not in merged, "a builder may be merged once per control path"
+        merged.add(b)
+        spec = program.builders[b]
+        mask = val[m["pred"]] if m["pred"] is not None else np.ones(n, dtype=bool)
+        assert mask.dtype == np.bool_
+        if spec["kind"] == "merger":
+            v = val[m["vals"][0]][mask]
+            assert v.dtype == NP_TYPE[spec["type"]]
+            results[b] = _fold(spec["func"], spec["type"], v, sums)
+        elif spec["kind"] == "vecbuilder":
+            v = val[m["vals"][0]]
+            assert v.dtype == NP_TYPE[spec["type"]]
+            results[b] = v[mask].copy()
+        elif spec["kind"] == "dictmerger":
+            kc = [val[k][mask] for k in m["keys"]]
+            vc = [val[v][mask] for v in m["vals"]]
+            for c, t in zip(kc, spec["key_types"]):
+                assert c.dtype == NP_TYPE[t]
+            for c, t in zip(vc, spec["val_types"]):
+                assert c.dtype == NP_TYPE[t]
+            results[b] = _group(spec["func"], kc, vc, spec["val_types"], sums)
+        else:
+            raise ValueError(spec["kind"])
+    for b, spec in enumerate(program.builders):
+        if results[b] is None:                      # never merged: result(b) of a fresh builder
+            if spec["kind"] == "merger":
+                results[b] = identity(spec["func"], spec["type"])
+            elif spec["kind"] == "vecbuilder":
+                results[b] = np.zeros(0, dtype=NP_TYPE[spec["type"]])
+            else:
+                results[b] = ([np.zeros(0, NP_TYPE[t]) for t in spec["key_types"]],
+                              [np.zeros(0, NP_TYPE[t]) for t in spec["val_types"]])
+    return results

@@ -1,0 +1,161 @@
+"""CPU oracle, second form: the literal per-row `for` loop (pure Python).
+
+TEST INFRASTRUCTURE ONLY; for tiny inputs.  Shares no code with the HIP path
+and none with oracle/interp.py either: integers are Python ints wrapped by
+hand, doubles are Python floats, math functions come from `math` (libm).
+
+Follows Sec. 3.2 of the paper to the letter: for i = 0..n-1, call func with
+(builders, i, struct of the i-th elements); func evaluates its whole body for
+that one row and merges into each builder at most once.  Builders are kept as
+mutable state, which the linearity rule of Sec. 3.2 makes legal.
+
+It is used (a) as brute force against which interp.py is pinned, and (b) for the
+fused == unfused invariant (one pass over rows here, one pass per operator
+there; Sec. 4.5, the combined program versus the loop after fusion).
+"""
+import math
+
+BITS = {"i8": 8, "i32": 32, "i64": 64}
+
+
+def _wrap(x, t):
+    w = BITS[t]
+    x &= (1 << w) - 1
+    return x - (1 << w) if x >> (w - 1) else x
+
+
+def _tdiv(a, b):
+    q = abs(a) // abs(b)
+    return q if (a < 0) == (b < 0) else -q
+
+
+def _tmod(a, b):
+    return a - _tdiv(a, b) * b
+
+
+def _apply(code, t, a):
+    isint = t in BITS
+    if code == "neg":
+        return _wrap(-a[0], t) if isint else -a[0]
+    if code == "not":
+        return not a[0]
+    if code == "exp":
+        return math.exp(a[0])
+    if code == "log":
+        return math.log(a[0])
+    if code == "sqrt":
+        return math.sqrt(a[0])
+    if code == "erf":
+        return math.erf(a[0])
+    if code == "add":
+        return _wrap(a[0] + a[1], t) if isint else a[0] + a[1]
+    if code == "sub":
+        return _wrap(a[0] - a[1], t) if isint else a[0] - a[1]
+    if code == "mul":
+        return _wrap(a[0] * a[1], t) if isint else a[0] * a[1]
+    if code == "div":
+        return _wrap(_tdiv(a[0], a[1]), t) if isint else a[0] / a[1]
+    if code == "mod":
+        return _tmod(a[0], a[1]) if isint else math.fmod(a[0], a[1])
+    if code == "min":
+        return a[0] if a[0] <= a[1] else a[1]
+    if code == "max":
+        return a[0] if a[0] >= a[1] else a[1]
+    if code == "lt":
+        return a[0] < a[1]
+    if code == "le":
+        return a[0] <= a[1]
+    if code == "gt":
+        return a[0] > a[1]
+    if code == "ge":
+        return a[0] >= a[1]
+    if code == "eq":
+        return a[0] == a[1]
+    if code == "ne":
+        return a[0] != a[1]
+    if code == "and":
+        return bool(a[0]) and bool(a[1])
+    if code == "or":
+        return bool(a[0]) or bool(a[1])
+    if code == "select":
+        return a[1] if a[0] else a[2]
+    raise ValueError(code)
+
+
+def _cast(x, src, dst):
+    if dst == "bool":
+        return bool(x)
+    if dst == "f64":
+        return float(x)
+    if src == "f64":
+        return _wrap(int(x), dst)          # int() truncates toward zero
+    return _wrap(int(x), dst)
+
+
+def _combine(func, t, acc, v):
+    if func == "add":
+        return _wrap(acc + v, t) if t in BITS else acc + v
+    if func == "mul":
+        return _wrap(acc * v, t) if t in BITS else acc * v
+    if func == "min":
+        return v if v < acc else acc
+    return v if v > acc else acc
+
+
+def _identity(func, t):
+    if func == "add":
+        return 0 if t in BITS else 0.0
+    if func == "mul":
+        return 1 if t in BITS else 1.0
+    if t in BITS:
+        w = BITS[t]
+        return (1 << (w - 1)) - 1 if func == "min" else -(1 << (w - 1))
+    return math.inf if func == "min" else -math.inf
+
+
+def run(program, columns):
+    """columns: list of Python lists (ints / floats).  Returns Python values:
+    merger -> number, vecbuilder -> list, dictmerger -> {key tuple: [values]}."""
+    n = len(columns[0]) if columns else 0
+    state = []
+    for spec in program.builders:
+        if spec["kind"] == "merger":
+            state.append(_identity(spec["func"], spec["type"]))
+        elif spec["kind"] == "vecbuilder":
+            state.append([])
+        else:
+            state.append({})
+    for i in range(n):
+        val = []
+        for op in program.ops:                     # the whole body, for this row only
+            code, t = op[0], op[1]
+            if code == "col":
+                x = columns[op[2]][i]
+                val.append(float(x) if t == "f64" else (bool(x) if t == "bool" else int(x)))
+            elif code == "const":
+                val.append(float(op[2]) if t == "f64" else (bool(op[2]) if t == "bool" else int(op[2])))
+            elif code == "index":
+                val.append(i)
+            elif code == "cast":
+                val.append(_cast(val[op[2]], program.ops[op[2]][1], t))
+            else:
+                val.append(_apply(code, t, [val[j] for j in op[2:]]))
+        for m in program.merges:
+            if m["pred"] is not None and not val[m["pred"]]:
+                continue                            # `else b`: builder returned untouched
+            b = m["builder"]
+            spec = program.builders[b]
+            if spec["kind"] == "merger":
+                state[b] = _combine(spec["func"], spec["type"], state[b], val[m["vals"][0]])
+            elif spec["kind"] == "vecbuilder":
+                state[b].append(val[m["vals"][0]])
+            else:
+                key = tuple(val[k] for k in m["keys"])
+                vs = [val[v] for v in m["vals"]]
+                if key not in state[b]:
+                    state[b][key] = vs
+                else:
+                    cur = state[b][key]
+                    state[b][key] = [_combine(spec["func"], t, c, v)
+                                     for c, v, t in zip(cur, vs, spec["val_types"])]
+    return state
