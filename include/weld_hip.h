@@ -1,0 +1,265 @@
+/*
+ * weld_hip.h -- C ABI of the fused data-parallel `for` loop on one MI355X.
+ *
+ * One call submits what the paper's runtime hands to a backend after loop
+ * fusion (Sec. 4.5, the loop "after loop fusion"; Sec. 3.2, parallel `for` and
+ * builders; Table 1, builder types): a set of zipped input vectors, a loop
+ * body that maps one row to at most one merge per builder, and the builders.
+ * The library runs it as ONE pass over the columns in HBM (fused mode) or as
+ * one kernel per operator with every intermediate materialised in HBM
+ * (unfused mode, the function-call interface the paper argues against,
+ * Sec. 1 / Sec. 2.1).
+ *
+ * Conventions (Sec. 4.2, 4.3 of the paper):
+ *   - scalars and structs use C packed layout; a vector is {int64 len, T* ptr};
+ *   - input columns are DEVICE pointers owned by the caller; the library never
+ *     writes to them and never frees them;
+ *   - everything the library allocates, results included, is owned by the
+ *     library until weld_result_free(); temporaries go back to its pool when
+ *     the result is freed;
+ *   - a call only enqueues work on the caller's HIP stream and returns; the
+ *     accessors below are the evaluation point and synchronise that stream;
+ *   - every function returns a status; nothing throws across this boundary;
+ *     on error from weld_fused_for, *out is NULL.
+ *   - all pointers inside the argument structs are HOST pointers to host
+ *     arrays, except weld_col_t.data (device) and weld_conf_t.stream (a
+ *     hipStream_t, may be NULL for the default stream).
+ */
+#ifndef WELD_HIP_H
+#define WELD_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    WELD_OK = 0,
+    WELD_ERR_INVALID_ARG = 1, /* null pointer, negative size, bad index, malformed body    */
+    WELD_ERR_TYPE = 2,        /* operand / builder types do not match (no implicit casts)  */
+    WELD_ERR_LINEARITY = 3,   /* a builder is merged more than once on a control path      */
+    WELD_ERR_UNSUPPORTED = 4, /* legal IR outside the implemented subset                   */
+    WELD_ERR_OOM = 5,         /* needs more device memory than conf.memory_limit / device  */
+    WELD_ERR_CAPACITY = 6,    /* dictmerger saw more distinct keys than its capacity       */
+    WELD_ERR_DEVICE = 7,      /* HIP runtime / runtime-compiler failure, kernel-side abort */
+    WELD_ERR_NOT_READY = 8
+} weld_status_t;
+
+/* Scalar types of the data model (Sec. 3.1); WELD_BOOL is the type of predicates. */
+typedef enum { WELD_BOOL = 0, WELD_I8 = 1, WELD_I32 = 2, WELD_I64 = 3, WELD_F64 = 4 } weld_type_t;
+
+/* Expression operators of the loop body (Sec. 3.2: arithmetic, comparisons, select;
+ * exp/log/sqrt/erf are the math operators the Black-Scholes workload of Sec. 7.1 needs).
+ * Integers wrap modulo 2^w; integer DIV and MOD truncate toward zero; f64 is IEEE
+ * round-to-nearest with one rounding per operator (no contraction). */
+typedef enum {
+    WELD_OP_COL = 0,   /* a = column index: the i-th element of that zipped vector        */
+    WELD_OP_CONST = 1, /* imm: i64 bits for integer/bool types, f64 for WELD_F64          */
+    WELD_OP_INDEX = 2, /* the row index i, type WELD_I64                                  */
+    WELD_OP_NEG = 3, WELD_OP_NOT = 4, WELD_OP_CAST = 5,
+    WELD_OP_EXP = 6, WELD_OP_LOG = 7, WELD_OP_SQRT = 8, WELD_OP_ERF = 9,
+    WELD_OP_ADD = 10, WELD_OP_SUB = 11, WELD_OP_MUL = 12, WELD_OP_DIV = 13, WELD_OP_MOD = 14,
+    WELD_OP_MIN = 15, WELD_OP_MAX = 16,
+    WELD_OP_LT = 17, WELD_OP_LE = 18, WELD_OP_GT = 19, WELD_OP_GE = 20, WELD_OP_EQ = 21,
+    WELD_OP_NE = 22, WELD_OP_AND = 23, WELD_OP_OR = 24,
+    WELD_OP_SELECT = 25 /* a = bool condition, b = value if true, c = value if false      */
+} weld_opcode_t;
+
+/* One SSA value of the body.  Operands a, b, c are indices of EARLIER entries of
+ * weld_body_t.ops (or a column index for WELD_OP_COL); unused operands are -1.
+ * Giving every sub-result a name once is the `:=` binding of Sec. 3.2 and makes
+ * common sub-expressions shared by construction. */
+typedef struct {
+    int32_t opcode; /* weld_opcode_t */
+    int32_t type;   /* weld_type_t of the result */
+    int32_t a, b, c;
+    int32_t reserved;
+    union { int64_t i64; double f64; } imm;
+} weld_op_t;
+
+#define WELD_MAX_KEY_FIELDS 4
+#define WELD_MAX_VAL_FIELDS 8
+#define WELD_MAX_BUILDERS 8
+#define WELD_MAX_COLS 16
+
+/* `if (pred) merge(builders[builder], {keys.., vals..}) else builders[builder]`
+ * (Sec. 3.2, third builder example; Sec. 5, predication).  pred = -1 merges on
+ * every row.  merger and vecbuilder take nvals == 1, nkeys == 0; dictmerger takes
+ * the key struct fields in key[] and the value struct fields in val[]. */
+typedef struct {
+    int32_t builder;
+    int32_t pred;
+    int32_t nkeys;
+    int32_t key[WELD_MAX_KEY_FIELDS];
+    int32_t nvals;
+    int32_t val[WELD_MAX_VAL_FIELDS];
+} weld_merge_t;
+
+typedef struct {
+    int32_t nops;
+    const weld_op_t* ops;       /* host */
+    int32_t nmerges;
+    const weld_merge_t* merges; /* host; at most one merge per builder */
+} weld_body_t;
+
+typedef struct {
+    const void* data; /* DEVICE pointer to n contiguous elements; never written */
+    int32_t type;     /* weld_type_t (not WELD_BOOL) */
+} weld_col_t;
+
+typedef struct {
+    int32_t ncols;
+    const weld_col_t* col; /* host array */
+} weld_cols_t;
+
+typedef enum { WELD_MERGER = 0, WELD_VECBUILDER = 1, WELD_DICTMERGER = 2 } weld_builder_kind_t;
+typedef enum { WELD_FUNC_ADD = 0, WELD_FUNC_MUL = 1, WELD_FUNC_MIN = 2, WELD_FUNC_MAX = 3 } weld_func_t;
+
+/* One builder of Table 1.
+ *   merger[T,func,id]     : val_type[0] = T; id is func's identity (0, 1, +max, -max).
+ *   vecbuilder[T]         : val_type[0] = T; output keeps index order.
+ *   dictmerger[K,V,func]  : K = struct of key_type[0..nkeys), V = struct of
+ *                           val_type[0..nvals); func is applied field by field; the first
+ *                           merge of a key stores its value.  capacity = upper bound on the
+ *                           number of distinct keys (exceeding it -> WELD_ERR_CAPACITY). */
+typedef struct {
+    int32_t kind; /* weld_builder_kind_t */
+    int32_t func; /* weld_func_t (ignored by vecbuilder) */
+    int32_t nkeys;
+    int32_t key_type[WELD_MAX_KEY_FIELDS];
+    int32_t nvals;
+    int32_t val_type[WELD_MAX_VAL_FIELDS];
+    int64_t capacity;
+} weld_builder_spec_t;
+
+typedef enum { WELD_MODE_FUSED = 0, WELD_MODE_UNFUSED = 1 } weld_mode_t;
+
+/* Tuning knobs; 0 always means "library default".  They select among kernel
+ * variants that all return the same result. */
+typedef struct {
+    int32_t block_threads;   /* work-group size: 64..1024, multiple of 64            */
+    int32_t units_per_thread;/* 128-bit load groups in flight per lane and column    */
+    int32_t grid_blocks;     /* persistent grid size                                 */
+    int32_t dict_strategy;   /* 0 auto, 1 register slots, 2 LDS table, 3 global only */
+    int32_t lds_dict_slots;  /* slots of the per-block LDS hash table (power of two) */
+    int32_t spin_limit;      /* polls a tile waits for its predecessors before the call
+                                fails with WELD_ERR_DEVICE (the wait is always bounded)  */
+    int32_t reserved[2];
+} weld_tuning_t;
+
+typedef struct {
+    void* stream;         /* hipStream_t the work is enqueued on (NULL = default stream)      */
+    int32_t mode;         /* weld_mode_t                                                      */
+    int32_t flags;        /* reserved, 0                                                      */
+    int64_t memory_limit; /* bytes the call may hold in device memory (results + workspace);
+                             0 = unlimited.  Sec. 4.3: Evaluate takes a memory limit.         */
+    weld_tuning_t tune;
+} weld_conf_t;
+
+typedef struct {
+    int32_t count;
+    const weld_builder_spec_t* spec; /* host array, result order = this order */
+    weld_conf_t conf;
+} weld_builder_t;
+
+/* paper layout of vec[T] (Sec. 4.2): ptr is a DEVICE pointer owned by the library */
+typedef struct { int64_t len; void* ptr; } weld_vec_t;
+/* a dictionary result: entry i is (keys[i], values[i]); packed structs; unordered */
+typedef struct { weld_vec_t keys; weld_vec_t values; } weld_dict_t;
+
+typedef struct weld_result weld_result_t; /* opaque (the paper's WeldResult handle, Sec. 4.1) */
+
+/*
+ * weld_fused_for -- run `result(for(cols, builders, body))` over rows 0..n-1.
+ * Sec. 3.2 (for + builders), Sec. 4.1 (Evaluate returns a handle that can be checked
+ * for failure or queried for a pointer to the data), Sec. 4.3 (ownership, memory limit).
+ *
+ *  cols    : host struct; each column a device pointer to n elements of its type
+ *  n       : number of rows, >= 0 (0 is legal: every builder returns its empty result)
+ *  body    : host struct; validated (types, operand order, linearity) before any launch
+ *  builder : host struct; builders + configuration
+ *  out     : receives a new handle on WELD_OK, NULL otherwise
+ * Returns WELD_OK after the kernels are ENQUEUED on conf.stream; they may still be
+ * running.  The input columns must stay alive and unmodified until
+ * weld_result_status() has returned.  Thread-compatible, not thread-safe.
+ */
+weld_status_t weld_fused_for(const weld_cols_t* cols, int64_t n, const weld_body_t* body,
+                             const weld_builder_t* builder, weld_result_t** out);
+
+/* Evaluation point: waits for the stream, reads back lengths and kernel-side error
+ * flags.  WELD_OK, WELD_ERR_CAPACITY or WELD_ERR_DEVICE.  Idempotent. */
+weld_status_t weld_result_status(weld_result_t* r);
+
+/* Human-readable text of the last error on this handle ("" if none).  Never NULL
+ * for a non-NULL handle; owned by the handle. */
+const char* weld_result_error(const weld_result_t* r);
+
+/* Pointer to builder `idx`'s result (Sec. 4.1: "queried for a pointer to the
+ * returned data").  Calls weld_result_status() first; NULL on any error.
+ *   merger     -> DEVICE pointer to one scalar of its type (8-byte aligned)
+ *   vecbuilder -> HOST pointer to a weld_vec_t  (ptr inside is a device pointer)
+ *   dictmerger -> HOST pointer to a weld_dict_t (device pointers inside)
+ * Valid until weld_result_free(). */
+const void* weld_result_data(weld_result_t* r, int32_t idx);
+
+/* Convenience for callers without a HIP runtime of their own: copy `bytes` bytes of
+ * builder idx's payload, starting at byte `offset`, to `dst`.
+ *   part 0: merger scalar / vecbuilder elements / dictmerger keys;  part 1: dictmerger values.
+ *   dst_is_device != 0: dst is a device pointer (copy stays on the GPU). */
+weld_status_t weld_result_fetch(weld_result_t* r, int32_t idx, int32_t part, void* dst,
+                                int64_t offset, int64_t bytes, int32_t dst_is_device);
+
+/* Milliseconds between the first and last kernel of the call, from HIP events recorded
+ * on conf.stream around the enqueued work (valid after weld_result_status()). */
+weld_status_t weld_result_elapsed_ms(weld_result_t* r, float* ms);
+
+/* Number of kernels the call launched (1-2 in fused mode, one per operator unfused). */
+int32_t weld_result_kernel_count(const weld_result_t* r);
+
+/* Frees the results and returns workspace to the library's pool (Sec. 4.1 FreeWeldResult).
+ * NULL is allowed. */
+void weld_result_free(weld_result_t* r);
+
+/* Compile (or load from the on-disk cache) the fused kernel for this loop without
+ * running it and without touching a GPU; used to build kernels ahead of time.
+ * col_types: ncols weld_type_t values. */
+weld_status_t weld_precompile(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
+                              const weld_builder_t* builder);
+
+/* Directory for compiled code objects (created if missing).  NULL/"" disables the
+ * disk cache.  Default: $WELD_HIP_CACHE_DIR, else "kcache" next to the library. */
+weld_status_t weld_set_cache_dir(const char* path);
+
+/* Validation only (no GPU needed): the status weld_fused_for would return before
+ * planning.  err/errlen: optional buffer for the message. */
+weld_status_t weld_validate(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
+                            const weld_builder_t* builder, char* err, size_t errlen);
+
+/* The HIP source the runtime compiler is given for this loop (for inspection);
+ * returns bytes needed including the terminator, copies at most buflen. */
+int64_t weld_generated_source(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
+                              const weld_builder_t* builder, char* buf, int64_t buflen);
+
+/* Release every cached device allocation of the pool back to the device. */
+void weld_pool_trim(void);
+/* Bytes currently held by the pool (in use + cached). */
+int64_t weld_pool_bytes(void);
+
+/* Text of the last error of a call that returned no handle (thread-local). */
+const char* weld_last_error(void);
+
+/* Streaming-read probe: sums `bytes` bytes at `data` (device, 16-byte aligned) with
+ * 128-bit loads; used to measure the attainable HBM read rate on the box.
+ * Writes a 64-bit checksum to *checksum_dev (device pointer). */
+weld_status_t weld_probe_read(const void* data, int64_t bytes, void* checksum_dev, void* stream);
+/* Plain copy kernel of known size (device to device), used to scale the HBM counters. */
+weld_status_t weld_probe_copy(void* dst, const void* src, int64_t bytes, void* stream);
+
+const char* weld_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WELD_HIP_H */

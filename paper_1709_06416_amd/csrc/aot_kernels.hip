@@ -1,0 +1,118 @@
+// Ahead-of-time compiled helper kernels (gfx950): workspace fills, dictionary
+// result extraction, and the two memory probes used for roofline measurements.
+#include <hip/hip_runtime.h>
+
+#include "aot_kernels.h"
+
+namespace weld {
+
+typedef unsigned long long u64;
+typedef long long i64;
+typedef unsigned int u32;
+typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+
+static const u64 kEmptyKey = 0x8000000000000000ull;
+
+// ---------------------------------------------------------------- fill
+// Workspace is cleared with a kernel rather than a memset node so that a caller may
+// capture the whole call into a HIP graph.
+__global__ void __launch_bounds__(256) fill64_kernel(u64* p, i64 count, u64 value) {
+    for (i64 i = (i64)blockIdx.x * 256 + threadIdx.x; i < count; i += (i64)gridDim.x * 256) p[i] = value;
+}
+
+hipError_t launch_fill64(void* p, int64_t count, uint64_t value, hipStream_t stream) {
+    if (count <= 0) return hipSuccess;
+    int64_t blocks = (count + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    fill64_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>((u64*)p, count, value);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- dictionary result
+// Walks the open-addressing table and writes every occupied slot as one (key struct,
+// value struct) pair in C packed layout (Sec. 4.2 of the paper).  Entry order is
+// unspecified (the paper's dict is unordered).  Entries beyond `capacity` raise the
+// capacity error instead of being written.
+__global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, const u32* hdr, i64 slots,
+                                                           DictValues vals, DictLayout lay, i64 capacity,
+                                                           unsigned char* out_keys, unsigned char* out_vals,
+                                                           u64* count, int* err) {
+    for (i64 s = (i64)blockIdx.x * 256 + threadIdx.x; s <= slots; s += (i64)gridDim.x * 256) {
+        const u64 kb = s < slots ? keys[s] : kEmptyKey;
+        const bool used = s < slots ? (kb != kEmptyKey) : (hdr[1] != 0);
+        if (!used) continue;
+        const u64 pos = atomicAdd(count, 1ull);
+        if ((i64)pos >= capacity) {
+            atomicOr(err, 1);
+            continue;
+        }
+        unsigned char* ko = out_keys + pos * lay.key_stride;
+        int off = 0;
+        for (int k = 0; k < lay.nkeys; ++k) {
+            const u64 field = kb >> lay.key_shift[k];
+            for (int b = 0; b < lay.key_size[k]; ++b) ko[off + b] = (unsigned char)(field >> (8 * b));
+            off += lay.key_size[k];
+        }
+        unsigned char* vo = out_vals + pos * lay.val_stride;
+        off = 0;
+        for (int k = 0; k < lay.nvals; ++k) {
+            const u64 bits = vals.p[k][s];
+            for (int b = 0; b < lay.val_size[k]; ++b) vo[off + b] = (unsigned char)(bits >> (8 * b));
+            off += lay.val_size[k];
+        }
+    }
+}
+
+hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots, const DictValues& vals,
+                               const DictLayout& lay, int64_t capacity, void* out_keys, void* out_vals,
+                               void* count, void* err, hipStream_t stream) {
+    int64_t blocks = (slots + 1 + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    dict_extract_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
+        (const u64*)keys, (const u32*)hdr, slots, vals, lay, capacity, (unsigned char*)out_keys,
+        (unsigned char*)out_vals, (u64*)count, (int*)err);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- probes
+// Pure streaming read with 16-byte loads: the attainable HBM read rate on this machine.
+__global__ void __launch_bounds__(256) probe_read_kernel(const u32x4* p, i64 n16, u64* checksum) {
+    u32 a = 0, b = 0, c = 0, d = 0;
+    const i64 stride = (i64)gridDim.x * 256;
+    i64 i = (i64)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4 v0 = __builtin_nontemporal_load(p + i);
+        const u32x4 v1 = __builtin_nontemporal_load(p + i + stride);
+        const u32x4 v2 = __builtin_nontemporal_load(p + i + 2 * stride);
+        const u32x4 v3 = __builtin_nontemporal_load(p + i + 3 * stride);
+        a += v0.x + v1.x + v2.x + v3.x;
+        b += v0.y + v1.y + v2.y + v3.y;
+        c += v0.z + v1.z + v2.z + v3.z;
+        d += v0.w + v1.w + v2.w + v3.w;
+    }
+    for (; i < n16; i += stride) {
+        const u32x4 v = __builtin_nontemporal_load(p + i);
+        a += v.x; b += v.y; c += v.z; d += v.w;
+    }
+    u64 s = (u64)a + b + c + d;
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if ((threadIdx.x & 63) == 0) atomicAdd(checksum, s);
+}
+
+hipError_t launch_probe_read(const void* data, int64_t bytes, void* checksum, int blocks, hipStream_t stream) {
+    probe_read_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>((const u32x4*)data, bytes / 16, (u64*)checksum);
+    return hipGetLastError();
+}
+
+// Plain copy of known size: bytes read == bytes written == `bytes`.
+__global__ void __launch_bounds__(256) probe_copy_kernel(uint4* dst, const uint4* src, i64 n16) {
+    const i64 stride = (i64)gridDim.x * 256;
+    for (i64 i = (i64)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_probe_copy(void* dst, const void* src, int64_t bytes, int blocks, hipStream_t stream) {
+    probe_copy_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>((uint4*)dst, (const uint4*)src, bytes / 16);
+    return hipGetLastError();
+}
+
+}  // namespace weld

@@ -1,0 +1,555 @@
+// HIP source generation for one fused loop.
+//
+// The paper's backends turn the optimised IR into one kernel per program (Sec. 5);
+// this file does the same for gfx950.  What is generated is small: the row function
+// (the loop body as straight-line SSA code, one C++ statement per IR operator, so
+// shared sub-expressions are computed once), the merge statements, and a kernel
+// skeleton that wires the hand-written building blocks of fused_prelude.hip.h
+// (column loader, wavefront/work-group reductions, look-back scan, hash tables)
+// together for the builders of this particular loop.
+//
+// Row ownership: a tile is W_WAVES consecutive runs of W_WAVE_ROWS rows, one run
+// per wavefront; inside a run, load u of lane l covers rows
+// run + (u*64 + l)*W_V .. +W_V-1.  Every wavefront-wide load is therefore one
+// contiguous span, and index order inside a wavefront is (u, lane, k), which is
+// what the order-preserving vecbuilder ranks rely on.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "weld_internal.h"
+
+namespace weld {
+
+extern const char* const kPreludeSource;  // fused_prelude.hip.h, embedded at build time
+
+namespace {
+
+struct Out {
+    std::string s;
+    void f(const char* fmt, ...) __attribute__((format(printf, 2, 3))) {
+        char buf[2048];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        s += buf;
+    }
+};
+
+const char* ctype(int t) {
+    switch (t) {
+        case WELD_BOOL: return "bool";
+        case WELD_I8: return "signed char";
+        case WELD_I32: return "int";
+        case WELD_I64: return "i64";
+        case WELD_F64: return "double";
+    }
+    return "void";
+}
+// type a builder accumulates a value field in (integers widen to 64 bits: wrapping
+// sums/products and min/max commute with the final truncation)
+const char* acc_ctype(int t) { return t == WELD_F64 ? "double" : "i64"; }
+const char* utype(int t) {
+    switch (t) {
+        case WELD_I8: return "unsigned char";
+        case WELD_I32: return "u32";
+        case WELD_I64: return "u64";
+    }
+    return "u64";
+}
+
+std::string ident_expr(int func, int t) {
+    char buf[96];
+    if (t == WELD_F64) snprintf(buf, sizeof buf, "w_identity_f64<%d>()", func);
+    else snprintf(buf, sizeof buf, "w_identity_int<%d,%d>()", func, 8 * type_size(t));
+    return buf;
+}
+
+std::string const_expr(const weld_op_t& o) {
+    char buf[96];
+    switch (o.type) {
+        case WELD_BOOL: snprintf(buf, sizeof buf, "%s", o.imm.i64 ? "true" : "false"); break;
+        case WELD_F64: {
+            uint64_t bits;
+            memcpy(&bits, &o.imm.f64, 8);
+            snprintf(buf, sizeof buf, "__builtin_bit_cast(double, 0x%016llxull)", (unsigned long long)bits);
+            break;
+        }
+        case WELD_I64:
+            snprintf(buf, sizeof buf, "(i64)0x%016llxull", (unsigned long long)o.imm.i64);
+            break;
+        default:
+            snprintf(buf, sizeof buf, "(%s)(%lld)", ctype(o.type), (long long)o.imm.i64);
+    }
+    return buf;
+}
+
+// wrapping integer arithmetic through the unsigned type
+std::string wrap_bin(int t, const char* op, int a, int b) {
+    char buf[160];
+    if (t == WELD_I8)
+        snprintf(buf, sizeof buf, "(signed char)(unsigned char)((u32)(unsigned char)t%d %s (u32)(unsigned char)t%d)", a, op, b);
+    else
+        snprintf(buf, sizeof buf, "(%s)((%s)t%d %s (%s)t%d)", ctype(t), utype(t), a, op, utype(t), b);
+    return buf;
+}
+
+void emit_row_function(Out& o, const Loop& L) {
+    // ---- RowOut
+    o.f("struct RowOut {\n");
+    for (size_t b = 0; b < L.builders.size(); ++b) {
+        if (L.merge_of[b] < 0) continue;
+        const weld_builder_spec_t& s = L.builders[b];
+        o.f("  bool p%zu;", b);
+        for (int k = 0; k < s.nkeys; ++k) o.f(" %s k%zu_%d;", ctype(s.key_type[k]), b, k);
+        for (int k = 0; k < s.nvals; ++k) o.f(" %s v%zu_%d;", ctype(s.val_type[k]), b, k);
+        o.f("\n");
+    }
+    o.f("  int unused_;\n};\n\n");
+    // ---- invalid row (past the end of the input): merges nothing
+    o.f("__device__ __forceinline__ void weld_row_none(RowOut& o) {\n");
+    for (size_t b = 0; b < L.builders.size(); ++b) {
+        if (L.merge_of[b] < 0) continue;
+        const weld_builder_spec_t& s = L.builders[b];
+        o.f("  o.p%zu = false;", b);
+        for (int k = 0; k < s.nkeys; ++k) o.f(" o.k%zu_%d = 0;", b, k);
+        for (int k = 0; k < s.nvals; ++k) o.f(" o.v%zu_%d = 0;", b, k);
+        o.f("\n");
+    }
+    o.f("}\n\n");
+    // ---- the body, one statement per IR operator
+    o.f("__device__ __forceinline__ void weld_row(const i64 i");
+    for (int c = 0; c < L.ncols; ++c)
+        if (L.col_used[c]) o.f(", const %s x%d", ctype(L.col_type[c]), c);
+    o.f(", RowOut& o) {\n");
+    for (size_t i = 0; i < L.ops.size(); ++i) {
+        const weld_op_t& q = L.ops[i];
+        const int id = (int)i;
+        const char* T = ctype(q.type);
+        o.f("  const %s t%d = ", T, id);
+        switch (q.opcode) {
+            case WELD_OP_COL: o.f("x%d", q.a); break;
+            case WELD_OP_CONST: o.f("%s", const_expr(q).c_str()); break;
+            case WELD_OP_INDEX: o.f("i"); break;
+            case WELD_OP_NEG:
+                if (q.type == WELD_F64) o.f("-t%d", q.a);
+                else o.f("(%s)((%s)0 - (%s)t%d)", T, utype(q.type), utype(q.type), q.a);
+                break;
+            case WELD_OP_NOT: o.f("!t%d", q.a); break;
+            case WELD_OP_CAST: {
+                const int st = L.ops[q.a].type;
+                if (q.type == WELD_BOOL) o.f("(t%d != 0)", q.a);
+                else if (st == WELD_F64 && type_is_int(q.type)) o.f("(%s)(i64)t%d", T, q.a);
+                else o.f("(%s)t%d", T, q.a);
+                break;
+            }
+            case WELD_OP_EXP: o.f("exp(t%d)", q.a); break;
+            case WELD_OP_LOG: o.f("log(t%d)", q.a); break;
+            case WELD_OP_SQRT: o.f("sqrt(t%d)", q.a); break;
+            case WELD_OP_ERF: o.f("erf(t%d)", q.a); break;
+            case WELD_OP_ADD:
+                if (q.type == WELD_F64) o.f("t%d + t%d", q.a, q.b);
+                else o.f("%s", wrap_bin(q.type, "+", q.a, q.b).c_str());
+                break;
+            case WELD_OP_SUB:
+                if (q.type == WELD_F64) o.f("t%d - t%d", q.a, q.b);
+                else o.f("%s", wrap_bin(q.type, "-", q.a, q.b).c_str());
+                break;
+            case WELD_OP_MUL:
+                if (q.type == WELD_F64) o.f("t%d * t%d", q.a, q.b);
+                else o.f("%s", wrap_bin(q.type, "*", q.a, q.b).c_str());
+                break;
+            case WELD_OP_DIV:
+                if (q.type == WELD_F64) o.f("t%d / t%d", q.a, q.b);
+                else o.f("(%s)(t%d / t%d)", T, q.a, q.b);
+                break;
+            case WELD_OP_MOD:
+                if (q.type == WELD_F64) o.f("fmod(t%d, t%d)", q.a, q.b);
+                else o.f("(%s)(t%d %% t%d)", T, q.a, q.b);
+                break;
+            case WELD_OP_MIN: o.f("(t%d < t%d ? t%d : t%d)", q.b, q.a, q.b, q.a); break;
+            case WELD_OP_MAX: o.f("(t%d > t%d ? t%d : t%d)", q.b, q.a, q.b, q.a); break;
+            case WELD_OP_LT: o.f("t%d < t%d", q.a, q.b); break;
+            case WELD_OP_LE: o.f("t%d <= t%d", q.a, q.b); break;
+            case WELD_OP_GT: o.f("t%d > t%d", q.a, q.b); break;
+            case WELD_OP_GE: o.f("t%d >= t%d", q.a, q.b); break;
+            case WELD_OP_EQ: o.f("t%d == t%d", q.a, q.b); break;
+            case WELD_OP_NE: o.f("t%d != t%d", q.a, q.b); break;
+            case WELD_OP_AND: o.f("(bool)((int)t%d & (int)t%d)", q.a, q.b); break;
+            case WELD_OP_OR: o.f("(bool)((int)t%d | (int)t%d)", q.a, q.b); break;
+            case WELD_OP_SELECT: o.f("t%d ? t%d : t%d", q.a, q.b, q.c); break;
+        }
+        o.f(";\n");
+    }
+    for (size_t b = 0; b < L.builders.size(); ++b) {
+        const int m = L.merge_of[b];
+        if (m < 0) continue;
+        const weld_merge_t& g = L.merges[m];
+        if (g.pred >= 0) o.f("  o.p%zu = t%d;", b, g.pred);
+        else o.f("  o.p%zu = true;", b);
+        for (int k = 0; k < g.nkeys; ++k) o.f(" o.k%zu_%d = t%d;", b, k, g.key[k]);
+        for (int k = 0; k < g.nvals; ++k) o.f(" o.v%zu_%d = t%d;", b, k, g.val[k]);
+        o.f("\n");
+    }
+    o.f("}\n\n");
+}
+
+// expression packing the key struct of builder b into 64 bits (field 0 lowest)
+std::string pack_key(const weld_builder_spec_t& s, size_t b, const char* row) {
+    std::string e;
+    int shift = 0;
+    for (int k = 0; k < s.nkeys; ++k) {
+        char buf[128];
+        snprintf(buf, sizeof buf, "%s((u64)(%s)%s.k%zu_%d << %d)", k ? " | " : "", utype(s.key_type[k]), row, b, k, shift);
+        e += buf;
+        shift += 8 * type_size(s.key_type[k]);
+    }
+    return e;
+}
+
+}  // namespace
+
+Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
+    Variant var;
+    int widest = 1;
+    bool any = false;
+    for (int c = 0; c < L.ncols; ++c)
+        if (L.col_used[c]) { any = true; if (type_size(L.col_type[c]) > widest) widest = type_size(L.col_type[c]); }
+    var.backend.assign(L.builders.size(), BK_MERGER);
+    for (size_t b = 0; b < L.builders.size(); ++b) {
+        const weld_builder_spec_t& s = L.builders[b];
+        const int m = L.merge_of[b];
+        if (s.kind == WELD_MERGER) {
+            var.backend[b] = BK_MERGER;
+        } else if (s.kind == WELD_VECBUILDER) {
+            const bool cond = m >= 0 && L.merges[m].pred >= 0;
+            var.backend[b] = cond ? BK_VEC_COMPACT : BK_VEC_DIRECT;
+            if (cond) var.ticketed = true;
+            if (m >= 0 && type_size(s.val_type[0]) > widest) widest = type_size(s.val_type[0]);
+        } else {
+            int strat = tune.dict_strategy;
+            if (strat == 1 && (s.capacity > 8 || key_bits(s) >= 64)) strat = 0;
+            if (strat == 0) strat = (s.capacity <= 8 && key_bits(s) < 64) ? 1 : 2;
+            var.backend[b] = strat == 1 ? BK_DICT_REG : (strat == 2 ? BK_DICT_LDS : BK_DICT_GLOBAL);
+            if (var.backend[b] == BK_DICT_LDS) {
+                int want = tune.lds_dict_slots;
+                if (want <= 0) {
+                    const int per_slot = 8 * (1 + s.nvals);
+                    want = 64;
+                    while (want * 2 * per_slot <= 48 * 1024 && want < 2 * s.capacity) want *= 2;
+                }
+                int p2 = 64;
+                while (p2 < want && p2 < (1 << 14)) p2 *= 2;
+                var.lds_slots = p2;
+            }
+        }
+    }
+    (void)any;
+    var.v = widest >= 8 ? 2 : 4;
+    var.u = tune.units_per_thread > 0 ? tune.units_per_thread : (var.v == 2 ? 4 : 2);
+    if (var.u > 8) var.u = 8;
+    var.block = tune.block_threads > 0 ? tune.block_threads : 256;
+    if (var.block < 64) var.block = 64;
+    if (var.block > 1024) var.block = 1024;
+    var.block = (var.block / 64) * 64;
+    var.aligned = aligned ? 1 : 0;
+    return var;
+}
+
+Generated generate(const Loop& L, const Variant& var) {
+    Generated G;
+    Out o;
+    const size_t NB = L.builders.size();
+    o.f("// generated: fused for-loop kernel, %d columns, %zu builders\n", L.ncols, NB);
+    o.f("#define W_BLOCK %d\n#define W_V %d\n#define W_U %d\n#define W_ALIGNED %d\n", var.block, var.v, var.u, var.aligned);
+    o.s += kPreludeSource;
+    o.f("\n");
+
+    // ------------------------------------------------------------ kernel arguments
+    auto slot = [&](SlotKind k, int builder, int field, const std::string& name, const std::string& ct) {
+        Slot s{k, builder, field, name, ct};
+        G.slots.push_back(s);
+    };
+    slot(SLOT_N, -1, 0, "n", "i64");
+    slot(SLOT_SPIN, -1, 0, "spin_limit", "i64");
+    for (int c = 0; c < L.ncols; ++c)
+        if (L.col_used[c]) slot(SLOT_COL, c, 0, "c" + std::to_string(c), std::string("const ") + ctype(L.col_type[c]) + "* __restrict__");
+    slot(SLOT_CTL, -1, 0, "ctl", "u32*");
+    int ncompact = 0;
+    for (size_t b = 0; b < NB; ++b) {
+        const weld_builder_spec_t& s = L.builders[b];
+        const std::string B = "b" + std::to_string(b);
+        switch (var.backend[b]) {
+            case BK_MERGER:
+                slot(SLOT_PARTIAL, (int)b, 0, B + "_part", "u64*");
+                slot(SLOT_RESULT, (int)b, 0, B + "_res", std::string(ctype(s.val_type[0])) + "*");
+                break;
+            case BK_VEC_DIRECT:
+                slot(SLOT_OUT, (int)b, 0, B + "_out", std::string(ctype(s.val_type[0])) + "* __restrict__");
+                break;
+            case BK_VEC_COMPACT:
+                slot(SLOT_OUT, (int)b, 0, B + "_out", std::string(ctype(s.val_type[0])) + "* __restrict__");
+                slot(SLOT_DESC, (int)b, 0, B + "_desc", "u64*");
+                slot(SLOT_LEN, (int)b, 0, B + "_len", "i64*");
+                ++ncompact;
+                break;
+            default:
+                slot(SLOT_DKEYS, (int)b, 0, B + "_keys", "u64*");
+                slot(SLOT_DHDR, (int)b, 0, B + "_hdr", "u32*");
+                slot(SLOT_DSLOTS, (int)b, 0, B + "_slots", "i64");
+                for (int k = 0; k < s.nvals; ++k)
+                    slot(SLOT_DVAL, (int)b, k, B + "_v" + std::to_string(k), std::string(acc_ctype(s.val_type[k])) + "*");
+        }
+    }
+    o.f("struct KArgs {\n");
+    for (const Slot& s : G.slots) o.f("  %s %s;\n", s.ctype.c_str(), s.name.c_str());
+    o.f("};\n\n");
+
+    emit_row_function(o, L);
+
+    // ------------------------------------------------------------ merge statements
+    // (everything except vecbuilders, which the tile code handles)
+    o.f("#define WELD_MERGE(o) do { \\\n");
+    for (size_t b = 0; b < NB; ++b) {
+        if (L.merge_of[b] < 0) continue;
+        const weld_builder_spec_t& s = L.builders[b];
+        const int F = s.func;
+        if (var.backend[b] == BK_MERGER) {
+            o.f("  if ((o).p%zu) m%zu = w_combine<%d>(m%zu, (%s)(o).v%zu_0); \\\n", b, b, F, b, acc_ctype(s.val_type[0]), b);
+        } else if (var.backend[b] == BK_DICT_REG) {
+            const int S = (int)s.capacity;
+            o.f("  if ((o).p%zu) { \\\n", b);
+            o.f("    const u64 kb = %s; \\\n", pack_key(s, b, "(o)").c_str());
+            o.f("    int sl = -1; \\\n");
+            o.f("    _Pragma(\"unroll\") for (int q = 0; q < %d; ++q) if (kb == d%zu_kreg[q]) sl = q; \\\n", S, b);
+            o.f("    if (sl < 0) { \\\n");
+            o.f("      sl = w_slot_list_insert<%d>(d%zu_lk, kb, errp); \\\n", S, b);
+            o.f("      _Pragma(\"unroll\") for (int q = 0; q < %d; ++q) d%zu_kreg[q] = __hip_atomic_load(d%zu_lk + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); \\\n", S, b, b);
+            o.f("    } \\\n");
+            o.f("    _Pragma(\"unroll\") for (int q = 0; q < %d; ++q) if (sl == q) { \\\n", S);
+            for (int k = 0; k < s.nvals; ++k)
+                o.f("      d%zu_a%d[q] = w_combine<%d>(d%zu_a%d[q], (%s)(o).v%zu_%d); \\\n", b, k, F, b, k, acc_ctype(s.val_type[k]), b, k);
+            o.f("    } \\\n");
+            o.f("  } \\\n");
+        } else if (var.backend[b] == BK_DICT_LDS || var.backend[b] == BK_DICT_GLOBAL) {
+            o.f("  if ((o).p%zu) { \\\n", b);
+            o.f("    const u64 kb = %s; \\\n", pack_key(s, b, "(o)").c_str());
+            if (var.backend[b] == BK_DICT_LDS) {
+                o.f("    const int sl = w_lds_slot(d%zu_lk, %d, kb, 8); \\\n", b, var.lds_slots);
+                o.f("    if (sl >= 0) { \\\n");
+                for (int k = 0; k < s.nvals; ++k)
+                    o.f("      w_atomic<%d>(d%zu_lv%d + sl, (%s)(o).v%zu_%d, 0); \\\n", F, b, k, acc_ctype(s.val_type[k]), b, k);
+                o.f("    } else { \\\n");
+            } else {
+                o.f("    { \\\n");
+            }
+            o.f("      const i64 g = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, kb, errp); \\\n", b, b, b);
+            o.f("      if (g >= 0) { \\\n");
+            for (int k = 0; k < s.nvals; ++k)
+                o.f("        w_atomic<%d>(a.b%zu_v%d + g, (%s)(o).v%zu_%d, 1); \\\n", F, b, k, acc_ctype(s.val_type[k]), b, k);
+            o.f("      } \\\n    } \\\n  } \\\n");
+        }
+    }
+    o.f("} while (0)\n\n");
+
+    // ------------------------------------------------------------ kernel
+    o.f("extern \"C\" __global__ void __launch_bounds__(W_BLOCK) weld_kernel(const KArgs a) {\n");
+    o.f("  __shared__ u64 s_red[W_WAVES];\n  __shared__ int s_flag;\n");
+    o.f("  int* const errp = (int*)(a.ctl + 2);\n");
+    o.f("  const int lane = threadIdx.x & 63;\n  const int wave = threadIdx.x >> 6;\n");
+    o.f("  (void)lane; (void)wave; (void)errp; (void)s_flag;\n");
+    int lds = 8 * (var.block / 64) + 4;
+    if (var.ticketed) {
+        o.f("  __shared__ i64 s_tile;\n  __shared__ i64 s_cnt[%d][W_WAVES];\n  __shared__ i64 s_pfx[%d];\n", ncompact, ncompact);
+        lds += 8 + 8 * ncompact * (var.block / 64) + 8 * ncompact;
+    }
+    // builder state
+    bool need_sync = false;
+    int nmergers = 0;
+    for (size_t b = 0; b < NB; ++b) {
+        const weld_builder_spec_t& s = L.builders[b];
+        if (var.backend[b] == BK_MERGER) {
+            ++nmergers;
+            o.f("  %s m%zu = %s;\n", acc_ctype(s.val_type[0]), b, ident_expr(s.func, s.val_type[0]).c_str());
+        } else if (var.backend[b] == BK_DICT_REG) {
+            const int S = (int)s.capacity;
+            o.f("  __shared__ u64 d%zu_lk[%d];\n", b, S);
+            lds += 8 * S;
+            o.f("  if (threadIdx.x < %d) d%zu_lk[threadIdx.x] = W_EMPTY_KEY;\n", S, b);
+            o.f("  u64 d%zu_kreg[%d];\n", b, S);
+            o.f("  _Pragma(\"unroll\") for (int q = 0; q < %d; ++q) d%zu_kreg[q] = W_EMPTY_KEY;\n", S, b);
+            for (int k = 0; k < s.nvals; ++k) {
+                o.f("  %s d%zu_a%d[%d];\n", acc_ctype(s.val_type[k]), b, k, S);
+                o.f("  _Pragma(\"unroll\") for (int q = 0; q < %d; ++q) d%zu_a%d[q] = %s;\n", S, b, k, ident_expr(s.func, s.val_type[k]).c_str());
+            }
+            need_sync = true;
+        } else if (var.backend[b] == BK_DICT_LDS) {
+            o.f("  __shared__ u64 d%zu_lk[%d];\n", b, var.lds_slots);
+            lds += 8 * var.lds_slots * (1 + s.nvals);
+            for (int k = 0; k < s.nvals; ++k) o.f("  __shared__ %s d%zu_lv%d[%d];\n", acc_ctype(s.val_type[k]), b, k, var.lds_slots);
+            o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) {\n    d%zu_lk[q] = W_EMPTY_KEY;\n", var.lds_slots, b);
+            for (int k = 0; k < s.nvals; ++k) o.f("    d%zu_lv%d[q] = %s;\n", b, k, ident_expr(s.func, s.val_type[k]).c_str());
+            o.f("  }\n");
+            need_sync = true;
+        }
+    }
+    if (need_sync) o.f("  __syncthreads();\n");
+
+    // row evaluation call text
+    auto row_call = [&](const char* idx, const char* fmt_col, const char* dst) {
+        // fmt_col is a printf format taking the column number
+        std::string c = "weld_row(";
+        c += idx;
+        for (int k = 0; k < L.ncols; ++k)
+            if (L.col_used[k]) {
+                char buf[96];
+                snprintf(buf, sizeof buf, fmt_col, k);
+                c += ", ";
+                c += buf;
+            }
+        c += ", ";
+        c += dst;
+        c += ");";
+        return c;
+    };
+
+    if (!var.ticketed) {
+        // ---------------- static tile order: no barriers inside the main loop
+        o.f("  const i64 nfull = a.n / W_TILE;\n");
+        o.f("  for (i64 t = blockIdx.x; t < nfull; t += gridDim.x) {\n");
+        o.f("    const i64 r0 = t * W_TILE + (i64)wave * W_WAVE_ROWS + lane * W_V;\n");
+        for (int c = 0; c < L.ncols; ++c)
+            if (L.col_used[c]) o.f("    wvec<%s, W_V> x%d[W_U];\n", ctype(L.col_type[c]), c);
+        o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+        for (int c = 0; c < L.ncols; ++c)
+            if (L.col_used[c]) o.f("      x%d[u] = w_load<%s, W_V>(a.c%d + r0 + u * W_UNIT);\n", c, ctype(L.col_type[c]), c);
+        o.f("    }\n");
+        o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+        for (size_t b = 0; b < NB; ++b)
+            if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) o.f("      wvec<%s, W_V> y%zu;\n", ctype(L.builders[b].val_type[0]), b);
+        o.f("      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
+        o.f("        RowOut o;\n        %s\n", row_call("r0 + u * W_UNIT + k", "x%d[u].e[k]", "o").c_str());
+        o.f("        WELD_MERGE(o);\n");
+        for (size_t b = 0; b < NB; ++b)
+            if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) o.f("        y%zu.e[k] = o.v%zu_0;\n", b, b);
+        o.f("      }\n");
+        for (size_t b = 0; b < NB; ++b)
+            if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0)
+                o.f("      w_store<%s, W_V>(a.b%zu_out + r0 + u * W_UNIT, y%zu);\n", ctype(L.builders[b].val_type[0]), b, b);
+        o.f("    }\n  }\n");
+        // tail rows, one per thread
+        o.f("  for (i64 i = nfull * W_TILE + (i64)blockIdx.x * W_BLOCK + threadIdx.x; i < a.n; i += (i64)gridDim.x * W_BLOCK) {\n");
+        o.f("    RowOut o;\n    %s\n    WELD_MERGE(o);\n", row_call("i", "a.c%d[i]", "o").c_str());
+        for (size_t b = 0; b < NB; ++b)
+            if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) o.f("    a.b%zu_out[i] = o.v%zu_0;\n", b, b);
+        o.f("  }\n");
+    } else {
+        // ---------------- ticketed tile order (needed by the look-back scan)
+        o.f("  const i64 ntiles = (a.n + W_TILE - 1) / W_TILE;\n");
+        o.f("  for (;;) {\n");
+        o.f("    if (threadIdx.x == 0) s_tile = (i64)__hip_atomic_fetch_add(a.ctl, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n");
+        o.f("    __syncthreads();\n    const i64 t = s_tile;\n    if (t >= ntiles) break;\n");
+        o.f("    const i64 r0 = t * W_TILE + (i64)wave * W_WAVE_ROWS + lane * W_V;\n");
+        o.f("    const bool full = (t + 1) * W_TILE <= a.n;\n");
+        o.f("    RowOut o[W_U][W_V];\n");
+        o.f("    if (full) {\n");
+        for (int c = 0; c < L.ncols; ++c)
+            if (L.col_used[c]) o.f("      wvec<%s, W_V> x%d[W_U];\n", ctype(L.col_type[c]), c);
+        o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+        for (int c = 0; c < L.ncols; ++c)
+            if (L.col_used[c]) o.f("        x%d[u] = w_load<%s, W_V>(a.c%d + r0 + u * W_UNIT);\n", c, ctype(L.col_type[c]), c);
+        o.f("      }\n");
+        o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
+        o.f("          %s\n        }\n", row_call("r0 + u * W_UNIT + k", "x%d[u].e[k]", "o[u][k]").c_str());
+        o.f("    } else {\n");
+        o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
+        o.f("          const i64 i = r0 + u * W_UNIT + k;\n");
+        o.f("          if (i < a.n) { %s } else weld_row_none(o[u][k]);\n        }\n", row_call("i", "a.c%d[i]", "o[u][k]").c_str());
+        o.f("    }\n");
+        o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) WELD_MERGE(o[u][k]);\n");
+        // direct vecbuilders inside a ticketed kernel
+        for (size_t b = 0; b < NB; ++b)
+            if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) {
+                o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
+                o.f("        const i64 i = r0 + u * W_UNIT + k;\n        if (i < a.n) a.b%zu_out[i] = o[u][k].v%zu_0;\n      }\n", b, b);
+            }
+        // ranks of the selected rows inside this wavefront's run, per compacting builder
+        int j = 0;
+        for (size_t b = 0; b < NB; ++b) {
+            if (var.backend[b] != BK_VEC_COMPACT) continue;
+            o.f("    int rk%zu[W_U][W_V];\n    {\n      int wtot = 0;\n", b);
+            o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n        int below = 0, utot = 0, mine = 0;\n");
+            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
+            o.f("          const u64 bal = w_ballot(o[u][k].p%zu);\n          below += w_rank_below(bal);\n          utot += __popcll(bal);\n        }\n", b);
+            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n          rk%zu[u][k] = wtot + below + mine;\n          mine += o[u][k].p%zu ? 1 : 0;\n        }\n", b, b);
+            o.f("        wtot += utot;\n      }\n");
+            o.f("      if (lane == 0) s_cnt[%d][wave] = wtot;\n    }\n", j);
+            ++j;
+        }
+        o.f("    __syncthreads();\n");
+        o.f("    if (wave == 0) {\n");
+        j = 0;
+        for (size_t b = 0; b < NB; ++b) {
+            if (var.backend[b] != BK_VEC_COMPACT) continue;
+            o.f("      {\n        i64 tot = 0;\n        _Pragma(\"unroll\") for (int w = 0; w < W_WAVES; ++w) tot += s_cnt[%d][w];\n", j);
+            o.f("        const i64 ex = w_lookback(a.b%zu_desc, t, tot, a.spin_limit, errp);\n", b);
+            o.f("        if (lane == 0) {\n          s_pfx[%d] = ex;\n          if (t == ntiles - 1) *a.b%zu_len = ex + tot;\n        }\n      }\n", j, b);
+            ++j;
+        }
+        o.f("    }\n    __syncthreads();\n");
+        j = 0;
+        for (size_t b = 0; b < NB; ++b) {
+            if (var.backend[b] != BK_VEC_COMPACT) continue;
+            o.f("    {\n      i64 base = s_pfx[%d];\n      for (int w = 0; w < wave; ++w) base += s_cnt[%d][w];\n", j, j);
+            o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k)\n");
+            o.f("          if (o[u][k].p%zu) a.b%zu_out[base + rk%zu[u][k]] = o[u][k].v%zu_0;\n    }\n", b, b, b, b);
+            ++j;
+        }
+        o.f("  }\n");
+    }
+
+    // ------------------------------------------------------------ builder results
+    for (size_t b = 0; b < NB; ++b) {
+        const weld_builder_spec_t& s = L.builders[b];
+        if (var.backend[b] == BK_MERGER) {
+            const char* A = acc_ctype(s.val_type[0]);
+            o.f("  {\n    const %s tot = w_block_reduce<%d>(m%zu, (%s*)s_red, %s);\n", A, s.func, b, A, ident_expr(s.func, s.val_type[0]).c_str());
+            o.f("    if (threadIdx.x == 0) { u64 bits; __builtin_memcpy(&bits, &tot, 8); w_st_agent(a.b%zu_part + blockIdx.x, bits); }\n  }\n", b);
+        } else if (var.backend[b] == BK_DICT_REG) {
+            const int S = (int)s.capacity;
+            o.f("  __syncthreads();\n");
+            o.f("  _Pragma(\"unroll\") for (int q = 0; q < %d; ++q) {\n    const u64 kb = d%zu_lk[q];\n    if (kb != W_EMPTY_KEY) {\n", S, b);
+            for (int k = 0; k < s.nvals; ++k) {
+                const char* A = acc_ctype(s.val_type[k]);
+                o.f("      const %s r%d = w_block_reduce<%d>(d%zu_a%d[q], (%s*)s_red, %s);\n", A, k, s.func, b, k, A, ident_expr(s.func, s.val_type[k]).c_str());
+            }
+            o.f("      if (threadIdx.x == 0) {\n        const i64 g = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, kb, errp);\n        if (g >= 0) {\n", b, b, b);
+            for (int k = 0; k < s.nvals; ++k) o.f("          w_atomic<%d>(a.b%zu_v%d + g, r%d, 1);\n", s.func, b, k, k);
+            o.f("        }\n      }\n    }\n  }\n");
+        } else if (var.backend[b] == BK_DICT_LDS) {
+            o.f("  __syncthreads();\n");
+            o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) {\n    const u64 kb = d%zu_lk[q];\n    if (kb != W_EMPTY_KEY) {\n", var.lds_slots, b);
+            o.f("      const i64 g = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, kb, errp);\n      if (g >= 0) {\n", b, b, b);
+            for (int k = 0; k < s.nvals; ++k) o.f("        w_atomic<%d>(a.b%zu_v%d + g, d%zu_lv%d[q], 1);\n", s.func, b, k, b, k);
+            o.f("      }\n    }\n  }\n");
+        }
+    }
+    if (nmergers > 0) {
+        o.f("  if (w_arrive_last(a.ctl + 1, &s_flag)) {\n");
+        for (size_t b = 0; b < NB; ++b) {
+            const weld_builder_spec_t& s = L.builders[b];
+            if (var.backend[b] != BK_MERGER) continue;
+            const char* A = acc_ctype(s.val_type[0]);
+            o.f("    {\n      const %s tot = w_combine_partials<%d, %s>(a.b%zu_part, (%s*)s_red, %s);\n", A, s.func, A, b, A, ident_expr(s.func, s.val_type[0]).c_str());
+            o.f("      if (threadIdx.x == 0) *a.b%zu_res = (%s)tot;\n    }\n", b, ctype(s.val_type[0]));
+        }
+        o.f("  }\n");
+    }
+    o.f("}\n");
+    G.source = o.s;
+    G.lds_bytes = lds;
+    return G;
+}
+
+}  // namespace weld

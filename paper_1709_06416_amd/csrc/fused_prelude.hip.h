@@ -1,0 +1,332 @@
+// Device-side building blocks of the fused `for` loop kernels (gfx950, wave64).
+//
+// This text is compiled at run time together with a generated row function and
+// kernel skeleton, once per distinct loop (the paper's backends also generate
+// one fused kernel per program, Sec. 5 "Partial GPU Backend").  Everything in
+// here is written for 64-wide wavefronts: ballots are 64-bit, a work-group is
+// W_WAVES wavefronts, and each wavefront owns contiguous runs of rows so that
+// one load instruction of a wavefront covers one contiguous 64*16-byte span.
+//
+// Macros the generated code defines before this text:
+//   W_BLOCK  work-group size (multiple of 64)     W_V  rows per lane per load
+//   W_U      loads in flight per lane and column  W_ALIGNED 1 = 16-byte loads legal
+#define W_WAVES (W_BLOCK / 64)
+#define W_UNIT (64 * W_V)            /* rows one wavefront covers with one load   */
+#define W_WAVE_ROWS (W_UNIT * W_U)   /* contiguous rows owned by a wavefront      */
+#define W_TILE (W_WAVE_ROWS * W_WAVES)
+
+typedef unsigned long long u64;
+typedef long long i64;
+typedef unsigned int u32;
+
+#define W_FUNC_ADD 0
+#define W_FUNC_MUL 1
+#define W_FUNC_MIN 2
+#define W_FUNC_MAX 3
+
+#define W_EMPTY_KEY 0x8000000000000000ull
+
+// ---------------------------------------------------------------- column loader
+template <class T, int V> struct wvec { T e[V]; };
+
+// One lane reads V consecutive elements with a single wide load (16 bytes when
+// sizeof(T)*V == 16); a wavefront thereby reads one contiguous span.
+template <class T, int V>
+__device__ __forceinline__ wvec<T, V> w_load(const T* __restrict__ p) {
+    wvec<T, V> r;
+#if W_ALIGNED
+    typedef T vt __attribute__((ext_vector_type(V)));
+    const vt x = __builtin_nontemporal_load(reinterpret_cast<const vt*>(p));
+#pragma unroll
+    for (int k = 0; k < V; ++k) r.e[k] = x[k];
+#else
+#pragma unroll
+    for (int k = 0; k < V; ++k) r.e[k] = p[k];
+#endif
+    return r;
+}
+
+template <class T, int V>
+__device__ __forceinline__ void w_store(T* __restrict__ p, const wvec<T, V>& v) {
+#if W_ALIGNED
+    typedef T vt __attribute__((ext_vector_type(V)));
+    vt x;
+#pragma unroll
+    for (int k = 0; k < V; ++k) x[k] = v.e[k];
+    __builtin_nontemporal_store(x, reinterpret_cast<vt*>(p));
+#else
+#pragma unroll
+    for (int k = 0; k < V; ++k) p[k] = v.e[k];
+#endif
+}
+
+// ---------------------------------------------------------------- merge functions
+template <int F, class T> __device__ __forceinline__ T w_combine(T a, T b) {
+    if (F == W_FUNC_ADD) return a + b;
+    if (F == W_FUNC_MUL) return a * b;
+    if (F == W_FUNC_MIN) return b < a ? b : a;
+    return b > a ? b : a;
+}
+template <int F> __device__ __forceinline__ double w_identity_f64() {
+    if (F == W_FUNC_ADD) return 0.0;
+    if (F == W_FUNC_MUL) return 1.0;
+    if (F == W_FUNC_MIN) return __builtin_huge_val();
+    return -__builtin_huge_val();
+}
+// identity of an integer merger whose declared width is BITS (accumulated in 64 bits)
+template <int F, int BITS> __device__ __forceinline__ i64 w_identity_int() {
+    if (F == W_FUNC_ADD) return 0;
+    if (F == W_FUNC_MUL) return 1;
+    if (F == W_FUNC_MIN) return (i64)((1ull << (BITS - 1)) - 1);
+    return -(i64)(1ull << (BITS - 1));
+}
+
+// ---------------------------------------------------------------- wavefront level
+__device__ __forceinline__ int w_lane() {
+    return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+}
+// number of set bits of a 64-bit ballot below this lane
+__device__ __forceinline__ int w_rank_below(u64 ballot) {
+    return (int)__builtin_amdgcn_mbcnt_hi((u32)(ballot >> 32),
+                                          __builtin_amdgcn_mbcnt_lo((u32)ballot, 0u));
+}
+__device__ __forceinline__ u64 w_ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+
+// butterfly reduction over the 64 lanes; every lane ends with the same value, and
+// the combination order is fixed, so the result does not depend on scheduling
+template <int F, class T> __device__ __forceinline__ T w_wave_reduce(T v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = w_combine<F>(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+// work-group reduction: wavefront butterfly, then W_WAVES partials through LDS,
+// combined in wavefront order.  `scratch` has W_WAVES slots.  All threads call it;
+// all threads return the total.
+template <int F, class T>
+__device__ __forceinline__ T w_block_reduce(T v, T* scratch, T ident) {
+    v = w_wave_reduce<F>(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    T r = ident;
+#pragma unroll
+    for (int w = 0; w < W_WAVES; ++w) r = w_combine<F>(r, scratch[w]);
+    return r;
+}
+
+// ---------------------------------------------------------------- device-scope access
+// The eight XCDs have separate L2s: words other work-groups must see are read and
+// written with agent-scope atomics.
+__device__ __forceinline__ u64 w_ld_agent(const u64* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void w_st_agent(u64* p, u64 v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// ---------------------------------------------------------------- merger finish
+// Every work-group stores one partial per merger; the last one to arrive (ticket
+// on `done`) combines the partials in index order, which makes the result
+// independent of the order in which work-groups ran.  Call with all threads.
+// Returns true in the last work-group (which then holds the total in `total`).
+__device__ __forceinline__ bool w_arrive_last(u32* done, int* s_flag) {
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const u32 prev = __hip_atomic_fetch_add(done, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        *s_flag = (prev == gridDim.x - 1);
+    }
+    __syncthreads();
+    const bool last = (*s_flag != 0);
+    if (last) __threadfence();
+    return last;
+}
+
+template <int F, class T>
+__device__ __forceinline__ T w_combine_partials(const u64* partial, T* scratch, T ident) {
+    T v = ident;
+    for (u32 b = threadIdx.x; b < gridDim.x; b += W_BLOCK) {
+        const u64 bits = w_ld_agent(partial + b);
+        T x;
+        __builtin_memcpy(&x, &bits, 8);
+        v = w_combine<F>(v, x);
+    }
+    return w_block_reduce<F>(v, scratch, ident);
+}
+
+// ---------------------------------------------------------------- vecbuilder scan
+// Decoupled look-back over tile descriptors: bits 63..62 = state, 61..0 = count.
+//   0 = not yet published, 1 = this tile's own count, 2 = inclusive prefix.
+// Tiles are numbered by an atomic ticket in the order they START, so a tile only
+// ever waits for tiles that are already running.  Called by the 64 lanes of one
+// wavefront.  Returns the number of elements appended by all earlier tiles.
+// The wait is bounded: after `spin_limit` polls without progress the error flag is
+// raised and 0 is returned (writes then stay inside the output, the call reports
+// a device error), so the kernel always terminates.
+#define W_DESC_AGG (1ull << 62)
+#define W_DESC_PFX (2ull << 62)
+#define W_DESC_VAL ((1ull << 62) - 1)
+
+__device__ __forceinline__ i64 w_lookback(u64* desc, i64 tile, i64 own, i64 spin_limit, int* err) {
+    const int lane = w_lane();
+    if (tile == 0) {
+        if (lane == 0) w_st_agent(desc, W_DESC_PFX | (u64)own);
+        return 0;
+    }
+    if (lane == 0) w_st_agent(desc + tile, W_DESC_AGG | (u64)own);
+    i64 excl = 0;
+    i64 j = tile - 1;                       // nearest predecessor of the current window
+    i64 spins = 0;
+    bool failed = false;
+    for (;;) {
+        const i64 idx = j - lane;
+        const u64 d = idx >= 0 ? w_ld_agent(desc + idx) : W_DESC_PFX;
+        const u32 state = (u32)(d >> 62);
+        const u64 unpublished = w_ballot(state == 0);
+        const u64 have_prefix = w_ballot(state == 2);
+        const int first = have_prefix ? (int)__builtin_ctzll(have_prefix) : 64;
+        const u64 need = first >= 63 ? ~0ull : ((2ull << first) - 1);
+        if (unpublished & need) {
+            if (++spins > spin_limit) { failed = true; break; }
+            __builtin_amdgcn_s_sleep(2);
+            continue;
+        }
+        const i64 mine = (lane <= first) ? (i64)(d & W_DESC_VAL) : 0;
+        excl += w_wave_reduce<W_FUNC_ADD>(mine);
+        if (first < 64) break;
+        j -= 64;
+    }
+    if (failed) {
+        if (lane == 0) atomicOr(err, 2);
+        excl = 0;
+    }
+    if (lane == 0) w_st_agent(desc + tile, W_DESC_PFX | (u64)(excl + own));
+    return excl;
+}
+
+// ---------------------------------------------------------------- atomics on builders
+template <int F> __device__ __forceinline__ void w_atomic_f64(double* p, double v, const int scope_agent) {
+    if (F == W_FUNC_ADD) {
+        if (scope_agent) __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    } else {
+        u64* q = reinterpret_cast<u64*>(p);
+        u64 old = scope_agent ? __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                              : __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        for (;;) {
+            double cur;
+            __builtin_memcpy(&cur, &old, 8);
+            const double nxt = w_combine<F>(cur, v);
+            u64 nb;
+            __builtin_memcpy(&nb, &nxt, 8);
+            if (nb == old) break;
+            const bool ok = scope_agent
+                ? __hip_atomic_compare_exchange_strong(q, &old, nb, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                : __hip_atomic_compare_exchange_strong(q, &old, nb, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (ok) break;
+        }
+    }
+}
+template <int F> __device__ __forceinline__ void w_atomic_i64(i64* p, i64 v, const int scope_agent) {
+    if (F == W_FUNC_ADD) {
+        if (scope_agent) __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    } else if (F == W_FUNC_MIN) {
+        if (scope_agent) __hip_atomic_fetch_min(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else __hip_atomic_fetch_min(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    } else if (F == W_FUNC_MAX) {
+        if (scope_agent) __hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else __hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    } else {
+        i64 old = scope_agent ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                              : __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        for (;;) {
+            const i64 nxt = (i64)((u64)old * (u64)v);
+            const bool ok = scope_agent
+                ? __hip_atomic_compare_exchange_strong(p, &old, nxt, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                : __hip_atomic_compare_exchange_strong(p, &old, nxt, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (ok) break;
+        }
+    }
+}
+template <int F> __device__ __forceinline__ void w_atomic(double* p, double v, const int agent) { w_atomic_f64<F>(p, v, agent); }
+template <int F> __device__ __forceinline__ void w_atomic(i64* p, i64 v, const int agent) { w_atomic_i64<F>(p, v, agent); }
+
+// ---------------------------------------------------------------- hash tables
+__device__ __forceinline__ u32 w_hash(u64 k) {
+    k ^= k >> 33;
+    k *= 0xff51afd7ed558ccdull;
+    k ^= k >> 33;
+    return (u32)k ^ (u32)(k >> 32);
+}
+
+// Global open-addressing table (linear probing, power-of-two slot count, keys packed
+// into 64 bits, W_EMPTY_KEY marks a free slot).  The one key whose packed bits equal
+// the marker lives in the extra slot `slots` and is flagged in hdr[1].
+// Returns the slot, or -1 (and raises the capacity error) if the table is full.
+__device__ __forceinline__ i64 w_table_slot(u64* keys, u32* hdr, i64 slots, u64 kbits, int* err) {
+    if (kbits == W_EMPTY_KEY) {
+        __hip_atomic_store(hdr + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return slots;
+    }
+    const i64 mask = slots - 1;
+    i64 s = (i64)w_hash(kbits) & mask;
+    for (i64 probe = 0; probe < slots; ++probe) {
+        u64 cur = __hip_atomic_load(keys + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (cur == kbits) return s;
+        if (cur == W_EMPTY_KEY) {
+            u64 expect = W_EMPTY_KEY;
+            if (__hip_atomic_compare_exchange_strong(keys + s, &expect, kbits, __ATOMIC_RELAXED,
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+                return s;
+            if (expect == kbits) return s;
+        }
+        s = (s + 1) & mask;
+    }
+    atomicOr(err, 1);
+    return -1;
+}
+
+// Work-group private table in LDS: same scheme, at most `max_probe` probes; -1 means
+// "no room here", and the caller sends that merge to the global table instead.
+__device__ __forceinline__ int w_lds_slot(u64* keys, int slots, u64 kbits, int max_probe) {
+    if (kbits == W_EMPTY_KEY) return -1;
+    const int mask = slots - 1;
+    int s = (int)w_hash(kbits) & mask;
+    for (int probe = 0; probe < max_probe; ++probe) {
+        u64 cur = __hip_atomic_load(keys + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (cur == kbits) return s;
+        if (cur == W_EMPTY_KEY) {
+            u64 expect = W_EMPTY_KEY;
+            if (__hip_atomic_compare_exchange_strong(keys + s, &expect, kbits, __ATOMIC_RELAXED,
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP))
+                return s;
+            if (expect == kbits) return s;
+        }
+        s = (s + 1) & mask;
+    }
+    return -1;
+}
+
+// Register-slot dictionary for a handful of groups: the work-group keeps the list
+// of keys it has met in LDS (append-only); every lane accumulates each group in
+// registers.  Returns the slot of `kbits`, appending it if new; -1 if the list is
+// full (capacity error).
+template <int S>
+__device__ __forceinline__ int w_slot_list_insert(u64* s_keys, u64 kbits, int* err) {
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        u64 cur = __hip_atomic_load(s_keys + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (cur == kbits) return s;
+        if (cur == W_EMPTY_KEY) {
+            u64 expect = W_EMPTY_KEY;
+            if (__hip_atomic_compare_exchange_strong(s_keys + s, &expect, kbits, __ATOMIC_RELAXED,
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP))
+                return s;
+            if (expect == kbits) return s;
+        }
+    }
+    atomicOr(err, 1);
+    return -1;
+}

@@ -1,0 +1,457 @@
+// The C ABI: planning, workspace layout, launches and result handles.
+//
+// weld_fused_for is the evaluation entry of Sec. 4.1 of the paper restricted to one
+// already-fused loop: it validates the submitted body, plans how each builder is
+// realised on the GPU, takes one block from the device pool that holds results and
+// workspace together, and enqueues the kernels on the caller's stream.  The handle it
+// returns is the paper's WeldResult: checked for failure, queried for pointers, freed
+// by the caller (Sec. 4.1, 4.3).
+#include <hip/hip_runtime_api.h>
+
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+
+#include "aot_kernels.h"
+#include "weld_internal.h"
+
+namespace weld {
+
+static thread_local std::string g_last_error;
+void set_last_error(const std::string& s) { g_last_error = s; }
+
+}  // namespace weld
+
+using namespace weld;
+
+namespace {
+
+const int kCtlBytes = 256;
+// control words (u32 index): 0 tile ticket, 1 arrived work-groups, 2 error bits,
+// byte 16 + 8*b: length / entry count of builder b, byte 96 + 8*b: dictionary header
+inline size_t ctl_count_off(int b) { return 16 + 8 * (size_t)b; }
+inline size_t ctl_hdr_off(int b) { return 96 + 8 * (size_t)b; }
+
+std::mutex g_cache_mu;
+std::vector<uint32_t*> g_pinned;
+std::vector<hipEvent_t> g_events;
+
+uint32_t* get_pinned() {
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    if (!g_pinned.empty()) { uint32_t* p = g_pinned.back(); g_pinned.pop_back(); return p; }
+    void* p = nullptr;
+    if (hipHostMalloc(&p, kCtlBytes, hipHostMallocDefault) != hipSuccess) return nullptr;
+    return (uint32_t*)p;
+}
+hipEvent_t get_event() {
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    if (!g_events.empty()) { hipEvent_t e = g_events.back(); g_events.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+void put_back(weld_result* r) {
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    if (r->host_ctl) g_pinned.push_back(r->host_ctl);
+    if (r->ev0) g_events.push_back(r->ev0);
+    if (r->ev1) g_events.push_back(r->ev1);
+    r->host_ctl = nullptr;
+    r->ev0 = r->ev1 = nullptr;
+}
+
+Error mk(weld_status_t st, const std::string& s) {
+    Error e;
+    e.status = st;
+    e.text = s;
+    return e;
+}
+Error hip_err(const char* what, hipError_t h) {
+    return mk(WELD_ERR_DEVICE, std::string(what) + ": " + hipGetErrorString(h));
+}
+
+struct DeviceInfo {
+    bool ok = false;
+    int cus = 256;
+};
+DeviceInfo& device_info() {
+    static DeviceInfo d;
+    if (!d.ok) {
+        int dev = 0;
+        hipDeviceProp_t p;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&p, dev) == hipSuccess) {
+            d.cus = p.multiProcessorCount > 0 ? p.multiProcessorCount : 256;
+            d.ok = true;
+        }
+    }
+    return d;
+}
+
+uint64_t ident_bits(int func, int type) {
+    if (type == WELD_F64) {
+        double v = func == WELD_FUNC_ADD ? 0.0 : func == WELD_FUNC_MUL ? 1.0
+                 : func == WELD_FUNC_MIN ? __builtin_huge_val() : -__builtin_huge_val();
+        uint64_t b;
+        memcpy(&b, &v, 8);
+        return b;
+    }
+    const int bits = 8 * type_size(type);
+    int64_t v = func == WELD_FUNC_ADD ? 0 : func == WELD_FUNC_MUL ? 1
+              : func == WELD_FUNC_MIN ? (int64_t)((1ull << (bits - 1)) - 1) : -(int64_t)(1ull << (bits - 1));
+    return (uint64_t)v;
+}
+
+struct Layout {
+    size_t total = 0;
+    size_t take(size_t bytes) {
+        const size_t off = total;
+        total += (bytes + 255) / 256 * 256;
+        return off;
+    }
+};
+
+Error run_fused(const Loop& L, const weld_cols_t* cols, int64_t n, const weld_builder_t* builder, weld_result* r) {
+    const weld_conf_t& conf = builder->conf;
+    hipStream_t stream = (hipStream_t)conf.stream;
+    bool aligned = true;
+    for (int c = 0; c < L.ncols; ++c)
+        if (L.col_used[c] && ((uintptr_t)cols->col[c].data & 15)) aligned = false;
+    Variant var = choose_variant(L, conf.tune, aligned);
+    Generated G = generate(L, var);
+    Kernel* kern = nullptr;
+    Error e = jit_get(G.source, true, &kern);
+    if (!e.ok()) return e;
+
+    const size_t NB = L.builders.size();
+    const int64_t tile = (int64_t)var.block * var.v * var.u;
+    const int64_t ntiles = (n + tile - 1) / tile;
+    int64_t grid = conf.tune.grid_blocks > 0 ? conf.tune.grid_blocks : (int64_t)device_info().cus * 8;
+    if (grid > ntiles) grid = ntiles;
+    if (grid < 1) grid = 1;
+
+    // ---- one block: control words, per-builder workspace, results
+    Layout lay;
+    const size_t off_ctl = lay.take(kCtlBytes);
+    struct Off { size_t part = 0, res = 0, out = 0, desc = 0, keys = 0, vals[8] = {0}, okeys = 0, ovals = 0; int64_t slots = 0; };
+    std::vector<Off> off(NB);
+    for (size_t b = 0; b < NB; ++b) {
+        const weld_builder_spec_t& s = L.builders[b];
+        switch (var.backend[b]) {
+            case BK_MERGER:
+                off[b].part = lay.take(8 * (size_t)grid);
+                off[b].res = lay.take(8);
+                break;
+            case BK_VEC_DIRECT:
+                off[b].out = lay.take((size_t)n * type_size(s.val_type[0]));
+                break;
+            case BK_VEC_COMPACT:
+                off[b].out = lay.take((size_t)n * type_size(s.val_type[0]));
+                off[b].desc = lay.take(8 * (size_t)ntiles);
+                break;
+            default: {
+                int64_t slots = 64;
+                while (slots < 2 * s.capacity) slots *= 2;
+                off[b].slots = slots;
+                off[b].keys = lay.take(8 * (size_t)(slots + 1));
+                for (int k = 0; k < s.nvals; ++k) off[b].vals[k] = lay.take(8 * (size_t)(slots + 1));
+                int ks = 0, vs = 0;
+                for (int k = 0; k < s.nkeys; ++k) ks += type_size(s.key_type[k]);
+                for (int k = 0; k < s.nvals; ++k) vs += type_size(s.val_type[k]);
+                off[b].okeys = lay.take((size_t)s.capacity * ks);
+                off[b].ovals = lay.take((size_t)s.capacity * vs);
+            }
+        }
+    }
+    if (conf.memory_limit > 0 && (int64_t)lay.total > conf.memory_limit)
+        return mk(WELD_ERR_OOM, "the loop needs " + std::to_string(lay.total) + " bytes of device memory, limit is " +
+                                    std::to_string(conf.memory_limit));
+    void* block = nullptr;
+    e = pool_alloc(lay.total, &block);
+    if (!e.ok()) return e;
+    r->blocks.push_back(block);
+    char* base = (char*)block;
+
+    // ---- results
+    r->res.assign(NB, BuilderResult());
+    for (size_t b = 0; b < NB; ++b) {
+        const weld_builder_spec_t& s = L.builders[b];
+        BuilderResult& br = r->res[b];
+        br.kind = s.kind;
+        br.elem_size = type_size(s.val_type[0]);
+        if (s.kind == WELD_MERGER) {
+            br.scalar = base + off[b].res;
+        } else if (s.kind == WELD_VECBUILDER) {
+            br.vec.ptr = base + off[b].out;
+            br.known_len = (var.backend[b] == BK_VEC_DIRECT) ? (L.merge_of[b] >= 0 ? n : 0) : -1;
+        } else {
+            for (int k = 0; k < s.nkeys; ++k) br.key_stride += type_size(s.key_type[k]);
+            for (int k = 0; k < s.nvals; ++k) br.val_stride += type_size(s.val_type[k]);
+            br.dict.keys.ptr = base + off[b].okeys;
+            br.dict.values.ptr = base + off[b].ovals;
+        }
+    }
+
+    // ---- kernel arguments, in the order the generated struct declares them
+    std::vector<uint64_t> args;
+    for (const Slot& s : G.slots) {
+        uint64_t v = 0;
+        const int b = s.builder;
+        switch (s.kind) {
+            case SLOT_N: v = (uint64_t)n; break;
+            case SLOT_SPIN: v = conf.tune.spin_limit > 0 ? (uint64_t)conf.tune.spin_limit : (uint64_t)1 << 22; break;
+            case SLOT_COL: v = (uint64_t)(uintptr_t)cols->col[b].data; break;
+            case SLOT_CTL: v = (uint64_t)(uintptr_t)(base + off_ctl); break;
+            case SLOT_PARTIAL: v = (uint64_t)(uintptr_t)(base + off[b].part); break;
+            case SLOT_RESULT: v = (uint64_t)(uintptr_t)(base + off[b].res); break;
+            case SLOT_OUT: v = (uint64_t)(uintptr_t)(base + off[b].out); break;
+            case SLOT_DESC: v = (uint64_t)(uintptr_t)(base + off[b].desc); break;
+            case SLOT_LEN: v = (uint64_t)(uintptr_t)(base + off_ctl + ctl_count_off(b)); break;
+            case SLOT_DKEYS: v = (uint64_t)(uintptr_t)(base + off[b].keys); break;
+            case SLOT_DHDR: v = (uint64_t)(uintptr_t)(base + off_ctl + ctl_hdr_off(b)); break;
+            case SLOT_DSLOTS: v = (uint64_t)off[b].slots; break;
+            case SLOT_DVAL: v = (uint64_t)(uintptr_t)(base + off[b].vals[s.field]); break;
+        }
+        args.push_back(v);
+    }
+
+    // ---- enqueue
+    hipError_t h;
+    if ((h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    if ((h = launch_fill64(base + off_ctl, kCtlBytes / 8, 0, stream)) != hipSuccess) return hip_err("fill", h);
+    r->kernel_count++;
+    for (size_t b = 0; b < NB; ++b) {
+        const weld_builder_spec_t& s = L.builders[b];
+        if (var.backend[b] == BK_VEC_COMPACT && ntiles > 0) {
+            if ((h = launch_fill64(base + off[b].desc, ntiles, 0, stream)) != hipSuccess) return hip_err("fill", h);
+            r->kernel_count++;
+        } else if (s.kind == WELD_DICTMERGER) {
+            if ((h = launch_fill64(base + off[b].keys, off[b].slots + 1, 0x8000000000000000ull, stream)) != hipSuccess)
+                return hip_err("fill", h);
+            r->kernel_count++;
+            for (int k = 0; k < s.nvals; ++k) {
+                if ((h = launch_fill64(base + off[b].vals[k], off[b].slots + 1, ident_bits(s.func, s.val_type[k]), stream)) != hipSuccess)
+                    return hip_err("fill", h);
+                r->kernel_count++;
+            }
+        }
+    }
+    e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream);
+    if (!e.ok()) return e;
+    r->kernel_count++;
+    for (size_t b = 0; b < NB; ++b) {
+        const weld_builder_spec_t& s = L.builders[b];
+        if (s.kind != WELD_DICTMERGER) continue;
+        DictLayout dl;
+        memset(&dl, 0, sizeof dl);
+        DictValues dv;
+        memset(&dv, 0, sizeof dv);
+        dl.nkeys = s.nkeys;
+        int shift = 0;
+        for (int k = 0; k < s.nkeys; ++k) {
+            dl.key_size[k] = type_size(s.key_type[k]);
+            dl.key_shift[k] = shift;
+            shift += 8 * dl.key_size[k];
+            dl.key_stride += dl.key_size[k];
+        }
+        dl.nvals = s.nvals;
+        for (int k = 0; k < s.nvals; ++k) {
+            dl.val_size[k] = type_size(s.val_type[k]);
+            dl.val_stride += dl.val_size[k];
+            dv.p[k] = (const unsigned long long*)(base + off[b].vals[k]);
+        }
+        h = launch_dict_extract(base + off[b].keys, base + off_ctl + ctl_hdr_off((int)b), off[b].slots, dv, dl, s.capacity,
+                                base + off[b].okeys, base + off[b].ovals, base + off_ctl + ctl_count_off((int)b),
+                                base + off_ctl + 8, stream);
+        if (h != hipSuccess) return hip_err("dict extract", h);
+        r->kernel_count++;
+    }
+    if ((h = hipEventRecord(r->ev1, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    if ((h = hipMemcpyAsync(r->host_ctl, base + off_ctl, kCtlBytes, hipMemcpyDeviceToHost, stream)) != hipSuccess)
+        return hip_err("hipMemcpyAsync", h);
+    return Error();
+}
+
+void destroy(weld_result* r) {
+    if (!r) return;
+    if (!r->synced && !r->blocks.empty()) (void)hipStreamSynchronize((hipStream_t)r->stream);
+    for (void* p : r->blocks) pool_free(p);
+    put_back(r);
+    delete r;
+}
+
+}  // namespace
+
+extern "C" {
+
+weld_status_t weld_fused_for(const weld_cols_t* cols, int64_t n, const weld_body_t* body,
+                             const weld_builder_t* builder, weld_result_t** out) {
+    if (out) *out = nullptr;
+    if (!cols || !body || !builder || !out) { set_last_error("null argument"); return WELD_ERR_INVALID_ARG; }
+    if (n < 0) { set_last_error("negative row count"); return WELD_ERR_INVALID_ARG; }
+    if (cols->ncols < 0 || cols->ncols > WELD_MAX_COLS || (cols->ncols > 0 && !cols->col)) {
+        set_last_error("bad column list");
+        return WELD_ERR_INVALID_ARG;
+    }
+    int32_t types[WELD_MAX_COLS];
+    for (int c = 0; c < cols->ncols; ++c) types[c] = cols->col[c].type;
+    Loop L;
+    Error e = validate(types, cols->ncols, body, builder, &L);
+    if (!e.ok()) { set_last_error(e.text); return e.status; }
+    for (int c = 0; c < cols->ncols; ++c) {
+        if (n > 0 && L.col_used[c] && !cols->col[c].data) { set_last_error("null column pointer"); return WELD_ERR_INVALID_ARG; }
+        if ((uintptr_t)cols->col[c].data % (uintptr_t)type_size(L.col_type[c])) {
+            set_last_error("column pointer not aligned to its element size");
+            return WELD_ERR_INVALID_ARG;
+        }
+    }
+    weld_result* r = new weld_result();
+    r->stream = builder->conf.stream;
+    r->host_ctl = get_pinned();
+    r->ev0 = get_event();
+    r->ev1 = get_event();
+    if (!r->host_ctl || !r->ev0 || !r->ev1) {
+        destroy(r);
+        set_last_error("could not allocate pinned memory / events (no usable HIP device?)");
+        return WELD_ERR_DEVICE;
+    }
+    memset(r->host_ctl, 0, kCtlBytes);
+    e = builder->conf.mode == WELD_MODE_FUSED ? run_fused(L, cols, n, builder, r) : run_unfused(L, cols, n, builder, r);
+    if (!e.ok()) {
+        set_last_error(e.text);
+        destroy(r);
+        return e.status;
+    }
+    *out = r;
+    return WELD_OK;
+}
+
+weld_status_t weld_result_status(weld_result_t* r) {
+    if (!r) return WELD_ERR_INVALID_ARG;
+    if (r->synced) return r->status;
+    hipError_t h = hipStreamSynchronize((hipStream_t)r->stream);
+    r->synced = true;
+    if (h != hipSuccess) {
+        r->status = WELD_ERR_DEVICE;
+        r->error = std::string("hipStreamSynchronize: ") + hipGetErrorString(h);
+        return r->status;
+    }
+    (void)hipEventElapsedTime(&r->ms, r->ev0, r->ev1);
+    const uint32_t err = r->host_ctl[2];
+    if (err & 2) {
+        r->status = WELD_ERR_DEVICE;
+        r->error = "a tile gave up waiting for the prefix of its predecessors (spin limit reached)";
+    } else if (err & 1) {
+        r->status = WELD_ERR_CAPACITY;
+        r->error = "dictmerger met more distinct keys than its declared capacity";
+    }
+    for (size_t b = 0; b < r->res.size(); ++b) {
+        BuilderResult& br = r->res[b];
+        int64_t cnt;
+        memcpy(&cnt, (const char*)r->host_ctl + ctl_count_off((int)b), 8);
+        if (br.kind == WELD_VECBUILDER) {
+            br.vec.len = br.known_len >= 0 ? br.known_len : cnt;
+        } else if (br.kind == WELD_DICTMERGER) {
+            br.dict.keys.len = cnt;
+            br.dict.values.len = cnt;
+        }
+    }
+    return r->status;
+}
+
+const char* weld_result_error(const weld_result_t* r) { return r ? r->error.c_str() : ""; }
+
+const void* weld_result_data(weld_result_t* r, int32_t idx) {
+    if (!r || idx < 0 || idx >= (int32_t)r->res.size()) return nullptr;
+    if (weld_result_status(r) != WELD_OK) return nullptr;
+    BuilderResult& br = r->res[idx];
+    if (br.kind == WELD_MERGER) return br.scalar;
+    if (br.kind == WELD_VECBUILDER) return &br.vec;
+    return &br.dict;
+}
+
+weld_status_t weld_result_fetch(weld_result_t* r, int32_t idx, int32_t part, void* dst, int64_t offset,
+                                int64_t bytes, int32_t dst_is_device) {
+    if (!r || idx < 0 || idx >= (int32_t)r->res.size() || !dst || offset < 0 || bytes < 0) return WELD_ERR_INVALID_ARG;
+    weld_status_t st = weld_result_status(r);
+    if (st != WELD_OK) return st;
+    BuilderResult& br = r->res[idx];
+    const char* src = nullptr;
+    int64_t avail = 0;
+    if (br.kind == WELD_MERGER) { src = (const char*)br.scalar; avail = br.elem_size; }
+    else if (br.kind == WELD_VECBUILDER) { src = (const char*)br.vec.ptr; avail = br.vec.len * br.elem_size; }
+    else if (part == 0) { src = (const char*)br.dict.keys.ptr; avail = br.dict.keys.len * br.key_stride; }
+    else { src = (const char*)br.dict.values.ptr; avail = br.dict.values.len * br.val_stride; }
+    if (offset + bytes > avail) return WELD_ERR_INVALID_ARG;
+    if (bytes == 0) return WELD_OK;
+    hipError_t h = hipMemcpy(dst, src + offset, (size_t)bytes, dst_is_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost);
+    if (h != hipSuccess) { r->error = std::string("hipMemcpy: ") + hipGetErrorString(h); return WELD_ERR_DEVICE; }
+    return WELD_OK;
+}
+
+weld_status_t weld_result_elapsed_ms(weld_result_t* r, float* ms) {
+    if (!r || !ms) return WELD_ERR_INVALID_ARG;
+    weld_status_t st = weld_result_status(r);
+    *ms = r->ms;
+    return st;
+}
+
+int32_t weld_result_kernel_count(const weld_result_t* r) { return r ? r->kernel_count : 0; }
+
+void weld_result_free(weld_result_t* r) { destroy(r); }
+
+weld_status_t weld_validate(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
+                            const weld_builder_t* builder, char* err, size_t errlen) {
+    Loop L;
+    Error e = validate(col_types, ncols, body, builder, &L);
+    if (err && errlen) snprintf(err, errlen, "%s", e.text.c_str());
+    if (!e.ok()) set_last_error(e.text);
+    return e.status;
+}
+
+int64_t weld_generated_source(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
+                              const weld_builder_t* builder, char* buf, int64_t buflen) {
+    Loop L;
+    Error e = validate(col_types, ncols, body, builder, &L);
+    if (!e.ok()) { set_last_error(e.text); return -1; }
+    Variant var = choose_variant(L, builder->conf.tune, true);
+    Generated G = generate(L, var);
+    if (buf && buflen > 0) snprintf(buf, (size_t)buflen, "%s", G.source.c_str());
+    return (int64_t)G.source.size() + 1;
+}
+
+weld_status_t weld_precompile(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
+                              const weld_builder_t* builder) {
+    Loop L;
+    Error e = validate(col_types, ncols, body, builder, &L);
+    if (!e.ok()) { set_last_error(e.text); return e.status; }
+    if (builder->conf.mode != WELD_MODE_FUSED) return WELD_OK;  // unfused kernels are compiled ahead of time
+    for (int aligned = 1; aligned >= 0; --aligned) {
+        Variant var = choose_variant(L, builder->conf.tune, aligned != 0);
+        Generated G = generate(L, var);
+        Kernel* k = nullptr;
+        e = jit_get(G.source, false, &k);
+        if (!e.ok()) { set_last_error(e.text); return e.status; }
+    }
+    return WELD_OK;
+}
+
+weld_status_t weld_set_cache_dir(const char* path) { return set_cache_dir(path).status; }
+
+void weld_pool_trim(void) { pool_trim(); }
+int64_t weld_pool_bytes(void) { return pool_bytes(); }
+const char* weld_last_error(void) { return g_last_error.c_str(); }
+
+weld_status_t weld_probe_read(const void* data, int64_t bytes, void* checksum_dev, void* stream) {
+    if (!data || !checksum_dev || bytes < 0 || ((uintptr_t)data & 15)) return WELD_ERR_INVALID_ARG;
+    hipError_t h = launch_probe_read(data, bytes, checksum_dev, device_info().cus * 8, (hipStream_t)stream);
+    return h == hipSuccess ? WELD_OK : WELD_ERR_DEVICE;
+}
+
+weld_status_t weld_probe_copy(void* dst, const void* src, int64_t bytes, void* stream) {
+    if (!dst || !src || bytes < 0 || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return WELD_ERR_INVALID_ARG;
+    hipError_t h = launch_probe_copy(dst, src, bytes, device_info().cus * 8, (hipStream_t)stream);
+    return h == hipSuccess ? WELD_OK : WELD_ERR_DEVICE;
+}
+
+const char* weld_version(void) { return "weld-hip 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,138 @@
+// Internal declarations shared by the host-side translation units of libweldhip.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "weld_hip.h"
+
+#include <hip/hip_runtime_api.h>
+
+struct BuilderResult {
+    int kind = 0;
+    void* scalar = nullptr;   // merger: device pointer to the scalar
+    weld_vec_t vec = {0, nullptr};
+    weld_dict_t dict = {{0, nullptr}, {0, nullptr}};
+    int elem_size = 0;        // vecbuilder element / merger scalar size
+    int key_stride = 0, val_stride = 0;
+    int64_t known_len = -1;   // vecbuilder without predicate: n
+};
+
+struct weld_result {
+    std::vector<BuilderResult> res;
+    std::vector<void*> blocks;   // pool blocks owned by this result
+    void* stream = nullptr;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    uint32_t* host_ctl = nullptr;  // pinned copy of the control words
+    bool synced = false;
+    weld_status_t status = WELD_OK;
+    std::string error;
+    int kernel_count = 0;
+    float ms = -1.f;
+};
+
+namespace weld {
+
+inline int type_size(int t) {
+    switch (t) {
+        case WELD_BOOL: return 1;
+        case WELD_I8: return 1;
+        case WELD_I32: return 4;
+        case WELD_I64: return 8;
+        case WELD_F64: return 8;
+    }
+    return 0;
+}
+inline bool type_is_int(int t) { return t == WELD_I8 || t == WELD_I32 || t == WELD_I64; }
+inline bool type_is_num(int t) { return type_is_int(t) || t == WELD_F64; }
+inline bool type_valid(int t) { return t >= WELD_BOOL && t <= WELD_F64; }
+
+// A validated copy of one submitted loop.
+struct Loop {
+    int ncols = 0;
+    int col_type[WELD_MAX_COLS] = {0};
+    bool col_used[WELD_MAX_COLS] = {false};
+    std::vector<weld_op_t> ops;
+    std::vector<weld_builder_spec_t> builders;
+    std::vector<int> merge_of;           // per builder: index into merges, or -1
+    std::vector<weld_merge_t> merges;
+};
+
+struct Error {
+    weld_status_t status = WELD_OK;
+    std::string text;
+    bool ok() const { return status == WELD_OK; }
+};
+
+void set_last_error(const std::string& s);
+
+// validate.cpp
+Error validate(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
+               const weld_builder_t* builder, Loop* out);
+
+// How each builder is realised inside the fused kernel.
+enum Backend {
+    BK_MERGER = 0,      // register accumulator, work-group partials, last-arriver combine
+    BK_VEC_DIRECT = 1,  // no predicate: out[i] = v, length known in advance (size analysis)
+    BK_VEC_COMPACT = 2, // ballot/popcount ranks + decoupled look-back over tile descriptors
+    BK_DICT_REG = 3,    // <= 8 groups: key list in LDS, per-lane register accumulators
+    BK_DICT_LDS = 4,    // work-group hash table in LDS in front of the global table
+    BK_DICT_GLOBAL = 5  // global open-addressing table only
+};
+
+// Compile-time shape of one fused kernel.  Two loops with equal Variant and equal
+// body text share one compiled code object.
+struct Variant {
+    int block = 256;      // W_BLOCK
+    int v = 2;            // W_V rows per lane per load
+    int u = 4;            // W_U loads in flight per lane and column
+    int aligned = 1;      // 16-byte accesses legal for every pointer
+    bool ticketed = false;// tile order taken from an atomic ticket (needed by look-back)
+    int lds_slots = 0;    // slots of the LDS dictionary (BK_DICT_LDS)
+    std::vector<int> backend;   // per builder
+};
+
+// One 8-byte kernel argument.  The generated `struct KArgs` lists them in this order.
+enum SlotKind {
+    SLOT_N = 0, SLOT_SPIN, SLOT_COL, SLOT_CTL,
+    SLOT_PARTIAL, SLOT_RESULT,          // merger
+    SLOT_OUT, SLOT_DESC, SLOT_LEN,      // vecbuilder
+    SLOT_DKEYS, SLOT_DHDR, SLOT_DSLOTS, SLOT_DVAL  // dictmerger
+};
+struct Slot {
+    SlotKind kind;
+    int builder;  // or column index
+    int field;    // value field for SLOT_DVAL
+    std::string name;
+    std::string ctype;
+};
+
+struct Generated {
+    std::string source;
+    std::vector<Slot> slots;
+    int lds_bytes = 0;
+};
+
+// codegen.cpp
+Variant choose_variant(const Loop& loop, const weld_tuning_t& tune, bool aligned);
+Generated generate(const Loop& loop, const Variant& var);
+int key_bits(const weld_builder_spec_t& b);
+
+// jit.cpp
+struct Kernel;  // compiled + loaded
+Error jit_get(const std::string& source, bool load_on_device, Kernel** out);
+Error jit_launch(Kernel* k, unsigned grid, unsigned block, void* args, size_t args_bytes, void* stream);
+Error set_cache_dir(const char* path);
+
+// pool.cpp
+Error pool_alloc(size_t bytes, void** out);
+void pool_free(void* p);
+void pool_trim();
+int64_t pool_bytes();
+
+// unfused.cpp
+Error run_unfused(const Loop& loop, const weld_cols_t* cols, int64_t n, const weld_builder_t* builder,
+                  weld_result* r);
+
+}  // namespace weld

@@ -1,0 +1,61 @@
+"""Shared comparison rules for the GPU parity tests (test infrastructure).
+
+Tolerances (stated by the benchmark spec, restated in the design doc):
+  * integer, count, compaction-order and key-set outputs: bit-exact;
+  * f64 merger / dictmerger sums: 1e-9 relative to the correctly rounded sum;
+  * f64 min / max: bit-exact (order independent);
+  * f64 map outputs (vecbuilder of f64): 1e-12 relative per element, with an
+    absolute floor `map_floor` (0 unless a test states why it needs one).
+"""
+import numpy as np
+
+from oracle import interp
+
+SUM_RTOL = 1e-9
+MAP_RTOL = 1e-12
+
+
+def oracle_results(prog, cols_gpu):
+    return interp.run(prog, [c.cpu().numpy() for c in cols_gpu], sums="exact")
+
+
+def _close_sum(got, want, func):
+    got, want = float(got), float(want)
+    if func in ("min", "max"):
+        return got == want
+    return abs(got - want) <= SUM_RTOL * abs(want)
+
+
+def assert_matches(prog, res, want, map_floor=0.0, label=""):
+    res.check()
+    for b, spec in enumerate(prog.builders):
+        tag = "%s builder %d (%s)" % (label, b, spec["kind"])
+        if spec["kind"] == "merger":
+            got = res.merger(b)
+            if spec["type"] == "f64":
+                assert _close_sum(got, want[b], spec["func"]), (tag, got, want[b])
+            else:
+                assert int(got) == int(want[b]), (tag, got, want[b])
+        elif spec["kind"] == "vecbuilder":
+            got = res.vec_host(b)
+            assert len(got) == len(want[b]), (tag, len(got), len(want[b]))
+            if spec["type"] == "f64":
+                bound = MAP_RTOL * np.maximum(np.abs(want[b]), map_floor)
+                bad = np.flatnonzero(~(np.abs(got - want[b]) <= bound))
+                assert bad.size == 0, (tag, bad[:5], got[bad[:5]], want[b][bad[:5]])
+            else:
+                assert np.array_equal(got, want[b]), tag
+        else:
+            keys, vals = res.dict(b, sort=True)
+            wkeys, wvals = want[b]
+            assert len(keys[0]) == len(wkeys[0]), (tag, len(keys[0]), len(wkeys[0]))
+            for g, w in zip(keys, wkeys):
+                assert np.array_equal(g, w), tag + " keys"
+            for t, g, w in zip(spec["val_types"], vals, wvals):
+                if t == "f64":
+                    if spec["func"] in ("min", "max"):
+                        assert np.array_equal(g, w), tag + " values"
+                    else:
+                        assert np.all(np.abs(g - w) <= SUM_RTOL * np.abs(w)), (tag, g, w)
+                else:
+                    assert np.array_equal(g, w), tag + " values"

@@ -1,0 +1,121 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+declared symbol, validates loop bodies (Sec. 3.2: typed IR, linear builders) and can
+generate and compile kernels for gfx950 on a machine without the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from workloads import configs
+from workloads.ir import Program
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_1709_06416_amd", "libweldhip.so")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libweldhip.so not built (python -m paper_1709_06416_amd.build)")
+
+
+@pytest.fixture(scope="module")
+def wb():
+    from paper_1709_06416_amd import binding
+    return binding
+
+
+def test_every_declared_symbol_is_exported(wb):
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for fn in os.listdir(inc):
+        text = open(os.path.join(inc, fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(weld_[a-z0-9_]+)\s*\(", text))
+    assert "weld_fused_for" in names and len(names) >= 15
+    lib = ctypes.CDLL(LIB)
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+@pytest.mark.parametrize("name", list(configs.PROGRAMS) + list(configs.EXAMPLES))
+def test_standard_loops_validate(wb, name):
+    make = configs.PROGRAMS.get(name) or configs.EXAMPLES[name]
+    st, msg = wb.validate(make())
+    assert st == wb.OK, msg
+
+
+def test_linearity_violation_is_rejected(wb):
+    p = Program(["i64"])
+    m = p.merger("i64", "add")
+    p.merge(m, p.col(0))
+    p.merge(m, p.col(0))                      # the same builder consumed twice
+    st, msg = wb.validate(p)
+    assert st == wb.ERR_LINEARITY and "builder 0" in msg
+
+
+def test_type_errors_are_rejected(wb):
+    p = Program(["i32", "f64"])
+    p.ops.append(("add", "f64", p.col(0), p.col(1)))          # i32 + f64 without a cast
+    p.merge(p.merger("f64", "add"), len(p.ops) - 1)
+    assert wb.validate(p)[0] == wb.ERR_TYPE
+
+    p = Program(["f64"])
+    p.merge(p.merger("i64", "add"), p.col(0))                  # f64 value into an i64 merger
+    assert wb.validate(p)[0] == wb.ERR_TYPE
+
+    p = Program(["f64"])
+    p.merge(p.merger("f64", "add"), p.col(0), pred=p.col(0))   # predicate is not bool
+    assert wb.validate(p)[0] == wb.ERR_TYPE
+
+    p = Program(["i32"])
+    p.ops.append(("lt", "bool", p.col(0), p.const("i64", 3)))  # compare i32 with i64
+    p.merge(p.merger("i32", "add"), 0, pred=len(p.ops) - 1)
+    assert wb.validate(p)[0] == wb.ERR_TYPE
+
+
+def test_malformed_bodies_are_rejected(wb):
+    p = Program(["i64"])
+    p.ops.append(("col", "i64", 3))                            # undeclared column
+    p.merge(p.merger("i64", "add"), 0)
+    assert wb.validate(p)[0] == wb.ERR_INVALID_ARG
+
+    p = Program(["i64"])
+    p.ops.append(("add", "i64", 0, 1))                         # operand is not an earlier op
+    p.merge(p.merger("i64", "add"), 0)
+    assert wb.validate(p)[0] == wb.ERR_INVALID_ARG
+
+    p = Program(["i64"])
+    p.merge(p.merger("i64", "add"), p.bin("mod", p.col(0), p.const("i64", 0)))   # mod by constant 0
+    assert wb.validate(p)[0] == wb.ERR_INVALID_ARG
+
+    p = Program(["f64"])
+    p.merge(p.dictmerger(["f64"], ["i64"], "add", 8), [p.const("i64", 1)], keys=[p.col(0)])  # f64 key
+    assert wb.validate(p)[0] == wb.ERR_UNSUPPORTED
+
+    p = Program(["i64"])
+    p.merge(p.dictmerger(["i64", "i8"], ["i64"], "add", 8), [p.const("i64", 1)],
+            keys=[p.col(0), p.un("cast", p.col(0), to="i8")])                    # 72-bit key struct
+    assert wb.validate(p)[0] == wb.ERR_UNSUPPORTED
+
+
+def test_generated_source_has_one_statement_per_operator(wb):
+    prog = configs.program_c3()
+    src = wb.generated_source(prog)
+    body = src[src.index("void weld_row("):src.index("#define WELD_MERGE")]
+    assert len(re.findall(r"^\s+const \w[\w ]* t\d+ = ", body, flags=re.M)) == len(prog.ops)
+    assert "weld_kernel" in src and "w_block_reduce" in src
+    # constants are emitted bit-exactly
+    assert "0x3fa999999999999a" in src            # 0.05
+
+
+def test_kernels_compile_for_gfx950_without_a_gpu(wb, tmp_path):
+    assert wb.lib.weld_set_cache_dir(str(tmp_path).encode()) == wb.OK
+    try:
+        p = Program(["i32", "f64"])
+        pred = p.bin("lt", p.col(0), p.const("i32", 17))
+        p.merge(p.vecbuilder("f64"), p.un("sqrt", p.col(1)), pred=pred)
+        p.merge(p.merger("f64", "max"), p.col(1))
+        wb.precompile(p)
+        objs = [f for f in os.listdir(tmp_path) if f.endswith(".hsaco")]
+        assert len(objs) == 2                      # aligned and scalar-load variants
+        assert all(os.path.getsize(os.path.join(tmp_path, f)) > 1000 for f in objs)
+    finally:
+        wb.lib.weld_set_cache_dir(os.path.join(ROOT, "paper_1709_06416_amd", "kcache").encode())
