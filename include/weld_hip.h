@@ -215,6 +215,9 @@ weld_status_t weld_result_fetch(weld_result_t* r, int32_t idx, int32_t part, voi
  * on conf.stream around the enqueued work (valid after weld_result_status()). */
 weld_status_t weld_result_elapsed_ms(weld_result_t* r, float* ms);
 
+/* Same, for the main loop kernel alone (fused mode; -1 if the call ran none). */
+weld_status_t weld_result_kernel_ms(weld_result_t* r, float* ms);
+
 /* Number of kernels the call launched (1-2 in fused mode, one per operator unfused). */
 int32_t weld_result_kernel_count(const weld_result_t* r);
 

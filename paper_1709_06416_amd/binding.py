@@ -105,6 +105,8 @@ lib.weld_result_fetch.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, 
 lib.weld_result_fetch.restype = C.c_int
 lib.weld_result_elapsed_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
 lib.weld_result_elapsed_ms.restype = C.c_int
+lib.weld_result_kernel_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
+lib.weld_result_kernel_ms.restype = C.c_int
 lib.weld_result_kernel_count.argtypes = [C.c_void_p]
 lib.weld_result_kernel_count.restype = C.c_int32
 lib.weld_result_free.argtypes = [C.c_void_p]
@@ -235,6 +237,11 @@ class Result:
     def elapsed_ms(self):
         ms = C.c_float()
         lib.weld_result_elapsed_ms(self._h, C.byref(ms))
+        return ms.value
+
+    def kernel_ms(self):
+        ms = C.c_float()
+        lib.weld_result_kernel_ms(self._h, C.byref(ms))
         return ms.value
 
     def kernel_count(self):

@@ -20,6 +20,19 @@ struct DictValues {
     const unsigned long long* p[8];
 };
 
+// One entry per merger of a call: combine `count` 8-byte partials with `func` in index
+// order and store the result, narrowed to `elem_size` bytes for integer types.
+struct MergerFinish {
+    int n;
+    const unsigned long long* partial[8];
+    void* result[8];
+    int func[8];
+    int is_f64[8];
+    int elem_size[8];
+    int bits[8];
+};
+hipError_t launch_merger_finish(const MergerFinish& m, int count, hipStream_t stream);
+
 hipError_t launch_fill64(void* p, int64_t count, uint64_t value, hipStream_t stream);
 hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots, const DictValues& vals,
                                const DictLayout& lay, int64_t capacity, void* out_keys, void* out_vals,

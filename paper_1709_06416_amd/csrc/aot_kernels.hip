@@ -28,6 +28,70 @@ hipError_t launch_fill64(void* p, int64_t count, uint64_t value, hipStream_t str
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- merger result
+// Fixed-order combination of the per-work-group partials of every merger of a call
+// (one work-group per merger).  Thread j folds partials j, j+256, ... in that order,
+// then the 256 per-thread values are combined by a fixed butterfly and in wavefront
+// order, so the result is the same on every run.
+template <class T> __device__ T combine(int func, T a, T b) {
+    switch (func) {
+        case 0: return a + b;
+        case 1: return a * b;
+        case 2: return b < a ? b : a;
+        default: return b > a ? b : a;
+    }
+}
+template <class T> __device__ T block_combine(int func, T v, T ident, T* scratch) {
+    for (int off = 32; off > 0; off >>= 1) v = combine(func, v, (T)__shfl_xor(v, off, 64));
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    T r = ident;
+    for (int w = 0; w < 4; ++w) r = combine(func, r, scratch[w]);
+    return r;
+}
+
+__global__ void __launch_bounds__(256) merger_finish_kernel(MergerFinish m, int count) {
+    __shared__ u64 scratch[4];
+    const int b = blockIdx.x;
+    const int func = m.func[b];
+    const u64* part = m.partial[b];
+    if (m.is_f64[b]) {
+        const double ident = func == 0 ? 0.0 : func == 1 ? 1.0 : func == 2 ? __builtin_huge_val() : -__builtin_huge_val();
+        double v = ident;
+        for (int i = threadIdx.x; i < count; i += 256) v = combine(func, v, __longlong_as_double((i64)part[i]));
+        v = block_combine(func, v, ident, (double*)scratch);
+        if (threadIdx.x == 0) *(double*)m.result[b] = v;
+    } else {
+        const int bits = m.bits[b];
+        const i64 ident = func == 0 ? 0 : func == 1 ? 1 : func == 2 ? (i64)((1ull << (bits - 1)) - 1) : -(i64)(1ull << (bits - 1));
+        i64 v = ident;
+        for (int i = threadIdx.x; i < count; i += 256) {
+            const i64 x = (i64)part[i];
+            v = func == 1 ? (i64)((u64)v * (u64)x) : func == 0 ? (i64)((u64)v + (u64)x) : combine(func, v, x);
+        }
+        // wrapping arithmetic through the unsigned type inside the tree as well
+        for (int off = 32; off > 0; off >>= 1) {
+            const i64 o = __shfl_xor(v, off, 64);
+            v = func == 1 ? (i64)((u64)v * (u64)o) : func == 0 ? (i64)((u64)v + (u64)o) : combine(func, v, o);
+        }
+        i64* sc = (i64*)scratch;
+        if ((threadIdx.x & 63) == 0) sc[threadIdx.x >> 6] = v;
+        __syncthreads();
+        i64 r = ident;
+        for (int w = 0; w < 4; ++w) r = func == 1 ? (i64)((u64)r * (u64)sc[w]) : func == 0 ? (i64)((u64)r + (u64)sc[w]) : combine(func, r, sc[w]);
+        if (threadIdx.x == 0) {
+            unsigned char* out = (unsigned char*)m.result[b];
+            for (int k = 0; k < m.elem_size[b]; ++k) out[k] = (unsigned char)((u64)r >> (8 * k));
+        }
+    }
+}
+
+hipError_t launch_merger_finish(const MergerFinish& m, int count, hipStream_t stream) {
+    if (m.n <= 0) return hipSuccess;
+    merger_finish_kernel<<<dim3((unsigned)m.n), dim3(256), 0, stream>>>(m, count);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- dictionary result
 // Walks the open-addressing table and writes every occupied slot as one (key struct,
 // value struct) pair in C packed layout (Sec. 4.2 of the paper).  Entry order is

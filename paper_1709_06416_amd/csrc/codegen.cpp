@@ -283,7 +283,6 @@ Generated generate(const Loop& L, const Variant& var) {
         switch (var.backend[b]) {
             case BK_MERGER:
                 slot(SLOT_PARTIAL, (int)b, 0, B + "_part", "u64*");
-                slot(SLOT_RESULT, (int)b, 0, B + "_res", std::string(ctype(s.val_type[0])) + "*");
                 break;
             case BK_VEC_DIRECT:
                 slot(SLOT_OUT, (int)b, 0, B + "_out", std::string(ctype(s.val_type[0])) + "* __restrict__");
@@ -355,10 +354,10 @@ Generated generate(const Loop& L, const Variant& var) {
 
     // ------------------------------------------------------------ kernel
     o.f("extern \"C\" __global__ void __launch_bounds__(W_BLOCK) weld_kernel(const KArgs a) {\n");
-    o.f("  __shared__ u64 s_red[W_WAVES];\n  __shared__ int s_flag;\n");
+    o.f("  __shared__ u64 s_red[W_WAVES];\n");
     o.f("  int* const errp = (int*)(a.ctl + 2);\n");
     o.f("  const int lane = threadIdx.x & 63;\n  const int wave = threadIdx.x >> 6;\n");
-    o.f("  (void)lane; (void)wave; (void)errp; (void)s_flag;\n");
+    o.f("  (void)lane; (void)wave; (void)errp;\n");
     int lds = 8 * (var.block / 64) + 4;
     if (var.ticketed) {
         o.f("  __shared__ i64 s_tile;\n  __shared__ i64 s_cnt[%d][W_WAVES];\n  __shared__ i64 s_pfx[%d];\n", ncompact, ncompact);
@@ -366,11 +365,9 @@ Generated generate(const Loop& L, const Variant& var) {
     }
     // builder state
     bool need_sync = false;
-    int nmergers = 0;
     for (size_t b = 0; b < NB; ++b) {
         const weld_builder_spec_t& s = L.builders[b];
         if (var.backend[b] == BK_MERGER) {
-            ++nmergers;
             o.f("  %s m%zu = %s;\n", acc_ctype(s.val_type[0]), b, ident_expr(s.func, s.val_type[0]).c_str());
         } else if (var.backend[b] == BK_DICT_REG) {
             const int S = (int)s.capacity;
@@ -515,7 +512,7 @@ Generated generate(const Loop& L, const Variant& var) {
         if (var.backend[b] == BK_MERGER) {
             const char* A = acc_ctype(s.val_type[0]);
             o.f("  {\n    const %s tot = w_block_reduce<%d>(m%zu, (%s*)s_red, %s);\n", A, s.func, b, A, ident_expr(s.func, s.val_type[0]).c_str());
-            o.f("    if (threadIdx.x == 0) { u64 bits; __builtin_memcpy(&bits, &tot, 8); w_st_agent(a.b%zu_part + blockIdx.x, bits); }\n  }\n", b);
+            o.f("    if (threadIdx.x == 0) w_store_partial(a.b%zu_part, tot);\n  }\n", b);
         } else if (var.backend[b] == BK_DICT_REG) {
             const int S = (int)s.capacity;
             o.f("  __syncthreads();\n");
@@ -534,17 +531,6 @@ Generated generate(const Loop& L, const Variant& var) {
             for (int k = 0; k < s.nvals; ++k) o.f("        w_atomic<%d>(a.b%zu_v%d + g, d%zu_lv%d[q], 1);\n", s.func, b, k, b, k);
             o.f("      }\n    }\n  }\n");
         }
-    }
-    if (nmergers > 0) {
-        o.f("  if (w_arrive_last(a.ctl + 1, &s_flag)) {\n");
-        for (size_t b = 0; b < NB; ++b) {
-            const weld_builder_spec_t& s = L.builders[b];
-            if (var.backend[b] != BK_MERGER) continue;
-            const char* A = acc_ctype(s.val_type[0]);
-            o.f("    {\n      const %s tot = w_combine_partials<%d, %s>(a.b%zu_part, (%s*)s_red, %s);\n", A, s.func, A, b, A, ident_expr(s.func, s.val_type[0]).c_str());
-            o.f("      if (threadIdx.x == 0) *a.b%zu_res = (%s)tot;\n    }\n", b, ctype(s.val_type[0]));
-        }
-        o.f("  }\n");
     }
     o.f("}\n");
     G.source = o.s;

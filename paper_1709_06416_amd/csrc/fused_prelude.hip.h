@@ -61,9 +61,16 @@ __device__ __forceinline__ void w_store(T* __restrict__ p, const wvec<T, V>& v) 
 }
 
 // ---------------------------------------------------------------- merge functions
-template <int F, class T> __device__ __forceinline__ T w_combine(T a, T b) {
+template <int F> __device__ __forceinline__ double w_combine(double a, double b) {
     if (F == W_FUNC_ADD) return a + b;
     if (F == W_FUNC_MUL) return a * b;
+    if (F == W_FUNC_MIN) return b < a ? b : a;
+    return b > a ? b : a;
+}
+// integers wrap: sums and products go through the unsigned type
+template <int F> __device__ __forceinline__ i64 w_combine(i64 a, i64 b) {
+    if (F == W_FUNC_ADD) return (i64)((u64)a + (u64)b);
+    if (F == W_FUNC_MUL) return (i64)((u64)a * (u64)b);
     if (F == W_FUNC_MIN) return b < a ? b : a;
     return b > a ? b : a;
 }
@@ -126,33 +133,15 @@ __device__ __forceinline__ void w_st_agent(u64* p, u64 v) {
 }
 
 // ---------------------------------------------------------------- merger finish
-// Every work-group stores one partial per merger; the last one to arrive (ticket
-// on `done`) combines the partials in index order, which makes the result
-// independent of the order in which work-groups ran.  Call with all threads.
-// Returns true in the last work-group (which then holds the total in `total`).
-__device__ __forceinline__ bool w_arrive_last(u32* done, int* s_flag) {
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const u32 prev = __hip_atomic_fetch_add(done, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        *s_flag = (prev == gridDim.x - 1);
-    }
-    __syncthreads();
-    const bool last = (*s_flag != 0);
-    if (last) __threadfence();
-    return last;
-}
-
-template <int F, class T>
-__device__ __forceinline__ T w_combine_partials(const u64* partial, T* scratch, T ident) {
-    T v = ident;
-    for (u32 b = threadIdx.x; b < gridDim.x; b += W_BLOCK) {
-        const u64 bits = w_ld_agent(partial + b);
-        T x;
-        __builtin_memcpy(&x, &bits, 8);
-        v = w_combine<F>(v, x);
-    }
-    return w_block_reduce<F>(v, scratch, ident);
+// Every work-group stores one partial per merger (index = its work-group id).  A
+// small second kernel combines the partials in index order, so the result does not
+// depend on the order in which work-groups ran, and no cross-XCD release/acquire
+// fence is needed inside the loop kernel (such a fence writes back and invalidates
+// the whole L2 of the XCD: measured at about 0.25 us per work-group, serialised).
+template <class T> __device__ __forceinline__ void w_store_partial(u64* partial, T v) {
+    u64 bits;
+    __builtin_memcpy(&bits, &v, 8);
+    partial[blockIdx.x] = bits;
 }
 
 // ---------------------------------------------------------------- vecbuilder scan

@@ -55,8 +55,10 @@ void put_back(weld_result* r) {
     if (r->host_ctl) g_pinned.push_back(r->host_ctl);
     if (r->ev0) g_events.push_back(r->ev0);
     if (r->ev1) g_events.push_back(r->ev1);
+    if (r->ev2) g_events.push_back(r->ev2);
+    if (r->ev3) g_events.push_back(r->ev3);
     r->host_ctl = nullptr;
-    r->ev0 = r->ev1 = nullptr;
+    r->ev0 = r->ev1 = r->ev2 = r->ev3 = nullptr;
 }
 
 Error mk(weld_status_t st, const std::string& s) {
@@ -201,7 +203,7 @@ Error run_fused(const Loop& L, const weld_cols_t* cols, int64_t n, const weld_bu
             case SLOT_COL: v = (uint64_t)(uintptr_t)cols->col[b].data; break;
             case SLOT_CTL: v = (uint64_t)(uintptr_t)(base + off_ctl); break;
             case SLOT_PARTIAL: v = (uint64_t)(uintptr_t)(base + off[b].part); break;
-            case SLOT_RESULT: v = (uint64_t)(uintptr_t)(base + off[b].res); break;
+            case SLOT_RESULT: break;
             case SLOT_OUT: v = (uint64_t)(uintptr_t)(base + off[b].out); break;
             case SLOT_DESC: v = (uint64_t)(uintptr_t)(base + off[b].desc); break;
             case SLOT_LEN: v = (uint64_t)(uintptr_t)(base + off_ctl + ctl_count_off(b)); break;
@@ -234,9 +236,28 @@ Error run_fused(const Loop& L, const weld_cols_t* cols, int64_t n, const weld_bu
             }
         }
     }
+    if ((h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream);
     if (!e.ok()) return e;
+    if ((h = hipEventRecord(r->ev3, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     r->kernel_count++;
+    MergerFinish mf;
+    memset(&mf, 0, sizeof mf);
+    for (size_t b = 0; b < NB; ++b) {
+        const weld_builder_spec_t& s = L.builders[b];
+        if (s.kind != WELD_MERGER) continue;
+        const int k = mf.n++;
+        mf.partial[k] = (const unsigned long long*)(base + off[b].part);
+        mf.result[k] = base + off[b].res;
+        mf.func[k] = s.func;
+        mf.is_f64[k] = s.val_type[0] == WELD_F64;
+        mf.elem_size[k] = type_size(s.val_type[0]);
+        mf.bits[k] = 8 * type_size(s.val_type[0]);
+    }
+    if (mf.n > 0) {
+        if ((h = launch_merger_finish(mf, (int)grid, stream)) != hipSuccess) return hip_err("merger finish", h);
+        r->kernel_count++;
+    }
     for (size_t b = 0; b < NB; ++b) {
         const weld_builder_spec_t& s = L.builders[b];
         if (s.kind != WELD_DICTMERGER) continue;
@@ -308,7 +329,9 @@ weld_status_t weld_fused_for(const weld_cols_t* cols, int64_t n, const weld_body
     r->host_ctl = get_pinned();
     r->ev0 = get_event();
     r->ev1 = get_event();
-    if (!r->host_ctl || !r->ev0 || !r->ev1) {
+    r->ev2 = get_event();
+    r->ev3 = get_event();
+    if (!r->host_ctl || !r->ev0 || !r->ev1 || !r->ev2 || !r->ev3) {
         destroy(r);
         set_last_error("could not allocate pinned memory / events (no usable HIP device?)");
         return WELD_ERR_DEVICE;
@@ -335,6 +358,8 @@ weld_status_t weld_result_status(weld_result_t* r) {
         return r->status;
     }
     (void)hipEventElapsedTime(&r->ms, r->ev0, r->ev1);
+    if (hipEventQuery(r->ev3) == hipSuccess) (void)hipEventElapsedTime(&r->kernel_ms, r->ev2, r->ev3);
+    (void)hipGetLastError();
     const uint32_t err = r->host_ctl[2];
     if (err & 2) {
         r->status = WELD_ERR_DEVICE;
@@ -391,6 +416,13 @@ weld_status_t weld_result_elapsed_ms(weld_result_t* r, float* ms) {
     if (!r || !ms) return WELD_ERR_INVALID_ARG;
     weld_status_t st = weld_result_status(r);
     *ms = r->ms;
+    return st;
+}
+
+weld_status_t weld_result_kernel_ms(weld_result_t* r, float* ms) {
+    if (!r || !ms) return WELD_ERR_INVALID_ARG;
+    weld_status_t st = weld_result_status(r);
+    *ms = r->kernel_ms;
     return st;
 }
 

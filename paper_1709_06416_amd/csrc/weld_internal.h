@@ -23,13 +23,15 @@ struct weld_result {
     std::vector<BuilderResult> res;
     std::vector<void*> blocks;   // pool blocks owned by this result
     void* stream = nullptr;
-    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;   // around everything the call enqueues
+    hipEvent_t ev2 = nullptr, ev3 = nullptr;   // around the main loop kernel alone
     uint32_t* host_ctl = nullptr;  // pinned copy of the control words
     bool synced = false;
     weld_status_t status = WELD_OK;
     std::string error;
     int kernel_count = 0;
     float ms = -1.f;
+    float kernel_ms = -1.f;
 };
 
 namespace weld {
