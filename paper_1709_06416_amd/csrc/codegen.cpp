@@ -232,24 +232,51 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
             if (strat == 1 && (s.capacity > 8 || key_bits(s) >= 64)) strat = 0;
             if (strat == 0) strat = (s.capacity <= 8 && key_bits(s) < 64) ? 1 : 2;
             var.backend[b] = strat == 1 ? BK_DICT_REG : (strat == 2 ? BK_DICT_LDS : BK_DICT_GLOBAL);
+        }
+    }
+    // every LDS dictionary of the loop gets the same slot count; the LDS budget (64 KiB,
+    // 128 KiB when some dictionary has more keys than 64 KiB hold) is shared among them
+    bool big_dict = false;
+    {
+        int ndl = 0, per_slot = 0;
+        int64_t max_cap = 0;
+        for (size_t b = 0; b < L.builders.size(); ++b)
             if (var.backend[b] == BK_DICT_LDS) {
-                int want = tune.lds_dict_slots;
-                if (want <= 0) {
-                    const int per_slot = 8 * (1 + s.nvals);
-                    want = 64;
-                    while (want * 2 * per_slot <= 48 * 1024 && want < 2 * s.capacity) want *= 2;
-                }
-                int p2 = 64;
-                while (p2 < want && p2 < (1 << 14)) p2 *= 2;
-                var.lds_slots = p2;
+                ++ndl;
+                per_slot += 8 * (1 + L.builders[b].nvals);
+                if (L.builders[b].capacity > max_cap) max_cap = L.builders[b].capacity;
             }
+        if (ndl > 0) {
+            int want = tune.lds_dict_slots;
+            if (want <= 0) {
+                want = 64;
+                while (want * 2 * per_slot <= 64 * 1024 && want < 2 * max_cap) want *= 2;
+                if (max_cap > want) {
+                    big_dict = true;
+                    while (want * 2 * per_slot <= 128 * 1024) want *= 2;
+                }
+            }
+            int p2 = 64;
+            while (p2 < want && p2 < (1 << 14)) p2 *= 2;
+            var.lds_slots = p2;
         }
     }
     (void)any;
     var.v = widest >= 8 ? 2 : 4;
-    var.u = tune.units_per_thread > 0 ? tune.units_per_thread : (var.v == 2 ? 4 : 2);
-    if (var.u > 8) var.u = 8;
-    var.block = tune.block_threads > 0 ? tune.block_threads : 256;
+    // Look-back kernels pay one same-address device atomic (about 12 ns, serialised) and
+    // three barriers per tile: they take large tiles (8192 rows).  Other kernels keep
+    // 8 KiB (4 KiB for V=4) of loads in flight per wavefront and column.
+    if (big_dict) {
+        var.u = tune.units_per_thread > 0 ? tune.units_per_thread : 16 / var.v;
+        var.block = tune.block_threads > 0 ? tune.block_threads : 1024;
+    } else if (var.ticketed) {
+        var.u = tune.units_per_thread > 0 ? tune.units_per_thread : 16 / var.v;
+        var.block = tune.block_threads > 0 ? tune.block_threads : 512;
+    } else {
+        var.u = tune.units_per_thread > 0 ? tune.units_per_thread : (var.v == 2 ? 4 : 2);
+        var.block = tune.block_threads > 0 ? tune.block_threads : 256;
+    }
+    if (var.u > 16) var.u = 16;
     if (var.block < 64) var.block = 64;
     if (var.block > 1024) var.block = 1024;
     var.block = (var.block / 64) * 64;
@@ -335,7 +362,7 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("  if ((o).p%zu) { \\\n", b);
             o.f("    const u64 kb = %s; \\\n", pack_key(s, b, "(o)").c_str());
             if (var.backend[b] == BK_DICT_LDS) {
-                o.f("    const int sl = w_lds_slot(d%zu_lk, %d, kb, 8); \\\n", b, var.lds_slots);
+                o.f("    const int sl = w_lds_slot(d%zu_lk, %d, kb, 3); \\\n", b, var.lds_slots);
                 o.f("    if (sl >= 0) { \\\n");
                 for (int k = 0; k < s.nvals; ++k)
                     o.f("      w_atomic<%d>(d%zu_lv%d + sl, (%s)(o).v%zu_%d, 0); \\\n", F, b, k, acc_ctype(s.val_type[k]), b, k);

@@ -243,11 +243,14 @@ template <int F> __device__ __forceinline__ void w_atomic(double* p, double v, c
 template <int F> __device__ __forceinline__ void w_atomic(i64* p, i64 v, const int agent) { w_atomic_i64<F>(p, v, agent); }
 
 // ---------------------------------------------------------------- hash tables
+// 32-bit multiplicative (Fibonacci) hash of the folded key: a handful of 32-bit
+// instructions; callers take the HIGH bits (w_hash(k) >> (32 - log2 slots)).
 __device__ __forceinline__ u32 w_hash(u64 k) {
-    k ^= k >> 33;
-    k *= 0xff51afd7ed558ccdull;
-    k ^= k >> 33;
-    return (u32)k ^ (u32)(k >> 32);
+    const u32 x = (u32)k ^ ((u32)(k >> 32) * 0x85ebca6bu);
+    return x * 0x9e3779b1u;
+}
+__device__ __forceinline__ u32 w_hash_slot(u64 k, u32 slots) {   // slots is a power of two >= 2
+    return w_hash(k) >> (__builtin_clz(slots) + 1);
 }
 
 // Global open-addressing table (linear probing, power-of-two slot count, keys packed
@@ -260,9 +263,11 @@ __device__ __forceinline__ i64 w_table_slot(u64* keys, u32* hdr, i64 slots, u64 
         return slots;
     }
     const i64 mask = slots - 1;
-    i64 s = (i64)w_hash(kbits) & mask;
+    i64 s = (i64)w_hash_slot(kbits, (u32)slots);
     for (i64 probe = 0; probe < slots; ++probe) {
-        u64 cur = __hip_atomic_load(keys + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // a key cell changes once, from the marker to its key: a cached copy that already
+        // shows the key is final, and a stale marker is resolved by the compare-and-swap
+        u64 cur = keys[s];
         if (cur == kbits) return s;
         if (cur == W_EMPTY_KEY) {
             u64 expect = W_EMPTY_KEY;
@@ -282,7 +287,7 @@ __device__ __forceinline__ i64 w_table_slot(u64* keys, u32* hdr, i64 slots, u64 
 __device__ __forceinline__ int w_lds_slot(u64* keys, int slots, u64 kbits, int max_probe) {
     if (kbits == W_EMPTY_KEY) return -1;
     const int mask = slots - 1;
-    int s = (int)w_hash(kbits) & mask;
+    int s = (int)w_hash_slot(kbits, (u32)slots);
     for (int probe = 0; probe < max_probe; ++probe) {
         u64 cur = __hip_atomic_load(keys + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         if (cur == kbits) return s;

@@ -126,7 +126,11 @@ Error run_fused(const Loop& L, const weld_cols_t* cols, int64_t n, const weld_bu
     const size_t NB = L.builders.size();
     const int64_t tile = (int64_t)var.block * var.v * var.u;
     const int64_t ntiles = (n + tile - 1) / tile;
-    int64_t grid = conf.tune.grid_blocks > 0 ? conf.tune.grid_blocks : (int64_t)device_info().cus * 8;
+    // persistent grid: as many work-groups as are resident at once (registers and LDS
+    // of this kernel decide), at most 8 per CU
+    int per_cu = jit_blocks_per_cu(kern, var.block);
+    if (per_cu <= 0 || per_cu > 8) per_cu = 8;
+    int64_t grid = conf.tune.grid_blocks > 0 ? conf.tune.grid_blocks : (int64_t)device_info().cus * per_cu;
     if (grid > ntiles) grid = ntiles;
     if (grid < 1) grid = 1;
 

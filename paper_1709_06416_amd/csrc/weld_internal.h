@@ -124,6 +124,7 @@ int key_bits(const weld_builder_spec_t& b);
 // jit.cpp
 struct Kernel;  // compiled + loaded
 Error jit_get(const std::string& source, bool load_on_device, Kernel** out);
+int jit_blocks_per_cu(Kernel* k, int block);  // resident work-groups per CU, 0 if unknown
 Error jit_launch(Kernel* k, unsigned grid, unsigned block, void* args, size_t args_bytes, void* stream);
 Error set_cache_dir(const char* path);
 
