@@ -47,6 +47,8 @@ const char* ctype(int t) {
     }
     return "void";
 }
+// type a value has in memory: predicates are stored as bytes holding 0 or 1
+const char* stype(int t) { return t == WELD_BOOL ? "unsigned char" : ctype(t); }
 // type a builder accumulates a value field in (integers widen to 64 bits: wrapping
 // sums/products and min/max commute with the final truncation)
 const char* acc_ctype(int t) { return t == WELD_F64 ? "double" : "i64"; }
@@ -121,7 +123,7 @@ void emit_row_function(Out& o, const Loop& L) {
     // ---- the body, one statement per IR operator
     o.f("__device__ __forceinline__ void weld_row(const i64 i");
     for (int c = 0; c < L.ncols; ++c)
-        if (L.col_used[c]) o.f(", const %s x%d", ctype(L.col_type[c]), c);
+        if (L.col_used[c]) o.f(", const %s x%d", stype(L.col_type[c]), c);
     o.f(", RowOut& o) {\n");
     for (size_t i = 0; i < L.ops.size(); ++i) {
         const weld_op_t& q = L.ops[i];
@@ -301,7 +303,7 @@ Generated generate(const Loop& L, const Variant& var) {
     slot(SLOT_N, -1, 0, "n", "i64");
     slot(SLOT_SPIN, -1, 0, "spin_limit", "i64");
     for (int c = 0; c < L.ncols; ++c)
-        if (L.col_used[c]) slot(SLOT_COL, c, 0, "c" + std::to_string(c), std::string("const ") + ctype(L.col_type[c]) + "* __restrict__");
+        if (L.col_used[c]) slot(SLOT_COL, c, 0, "c" + std::to_string(c), std::string("const ") + stype(L.col_type[c]) + "* __restrict__");
     slot(SLOT_CTL, -1, 0, "ctl", "u32*");
     int ncompact = 0;
     for (size_t b = 0; b < NB; ++b) {
@@ -312,10 +314,10 @@ Generated generate(const Loop& L, const Variant& var) {
                 slot(SLOT_PARTIAL, (int)b, 0, B + "_part", "u64*");
                 break;
             case BK_VEC_DIRECT:
-                slot(SLOT_OUT, (int)b, 0, B + "_out", std::string(ctype(s.val_type[0])) + "* __restrict__");
+                slot(SLOT_OUT, (int)b, 0, B + "_out", std::string(stype(s.val_type[0])) + "* __restrict__");
                 break;
             case BK_VEC_COMPACT:
-                slot(SLOT_OUT, (int)b, 0, B + "_out", std::string(ctype(s.val_type[0])) + "* __restrict__");
+                slot(SLOT_OUT, (int)b, 0, B + "_out", std::string(stype(s.val_type[0])) + "* __restrict__");
                 slot(SLOT_DESC, (int)b, 0, B + "_desc", "u64*");
                 slot(SLOT_LEN, (int)b, 0, B + "_len", "i64*");
                 ++ncompact;
@@ -444,14 +446,14 @@ Generated generate(const Loop& L, const Variant& var) {
         o.f("  for (i64 t = blockIdx.x; t < nfull; t += gridDim.x) {\n");
         o.f("    const i64 r0 = t * W_TILE + (i64)wave * W_WAVE_ROWS + lane * W_V;\n");
         for (int c = 0; c < L.ncols; ++c)
-            if (L.col_used[c]) o.f("    wvec<%s, W_V> x%d[W_U];\n", ctype(L.col_type[c]), c);
+            if (L.col_used[c]) o.f("    wvec<%s, W_V> x%d[W_U];\n", stype(L.col_type[c]), c);
         o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
         for (int c = 0; c < L.ncols; ++c)
-            if (L.col_used[c]) o.f("      x%d[u] = w_load<%s, W_V>(a.c%d + r0 + u * W_UNIT);\n", c, ctype(L.col_type[c]), c);
+            if (L.col_used[c]) o.f("      x%d[u] = w_load<%s, W_V>(a.c%d + r0 + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
         o.f("    }\n");
         o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
         for (size_t b = 0; b < NB; ++b)
-            if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) o.f("      wvec<%s, W_V> y%zu;\n", ctype(L.builders[b].val_type[0]), b);
+            if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) o.f("      wvec<%s, W_V> y%zu;\n", stype(L.builders[b].val_type[0]), b);
         o.f("      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
         o.f("        RowOut o;\n        %s\n", row_call("r0 + u * W_UNIT + k", "x%d[u].e[k]", "o").c_str());
         o.f("        WELD_MERGE(o);\n");
@@ -460,7 +462,7 @@ Generated generate(const Loop& L, const Variant& var) {
         o.f("      }\n");
         for (size_t b = 0; b < NB; ++b)
             if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0)
-                o.f("      w_store<%s, W_V>(a.b%zu_out + r0 + u * W_UNIT, y%zu);\n", ctype(L.builders[b].val_type[0]), b, b);
+                o.f("      w_store<%s, W_V>(a.b%zu_out + r0 + u * W_UNIT, y%zu);\n", stype(L.builders[b].val_type[0]), b, b);
         o.f("    }\n  }\n");
         // tail rows, one per thread
         o.f("  for (i64 i = nfull * W_TILE + (i64)blockIdx.x * W_BLOCK + threadIdx.x; i < a.n; i += (i64)gridDim.x * W_BLOCK) {\n");
@@ -479,10 +481,10 @@ Generated generate(const Loop& L, const Variant& var) {
         o.f("    RowOut o[W_U][W_V];\n");
         o.f("    if (full) {\n");
         for (int c = 0; c < L.ncols; ++c)
-            if (L.col_used[c]) o.f("      wvec<%s, W_V> x%d[W_U];\n", ctype(L.col_type[c]), c);
+            if (L.col_used[c]) o.f("      wvec<%s, W_V> x%d[W_U];\n", stype(L.col_type[c]), c);
         o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
         for (int c = 0; c < L.ncols; ++c)
-            if (L.col_used[c]) o.f("        x%d[u] = w_load<%s, W_V>(a.c%d + r0 + u * W_UNIT);\n", c, ctype(L.col_type[c]), c);
+            if (L.col_used[c]) o.f("        x%d[u] = w_load<%s, W_V>(a.c%d + r0 + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
         o.f("      }\n");
         o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
         o.f("          %s\n        }\n", row_call("r0 + u * W_UNIT + k", "x%d[u].e[k]", "o[u][k]").c_str());

@@ -111,12 +111,15 @@ struct Layout {
     }
 };
 
-Error run_fused(const Loop& L, const weld_cols_t* cols, int64_t n, const weld_builder_t* builder, weld_result* r) {
-    const weld_conf_t& conf = builder->conf;
+}  // namespace
+
+namespace weld {
+
+Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t& conf, weld_result* r) {
     hipStream_t stream = (hipStream_t)conf.stream;
     bool aligned = true;
     for (int c = 0; c < L.ncols; ++c)
-        if (L.col_used[c] && ((uintptr_t)cols->col[c].data & 15)) aligned = false;
+        if (L.col_used[c] && ((uintptr_t)cols[c].data & 15)) aligned = false;
     Variant var = choose_variant(L, conf.tune, aligned);
     Generated G = generate(L, var);
     Kernel* kern = nullptr;
@@ -204,7 +207,7 @@ Error run_fused(const Loop& L, const weld_cols_t* cols, int64_t n, const weld_bu
         switch (s.kind) {
             case SLOT_N: v = (uint64_t)n; break;
             case SLOT_SPIN: v = conf.tune.spin_limit > 0 ? (uint64_t)conf.tune.spin_limit : (uint64_t)1 << 22; break;
-            case SLOT_COL: v = (uint64_t)(uintptr_t)cols->col[b].data; break;
+            case SLOT_COL: v = (uint64_t)(uintptr_t)cols[b].data; break;
             case SLOT_CTL: v = (uint64_t)(uintptr_t)(base + off_ctl); break;
             case SLOT_PARTIAL: v = (uint64_t)(uintptr_t)(base + off[b].part); break;
             case SLOT_RESULT: break;
@@ -295,7 +298,7 @@ Error run_fused(const Loop& L, const weld_cols_t* cols, int64_t n, const weld_bu
     return Error();
 }
 
-void destroy(weld_result* r) {
+void destroy_result(weld_result* r) {
     if (!r) return;
     if (!r->synced && !r->blocks.empty()) (void)hipStreamSynchronize((hipStream_t)r->stream);
     for (void* p : r->blocks) pool_free(p);
@@ -303,7 +306,23 @@ void destroy(weld_result* r) {
     delete r;
 }
 
-}  // namespace
+weld_result* new_result(void* stream) {
+    weld_result* r = new weld_result();
+    r->stream = stream;
+    r->host_ctl = get_pinned();
+    r->ev0 = get_event();
+    r->ev1 = get_event();
+    r->ev2 = get_event();
+    r->ev3 = get_event();
+    if (!r->host_ctl || !r->ev0 || !r->ev1 || !r->ev2 || !r->ev3) {
+        destroy_result(r);
+        return nullptr;
+    }
+    memset(r->host_ctl, 0, kCtlBytes);
+    return r;
+}
+
+}  // namespace weld
 
 extern "C" {
 
@@ -328,23 +347,18 @@ weld_status_t weld_fused_for(const weld_cols_t* cols, int64_t n, const weld_body
             return WELD_ERR_INVALID_ARG;
         }
     }
-    weld_result* r = new weld_result();
-    r->stream = builder->conf.stream;
-    r->host_ctl = get_pinned();
-    r->ev0 = get_event();
-    r->ev1 = get_event();
-    r->ev2 = get_event();
-    r->ev3 = get_event();
-    if (!r->host_ctl || !r->ev0 || !r->ev1 || !r->ev2 || !r->ev3) {
-        destroy(r);
+    weld_result* r = new_result(builder->conf.stream);
+    if (!r) {
         set_last_error("could not allocate pinned memory / events (no usable HIP device?)");
         return WELD_ERR_DEVICE;
     }
-    memset(r->host_ctl, 0, kCtlBytes);
-    e = builder->conf.mode == WELD_MODE_FUSED ? run_fused(L, cols, n, builder, r) : run_unfused(L, cols, n, builder, r);
+    ColRef refs[WELD_MAX_COLS];
+    for (int c = 0; c < cols->ncols; ++c) { refs[c].data = cols->col[c].data; refs[c].type = cols->col[c].type; }
+    e = builder->conf.mode == WELD_MODE_FUSED ? run_fused(L, refs, n, builder->conf, r)
+                                              : run_unfused(L, refs, n, builder->conf, r);
     if (!e.ok()) {
         set_last_error(e.text);
-        destroy(r);
+        destroy_result(r);
         return e.status;
     }
     *out = r;
@@ -432,7 +446,7 @@ weld_status_t weld_result_kernel_ms(weld_result_t* r, float* ms) {
 
 int32_t weld_result_kernel_count(const weld_result_t* r) { return r ? r->kernel_count : 0; }
 
-void weld_result_free(weld_result_t* r) { destroy(r); }
+void weld_result_free(weld_result_t* r) { destroy_result(r); }
 
 weld_status_t weld_validate(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
                             const weld_builder_t* builder, char* err, size_t errlen) {

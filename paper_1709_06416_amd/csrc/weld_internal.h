@@ -134,8 +134,18 @@ void pool_free(void* p);
 void pool_trim();
 int64_t pool_bytes();
 
-// unfused.cpp
-Error run_unfused(const Loop& loop, const weld_cols_t* cols, int64_t n, const weld_builder_t* builder,
-                  weld_result* r);
+// A device column handed to a loop.
+struct ColRef {
+    const void* data = nullptr;
+    int type = 0;
+};
+
+// runtime.cpp: enqueue one fused loop (validated `loop`) on conf.stream into `r`
+Error run_fused(const Loop& loop, const ColRef* cols, int64_t n, const weld_conf_t& conf, weld_result* r);
+weld_result* new_result(void* stream);   // with pinned control words and events; nullptr on failure
+void destroy_result(weld_result* r);
+
+// unfused.cpp: the same loop as one kernel per operator, every intermediate in HBM
+Error run_unfused(const Loop& loop, const ColRef* cols, int64_t n, const weld_conf_t& conf, weld_result* r);
 
 }  // namespace weld

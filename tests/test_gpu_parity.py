@@ -337,3 +337,73 @@ def test_single_library_instance_loaded():
         if "libamdhip64" in line:
             libs.add(line.split()[-1])
     assert len(libs) == 1, libs
+
+
+# ----------------------------------------------------------------------
+# operator-at-a-time mode (every intermediate materialised in HBM)
+# ----------------------------------------------------------------------
+@pytest.mark.parametrize("name,n", [("C1", 200_003), ("C3", 300_001), ("C4", 200_001), ("C5", 300_007)])
+def test_unfused_config(wb, name, n):
+    cols = configs.make_columns(name, n, device="cuda")
+    _check(wb, configs.PROGRAMS[name](), cols, label=name + " unfused", mode="unfused")
+
+
+def test_unfused_black_scholes(wb):
+    cols = configs.make_columns("C2", 100_003, device="cuda")
+    _check(wb, configs.program_c2(), cols, map_floor=1.0, label="C2 unfused", mode="unfused")
+
+
+@pytest.mark.parametrize("name,vecs,exp", _golden_cases())
+def test_unfused_paper_printed_results(wb, name, vecs, exp):
+    prog = configs.EXAMPLES[name]()
+    cols = [_dev(np.array(v, dtype=np.int32)) for v in vecs]
+    res = _run(wb, prog, cols, mode="unfused").check()
+    for b, (spec, e) in enumerate(zip(prog.builders, exp)):
+        if spec["kind"] == "vecbuilder":
+            assert res.vec_host(b).tolist() == e
+        else:
+            assert [int(res.merger(b))] == e
+    res.free()
+
+
+def test_fused_equals_unfused_on_the_gpu(wb):
+    # Sec. 4.5: the combined program and the loop after fusion return the same value.
+    # Integer results, compaction order and f64 maps agree to the bit between the modes.
+    cols = configs.make_columns("C5", 150_001, device="cuda")
+    prog = configs.program_c5()
+    a = _run(wb, prog, cols).check()
+    b = _run(wb, prog, cols, mode="unfused").check()
+    assert np.array_equal(a.vec_host(0), b.vec_host(0))
+    ka, va = a.dict(1)
+    kb, vb = b.dict(1)
+    assert np.array_equal(ka[0], kb[0]) and np.array_equal(va[0], vb[0])
+    assert b.kernel_count() > 3 * a.kernel_count()
+    a.free()
+    b.free()
+    cols = configs.make_columns("C2", 50_001, device="cuda")
+    prog = configs.program_c2()
+    a = _run(wb, prog, cols).check()
+    b = _run(wb, prog, cols, mode="unfused").check()
+    assert np.array_equal(a.vec_host(0), b.vec_host(0)) and np.array_equal(a.vec_host(1), b.vec_host(1))
+    a.free()
+    b.free()
+
+
+@pytest.mark.parametrize("n", [0, 1, 63, 8191, 8193])
+def test_unfused_ragged_sizes(wb, n):
+    for name in ("C1", "C5"):
+        cols = configs.make_columns(name, n, device="cuda")
+        _check(wb, configs.PROGRAMS[name](), cols, label="%s unfused n=%d" % (name, n), mode="unfused")
+
+
+def test_unfused_index_constants_and_unmerged_builders(wb):
+    p = Program(["i64"])
+    pred = p.bin("gt", p.col(0), p.const("i64", 49))
+    p.merge(p.vecbuilder("i64"), p.index(), pred=pred)
+    p.merge(p.vecbuilder("i64"), p.col(0))
+    p.merge(p.merger("i64", "add"), p.const("i64", 1), pred=pred)
+    p.merge(p.vecbuilder("i64"), p.bin("add", p.index(), p.col(0)))
+    p.merger("f64", "max")
+    rnd = np.random.RandomState(5)
+    x = rnd.randint(0, 100, size=20_011).astype(np.int64)
+    _check(wb, p, [_dev(x)], label="unfused misc", mode="unfused")
