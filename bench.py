@@ -1,0 +1,185 @@
+"""Throughput of the fused `for` loop on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--configs C1,C2,...]
+
+A step is one pass of the whole hot path: the fused loops of the five benchmark
+configurations (merger, size-known vecbuilder, compacting vecbuilder, low- and
+high-cardinality dictmerger, multi-builder loops) run back to back over
+synthetic columns that are already resident in HBM.  Prints ONE JSON line:
+value = total input bytes of a step / time of a step (GB/s), plus per-config
+numbers, the operator-at-a-time GPU mode for comparison, the roofline of the
+dominant kernel and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+CPU_SAMPLE_ROWS = {"C1": 1_000_000, "C2": 20_000_000, "C3": 100_000_000, "C4": 40_000_000, "C5": 40_000_000}
+
+
+def median(xs):
+    s = sorted(xs)
+    return s[len(s) // 2]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--configs", default="C1,C2,C3,C4,C5")
+    ap.add_argument("--scale", type=float, default=1.0, help="fraction of the full row counts (for quick checks)")
+    ap.add_argument("--no-unfused", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the loop shards by "
+                 "contiguous row ranges, see DESIGN.md, but no multi-GPU path is built)" % args.gpus)
+
+    import torch
+    from paper_1709_06416_amd import binding as wb
+    from workloads import configs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    names = [c for c in args.configs.split(",") if c]
+    rows = {c: max(1, int(configs.FULL_ROWS[c] * args.scale)) for c in names}
+    progs = {c: configs.PROGRAMS[c]() for c in names}
+    cols = {c: configs.make_columns(c, rows[c], device="cuda") for c in names}
+    torch.cuda.synchronize()
+    in_bytes = {c: configs.IN_BYTES[c] * rows[c] for c in names}
+
+    def step(collect=None):
+        handles = [(c, wb.fused_for(progs[c], cols[c])) for c in names]     # enqueue everything
+        for c, r in handles:
+            r.check()
+            if collect is not None:
+                collect[c]["call_ms"].append(r.elapsed_ms())
+                collect[c]["kernel_ms"].append(r.kernel_ms())
+                collect[c]["kernel"] = r.kernel_name()
+                collect[c]["launches"] = r.kernel_count()
+            r.free()
+
+    for _ in range(args.warmup):
+        step()
+    stats = {c: {"call_ms": [], "kernel_ms": []} for c in names}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(stats)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    total_in = sum(in_bytes.values())
+    value = total_in / ms_per_step / 1e6
+
+    per = {}
+    for c in names:
+        k = median(stats[c]["kernel_ms"])
+        out_b = configs.OUT_BYTES[c] * rows[c]
+        per[c] = {"rows": rows[c], "kernel": stats[c]["kernel"], "launches": stats[c]["launches"],
+                  "call_ms": round(median(stats[c]["call_ms"]), 4), "kernel_ms": round(k, 4),
+                  "kernel_ms_min": round(min(stats[c]["kernel_ms"]), 4),
+                  "rows_per_s": rows[c] / k * 1e3, "input_GBps": round(in_bytes[c] / k / 1e6, 1),
+                  "input_frac_of_hbm_peak": round(in_bytes[c] / k / 1e6 / HBM_PEAK_GBPS, 4),
+                  "in_plus_out_GBps": round((in_bytes[c] + out_b) / k / 1e6, 1)}
+
+    # ---- operator-at-a-time GPU mode, same columns (comparison arm)
+    if not args.no_unfused:
+        for c in names:
+            ts = []
+            launches = 0
+            for i in range(4):
+                r = wb.fused_for(progs[c], cols[c], mode="unfused").check()
+                if i:
+                    ts.append(r.elapsed_ms())
+                launches = r.kernel_count()
+                r.free()
+            per[c]["unfused_ms"] = round(median(ts), 4)
+            per[c]["unfused_launches"] = launches
+            per[c]["fused_speedup_over_unfused"] = round(median(ts) / per[c]["call_ms"], 2)
+        wb.lib.weld_pool_trim()
+
+    # ---- attainable read rate on this machine (streaming 16-byte loads)
+    probe = torch.empty(1 << 30, dtype=torch.int32, device="cuda")
+    probe.fill_(1)
+    pts = []
+    for _ in range(6):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        wb.probe_read(probe)
+        e1.record()
+        torch.cuda.synchronize()
+        pts.append(e0.elapsed_time(e1))
+    read_probe = probe.numel() * 4 / median(pts) / 1e6
+    # plain copy of known size (1 GiB read + 1 GiB written): the kernel the HBM counters are scaled by
+    dst = torch.empty_like(probe)
+    cts = []
+    for _ in range(4):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        wb.probe_copy(dst, probe)
+        e1.record()
+        torch.cuda.synchronize()
+        cts.append(e0.elapsed_time(e1))
+    copy_probe = 2 * probe.numel() * 4 / median(cts) / 1e6
+    del probe, dst
+
+    # ---- roofline of the dominant kernel: algorithmic bytes of its loop / its own duration
+    dom = max(names, key=lambda c: per[c]["kernel_ms"])
+    alg_bytes = (configs.IN_BYTES[dom] + configs.OUT_BYTES[dom]) * rows[dom]
+    achieved = alg_bytes / per[dom]["kernel_ms"] / 1e6
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "hbm_traffic.txt")     # measured with rocprofv3 --pmc
+    if os.path.exists(tfile) and args.scale == 1.0:
+        for ln in open(tfile):
+            f = ln.split()
+            if len(f) == 2 and f[0] == dom:
+                traffic = int(f[1])
+    roofline = {"bound": "hbm", "kernel": per[dom]["kernel"], "workload": dom, "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": traffic, "read_probe_GBps": round(read_probe, 1),
+                "copy_probe_GBps": round(copy_probe, 1)}
+
+    # ---- the CPU oracle as it stands, on a bounded sample of the same workloads
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import interp
+        try:
+            import threadpoolctl
+            limit = threadpoolctl.threadpool_limits(1)
+        except Exception:
+            limit = None
+        tot_b, tot_s, desc = 0, 0.0, []
+        for c in names:
+            m = min(rows[c], CPU_SAMPLE_ROWS[c])
+            host = [t[:m].cpu().numpy() for t in cols[c]]
+            t1 = time.perf_counter()
+            interp.run(progs[c], host)
+            tot_s += time.perf_counter() - t1
+            tot_b += configs.IN_BYTES[c] * m
+            desc.append("%s:%d" % (c, m))
+        del limit
+        cpu = {"value": round(tot_b / tot_s / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "seconds": round(tot_s, 2),
+               "sample": "first rows of each config (" + ", ".join(desc) + "), numpy operator-at-a-time oracle, 1 thread"}
+
+    line = {
+        "metric": "fused-loop input GB/s (all five configs back to back)", "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "C1..C5 fused loops, rows " + ", ".join("%s=%d" % (c, rows[c]) for c in names),
+                   "input_bytes_per_step": total_in, "hbm_peak_GBps": HBM_PEAK_GBPS},
+        "rows_per_s": sum(rows.values()) / ms_per_step * 1e3,
+        "per_config": per, "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

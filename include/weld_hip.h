@@ -142,7 +142,8 @@ typedef struct {
     int32_t block_threads;   /* work-group size: 64..1024, multiple of 64            */
     int32_t units_per_thread;/* 128-bit load groups in flight per lane and column    */
     int32_t grid_blocks;     /* persistent grid size                                 */
-    int32_t dict_strategy;   /* 0 auto, 1 register slots, 2 LDS table, 3 global only */
+    int32_t dict_strategy;   /* 0 auto, 1 register slots, 2 LDS hash table, 3 global only,
+                                4 per-lane LDS slots                                */
     int32_t lds_dict_slots;  /* slots of the per-block LDS hash table (power of two) */
     int32_t spin_limit;      /* polls a tile waits for its predecessors before the call
                                 fails with WELD_ERR_DEVICE (the wait is always bounded)  */
@@ -217,6 +218,9 @@ weld_status_t weld_result_elapsed_ms(weld_result_t* r, float* ms);
 
 /* Same, for the main loop kernel alone (fused mode; -1 if the call ran none). */
 weld_status_t weld_result_kernel_ms(weld_result_t* r, float* ms);
+
+/* Name of the main loop kernel as profilers show it ("" in unfused mode); owned by the handle. */
+const char* weld_result_kernel_name(const weld_result_t* r);
 
 /* Number of kernels the call launched (1-2 in fused mode, one per operator unfused). */
 int32_t weld_result_kernel_count(const weld_result_t* r);

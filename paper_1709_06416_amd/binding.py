@@ -107,6 +107,8 @@ lib.weld_result_elapsed_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
 lib.weld_result_elapsed_ms.restype = C.c_int
 lib.weld_result_kernel_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
 lib.weld_result_kernel_ms.restype = C.c_int
+lib.weld_result_kernel_name.argtypes = [C.c_void_p]
+lib.weld_result_kernel_name.restype = C.c_char_p
 lib.weld_result_kernel_count.argtypes = [C.c_void_p]
 lib.weld_result_kernel_count.restype = C.c_int32
 lib.weld_result_free.argtypes = [C.c_void_p]
@@ -243,6 +245,9 @@ class Result:
         ms = C.c_float()
         lib.weld_result_kernel_ms(self._h, C.byref(ms))
         return ms.value
+
+    def kernel_name(self):
+        return lib.weld_result_kernel_name(self._h).decode()
 
     def kernel_count(self):
         return lib.weld_result_kernel_count(self._h)

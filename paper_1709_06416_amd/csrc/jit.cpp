@@ -113,7 +113,7 @@ Error set_cache_dir(const char* path) {
     return Error();
 }
 
-Error jit_get(const std::string& source, bool load_on_device, Kernel** out) {
+Error jit_get(const std::string& source, const std::string& kernel_name, bool load_on_device, Kernel** out) {
     std::lock_guard<std::mutex> lk(g_mu);
     Kernel* k = nullptr;
     auto it = g_kernels.find(source);
@@ -149,7 +149,7 @@ Error jit_get(const std::string& source, bool load_on_device, Kernel** out) {
     if (load_on_device && !k->loaded) {
         hipError_t h = hipModuleLoadData(&k->mod, k->code.data());
         if (h != hipSuccess) return err(WELD_ERR_DEVICE, std::string("hipModuleLoadData: ") + hipGetErrorString(h));
-        h = hipModuleGetFunction(&k->fn, k->mod, "weld_kernel");
+        h = hipModuleGetFunction(&k->fn, k->mod, kernel_name.c_str());
         if (h != hipSuccess) return err(WELD_ERR_DEVICE, std::string("hipModuleGetFunction: ") + hipGetErrorString(h));
         k->loaded = true;
     }

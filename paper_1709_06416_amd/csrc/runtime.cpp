@@ -123,8 +123,9 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
     Variant var = choose_variant(L, conf.tune, aligned);
     Generated G = generate(L, var);
     Kernel* kern = nullptr;
-    Error e = jit_get(G.source, true, &kern);
+    Error e = jit_get(G.source, G.kernel_name, true, &kern);
     if (!e.ok()) return e;
+    r->kernel_name = G.kernel_name;
 
     const size_t NB = L.builders.size();
     const int64_t tile = (int64_t)var.block * var.v * var.u;
@@ -444,6 +445,8 @@ weld_status_t weld_result_kernel_ms(weld_result_t* r, float* ms) {
     return st;
 }
 
+const char* weld_result_kernel_name(const weld_result_t* r) { return r ? r->kernel_name.c_str() : ""; }
+
 int32_t weld_result_kernel_count(const weld_result_t* r) { return r ? r->kernel_count : 0; }
 
 void weld_result_free(weld_result_t* r) { destroy_result(r); }
@@ -478,7 +481,7 @@ weld_status_t weld_precompile(const int32_t* col_types, int32_t ncols, const wel
         Variant var = choose_variant(L, builder->conf.tune, aligned != 0);
         Generated G = generate(L, var);
         Kernel* k = nullptr;
-        e = jit_get(G.source, false, &k);
+        e = jit_get(G.source, G.kernel_name, false, &k);
         if (!e.ok()) { set_last_error(e.text); return e.status; }
     }
     return WELD_OK;

@@ -32,6 +32,7 @@ struct weld_result {
     int kernel_count = 0;
     float ms = -1.f;
     float kernel_ms = -1.f;
+    std::string kernel_name;
 };
 
 namespace weld {
@@ -80,7 +81,8 @@ enum Backend {
     BK_VEC_COMPACT = 2, // ballot/popcount ranks + decoupled look-back over tile descriptors
     BK_DICT_REG = 3,    // <= 8 groups: key list in LDS, per-lane register accumulators
     BK_DICT_LDS = 4,    // work-group hash table in LDS in front of the global table
-    BK_DICT_GLOBAL = 5  // global open-addressing table only
+    BK_DICT_GLOBAL = 5, // global open-addressing table only
+    BK_DICT_LANE = 6    // <= 8 groups: key list in LDS, per-lane accumulators in LDS ([slot][lane])
 };
 
 // Compile-time shape of one fused kernel.  Two loops with equal Variant and equal
@@ -112,6 +114,7 @@ struct Slot {
 
 struct Generated {
     std::string source;
+    std::string kernel_name;
     std::vector<Slot> slots;
     int lds_bytes = 0;
 };
@@ -123,7 +126,7 @@ int key_bits(const weld_builder_spec_t& b);
 
 // jit.cpp
 struct Kernel;  // compiled + loaded
-Error jit_get(const std::string& source, bool load_on_device, Kernel** out);
+Error jit_get(const std::string& source, const std::string& kernel_name, bool load_on_device, Kernel** out);
 int jit_blocks_per_cu(Kernel* k, int block);  // resident work-groups per CU, 0 if unknown
 Error jit_launch(Kernel* k, unsigned grid, unsigned block, void* args, size_t args_bytes, void* stream);
 Error set_cache_dir(const char* path);

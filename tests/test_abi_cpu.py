@@ -101,7 +101,7 @@ def test_generated_source_has_one_statement_per_operator(wb):
     src = wb.generated_source(prog)
     body = src[src.index("void weld_row("):src.index("#define WELD_MERGE")]
     assert len(re.findall(r"^\s+const \w[\w ]* t\d+ = ", body, flags=re.M)) == len(prog.ops)
-    assert "weld_kernel" in src and "w_block_reduce" in src
+    assert "weld_fused_" in src and "w_block_reduce" in src
     # constants are emitted bit-exactly
     assert "0x3fa999999999999a" in src            # 0.05
 

@@ -222,7 +222,7 @@ def test_f64_sum_is_reproducible_and_inputs_untouched(wb):
 # ----------------------------------------------------------------------
 # dictmerger
 # ----------------------------------------------------------------------
-@pytest.mark.parametrize("strategy", [1, 2, 3])
+@pytest.mark.parametrize("strategy", [1, 2, 3, 4])
 def test_c4_every_dictionary_strategy(wb, strategy):
     cols = configs.make_columns("C4", 200_003, device="cuda")
     _check(wb, configs.program_c4(), cols, label="C4 strategy %d" % strategy, tune={"dict_strategy": strategy})
