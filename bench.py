@@ -35,6 +35,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--configs", default="C1,C2,C3,C4,C5")
     ap.add_argument("--scale", type=float, default=1.0, help="fraction of the full row counts (for quick checks)")
+    ap.add_argument("--tune", default="", help='JSON of weld_tuning_t fields applied to every fused call, e.g. {"dict_strategy": 2}')
     ap.add_argument("--no-unfused", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -49,6 +50,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     names = [c for c in args.configs.split(",") if c]
+    tune = json.loads(args.tune) if args.tune else None
     rows = {c: max(1, int(configs.FULL_ROWS[c] * args.scale)) for c in names}
     progs = {c: configs.PROGRAMS[c]() for c in names}
     cols = {c: configs.make_columns(c, rows[c], device="cuda") for c in names}
@@ -56,7 +58,7 @@ def main():
     in_bytes = {c: configs.IN_BYTES[c] * rows[c] for c in names}
 
     def step(collect=None):
-        handles = [(c, wb.fused_for(progs[c], cols[c])) for c in names]     # enqueue everything
+        handles = [(c, wb.fused_for(progs[c], cols[c], tune=tune)) for c in names]     # enqueue everything
         for c, r in handles:
             r.check()
             if collect is not None:
@@ -174,7 +176,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": "C1..C5 fused loops, rows " + ", ".join("%s=%d" % (c, rows[c]) for c in names),
-                   "input_bytes_per_step": total_in, "hbm_peak_GBps": HBM_PEAK_GBPS},
+                   "input_bytes_per_step": total_in, "hbm_peak_GBps": HBM_PEAK_GBPS, "tune": tune},
         "rows_per_s": sum(rows.values()) / ms_per_step * 1e3,
         "per_config": per, "roofline": roofline, "cpu_baseline": cpu,
     }
