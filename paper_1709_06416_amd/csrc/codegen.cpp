@@ -342,21 +342,6 @@ Generated generate(const Loop& L, const Variant& var) {
 
     // ------------------------------------------------------------ merge statements
     // (everything except vecbuilders, which the tile code handles)
-    for (size_t b = 0; b < NB; ++b) {
-        if (var.backend[b] != BK_DICT_LDS || L.merge_of[b] < 0) continue;
-        const weld_builder_spec_t& s = L.builders[b];
-        // the active lanes of the wavefront share the parked entries among themselves
-        o.f("#define WELD_DRAIN_%zu(cnt) do { \\\n", b);
-        o.f("  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\"); \\\n");
-        o.f("  const u64 act_ = w_ballot(true); \\\n  const int step_ = __popcll(act_); \\\n");
-        o.f("  for (int e_ = w_rank_below(act_); e_ < (cnt); e_ += step_) { \\\n");
-        o.f("    const i64 g_ = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, d%zu_ck[wave * 64 + e_], errp); \\\n", b, b, b, b);
-        o.f("    if (g_ >= 0) { \\\n");
-        for (int k = 0; k < s.nvals; ++k)
-            o.f("      w_atomic<%d>(a.b%zu_v%d + g_, d%zu_cv%d[wave * 64 + e_], 1); \\\n", s.func, b, k, b, k);
-        o.f("    } \\\n  } \\\n");
-        o.f("  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\"); \\\n} while (0)\n\n");
-    }
     o.f("#define WELD_MERGE(o) do { \\\n");
     for (size_t b = 0; b < NB; ++b) {
         if (L.merge_of[b] < 0) continue;
@@ -388,37 +373,23 @@ Generated generate(const Loop& L, const Variant& var) {
                 o.f("    } \\\n");
             }
             o.f("  } \\\n");
-        } else if (var.backend[b] == BK_DICT_GLOBAL) {
+        } else if (var.backend[b] == BK_DICT_LDS || var.backend[b] == BK_DICT_GLOBAL) {
             o.f("  if ((o).p%zu) { \\\n", b);
             o.f("    const u64 kb = %s; \\\n", pack_key(s, b, "(o)").c_str());
-            o.f("    const i64 g = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, kb, errp); \\\n", b, b, b);
-            o.f("    if (g >= 0) { \\\n");
+            if (var.backend[b] == BK_DICT_LDS) {
+                o.f("    const int sl = w_lds_slot(d%zu_lk, %d, kb, 3); \\\n", b, var.lds_slots);
+                o.f("    if (sl >= 0) { \\\n");
+                for (int k = 0; k < s.nvals; ++k)
+                    o.f("      w_atomic<%d>(d%zu_lv%d + sl, (%s)(o).v%zu_%d, 0); \\\n", F, b, k, acc_ctype(s.val_type[k]), b, k);
+                o.f("    } else { \\\n");
+            } else {
+                o.f("    { \\\n");
+            }
+            o.f("      const i64 g = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, kb, errp); \\\n", b, b, b);
+            o.f("      if (g >= 0) { \\\n");
             for (int k = 0; k < s.nvals; ++k)
-                o.f("      w_atomic<%d>(a.b%zu_v%d + g, (%s)(o).v%zu_%d, 1); \\\n", F, b, k, acc_ctype(s.val_type[k]), b, k);
-            o.f("    } \\\n  } \\\n");
-        } else if (var.backend[b] == BK_DICT_LDS) {
-            // hit: LDS atomics.  miss: the (key, value) pair is parked in this wavefront's cold
-            // buffer; the buffer is sent to the global table 64 entries at a time with every lane
-            // busy, instead of running the global path once per row for a few lanes.
-            o.f("  { \\\n    const bool want_ = (o).p%zu; \\\n", b);
-            o.f("    const u64 kb = %s; \\\n", pack_key(s, b, "(o)").c_str());
-            o.f("    const int sl = want_ ? w_lds_slot(d%zu_lk, %d, kb, 3) : 0; \\\n", b, var.lds_slots);
-            o.f("    if (want_ && sl >= 0) { \\\n");
-            for (int k = 0; k < s.nvals; ++k)
-                o.f("      w_atomic<%d>(d%zu_lv%d + sl, (%s)(o).v%zu_%d, 0); \\\n", F, b, k, acc_ctype(s.val_type[k]), b, k);
-            o.f("    } \\\n");
-            o.f("    const bool miss_ = want_ && sl < 0; \\\n    const u64 mm_ = w_ballot(miss_); \\\n");
-            o.f("    if (mm_) { \\\n      const int add_ = __popcll(mm_); \\\n");
-            o.f("      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\"); \\\n");
-            o.f("      int cnt_ = d%zu_cc[wave]; \\\n", b);
-            o.f("      if (cnt_ + add_ > 64) { WELD_DRAIN_%zu(cnt_); cnt_ = 0; } \\\n", b);
-            o.f("      if (miss_) { \\\n        const int pos_ = wave * 64 + cnt_ + w_rank_below(mm_); \\\n        d%zu_ck[pos_] = kb; \\\n", b);
-            for (int k = 0; k < s.nvals; ++k)
-                o.f("        d%zu_cv%d[pos_] = (%s)(o).v%zu_%d; \\\n", b, k, acc_ctype(s.val_type[k]), b, k);
-            o.f("      } \\\n");
-            o.f("      if (w_rank_below(w_ballot(true)) == 0) d%zu_cc[wave] = cnt_ + add_; \\\n", b);
-            o.f("      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\"); \\\n");
-            o.f("    } \\\n  } \\\n");
+                o.f("        w_atomic<%d>(a.b%zu_v%d + g, (%s)(o).v%zu_%d, 1); \\\n", F, b, k, acc_ctype(s.val_type[k]), b, k);
+            o.f("      } \\\n    } \\\n  } \\\n");
         }
     }
     o.f("} while (0)\n\n");
@@ -432,7 +403,8 @@ Generated generate(const Loop& L, const Variant& var) {
     int lds = 8 * (var.block / 64) + 4;
     if (var.ticketed) {
         o.f("  __shared__ i64 s_tile;\n  __shared__ i64 s_cnt[%d][W_WAVES];\n  __shared__ i64 s_pfx[%d];\n", ncompact, ncompact);
-        lds += 8 + 8 * ncompact * (var.block / 64) + 8 * ncompact;
+        o.f("  __shared__ u64 s_stage[W_WAVES * W_UNIT];\n");
+        lds += 8 + 8 * ncompact * (var.block / 64) + 8 * ncompact + 8 * (var.block / 64) * 64 * var.v;
     }
     // builder state
     bool need_sync = false;
@@ -462,10 +434,6 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("  __shared__ u64 d%zu_lk[%d];\n", b, var.lds_slots);
             lds += 8 * var.lds_slots * (1 + s.nvals);
             for (int k = 0; k < s.nvals; ++k) o.f("  __shared__ %s d%zu_lv%d[%d];\n", acc_ctype(s.val_type[k]), b, k, var.lds_slots);
-            o.f("  __shared__ u64 d%zu_ck[W_WAVES * 64];\n  __shared__ int d%zu_cc[W_WAVES];\n", b, b);
-            for (int k = 0; k < s.nvals; ++k) o.f("  __shared__ %s d%zu_cv%d[W_WAVES * 64];\n", acc_ctype(s.val_type[k]), b, k);
-            lds += (var.block / 64) * (64 * 8 * (1 + s.nvals) + 4);
-            o.f("  if (threadIdx.x < W_WAVES) d%zu_cc[threadIdx.x] = 0;\n", b);
             o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) {\n    d%zu_lk[q] = W_EMPTY_KEY;\n", var.lds_slots, b);
             for (int k = 0; k < s.nvals; ++k) o.f("    d%zu_lv%d[q] = %s;\n", b, k, ident_expr(s.func, s.val_type[k]).c_str());
             o.f("  }\n");
@@ -556,12 +524,12 @@ Generated generate(const Loop& L, const Variant& var) {
         int j = 0;
         for (size_t b = 0; b < NB; ++b) {
             if (var.backend[b] != BK_VEC_COMPACT) continue;
-            o.f("    int rk%zu[W_U][W_V];\n    {\n      int wtot = 0;\n", b);
+            o.f("    int rk%zu[W_U][W_V];\n    int uo%zu[W_U], uc%zu[W_U];\n    {\n      int wtot = 0;\n", b, b, b);
             o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n        int below = 0, utot = 0, mine = 0;\n");
             o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
             o.f("          const u64 bal = w_ballot(o[u][k].p%zu);\n          below += w_rank_below(bal);\n          utot += __popcll(bal);\n        }\n", b);
-            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n          rk%zu[u][k] = wtot + below + mine;\n          mine += o[u][k].p%zu ? 1 : 0;\n        }\n", b, b);
-            o.f("        wtot += utot;\n      }\n");
+            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n          rk%zu[u][k] = below + mine;\n          mine += o[u][k].p%zu ? 1 : 0;\n        }\n", b, b);
+            o.f("        uo%zu[u] = wtot;\n        uc%zu[u] = utot;\n        wtot += utot;\n      }\n", b, b);
             o.f("      if (lane == 0) s_cnt[%d][wave] = wtot;\n    }\n", j);
             ++j;
         }
@@ -580,8 +548,17 @@ Generated generate(const Loop& L, const Variant& var) {
         for (size_t b = 0; b < NB; ++b) {
             if (var.backend[b] != BK_VEC_COMPACT) continue;
             o.f("    {\n      i64 base = s_pfx[%d];\n      for (int w = 0; w < wave; ++w) base += s_cnt[%d][w];\n", j, j);
-            o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k)\n");
-            o.f("          if (o[u][k].p%zu) __builtin_nontemporal_store((%s)o[u][k].v%zu_0, a.b%zu_out + base + rk%zu[u][k]);\n    }\n", b, stype(L.builders[b].val_type[0]), b, b, b);
+            // The selected values of one load unit are packed in LDS at their ranks and written
+            // out as one dense run per instruction (lane l writes elements l, l+64, ...), so HBM
+            // sees full lines instead of scattered 8-byte pieces.
+            const char* ST = stype(L.builders[b].val_type[0]);
+            o.f("      %s* const stg = (%s*)(s_stage + wave * W_UNIT);\n", ST, ST);
+            o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+            o.f("        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\");\n");
+            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k)\n          if (o[u][k].p%zu) stg[rk%zu[u][k]] = (%s)o[u][k].v%zu_0;\n", b, b, ST, b);
+            o.f("        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\");\n");
+            o.f("        _Pragma(\"unroll\") for (int q = 0; q < W_V; ++q) {\n          const int e = q * 64 + lane;\n");
+            o.f("          if (e < uc%zu[u]) __builtin_nontemporal_store(stg[e], a.b%zu_out + base + uo%zu[u] + e);\n        }\n      }\n    }\n", b, b, b);
             ++j;
         }
         o.f("  }\n");
@@ -610,7 +587,6 @@ Generated generate(const Loop& L, const Variant& var) {
             for (int k = 0; k < s.nvals; ++k) o.f("          w_atomic<%d>(a.b%zu_v%d + g, r%d, 1);\n", s.func, b, k, k);
             o.f("        }\n      }\n    }\n  }\n");
         } else if (var.backend[b] == BK_DICT_LDS) {
-            if (L.merge_of[b] >= 0) o.f("  {\n    const int left_ = d%zu_cc[wave];\n    WELD_DRAIN_%zu(left_);\n  }\n", b, b);
             o.f("  __syncthreads();\n");
             o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) {\n    const u64 kb = d%zu_lk[q];\n    if (kb != W_EMPTY_KEY) {\n", var.lds_slots, b);
             o.f("      const i64 g = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, kb, errp);\n      if (g >= 0) {\n", b, b, b);
