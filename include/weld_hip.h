@@ -114,7 +114,7 @@ typedef struct {
     const weld_col_t* col; /* host array */
 } weld_cols_t;
 
-typedef enum { WELD_MERGER = 0, WELD_VECBUILDER = 1, WELD_DICTMERGER = 2 } weld_builder_kind_t;
+typedef enum { WELD_MERGER = 0, WELD_VECBUILDER = 1, WELD_DICTMERGER = 2, WELD_VECMERGER = 3 } weld_builder_kind_t;
 typedef enum { WELD_FUNC_ADD = 0, WELD_FUNC_MUL = 1, WELD_FUNC_MIN = 2, WELD_FUNC_MAX = 3 } weld_func_t;
 
 /* One builder of Table 1.
@@ -123,7 +123,13 @@ typedef enum { WELD_FUNC_ADD = 0, WELD_FUNC_MUL = 1, WELD_FUNC_MIN = 2, WELD_FUN
  *   dictmerger[K,V,func]  : K = struct of key_type[0..nkeys), V = struct of
  *                           val_type[0..nvals); func is applied field by field; the first
  *                           merge of a key stores its value.  capacity = upper bound on the
- *                           number of distinct keys (exceeding it -> WELD_ERR_CAPACITY). */
+ *                           number of distinct keys (exceeding it -> WELD_ERR_CAPACITY).
+ *   vecmerger[T,func]     : merges {index, T} pairs into the cells of a vector of `length`
+ *                           elements that starts as a copy of `init` (a DEVICE pointer to
+ *                           `length` elements of T owned by the caller, never written; NULL =
+ *                           every cell starts at func's identity).  key_type[0] = WELD_I64 (the
+ *                           index), val_type[0] = T (WELD_I64 or WELD_F64).  An index outside
+ *                           0..length-1 makes the call fail with WELD_ERR_INVALID_ARG. */
 typedef struct {
     int32_t kind; /* weld_builder_kind_t */
     int32_t func; /* weld_func_t (ignored by vecbuilder) */
@@ -132,6 +138,8 @@ typedef struct {
     int32_t nvals;
     int32_t val_type[WELD_MAX_VAL_FIELDS];
     int64_t capacity;
+    int64_t length;   /* vecmerger only */
+    const void* init; /* vecmerger only */
 } weld_builder_spec_t;
 
 typedef enum { WELD_MODE_FUSED = 0, WELD_MODE_UNFUSED = 1 } weld_mode_t;
@@ -147,7 +155,9 @@ typedef struct {
     int32_t lds_dict_slots;  /* slots of the per-block LDS hash table (power of two) */
     int32_t spin_limit;      /* polls a tile waits for its predecessors before the call
                                 fails with WELD_ERR_DEVICE (the wait is always bounded)  */
-    int32_t reserved[2];
+    int32_t vecmerger_strategy; /* 0 auto, 1 per-lane register copies (length <= 8), 2 work-group
+                                   copy in LDS updated with LDS atomics, 3 global atomics only   */
+    int32_t reserved[1];
 } weld_tuning_t;
 
 typedef struct {
@@ -200,7 +210,7 @@ const char* weld_result_error(const weld_result_t* r);
 /* Pointer to builder `idx`'s result (Sec. 4.1: "queried for a pointer to the
  * returned data").  Calls weld_result_status() first; NULL on any error.
  *   merger     -> DEVICE pointer to one scalar of its type (8-byte aligned)
- *   vecbuilder -> HOST pointer to a weld_vec_t  (ptr inside is a device pointer)
+ *   vecbuilder, vecmerger -> HOST pointer to a weld_vec_t  (ptr inside is a device pointer)
  *   dictmerger -> HOST pointer to a weld_dict_t (device pointers inside)
  * Valid until weld_result_free(). */
 const void* weld_result_data(weld_result_t* r, int32_t idx);

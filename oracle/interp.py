@@ -18,6 +18,8 @@ What it follows (paper, Sec. 3.2 and Table 1; Sec. 3.3 for the macros):
     in index order (all three printed examples keep index order).
   * dictmerger[K,V,func]: first merge of a key stores the value, later ones
     combine with func, field by field when V is a struct.
+  * vecmerger[T,func] (Table 1, Sec. 7.7): starts from a copy of an input vector and
+    merges each {index, value} pair into the cell at that index with func.
 
 Readings where the paper is silent: integers wrap modulo 2^w; integer div/mod
 truncate toward zero (C); no implicit promotion (a `cast` op is required); f64
@@ -195,12 +197,29 @@ def _group(func, key_cols, val_cols, val_types, sums):
     return (out_keys, out_vals)
 
 
-def run(program, columns, sums="exact"):
+_AT = {"add": np.add, "mul": np.multiply, "min": np.minimum, "max": np.maximum}
+
+
+def _vecmerge(spec, init, idx, v):
+    """vecmerger: out = copy(init); out[idx[j]] = func(out[idx[j]], v[j]) for j in index order."""
+    dt = NP_TYPE[spec["type"]]
+    out = (np.full(spec["length"], identity(spec["func"], spec["type"]), dtype=dt) if init is None
+           else np.array(init, dtype=dt, copy=True))
+    assert out.shape == (spec["length"],)
+    assert idx.size == 0 or (idx.min() >= 0 and idx.max() < spec["length"]), "index out of range"
+    with np.errstate(all="ignore"):
+        _AT[spec["func"]].at(out, idx, v)          # unbuffered: applied pair by pair, in order
+    return out
+
+
+def run(program, columns, sums="exact", inits=None):
     """Evaluate the loop; returns one result per builder, in builder order.
 
     merger      -> numpy scalar of its type
     vecbuilder  -> 1-d numpy array
     dictmerger  -> (list of key columns, list of value columns), sorted by key
+
+    vecmerger   -> 1-d numpy array (inits: {builder index: initial vector})
 
     sums = "exact": an f64 `add` returns the correctly rounded real sum (any
     merge order is legal, Sec. 3.2, so this is the value every order
@@ -233,6 +252,11 @@ def run(program, columns, sums="exact"):
             for c, t in zip(vc, spec["val_types"]):
                 assert c.dtype == NP_TYPE[t]
             results[b] = _group(spec["func"], kc, vc, spec["val_types"], sums)
+        elif spec["kind"] == "vecmerger":
+            idx = val[m["keys"][0]][mask]
+            v = val[m["vals"][0]][mask]
+            assert idx.dtype == np.int64 and v.dtype == NP_TYPE[spec["type"]]
+            results[b] = _vecmerge(spec, (inits or {}).get(b), idx, v)
         else:
             raise ValueError(spec["kind"])
     for b, spec in enumerate(program.builders):
@@ -241,6 +265,9 @@ def run(program, columns, sums="exact"):
                 results[b] = identity(spec["func"], spec["type"])
             elif spec["kind"] == "vecbuilder":
                 results[b] = np.zeros(0, dtype=NP_TYPE[spec["type"]])
+            elif spec["kind"] == "vecmerger":
+                results[b] = _vecmerge(spec, (inits or {}).get(b), np.zeros(0, np.int64),
+                                       np.zeros(0, NP_TYPE[spec["type"]]))
             else:
                 results[b] = ([np.zeros(0, NP_TYPE[t]) for t in spec["key_types"]],
                               [np.zeros(0, NP_TYPE[t]) for t in spec["val_types"]])

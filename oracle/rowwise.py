@@ -113,16 +113,21 @@ def _identity(func, t):
     return math.inf if func == "min" else -math.inf
 
 
-def run(program, columns):
+def run(program, columns, inits=None):
     """columns: list of Python lists (ints / floats).  Returns Python values:
-    merger -> number, vecbuilder -> list, dictmerger -> {key tuple: [values]}."""
+    merger -> number, vecbuilder -> list, dictmerger -> {key tuple: [values]},
+    vecmerger -> list (inits: {builder index: list})."""
     n = len(columns[0]) if columns else 0
     state = []
-    for spec in program.builders:
+    for b, spec in enumerate(program.builders):
         if spec["kind"] == "merger":
             state.append(_identity(spec["func"], spec["type"]))
         elif spec["kind"] == "vecbuilder":
             state.append([])
+        elif spec["kind"] == "vecmerger":
+            init = (inits or {}).get(b)
+            state.append(list(init) if init is not None
+                         else [_identity(spec["func"], spec["type"])] * spec["length"])
         else:
             state.append({})
     for i in range(n):
@@ -149,6 +154,9 @@ def run(program, columns):
                 state[b] = _combine(spec["func"], spec["type"], state[b], val[m["vals"][0]])
             elif spec["kind"] == "vecbuilder":
                 state[b].append(val[m["vals"][0]])
+            elif spec["kind"] == "vecmerger":
+                ix = val[m["keys"][0]]
+                state[b][ix] = _combine(spec["func"], spec["type"], state[b][ix], val[m["vals"][0]])
             else:
                 key = tuple(val[k] for k in m["keys"])
                 vs = [val[v] for v in m["vals"]]

@@ -29,7 +29,7 @@ TORCH_TYPE = {v: k for k, v in TYPE_TORCH.items()}
 OPCODE = {"col": 0, "const": 1, "index": 2, "neg": 3, "not": 4, "cast": 5, "exp": 6, "log": 7, "sqrt": 8,
           "erf": 9, "add": 10, "sub": 11, "mul": 12, "div": 13, "mod": 14, "min": 15, "max": 16, "lt": 17,
           "le": 18, "gt": 19, "ge": 20, "eq": 21, "ne": 22, "and": 23, "or": 24, "select": 25}
-KIND = {"merger": 0, "vecbuilder": 1, "dictmerger": 2}
+KIND = {"merger": 0, "vecbuilder": 1, "dictmerger": 2, "vecmerger": 3}
 FUNC = {"add": 0, "mul": 1, "min": 2, "max": 3}
 MODE = {"fused": 0, "unfused": 1}
 
@@ -66,13 +66,14 @@ class Cols(C.Structure):
 class BuilderSpec(C.Structure):
     _fields_ = [("kind", C.c_int32), ("func", C.c_int32), ("nkeys", C.c_int32),
                 ("key_type", C.c_int32 * MAX_KEY), ("nvals", C.c_int32),
-                ("val_type", C.c_int32 * MAX_VAL), ("capacity", C.c_int64)]
+                ("val_type", C.c_int32 * MAX_VAL), ("capacity", C.c_int64), ("length", C.c_int64),
+                ("init", C.c_void_p)]
 
 
 class Tuning(C.Structure):
     _fields_ = [("block_threads", C.c_int32), ("units_per_thread", C.c_int32), ("grid_blocks", C.c_int32),
                 ("dict_strategy", C.c_int32), ("lds_dict_slots", C.c_int32), ("spin_limit", C.c_int32),
-                ("reserved", C.c_int32 * 2)]
+                ("vecmerger_strategy", C.c_int32), ("reserved", C.c_int32 * 1)]
 
 
 class Conf(C.Structure):
@@ -146,8 +147,9 @@ class WeldError(RuntimeError):
 class Marshalled:
     """C structs of one loop description; keeps the backing arrays alive."""
 
-    def __init__(self, program, mode="fused", stream=0, memory_limit=0, tune=None):
+    def __init__(self, program, mode="fused", stream=0, memory_limit=0, tune=None, inits=None):
         nops = len(program.ops)
+        inits = inits or {}
         self.ops = (Op * max(nops, 1))()
         for i, op in enumerate(program.ops):
             o = self.ops[i]
@@ -198,6 +200,18 @@ class Marshalled:
                 for k, t in enumerate(b["val_types"]):
                     s.val_type[k] = TYPE_ID[t]
                 s.capacity = int(b["capacity"])
+            elif b["kind"] == "vecmerger":
+                s.nkeys = 1
+                s.key_type[0] = TYPE_ID["i64"]
+                s.nvals = 1
+                s.val_type[0] = TYPE_ID[b["type"]]
+                s.length = int(b["length"])
+                t = inits.get(i)
+                if t is not None:
+                    if (not t.is_cuda or not t.is_contiguous() or t.numel() != s.length
+                            or TORCH_TYPE.get(t.dtype) != b["type"]):
+                        raise WeldError(ERR_INVALID_ARG, "vecmerger init must be a contiguous CUDA tensor of its type and length")
+                    s.init = t.data_ptr()
             else:
                 s.nkeys = 0
                 s.nvals = 1
@@ -319,11 +333,12 @@ class Result:
             pass
 
 
-def fused_for(program, columns, mode="fused", stream=None, memory_limit=0, tune=None, n=None):
-    """weld_fused_for over torch CUDA tensors; returns a Result (work is only enqueued)."""
+def fused_for(program, columns, mode="fused", stream=None, memory_limit=0, tune=None, n=None, inits=None):
+    """weld_fused_for over torch CUDA tensors; returns a Result (work is only enqueued).
+    inits: {builder index: CUDA tensor} initial vectors of vecmergers."""
     if stream is None:
         stream = torch.cuda.current_stream().cuda_stream
-    m = Marshalled(program, mode=mode, stream=stream, memory_limit=memory_limit, tune=tune)
+    m = Marshalled(program, mode=mode, stream=stream, memory_limit=memory_limit, tune=tune, inits=inits)
     if len(columns) != len(program.columns):
         raise WeldError(ERR_INVALID_ARG, "column count mismatch")
     cols = (Col * max(len(columns), 1))()
@@ -346,7 +361,7 @@ def fused_for(program, columns, mode="fused", stream=None, memory_limit=0, tune=
     st = lib.weld_fused_for(C.byref(cs), n, C.byref(m.body), C.byref(m.builder), C.byref(out))
     if st != OK:
         raise WeldError(st, lib.weld_last_error().decode())
-    return Result(out, program, (m, cols, list(columns)))
+    return Result(out, program, (m, cols, list(columns), inits))
 
 
 def validate(program, mode="fused"):

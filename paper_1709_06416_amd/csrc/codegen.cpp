@@ -229,6 +229,13 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
             var.backend[b] = cond ? BK_VEC_COMPACT : BK_VEC_DIRECT;
             if (cond) var.ticketed = true;
             if (m >= 0 && type_size(s.val_type[0]) > widest) widest = type_size(s.val_type[0]);
+        } else if (s.kind == WELD_VECMERGER) {
+            // Sec. 7.7: thread-local copies, work-group copies with atomics, one global copy
+            int strat = tune.vecmerger_strategy;
+            if (strat == 1 && s.length > 8) strat = 0;
+            if (strat == 2 && s.length > 16384) strat = 0;
+            if (strat == 0) strat = s.length <= 8 ? 1 : (s.length <= 8192 ? 2 : 3);
+            var.backend[b] = strat == 1 ? BK_VECM_REG : strat == 2 ? BK_VECM_LDS : BK_VECM_GLOBAL;
         } else {
             int strat = tune.dict_strategy;
             const bool few = s.capacity <= 8 && key_bits(s) < 64;
@@ -326,6 +333,9 @@ Generated generate(const Loop& L, const Variant& var) {
                 slot(SLOT_LEN, (int)b, 0, B + "_len", "i64*");
                 ++ncompact;
                 break;
+            case BK_VECM_REG: case BK_VECM_LDS: case BK_VECM_GLOBAL:
+                slot(SLOT_OUT, (int)b, 0, B + "_out", std::string(acc_ctype(s.val_type[0])) + "*");
+                break;
             default:
                 slot(SLOT_DKEYS, (int)b, 0, B + "_keys", "u64*");
                 slot(SLOT_DHDR, (int)b, 0, B + "_hdr", "u32*");
@@ -373,6 +383,17 @@ Generated generate(const Loop& L, const Variant& var) {
                 o.f("    } \\\n");
             }
             o.f("  } \\\n");
+        } else if (var.backend[b] == BK_VECM_REG || var.backend[b] == BK_VECM_LDS || var.backend[b] == BK_VECM_GLOBAL) {
+            const char* A = acc_ctype(s.val_type[0]);
+            o.f("  if ((o).p%zu) { \\\n    const i64 ix = (o).k%zu_0; \\\n", b, b);
+            o.f("    if ((u64)ix < (u64)%lldll) { \\\n", (long long)s.length);
+            if (var.backend[b] == BK_VECM_REG)
+                o.f("      _Pragma(\"unroll\") for (int q = 0; q < %d; ++q) if (ix == q) v%zu_a[q] = w_combine<%d>(v%zu_a[q], (%s)(o).v%zu_0); \\\n", (int)s.length, b, F, b, A, b);
+            else if (var.backend[b] == BK_VECM_LDS)
+                o.f("      w_atomic<%d>(v%zu_l + ix, (%s)(o).v%zu_0, 0); \\\n", F, b, A, b);
+            else
+                o.f("      w_atomic<%d>(a.b%zu_out + ix, (%s)(o).v%zu_0, 1); \\\n", F, b, A, b);
+            o.f("    } else atomicOr(errp, 4); \\\n  } \\\n");
         } else if (var.backend[b] == BK_DICT_LDS || var.backend[b] == BK_DICT_GLOBAL) {
             o.f("  if ((o).p%zu) { \\\n", b);
             o.f("    const u64 kb = %s; \\\n", pack_key(s, b, "(o)").c_str());
@@ -412,6 +433,14 @@ Generated generate(const Loop& L, const Variant& var) {
         const weld_builder_spec_t& s = L.builders[b];
         if (var.backend[b] == BK_MERGER) {
             o.f("  %s m%zu = %s;\n", acc_ctype(s.val_type[0]), b, ident_expr(s.func, s.val_type[0]).c_str());
+        } else if (var.backend[b] == BK_VECM_REG) {
+            o.f("  %s v%zu_a[%d];\n", acc_ctype(s.val_type[0]), b, (int)s.length);
+            o.f("  _Pragma(\"unroll\") for (int q = 0; q < %d; ++q) v%zu_a[q] = %s;\n", (int)s.length, b, ident_expr(s.func, s.val_type[0]).c_str());
+        } else if (var.backend[b] == BK_VECM_LDS) {
+            o.f("  __shared__ %s v%zu_l[%d];\n", acc_ctype(s.val_type[0]), b, (int)s.length);
+            lds += 8 * (int)s.length;
+            o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) v%zu_l[q] = %s;\n", (int)s.length, b, ident_expr(s.func, s.val_type[0]).c_str());
+            need_sync = true;
         } else if (var.backend[b] == BK_DICT_REG || var.backend[b] == BK_DICT_LANE) {
             const int S = (int)s.capacity;
             o.f("  __shared__ u64 d%zu_lk[%d];\n", b, S);
@@ -571,6 +600,17 @@ Generated generate(const Loop& L, const Variant& var) {
             const char* A = acc_ctype(s.val_type[0]);
             o.f("  {\n    const %s tot = w_block_reduce<%d>(m%zu, (%s*)s_red, %s);\n", A, s.func, b, A, ident_expr(s.func, s.val_type[0]).c_str());
             o.f("    if (threadIdx.x == 0) w_store_partial(a.b%zu_part, tot);\n  }\n", b);
+        } else if (var.backend[b] == BK_VECM_REG) {
+            const char* A = acc_ctype(s.val_type[0]);
+            o.f("  _Pragma(\"unroll\") for (int q = 0; q < %d; ++q) {\n", (int)s.length);
+            o.f("    const %s r = w_block_reduce<%d>(v%zu_a[q], (%s*)s_red, %s);\n", A, s.func, b, A, ident_expr(s.func, s.val_type[0]).c_str());
+            o.f("    if (threadIdx.x == 0) w_atomic<%d>(a.b%zu_out + q, r, 1);\n  }\n", s.func, b);
+        } else if (var.backend[b] == BK_VECM_LDS) {
+            // cells this work-group never touched still hold the identity: nothing to send
+            const char* A = acc_ctype(s.val_type[0]);
+            o.f("  __syncthreads();\n  for (int q = threadIdx.x; q < %d; q += W_BLOCK) {\n    const %s x = v%zu_l[q];\n", (int)s.length, A, b);
+            o.f("    const %s id = %s;\n    u64 xb, ib;\n    __builtin_memcpy(&xb, &x, 8);\n    __builtin_memcpy(&ib, &id, 8);\n", A, ident_expr(s.func, s.val_type[0]).c_str());
+            o.f("    if (xb != ib) w_atomic<%d>(a.b%zu_out + q, x, 1);\n  }\n", s.func, b);
         } else if (var.backend[b] == BK_DICT_REG || var.backend[b] == BK_DICT_LANE) {
             const int S = (int)s.capacity;
             const bool lanes = var.backend[b] == BK_DICT_LANE;

@@ -85,7 +85,7 @@ template <int F, int BITS> __device__ __forceinline__ i64 w_identity_int() {
     if (F == W_FUNC_ADD) return 0;
     if (F == W_FUNC_MUL) return 1;
     if (F == W_FUNC_MIN) return (i64)((1ull << (BITS - 1)) - 1);
-    return -(i64)(1ull << (BITS - 1));
+    return (i64)(~0ull << (BITS - 1));
 }
 
 // ---------------------------------------------------------------- wavefront level

@@ -157,6 +157,9 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
                 off[b].out = lay.take((size_t)n * type_size(s.val_type[0]));
                 off[b].desc = lay.take(8 * (size_t)ntiles);
                 break;
+            case BK_VECM_REG: case BK_VECM_LDS: case BK_VECM_GLOBAL:
+                off[b].out = lay.take(8 * (size_t)s.length);
+                break;
             default: {
                 int64_t slots = 64;
                 while (slots < 2 * s.capacity) slots *= 2;
@@ -189,6 +192,10 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
         br.elem_size = type_size(s.val_type[0]);
         if (s.kind == WELD_MERGER) {
             br.scalar = base + off[b].res;
+        } else if (s.kind == WELD_VECMERGER) {
+            br.kind = WELD_VECBUILDER;   // read back like any vector
+            br.vec.ptr = base + off[b].out;
+            br.known_len = s.length;
         } else if (s.kind == WELD_VECBUILDER) {
             br.vec.ptr = base + off[b].out;
             br.known_len = (var.backend[b] == BK_VEC_DIRECT) ? (L.merge_of[b] >= 0 ? n : 0) : -1;
@@ -232,6 +239,12 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
         const weld_builder_spec_t& s = L.builders[b];
         if (var.backend[b] == BK_VEC_COMPACT && ntiles > 0) {
             if ((h = launch_fill64(base + off[b].desc, ntiles, 0, stream)) != hipSuccess) return hip_err("fill", h);
+            r->kernel_count++;
+        } else if (s.kind == WELD_VECMERGER) {
+            // the result starts as a copy of the caller's vector (or as identities)
+            if (s.init) h = hipMemcpyAsync(base + off[b].out, s.init, 8 * (size_t)s.length, hipMemcpyDeviceToDevice, stream);
+            else h = launch_fill64(base + off[b].out, s.length, ident_bits(s.func, s.val_type[0]), stream);
+            if (h != hipSuccess) return hip_err("vecmerger init", h);
             r->kernel_count++;
         } else if (s.kind == WELD_DICTMERGER) {
             if ((h = launch_fill64(base + off[b].keys, off[b].slots + 1, 0x8000000000000000ull, stream)) != hipSuccess)
@@ -380,7 +393,10 @@ weld_status_t weld_result_status(weld_result_t* r) {
     if (hipEventQuery(r->ev3) == hipSuccess) (void)hipEventElapsedTime(&r->kernel_ms, r->ev2, r->ev3);
     (void)hipGetLastError();
     const uint32_t err = r->host_ctl[2];
-    if (err & 2) {
+    if (err & 4) {
+        r->status = WELD_ERR_INVALID_ARG;
+        r->error = "a vecmerger index was outside 0..length-1";
+    } else if (err & 2) {
         r->status = WELD_ERR_DEVICE;
         r->error = "a tile gave up waiting for the prefix of its predecessors (spin limit reached)";
     } else if (err & 1) {

@@ -367,7 +367,7 @@ Error run_unfused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_
     }
     for (weld_result* s : R.subs) {
         if (s->host_ctl[2] != 0 && top->status == WELD_OK) {
-            top->status = (s->host_ctl[2] & 2) ? WELD_ERR_DEVICE : WELD_ERR_CAPACITY;
+            top->status = (s->host_ctl[2] & 4) ? WELD_ERR_INVALID_ARG : (s->host_ctl[2] & 2) ? WELD_ERR_DEVICE : WELD_ERR_CAPACITY;
             top->error = "an operator kernel reported an error";
         }
     }

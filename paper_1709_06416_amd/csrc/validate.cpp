@@ -145,6 +145,15 @@ Error validate(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
                 if (s.func < WELD_FUNC_ADD || s.func > WELD_FUNC_MAX) return fail(WELD_ERR_INVALID_ARG, "builder %d: unknown func %d", b, s.func);
                 if (s.capacity < 1 || s.capacity > (1ll << 30)) return fail(WELD_ERR_INVALID_ARG, "builder %d: capacity out of range", b);
                 break;
+            case WELD_VECMERGER:
+                if (s.nvals != 1 || s.nkeys != 1) return fail(WELD_ERR_INVALID_ARG, "builder %d: vecmerger takes {index, value}", b);
+                if (s.key_type[0] != WELD_I64) return fail(WELD_ERR_TYPE, "builder %d: vecmerger index must be i64", b);
+                if (s.val_type[0] != WELD_I64 && s.val_type[0] != WELD_F64)
+                    return fail(WELD_ERR_UNSUPPORTED, "builder %d: vecmerger of type %d (i64 and f64 are implemented)", b, s.val_type[0]);
+                if (s.func < WELD_FUNC_ADD || s.func > WELD_FUNC_MAX) return fail(WELD_ERR_INVALID_ARG, "builder %d: unknown func %d", b, s.func);
+                if (s.length < 1 || s.length > (1ll << 31)) return fail(WELD_ERR_INVALID_ARG, "builder %d: vecmerger length out of range", b);
+                if (s.init && ((uintptr_t)s.init & 7)) return fail(WELD_ERR_INVALID_ARG, "builder %d: init vector not 8-byte aligned", b);
+                break;
             default:
                 return fail(WELD_ERR_INVALID_ARG, "builder %d: unknown kind %d", b, s.kind);
         }

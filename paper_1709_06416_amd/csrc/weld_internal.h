@@ -82,7 +82,10 @@ enum Backend {
     BK_DICT_REG = 3,    // <= 8 groups: key list in LDS, per-lane register accumulators
     BK_DICT_LDS = 4,    // work-group hash table in LDS in front of the global table
     BK_DICT_GLOBAL = 5, // global open-addressing table only
-    BK_DICT_LANE = 6    // <= 8 groups: key list in LDS, per-lane accumulators in LDS ([slot][lane])
+    BK_DICT_LANE = 6,   // <= 8 groups: key list in LDS, per-lane accumulators in LDS ([slot][lane])
+    BK_VECM_REG = 7,    // vecmerger, <= 8 cells: per-lane register copies ("local")
+    BK_VECM_LDS = 8,    // vecmerger: work-group copy in LDS, LDS atomics ("shared")
+    BK_VECM_GLOBAL = 9  // vecmerger: one global copy, device atomics ("global")
 };
 
 // Compile-time shape of one fused kernel.  Two loops with equal Variant and equal

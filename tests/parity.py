@@ -15,8 +15,9 @@ SUM_RTOL = 1e-9
 MAP_RTOL = 1e-12
 
 
-def oracle_results(prog, cols_gpu):
-    return interp.run(prog, [c.cpu().numpy() for c in cols_gpu], sums="exact")
+def oracle_results(prog, cols_gpu, inits=None):
+    host_inits = {b: t.cpu().numpy() for b, t in (inits or {}).items()}
+    return interp.run(prog, [c.cpu().numpy() for c in cols_gpu], sums="exact", inits=host_inits)
 
 
 def _close_sum(got, want, func):
@@ -36,6 +37,15 @@ def assert_matches(prog, res, want, map_floor=0.0, label=""):
                 assert _close_sum(got, want[b], spec["func"]), (tag, got, want[b])
             else:
                 assert int(got) == int(want[b]), (tag, got, want[b])
+        elif spec["kind"] == "vecmerger":
+            got = res.vec_host(b)
+            assert len(got) == spec["length"], tag
+            if spec["type"] == "f64" and spec["func"] in ("add", "mul"):
+                # cells are sums in some order: relative to the cell, floored at the largest cell
+                scale = np.maximum(np.abs(want[b]), np.max(np.abs(want[b])) if len(got) else 0.0)
+                assert np.all(np.abs(got - want[b]) <= SUM_RTOL * scale), tag
+            else:
+                assert np.array_equal(got, want[b]), tag
         elif spec["kind"] == "vecbuilder":
             got = res.vec_host(b)
             assert len(got) == len(want[b]), (tag, len(got), len(want[b]))

@@ -31,7 +31,7 @@ def _run(wb, prog, cols, **kw):
 
 def _check(wb, prog, cols, map_floor=0.0, label="", **kw):
     from tests import parity
-    want = parity.oracle_results(prog, cols)
+    want = parity.oracle_results(prog, cols, kw.get("inits"))
     res = _run(wb, prog, cols, **kw)
     try:
         parity.assert_matches(prog, res, want, map_floor=map_floor, label=label)
@@ -407,3 +407,81 @@ def test_unfused_index_constants_and_unmerged_builders(wb):
     rnd = np.random.RandomState(5)
     x = rnd.randint(0, 100, size=20_011).astype(np.int64)
     _check(wb, p, [_dev(x)], label="unfused misc", mode="unfused")
+
+
+# ----------------------------------------------------------------------
+# vecmerger (Table 1; the count-occurrences program of Sec. 7.7)
+# ----------------------------------------------------------------------
+def _count_program(length, t="i64", func="add"):
+    p = Program(["i32"])
+    idx = p.un("cast", p.col(0), to="i64")
+    one = p.const(t, 1) if t == "i64" else p.const(t, 1.0)
+    p.merge(p.vecmerger(t, func, length), [one], keys=[idx])
+    return p
+
+
+@pytest.mark.parametrize("strategy", [0, 1, 2, 3])
+@pytest.mark.parametrize("length", [1, 5, 8, 9, 1000, 8192, 8193, 300_000])
+def test_vecmerger_counts_occurrences(wb, length, strategy):
+    rnd = np.random.RandomState(length)
+    n = 200_003
+    keys = rnd.randint(0, length, size=n).astype(np.int32)
+    keys[: n // 4] = keys[0]                                   # one hot cell
+    p = _count_program(length)
+    res = _run(wb, p, [_dev(keys)], tune={"vecmerger_strategy": strategy}).check()
+    got = res.vec_host(0)
+    res.free()
+    assert np.array_equal(got, np.bincount(keys, minlength=length))     # library routine
+    _check(wb, p, [_dev(keys)], label="vecmerger %d/%d" % (length, strategy), tune={"vecmerger_strategy": strategy})
+
+
+@pytest.mark.parametrize("func", ["add", "mul", "min", "max"])
+@pytest.mark.parametrize("t", ["i64", "f64"])
+def test_vecmerger_functions_with_initial_vector(wb, func, t):
+    rnd = np.random.RandomState(3)
+    n, m = 50_021, 777
+    idx = rnd.randint(0, m, size=n).astype(np.int64)
+    if t == "f64":
+        v = rnd.choice([0.5, 1.0, 2.0, 1.0], size=n) if func == "mul" else rnd.randint(-50, 50, size=n).astype(np.float64)
+        init = rnd.randint(-5, 5, size=m).astype(np.float64)
+    else:
+        v = rnd.choice([1, -1, 1, 1], size=n).astype(np.int64) if func == "mul" else rnd.randint(-50, 50, size=n).astype(np.int64)
+        init = rnd.randint(-5, 5, size=m).astype(np.int64)
+    p = Program(["i64", t])
+    pred = p.bin("ne", p.col(0), p.const("i64", 13))           # cell 13 keeps its initial value
+    p.merge(p.vecmerger(t, func, m), [p.col(1)], keys=[p.col(0)], pred=pred)
+    p.merge(p.merger("i64", "add"), p.const("i64", 1), pred=pred)
+    inits = {0: _dev(init)}
+    for strategy in (2, 3):
+        _check(wb, p, [_dev(idx), _dev(v)], label="vecmerger %s %s" % (func, t), inits=inits,
+               tune={"vecmerger_strategy": strategy})
+    _check(wb, p, [_dev(idx), _dev(v)], label="vecmerger unfused", inits=inits, mode="unfused")
+    res = _run(wb, p, [_dev(idx), _dev(v)], inits=inits).check()
+    assert res.vec_host(0)[13] == init[13]
+    assert np.array_equal(inits[0].cpu().numpy(), init)        # the caller's vector is not written
+    res.free()
+
+
+def test_vecmerger_index_out_of_range_is_reported(wb):
+    keys = np.array([0, 1, 2, 70, 3], dtype=np.int32)
+    for strategy in (1, 2, 3):
+        res = _run(wb, _count_program(8), [_dev(keys)], tune={"vecmerger_strategy": strategy})
+        assert res.status() == wb.ERR_INVALID_ARG
+        res.free()
+
+
+def test_vecmerger_agrees_with_dictmerger(wb):
+    # the same counts through two different builders
+    cols = configs.make_columns("C5", 300_011, device="cuda")
+    base = configs.program_c5()
+    p = Program(["i64"])
+    p.ops = list(base.ops)
+    m = base.merges[1]
+    p.merge(p.vecmerger("i64", "add", 100_000), m["vals"], keys=m["keys"], pred=m["pred"])
+    p.merge(p.dictmerger(["i64"], ["i64"], "add", 100_000), m["vals"], keys=m["keys"], pred=m["pred"])
+    res = _run(wb, p, cols).check()
+    counts = res.vec_host(0)
+    keys, vals = res.dict(1)
+    res.free()
+    assert np.array_equal(np.flatnonzero(counts), keys[0])
+    assert np.array_equal(counts[keys[0]], vals[0])

@@ -460,3 +460,49 @@ def test_generators_are_reproducible_and_chunk_independent():
     k = rng.uniform_int(1, 1, 0, 100_000, 0, 10).numpy()
     assert k.min() == 0 and k.max() == 10
     assert np.all(np.abs(np.bincount(k) / 100_000 - 1 / 11) < 0.01)
+
+
+# ----------------------------------------------------------------------
+# vecmerger (Table 1; Sec. 7.7 counts occurrences of keys with it)
+# ----------------------------------------------------------------------
+def _vecmerger_count_program(m):
+    p = Program(["i32"])
+    p.merge(p.vecmerger("i64", "add", m), [p.const("i64", 1)], keys=[p.un("cast", p.col(0), to="i64")])
+    return p
+
+
+def test_vecmerger_counts_match_bincount_and_closed_form():
+    m, n = 37, 10_000
+    keys = (np.arange(n) % m).astype(np.int32)
+    got = interp.run(_vecmerger_count_program(m), [keys])[0]
+    assert got.tolist() == [n // m + (1 if c < n % m else 0) for c in range(m)]     # closed form
+    rnd = np.random.RandomState(2)
+    keys = rnd.randint(0, m, size=n).astype(np.int32)
+    got = interp.run(_vecmerger_count_program(m), [keys])[0]
+    assert np.array_equal(got, np.bincount(keys, minlength=m))
+    assert rowwise.run(_vecmerger_count_program(m), [keys.tolist()])[0] == got.tolist()
+    perm = rnd.permutation(n)
+    assert np.array_equal(interp.run(_vecmerger_count_program(m), [keys[perm]])[0], got)
+
+
+@pytest.mark.parametrize("func", ["add", "mul", "min", "max"])
+def test_vecmerger_brute_force_with_initial_vector(func):
+    rnd = random.Random(5)
+    n, m = 300, 11
+    idx = [rnd.randrange(m) for _ in range(n)]
+    v = [rnd.choice([1, 2, -1, 3]) for _ in range(n)]
+    init = [rnd.randrange(-3, 4) for _ in range(m)]
+    p = Program(["i64", "i64"])
+    pred = p.bin("ne", p.col(0), p.const("i64", 4))
+    p.merge(p.vecmerger("i64", func, m), [p.col(1)], keys=[p.col(0)], pred=pred)
+    want = list(init)
+    for i, x in zip(idx, v):
+        if i == 4:
+            continue
+        want[i] = {"add": want[i] + x, "mul": want[i] * x, "min": min(want[i], x), "max": max(want[i], x)}[func]
+    want = [(w + (1 << 63)) % (1 << 64) - (1 << 63) for w in want]
+    got = interp.run(p, [np.array(idx, np.int64), np.array(v, np.int64)], inits={0: np.array(init, np.int64)})[0]
+    assert got.tolist() == want and want[4] == init[4]
+    assert rowwise.run(p, [idx, v], inits={0: init})[0] == want
+    fresh = interp.run(p, [np.array(idx, np.int64), np.array(v, np.int64)])[0]      # no init: identities
+    assert fresh[4] == interp.identity(func, "i64")

@@ -25,6 +25,9 @@ A `Program` holds
              {'kind': 'vecbuilder', 'type': T}
              {'kind': 'dictmerger', 'key_types': [..], 'val_types': [..],
               'func': f, 'capacity': hint}
+             {'kind': 'vecmerger', 'type': T, 'func': f, 'length': m}
+               (merges {index, value} pairs into a vector of m cells; the
+                initial vector is an input of the call, not of the program)
   merges   : list of dicts {'builder': b, 'pred': op or None,
                             'keys': [ops], 'vals': [ops]}
              (Sec. 3.2: `if (p) merge(b, v) else b` is a merge under predicate p.)
@@ -99,6 +102,11 @@ class Program:
         self.builders.append({"kind": "dictmerger", "key_types": list(key_types),
                               "val_types": list(val_types), "func": func,
                               "capacity": int(capacity)})
+        return len(self.builders) - 1
+
+    def vecmerger(self, t, func, length):
+        assert func in FUNCS
+        self.builders.append({"kind": "vecmerger", "type": t, "func": func, "length": int(length)})
         return len(self.builders) - 1
 
     def merge(self, builder, vals, keys=(), pred=None):
