@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--configs", default="C1,C2,C3,C4,C5")
     ap.add_argument("--scale", type=float, default=1.0, help="fraction of the full row counts (for quick checks)")
     ap.add_argument("--tune", default="", help='JSON of weld_tuning_t fields applied to every fused call, e.g. {"dict_strategy": 2}')
+    ap.add_argument("--vecmerger-sweep", action="store_true",
+                    help="also time the count-occurrences vecmerger program (1e8 32-bit keys) over vector sizes and strategies")
     ap.add_argument("--no-unfused", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -171,6 +173,32 @@ def main():
                "seconds": round(tot_s, 2),
                "sample": "first rows of each config (" + ", ".join(desc) + "), numpy operator-at-a-time oracle, 1 thread"}
 
+    # ---- vecmerger strategies on the count-occurrences program (1e8 32-bit keys, uniform)
+    sweep = None
+    if args.vecmerger_sweep:
+        from workloads import rng
+        from workloads.ir import Program
+        nk = max(1, int(100_000_000 * args.scale))
+        sweep = []
+        for m in (8, 64, 1024, 8192, 65536, 1 << 20, 1 << 24):
+            keys = rng.uniform_int(6, 0, 0, nk, 0, m - 1, "cuda").to(torch.int32)
+            for strat, label in ((1, "local"), (2, "shared"), (3, "global")):
+                if (strat == 1 and m > 8) or (strat == 2 and m > 16384):
+                    continue
+                p = Program(["i32"])
+                p.merge(p.vecmerger("i64", "add", m), [p.const("i64", 1)], keys=[p.un("cast", p.col(0), to="i64")])
+                ts = []
+                for i in range(5):
+                    r = wb.fused_for(p, [keys], tune={"vecmerger_strategy": strat}).check()
+                    if i >= 2:
+                        ts.append(r.kernel_ms())
+                    total = int(r.vec(0).sum().item()) if i == 0 else nk
+                    r.free()
+                    assert total == nk
+                sweep.append({"length": m, "strategy": label, "kernel_ms": round(median(ts), 4),
+                              "keys_per_s": nk / median(ts) * 1e3})
+            del keys
+
     line = {
         "metric": "fused-loop input GB/s (all five configs back to back)", "value": round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -180,6 +208,8 @@ def main():
         "rows_per_s": sum(rows.values()) / ms_per_step * 1e3,
         "per_config": per, "roofline": roofline, "cpu_baseline": cpu,
     }
+    if sweep is not None:
+        line["vecmerger_sweep"] = sweep
     print(json.dumps(line))
 
 

@@ -157,7 +157,8 @@ typedef struct {
                                 fails with WELD_ERR_DEVICE (the wait is always bounded)  */
     int32_t vecmerger_strategy; /* 0 auto, 1 per-lane register copies (length <= 8), 2 work-group
                                    copy in LDS updated with LDS atomics, 3 global atomics only   */
-    int32_t reserved[1];
+    int32_t lds_filter_words;   /* admission filter in front of an LDS hash table that is smaller than
+                                   the key set: 32-bit words of its bitmap (power of two); -1 = none */
 } weld_tuning_t;
 
 typedef struct {

@@ -303,6 +303,35 @@ __device__ __forceinline__ int w_lds_slot(u64* keys, int slots, u64 kbits, int m
     return -1;
 }
 
+// Same, with an admission filter for key sets much larger than the table: a key may take a
+// free slot only the second time this work-group sees it (a bit per hashed key in `door`
+// remembers the first time).  Keys that occur once per work-group - most of a heavy-tailed
+// key set - then never occupy slots that the frequent keys need.
+__device__ __forceinline__ int w_lds_slot_filtered(u64* keys, int slots, u64 kbits, int max_probe,
+                                                   u32* door, u32 door_words) {
+    if (kbits == W_EMPTY_KEY) return -1;
+    const int mask = slots - 1;
+    int s = (int)w_hash_slot(kbits, (u32)slots);
+    for (int probe = 0; probe < max_probe; ++probe) {
+        u64 cur = __hip_atomic_load(keys + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (cur == kbits) return s;
+        if (cur == W_EMPTY_KEY) {
+            const u32 h2 = w_hash(kbits * 0xc2b2ae3d27d4eb4full + 0x165667b19e3779f9ull);
+            const u32 bit = 1u << (h2 & 31);
+            const u32 seen = __hip_atomic_fetch_or(door + ((h2 >> 5) & (door_words - 1)), bit, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (!(seen & bit)) return -1;
+            u64 expect = W_EMPTY_KEY;
+            if (__hip_atomic_compare_exchange_strong(keys + s, &expect, kbits, __ATOMIC_RELAXED,
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP))
+                return s;
+            if (expect == kbits) return s;
+        }
+        s = (s + 1) & mask;
+    }
+    return -1;
+}
+
 // Register-slot dictionary for a handful of groups: the work-group keeps the list
 // of keys it has met in LDS (append-only); every lane accumulates each group in
 // registers.  Returns the slot of `kbits`, appending it if new; -1 if the list is

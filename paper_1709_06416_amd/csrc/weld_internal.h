@@ -97,6 +97,7 @@ struct Variant {
     int aligned = 1;      // 16-byte accesses legal for every pointer
     bool ticketed = false;// tile order taken from an atomic ticket (needed by look-back)
     int lds_slots = 0;    // slots of the LDS dictionary (BK_DICT_LDS)
+    int door_words = 0;   // > 0: admission filter of that many 32-bit words in front of the LDS table
     std::vector<int> backend;   // per builder
 };
 
