@@ -485,3 +485,67 @@ def test_vecmerger_agrees_with_dictmerger(wb):
     res.free()
     assert np.array_equal(np.flatnonzero(counts), keys[0])
     assert np.array_equal(counts[keys[0]], vals[0])
+
+
+# ----------------------------------------------------------------------
+# lazy objects + fusion pass (Sec. 4.1, 4.5): library-style programs evaluated as one loop
+# ----------------------------------------------------------------------
+def test_lazy_pandas_numpy_example(wb):
+    from paper_1709_06416_amd import lazy
+    rnd = np.random.RandomState(7)
+    pop = rnd.randint(0, 1_000_000, size=123_457).astype(np.int64)
+    data = lazy.Vec.from_tensor(_dev(pop))
+    total = data[data > 500000].sum()                      # filtered = data[data > 500000]; numpy.sum(filtered)
+    for mode in ("fused", "unfused"):
+        res = lazy.evaluate(total, mode=mode).check()
+        assert int(res.merger(0)) == int(pop[pop > 500000].sum())
+        launches = res.kernel_count()
+        res.free()
+        assert (launches <= 3) if mode == "fused" else (launches > 6)
+
+
+def test_lazy_c1_and_c3_match_the_oracle(wb):
+    from oracle import interp
+    from paper_1709_06416_amd import lazy
+    cols = configs.make_columns("C1", 400_003, device="cuda")
+    x, y = [lazy.Vec.from_tensor(c) for c in cols]
+    keep = x > 0.5
+    v = x * y + 1.0
+    res = lazy.evaluate(v[keep].sum(), v[keep].count()).check()
+    want = interp.run(configs.program_c1(), [c.cpu().numpy() for c in cols])
+    assert abs(float(res.merger(0)) - float(want[0])) <= 1e-9 * abs(float(want[0]))
+    assert int(res.merger(1)) == int(want[1])
+    res.free()
+
+    cols = configs.make_columns("C3", 500_009, device="cuda")
+    day, disc, qty, price = [lazy.Vec.from_tensor(c) for c in cols]
+    keep = (day >= 365) & (day < 730) & (disc >= 0.05) & (disc <= 0.07) & (qty < 24.0)
+    res = lazy.evaluate((price * disc)[keep].sum()).check()
+    want = interp.run(configs.program_c3(), [c.cpu().numpy() for c in cols])
+    assert abs(float(res.merger(0)) - float(want[0])) <= 1e-9 * abs(float(want[0]))
+    assert res.kernel_count() <= 3                        # one fused loop, not one kernel per operator
+    res.free()
+
+
+def test_lazy_groupby_and_materialised_vector(wb):
+    from oracle import interp
+    from paper_1709_06416_amd import lazy
+    cols = configs.make_columns("C4", 300_007, device="cuda")
+    flag, status, day, qty, price, disc, tax = [lazy.Vec.from_tensor(c) for c in cols]
+    keep = day <= 2400
+    dp = price * (1.0 - disc)
+    charge = dp * (1.0 + tax)
+    ones = (day * 0).cast("i64") + 1
+    d = lazy.groupby([flag[keep], status[keep]], [qty[keep], price[keep], dp[keep], charge[keep], ones[keep]], "add", 8)
+    res = lazy.evaluate(d, charge[keep]).check()
+    (wkeys, wvals), = interp.run(configs.program_c4(), [c.cpu().numpy() for c in cols])
+    keys, vals = res.dict(0)
+    assert np.array_equal(keys[0], wkeys[0]) and np.array_equal(keys[1], wkeys[1])
+    for k in range(4):
+        assert np.all(np.abs(vals[k] - wvals[k]) <= 1e-9 * np.abs(wvals[k]))
+    assert np.array_equal(vals[4], wvals[4])
+    host = [c.cpu().numpy() for c in cols]
+    m = host[2] <= 2400
+    want_vec = ((host[4] * (1.0 - host[5])) * (1.0 + host[6]))[m]
+    assert np.array_equal(res.vec_host(1), want_vec)      # order-preserving, bit-exact
+    res.free()

@@ -1,0 +1,74 @@
+"""The lazy object API and its fusion pass, without a GPU: the fused loop is inspected
+through weld_object_describe (the loop in the notation of the paper's listings)."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_1709_06416_amd", "libweldhip.so")
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libweldhip.so not built")
+
+
+@pytest.fixture(scope="module")
+def lz():
+    from paper_1709_06416_amd import lazy
+    return lazy
+
+
+def _vec(lz, dtype, n=1000, addr=0x10000):
+    return lz.Vec.from_pointer(addr, dtype, n)     # never dereferenced on the CPU
+
+
+def test_pandas_numpy_example_fuses_into_the_printed_loop(lz):
+    # Sec. 4.5: filtered = data[data > 500000]; sum = numpy.sum(filtered)
+    # must become  for(v0, merger[+,0], (b, x) => if (x > 500000) merge(b, x) else b)
+    pop = _vec(lz, "i64")
+    total = pop[pop > 500000].sum()
+    text = lz.describe(total)
+    assert text.count("for(") == 1 and "zip" not in text
+    assert "merger[i64,+]" in text
+    assert "let t2 = x.0 > 500000;" in text
+    assert "if (t2) merge(bs.0, x.0) else bs.0" in text
+
+
+def test_vertical_and_horizontal_fusion_with_shared_subexpressions(lz):
+    x, y = _vec(lz, "f64", addr=0x10000), _vec(lz, "f64", addr=0x20000)
+    v = x * y + 1.0
+    keep = x > 0.5
+    text = lz.describe(v[keep].sum(), v[keep].count(), (x * y)[keep].max())
+    assert text.count("for(") == 1 and "zip(v0, v1)" in text
+    assert text.count("merge(") == 3
+    assert len(re.findall(r"x\.0 \* x\.1", text)) == 1          # x*y is computed once for all three results
+    assert len(re.findall(r"x\.0 > 0\.5", text)) == 1
+
+
+def test_chained_filters_conjoin(lz):
+    a = _vec(lz, "i32")
+    b = a[a > 3]
+    c = b[b < 10]
+    text = lz.describe(c.sum())
+    assert "&&" in text and text.count("for(") == 1
+
+
+def test_what_cannot_be_fused_is_reported(lz):
+    from paper_1709_06416_amd import binding as wb
+    a, b = _vec(lz, "i64", n=1000), _vec(lz, "i64", n=999, addr=0x30000)
+    with pytest.raises(wb.WeldError) as e:
+        lz.describe((a + b).sum())                     # zip of vectors of different length
+    assert "different length" in str(e.value)
+    with pytest.raises(wb.WeldError):
+        lz.describe((a[a > 1] + a).sum())              # one operand filtered, the other not
+    with pytest.raises(wb.WeldError) as e:
+        lz.describe(a.sum(), b.sum())                  # two iteration spaces in one evaluation
+    assert "different lengths" in str(e.value)
+    with pytest.raises(AssertionError):
+        a + _vec(lz, "f64")                            # no implicit casts
+
+
+def test_groupby_becomes_a_dictmerger(lz):
+    k1, k2 = _vec(lz, "i8", addr=0x1000), _vec(lz, "i8", addr=0x2000)
+    q, p = _vec(lz, "f64", addr=0x3000), _vec(lz, "f64", addr=0x4000)
+    d = lz.groupby([k1, k2], [q, p * (1.0 - q)], "add", 8)
+    text = lz.describe(d)
+    assert "dictmerger[{2 keys},{2 values},+]" in text and text.count("for(") == 1
