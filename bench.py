@@ -180,10 +180,10 @@ def main():
         from workloads.ir import Program
         nk = max(1, int(100_000_000 * args.scale))
         sweep = []
-        for m in (8, 64, 1024, 8192, 65536, 1 << 20, 1 << 24):
+        for m in (8, 64, 1024, 8192, 32768, 65536, 1 << 18, 1 << 19, 1 << 20, 1 << 24):
             keys = rng.uniform_int(6, 0, 0, nk, 0, m - 1, "cuda").to(torch.int32)
-            for strat, label in ((1, "local"), (2, "shared"), (3, "global")):
-                if (strat == 1 and m > 8) or (strat == 2 and m > 16384):
+            for strat, label in ((1, "local"), (2, "shared"), (4, "shared by range"), (3, "global")):
+                if (strat == 1 and m > 8) or (strat == 2 and m > 16384) or (strat == 4 and not 8192 < m <= 8192 * 64):
                     continue
                 p = Program(["i32"])
                 p.merge(p.vecmerger("i64", "add", m), [p.const("i64", 1)], keys=[p.un("cast", p.col(0), to="i64")])

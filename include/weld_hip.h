@@ -156,7 +156,8 @@ typedef struct {
     int32_t spin_limit;      /* polls a tile waits for its predecessors before the call
                                 fails with WELD_ERR_DEVICE (the wait is always bounded)  */
     int32_t vecmerger_strategy; /* 0 auto, 1 per-lane register copies (length <= 8), 2 work-group
-                                   copy in LDS updated with LDS atomics, 3 global atomics only   */
+                                   copy in LDS updated with LDS atomics, 3 global atomics only,
+                                   4 LDS copies of 8192-cell ranges, each range scanning all rows */
     int32_t lds_filter_words;   /* admission filter in front of an LDS hash table that is smaller than
                                    the key set: 32-bit words of its bitmap (power of two); -1 = none */
 } weld_tuning_t;

@@ -237,8 +237,17 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
             // measured with 1e8 uniform keys: LDS copy 0.09-0.12 ms up to 8192 cells; register copies
             // 0.24 ms at 8 cells (kept for f64, whose LDS atomics serialise on few addresses);
             // global copy 4.2 ms (23.7 G atomics/s) for large vectors, 13-390 ms below 1024 cells
-            if (strat == 0) strat = (s.length <= 8 && s.val_type[0] == WELD_F64) ? 1 : (s.length <= 8192 ? 2 : 3);
-            var.backend[b] = strat == 1 ? BK_VECM_REG : strat == 2 ? BK_VECM_LDS : BK_VECM_GLOBAL;
+            // Between 8192 cells and about 3e5 a fourth strategy wins on this part: the cells are
+            // split into 8192-cell ranges, each owned by a group of work-groups that scans ALL rows
+            // and merges only its range in LDS.  Reading the keys R times at 6+ TB/s (0.09 ms a pass)
+            // beats one pass of global atomics (4.2 ms) up to R ~ 40.  Only for loops whose single
+            // builder is this vecmerger: everything else would be repeated R times too.
+            const bool alone = L.builders.size() == 1;
+            if (strat == 4 && (!alone || s.length > 8192 * 64)) strat = 0;
+            if (strat == 0) strat = (s.length <= 8 && s.val_type[0] == WELD_F64) ? 1
+                                  : s.length <= 8192 ? 2 : (alone && s.length <= 8192 * 36) ? 4 : 3;
+            var.backend[b] = strat == 1 ? BK_VECM_REG : (strat == 2 || strat == 4) ? BK_VECM_LDS : BK_VECM_GLOBAL;
+            if (strat == 4) var.ranges = (int)((s.length + 8191) / 8192);
         } else {
             int strat = tune.dict_strategy;
             const bool few = s.capacity <= 8 && key_bits(s) < 64;
@@ -403,6 +412,8 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("    if ((u64)ix < (u64)%lldll) { \\\n", (long long)s.length);
             if (var.backend[b] == BK_VECM_REG)
                 o.f("      _Pragma(\"unroll\") for (int q = 0; q < %d; ++q) if (ix == q) v%zu_a[q] = w_combine<%d>(v%zu_a[q], (%s)(o).v%zu_0); \\\n", (int)s.length, b, F, b, A, b);
+            else if (var.backend[b] == BK_VECM_LDS && var.ranges > 1)
+                o.f("      const i64 rx = ix - range_lo; \\\n      if ((u64)rx < 8192ull) w_atomic<%d>(v%zu_l + rx, (%s)(o).v%zu_0, 0); \\\n", F, b, A, b);
             else if (var.backend[b] == BK_VECM_LDS)
                 o.f("      w_atomic<%d>(v%zu_l + ix, (%s)(o).v%zu_0, 0); \\\n", F, b, A, b);
             else
@@ -454,9 +465,10 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("  %s v%zu_a[%d];\n", acc_ctype(s.val_type[0]), b, (int)s.length);
             o.f("  _Pragma(\"unroll\") for (int q = 0; q < %d; ++q) v%zu_a[q] = %s;\n", (int)s.length, b, ident_expr(s.func, s.val_type[0]).c_str());
         } else if (var.backend[b] == BK_VECM_LDS) {
-            o.f("  __shared__ %s v%zu_l[%d];\n", acc_ctype(s.val_type[0]), b, (int)s.length);
-            lds += 8 * (int)s.length;
-            o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) v%zu_l[q] = %s;\n", (int)s.length, b, ident_expr(s.func, s.val_type[0]).c_str());
+            const int cells = var.ranges > 1 ? 8192 : (int)s.length;
+            o.f("  __shared__ %s v%zu_l[%d];\n", acc_ctype(s.val_type[0]), b, cells);
+            lds += 8 * cells;
+            o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) v%zu_l[q] = %s;\n", cells, b, ident_expr(s.func, s.val_type[0]).c_str());
             need_sync = true;
         } else if (var.backend[b] == BK_DICT_REG || var.backend[b] == BK_DICT_LANE) {
             const int S = (int)s.capacity;
@@ -513,7 +525,14 @@ Generated generate(const Loop& L, const Variant& var) {
     if (!var.ticketed) {
         // ---------------- static tile order: no barriers inside the main loop
         o.f("  const i64 nfull = a.n / W_TILE;\n");
-        o.f("  for (i64 t = blockIdx.x; t < nfull; t += gridDim.x) {\n");
+        if (var.ranges > 1) {
+            // work-group g belongs to range g % R and is member g / R of that range's group
+            o.f("  const i64 range_lo = (i64)(blockIdx.x %% %d) * 8192;\n", var.ranges);
+            o.f("  const u32 member = blockIdx.x / %d, members = gridDim.x / %d;\n", var.ranges, var.ranges);
+            o.f("  for (i64 t = member; t < nfull; t += members) {\n");
+        } else {
+            o.f("  for (i64 t = blockIdx.x; t < nfull; t += gridDim.x) {\n");
+        }
         o.f("    const i64 r0 = t * W_TILE + (i64)wave * W_WAVE_ROWS + lane * W_V;\n");
         for (int c = 0; c < L.ncols; ++c)
             if (L.col_used[c]) o.f("    wvec<%s, W_V> x%d[W_U];\n", stype(L.col_type[c]), c);
@@ -535,7 +554,10 @@ Generated generate(const Loop& L, const Variant& var) {
                 o.f("      w_store<%s, W_V>(a.b%zu_out + r0 + u * W_UNIT, y%zu);\n", stype(L.builders[b].val_type[0]), b, b);
         o.f("    }\n  }\n");
         // tail rows, one per thread
-        o.f("  for (i64 i = nfull * W_TILE + (i64)blockIdx.x * W_BLOCK + threadIdx.x; i < a.n; i += (i64)gridDim.x * W_BLOCK) {\n");
+        if (var.ranges > 1)
+            o.f("  for (i64 i = nfull * W_TILE + (i64)member * W_BLOCK + threadIdx.x; i < a.n; i += (i64)members * W_BLOCK) {\n");
+        else
+            o.f("  for (i64 i = nfull * W_TILE + (i64)blockIdx.x * W_BLOCK + threadIdx.x; i < a.n; i += (i64)gridDim.x * W_BLOCK) {\n");
         o.f("    RowOut o;\n    %s\n    WELD_MERGE(o);\n", row_call("i", "a.c%d[i]", "o").c_str());
         for (size_t b = 0; b < NB; ++b)
             if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) o.f("    a.b%zu_out[i] = o.v%zu_0;\n", b, b);
@@ -629,9 +651,13 @@ Generated generate(const Loop& L, const Variant& var) {
         } else if (var.backend[b] == BK_VECM_LDS) {
             // cells this work-group never touched still hold the identity: nothing to send
             const char* A = acc_ctype(s.val_type[0]);
-            o.f("  __syncthreads();\n  for (int q = threadIdx.x; q < %d; q += W_BLOCK) {\n    const %s x = v%zu_l[q];\n", (int)s.length, A, b);
+            const int cells = var.ranges > 1 ? 8192 : (int)s.length;
+            o.f("  __syncthreads();\n  for (int q = threadIdx.x; q < %d; q += W_BLOCK) {\n    const %s x = v%zu_l[q];\n", cells, A, b);
             o.f("    const %s id = %s;\n    u64 xb, ib;\n    __builtin_memcpy(&xb, &x, 8);\n    __builtin_memcpy(&ib, &id, 8);\n", A, ident_expr(s.func, s.val_type[0]).c_str());
-            o.f("    if (xb != ib) w_atomic<%d>(a.b%zu_out + q, x, 1);\n  }\n", s.func, b);
+            if (var.ranges > 1)
+                o.f("    if (xb != ib && range_lo + q < %lldll) w_atomic<%d>(a.b%zu_out + range_lo + q, x, 1);\n  }\n", (long long)s.length, s.func, b);
+            else
+                o.f("    if (xb != ib) w_atomic<%d>(a.b%zu_out + q, x, 1);\n  }\n", s.func, b);
         } else if (var.backend[b] == BK_DICT_REG || var.backend[b] == BK_DICT_LANE) {
             const int S = (int)s.capacity;
             const bool lanes = var.backend[b] == BK_DICT_LANE;

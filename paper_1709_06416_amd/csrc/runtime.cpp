@@ -137,6 +137,10 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
     int64_t grid = conf.tune.grid_blocks > 0 ? conf.tune.grid_blocks : (int64_t)device_info().cus * per_cu;
     if (grid > ntiles) grid = ntiles;
     if (grid < 1) grid = 1;
+    if (var.ranges > 1) {   // range-partitioned vecmerger: the same number of work-groups for every range
+        grid = grid / var.ranges * var.ranges;
+        if (grid < var.ranges) grid = var.ranges;
+    }
 
     // ---- one block: control words, per-builder workspace, results
     Layout lay;

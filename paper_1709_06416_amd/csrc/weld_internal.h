@@ -97,6 +97,8 @@ struct Variant {
     int aligned = 1;      // 16-byte accesses legal for every pointer
     bool ticketed = false;// tile order taken from an atomic ticket (needed by look-back)
     int lds_slots = 0;    // slots of the LDS dictionary (BK_DICT_LDS)
+    int ranges = 1;       // > 1: vecmerger cells split into this many 8192-cell ranges, one per group of
+                          // work-groups; every group scans all rows and merges only its own range
     int door_words = 0;   // > 0: admission filter of that many 32-bit words in front of the LDS table
     std::vector<int> backend;   // per builder
 };

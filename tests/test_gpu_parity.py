@@ -420,8 +420,8 @@ def _count_program(length, t="i64", func="add"):
     return p
 
 
-@pytest.mark.parametrize("strategy", [0, 1, 2, 3])
-@pytest.mark.parametrize("length", [1, 5, 8, 9, 1000, 8192, 8193, 300_000])
+@pytest.mark.parametrize("strategy", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("length", [1, 5, 8, 9, 1000, 8192, 8193, 20_000, 300_000])
 def test_vecmerger_counts_occurrences(wb, length, strategy):
     rnd = np.random.RandomState(length)
     n = 200_003
@@ -452,7 +452,7 @@ def test_vecmerger_functions_with_initial_vector(wb, func, t):
     p.merge(p.vecmerger(t, func, m), [p.col(1)], keys=[p.col(0)], pred=pred)
     p.merge(p.merger("i64", "add"), p.const("i64", 1), pred=pred)
     inits = {0: _dev(init)}
-    for strategy in (2, 3):
+    for strategy in (2, 3, 4):
         _check(wb, p, [_dev(idx), _dev(v)], label="vecmerger %s %s" % (func, t), inits=inits,
                tune={"vecmerger_strategy": strategy})
     _check(wb, p, [_dev(idx), _dev(v)], label="vecmerger unfused", inits=inits, mode="unfused")
