@@ -222,7 +222,6 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
             case SLOT_COL: v = (uint64_t)(uintptr_t)cols[b].data; break;
             case SLOT_CTL: v = (uint64_t)(uintptr_t)(base + off_ctl); break;
             case SLOT_PARTIAL: v = (uint64_t)(uintptr_t)(base + off[b].part); break;
-            case SLOT_RESULT: break;
             case SLOT_OUT: v = (uint64_t)(uintptr_t)(base + off[b].out); break;
             case SLOT_DESC: v = (uint64_t)(uintptr_t)(base + off[b].desc); break;
             case SLOT_LEN: v = (uint64_t)(uintptr_t)(base + off_ctl + ctl_count_off(b)); break;

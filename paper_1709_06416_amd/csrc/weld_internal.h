@@ -106,7 +106,7 @@ struct Variant {
 // One 8-byte kernel argument.  The generated `struct KArgs` lists them in this order.
 enum SlotKind {
     SLOT_N = 0, SLOT_SPIN, SLOT_COL, SLOT_CTL,
-    SLOT_PARTIAL, SLOT_RESULT,          // merger
+    SLOT_PARTIAL,                       // merger
     SLOT_OUT, SLOT_DESC, SLOT_LEN,      // vecbuilder
     SLOT_DKEYS, SLOT_DHDR, SLOT_DSLOTS, SLOT_DVAL  // dictmerger
 };
