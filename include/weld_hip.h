@@ -160,6 +160,10 @@ typedef struct {
                                    4 LDS copies of 8192-cell ranges, each range scanning all rows */
     int32_t lds_filter_words;   /* admission filter in front of an LDS hash table that is smaller than
                                    the key set: 32-bit words of its bitmap (power of two); -1 = none */
+    int32_t dict_spill;         /* merges that miss such an LDS table: -1 = device atomics on the global
+                                   table; otherwise they are appended to key-partitioned queues that a
+                                   second kernel aggregates in LDS (> 0: entries per queue segment,
+                                   0 = sized so that no merge can overflow a segment)               */
 } weld_tuning_t;
 
 typedef struct {

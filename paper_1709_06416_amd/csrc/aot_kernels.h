@@ -37,6 +37,26 @@ hipError_t launch_fill64(void* p, int64_t count, uint64_t value, hipStream_t str
 hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots, const DictValues& vals,
                                const DictLayout& lay, int64_t capacity, void* out_keys, void* out_vals,
                                void* count, void* err, hipStream_t stream);
+// Aggregation of the key-partitioned spill queues of a large dictmerger (spill_kernels.hip).
+// The loop kernel's work-group g appends to segment [g][partition] of `log` (cap entries of
+// 1 + nvals 8-byte words each) and stores the segment lengths in qcnt[g * kSpillParts + partition].
+constexpr int kSpillParts = 256;
+struct SpillMerge {
+    const unsigned long long* log;
+    const unsigned int* qcnt;
+    int groups;                    // work-groups of the loop kernel, <= 1024
+    long long cap;
+    int func;
+    int is_f64[8];
+    unsigned long long ident[8];
+    unsigned long long* keys;      // the global table the loop kernel uses
+    unsigned int* hdr;
+    long long slots;
+    unsigned long long* vals[8];
+    int* err;
+};
+hipError_t launch_dict_spill_merge(const SpillMerge& a, int nvals, hipStream_t stream);
+
 hipError_t launch_probe_read(const void* data, int64_t bytes, void* checksum, int blocks, hipStream_t stream);
 hipError_t launch_probe_copy(void* dst, const void* src, int64_t bytes, int blocks, hipStream_t stream);
 

@@ -276,20 +276,26 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
             if (want <= 0) {
                 want = 64;
                 while (want * 2 * per_slot <= 64 * 1024 && want < 2 * max_cap) want *= 2;
-                if (max_cap > want) {
-                    big_dict = true;
+                if (max_cap > want)
                     while (want * 2 * per_slot <= 128 * 1024) want *= 2;
-                    if (ndl == 1 && tune.lds_filter_words >= 0) {
-                        int w = tune.lds_filter_words > 0 ? tune.lds_filter_words : 2048;   // 65536 bits
-                        int p2w = 64;
-                        while (p2w < w && p2w < 8192) p2w *= 2;
-                        var.door_words = p2w;
-                    }
-                }
             }
             int p2 = 64;
             while (p2 < want && p2 < (1 << 14)) p2 *= 2;
             var.lds_slots = p2;
+            big_dict = (int64_t)p2 * per_slot > 64 * 1024;
+            if (max_cap > p2 && ndl == 1) {
+                // more keys than slots: an admission filter keeps the once-per-work-group keys
+                // of a heavy tail out of the table, and the misses - the bulk of the kernel's
+                // time when each is a device atomic (C5: 1.2e7 of them at 23.7 G/s) - are
+                // queued for a second kernel instead
+                if (tune.lds_filter_words >= 0) {
+                    const int w = tune.lds_filter_words > 0 ? tune.lds_filter_words : 2048;   // 65536 bits
+                    int p2w = 64;
+                    while (p2w < w && p2w < 8192) p2w *= 2;
+                    var.door_words = p2w;
+                }
+                if (tune.dict_spill >= 0) var.spill = true;
+            }
         }
     }
     (void)any;
@@ -318,6 +324,19 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
     var.block = (var.block / 64) * 64;
     var.aligned = aligned ? 1 : 0;
     return var;
+}
+
+// Stores of one spill-queue entry at word offset `ei` of builder b's log: 16 bytes at a time
+// when the entry has an even number of words (entries are then 16-byte aligned).
+static void emit_log_stores(Out& o, size_t b, const std::vector<std::string>& words, const char* eol) {
+    const size_t n = words.size();
+    if (n % 2 == 0) {
+        for (size_t q = 0; q < n; q += 2)
+            o.f("        w_gstore2(a.b%zu_log + ei + %zu, %s, %s);%s\n", b, q, words[q].c_str(), words[q + 1].c_str(), eol);
+    } else {
+        for (size_t q = 0; q < n; ++q)
+            o.f("        w_gstore1(a.b%zu_log + ei + %zu, %s);%s\n", b, q, words[q].c_str(), eol);
+    }
 }
 
 Generated generate(const Loop& L, const Variant& var) {
@@ -365,6 +384,11 @@ Generated generate(const Loop& L, const Variant& var) {
                 slot(SLOT_DSLOTS, (int)b, 0, B + "_slots", "i64");
                 for (int k = 0; k < s.nvals; ++k)
                     slot(SLOT_DVAL, (int)b, k, B + "_v" + std::to_string(k), std::string(acc_ctype(s.val_type[k])) + "*");
+                if (var.backend[b] == BK_DICT_LDS && var.spill) {
+                    slot(SLOT_DLOG, (int)b, 0, B + "_log", "u64*");
+                    slot(SLOT_DQCNT, (int)b, 0, B + "_qcnt", "u32*");
+                    slot(SLOT_DQCAP, (int)b, 0, B + "_qcap", "i64");
+                }
         }
     }
     o.f("struct KArgs {\n");
@@ -434,10 +458,27 @@ Generated generate(const Loop& L, const Variant& var) {
             } else {
                 o.f("    { \\\n");
             }
+            const bool spill = var.backend[b] == BK_DICT_LDS && var.spill;
+            if (spill) {
+                o.f("      const i64 ei = w_spill_index(d%zu_qn, a.b%zu_qcap, %d, kb); \\\n", b, b, 1 + s.nvals);
+                o.f("      if (ei >= 0) { \\\n");
+                {
+                    std::vector<std::string> words;
+                    words.push_back("kb");
+                    for (int k = 0; k < s.nvals; ++k) {
+                        char buf[96];
+                        snprintf(buf, sizeof buf, "w_bits((%s)(o).v%zu_%d)", acc_ctype(s.val_type[k]), b, k);
+                        words.push_back(buf);
+                    }
+                    emit_log_stores(o, b, words, " \\");
+                }
+                o.f("      } else { \\\n");
+            }
             o.f("      const i64 g = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, kb, errp); \\\n", b, b, b);
             o.f("      if (g >= 0) { \\\n");
             for (int k = 0; k < s.nvals; ++k)
                 o.f("        w_atomic<%d>(a.b%zu_v%d + g, (%s)(o).v%zu_%d, 1); \\\n", F, b, k, acc_ctype(s.val_type[k]), b, k);
+            if (spill) o.f("      } \\\n");
             o.f("      } \\\n    } \\\n  } \\\n");
         }
     }
@@ -495,6 +536,10 @@ Generated generate(const Loop& L, const Variant& var) {
             if (var.door_words > 0) {
                 o.f("  __shared__ u32 d%zu_door[%d];\n  for (int q = threadIdx.x; q < %d; q += W_BLOCK) d%zu_door[q] = 0;\n", b, var.door_words, var.door_words, b);
                 lds += 4 * var.door_words;
+            }
+            if (var.spill) {
+                o.f("  __shared__ u32 d%zu_qn[W_SPILL_PARTS];\n  for (int q = threadIdx.x; q < W_SPILL_PARTS; q += W_BLOCK) d%zu_qn[q] = 0;\n", b, b);
+                lds += 4 * 256;
             }
             o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) {\n    d%zu_lk[q] = W_EMPTY_KEY;\n", var.lds_slots, b);
             for (int k = 0; k < s.nvals; ++k) o.f("    d%zu_lv%d[q] = %s;\n", b, k, ident_expr(s.func, s.val_type[k]).c_str());
@@ -676,9 +721,29 @@ Generated generate(const Loop& L, const Variant& var) {
         } else if (var.backend[b] == BK_DICT_LDS) {
             o.f("  __syncthreads();\n");
             o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) {\n    const u64 kb = d%zu_lk[q];\n    if (kb != W_EMPTY_KEY) {\n", var.lds_slots, b);
+            if (var.spill) {
+                // the table's own contents take the same road as the misses
+                o.f("      const i64 ei = w_spill_index(d%zu_qn, a.b%zu_qcap, %d, kb);\n", b, b, 1 + s.nvals);
+                o.f("      if (ei >= 0) {\n");
+                {
+                    std::vector<std::string> words;
+                    words.push_back("kb");
+                    for (int k = 0; k < s.nvals; ++k) {
+                        char buf[96];
+                        snprintf(buf, sizeof buf, "w_bits(d%zu_lv%d[q])", b, k);
+                        words.push_back(buf);
+                    }
+                    emit_log_stores(o, b, words, "");
+                }
+                o.f("        continue;\n      }\n");
+            }
             o.f("      const i64 g = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, kb, errp);\n      if (g >= 0) {\n", b, b, b);
             for (int k = 0; k < s.nvals; ++k) o.f("        w_atomic<%d>(a.b%zu_v%d + g, d%zu_lv%d[q], 1);\n", s.func, b, k, b, k);
             o.f("      }\n    }\n  }\n");
+            if (var.spill) {
+                o.f("  __syncthreads();\n  for (int q = threadIdx.x; q < W_SPILL_PARTS; q += W_BLOCK)\n");
+                o.f("    a.b%zu_qcnt[(u64)blockIdx.x * W_SPILL_PARTS + q] = d%zu_qn[q] < (u64)a.b%zu_qcap ? d%zu_qn[q] : (u32)a.b%zu_qcap;\n", b, b, b, b, b);
+            }
         }
     }
     o.f("}\n");

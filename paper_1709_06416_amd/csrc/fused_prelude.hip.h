@@ -332,6 +332,39 @@ __device__ __forceinline__ int w_lds_slot_filtered(u64* keys, int slots, u64 kbi
     return -1;
 }
 
+// Spill queues of a large dictionary.  A merge that found no room in the LDS table is
+// appended to segment [work-group][partition] of a log in global memory instead of
+// going to the global table with device atomics; the partition is taken from a hash that
+// is independent of the table hashes.  `qn` are the work-group's W_SPILL_PARTS segment
+// lengths (LDS), `cap` the entries a segment holds, `words` = 1 + value fields.  Returns
+// the word offset of the entry in the log (key word first), or -1 if the segment is full:
+// the caller then falls back to the global table.  A second kernel aggregates partition by
+// partition in LDS.
+#define W_SPILL_PARTS 256
+__device__ __forceinline__ i64 w_spill_index(u32* qn, i64 cap, int words, u64 kbits) {
+    const u32 part = w_hash(kbits * 0xc2b2ae3d27d4eb4full + 0x165667b19e3779f9ull) >> 24;
+    const u32 pos = __hip_atomic_fetch_add(qn + part, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if ((i64)pos >= cap) return -1;
+    return (i64)((((u64)blockIdx.x * W_SPILL_PARTS + part) * (u64)cap + pos) * (u64)words);
+}
+// Stores to device memory that say so (a pointer that went through a select or a helper is
+// otherwise stored through with flat instructions, which also count as LDS operations and
+// make every later wait on LDS wait for memory as well).
+typedef u64 w_u64x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void w_gstore1(u64* p, u64 x) {
+    *(__attribute__((address_space(1))) u64*)p = x;
+}
+__device__ __forceinline__ void w_gstore2(u64* p, u64 x, u64 y) {   // p is 16-byte aligned
+    const w_u64x2 v = {x, y};
+    *(__attribute__((address_space(1))) w_u64x2*)p = v;
+}
+__device__ __forceinline__ u64 w_bits(double v) {
+    u64 b;
+    __builtin_memcpy(&b, &v, 8);
+    return b;
+}
+__device__ __forceinline__ u64 w_bits(i64 v) { return (u64)v; }
+
 // Register-slot dictionary for a handful of groups: the work-group keeps the list
 // of keys it has met in LDS (append-only); every lane accumulates each group in
 // registers.  Returns the slot of `kbits`, appending it if new; -1 if the list is

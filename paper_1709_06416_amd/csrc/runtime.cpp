@@ -9,6 +9,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <cstdio>
+#include <cmath>
 #include <cstring>
 #include <mutex>
 
@@ -137,6 +138,7 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
     int64_t grid = conf.tune.grid_blocks > 0 ? conf.tune.grid_blocks : (int64_t)device_info().cus * per_cu;
     if (grid > ntiles) grid = ntiles;
     if (grid < 1) grid = 1;
+    if (var.spill && grid > 1024) grid = 1024;   // the queue aggregation scans one segment per work-group and thread
     if (var.ranges > 1) {   // range-partitioned vecmerger: the same number of work-groups for every range
         grid = grid / var.ranges * var.ranges;
         if (grid < var.ranges) grid = var.ranges;
@@ -145,7 +147,7 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
     // ---- one block: control words, per-builder workspace, results
     Layout lay;
     const size_t off_ctl = lay.take(kCtlBytes);
-    struct Off { size_t part = 0, res = 0, out = 0, desc = 0, keys = 0, vals[8] = {0}, okeys = 0, ovals = 0; int64_t slots = 0; };
+    struct Off { size_t part = 0, res = 0, out = 0, desc = 0, keys = 0, vals[8] = {0}, okeys = 0, ovals = 0, log = 0, qcnt = 0; int64_t slots = 0, qcap = 0; };
     std::vector<Off> off(NB);
     for (size_t b = 0; b < NB; ++b) {
         const weld_builder_spec_t& s = L.builders[b];
@@ -177,6 +179,31 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
                 off[b].ovals = lay.take((size_t)s.capacity * vs);
             }
         }
+    }
+    // spill queues of a large LDS dictionary come last, so that they can shrink to what
+    // the memory limit leaves: a full segment only sends its merges to the global table
+    for (size_t b = 0; b < NB; ++b) {
+        if (var.backend[b] != BK_DICT_LDS || !var.spill) continue;
+        const weld_builder_spec_t& s = L.builders[b];
+        const size_t entry = 8 * (size_t)(1 + s.nvals);
+        off[b].qcnt = lay.take(4 * (size_t)grid * kSpillParts);
+        int64_t cap = conf.tune.dict_spill;
+        if (cap <= 0) {
+            // every row of a work-group may miss: its share of the rows (tickets hand tiles out
+            // unevenly: a quarter more), spread over the partitions by a hash (six standard
+            // deviations more), plus what the table itself holds when it is flushed
+            const double rows = (double)((ntiles + grid - 1) / grid) * (double)tile * (var.ticketed ? 1.25 : 1.0);
+            const double mean = (rows + var.lds_slots) / kSpillParts;
+            cap = (int64_t)(mean + 6.0 * std::sqrt(mean) + 16.0);
+        }
+        const size_t seg = (size_t)grid * kSpillParts * entry;
+        if (conf.memory_limit > 0) {
+            const int64_t room = conf.memory_limit - (int64_t)lay.total;
+            const int64_t fit = room > 0 ? (room - 256) / (int64_t)seg : 0;
+            if (cap > fit) cap = fit > 0 ? fit : 0;
+        }
+        off[b].qcap = cap;
+        off[b].log = lay.take(seg * (size_t)cap);
     }
     if (conf.memory_limit > 0 && (int64_t)lay.total > conf.memory_limit)
         return mk(WELD_ERR_OOM, "the loop needs " + std::to_string(lay.total) + " bytes of device memory, limit is " +
@@ -229,6 +256,9 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
             case SLOT_DHDR: v = (uint64_t)(uintptr_t)(base + off_ctl + ctl_hdr_off(b)); break;
             case SLOT_DSLOTS: v = (uint64_t)off[b].slots; break;
             case SLOT_DVAL: v = (uint64_t)(uintptr_t)(base + off[b].vals[s.field]); break;
+            case SLOT_DLOG: v = (uint64_t)(uintptr_t)(base + off[b].log); break;
+            case SLOT_DQCNT: v = (uint64_t)(uintptr_t)(base + off[b].qcnt); break;
+            case SLOT_DQCAP: v = (uint64_t)off[b].qcap; break;
         }
         args.push_back(v);
     }
@@ -263,8 +293,32 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
     if ((h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream);
     if (!e.ok()) return e;
-    if ((h = hipEventRecord(r->ev3, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     r->kernel_count++;
+    // queued dictionary merges: aggregated per key partition, then added to the global table
+    // (timed with the loop kernel: it is the second half of that kernel's work)
+    for (size_t b = 0; b < NB; ++b) {
+        if (var.backend[b] != BK_DICT_LDS || !var.spill) continue;
+        const weld_builder_spec_t& s = L.builders[b];
+        SpillMerge sm;
+        memset(&sm, 0, sizeof sm);
+        sm.log = (const unsigned long long*)(base + off[b].log);
+        sm.qcnt = (const unsigned int*)(base + off[b].qcnt);
+        sm.groups = (int)grid;
+        sm.cap = off[b].qcap;
+        sm.func = s.func;
+        for (int k = 0; k < s.nvals; ++k) {
+            sm.is_f64[k] = s.val_type[k] == WELD_F64;
+            sm.ident[k] = ident_bits(s.func, s.val_type[k]);
+            sm.vals[k] = (unsigned long long*)(base + off[b].vals[k]);
+        }
+        sm.keys = (unsigned long long*)(base + off[b].keys);
+        sm.hdr = (unsigned int*)(base + off_ctl + ctl_hdr_off((int)b));
+        sm.slots = off[b].slots;
+        sm.err = (int*)(base + off_ctl + 8);
+        if ((h = launch_dict_spill_merge(sm, s.nvals, stream)) != hipSuccess) return hip_err("dict spill merge", h);
+        r->kernel_count++;
+    }
+    if ((h = hipEventRecord(r->ev3, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     MergerFinish mf;
     memset(&mf, 0, sizeof mf);
     for (size_t b = 0; b < NB; ++b) {

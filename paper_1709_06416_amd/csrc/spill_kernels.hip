@@ -1,0 +1,246 @@
+// Second half of the large-dictionary path (dictmerger, Table 1 of the paper): merges that
+// found no room in a work-group's LDS table were appended by the loop kernel to
+// key-partitioned queues (segment [group][partition], `cap` entries of 1 + NV words:
+// packed key, then one 8-byte cell per value field).  Here one 1024-thread work-group
+// per partition aggregates its partition in an LDS hash table and then adds the table to
+// the global one.  A partition holds about keys / 256 distinct keys, so its table fits LDS
+// where the whole key set did not, and the random-address device atomics of the direct
+// path (23.7 G/s on this part, the bound of that path) shrink to one per distinct key.
+//
+// The hash functions and the global-table insert are the ones of the loop kernels: both
+// write the same table.
+#include <hip/hip_runtime.h>
+
+#define W_BLOCK 1024
+#define W_V 2
+#define W_U 1
+#define W_ALIGNED 1
+#include "fused_prelude.hip.h"
+
+#include "aot_kernels.h"
+
+namespace weld {
+
+// largest power of two with slots * 8 * (1 + NV) <= 128 KiB
+template <int NV> struct SpillTable {
+    static constexpr int kSlots = NV <= 1 ? 8192 : NV <= 3 ? 4096 : NV <= 7 ? 2048 : 1024;
+    static constexpr int kBatch = NV <= 1 ? 4 : NV <= 3 ? 2 : 1;   // entries a thread holds in registers, twice
+};
+
+// One value cell: the bits are an i64 or a double, FUNC is the dictmerger's merge function.
+template <int FUNC> __device__ __forceinline__ void cell_combine(u64* p, u64 bits, int is_f64, const int agent) {
+    if (is_f64) {
+        double v;
+        __builtin_memcpy(&v, &bits, 8);
+        w_atomic<FUNC>(reinterpret_cast<double*>(p), v, agent);
+    } else {
+        w_atomic<FUNC>(reinterpret_cast<i64*>(p), (i64)bits, agent);
+    }
+}
+
+// w_lds_slot with a probe loop that stays a loop (32 unrolled probes per call site made the
+// kernel larger than the instruction cache)
+__device__ __forceinline__ int lds_slot_looped(u64* keys, int slots, u64 kbits, int max_probe) {
+    if (kbits == W_EMPTY_KEY) return -1;
+    const int mask = slots - 1;
+    int s = (int)w_hash_slot(kbits, (u32)slots);
+#pragma unroll 1
+    for (int probe = 0; probe < max_probe; ++probe) {
+        u64 cur = __hip_atomic_load(keys + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (cur == kbits) return s;
+        if (cur == W_EMPTY_KEY) {
+            u64 expect = W_EMPTY_KEY;
+            if (__hip_atomic_compare_exchange_strong(keys + s, &expect, kbits, __ATOMIC_RELAXED,
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP))
+                return s;
+            if (expect == kbits) return s;
+        }
+        s = (s + 1) & mask;
+    }
+    return -1;
+}
+
+template <int NV, int FUNC>
+__global__ void __launch_bounds__(1024) dict_spill_merge_kernel(const SpillMerge a) {
+    constexpr int S = SpillTable<NV>::kSlots;
+    __shared__ u64 s_keys[S];
+    __shared__ u64 s_vals[NV][S];
+    __shared__ u32 s_off[1025];
+    __shared__ u32 s_wave[16];
+    const int part = blockIdx.x;
+    const int tid = threadIdx.x;
+    for (int q = tid; q < S; q += 1024) {
+        s_keys[q] = W_EMPTY_KEY;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) s_vals[k][q] = a.ident[k];
+    }
+    // exclusive prefix of the segment lengths of this partition over the groups (<= 1024)
+    u32 mine = 0;
+    if (tid < a.groups) {
+        mine = a.qcnt[(size_t)tid * kSpillParts + part];
+        if ((i64)mine > a.cap) mine = (u32)a.cap;
+    }
+    u32 incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const u32 o = __shfl_up(incl, off, 64);
+        if ((tid & 63) >= off) incl += o;
+    }
+    if ((tid & 63) == 63) s_wave[tid >> 6] = incl;
+    __syncthreads();
+    u32 before = 0;
+    for (int w = 0; w < (tid >> 6); ++w) before += s_wave[w];
+    s_off[tid + 1] = before + incl;
+    if (tid == 0) s_off[0] = 0;
+    __syncthreads();
+    const u32 total = s_off[a.groups];
+
+    // adds one entry to the global table: for what the LDS table cannot take, and for the
+    // LDS table's own contents at the end
+    auto to_global = [&](u64 key, const u64 (&w)[NV]) {
+        const i64 g = w_table_slot(a.keys, a.hdr, a.slots, key, a.err);
+        if (g >= 0) {
+#pragma unroll
+            for (int f = 0; f < NV; ++f) cell_combine<FUNC>(a.vals[f] + g, w[f], a.is_f64[f], 1);
+        }
+    };
+
+    // ENT entries per thread and round, entry j of thread t at i0 + j * 1024 + t: the lanes of
+    // a wavefront read neighbouring entries (one contiguous span per load when an entry is 16
+    // bytes).  The loads of the next round are issued before the entries of this round are
+    // merged, so the merges hide their latency.
+    constexpr int ENT = SpillTable<NV>::kBatch;
+    constexpr int WORDS = 1 + NV;
+    typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+    u64 kcur[ENT], knext[ENT];
+    u64 vcur[ENT][NV], vnext[ENT][NV];
+    auto fetch = [&](u32 i0, u64 (&k)[ENT], u64 (&w)[ENT][NV]) {
+#pragma unroll
+        for (int j = 0; j < ENT; ++j) {
+            const u32 i = i0 + (u32)j * 1024u + (u32)tid;
+            if (i < total) {
+                // the segment of entry i: segments of one partition are about equally long, so
+                // start from the proportional guess and walk (s_off[lo] <= i < s_off[lo + 1])
+                int lo = (int)(((u64)i * (u64)a.groups) / total);
+                while (s_off[lo] > i) --lo;
+                while (s_off[lo + 1] <= i) ++lo;
+                const u64* e = a.log + (((size_t)lo * kSpillParts + part) * (size_t)a.cap + (i - s_off[lo])) * WORDS;
+                u64 buf[WORDS];
+                if (WORDS % 2 == 0) {               // entries are 16-byte aligned
+                    const u64x2* e2 = reinterpret_cast<const u64x2*>(e);
+#pragma unroll
+                    for (int q = 0; q < WORDS / 2; ++q) {
+                        const u64x2 t = e2[q];
+                        buf[2 * q] = t.x;
+                        buf[2 * q + 1] = t.y;
+                    }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < WORDS; ++q) buf[q] = e[q];
+                }
+                k[j] = buf[0];
+#pragma unroll
+                for (int f = 0; f < NV; ++f) w[j][f] = buf[1 + f];
+            } else {
+                k[j] = W_EMPTY_KEY;
+#pragma unroll
+                for (int f = 0; f < NV; ++f) w[j][f] = 0;
+            }
+        }
+    };
+    fetch(0, kcur, vcur);
+    for (u32 i0 = 0; i0 < total; i0 += 1024u * ENT) {
+        fetch(i0 + 1024u * ENT, knext, vnext);
+        // first probe of all entries of the round side by side (one LDS latency instead of
+        // one per entry); an entry whose first slot holds another key or nothing goes the
+        // whole way (claim the free slot, or probe on)
+        int sl[ENT];
+        u64 first[ENT];
+#pragma unroll
+        for (int j = 0; j < ENT; ++j) {
+            sl[j] = (int)w_hash_slot(kcur[j], (u32)S);
+            first[j] = __hip_atomic_load(s_keys + sl[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+#pragma unroll
+        for (int j = 0; j < ENT; ++j) {
+            const bool live = i0 + (u32)j * 1024u + (u32)tid < total;
+            if (!live) sl[j] = -2;
+            else if (first[j] != kcur[j] || kcur[j] == W_EMPTY_KEY) sl[j] = lds_slot_looped(s_keys, S, kcur[j], 32);
+        }
+#pragma unroll
+        for (int j = 0; j < ENT; ++j) {
+            if (sl[j] >= 0) {
+#pragma unroll
+                for (int f = 0; f < NV; ++f) cell_combine<FUNC>(&s_vals[f][sl[j]], vcur[j][f], a.is_f64[f], 0);
+            } else if (sl[j] == -1) {
+                // no room in this partition's table (or the one key equal to the free marker)
+                to_global(kcur[j], vcur[j]);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < ENT; ++j) {
+            kcur[j] = knext[j];
+#pragma unroll
+            for (int f = 0; f < NV; ++f) vcur[j][f] = vnext[j][f];
+        }
+    }
+    __syncthreads();
+    // occupied slots are few (a partition's distinct keys): list them first, so that the global
+    // inserts - three dependent device-memory operations each - run side by side
+    u32* const s_list = s_off;      // the prefix is not needed any more
+    if (tid == 0) s_wave[0] = 0;
+    __syncthreads();
+    for (int q = tid; q < S; q += 1024) {
+        if (s_keys[q] == W_EMPTY_KEY) continue;
+        const u32 at = __hip_atomic_fetch_add(&s_wave[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (at < 1024) s_list[at] = (u32)q;
+    }
+    __syncthreads();
+    const u32 occupied = s_wave[0];
+    if (occupied <= 1024u) {
+        if ((u32)tid < occupied) {
+            const int q = (int)s_list[tid];
+            u64 w[NV];
+#pragma unroll
+            for (int f = 0; f < NV; ++f) w[f] = s_vals[f][q];
+            to_global(s_keys[q], w);
+        }
+    } else {                        // more than the list holds: every thread walks its slots
+        for (int q = tid; q < S; q += 1024) {
+            if (s_keys[q] == W_EMPTY_KEY) continue;
+            u64 w[NV];
+#pragma unroll
+            for (int f = 0; f < NV; ++f) w[f] = s_vals[f][q];
+            to_global(s_keys[q], w);
+        }
+    }
+}
+
+template <int NV>
+static hipError_t launch_nv(const SpillMerge& a, hipStream_t stream) {
+    const dim3 grid(kSpillParts), block(1024);
+    switch (a.func) {
+        case W_FUNC_ADD: dict_spill_merge_kernel<NV, W_FUNC_ADD><<<grid, block, 0, stream>>>(a); break;
+        case W_FUNC_MUL: dict_spill_merge_kernel<NV, W_FUNC_MUL><<<grid, block, 0, stream>>>(a); break;
+        case W_FUNC_MIN: dict_spill_merge_kernel<NV, W_FUNC_MIN><<<grid, block, 0, stream>>>(a); break;
+        case W_FUNC_MAX: dict_spill_merge_kernel<NV, W_FUNC_MAX><<<grid, block, 0, stream>>>(a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_dict_spill_merge(const SpillMerge& a, int nvals, hipStream_t stream) {
+    switch (nvals) {
+        case 1: return launch_nv<1>(a, stream);
+        case 2: return launch_nv<2>(a, stream);
+        case 3: return launch_nv<3>(a, stream);
+        case 4: return launch_nv<4>(a, stream);
+        case 5: return launch_nv<5>(a, stream);
+        case 6: return launch_nv<6>(a, stream);
+        case 7: return launch_nv<7>(a, stream);
+        case 8: return launch_nv<8>(a, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace weld

@@ -100,6 +100,8 @@ struct Variant {
     int ranges = 1;       // > 1: vecmerger cells split into this many 8192-cell ranges, one per group of
                           // work-groups; every group scans all rows and merges only its own range
     int door_words = 0;   // > 0: admission filter of that many 32-bit words in front of the LDS table
+    bool spill = false;   // merges that miss the LDS dictionary are appended to key-partitioned queues
+                          // which a second kernel aggregates, instead of device atomics on the global table
     std::vector<int> backend;   // per builder
 };
 
@@ -108,7 +110,8 @@ enum SlotKind {
     SLOT_N = 0, SLOT_SPIN, SLOT_COL, SLOT_CTL,
     SLOT_PARTIAL,                       // merger
     SLOT_OUT, SLOT_DESC, SLOT_LEN,      // vecbuilder
-    SLOT_DKEYS, SLOT_DHDR, SLOT_DSLOTS, SLOT_DVAL  // dictmerger
+    SLOT_DKEYS, SLOT_DHDR, SLOT_DSLOTS, SLOT_DVAL,  // dictmerger
+    SLOT_DLOG, SLOT_DQCNT, SLOT_DQCAP               // dictmerger spill queues
 };
 struct Slot {
     SlotKind kind;

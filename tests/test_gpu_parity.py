@@ -239,6 +239,37 @@ def test_small_lds_table_overflows_into_global(wb):
     _check(wb, configs.program_c5(), cols, label="C5 tiny LDS", tune={"dict_strategy": 2, "lds_dict_slots": 64})
 
 
+@pytest.mark.parametrize("spill", [0, -1, 3, 40])
+def test_c5_spill_queue_variants(wb, spill):
+    # misses of the LDS table: queued and aggregated per key partition (0: queues sized for
+    # every row), straight to the global table (-1), or queues so short that most merges
+    # overflow them and take the global road after all (3, 40)
+    cols = configs.make_columns("C5", 400_009, device="cuda")
+    _check(wb, configs.program_c5(), cols, label="C5 spill %d" % spill, tune={"dict_spill": spill})
+
+
+def test_spill_queues_shrink_to_the_memory_limit(wb):
+    cols = configs.make_columns("C5", 400_009, device="cuda")
+    _check(wb, configs.program_c5(), cols, label="C5 spill under a limit", memory_limit=12_000_000)
+    with pytest.raises(wb.WeldError) as e:
+        _run(wb, configs.program_c5(), cols, memory_limit=5_000_000)
+    assert e.value.status == wb.ERR_OOM
+
+
+def test_large_dictionary_of_mostly_distinct_keys(wb):
+    # nearly every merge misses the LDS table; includes the key equal to the free-slot marker
+    rnd = np.random.RandomState(5)
+    n = 300_011
+    keys = rnd.randint(0, 150_000, size=n).astype(np.int64) * 7_919 - 500_000_000
+    keys[::1001] = np.iinfo(np.int64).min
+    vals = rnd.uniform(-1, 1, size=n)
+    p = Program(["i64", "f64"])
+    p.merge(p.dictmerger(["i64"], ["f64", "i64", "f64"], "add", 160_000),
+            [p.col(1), p.const("i64", 1), p.bin("mul", p.col(1), p.col(1))], keys=[p.col(0)])
+    for spill in (0, -1, 5):
+        _check(wb, p, [_dev(keys), _dev(vals)], label="distinct keys spill %d" % spill, tune={"dict_spill": spill})
+
+
 @pytest.mark.parametrize("func", ["add", "min", "max", "mul"])
 def test_dictmerger_functions_and_struct_keys(wb, func):
     rnd = np.random.RandomState(23)
@@ -377,7 +408,7 @@ def test_fused_equals_unfused_on_the_gpu(wb):
     ka, va = a.dict(1)
     kb, vb = b.dict(1)
     assert np.array_equal(ka[0], kb[0]) and np.array_equal(va[0], vb[0])
-    assert b.kernel_count() > 3 * a.kernel_count()
+    assert b.kernel_count() > 2 * a.kernel_count()
     a.free()
     b.free()
     cols = configs.make_columns("C2", 50_001, device="cuda")
