@@ -21,6 +21,11 @@ What it follows (paper, Sec. 3.2 and Table 1; Sec. 3.3 for the macros):
   * vecmerger[T,func] (Table 1, Sec. 7.7): starts from a copy of an input vector and
     merges each {index, value} pair into the cell at that index with func.
 
+  * nested loops (Sec. 3.2: loops nest arbitrarily; a loop may take a start and an end
+    index per vector): `run_nested` evaluates the inner body over every (outer element,
+    inner element) pair, folds each outer element's pairs with the inner merger, and
+    runs the outer body over the outer elements with those results as a column.
+
 Readings where the paper is silent: integers wrap modulo 2^w; integer div/mod
 truncate toward zero (C); no implicit promotion (a `cast` op is required); f64
 is IEEE round-to-nearest with one rounding per operator and no contraction;
@@ -28,7 +33,9 @@ dictionary entries are returned sorted by key (the paper leaves them
 unordered, so callers compare sorted).
 
 Parity pins live in tests/test_oracle_pins.py (paper-printed results, closed
-forms, brute force against oracle/rowwise.py, library routines, exact sums).
+forms, brute force against oracle/rowwise.py, library routines, exact sums) and, for
+nested loops, tests/test_oracle_nested_pins.py (a hand-worked example, scipy's sparse
+product, the literal nested loops, PageRank fixed points and rank conservation).
 Black-Scholes prices have no printed value in the paper: they are pinned by
 put-call parity, bounds and a decimal-arithmetic evaluation of the formula;
 agreement of erf/exp/log with higher precision is checked on samples only.
@@ -65,9 +72,15 @@ def _trunc_div(a, b):
     return (a - r) // b
 
 
-def eval_columns(program, columns):
-    """Materialise every body expression as a full column (one operator at a time)."""
-    n = len(columns[0]) if columns else 0
+def eval_columns(program, columns, n=None, gather=None, outer=None, inner=None):
+    """Materialise every body expression as a full column (one operator at a time).
+
+    gather / outer / inner give meaning to the operators of nested loops: the vectors
+    `lookup` reads, the outer vectors already expanded to one element per row of this
+    (inner) loop, and the column of inner-loop results seen by an outer body.
+    """
+    if n is None:
+        n = len(columns[0]) if columns else 0
     for k, c in enumerate(columns):
         assert c.dtype == NP_TYPE[program.columns[k]], (k, c.dtype)
         assert len(c) == n
@@ -76,9 +89,18 @@ def eval_columns(program, columns):
         for op in program.ops:
             code, t = op[0], op[1]
             dt = NP_TYPE[t]
-            a = [val[j] for j in op[2:]] if code not in ("col", "const", "index") else None
+            a = ([val[j] for j in op[2:]]
+                 if code not in ("col", "const", "index", "lookup", "outer", "inner") else None)
             if code == "col":
                 out = columns[op[2]]
+            elif code == "lookup":
+                vec, idx = gather[op[2]], val[op[3]].astype(np.int64)
+                assert idx.size == 0 or (idx.min() >= 0 and idx.max() < len(vec)), "lookup out of range"
+                out = vec[idx]
+            elif code == "outer":
+                out = outer[op[2]]
+            elif code == "inner":
+                out = inner
             elif code == "const":
                 out = np.full(n, op[2], dtype=dt)
             elif code == "index":
@@ -227,6 +249,11 @@ def run(program, columns, sums="exact", inits=None):
     """
     val = eval_columns(program, columns)
     n = len(columns[0]) if columns else 0
+    return _results(program, val, n, sums, inits)
+
+
+def _results(program, val, n, sums, inits):
+    """The builders' results, given every body expression as a column."""
     results = [None] * len(program.builders)
     merged = set()
     for m in program.merges:
@@ -272,3 +299,49 @@ def run(program, columns, sums="exact", inits=None):
                 results[b] = ([np.zeros(0, NP_TYPE[t]) for t in spec["key_types"]],
                               [np.zeros(0, NP_TYPE[t]) for t in spec["val_types"]])
     return results
+
+
+def run_nested(nested, outer_columns, inner_columns, gather, sums="exact"):
+    """A `for` nested in a `for` (Sec. 3.2: loops nest arbitrarily; a loop takes an
+    optional start and end index per vector), evaluated one operator at a time:
+
+      1. every (outer element i, inner element j in [start[i], end[i])) pair becomes one row:
+         the inner body is evaluated over all pairs, `outer` reading element i of an outer
+         vector and `col` element j of an inner vector;
+      2. the pairs of one outer element are folded with the inner merger's function
+         (f64 sums: the correctly rounded real sum when sums == "exact"): one result per
+         outer element, the identity for an empty range;
+      3. the outer body is the ordinary loop of `run` over the outer elements, with that
+         column of results as the value of `inner`.
+
+    Ranges may overlap or leave gaps: nothing here assumes they are consecutive.
+    Returns one result per builder of the outer program, like `run`.
+    """
+    n_outer = len(outer_columns[0]) if outer_columns else 0
+    start = outer_columns[nested.start_col].astype(np.int64)
+    end = outer_columns[nested.end_col].astype(np.int64)
+    n_inner = len(inner_columns[0]) if inner_columns else None
+    assert np.all(start <= end) and (n_outer == 0 or start.min() >= 0)
+    if n_inner is not None and n_outer:
+        assert end.max() <= n_inner
+    length = end - start
+    seg = np.repeat(np.arange(n_outer, dtype=np.int64), length)      # outer element of each pair
+    first = np.cumsum(length) - length                               # pairs before each outer element
+    j = np.arange(int(length.sum()), dtype=np.int64) - np.repeat(first, length) + np.repeat(start, length)
+    prog = nested.inner
+    val = eval_columns(prog, [c[j] for c in inner_columns], n=len(j), gather=gather,
+                       outer=[c[seg] for c in outer_columns])
+    assert len(prog.merges) == 1 and prog.merges[0]["builder"] == 0
+    m = prog.merges[0]
+    mask = val[m["pred"]] if m["pred"] is not None else np.ones(len(j), dtype=bool)
+    v = val[m["vals"][0]]
+    assert v.dtype == NP_TYPE[nested.inner_type]
+    r = np.empty(n_outer, dtype=NP_TYPE[nested.inner_type])
+    bounds = np.append(first, len(j))
+    for i in range(n_outer):
+        lo, hi = bounds[i], bounds[i + 1]
+        r[i] = _fold(nested.inner_func, nested.inner_type, v[lo:hi][mask[lo:hi]], sums)
+    # step 3: the outer loop, `inner` bound to r
+    outer_prog = nested.outer
+    oval = eval_columns(outer_prog, outer_columns, n=n_outer, inner=r)
+    return _results(outer_prog, oval, n_outer, sums, None)

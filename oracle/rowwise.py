@@ -113,7 +113,57 @@ def _identity(func, t):
     return math.inf if func == "min" else -math.inf
 
 
-def run(program, columns, inits=None):
+def _typed(x, t):
+    return float(x) if t == "f64" else (bool(x) if t == "bool" else int(x))
+
+
+def _body(program, i, elem, gather=None, outer_elem=None, inner_value=None):
+    """Every expression of the body for ONE row: index i, `elem` = this row's element of each
+    zipped vector.  Nested loops: `gather` are the vectors lookup may read, `outer_elem` the
+    current outer element (inner bodies), `inner_value` the inner loop's result (outer bodies)."""
+    val = []
+    for op in program.ops:
+        code, t = op[0], op[1]
+        if code == "col":
+            val.append(_typed(elem[op[2]], t))
+        elif code == "const":
+            val.append(_typed(op[2], t))
+        elif code == "index":
+            val.append(i)
+        elif code == "cast":
+            val.append(_cast(val[op[2]], program.ops[op[2]][1], t))
+        elif code == "lookup":
+            ix = val[op[3]]
+            assert 0 <= ix < len(gather[op[2]]), "lookup out of range"
+            val.append(_typed(gather[op[2]][ix], t))
+        elif code == "outer":
+            val.append(_typed(outer_elem[op[2]], t))
+        elif code == "inner":
+            val.append(inner_value)
+        else:
+            val.append(_apply(code, t, [val[j] for j in op[2:]]))
+    return val
+
+
+def run_nested(nested, outer_columns, inner_columns, gather):
+    """The nested loop written out: for every outer element, run its inner `for` over
+    [start, end) with a fresh merger, take result(), then evaluate the outer body and merge.
+    Returns the outer builders like `run` (merger -> number, vecbuilder -> list, ...)."""
+    n_outer = len(outer_columns[0]) if outer_columns else 0
+    inner_results = []
+    for i in range(n_outer):
+        x = [c[i] for c in outer_columns]
+        acc = _identity(nested.inner_func, nested.inner_type)        # a new merger per outer element
+        m = nested.inner.merges[0]
+        for j in range(int(x[nested.start_col]), int(x[nested.end_col])):
+            val = _body(nested.inner, j, [c[j] for c in inner_columns], gather=gather, outer_elem=x)
+            if m["pred"] is None or val[m["pred"]]:
+                acc = _combine(nested.inner_func, nested.inner_type, acc, val[m["vals"][0]])
+        inner_results.append(acc)                                    # result(inner builder)
+    return run(nested.outer, outer_columns, inner_results=inner_results)
+
+
+def run(program, columns, inits=None, inner_results=None):
     """columns: list of Python lists (ints / floats).  Returns Python values:
     merger -> number, vecbuilder -> list, dictmerger -> {key tuple: [values]},
     vecmerger -> list (inits: {builder index: list})."""
@@ -131,20 +181,8 @@ def run(program, columns, inits=None):
         else:
             state.append({})
     for i in range(n):
-        val = []
-        for op in program.ops:                     # the whole body, for this row only
-            code, t = op[0], op[1]
-            if code == "col":
-                x = columns[op[2]][i]
-                val.append(float(x) if t == "f64" else (bool(x) if t == "bool" else int(x)))
-            elif code == "const":
-                val.append(float(op[2]) if t == "f64" else (bool(op[2]) if t == "bool" else int(op[2])))
-            elif code == "index":
-                val.append(i)
-            elif code == "cast":
-                val.append(_cast(val[op[2]], program.ops[op[2]][1], t))
-            else:
-                val.append(_apply(code, t, [val[j] for j in op[2:]]))
+        val = _body(program, i, [c[i] for c in columns],
+                    inner_value=None if inner_results is None else inner_results[i])
         for m in program.merges:
             if m["pred"] is not None and not val[m["pred"]]:
                 continue                            # `else b`: builder returned untouched

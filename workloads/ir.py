@@ -19,6 +19,12 @@ A `Program` holds
              binary  -> args = (a, b)        add sub mul div mod min max
                                              lt le gt ge eq ne and or
              'select'-> args = (cond, a, b)
+             'lookup'-> args = (gather_vector_index, index_value)   element of a
+                        vector read at a computed position (nested loops only)
+             'outer' -> args = (outer_column_index,)   inner body of a nested loop:
+                        the current OUTER element of that vector
+             'inner' -> args = ()   outer body of a nested loop: the result of this
+                        outer element's inner loop
            operand references are indices of earlier entries.
   builders : list of dicts
              {'kind': 'merger',     'type': T, 'func': f}
@@ -44,10 +50,13 @@ FUNCS = ("add", "mul", "min", "max")
 class Program:
     """Builder for the plain-data loop description (no evaluation here)."""
 
-    def __init__(self, columns):
-        for t in columns:
+    def __init__(self, columns, gather=(), outer=(), inner_type=None):
+        for t in list(columns) + list(gather) + list(outer):
             assert t in TYPES, t
         self.columns = list(columns)
+        self.gather = list(gather)        # element types of the vectors `lookup` may read
+        self.outer_columns = list(outer)  # an inner body's view of the outer vectors
+        self.inner_type = inner_type      # an outer body's view of the inner loop's result
         self.ops = []
         self.builders = []
         self.merges = []
@@ -87,6 +96,17 @@ class Program:
     def select(self, c, a, b):
         return self._push(("select", self.type_of(a), c, a, b))
 
+    def lookup(self, k, idx):
+        assert self.type_of(idx) in ("i8", "i32", "i64")
+        return self._push(("lookup", self.gather[k], k, idx))
+
+    def outer(self, k):
+        return self._push(("outer", self.outer_columns[k], k))
+
+    def inner(self):
+        assert self.inner_type is not None
+        return self._push(("inner", self.inner_type))
+
     # ---- builders ---------------------------------------------------
     def merger(self, t, func):
         assert func in FUNCS
@@ -114,3 +134,28 @@ class Program:
             vals = [vals]
         self.merges.append({"builder": builder, "pred": pred,
                             "keys": list(keys), "vals": list(vals)})
+
+
+class NestedProgram:
+    """A `for` nested in a `for` (Sec. 3.2 of the paper: loops nest; a loop may take a
+    start and an end index per input vector):
+
+        for(zip(outer...), builders, (bs, i, x) =>
+            let r = result(for(iter(zip(inner...), x.start, x.end), merger[T, func], inner_body));
+            outer_body(x, r, i))
+
+    `inner` is a Program over the inner vectors with exactly one merger (builder 0) and may
+    use `lookup` and `outer`; `outer` is a Program over the outer vectors that may use
+    `inner()`; start_col / end_col name the outer columns that hold each outer element's
+    inner range [start, end).  Plain data, no evaluation.
+    """
+
+    def __init__(self, outer_columns, start_col, end_col, inner_columns, gather, inner_type, inner_func):
+        assert inner_func in FUNCS and inner_type in ("i64", "f64")
+        assert outer_columns[start_col] == outer_columns[end_col] and outer_columns[start_col] in ("i32", "i64")
+        self.start_col, self.end_col = start_col, end_col
+        self.inner_type, self.inner_func = inner_type, inner_func
+        self.inner = Program(inner_columns, gather=gather, outer=outer_columns)
+        self.inner.merger(inner_type, inner_func)
+        self.outer = Program(outer_columns, inner_type=inner_type)
+        self.gather = list(gather)
