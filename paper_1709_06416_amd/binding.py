@@ -28,7 +28,8 @@ TYPE_TORCH = {"i8": torch.int8, "i32": torch.int32, "i64": torch.int64, "f64": t
 TORCH_TYPE = {v: k for k, v in TYPE_TORCH.items()}
 OPCODE = {"col": 0, "const": 1, "index": 2, "neg": 3, "not": 4, "cast": 5, "exp": 6, "log": 7, "sqrt": 8,
           "erf": 9, "add": 10, "sub": 11, "mul": 12, "div": 13, "mod": 14, "min": 15, "max": 16, "lt": 17,
-          "le": 18, "gt": 19, "ge": 20, "eq": 21, "ne": 22, "and": 23, "or": 24, "select": 25}
+          "le": 18, "gt": 19, "ge": 20, "eq": 21, "ne": 22, "and": 23, "or": 24, "select": 25,
+          "lookup": 26, "outer": 27, "inner": 28}      # the last three: include/weld_nested.h
 KIND = {"merger": 0, "vecbuilder": 1, "dictmerger": 2, "vecmerger": 3}
 FUNC = {"add": 0, "mul": 1, "min": 2, "max": 3}
 MODE = {"fused": 0, "unfused": 1}
@@ -136,6 +137,21 @@ lib.weld_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
 lib.weld_probe_copy.restype = C.c_int
 lib.weld_version.argtypes = []
 lib.weld_version.restype = C.c_char_p
+
+
+class Nested(C.Structure):
+    _fields_ = [("n_outer", C.c_int64), ("outer", Cols), ("start_col", C.c_int32), ("end_col", C.c_int32),
+                ("n_inner", C.c_int64), ("inner", Cols), ("ngather", C.c_int32), ("gather", C.POINTER(Col)),
+                ("gather_len", C.POINTER(C.c_int64)), ("inner_body", Body), ("inner_type", C.c_int32),
+                ("inner_func", C.c_int32), ("outer_body", Body)]
+
+
+lib.weld_nested_for.argtypes = [C.POINTER(Nested), C.POINTER(Builder), C.POINTER(C.c_void_p)]
+lib.weld_nested_for.restype = C.c_int
+lib.weld_nested_validate.argtypes = [C.POINTER(Nested), C.POINTER(Builder), C.c_char_p, C.c_size_t]
+lib.weld_nested_validate.restype = C.c_int
+lib.weld_nested_precompile.argtypes = [C.POINTER(Nested), C.POINTER(Builder)]
+lib.weld_nested_precompile.restype = C.c_int
 
 
 class WeldError(RuntimeError):
@@ -362,6 +378,81 @@ def fused_for(program, columns, mode="fused", stream=None, memory_limit=0, tune=
     if st != OK:
         raise WeldError(st, lib.weld_last_error().decode())
     return Result(out, program, (m, cols, list(columns), inits))
+
+
+def _col_array(tensors, types, what):
+    cols = (Col * max(len(types), 1))()
+    rows = None
+    for k, ty in enumerate(types):
+        cols[k].type = TYPE_ID[ty]
+        if tensors is None:
+            continue
+        t = tensors[k]
+        if not t.is_cuda or not t.is_contiguous():
+            raise WeldError(ERR_INVALID_ARG, "%s vectors must be contiguous CUDA tensors" % what)
+        if TORCH_TYPE.get(t.dtype) != ty:
+            raise WeldError(ERR_TYPE, "%s vector %d: tensor dtype %s, declared %s" % (what, k, t.dtype, ty))
+        cols[k].data = t.data_ptr()
+        rows = t.numel() if rows is None else rows
+    return cols, rows
+
+
+class MarshalledNested:
+    """C structs of a nested loop (workloads.ir.NestedProgram); tensors may be None (validation,
+    ahead-of-time compilation)."""
+
+    def __init__(self, nested, outer=None, inner=None, gather=None, stream=0, memory_limit=0, tune=None):
+        self.mi = Marshalled(nested.inner)
+        self.mo = Marshalled(nested.outer, stream=stream, memory_limit=memory_limit, tune=tune)
+        self.ocols, n_outer = _col_array(outer, nested.outer.columns, "outer")
+        self.icols, n_inner = _col_array(inner, nested.inner.columns, "inner")
+        self.gcols, _ = _col_array(gather, nested.gather, "gather")
+        if outer is not None and any(t.numel() != n_outer for t in outer):
+            raise WeldError(ERR_INVALID_ARG, "outer vectors differ in length")
+        if inner is not None and any(t.numel() != n_inner for t in inner):
+            raise WeldError(ERR_INVALID_ARG, "inner vectors differ in length")
+        ng = len(nested.gather)
+        self.glen = (C.c_int64 * max(ng, 1))(*([t.numel() for t in gather] if gather is not None else [0] * ng))
+        self.keep = (outer, inner, gather)
+        s = self.struct = Nested()
+        s.n_outer = n_outer or 0
+        s.outer = Cols(len(nested.outer.columns), self.ocols)
+        s.start_col, s.end_col = nested.start_col, nested.end_col
+        s.n_inner = n_inner or 0
+        s.inner = Cols(len(nested.inner.columns), self.icols)
+        s.ngather = ng
+        s.gather = self.gcols
+        s.gather_len = self.glen
+        s.inner_body = self.mi.body
+        s.inner_type = TYPE_ID[nested.inner_type]
+        s.inner_func = FUNC[nested.inner_func]
+        s.outer_body = self.mo.body
+
+
+def nested_for(nested, outer, inner, gather, stream=None, memory_limit=0, tune=None):
+    """weld_nested_for over torch CUDA tensors; returns a Result for the outer builders."""
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    m = MarshalledNested(nested, outer, inner, gather, stream=stream, memory_limit=memory_limit, tune=tune)
+    out = C.c_void_p()
+    st = lib.weld_nested_for(C.byref(m.struct), C.byref(m.mo.builder), C.byref(out))
+    if st != OK:
+        raise WeldError(st, lib.weld_last_error().decode())
+    return Result(out, nested.outer, m)
+
+
+def nested_validate(nested):
+    m = MarshalledNested(nested)
+    buf = C.create_string_buffer(512)
+    st = lib.weld_nested_validate(C.byref(m.struct), C.byref(m.mo.builder), buf, 512)
+    return st, buf.value.decode()
+
+
+def nested_precompile(nested, tune=None):
+    m = MarshalledNested(nested, tune=tune)
+    st = lib.weld_nested_precompile(C.byref(m.struct), C.byref(m.mo.builder))
+    if st != OK:
+        raise WeldError(st, lib.weld_last_error().decode())
 
 
 def validate(program, mode="fused"):

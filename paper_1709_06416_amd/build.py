@@ -17,7 +17,7 @@ INCLUDE = os.path.join(ROOT, "include")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libweldhip.so")
 
-HOST_SOURCES = ["validate.cpp", "codegen.cpp", "jit.cpp", "pool.cpp", "runtime.cpp", "unfused.cpp", "lazy.cpp"]
+HOST_SOURCES = ["validate.cpp", "codegen.cpp", "jit.cpp", "pool.cpp", "runtime.cpp", "unfused.cpp", "lazy.cpp", "nested.cpp"]
 HIP_SOURCES = ["aot_kernels.hip", "spill_kernels.hip"]
 ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 HIPCC = os.path.join(ROCM, "bin", "hipcc")

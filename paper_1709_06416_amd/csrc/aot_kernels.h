@@ -57,6 +57,18 @@ struct SpillMerge {
 };
 hipError_t launch_dict_spill_merge(const SpillMerge& a, int nvals, hipStream_t stream);
 
+// Nested loops.  is64: the start / end vectors hold 64-bit (else 32-bit) integers.
+// segments_check raises bit 8 of *err unless start[0] == 0, start[i] <= end[i],
+// end[i] == start[i+1] and end[n_outer-1] == n_inner.  tile_rows writes, for every tile t of
+// `tile` inner elements, the last outer element whose range starts at or before the tile's
+// first inner element (tile_row[ntiles] = n_outer - 1).  or_error ORs the error word of an
+// earlier step's control block into a later one's.
+hipError_t launch_segments_check(const void* start, const void* end, int is64, int64_t n_outer, int64_t n_inner,
+                                 void* err, hipStream_t stream);
+hipError_t launch_tile_rows(const void* start, int is64, int64_t n_outer, int64_t tile, int64_t ntiles,
+                            void* tile_row, hipStream_t stream);
+hipError_t launch_or_error(void* dst_ctl, const void* src_ctl, hipStream_t stream);
+
 hipError_t launch_probe_read(const void* data, int64_t bytes, void* checksum, int blocks, hipStream_t stream);
 hipError_t launch_probe_copy(void* dst, const void* src, int64_t bytes, int blocks, hipStream_t stream);
 

@@ -138,6 +138,69 @@ hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots,
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- nested loops
+template <class T>
+__global__ void __launch_bounds__(256) segments_check_kernel(const T* start, const T* end, i64 n_outer, i64 n_inner, int* err) {
+    bool bad = false;
+    for (i64 i = (i64)blockIdx.x * 256 + threadIdx.x; i < n_outer; i += (i64)gridDim.x * 256) {
+        const i64 s = (i64)start[i], e = (i64)end[i];
+        if (s < 0 || e < s || e > n_inner) bad = true;
+        if (i == 0 && s != 0) bad = true;
+        if (i == n_outer - 1 && e != n_inner) bad = true;
+        if (i + 1 < n_outer && e != (i64)start[i + 1]) bad = true;
+    }
+    if (bad) atomicOr(err, 8);
+}
+
+hipError_t launch_segments_check(const void* start, const void* end, int is64, int64_t n_outer, int64_t n_inner,
+                                 void* err, hipStream_t stream) {
+    if (n_outer <= 0) return hipSuccess;
+    int64_t blocks = (n_outer + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    if (is64)
+        segments_check_kernel<i64><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>((const i64*)start, (const i64*)end, n_outer, n_inner, (int*)err);
+    else
+        segments_check_kernel<int><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>((const int*)start, (const int*)end, n_outer, n_inner, (int*)err);
+    return hipGetLastError();
+}
+
+template <class T>
+__global__ void __launch_bounds__(256) tile_rows_kernel(const T* start, i64 n_outer, i64 tile, i64 ntiles, int* tile_row) {
+    const i64 t = (i64)blockIdx.x * 256 + threadIdx.x;
+    if (t > ntiles) return;
+    if (t == ntiles) {
+        tile_row[t] = (int)(n_outer - 1);
+        return;
+    }
+    const i64 e0 = t * tile;
+    i64 lo = 0, hi = n_outer;              // start[lo] <= e0 (start[0] == 0), "start[n_outer]" > e0
+    while (hi - lo > 1) {
+        const i64 mid = (lo + hi) >> 1;
+        if ((i64)start[mid] <= e0) lo = mid; else hi = mid;
+    }
+    tile_row[t] = (int)lo;
+}
+
+hipError_t launch_tile_rows(const void* start, int is64, int64_t n_outer, int64_t tile, int64_t ntiles,
+                            void* tile_row, hipStream_t stream) {
+    if (n_outer <= 0) return hipSuccess;
+    const int64_t blocks = (ntiles + 1 + 255) / 256;
+    if (is64)
+        tile_rows_kernel<i64><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>((const i64*)start, n_outer, tile, ntiles, (int*)tile_row);
+    else
+        tile_rows_kernel<int><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>((const int*)start, n_outer, tile, ntiles, (int*)tile_row);
+    return hipGetLastError();
+}
+
+__global__ void or_error_kernel(u32* dst_ctl, const u32* src_ctl) {
+    if (threadIdx.x == 0 && src_ctl[2]) atomicOr(dst_ctl + 2, src_ctl[2]);
+}
+
+hipError_t launch_or_error(void* dst_ctl, const void* src_ctl, hipStream_t stream) {
+    or_error_kernel<<<dim3(1), dim3(64), 0, stream>>>((u32*)dst_ctl, (const u32*)src_ctl);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- probes
 // Pure streaming read with 16-byte loads: the attainable HBM read rate on this machine.
 __global__ void __launch_bounds__(256) probe_read_kernel(const u32x4* p, i64 n16, u64* checksum) {

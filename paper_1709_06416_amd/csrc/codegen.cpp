@@ -97,7 +97,10 @@ std::string wrap_bin(int t, const char* op, int a, int b) {
     return buf;
 }
 
-void emit_row_function(Out& o, const Loop& L) {
+// `segmented`: the row function of a nested loop's inner body, which also gets the outer
+// element it belongs to (`row`), the kernel arguments (gather and outer vectors) and the
+// error word.
+void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
     // ---- RowOut
     o.f("struct RowOut {\n");
     for (size_t b = 0; b < L.builders.size(); ++b) {
@@ -122,6 +125,7 @@ void emit_row_function(Out& o, const Loop& L) {
     o.f("}\n\n");
     // ---- the body, one statement per IR operator
     o.f("__device__ __forceinline__ void weld_row(const i64 i");
+    if (segmented) o.f(", const i64 row, const KArgs& a, int* errp");
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c]) o.f(", const %s x%d", stype(L.col_type[c]), c);
     o.f(", RowOut& o) {\n");
@@ -181,6 +185,8 @@ void emit_row_function(Out& o, const Loop& L) {
             case WELD_OP_AND: o.f("(bool)((int)t%d & (int)t%d)", q.a, q.b); break;
             case WELD_OP_OR: o.f("(bool)((int)t%d | (int)t%d)", q.a, q.b); break;
             case WELD_OP_SELECT: o.f("t%d ? t%d : t%d", q.a, q.b, q.c); break;
+            case WELD_OP_LOOKUP: o.f("w_lookup(a.g%d, a.g%d_len, (i64)t%d, errp)", q.a, q.a, q.b); break;
+            case WELD_OP_OUTER: o.f("a.o%d[row]", q.a); break;
         }
         o.f(";\n");
     }
@@ -758,6 +764,152 @@ Generated generate(const Loop& L, const Variant& var) {
     G.kernel_name = name;
     G.source = o.s;
     G.lds_bytes = lds;
+    return G;
+}
+
+// ---------------------------------------------------------------------------------------
+// Flattened inner loop of a nested `for` (un-nesting, Sec. 5 "Partial GPU Backend").
+//
+// The inner loops of all outer elements become ONE loop over the inner elements, tiled like
+// every other loop here, so the work is balanced by inner elements whatever the lengths of the
+// ranges.  The merger of the inner loop becomes a segmented merger with one cell per outer
+// element: a tile stages the range boundaries that fall into it in LDS (relative to the tile
+// start), every lane finds the outer element of its first inner element by binary search and
+// walks from there, runs of equal outer element are combined in registers, each run ends in
+// one LDS atomic on that outer element's cell, and at the end of the tile the cells go to
+// memory: outer elements that lie entirely inside the tile with a plain store, the (at most
+// two) that continue in a neighbouring tile with a device atomic.  The first outer element of
+// every tile comes from a small kernel run before this one.
+Variant choose_segmented_variant(const Loop& L, bool aligned) {
+    Variant var;
+    int widest = 4;
+    for (int c = 0; c < L.ncols; ++c)
+        if (L.col_used[c] && type_size(L.col_type[c]) > widest) widest = type_size(L.col_type[c]);
+    var.v = widest >= 8 ? 2 : 4;
+    var.u = 4;
+    var.block = 256;
+    var.aligned = aligned ? 1 : 0;
+    var.backend.assign(1, BK_MERGER);
+    return var;
+}
+
+Generated generate_segmented(const Loop& L, const Variant& var, int offset_type) {
+    Generated G;
+    Out o;
+    const weld_builder_spec_t& s = L.builders[0];
+    const char* A = acc_ctype(s.val_type[0]);
+    const std::string ID = ident_expr(s.func, s.val_type[0]);
+    const int F = s.func;
+    o.f("// generated: flattened inner loop of a nested for, %d inner columns\n", L.ncols);
+    o.f("#define W_BLOCK %d\n#define W_V %d\n#define W_U %d\n#define W_ALIGNED %d\n#define W_SEG_CAP 2048\n", var.block, var.v, var.u, var.aligned);
+    o.s += kPreludeSource;
+    o.f("\n");
+    auto slot = [&](SlotKind k, int idx, const std::string& name, const std::string& ct) {
+        Slot sl{k, idx, 0, name, ct};
+        G.slots.push_back(sl);
+    };
+    slot(SLOT_N, -1, "n", "i64");
+    slot(SLOT_N_OUTER, -1, "n_outer", "i64");
+    for (int c = 0; c < L.ncols; ++c)
+        if (L.col_used[c]) slot(SLOT_COL, c, "c" + std::to_string(c), std::string("const ") + stype(L.col_type[c]) + "* __restrict__");
+    for (int g = 0; g < L.ngather; ++g)
+        if (L.gather_used[g]) {
+            slot(SLOT_GATHER, g, "g" + std::to_string(g), std::string("const ") + stype(L.gather_type[g]) + "* __restrict__");
+            slot(SLOT_GATHER_LEN, g, "g" + std::to_string(g) + "_len", "i64");
+        }
+    for (int c = 0; c < L.nouter; ++c)
+        if (L.outer_used[c]) slot(SLOT_OUTER_COL, c, "o" + std::to_string(c), std::string("const ") + stype(L.outer_type[c]) + "* __restrict__");
+    slot(SLOT_SEG_START, -1, "seg_start", std::string("const ") + ctype(offset_type) + "* __restrict__");
+    slot(SLOT_TILE_ROW, -1, "tile_row", "const int* __restrict__");
+    slot(SLOT_SUMS, -1, "sums", std::string(A) + "*");
+    slot(SLOT_CTL, -1, "ctl", "u32*");
+    o.f("struct KArgs {\n");
+    for (const Slot& sl : G.slots) o.f("  %s %s;\n", sl.ctype.c_str(), sl.name.c_str());
+    o.f("};\n\n");
+    emit_row_function(o, L, true);
+
+    std::string call_args;      // the column values of element (u, k)
+    for (int c = 0; c < L.ncols; ++c)
+        if (L.col_used[c]) call_args += ", x" + std::to_string(c) + "[u].e[k]";
+
+    o.f("extern \"C\" __global__ void __launch_bounds__(W_BLOCK) weld_kernel(const KArgs a) {\n");
+    o.f("  __shared__ int s_b[W_SEG_CAP + 2];\n  __shared__ %s s_acc[W_SEG_CAP + 1];\n", A);
+    o.f("  int* const errp = (int*)(a.ctl + 2);\n");
+    o.f("  const int lane = threadIdx.x & 63;\n  const int wave = threadIdx.x >> 6;\n");
+    o.f("  const i64 ntiles = (a.n + W_TILE - 1) / W_TILE;\n");
+    o.f("  for (i64 t = blockIdx.x; t < ntiles; t += gridDim.x) {\n");
+    o.f("    const i64 e0 = t * W_TILE;\n    const i64 e1 = e0 + W_TILE < a.n ? e0 + W_TILE : a.n;\n");
+    o.f("    const i64 r0 = a.tile_row[t], r1 = a.tile_row[t + 1];\n");
+    o.f("    const i64 nrows = r1 - r0 + 1;\n");
+    o.f("    if (nrows < 1) continue;                 // only with boundaries that are not sorted (reported elsewhere)\n");
+    o.f("    const bool staged = nrows <= W_SEG_CAP;\n");
+    // boundary of outer element r: its start; one past the last outer element: n
+    o.f("    if (staged) {\n");
+    o.f("      for (int k = threadIdx.x; k <= (int)nrows; k += W_BLOCK) {\n");
+    o.f("        const i64 r = r0 + k;\n        const i64 bnd = r < a.n_outer ? (i64)a.seg_start[r] : a.n;\n");
+    o.f("        i64 rel = bnd - e0;\n        rel = rel < -1 ? -1 : (rel > W_TILE + 1 ? W_TILE + 1 : rel);\n");
+    o.f("        s_b[k] = (int)rel;\n        if (k < (int)nrows) s_acc[k] = %s;\n      }\n", ID.c_str());
+    o.f("      __syncthreads();\n    }\n");
+    o.f("    const i64 base = e0 + (i64)wave * W_WAVE_ROWS + lane * W_V;\n");
+    // ---- loads
+    for (int c = 0; c < L.ncols; ++c)
+        if (L.col_used[c]) o.f("    wvec<%s, W_V> x%d[W_U];\n", stype(L.col_type[c]), c);
+    o.f("    if (e0 + W_TILE <= a.n) {\n      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+    for (int c = 0; c < L.ncols; ++c)
+        if (L.col_used[c]) o.f("        x%d[u] = w_load<%s, W_V>(a.c%d + base + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
+    o.f("      }\n    } else {\n      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
+    o.f("          const i64 e = base + u * W_UNIT + k;\n");
+    for (int c = 0; c < L.ncols; ++c)
+        if (L.col_used[c]) o.f("          x%d[u].e[k] = e < a.n ? a.c%d[e] : (%s)0;\n", c, c, stype(L.col_type[c]));
+    o.f("        }\n    }\n");
+    // ---- outer element of every inner element of this lane (relative to r0)
+    o.f("    int rowid[W_U][W_V];\n");
+    o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+    o.f("      const i64 e = base + u * W_UNIT;\n      int rl = 0;\n");
+    o.f("      if (e < e1) {\n");
+    o.f("        if (staged) {\n          const int rel = (int)(e - e0);\n          int lo = 0, hi = (int)nrows;       // s_b[lo] <= rel < s_b[hi]\n");
+    o.f("          while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (s_b[mid] <= rel) lo = mid; else hi = mid; }\n          rl = lo;\n");
+    o.f("        } else {\n          i64 lo = r0, hi = r1 + 1;\n");
+    o.f("          while (hi - lo > 1) { const i64 mid = (lo + hi) >> 1; if ((i64)a.seg_start[mid] <= e) lo = mid; else hi = mid; }\n          rl = (int)(lo - r0);\n        }\n");
+    o.f("      }\n");
+    o.f("      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
+    o.f("        if (e + k < e1) {\n");
+    o.f("          if (staged) { const int rel = (int)(e + k - e0); while (rl < (int)nrows - 1 && rel >= s_b[rl + 1]) ++rl; }\n");
+    o.f("          else { while (rl < (int)nrows - 1 && e + k >= (i64)a.seg_start[r0 + rl + 1]) ++rl; }\n");
+    o.f("        }\n        rowid[u][k] = rl;\n      }\n    }\n");
+    // ---- values (all gathers of the lane are independent of each other: issued together)
+    o.f("    RowOut o[W_U][W_V];\n");
+    o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
+    o.f("        const i64 e = base + u * W_UNIT + k;\n");
+    o.f("        if (e < e1) weld_row(e, r0 + rowid[u][k], a, errp%s, o[u][k]); else weld_row_none(o[u][k]);\n      }\n", call_args.c_str());
+    // ---- segmented combine: runs of equal outer element in registers, one atomic per run
+    o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+    o.f("      %s acc = %s;\n      bool any = false;\n      int cur = rowid[u][0];\n", A, ID.c_str());
+    o.f("      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
+    o.f("        if (rowid[u][k] != cur) {\n");
+    o.f("          if (any) { if (staged) w_atomic<%d>(s_acc + cur, acc, 0); else w_atomic<%d>(a.sums + r0 + cur, acc, 1); }\n", F, F);
+    o.f("          acc = %s; any = false; cur = rowid[u][k];\n        }\n", ID.c_str());
+    o.f("        if (o[u][k].p0) { acc = w_combine<%d>(acc, (%s)o[u][k].v0_0); any = true; }\n      }\n", F, A);
+    o.f("      if (any) { if (staged) w_atomic<%d>(s_acc + cur, acc, 0); else w_atomic<%d>(a.sums + r0 + cur, acc, 1); }\n    }\n", F, F);
+    // ---- cells to memory
+    o.f("    if (staged) {\n      __syncthreads();\n");
+    o.f("      for (int k = threadIdx.x; k < (int)nrows; k += W_BLOCK) {\n");
+    o.f("        const %s x = s_acc[k];\n        const %s id = %s;\n        u64 xb, ib;\n", A, A, ID.c_str());
+    o.f("        __builtin_memcpy(&xb, &x, 8);\n        __builtin_memcpy(&ib, &id, 8);\n        if (xb == ib) continue;\n");
+    o.f("        const bool inside = s_b[k] >= 0 && s_b[k + 1] <= (int)(e1 - e0);\n");
+    o.f("        if (inside) a.sums[r0 + k] = x; else w_atomic<%d>(a.sums + r0 + k, x, 1);\n      }\n", F);
+    o.f("      __syncthreads();\n    }\n");
+    o.f("  }\n}\n");
+    uint64_t hsh = 0xcbf29ce484222325ull;
+    for (unsigned char c : o.s) { hsh ^= c; hsh *= 0x100000001b3ull; }
+    char name[48];
+    snprintf(name, sizeof name, "weld_inner_%016llx", (unsigned long long)hsh);
+    const std::string placeholder = "weld_kernel";
+    const size_t at = o.s.find(placeholder + "(const KArgs a)");
+    if (at != std::string::npos) o.s.replace(at, placeholder.size(), name);
+    G.kernel_name = name;
+    G.source = o.s;
+    G.lds_bytes = 4 * 2050 + 8 * 2049;
     return G;
 }
 

@@ -88,6 +88,16 @@ template <int F, int BITS> __device__ __forceinline__ i64 w_identity_int() {
     return (i64)(~0ull << (BITS - 1));
 }
 
+// ---------------------------------------------------------------- lookup
+// lookup(v, ix) of a nested loop's inner body: an index outside the vector raises error
+// bit 4 (the call then fails) and yields 0 instead of reading out of bounds.
+template <class T>
+__device__ __forceinline__ T w_lookup(const T* __restrict__ v, i64 len, i64 ix, int* err) {
+    if ((u64)ix < (u64)len) return v[ix];
+    atomicOr(err, 4);
+    return (T)0;
+}
+
 // ---------------------------------------------------------------- wavefront level
 __device__ __forceinline__ int w_lane() {
     return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));

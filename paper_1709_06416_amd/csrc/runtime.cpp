@@ -116,7 +116,8 @@ struct Layout {
 
 namespace weld {
 
-Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t& conf, weld_result* r) {
+Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t& conf, weld_result* r,
+                const void* prior_ctl) {
     hipStream_t stream = (hipStream_t)conf.stream;
     bool aligned = true;
     for (int c = 0; c < L.ncols; ++c)
@@ -126,7 +127,7 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
     Kernel* kern = nullptr;
     Error e = jit_get(G.source, G.kernel_name, true, &kern);
     if (!e.ok()) return e;
-    r->kernel_name = G.kernel_name;
+    if (!prior_ctl) r->kernel_name = G.kernel_name;
 
     const size_t NB = L.builders.size();
     const int64_t tile = (int64_t)var.block * var.v * var.u;
@@ -265,7 +266,7 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
 
     // ---- enqueue
     hipError_t h;
-    if ((h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    if (!prior_ctl && (h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     if ((h = launch_fill64(base + off_ctl, kCtlBytes / 8, 0, stream)) != hipSuccess) return hip_err("fill", h);
     r->kernel_count++;
     for (size_t b = 0; b < NB; ++b) {
@@ -290,7 +291,7 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
             }
         }
     }
-    if ((h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    if (!prior_ctl && (h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream);
     if (!e.ok()) return e;
     r->kernel_count++;
@@ -318,7 +319,7 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
         if ((h = launch_dict_spill_merge(sm, s.nvals, stream)) != hipSuccess) return hip_err("dict spill merge", h);
         r->kernel_count++;
     }
-    if ((h = hipEventRecord(r->ev3, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    if (!prior_ctl && (h = hipEventRecord(r->ev3, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     MergerFinish mf;
     memset(&mf, 0, sizeof mf);
     for (size_t b = 0; b < NB; ++b) {
@@ -363,10 +364,101 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
         if (h != hipSuccess) return hip_err("dict extract", h);
         r->kernel_count++;
     }
+    if (prior_ctl) {
+        if ((h = launch_or_error(base + off_ctl, prior_ctl, stream)) != hipSuccess) return hip_err("error word", h);
+        r->kernel_count++;
+    }
     if ((h = hipEventRecord(r->ev1, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     if ((h = hipMemcpyAsync(r->host_ctl, base + off_ctl, kCtlBytes, hipMemcpyDeviceToHost, stream)) != hipSuccess)
         return hip_err("hipMemcpyAsync", h);
     return Error();
+}
+
+// ---------------------------------------------------------------------------------------
+// Nested loop = flattened inner loop (segmented merger, one cell per outer element) followed
+// by the ordinary fused loop over the outer elements with the cells as one more column.
+Error run_nested(const NestedLoop& NL, const NestedData& D, const weld_conf_t& conf, weld_result* r) {
+    hipStream_t stream = (hipStream_t)conf.stream;
+    const Loop& L = NL.inner;
+    bool aligned = true;
+    for (int c = 0; c < L.ncols; ++c)
+        if (L.col_used[c] && ((uintptr_t)D.inner[c].data & 15)) aligned = false;
+    Variant var = choose_segmented_variant(L, aligned);
+    Generated G = generate_segmented(L, var, NL.offset_type);
+    Kernel* kern = nullptr;
+    Error e = jit_get(G.source, G.kernel_name, true, &kern);
+    if (!e.ok()) return e;
+    r->kernel_name = G.kernel_name;
+
+    const int64_t tile = (int64_t)var.block * var.v * var.u;
+    const int64_t ntiles = (D.n_inner + tile - 1) / tile;
+    int per_cu = jit_blocks_per_cu(kern, var.block);
+    if (per_cu <= 0 || per_cu > 8) per_cu = 8;
+    int64_t grid = conf.tune.grid_blocks > 0 ? conf.tune.grid_blocks : (int64_t)device_info().cus * per_cu;
+    if (grid > ntiles) grid = ntiles;
+    if (grid < 1) grid = 1;
+
+    Layout lay;
+    const size_t off_ctl = lay.take(kCtlBytes);
+    const size_t off_tiles = lay.take(4 * (size_t)(ntiles + 1));
+    const size_t off_sums = lay.take(8 * (size_t)(D.n_outer > 0 ? D.n_outer : 1));
+    if (conf.memory_limit > 0 && (int64_t)lay.total > conf.memory_limit)
+        return mk(WELD_ERR_OOM, "the inner loop needs " + std::to_string(lay.total) + " bytes of device memory, limit is " +
+                                    std::to_string(conf.memory_limit));
+    void* block = nullptr;
+    e = pool_alloc(lay.total, &block);
+    if (!e.ok()) return e;
+    r->blocks.push_back(block);
+    char* base = (char*)block;
+    const weld_builder_spec_t& ms = L.builders[0];
+
+    std::vector<uint64_t> args;
+    for (const Slot& s : G.slots) {
+        uint64_t v = 0;
+        switch (s.kind) {
+            case SLOT_N: v = (uint64_t)D.n_inner; break;
+            case SLOT_N_OUTER: v = (uint64_t)D.n_outer; break;
+            case SLOT_COL: v = (uint64_t)(uintptr_t)D.inner[s.builder].data; break;
+            case SLOT_GATHER: v = (uint64_t)(uintptr_t)D.gather[s.builder].data; break;
+            case SLOT_GATHER_LEN: v = (uint64_t)D.gather_len[s.builder]; break;
+            case SLOT_OUTER_COL: v = (uint64_t)(uintptr_t)D.outer[s.builder].data; break;
+            case SLOT_SEG_START: v = (uint64_t)(uintptr_t)D.outer[NL.start_col].data; break;
+            case SLOT_TILE_ROW: v = (uint64_t)(uintptr_t)(base + off_tiles); break;
+            case SLOT_SUMS: v = (uint64_t)(uintptr_t)(base + off_sums); break;
+            case SLOT_CTL: v = (uint64_t)(uintptr_t)(base + off_ctl); break;
+            default: break;
+        }
+        args.push_back(v);
+    }
+    hipError_t h;
+    const int is64 = NL.offset_type == WELD_I64;
+    if ((h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    if ((h = launch_fill64(base + off_ctl, kCtlBytes / 8, 0, stream)) != hipSuccess) return hip_err("fill", h);
+    if ((h = launch_fill64(base + off_sums, D.n_outer, ident_bits(ms.func, ms.val_type[0]), stream)) != hipSuccess) return hip_err("fill", h);
+    if ((h = launch_segments_check(D.outer[NL.start_col].data, D.outer[NL.end_col].data, is64, D.n_outer, D.n_inner,
+                                   base + off_ctl + 8, stream)) != hipSuccess) return hip_err("segments check", h);
+    if ((h = launch_tile_rows(D.outer[NL.start_col].data, is64, D.n_outer, tile, ntiles, base + off_tiles, stream)) != hipSuccess)
+        return hip_err("tile rows", h);
+    r->kernel_count += 4;
+    if ((h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    if (ntiles > 0 && D.n_outer > 0) {
+        e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream);
+        if (!e.ok()) return e;
+        r->kernel_count++;
+    }
+    if ((h = hipEventRecord(r->ev3, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+
+    // the outer loop: the cells are its last column
+    ColRef cols[WELD_MAX_COLS];
+    for (int c = 0; c + 1 < NL.outer.ncols; ++c) cols[c] = D.outer[c];
+    cols[NL.outer.ncols - 1].data = base + off_sums;
+    cols[NL.outer.ncols - 1].type = ms.val_type[0];
+    weld_conf_t conf2 = conf;
+    if (conf.memory_limit > 0) {
+        conf2.memory_limit = conf.memory_limit - (int64_t)lay.total;
+        if (conf2.memory_limit <= 0) return mk(WELD_ERR_OOM, "no device memory left for the outer loop under the limit");
+    }
+    return run_fused(NL.outer, cols, D.n_outer, conf2, r, base + off_ctl);
 }
 
 void destroy_result(weld_result* r) {
@@ -450,9 +542,12 @@ weld_status_t weld_result_status(weld_result_t* r) {
     if (hipEventQuery(r->ev3) == hipSuccess) (void)hipEventElapsedTime(&r->kernel_ms, r->ev2, r->ev3);
     (void)hipGetLastError();
     const uint32_t err = r->host_ctl[2];
-    if (err & 4) {
+    if (err & 8) {
         r->status = WELD_ERR_INVALID_ARG;
-        r->error = "a vecmerger index was outside 0..length-1";
+        r->error = "the inner ranges of the nested loop are not consecutive (start[0] == 0, end[i] == start[i+1], end[last] == n_inner)";
+    } else if (err & 4) {
+        r->status = WELD_ERR_INVALID_ARG;
+        r->error = "a vecmerger index or a lookup position was outside its vector";
     } else if (err & 2) {
         r->status = WELD_ERR_DEVICE;
         r->error = "a tile gave up waiting for the prefix of its predecessors (spin limit reached)";

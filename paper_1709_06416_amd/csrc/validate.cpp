@@ -29,13 +29,19 @@ int key_bits(const weld_builder_spec_t& b) {
 }
 
 Error validate(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
-               const weld_builder_t* builder, Loop* out) {
+               const weld_builder_t* builder, Loop* out, const NestedContext* inner_of) {
     if (!body || !builder || !out) return fail(WELD_ERR_INVALID_ARG, "null argument");
     if (ncols < 0 || ncols > WELD_MAX_COLS) return fail(WELD_ERR_INVALID_ARG, "ncols %d out of range", ncols);
     if (ncols > 0 && !col_types) return fail(WELD_ERR_INVALID_ARG, "null column types");
     Loop& L = *out;
     L = Loop();
     L.ncols = ncols;
+    if (inner_of) {
+        L.ngather = inner_of->ngather;
+        L.nouter = inner_of->nouter;
+        for (int k = 0; k < L.ngather; ++k) L.gather_type[k] = inner_of->gather_type[k];
+        for (int k = 0; k < L.nouter; ++k) L.outer_type[k] = inner_of->outer_type[k];
+    }
     for (int k = 0; k < ncols; ++k) {
         if (!type_is_num(col_types[k])) return fail(WELD_ERR_TYPE, "column %d: type %d is not i8/i32/i64/f64", k, col_types[k]);
         L.col_type[k] = col_types[k];
@@ -115,6 +121,22 @@ Error validate(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
                 if (ty(o.a) != WELD_BOOL || ty(o.b) != o.type || ty(o.c) != o.type)
                     return fail(WELD_ERR_TYPE, "op %d: select(bool, T, T) -> T", i);
                 break;
+            case WELD_OP_LOOKUP:
+                if (!inner_of) return fail(WELD_ERR_UNSUPPORTED, "op %d: lookup is only implemented in the inner body of weld_nested_for", i);
+                if (o.a < 0 || o.a >= L.ngather) return fail(WELD_ERR_INVALID_ARG, "op %d: gather vector %d not declared", i, o.a);
+                if (!operand(o.b)) return fail(WELD_ERR_INVALID_ARG, "op %d: operand %d is not an earlier op", i, o.b);
+                if (!type_is_int(ty(o.b))) return fail(WELD_ERR_TYPE, "op %d: lookup index must be an integer", i);
+                if (o.type != L.gather_type[o.a]) return fail(WELD_ERR_TYPE, "op %d: gather vector %d has type %d", i, o.a, L.gather_type[o.a]);
+                L.gather_used[o.a] = true;
+                break;
+            case WELD_OP_OUTER:
+                if (!inner_of) return fail(WELD_ERR_INVALID_ARG, "op %d: outer-element access outside an inner body", i);
+                if (o.a < 0 || o.a >= L.nouter) return fail(WELD_ERR_INVALID_ARG, "op %d: outer column %d not declared", i, o.a);
+                if (o.type != L.outer_type[o.a]) return fail(WELD_ERR_TYPE, "op %d: outer column %d has type %d", i, o.a, L.outer_type[o.a]);
+                L.outer_used[o.a] = true;
+                break;
+            case WELD_OP_INNER:
+                return fail(WELD_ERR_INVALID_ARG, "op %d: inner-loop result outside the outer body of weld_nested_for", i);
             default:
                 return fail(WELD_ERR_INVALID_ARG, "op %d: unknown opcode %d", i, o.opcode);
         }

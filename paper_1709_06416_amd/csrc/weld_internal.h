@@ -6,6 +6,7 @@
 #include <vector>
 
 #include "weld_hip.h"
+#include "weld_nested.h"
 
 #include <hip/hip_runtime_api.h>
 
@@ -60,6 +61,22 @@ struct Loop {
     std::vector<weld_builder_spec_t> builders;
     std::vector<int> merge_of;           // per builder: index into merges, or -1
     std::vector<weld_merge_t> merges;
+    // inner loop of a nested `for` only: vectors WELD_OP_LOOKUP may read, and the outer
+    // vectors WELD_OP_OUTER reads at the current outer element
+    int ngather = 0;
+    int gather_type[8] = {0};
+    bool gather_used[8] = {false};
+    int nouter = 0;
+    int outer_type[WELD_MAX_COLS] = {0};
+    bool outer_used[WELD_MAX_COLS] = {false};
+};
+
+// What the body of an inner loop may refer to besides its own zipped vectors.
+struct NestedContext {
+    int ngather = 0;
+    int gather_type[8] = {0};
+    int nouter = 0;
+    int outer_type[WELD_MAX_COLS] = {0};
 };
 
 struct Error {
@@ -72,7 +89,7 @@ void set_last_error(const std::string& s);
 
 // validate.cpp
 Error validate(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
-               const weld_builder_t* builder, Loop* out);
+               const weld_builder_t* builder, Loop* out, const NestedContext* inner_of = nullptr);
 
 // How each builder is realised inside the fused kernel.
 enum Backend {
@@ -111,7 +128,9 @@ enum SlotKind {
     SLOT_PARTIAL,                       // merger
     SLOT_OUT, SLOT_DESC, SLOT_LEN,      // vecbuilder
     SLOT_DKEYS, SLOT_DHDR, SLOT_DSLOTS, SLOT_DVAL,  // dictmerger
-    SLOT_DLOG, SLOT_DQCNT, SLOT_DQCAP               // dictmerger spill queues
+    SLOT_DLOG, SLOT_DQCNT, SLOT_DQCAP,              // dictmerger spill queues
+    // flattened inner loop of a nested for
+    SLOT_N_OUTER, SLOT_GATHER, SLOT_GATHER_LEN, SLOT_OUTER_COL, SLOT_SEG_START, SLOT_TILE_ROW, SLOT_SUMS
 };
 struct Slot {
     SlotKind kind;
@@ -131,6 +150,10 @@ struct Generated {
 // codegen.cpp
 Variant choose_variant(const Loop& loop, const weld_tuning_t& tune, bool aligned);
 Generated generate(const Loop& loop, const Variant& var);
+// The flattened inner loop of a nested for: `loop` is the inner body with one merger;
+// offset_type is the type of the outer start/end vectors.  Uses var.block / v / u / aligned.
+Variant choose_segmented_variant(const Loop& loop, bool aligned);
+Generated generate_segmented(const Loop& loop, const Variant& var, int offset_type);
 int key_bits(const weld_builder_spec_t& b);
 
 // jit.cpp
@@ -153,7 +176,26 @@ struct ColRef {
 };
 
 // runtime.cpp: enqueue one fused loop (validated `loop`) on conf.stream into `r`
-Error run_fused(const Loop& loop, const ColRef* cols, int64_t n, const weld_conf_t& conf, weld_result* r);
+// prior_ctl: control block (device) of work already enqueued for the same result handle (the
+// flattened inner loop of a nested for).  When given, the handle's start and kernel events are
+// left to the caller and that block's error word is folded into this loop's.
+Error run_fused(const Loop& loop, const ColRef* cols, int64_t n, const weld_conf_t& conf, weld_result* r,
+                const void* prior_ctl = nullptr);
+// A validated nested loop: `inner` holds the inner body with its merger as builder 0, `outer`
+// the outer body in which the inner loop's result is column `outer.ncols - 1`.
+struct NestedLoop {
+    Loop inner, outer;
+    int start_col = 0, end_col = 0;
+    int offset_type = WELD_I64;
+};
+struct NestedData {
+    int64_t n_outer = 0, n_inner = 0;
+    ColRef outer[WELD_MAX_COLS];
+    ColRef inner[WELD_MAX_COLS];
+    ColRef gather[8];
+    int64_t gather_len[8] = {0};
+};
+Error run_nested(const NestedLoop& loop, const NestedData& data, const weld_conf_t& conf, weld_result* r);
 weld_result* new_result(void* stream);   // with pinned control words and events; nullptr on failure
 void destroy_result(weld_result* r);
 

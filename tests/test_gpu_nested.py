@@ -1,0 +1,202 @@
+"""GPU parity of weld_nested_for (a `for` nested in a `for`, run by un-nesting) against the
+CPU oracle, through the C ABI.
+
+Tolerances: integer results bit-exact; an f64 result that is a sum over an inner range is
+compared at 1e-9 relative to the correctly rounded sum (the order of the merges is free), on
+data without cancellation; min / max bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+from workloads import graphs
+from workloads.ir import NestedProgram
+
+pytestmark = pytest.mark.gpu
+
+NP = {"i64": np.int64, "f64": np.float64}
+TT = {"i32": torch.int32, "i64": torch.int64, "f64": torch.float64}
+
+
+@pytest.fixture(scope="module")
+def wb():
+    from paper_1709_06416_amd import binding
+    return binding
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _compare(prog, res, want, label):
+    res.check()
+    for b, spec in enumerate(prog.builders):
+        tag = "%s builder %d" % (label, b)
+        if spec["kind"] == "merger":
+            got = res.merger(b)
+            if spec["type"] == "f64" and spec.get("func") in ("add", "mul"):
+                assert abs(float(got) - float(want[b])) <= 1e-9 * abs(float(want[b])), (tag, got, want[b])
+            else:
+                assert got == want[b], (tag, got, want[b])
+        else:
+            got = res.vec_host(b)
+            assert len(got) == len(want[b]), tag
+            if spec["type"] == "f64":
+                bad = np.flatnonzero(~(np.abs(got - want[b]) <= 1e-9 * np.abs(want[b])) & ~(got == want[b]))
+                assert bad.size == 0, (tag, bad[:5], got[bad[:5]], want[b][bad[:5]])
+            else:
+                assert np.array_equal(got, want[b]), tag
+
+
+def _check(wb, prog, outer, inner, gather, label="", **kw):
+    from oracle import interp
+    want = interp.run_nested(prog, outer, inner, gather, sums="exact")
+    res = wb.nested_for(prog, [_dev(c) for c in outer], [_dev(c) for c in inner], [_dev(g) for g in gather], **kw)
+    try:
+        _compare(prog.outer, res, want, label)
+    finally:
+        res.free()
+
+
+def _graph(n, offsets="i64", **kw):
+    rowptr, src, weight, outdeg = [t.numpy() for t in graphs.make_graph(n, offsets=offsets, **kw)]
+    return rowptr, src, weight, outdeg
+
+
+@pytest.mark.parametrize("offsets", ["i64", "i32"])
+@pytest.mark.parametrize("n", [1, 700, 60_001])
+def test_spmv(wb, n, offsets):
+    rowptr, src, weight, _ = _graph(n, offsets)
+    x = np.random.RandomState(n).uniform(0.5, 1.5, size=n)
+    _check(wb, graphs.program_spmv(offsets), [rowptr[:-1].copy(), rowptr[1:].copy()], [src, weight], [x], label="spmv %d" % n)
+
+
+@pytest.mark.parametrize("n", [5, 40_003])
+def test_pagerank_iteration(wb, n):
+    from oracle import interp
+    rowptr, src, _, outdeg = _graph(n)
+    rank = np.full(n, 1.0 / n)
+    contrib = interp.run(graphs.program_contrib(), [rank, outdeg])[0]
+    _check(wb, graphs.program_pagerank(n), [rowptr[:-1].copy(), rowptr[1:].copy()], [src], [contrib], label="pagerank %d" % n)
+
+
+def test_two_pagerank_iterations_through_the_library(wb):
+    """contrib (a fused map loop) and the nested loop, twice, all on the GPU; the oracle does the same."""
+    from oracle import interp
+    n = 30_011
+    rowptr, src, _, outdeg = _graph(n)
+    start, end = _dev(rowptr[:-1].copy()), _dev(rowptr[1:].copy())
+    d_src, d_deg = _dev(src), _dev(outdeg)
+    rank = torch.full((n,), 1.0 / n, dtype=torch.float64, device="cuda")
+    want = np.full(n, 1.0 / n)
+    for _ in range(2):
+        r1 = wb.fused_for(graphs.program_contrib(), [rank, d_deg]).check()
+        contrib = r1.vec(0)
+        r2 = wb.nested_for(graphs.program_pagerank(n), [start, end], [d_src], [contrib]).check()
+        rank = r2.vec(0)
+        r1.free()
+        r2.free()
+        c = interp.run(graphs.program_contrib(), [want, outdeg])[0]
+        want = interp.run_nested(graphs.program_pagerank(n), [rowptr[:-1], rowptr[1:]], [src], [c])[0]
+    got = rank.cpu().numpy()
+    assert np.all(np.abs(got - want) <= 1e-9 * np.abs(want))
+
+
+def _random_nested(rnd, func, t, with_pred, n_outer, n_inner, empty_share=0.3):
+    cuts = np.sort(rnd.randint(0, n_inner + 1, size=max(n_outer - 1, 0)))
+    if empty_share > 0 and cuts.size:                    # runs of empty ranges: repeat the previous cut
+        repeat = rnd.uniform(size=cuts.size) < empty_share
+        cuts = np.maximum.accumulate(np.where(repeat, 0, cuts))
+    if n_outer == 0:
+        start = end = np.zeros(0, dtype=np.int64)
+    else:
+        start = np.concatenate([[0], cuts]).astype(np.int64)
+        end = np.concatenate([cuts, [n_inner]]).astype(np.int64)
+    scale = rnd.randint(-3, 4, size=n_outer).astype(np.int64)
+    idx = rnd.randint(0, 1000, size=n_inner).astype(np.int32)
+    if t == "i64":
+        a = rnd.randint(-4, 5, size=n_inner).astype(np.int64)
+        g = rnd.randint(-5, 6, size=1000).astype(np.int64)
+    else:
+        a = rnd.uniform(0.5, 2.0, size=n_inner)
+        g = rnd.uniform(0.5, 2.0, size=1000)
+    if func == "mul":                                    # products stay exact and finite
+        a = np.where(rnd.uniform(size=n_inner) < 0.5, 1, -1).astype(NP[t])
+        g = np.where(rnd.uniform(size=1000) < 0.5, 1, -1).astype(NP[t])
+    p = NestedProgram(["i64", "i64", "i64"], 0, 1, ["i32", t], [t], t, func)
+    q = p.inner
+    v = q.bin("mul", q.col(1), q.lookup(0, q.col(0)))
+    if t == "i64":
+        v = q.bin("add", v, q.outer(2))                  # the current outer element, inside the inner loop
+    pred = q.bin("ne", q.bin("mod", q.col(0), q.const("i32", 7)), q.const("i32", 3)) if with_pred else None
+    q.merge(0, v, pred=pred)
+    o = p.outer
+    o.merge(o.vecbuilder(t), o.inner())
+    o.merge(o.merger(t, "max" if func == "mul" else func), o.inner(), pred=o.bin("gt", o.col(2), o.const("i64", -2)))
+    o.merge(o.vecbuilder("i64"), o.bin("add", o.index(), o.col(2)), pred=o.bin("lt", o.col(0), o.col(1)))
+    return p, [start, end, scale], [idx, a], [g]
+
+
+@pytest.mark.parametrize("with_pred", [False, True])
+@pytest.mark.parametrize("t", ["i64", "f64"])
+@pytest.mark.parametrize("func", ["add", "mul", "min", "max"])
+def test_functions_predicates_and_outer_access(wb, func, t, with_pred):
+    rnd = np.random.RandomState(17)
+    p, outer, inner, gather = _random_nested(rnd, func, t, with_pred, n_outer=7_001, n_inner=150_003)
+    _check(wb, p, outer, inner, gather, label="%s %s %s" % (func, t, with_pred))
+
+
+@pytest.mark.parametrize("n_outer,n_inner", [(0, 0), (1, 0), (5, 0), (1, 1), (1, 70_000), (3, 9_000), (2_000, 2_047),
+                                             (2_000, 2_048), (2_000, 2_049), (90_000, 30_001), (300_000, 5_000)])
+def test_shapes(wb, n_outer, n_inner):
+    """Empty inputs, one range spanning many tiles, tile-sized inputs with a ragged end, and
+    many more outer than inner elements (more range boundaries in a tile than LDS stages)."""
+    rnd = np.random.RandomState(n_outer + n_inner)
+    p, outer, inner, gather = _random_nested(rnd, "add", "f64", False, n_outer, n_inner, empty_share=0.0)
+    _check(wb, p, outer, inner, gather, label="shape %d %d" % (n_outer, n_inner))
+
+
+def test_one_huge_range_among_small_ones(wb):
+    rowptr, src, weight, _ = _graph(200_000)
+    deg = np.diff(rowptr)
+    assert deg.max() > 3 * 2048                                            # spans several tiles
+    x = np.random.RandomState(1).uniform(0.5, 1.5, size=200_000)
+    _check(wb, graphs.program_spmv(), [rowptr[:-1].copy(), rowptr[1:].copy()], [src, weight], [x], label="huge row")
+
+
+def test_ranges_that_are_not_consecutive_are_rejected(wb):
+    rowptr, src, weight, _ = _graph(5_000)
+    x = np.ones(5_000)
+    start, end = rowptr[:-1].copy(), rowptr[1:].copy()
+    bad_end = end.copy()
+    bad_end[100] -= 1 if bad_end[100] > start[100] else -1                # a gap / an overlap
+    for s, e in ((start, bad_end), (start + 1, end + 1), (start, np.minimum(end, end[-1] - 5))):
+        res = wb.nested_for(graphs.program_spmv(), [_dev(s), _dev(e)], [_dev(src), _dev(weight)], [_dev(x)])
+        assert res.status() == wb.ERR_INVALID_ARG and "consecutive" in res.error()
+        res.free()
+
+
+def test_lookup_outside_its_vector_is_reported(wb):
+    rowptr, src, weight, _ = _graph(5_000)
+    x = np.ones(4_000)                                                     # shorter than the vertex count
+    res = wb.nested_for(graphs.program_spmv(), [_dev(rowptr[:-1].copy()), _dev(rowptr[1:].copy())],
+                        [_dev(src), _dev(weight)], [_dev(x)])
+    assert res.status() == wb.ERR_INVALID_ARG and "lookup" in res.error()
+    res.free()
+
+
+def test_validation_errors(wb):
+    p = graphs.program_spmv()
+    p.inner.merges.append(dict(p.inner.merges[0]))
+    st, text = wb.nested_validate(p)
+    assert st == wb.ERR_LINEARITY, text
+    q = NestedProgram(["i64", "i64"], 0, 1, ["i32"], ["f64"], "f64", "add")
+    q.inner.merge(0, q.inner.un("cast", q.inner.col(0), to="f64"))
+    q.outer.merge(q.outer.vecbuilder("i64"), q.outer.inner())          # f64 result into an i64 vecbuilder
+    st, text = wb.nested_validate(q)
+    assert st == wb.ERR_TYPE, text
+    from workloads.ir import Program
+    plain = Program(["i64"], gather=["f64"])
+    plain.merge(plain.merger("f64", "add"), plain.lookup(0, plain.col(0)))
+    st, text = wb.validate(plain)                                       # lookup outside a nested loop
+    assert st == wb.ERR_UNSUPPORTED, text
