@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--tune", default="", help='JSON of weld_tuning_t fields applied to every fused call, e.g. {"dict_strategy": 2}')
     ap.add_argument("--vecmerger-sweep", action="store_true",
                     help="also time the count-occurrences vecmerger program (1e8 32-bit keys) over vector sizes and strategies")
+    ap.add_argument("--no-nested", action="store_true",
+                    help="skip the nested-loop leg (one PageRank iteration over the synthetic power-law graph)")
     ap.add_argument("--no-unfused", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -199,6 +201,47 @@ def main():
                               "keys_per_s": nk / median(ts) * 1e3})
             del keys
 
+    # ---- nested loops: one PageRank iteration (contributions map + nested for) and a CSR
+    # matrix-vector product over the synthetic power-law graph; not part of `value`
+    nested = None
+    if not args.no_nested:
+        from workloads import graphs
+        for c in names:
+            cols[c] = None                      # the step's columns are no longer needed
+        torch.cuda.empty_cache()
+        nv = max(1, int(graphs.PAGERANK_VERTICES * args.scale))
+        rowptr, src, weight, outdeg = graphs.make_graph(nv, device="cuda")
+        start, end = rowptr[:-1].contiguous(), rowptr[1:].contiguous()
+        ne = src.numel()
+        rank = torch.full((nv,), 1.0 / nv, dtype=torch.float64, device="cuda")
+        pr, spmv, contrib_prog = graphs.program_pagerank(nv), graphs.program_spmv(), graphs.program_contrib()
+        it_ms, inner_ms, total = [], [], None
+        for i in range(args.warmup + max(5, args.steps // 2)):
+            r1 = wb.fused_for(contrib_prog, [rank, outdeg])
+            contrib = r1.check().vec(0)
+            r2 = wb.nested_for(pr, [start, end], [src], [contrib]).check()
+            if i >= args.warmup:
+                it_ms.append(r1.elapsed_ms() + r2.elapsed_ms())
+                inner_ms.append(r2.kernel_ms())
+            total = float(r2.merger(1))
+            kname = r2.kernel_name()
+            r1.free()
+            r2.free()
+        sp_ms = []
+        for i in range(args.warmup + 5):
+            r = wb.nested_for(spmv, [start, end], [src, weight], [rank]).check()
+            if i >= args.warmup:
+                sp_ms.append(r.elapsed_ms())
+            r.free()
+        # algorithmic bytes of an iteration: every edge's source once, the contribution vector
+        # once, both row offsets, ranks and out-degrees in, new ranks out
+        alg = 4 * ne + 8 * nv + 2 * 8 * nv + 8 * nv + 8 * nv + 8 * nv
+        nested = {"workload": "PageRank iteration, synthetic power-law graph", "vertices": nv, "edges": ne,
+                  "iteration_ms": round(median(it_ms), 4), "inner_kernel_ms": round(median(inner_ms), 4),
+                  "inner_kernel": kname, "edges_per_s": ne / median(it_ms) * 1e3,
+                  "algorithmic_GBps": round(alg / median(it_ms) / 1e6, 1), "rank_sum_after_one_iteration": total,
+                  "spmv_ms": round(median(sp_ms), 4), "spmv_edges_per_s": ne / median(sp_ms) * 1e3}
+
     line = {
         "metric": "fused-loop input GB/s (all five configs back to back)", "value": round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -210,6 +253,8 @@ def main():
     }
     if sweep is not None:
         line["vecmerger_sweep"] = sweep
+    if nested is not None:
+        line["nested_loop"] = nested
     print(json.dumps(line))
 
 

@@ -780,14 +780,22 @@ Generated generate(const Loop& L, const Variant& var) {
 // memory: outer elements that lie entirely inside the tile with a plain store, the (at most
 // two) that continue in a neighbouring tile with a device atomic.  The first outer element of
 // every tile comes from a small kernel run before this one.
-Variant choose_segmented_variant(const Loop& L, bool aligned) {
+Variant choose_segmented_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
     Variant var;
     int widest = 4;
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c] && type_size(L.col_type[c]) > widest) widest = type_size(L.col_type[c]);
     var.v = widest >= 8 ? 2 : 4;
-    var.u = 4;
-    var.block = 256;
+    var.u = tune.units_per_thread > 0 ? tune.units_per_thread : 4;
+    if (var.u > 16) var.u = 16;
+    var.block = tune.block_threads > 0 ? tune.block_threads : 256;
+    if (var.block < 64) var.block = 64;
+    if (var.block > 1024) var.block = 1024;
+    var.block = (var.block / 64) * 64;
+    // range boundaries staged per tile: tiles with more fall back to device memory
+    var.lds_slots = tune.lds_dict_slots > 0 ? tune.lds_dict_slots : 2048;
+    if (var.lds_slots < 64) var.lds_slots = 64;
+    if (var.lds_slots > 8192) var.lds_slots = 8192;
     var.aligned = aligned ? 1 : 0;
     var.backend.assign(1, BK_MERGER);
     return var;
@@ -801,7 +809,7 @@ Generated generate_segmented(const Loop& L, const Variant& var, int offset_type)
     const std::string ID = ident_expr(s.func, s.val_type[0]);
     const int F = s.func;
     o.f("// generated: flattened inner loop of a nested for, %d inner columns\n", L.ncols);
-    o.f("#define W_BLOCK %d\n#define W_V %d\n#define W_U %d\n#define W_ALIGNED %d\n#define W_SEG_CAP 2048\n", var.block, var.v, var.u, var.aligned);
+    o.f("#define W_BLOCK %d\n#define W_V %d\n#define W_U %d\n#define W_ALIGNED %d\n#define W_SEG_CAP %d\n", var.block, var.v, var.u, var.aligned, var.lds_slots);
     o.s += kPreludeSource;
     o.f("\n");
     auto slot = [&](SlotKind k, int idx, const std::string& name, const std::string& ct) {
@@ -909,7 +917,7 @@ Generated generate_segmented(const Loop& L, const Variant& var, int offset_type)
     if (at != std::string::npos) o.s.replace(at, placeholder.size(), name);
     G.kernel_name = name;
     G.source = o.s;
-    G.lds_bytes = 4 * 2050 + 8 * 2049;
+    G.lds_bytes = 4 * (var.lds_slots + 2) + 8 * (var.lds_slots + 1);
     return G;
 }
 

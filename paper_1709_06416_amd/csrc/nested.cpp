@@ -137,7 +137,7 @@ weld_status_t weld_nested_precompile(const weld_nested_t* loop, const weld_build
     Error e = build(loop, builders, false, &NL, nullptr);
     if (!e.ok()) { set_last_error(e.text); return e.status; }
     for (int aligned = 1; aligned >= 0; --aligned) {
-        Variant v1 = choose_segmented_variant(NL.inner, aligned != 0);
+        Variant v1 = choose_segmented_variant(NL.inner, builders->conf.tune, aligned != 0);
         Generated g1 = generate_segmented(NL.inner, v1, NL.offset_type);
         Kernel* k = nullptr;
         e = jit_get(g1.source, g1.kernel_name, false, &k);

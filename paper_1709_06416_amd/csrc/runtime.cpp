@@ -383,7 +383,7 @@ Error run_nested(const NestedLoop& NL, const NestedData& D, const weld_conf_t& c
     bool aligned = true;
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c] && ((uintptr_t)D.inner[c].data & 15)) aligned = false;
-    Variant var = choose_segmented_variant(L, aligned);
+    Variant var = choose_segmented_variant(L, conf.tune, aligned);
     Generated G = generate_segmented(L, var, NL.offset_type);
     Kernel* kern = nullptr;
     Error e = jit_get(G.source, G.kernel_name, true, &kern);

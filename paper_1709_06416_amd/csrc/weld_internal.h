@@ -151,8 +151,9 @@ struct Generated {
 Variant choose_variant(const Loop& loop, const weld_tuning_t& tune, bool aligned);
 Generated generate(const Loop& loop, const Variant& var);
 // The flattened inner loop of a nested for: `loop` is the inner body with one merger;
-// offset_type is the type of the outer start/end vectors.  Uses var.block / v / u / aligned.
-Variant choose_segmented_variant(const Loop& loop, bool aligned);
+// offset_type is the type of the outer start/end vectors.  Uses var.block / v / u / aligned and
+// var.lds_slots (range boundaries a tile stages in LDS).
+Variant choose_segmented_variant(const Loop& loop, const weld_tuning_t& tune, bool aligned);
 Generated generate_segmented(const Loop& loop, const Variant& var, int offset_type);
 int key_bits(const weld_builder_spec_t& b);
 

@@ -126,3 +126,42 @@ def test_c1_full_size_unfused_equals_fused(wb):
     assert abs(float(a.merger(0)) - float(b.merger(0))) <= 1e-9 * abs(float(a.merger(0)))
     a.free()
     b.free()
+
+
+def test_pagerank_full_size_sampled_vertices_and_rank_conservation(wb):
+    """One PageRank iteration over the full-size graph bench.py uses.  The oracle re-evaluates
+    the nested loop for a sample of vertices (each with its whole in-edge range, the largest
+    ranges included); two properties tie down the rest at any size: the merger of the outer
+    loop equals the sum of the new ranks, and that sum is d * (rank held by vertices with
+    out-edges) + (1 - d)."""
+    from oracle import interp
+    from workloads import graphs
+    n = graphs.PAGERANK_VERTICES
+    rowptr, src, _, outdeg = graphs.make_graph(n, device="cuda")
+    start, end = rowptr[:-1].contiguous(), rowptr[1:].contiguous()
+    g = torch.Generator(device="cpu").manual_seed(3)
+    rank = torch.rand(n, dtype=torch.float64, generator=g) + 0.5
+    rank = (rank / rank.sum()).cuda()
+    r1 = wb.fused_for(graphs.program_contrib(), [rank, outdeg]).check()
+    contrib = r1.vec(0)
+    r1.free()
+    res = wb.nested_for(graphs.program_pagerank(n), [start, end], [src], [contrib]).check()
+    new_rank, total = res.vec(0), float(res.merger(1))
+    res.free()
+    assert new_rank.numel() == n
+    # sampled vertices, as a small nested loop of their own for the oracle
+    deg = end - start
+    pick = torch.cat([torch.randint(0, n, (20_000,), generator=g).cuda(), torch.topk(deg, 5).indices,
+                      torch.tensor([0, 1, n - 2, n - 1], device="cuda")])
+    lens = deg[pick]
+    first = torch.cumsum(lens, 0) - lens
+    pos = torch.arange(int(lens.sum().item()), device="cuda") - torch.repeat_interleave(first, lens) \
+        + torch.repeat_interleave(start[pick], lens)
+    sub_src = src[pos].cpu().numpy()
+    sub_ptr = torch.cat([first, lens.sum().reshape(1)]).cpu().numpy()
+    want = interp.run_nested(graphs.program_pagerank(n), [sub_ptr[:-1], sub_ptr[1:]], [sub_src], [contrib.cpu().numpy()])[0]
+    got = new_rank[pick].cpu().numpy()
+    assert np.all(np.abs(got - want) <= 1e-9 * np.abs(want))
+    assert abs(total - float(new_rank.sum().item())) <= 1e-9 * total
+    kept = float(rank[outdeg > 0].sum().item())
+    assert abs(total - (graphs.DAMPING * kept + (1.0 - graphs.DAMPING))) <= 1e-9 * total
