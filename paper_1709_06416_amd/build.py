@@ -16,6 +16,8 @@ ROOT = os.path.dirname(HERE)
 INCLUDE = os.path.join(ROOT, "include")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libweldhip.so")
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
 
 HOST_SOURCES = ["validate.cpp", "codegen.cpp", "jit.cpp", "pool.cpp", "runtime.cpp", "unfused.cpp", "lazy.cpp", "nested.cpp"]
 HIP_SOURCES = ["aot_kernels.hip", "spill_kernels.hip"]
@@ -38,6 +40,9 @@ def _run(cmd):
 
 def _embed_prelude():
     src = open(os.path.join(CSRC, "fused_prelude.hip.h")).read()
+    from paper_1709_06416_amd import erf_table
+    assert src.count("@W_ERF_TABLE@") == 1
+    src = src.replace("@W_ERF_TABLE@", erf_table.c_initialiser())
     assert ')WELDPRE"' not in src
     out = os.path.join(BUILD, "prelude_embed.cpp")
     # split into chunks: string literals have a length limit in some compilers
@@ -96,6 +101,11 @@ def precompile_standard_kernels():
     for name, make in configs.EXAMPLES.items():
         binding.precompile(make())
         names.append(name)
+    from workloads import graphs
+    binding.precompile(graphs.program_contrib())
+    binding.nested_precompile(graphs.program_pagerank(graphs.PAGERANK_VERTICES))
+    binding.nested_precompile(graphs.program_spmv())
+    names += ["pagerank", "spmv"]
     return names
 
 

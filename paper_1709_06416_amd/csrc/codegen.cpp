@@ -153,7 +153,7 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
             case WELD_OP_EXP: o.f("exp(t%d)", q.a); break;
             case WELD_OP_LOG: o.f("log(t%d)", q.a); break;
             case WELD_OP_SQRT: o.f("sqrt(t%d)", q.a); break;
-            case WELD_OP_ERF: o.f("erf(t%d)", q.a); break;
+            case WELD_OP_ERF: o.f("w_erf(t%d)", q.a); break;
             case WELD_OP_ADD:
                 if (q.type == WELD_F64) o.f("t%d + t%d", q.a, q.b);
                 else o.f("%s", wrap_bin(q.type, "+", q.a, q.b).c_str());
@@ -201,6 +201,12 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
         o.f("\n");
     }
     o.f("}\n\n");
+}
+
+bool body_uses(const Loop& L, int opcode) {
+    for (const weld_op_t& q : L.ops)
+        if (q.opcode == opcode) return true;
+    return false;
 }
 
 // expression packing the key struct of builder b into 64 bits (field 0 lowest)
@@ -351,6 +357,8 @@ Generated generate(const Loop& L, const Variant& var) {
     const size_t NB = L.builders.size();
     o.f("// generated: fused for-loop kernel, %d columns, %zu builders\n", L.ncols, NB);
     o.f("#define W_BLOCK %d\n#define W_V %d\n#define W_U %d\n#define W_ALIGNED %d\n", var.block, var.v, var.u, var.aligned);
+    const bool uses_erf = body_uses(L, WELD_OP_ERF);
+    if (uses_erf) o.f("#define W_USE_ERF 1\n");
     o.s += kPreludeSource;
     o.f("\n");
 
@@ -497,6 +505,10 @@ Generated generate(const Loop& L, const Variant& var) {
     o.f("  const int lane = threadIdx.x & 63;\n  const int wave = threadIdx.x >> 6;\n");
     o.f("  (void)lane; (void)wave; (void)errp;\n");
     int lds = 8 * (var.block / 64) + 4;
+    if (uses_erf) {
+        o.f("  w_erf_init();\n");
+        lds += 8 * 960;
+    }
     if (var.ticketed) {
         o.f("  __shared__ i64 s_tile;\n  __shared__ i64 s_cnt[%d][W_WAVES];\n  __shared__ i64 s_pfx[%d];\n", ncompact, ncompact);
         o.f("  __shared__ u64 s_stage[W_WAVES * W_UNIT];\n");
@@ -810,6 +822,8 @@ Generated generate_segmented(const Loop& L, const Variant& var, int offset_type)
     const int F = s.func;
     o.f("// generated: flattened inner loop of a nested for, %d inner columns\n", L.ncols);
     o.f("#define W_BLOCK %d\n#define W_V %d\n#define W_U %d\n#define W_ALIGNED %d\n#define W_SEG_CAP %d\n", var.block, var.v, var.u, var.aligned, var.lds_slots);
+    const bool uses_erf = body_uses(L, WELD_OP_ERF);
+    if (uses_erf) o.f("#define W_USE_ERF 1\n");
     o.s += kPreludeSource;
     o.f("\n");
     auto slot = [&](SlotKind k, int idx, const std::string& name, const std::string& ct) {
@@ -844,6 +858,7 @@ Generated generate_segmented(const Loop& L, const Variant& var, int offset_type)
     o.f("  __shared__ int s_b[W_SEG_CAP + 2];\n  __shared__ %s s_acc[W_SEG_CAP + 1];\n", A);
     o.f("  int* const errp = (int*)(a.ctl + 2);\n");
     o.f("  const int lane = threadIdx.x & 63;\n  const int wave = threadIdx.x >> 6;\n");
+    if (uses_erf) o.f("  w_erf_init();\n");
     o.f("  const i64 ntiles = (a.n + W_TILE - 1) / W_TILE;\n");
     o.f("  for (i64 t = blockIdx.x; t < ntiles; t += gridDim.x) {\n");
     o.f("    const i64 e0 = t * W_TILE;\n    const i64 e1 = e0 + W_TILE < a.n ? e0 + W_TILE : a.n;\n");

@@ -88,6 +88,38 @@ template <int F, int BITS> __device__ __forceinline__ i64 w_identity_int() {
     return (i64)(~0ull << (BITS - 1));
 }
 
+// ---------------------------------------------------------------- erf
+// The library's own erf for f64 (the device math library's costs about 100 vector
+// instructions, two of them per row made the Black-Scholes loop compute bound): a degree-9
+// Taylor polynomial per interval of width 1/16 on [0, 6), coefficients from a table that the
+// build step computes in 80-digit arithmetic (paper_1709_06416_amd/erf_table.py: remainder
+// below 4e-18; interval 0 is expanded about 0 and so keeps the relative accuracy of small
+// arguments; 1 from 6 on, where erf has long rounded to 1).  The table is copied to LDS once
+// per work-group: lanes index it with their own interval.
+#ifdef W_USE_ERF
+__device__ const double w_erf_table[960] = {
+@W_ERF_TABLE@
+};
+__shared__ double w_erf_lds[960];
+__device__ __forceinline__ void w_erf_init() {
+    for (int q = threadIdx.x; q < 960; q += W_BLOCK) w_erf_lds[q] = w_erf_table[q];
+    __syncthreads();
+}
+__device__ __forceinline__ double w_erf(double x) {
+    const double a = __builtin_fabs(x);
+    int k = (int)(a * 16.0);
+    k = k > 95 ? 95 : k;
+    const double c = k ? ((double)k + 0.5) * 0.0625 : 0.0;
+    const double h = a - c;
+    const double* t = w_erf_lds + k * 10;
+    double p = t[9];
+#pragma unroll
+    for (int j = 8; j >= 0; --j) p = __builtin_fma(p, h, t[j]);
+    p = a >= 6.0 ? 1.0 : p;
+    return __builtin_copysign(p, x);
+}
+#endif
+
 // ---------------------------------------------------------------- lookup
 // lookup(v, ix) of a nested loop's inner body: an index outside the vector raises error
 // bit 4 (the call then fails) and yields 0 instead of reading out of bounds.

@@ -107,6 +107,19 @@ def test_c2_intermediates_strict_relative(wb):
     _check(wb, p, cols, label="C2-d1d2")
 
 
+def test_erf_map_against_the_oracle(wb):
+    # the library evaluates erf itself (piecewise polynomial, table built with the library):
+    # relative 1e-12 everywhere, tiny arguments and the interval ends included; +-1 beyond 6
+    rnd = np.random.RandomState(9)
+    x = np.concatenate([rnd.uniform(-6.5, 6.5, 150_000), rnd.uniform(-0.07, 0.07, 20_000),
+                        10.0 ** rnd.uniform(-300, -1, 2_000), -(10.0 ** rnd.uniform(-300, -1, 2_000)),
+                        np.arange(0, 97) / 16.0, np.nextafter(np.arange(1, 97) / 16.0, 0),
+                        [-0.0, 0.0, 5.99999, 6.0, 7.5, -7.5, 1e300, -1e300, np.inf, -np.inf]])
+    p = Program(["f64"])
+    p.merge(p.vecbuilder("f64"), p.un("erf", p.col(0)))
+    _check(wb, p, [_dev(x)], label="erf map")
+
+
 def test_plain_arithmetic_maps_are_bit_exact(wb):
     # +,-,*,/ and sqrt are correctly rounded on both sides and nothing is contracted
     p = Program(["f64", "f64"])
