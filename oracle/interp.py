@@ -20,6 +20,9 @@ What it follows (paper, Sec. 3.2 and Table 1; Sec. 3.3 for the macros):
     combine with func, field by field when V is a struct.
   * vecmerger[T,func] (Table 1, Sec. 7.7): starts from a copy of an input vector and
     merges each {index, value} pair into the cell at that index with func.
+  * groupbuilder[K,V] (Table 1): groups the merged {key, value} pairs by key; the result
+    maps each key to the vector of its values (here: in index order, the order a
+    sequential loop appends them in; a parallel loop may return any order inside a group).
 
   * nested loops (Sec. 3.2: loops nest arbitrarily; a loop may take a start and an end
     index per vector): `run_nested` evaluates the inner body over every (outer element,
@@ -222,6 +225,22 @@ def _group(func, key_cols, val_cols, val_types, sums):
 _AT = {"add": np.add, "mul": np.multiply, "min": np.minimum, "max": np.maximum}
 
 
+def _groups(key_cols, v):
+    """groupbuilder: (key columns of the distinct keys sorted by key, offsets, values): the
+    values of key g are values[offsets[g]:offsets[g+1]], in index order."""
+    m = len(v)
+    if m == 0:
+        return ([k[:0] for k in key_cols], np.zeros(1, dtype=np.int64), v[:0].copy())
+    order = np.lexsort(tuple(reversed(key_cols)))          # stable: index order within a key
+    ks = [k[order] for k in key_cols]
+    change = np.zeros(m, dtype=bool)
+    change[0] = True
+    for k in ks:
+        change[1:] |= k[1:] != k[:-1]
+    starts = np.flatnonzero(change)
+    return ([k[starts] for k in ks], np.append(starts, m).astype(np.int64), v[order].copy())
+
+
 def _vecmerge(spec, init, idx, v):
     """vecmerger: out = copy(init); out[idx[j]] = func(out[idx[j]], v[j]) for j in index order."""
     dt = NP_TYPE[spec["type"]]
@@ -242,6 +261,7 @@ def run(program, columns, sums="exact", inits=None):
     dictmerger  -> (list of key columns, list of value columns), sorted by key
 
     vecmerger   -> 1-d numpy array (inits: {builder index: initial vector})
+    groupbuilder-> (list of key columns sorted by key, offsets, values)
 
     sums = "exact": an f64 `add` returns the correctly rounded real sum (any
     merge order is legal, Sec. 3.2, so this is the value every order
@@ -284,6 +304,13 @@ def _results(program, val, n, sums, inits):
             v = val[m["vals"][0]][mask]
             assert idx.dtype == np.int64 and v.dtype == NP_TYPE[spec["type"]]
             results[b] = _vecmerge(spec, (inits or {}).get(b), idx, v)
+        elif spec["kind"] == "groupbuilder":
+            kc = [val[k][mask] for k in m["keys"]]
+            v = val[m["vals"][0]][mask]
+            for c, t in zip(kc, spec["key_types"]):
+                assert c.dtype == NP_TYPE[t]
+            assert v.dtype == NP_TYPE[spec["type"]]
+            results[b] = _groups(kc, v)
         else:
             raise ValueError(spec["kind"])
     for b, spec in enumerate(program.builders):
@@ -295,6 +322,9 @@ def _results(program, val, n, sums, inits):
             elif spec["kind"] == "vecmerger":
                 results[b] = _vecmerge(spec, (inits or {}).get(b), np.zeros(0, np.int64),
                                        np.zeros(0, NP_TYPE[spec["type"]]))
+            elif spec["kind"] == "groupbuilder":
+                results[b] = _groups([np.zeros(0, NP_TYPE[t]) for t in spec["key_types"]],
+                                     np.zeros(0, NP_TYPE[spec["type"]]))
             else:
                 results[b] = ([np.zeros(0, NP_TYPE[t]) for t in spec["key_types"]],
                               [np.zeros(0, NP_TYPE[t]) for t in spec["val_types"]])

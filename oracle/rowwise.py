@@ -166,7 +166,7 @@ def run_nested(nested, outer_columns, inner_columns, gather):
 def run(program, columns, inits=None, inner_results=None):
     """columns: list of Python lists (ints / floats).  Returns Python values:
     merger -> number, vecbuilder -> list, dictmerger -> {key tuple: [values]},
-    vecmerger -> list (inits: {builder index: list})."""
+    vecmerger -> list (inits: {builder index: list}), groupbuilder -> {key tuple: list of values}."""
     n = len(columns[0]) if columns else 0
     state = []
     for b, spec in enumerate(program.builders):
@@ -174,6 +174,8 @@ def run(program, columns, inits=None, inner_results=None):
             state.append(_identity(spec["func"], spec["type"]))
         elif spec["kind"] == "vecbuilder":
             state.append([])
+        elif spec["kind"] == "groupbuilder":
+            state.append({})
         elif spec["kind"] == "vecmerger":
             init = (inits or {}).get(b)
             state.append(list(init) if init is not None
@@ -192,6 +194,8 @@ def run(program, columns, inits=None, inner_results=None):
                 state[b] = _combine(spec["func"], spec["type"], state[b], val[m["vals"][0]])
             elif spec["kind"] == "vecbuilder":
                 state[b].append(val[m["vals"][0]])
+            elif spec["kind"] == "groupbuilder":
+                state[b].setdefault(tuple(val[k] for k in m["keys"]), []).append(val[m["vals"][0]])
             elif spec["kind"] == "vecmerger":
                 ix = val[m["keys"][0]]
                 state[b][ix] = _combine(spec["func"], spec["type"], state[b][ix], val[m["vals"][0]])

@@ -506,3 +506,75 @@ def test_vecmerger_brute_force_with_initial_vector(func):
     assert rowwise.run(p, [idx, v], inits={0: init})[0] == want
     fresh = interp.run(p, [np.array(idx, np.int64), np.array(v, np.int64)])[0]      # no init: identities
     assert fresh[4] == interp.identity(func, "i64")
+
+
+# ----------------------------------------------------------------------
+# groupbuilder (Table 1): dict[K, vec[V]] by grouping {K, V} pairs by key
+# ----------------------------------------------------------------------
+def _group_program(key_types, t, with_pred):
+    p = Program(list(key_types) + [t])
+    keys = [p.col(i) for i in range(len(key_types))]
+    v = p.col(len(key_types))
+    pred = p.bin("ne", keys[0], p.const(key_types[0], 3)) if with_pred else None
+    p.merge(p.groupbuilder(key_types, t, 64), v, keys=keys, pred=pred)
+    return p
+
+
+def test_groupbuilder_hand_worked_example():
+    # pairs (k, v): (2,10) (1,20) (2,30) (7,40) (1,50) (2,60)  ->  1:[20,50]  2:[10,30,60]  7:[40]
+    k = np.array([2, 1, 2, 7, 1, 2], dtype=np.int32)
+    v = np.array([10, 20, 30, 40, 50, 60], dtype=np.int64)
+    keys, off, vals = interp.run(_group_program(["i32"], "i64", False), [k, v])[0]
+    assert keys[0].tolist() == [1, 2, 7] and off.tolist() == [0, 2, 5, 6]
+    assert vals.tolist() == [20, 50, 10, 30, 60, 40]
+    assert rowwise.run(_group_program(["i32"], "i64", False), [k.tolist(), v.tolist()])[0] == \
+        {(1,): [20, 50], (2,): [10, 30, 60], (7,): [40]}
+
+
+@pytest.mark.parametrize("with_pred", [False, True])
+@pytest.mark.parametrize("t", ["i8", "i32", "i64", "f64"])
+def test_groupbuilder_against_per_row_loop_and_pandas(t, with_pred):
+    import pandas as pd
+    rnd = np.random.RandomState(4)
+    n = 700
+    k1 = rnd.randint(-2, 6, size=n).astype(np.int8)
+    k2 = rnd.randint(0, 5, size=n).astype(np.int64) * 1_000_000_007
+    v = (rnd.uniform(-5, 5, size=n) if t == "f64" else rnd.randint(-100, 100, size=n)).astype(interp.NP_TYPE[t])
+    prog = _group_program(["i8", "i64"], t, with_pred)
+    keys, off, vals = interp.run(prog, [k1, k2, v])[0]
+    want = rowwise.run(prog, [k1.tolist(), k2.tolist(), v.tolist()])[0]
+    assert len(keys[0]) == len(want) and off[0] == 0 and off[-1] == len(vals) == sum(len(x) for x in want.values())
+    for g in range(len(keys[0])):
+        assert vals[off[g]:off[g + 1]].tolist() == want[(int(keys[0][g]), int(keys[1][g]))]     # index order inside a group
+    # a library group-by over the same filtered pairs
+    mask = k1 != 3 if with_pred else np.ones(n, dtype=bool)
+    df = pd.DataFrame({"a": k1[mask], "b": k2[mask], "v": v[mask]})
+    lib = df.groupby(["a", "b"], sort=True)["v"].apply(list)
+    assert [tuple(ix) for ix in lib.index] == list(zip(keys[0].tolist(), keys[1].tolist()))
+    assert [vals[off[g]:off[g + 1]].tolist() for g in range(len(lib))] == list(lib.values)
+
+
+def test_groupbuilder_relations_to_the_other_builders():
+    # group sizes are the dictmerger's counts; the groups' concatenation is the vecbuilder's output
+    # reordered; one key -> exactly the vecbuilder's output; all keys distinct -> singletons
+    cols = [c.numpy() for c in configs.make_columns("C5", 20_000)]
+    code = cols[0]
+    p = Program(["i64"])
+    c = p.col(0)
+    pred = p.bin("gt", c, p.const("i64", 0))
+    key = p.bin("mod", c, p.const("i64", 100_000))
+    p.merge(p.groupbuilder(["i64"], "i64", 100_000), c, keys=[key], pred=pred)
+    p.merge(p.dictmerger(["i64"], ["i64"], "add", 100_000), [p.const("i64", 1)], keys=[key], pred=pred)
+    p.merge(p.vecbuilder("i64"), c, pred=pred)
+    (gk, off, vals), (dk, dv), vec = interp.run(p, [code])
+    assert np.array_equal(gk[0], dk[0]) and np.array_equal(np.diff(off), dv[0])
+    assert np.array_equal(np.sort(vals), np.sort(vec))
+    assert all(np.all(vals[off[g]:off[g + 1]] % 100_000 == gk[0][g]) for g in range(len(off) - 1))
+    q = Program(["i64"])
+    q.merge(q.groupbuilder(["i64"], "i64", 4), q.col(0), keys=[q.const("i64", 5)], pred=q.bin("gt", q.col(0), q.const("i64", 0)))
+    gk, off, vals = interp.run(q, [code])[0]
+    assert gk[0].tolist() == [5] and np.array_equal(vals, vec)
+    r = Program(["i64"])
+    r.merge(r.groupbuilder(["i64"], "i64", 30_000), r.col(0), keys=[r.index()])
+    gk, off, vals = interp.run(r, [code])[0]
+    assert np.array_equal(gk[0], np.arange(len(code))) and np.array_equal(off, np.arange(len(code) + 1)) and np.array_equal(vals, code)

@@ -34,6 +34,8 @@ A `Program` holds
              {'kind': 'vecmerger', 'type': T, 'func': f, 'length': m}
                (merges {index, value} pairs into a vector of m cells; the
                 initial vector is an input of the call, not of the program)
+             {'kind': 'groupbuilder', 'key_types': [..], 'type': T, 'capacity': hint}
+               (groups merged {key, value} pairs by key: one vector of values per key)
   merges   : list of dicts {'builder': b, 'pred': op or None,
                             'keys': [ops], 'vals': [ops]}
              (Sec. 3.2: `if (p) merge(b, v) else b` is a merge under predicate p.)
@@ -127,6 +129,11 @@ class Program:
     def vecmerger(self, t, func, length):
         assert func in FUNCS
         self.builders.append({"kind": "vecmerger", "type": t, "func": func, "length": int(length)})
+        return len(self.builders) - 1
+
+    def groupbuilder(self, key_types, t, capacity):
+        self.builders.append({"kind": "groupbuilder", "key_types": list(key_types), "type": t,
+                              "capacity": int(capacity)})
         return len(self.builders) - 1
 
     def merge(self, builder, vals, keys=(), pred=None):
