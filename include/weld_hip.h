@@ -114,7 +114,7 @@ typedef struct {
     const weld_col_t* col; /* host array */
 } weld_cols_t;
 
-typedef enum { WELD_MERGER = 0, WELD_VECBUILDER = 1, WELD_DICTMERGER = 2, WELD_VECMERGER = 3 } weld_builder_kind_t;
+typedef enum { WELD_MERGER = 0, WELD_VECBUILDER = 1, WELD_DICTMERGER = 2, WELD_VECMERGER = 3, WELD_GROUPBUILDER = 4 } weld_builder_kind_t;
 typedef enum { WELD_FUNC_ADD = 0, WELD_FUNC_MUL = 1, WELD_FUNC_MIN = 2, WELD_FUNC_MAX = 3 } weld_func_t;
 
 /* One builder of Table 1.
@@ -129,7 +129,12 @@ typedef enum { WELD_FUNC_ADD = 0, WELD_FUNC_MUL = 1, WELD_FUNC_MIN = 2, WELD_FUN
  *                           `length` elements of T owned by the caller, never written; NULL =
  *                           every cell starts at func's identity).  key_type[0] = WELD_I64 (the
  *                           index), val_type[0] = T (WELD_I64 or WELD_F64).  An index outside
- *                           0..length-1 makes the call fail with WELD_ERR_INVALID_ARG. */
+ *                           0..length-1 makes the call fail with WELD_ERR_INVALID_ARG.
+ *   groupbuilder[K,V]     : groups the merged {K, V} pairs by key: the result maps every key
+ *                           to the vector of its values (dict[K, vec[V]]).  K as for
+ *                           dictmerger, V one scalar: val_type[0]; capacity = upper bound on
+ *                           the number of distinct keys.  The order of the values inside a
+ *                           group is unspecified (merges may run in any order). */
 typedef struct {
     int32_t kind; /* weld_builder_kind_t */
     int32_t func; /* weld_func_t (ignored by vecbuilder) */
@@ -186,6 +191,11 @@ typedef struct { int64_t len; void* ptr; } weld_vec_t;
 /* a dictionary result: entry i is (keys[i], values[i]); packed structs; unordered */
 typedef struct { weld_vec_t keys; weld_vec_t values; } weld_dict_t;
 
+/* a groupbuilder result, dict[K, vec[V]] in compressed form: group g has key keys[g] (packed
+ * struct) and the values values[offsets[g] .. offsets[g+1]); offsets holds keys.len + 1 int64;
+ * groups are unordered */
+typedef struct { weld_vec_t keys; weld_vec_t offsets; weld_vec_t values; } weld_groups_t;
+
 typedef struct weld_result weld_result_t; /* opaque (the paper's WeldResult handle, Sec. 4.1) */
 
 /*
@@ -218,12 +228,14 @@ const char* weld_result_error(const weld_result_t* r);
  *   merger     -> DEVICE pointer to one scalar of its type (8-byte aligned)
  *   vecbuilder, vecmerger -> HOST pointer to a weld_vec_t  (ptr inside is a device pointer)
  *   dictmerger -> HOST pointer to a weld_dict_t (device pointers inside)
+ *   groupbuilder -> HOST pointer to a weld_groups_t (device pointers inside)
  * Valid until weld_result_free(). */
 const void* weld_result_data(weld_result_t* r, int32_t idx);
 
 /* Convenience for callers without a HIP runtime of their own: copy `bytes` bytes of
  * builder idx's payload, starting at byte `offset`, to `dst`.
- *   part 0: merger scalar / vecbuilder elements / dictmerger keys;  part 1: dictmerger values.
+ *   part 0: merger scalar / vecbuilder elements / dictmerger or groupbuilder keys;
+ *   part 1: dictmerger values / groupbuilder offsets;  part 2: groupbuilder values.
  *   dst_is_device != 0: dst is a device pointer (copy stays on the GPU). */
 weld_status_t weld_result_fetch(weld_result_t* r, int32_t idx, int32_t part, void* dst,
                                 int64_t offset, int64_t bytes, int32_t dst_is_device);

@@ -30,7 +30,7 @@ OPCODE = {"col": 0, "const": 1, "index": 2, "neg": 3, "not": 4, "cast": 5, "exp"
           "erf": 9, "add": 10, "sub": 11, "mul": 12, "div": 13, "mod": 14, "min": 15, "max": 16, "lt": 17,
           "le": 18, "gt": 19, "ge": 20, "eq": 21, "ne": 22, "and": 23, "or": 24, "select": 25,
           "lookup": 26, "outer": 27, "inner": 28}      # the last three: include/weld_nested.h
-KIND = {"merger": 0, "vecbuilder": 1, "dictmerger": 2, "vecmerger": 3}
+KIND = {"merger": 0, "vecbuilder": 1, "dictmerger": 2, "vecmerger": 3, "groupbuilder": 4}
 FUNC = {"add": 0, "mul": 1, "min": 2, "max": 3}
 MODE = {"fused": 0, "unfused": 1}
 
@@ -92,6 +92,10 @@ class Vec(C.Structure):
 
 class Dict(C.Structure):
     _fields_ = [("keys", Vec), ("values", Vec)]
+
+
+class Groups(C.Structure):
+    _fields_ = [("keys", Vec), ("offsets", Vec), ("values", Vec)]
 
 
 lib.weld_fused_for.argtypes = [C.POINTER(Cols), C.c_int64, C.POINTER(Body), C.POINTER(Builder),
@@ -216,6 +220,15 @@ class Marshalled:
                 for k, t in enumerate(b["val_types"]):
                     s.val_type[k] = TYPE_ID[t]
                 s.capacity = int(b["capacity"])
+            elif b["kind"] == "groupbuilder":
+                s.nkeys = len(b["key_types"])
+                if s.nkeys > MAX_KEY:
+                    raise WeldError(ERR_INVALID_ARG, "too many key fields")
+                for k, t in enumerate(b["key_types"]):
+                    s.key_type[k] = TYPE_ID[t]
+                s.nvals = 1
+                s.val_type[0] = TYPE_ID[b["type"]]
+                s.capacity = int(b["capacity"])
             elif b["kind"] == "vecmerger":
                 s.nkeys = 1
                 s.key_type[0] = TYPE_ID["i64"]
@@ -336,6 +349,34 @@ class Result:
             kcols = [k[order] for k in kcols]
             vcols = [v[order] for v in vcols]
         return kcols, vcols
+
+    def groups(self, idx, sort=True):
+        """groupbuilder result as (key columns, offsets, values): the values of group g are
+        values[offsets[g]:offsets[g+1]].  sort=True: groups ordered by key and the values of each
+        group ascending (the library leaves both orders unspecified)."""
+        self.check()
+        spec = self._program.builders[idx]
+        p = lib.weld_result_data(self._h, idx)
+        g = C.cast(p, C.POINTER(Groups)).contents
+        ng, nv = g.keys.len, g.values.len
+        kdt = np.dtype({"names": ["k%d" % i for i in range(len(spec["key_types"]))],
+                        "formats": [TYPE_NP[t] for t in spec["key_types"]]}, align=False)
+        vt = TYPE_NP[spec["type"]]
+        keys = self._fetch_host(idx, 0, ng * kdt.itemsize).view(kdt)
+        offsets = self._fetch_host(idx, 1, (ng + 1) * 8).view(np.int64)
+        values = self._fetch_host(idx, 2, nv * np.dtype(vt).itemsize).view(vt)
+        kcols = [np.ascontiguousarray(keys[name]) for name in kdt.names]
+        if sort and ng:
+            sizes = np.diff(offsets)
+            gid = np.repeat(np.arange(ng), sizes)                     # group of every value, storage order
+            rank = np.empty(ng, dtype=np.int64)
+            order = np.lexsort(tuple(reversed(kcols)))
+            rank[order] = np.arange(ng)                                # position of each group once sorted by key
+            by = np.lexsort((values, rank[gid]))                       # by group (sorted), then by value
+            values = values[by]
+            kcols = [k[order] for k in kcols]
+            offsets = np.concatenate([[0], np.cumsum(sizes[order])]).astype(np.int64)
+        return kcols, offsets, values
 
     def free(self):
         if self._h:

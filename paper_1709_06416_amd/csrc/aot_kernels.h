@@ -34,9 +34,40 @@ struct MergerFinish {
 hipError_t launch_merger_finish(const MergerFinish& m, int count, hipStream_t stream);
 
 hipError_t launch_fill64(void* p, int64_t count, uint64_t value, hipStream_t stream);
+// slot_pos (may be null): receives, for every occupied slot (and the extra slot `slots`), the
+// position its entry was written to.
 hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots, const DictValues& vals,
                                const DictLayout& lay, int64_t capacity, void* out_keys, void* out_vals,
-                               void* count, void* err, hipStream_t stream);
+                               void* count, void* err, int* slot_pos, hipStream_t stream);
+
+// groupbuilder, second half.  The loop kernel has counted the pairs of every key in a
+// dictionary (extracted into `counts`, one int64 per group, *ngroups of them) and compacted
+// the pairs' key fields and values into vectors of *npairs elements.
+//   group_offsets: offsets[g] = sum of counts[0..g), offsets[ngroups] = total; cursor[g] = 0.
+//   group_scatter: value j goes to values_out[offsets[g] + position], g = the group of its
+//                  key (found through the dictionary's table and slot_pos), position handed
+//                  out per group: per tile of pairs an LDS table counts the pairs of each group
+//                  and one device atomic per (tile, group) reserves their places.
+struct GroupScatter {
+    const unsigned long long* npairs;      // device
+    int nkeys;
+    const void* key[4];
+    int key_size[4];
+    int key_shift[4];
+    const void* value;
+    int value_size;
+    const unsigned long long* table_keys;
+    const unsigned int* hdr;
+    long long slots;
+    const int* slot_pos;
+    long long capacity;
+    const long long* offsets;
+    unsigned long long* cursor;
+    void* values_out;
+};
+hipError_t launch_group_offsets(const void* counts, const void* ngroups, int64_t capacity, void* offsets, void* cursor,
+                                hipStream_t stream);
+hipError_t launch_group_scatter(const GroupScatter& g, int blocks, hipStream_t stream);
 // Aggregation of the key-partitioned spill queues of a large dictmerger (spill_kernels.hip).
 // The loop kernel's work-group g appends to segment [g][partition] of `log` (cap entries of
 // 1 + nvals 8-byte words each) and stores the segment lengths in qcnt[g * kSpillParts + partition].

@@ -100,12 +100,13 @@ hipError_t launch_merger_finish(const MergerFinish& m, int count, hipStream_t st
 __global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, const u32* hdr, i64 slots,
                                                            DictValues vals, DictLayout lay, i64 capacity,
                                                            unsigned char* out_keys, unsigned char* out_vals,
-                                                           u64* count, int* err) {
+                                                           u64* count, int* err, int* slot_pos) {
     for (i64 s = (i64)blockIdx.x * 256 + threadIdx.x; s <= slots; s += (i64)gridDim.x * 256) {
         const u64 kb = s < slots ? keys[s] : kEmptyKey;
         const bool used = s < slots ? (kb != kEmptyKey) : (hdr[1] != 0);
         if (!used) continue;
         const u64 pos = atomicAdd(count, 1ull);
+        if (slot_pos) slot_pos[s] = (i64)pos < capacity ? (int)pos : -1;
         if ((i64)pos >= capacity) {
             atomicOr(err, 1);
             continue;
@@ -129,12 +130,153 @@ __global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, cons
 
 hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots, const DictValues& vals,
                                const DictLayout& lay, int64_t capacity, void* out_keys, void* out_vals,
-                               void* count, void* err, hipStream_t stream) {
+                               void* count, void* err, int* slot_pos, hipStream_t stream) {
     int64_t blocks = (slots + 1 + 255) / 256;
     if (blocks > 2048) blocks = 2048;
     dict_extract_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
         (const u64*)keys, (const u32*)hdr, slots, vals, lay, capacity, (unsigned char*)out_keys,
-        (unsigned char*)out_vals, (u64*)count, (int*)err);
+        (unsigned char*)out_vals, (u64*)count, (int*)err, slot_pos);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- groupbuilder
+// Exclusive prefix sums of the group sizes, one work-group walking the groups in chunks of
+// 1024 with a running carry (groups are at most the dictionary's capacity; 1e5 groups take
+// 100 rounds).
+__global__ void __launch_bounds__(1024) group_offsets_kernel(const i64* counts, const u64* ngroups, i64 capacity,
+                                                             i64* offsets, u64* cursor) {
+    __shared__ i64 s_wave[16];
+    __shared__ i64 s_carry;
+    const int tid = threadIdx.x;
+    i64 n = (i64)*ngroups;
+    if (n > capacity) n = capacity;
+    if (tid == 0) s_carry = 0;
+    __syncthreads();
+    for (i64 base = 0; base < n; base += 1024) {
+        const i64 g = base + tid;
+        const i64 c = g < n ? counts[g] : 0;
+        i64 incl = c;
+        for (int off = 1; off < 64; off <<= 1) {
+            const i64 o = __shfl_up(incl, off, 64);
+            if ((tid & 63) >= off) incl += o;
+        }
+        if ((tid & 63) == 63) s_wave[tid >> 6] = incl;
+        __syncthreads();
+        i64 before = s_carry;
+        for (int w = 0; w < (tid >> 6); ++w) before += s_wave[w];
+        if (g < n) {
+            offsets[g] = before + incl - c;
+            cursor[g] = 0;
+        }
+        __syncthreads();
+        if (tid == 1023) s_carry = before + incl;
+        __syncthreads();
+    }
+    if (tid == 0) offsets[n] = s_carry;
+}
+
+hipError_t launch_group_offsets(const void* counts, const void* ngroups, int64_t capacity, void* offsets, void* cursor,
+                                hipStream_t stream) {
+    group_offsets_kernel<<<dim3(1), dim3(1024), 0, stream>>>((const i64*)counts, (const u64*)ngroups, capacity,
+                                                             (i64*)offsets, (u64*)cursor);
+    return hipGetLastError();
+}
+
+__device__ __forceinline__ u64 load_bits(const void* p, i64 i, int size) {
+    switch (size) {
+        case 1: return (u64)((const unsigned char*)p)[i];
+        case 4: return (u64)((const u32*)p)[i];
+        default: return ((const u64*)p)[i];
+    }
+}
+// same multiplicative hash as the loop kernels' tables (both probe the same table)
+__device__ __forceinline__ u32 table_hash_slot(u64 k, u32 slots) {
+    const u32 x = (u32)k ^ ((u32)(k >> 32) * 0x85ebca6bu);
+    return (x * 0x9e3779b1u) >> (__builtin_clz(slots) + 1);
+}
+
+#define GROUP_TILE 4096
+#define GROUP_LDS 8192
+__global__ void __launch_bounds__(1024) group_scatter_kernel(const GroupScatter a) {
+    __shared__ u32 s_gid[GROUP_LDS];       // group of the entry, ~0 = free
+    __shared__ u32 s_cnt[GROUP_LDS];       // pairs of that group in this tile
+    __shared__ i64 s_base[GROUP_LDS];      // where they start in values_out
+    const int tid = threadIdx.x;
+    const i64 npairs = (i64)*a.npairs;
+    const i64 ntiles = (npairs + GROUP_TILE - 1) / GROUP_TILE;
+    for (int q = tid; q < GROUP_LDS; q += 1024) { s_gid[q] = ~0u; s_cnt[q] = 0; }
+    __syncthreads();
+    for (i64 t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        int entry[4];
+        u32 rank[4];
+        u64 val[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const i64 i = t * GROUP_TILE + j * 1024 + tid;
+            entry[j] = -1;
+            rank[j] = 0;
+            val[j] = 0;
+            if (i >= npairs) continue;
+            u64 kb = 0;
+            for (int k = 0; k < a.nkeys; ++k) kb |= load_bits(a.key[k], i, a.key_size[k]) << a.key_shift[k];
+            val[j] = load_bits(a.value, i, a.value_size);
+            // the key's slot in the dictionary (every key is there unless the capacity overflowed)
+            i64 slot = -1;
+            if (kb == kEmptyKey) {
+                slot = a.hdr[1] ? a.slots : -1;
+            } else {
+                i64 s = (i64)table_hash_slot(kb, (u32)a.slots);
+                for (i64 probe = 0; probe < a.slots; ++probe) {
+                    const u64 cur = a.table_keys[s];
+                    if (cur == kb) { slot = s; break; }
+                    if (cur == kEmptyKey) break;
+                    s = (s + 1) & (a.slots - 1);
+                }
+            }
+            const int gid = slot >= 0 ? a.slot_pos[slot] : -1;
+            if (gid < 0) continue;                              // not extracted: the call fails with the capacity error
+            // this tile's entry for the group, and the pair's rank inside it
+            u32 e = ((u32)gid * 0x9e3779b1u) >> (32 - 13);
+            for (;;) {                                          // at most GROUP_TILE groups in 2 * GROUP_TILE entries
+                const u32 cur = __hip_atomic_load(&s_gid[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (cur == (u32)gid) break;
+                if (cur == ~0u) {
+                    u32 expect = ~0u;
+                    if (__hip_atomic_compare_exchange_strong(&s_gid[e], &expect, (u32)gid, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_WORKGROUP) || expect == (u32)gid)
+                        break;
+                }
+                e = (e + 1) & (GROUP_LDS - 1);
+            }
+            entry[j] = (int)e;
+            rank[j] = __hip_atomic_fetch_add(&s_cnt[e], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        __syncthreads();
+        for (int q = tid; q < GROUP_LDS; q += 1024) {
+            const u32 gid = s_gid[q];
+            if (gid == ~0u) continue;
+            s_base[q] = a.offsets[gid] + (i64)__hip_atomic_fetch_add(&a.cursor[gid], (u64)s_cnt[q], __ATOMIC_RELAXED,
+                                                                     __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (entry[j] < 0) continue;
+            const i64 dst = s_base[entry[j]] + rank[j];
+            switch (a.value_size) {
+                case 1: ((unsigned char*)a.values_out)[dst] = (unsigned char)val[j]; break;
+                case 4: ((u32*)a.values_out)[dst] = (u32)val[j]; break;
+                default: ((u64*)a.values_out)[dst] = val[j]; break;
+            }
+        }
+        __syncthreads();
+        for (int q = tid; q < GROUP_LDS; q += 1024) { s_gid[q] = ~0u; s_cnt[q] = 0; }
+        __syncthreads();
+    }
+}
+
+hipError_t launch_group_scatter(const GroupScatter& g, int blocks, hipStream_t stream) {
+    group_scatter_kernel<<<dim3((unsigned)blocks), dim3(1024), 0, stream>>>(g);
     return hipGetLastError();
 }
 

@@ -335,6 +335,16 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
     if (var.block > 1024) var.block = 1024;
     var.block = (var.block / 64) * 64;
     var.aligned = aligned ? 1 : 0;
+    // the LDS dictionary shares the 160 KiB with the compaction's staging buffer, the admission
+    // filter, the spill counters and the erf table: halve it until everything fits
+    if (var.lds_slots > 0) {
+        int per_slot = 0;
+        for (size_t b = 0; b < L.builders.size(); ++b)
+            if (var.backend[b] == BK_DICT_LDS) per_slot += 8 * (1 + L.builders[b].nvals);
+        const int other = (var.ticketed ? 8 * var.block * var.v : 0) + 4 * var.door_words + (var.spill ? 1024 : 0) +
+                          (body_uses(L, WELD_OP_ERF) ? 7680 : 0) + 2048;
+        while (var.lds_slots > 64 && var.lds_slots * per_slot + other > 160 * 1024) var.lds_slots /= 2;
+    }
     return var;
 }
 

@@ -116,8 +116,81 @@ struct Layout {
 
 namespace weld {
 
+Loop expand_groups(const Loop& in, std::vector<GroupLink>* links) {
+    links->clear();
+    bool any = false;
+    for (const weld_builder_spec_t& s : in.builders)
+        if (s.kind == WELD_GROUPBUILDER) any = true;
+    if (!any) return in;
+    Loop L = in;
+    const size_t NB = in.builders.size();
+    for (size_t b = 0; b < NB; ++b) {
+        if (in.builders[b].kind != WELD_GROUPBUILDER) continue;
+        const weld_builder_spec_t g = in.builders[b];
+        GroupLink link;
+        link.dict = (int)b;
+        // the counting dictionary: dictmerger[K, i64, +] of the constant 1
+        weld_builder_spec_t d = g;
+        d.kind = WELD_DICTMERGER;
+        d.func = WELD_FUNC_ADD;
+        d.nvals = 1;
+        d.val_type[0] = WELD_I64;
+        L.builders[b] = d;
+        const int m = in.merge_of[b];
+        int one = -1;
+        if (m >= 0) {
+            weld_op_t c;
+            memset(&c, 0, sizeof c);
+            c.opcode = WELD_OP_CONST;
+            c.type = WELD_I64;
+            c.a = c.b = c.c = -1;
+            c.imm.i64 = 1;
+            L.ops.push_back(c);
+            one = (int)L.ops.size() - 1;
+            L.merges[m].nvals = 1;
+            L.merges[m].val[0] = one;
+        }
+        auto add_vec = [&](int type, int value_op) {
+            weld_builder_spec_t v;
+            memset(&v, 0, sizeof v);
+            v.kind = WELD_VECBUILDER;
+            v.nvals = 1;
+            v.val_type[0] = type;
+            L.builders.push_back(v);
+            L.merge_of.push_back(-1);
+            const int nb = (int)L.builders.size() - 1;
+            if (m >= 0) {
+                weld_merge_t mg;
+                memset(&mg, 0, sizeof mg);
+                mg.builder = nb;
+                mg.pred = in.merges[m].pred;
+                mg.nvals = 1;
+                mg.val[0] = value_op;
+                L.merges.push_back(mg);
+                L.merge_of[nb] = (int)L.merges.size() - 1;
+            }
+            return nb;
+        };
+        for (int k = 0; k < g.nkeys; ++k) link.key_vec[k] = add_vec(g.key_type[k], m >= 0 ? in.merges[m].key[k] : -1);
+        link.val_vec = add_vec(g.val_type[0], m >= 0 ? in.merges[m].val[0] : -1);
+        links->push_back(link);
+    }
+    return L;
+}
+
+static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links, size_t user_builders, const ColRef* cols,
+                             int64_t n, const weld_conf_t& conf, weld_result* r, const void* prior_ctl);
+
 Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t& conf, weld_result* r,
                 const void* prior_ctl) {
+    std::vector<GroupLink> links;
+    const Loop X = expand_groups(L, &links);
+    if (X.builders.size() > 10) return mk(WELD_ERR_UNSUPPORTED, "too many builders once the groupbuilders are expanded (10 at most)");
+    return run_fused_plain(X, links, L.builders.size(), cols, n, conf, r, prior_ctl);
+}
+
+static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links, size_t user_builders, const ColRef* cols,
+                             int64_t n, const weld_conf_t& conf, weld_result* r, const void* prior_ctl) {
     hipStream_t stream = (hipStream_t)conf.stream;
     bool aligned = true;
     for (int c = 0; c < L.ncols; ++c)
@@ -148,7 +221,13 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
     // ---- one block: control words, per-builder workspace, results
     Layout lay;
     const size_t off_ctl = lay.take(kCtlBytes);
-    struct Off { size_t part = 0, res = 0, out = 0, desc = 0, keys = 0, vals[8] = {0}, okeys = 0, ovals = 0, log = 0, qcnt = 0; int64_t slots = 0, qcap = 0; };
+    struct Off { size_t part = 0, res = 0, out = 0, desc = 0, keys = 0, vals[8] = {0}, okeys = 0, ovals = 0, log = 0, qcnt = 0,
+                        slot_pos = 0, goffsets = 0, gcursor = 0, gvalues = 0; int64_t slots = 0, qcap = 0; };
+    auto link_of = [&](size_t b) -> const GroupLink* {
+        for (const GroupLink& g : links)
+            if ((size_t)g.dict == b) return &g;
+        return nullptr;
+    };
     std::vector<Off> off(NB);
     for (size_t b = 0; b < NB; ++b) {
         const weld_builder_spec_t& s = L.builders[b];
@@ -178,6 +257,12 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
                 for (int k = 0; k < s.nvals; ++k) vs += type_size(s.val_type[k]);
                 off[b].okeys = lay.take((size_t)s.capacity * ks);
                 off[b].ovals = lay.take((size_t)s.capacity * vs);
+                if (const GroupLink* g = link_of(b)) {      // second half of a groupbuilder
+                    off[b].slot_pos = lay.take(4 * (size_t)(slots + 1));
+                    off[b].goffsets = lay.take(8 * (size_t)(s.capacity + 1));
+                    off[b].gcursor = lay.take(8 * (size_t)s.capacity);
+                    off[b].gvalues = lay.take((size_t)n * type_size(L.builders[g->val_vec].val_type[0]));
+                }
             }
         }
     }
@@ -269,6 +354,12 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
     if (!prior_ctl && (h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     if ((h = launch_fill64(base + off_ctl, kCtlBytes / 8, 0, stream)) != hipSuccess) return hip_err("fill", h);
     r->kernel_count++;
+    for (const GroupLink& g : links) {
+        // pairs of a groupbuilder merged without a predicate: their number is n, known now
+        if (var.backend[g.val_vec] != BK_VEC_DIRECT || L.merge_of[g.val_vec] < 0) continue;
+        if ((h = launch_fill64(base + off_ctl + ctl_count_off(g.val_vec), 1, (uint64_t)n, stream)) != hipSuccess) return hip_err("fill", h);
+        r->kernel_count++;
+    }
     for (size_t b = 0; b < NB; ++b) {
         const weld_builder_spec_t& s = L.builders[b];
         if (var.backend[b] == BK_VEC_COMPACT && ntiles > 0) {
@@ -358,12 +449,53 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
             dl.val_stride += dl.val_size[k];
             dv.p[k] = (const unsigned long long*)(base + off[b].vals[k]);
         }
+        const GroupLink* g = link_of(b);
         h = launch_dict_extract(base + off[b].keys, base + off_ctl + ctl_hdr_off((int)b), off[b].slots, dv, dl, s.capacity,
                                 base + off[b].okeys, base + off[b].ovals, base + off_ctl + ctl_count_off((int)b),
-                                base + off_ctl + 8, stream);
+                                base + off_ctl + 8, g ? (int*)(base + off[b].slot_pos) : nullptr, stream);
         if (h != hipSuccess) return hip_err("dict extract", h);
         r->kernel_count++;
+        if (!g) continue;
+        // groupbuilder: group sizes -> offsets, then every compacted pair to its group's vector
+        h = launch_group_offsets(base + off[b].ovals, base + off_ctl + ctl_count_off((int)b), s.capacity,
+                                 base + off[b].goffsets, base + off[b].gcursor, stream);
+        if (h != hipSuccess) return hip_err("group offsets", h);
+        GroupScatter gs;
+        memset(&gs, 0, sizeof gs);
+        gs.npairs = (const unsigned long long*)(base + off_ctl + ctl_count_off(g->val_vec));
+        gs.nkeys = s.nkeys;
+        for (int k = 0; k < s.nkeys; ++k) {
+            gs.key[k] = base + off[g->key_vec[k]].out;
+            gs.key_size[k] = dl.key_size[k];
+            gs.key_shift[k] = dl.key_shift[k];
+        }
+        gs.value = base + off[g->val_vec].out;
+        gs.value_size = type_size(L.builders[g->val_vec].val_type[0]);
+        gs.table_keys = (const unsigned long long*)(base + off[b].keys);
+        gs.hdr = (const unsigned int*)(base + off_ctl + ctl_hdr_off((int)b));
+        gs.slots = off[b].slots;
+        gs.slot_pos = (const int*)(base + off[b].slot_pos);
+        gs.capacity = s.capacity;
+        gs.offsets = (const long long*)(base + off[b].goffsets);
+        gs.cursor = (unsigned long long*)(base + off[b].gcursor);
+        gs.values_out = base + off[b].gvalues;
+        int64_t gblocks = (n + 4095) / 4096;
+        if (gblocks > device_info().cus) gblocks = device_info().cus;
+        if (gblocks > 0) {
+            if ((h = launch_group_scatter(gs, (int)gblocks, stream)) != hipSuccess) return hip_err("group scatter", h);
+            r->kernel_count++;
+        }
+        r->kernel_count++;
+        BuilderResult& br = r->res[b];
+        br.kind = WELD_GROUPBUILDER;
+        br.groups.keys.ptr = base + off[b].okeys;
+        br.groups.offsets.ptr = base + off[b].goffsets;
+        br.groups.values.ptr = base + off[b].gvalues;
+        br.elem_size = gs.value_size;
+        br.ctl_index = (int)b;
+        br.ctl_index2 = g->val_vec;
     }
+    r->res.resize(user_builders);            // the vecbuilders of expanded groupbuilders are internal
     if (prior_ctl) {
         if ((h = launch_or_error(base + off_ctl, prior_ctl, stream)) != hipSuccess) return hip_err("error word", h);
         r->kernel_count++;
@@ -558,8 +690,14 @@ weld_status_t weld_result_status(weld_result_t* r) {
     for (size_t b = 0; b < r->res.size(); ++b) {
         BuilderResult& br = r->res[b];
         int64_t cnt;
-        memcpy(&cnt, (const char*)r->host_ctl + ctl_count_off((int)b), 8);
-        if (br.kind == WELD_VECBUILDER) {
+        memcpy(&cnt, (const char*)r->host_ctl + ctl_count_off(br.ctl_index >= 0 ? br.ctl_index : (int)b), 8);
+        if (br.kind == WELD_GROUPBUILDER) {
+            int64_t pairs;
+            memcpy(&pairs, (const char*)r->host_ctl + ctl_count_off(br.ctl_index2), 8);
+            br.groups.keys.len = cnt;
+            br.groups.offsets.len = cnt + 1;
+            br.groups.values.len = pairs;
+        } else if (br.kind == WELD_VECBUILDER) {
             br.vec.len = br.known_len >= 0 ? br.known_len : cnt;
         } else if (br.kind == WELD_DICTMERGER) {
             br.dict.keys.len = cnt;
@@ -577,6 +715,7 @@ const void* weld_result_data(weld_result_t* r, int32_t idx) {
     BuilderResult& br = r->res[idx];
     if (br.kind == WELD_MERGER) return br.scalar;
     if (br.kind == WELD_VECBUILDER) return &br.vec;
+    if (br.kind == WELD_GROUPBUILDER) return &br.groups;
     return &br.dict;
 }
 
@@ -590,6 +729,11 @@ weld_status_t weld_result_fetch(weld_result_t* r, int32_t idx, int32_t part, voi
     int64_t avail = 0;
     if (br.kind == WELD_MERGER) { src = (const char*)br.scalar; avail = br.elem_size; }
     else if (br.kind == WELD_VECBUILDER) { src = (const char*)br.vec.ptr; avail = br.vec.len * br.elem_size; }
+    else if (br.kind == WELD_GROUPBUILDER) {
+        if (part == 0) { src = (const char*)br.groups.keys.ptr; avail = br.groups.keys.len * br.key_stride; }
+        else if (part == 1) { src = (const char*)br.groups.offsets.ptr; avail = br.groups.offsets.len * 8; }
+        else { src = (const char*)br.groups.values.ptr; avail = br.groups.values.len * br.elem_size; }
+    }
     else if (part == 0) { src = (const char*)br.dict.keys.ptr; avail = br.dict.keys.len * br.key_stride; }
     else { src = (const char*)br.dict.values.ptr; avail = br.dict.values.len * br.val_stride; }
     if (offset + bytes > avail) return WELD_ERR_INVALID_ARG;
@@ -633,8 +777,10 @@ int64_t weld_generated_source(const int32_t* col_types, int32_t ncols, const wel
     Loop L;
     Error e = validate(col_types, ncols, body, builder, &L);
     if (!e.ok()) { set_last_error(e.text); return -1; }
-    Variant var = choose_variant(L, builder->conf.tune, true);
-    Generated G = generate(L, var);
+    std::vector<GroupLink> links;
+    const Loop X = expand_groups(L, &links);
+    Variant var = choose_variant(X, builder->conf.tune, true);
+    Generated G = generate(X, var);
     if (buf && buflen > 0) snprintf(buf, (size_t)buflen, "%s", G.source.c_str());
     return (int64_t)G.source.size() + 1;
 }
@@ -645,9 +791,11 @@ weld_status_t weld_precompile(const int32_t* col_types, int32_t ncols, const wel
     Error e = validate(col_types, ncols, body, builder, &L);
     if (!e.ok()) { set_last_error(e.text); return e.status; }
     if (builder->conf.mode != WELD_MODE_FUSED) return WELD_OK;  // unfused kernels are compiled ahead of time
+    std::vector<GroupLink> links;
+    const Loop X = expand_groups(L, &links);
     for (int aligned = 1; aligned >= 0; --aligned) {
-        Variant var = choose_variant(L, builder->conf.tune, aligned != 0);
-        Generated G = generate(L, var);
+        Variant var = choose_variant(X, builder->conf.tune, aligned != 0);
+        Generated G = generate(X, var);
         Kernel* k = nullptr;
         e = jit_get(G.source, G.kernel_name, false, &k);
         if (!e.ok()) { set_last_error(e.text); return e.status; }

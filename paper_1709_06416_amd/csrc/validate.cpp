@@ -167,6 +167,15 @@ Error validate(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
                 if (s.func < WELD_FUNC_ADD || s.func > WELD_FUNC_MAX) return fail(WELD_ERR_INVALID_ARG, "builder %d: unknown func %d", b, s.func);
                 if (s.capacity < 1 || s.capacity > (1ll << 30)) return fail(WELD_ERR_INVALID_ARG, "builder %d: capacity out of range", b);
                 break;
+            case WELD_GROUPBUILDER:
+                if (s.nkeys < 1 || s.nkeys > WELD_MAX_KEY_FIELDS) return fail(WELD_ERR_INVALID_ARG, "builder %d: groupbuilder needs 1..4 key fields", b);
+                if (s.nvals != 1) return fail(WELD_ERR_UNSUPPORTED, "builder %d: groupbuilder of a value struct (one scalar value is implemented)", b);
+                for (int k = 0; k < s.nkeys; ++k)
+                    if (!type_is_int(s.key_type[k])) return fail(WELD_ERR_UNSUPPORTED, "builder %d: key field %d must be an integer type", b, k);
+                if (key_bits(s) > 64) return fail(WELD_ERR_UNSUPPORTED, "builder %d: key struct wider than 64 bits", b);
+                if (!type_is_num(s.val_type[0])) return fail(WELD_ERR_TYPE, "builder %d: value has type %d", b, s.val_type[0]);
+                if (s.capacity < 1 || s.capacity > (1ll << 30)) return fail(WELD_ERR_INVALID_ARG, "builder %d: capacity out of range", b);
+                break;
             case WELD_VECMERGER:
                 if (s.nvals != 1 || s.nkeys != 1) return fail(WELD_ERR_INVALID_ARG, "builder %d: vecmerger takes {index, value}", b);
                 if (s.key_type[0] != WELD_I64) return fail(WELD_ERR_TYPE, "builder %d: vecmerger index must be i64", b);

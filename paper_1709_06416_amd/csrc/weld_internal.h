@@ -18,6 +18,9 @@ struct BuilderResult {
     int elem_size = 0;        // vecbuilder element / merger scalar size
     int key_stride = 0, val_stride = 0;
     int64_t known_len = -1;   // vecbuilder without predicate: n
+    weld_groups_t groups = {{0, nullptr}, {0, nullptr}, {0, nullptr}};   // groupbuilder
+    int ctl_index = -1;       // which length word of the control block belongs to this result (-1: its own index)
+    int ctl_index2 = -1;      // groupbuilder: the word holding the number of grouped values
 };
 
 struct weld_result {
@@ -70,6 +73,18 @@ struct Loop {
     int outer_type[WELD_MAX_COLS] = {0};
     bool outer_used[WELD_MAX_COLS] = {false};
 };
+
+// groupbuilder b of a loop, rewritten into builders the kernels know: a dictmerger that counts
+// the pairs of every key (it takes b's place), and, appended to the builder list, one
+// vecbuilder per key field and one for the value, all under b's predicate.
+struct GroupLink {
+    int dict = 0;                  // index of the counting dictmerger (= the groupbuilder's index)
+    int key_vec[WELD_MAX_KEY_FIELDS] = {0};
+    int val_vec = 0;
+};
+// Returns `loop` with every groupbuilder rewritten that way (links in builder order); a loop
+// without groupbuilders comes back unchanged.
+Loop expand_groups(const Loop& loop, std::vector<GroupLink>* links);
 
 // What the body of an inner loop may refer to besides its own zipped vectors.
 struct NestedContext {

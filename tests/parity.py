@@ -46,6 +46,19 @@ def assert_matches(prog, res, want, map_floor=0.0, label=""):
                 assert np.all(np.abs(got - want[b]) <= SUM_RTOL * scale), tag
             else:
                 assert np.array_equal(got, want[b]), tag
+        elif spec["kind"] == "groupbuilder":
+            # groups and the values inside a group come back in no particular order: compare the
+            # groups sorted by key and every group's values as a sorted list (values are moved,
+            # never computed with: bit-exact)
+            keys, offsets, values = res.groups(b, sort=True)
+            wkeys, woff, wvals = want[b]
+            assert len(keys[0]) == len(wkeys[0]), (tag, len(keys[0]), len(wkeys[0]))
+            for g, w in zip(keys, wkeys):
+                assert np.array_equal(g, w), tag + " keys"
+            assert np.array_equal(offsets, woff), tag + " group sizes"
+            gid = np.repeat(np.arange(len(woff) - 1), np.diff(woff))
+            wsorted = wvals[np.lexsort((wvals, gid))]
+            assert np.array_equal(values.view(np.uint8), wsorted.view(np.uint8)), tag + " values"
         elif spec["kind"] == "vecbuilder":
             got = res.vec_host(b)
             assert len(got) == len(want[b]), (tag, len(got), len(want[b]))

@@ -593,3 +593,62 @@ def test_lazy_groupby_and_materialised_vector(wb):
     want_vec = ((host[4] * (1.0 - host[5])) * (1.0 + host[6]))[m]
     assert np.array_equal(res.vec_host(1), want_vec)      # order-preserving, bit-exact
     res.free()
+
+
+# ----------------------------------------------------------------------
+# groupbuilder (Table 1): dict[K, vec[V]]
+# ----------------------------------------------------------------------
+def _group_on_c5(capacity=100_000):
+    p = Program(["i64"])
+    c = p.col(0)
+    pred = p.bin("gt", c, p.const("i64", 0))
+    key = p.bin("mod", c, p.const("i64", 100_000))
+    p.merge(p.groupbuilder(["i64"], "i64", capacity), c, keys=[key], pred=pred)
+    return p
+
+
+@pytest.mark.parametrize("n", [0, 1, 63, 4096, 4097, 300_007])
+def test_groupbuilder_on_the_zip_code_column(wb, n):
+    cols = configs.make_columns("C5", n, device="cuda")
+    _check(wb, _group_on_c5(), cols, label="groups %d" % n)
+
+
+@pytest.mark.parametrize("t", ["i8", "i32", "i64", "f64"])
+def test_groupbuilder_struct_keys_value_types_and_other_builders(wb, t):
+    rnd = np.random.RandomState(31)
+    n = 150_001
+    k1 = rnd.randint(-2, 3, size=n).astype(np.int8)
+    k2 = (rnd.zipf(1.5, size=n) % 3000).astype(np.int32) * 7
+    v = (rnd.uniform(-5, 5, size=n) if t == "f64" else rnd.randint(-100, 100, size=n)).astype(
+        {"i8": np.int8, "i32": np.int32, "i64": np.int64, "f64": np.float64}[t])
+    p = Program(["i8", "i32", t])
+    pred = p.bin("ne", p.col(1), p.const("i32", 14))
+    p.merge(p.merger("i64", "add"), p.un("cast", p.col(1), to="i64"))
+    p.merge(p.groupbuilder(["i8", "i32"], t, 20_000), p.col(2), keys=[p.col(0), p.col(1)], pred=pred)
+    p.merge(p.vecbuilder(t), p.col(2), pred=pred)
+    _check(wb, p, [_dev(k1), _dev(k2), _dev(v)], label="groups " + t)
+
+
+def test_groupbuilder_one_group_all_distinct_and_the_marker_key(wb):
+    n = 50_000
+    x = np.arange(n, dtype=np.int64) * 3 - 70_000
+    p = Program(["i64"])
+    p.merge(p.groupbuilder(["i64"], "i64", 4), p.col(0), keys=[p.const("i64", 5)])
+    _check(wb, p, [_dev(x)], label="one group")
+    q = Program(["i64"])
+    q.merge(q.groupbuilder(["i64"], "i64", n), q.col(0), keys=[q.col(0)])
+    _check(wb, q, [_dev(x)], label="all distinct")
+    lo = np.iinfo(np.int64).min
+    keys = np.array([lo, lo + 1, -1, 0, lo, 5, lo] * 300, dtype=np.int64)
+    vals = np.arange(len(keys), dtype=np.int64)
+    r = Program(["i64", "i64"])
+    r.merge(r.groupbuilder(["i64"], "i64", 16), r.col(1), keys=[r.col(0)])
+    _check(wb, r, [_dev(keys), _dev(vals)], label="marker key")
+
+
+def test_groupbuilder_capacity_error_and_unfused_mode(wb):
+    cols = configs.make_columns("C5", 100_003, device="cuda")
+    res = _run(wb, _group_on_c5(capacity=100), cols)
+    assert res.status() == wb.ERR_CAPACITY
+    res.free()
+    _check(wb, _group_on_c5(), cols, label="groups unfused", mode="unfused")
