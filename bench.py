@@ -242,6 +242,29 @@ def main():
                   "algorithmic_GBps": round(alg / median(it_ms) / 1e6, 1), "rank_sum_after_one_iteration": total,
                   "spmv_ms": round(median(sp_ms), 4), "spmv_edges_per_s": ne / median(sp_ms) * 1e3}
 
+    # ---- groupbuilder: the zip-code column grouped by its key (values = the codes themselves)
+    groups = None
+    if not args.no_nested and "C5" in names:
+        from workloads.ir import Program
+        gcols = configs.make_columns("C5", rows["C5"], device="cuda")
+        gp = Program(["i64"])
+        c0 = gp.col(0)
+        gp.merge(gp.groupbuilder(["i64"], "i64", 100_000), c0, keys=[gp.bin("mod", c0, gp.const("i64", 100_000))],
+                 pred=gp.bin("gt", c0, gp.const("i64", 0)))
+        ts, npairs, ngroups = [], 0, 0
+        for i in range(args.warmup + 5):
+            r = wb.fused_for(gp, gcols).check()
+            if i >= args.warmup:
+                ts.append(r.elapsed_ms())
+            if i == 0:
+                gk, go, gv = r.groups(0, sort=False)
+                npairs, ngroups = int(len(gv)), int(len(gk[0]))
+                assert int(go[-1]) == npairs
+            r.free()
+        groups = {"workload": "groupbuilder over the zip-code column", "rows": rows["C5"], "pairs": npairs,
+                  "groups": ngroups, "call_ms": round(median(ts), 4), "pairs_per_s": npairs / median(ts) * 1e3}
+        del gcols
+
     line = {
         "metric": "fused-loop input GB/s (all five configs back to back)", "value": round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -255,6 +278,8 @@ def main():
         line["vecmerger_sweep"] = sweep
     if nested is not None:
         line["nested_loop"] = nested
+    if groups is not None:
+        line["groupbuilder"] = groups
     print(json.dumps(line))
 
 

@@ -480,7 +480,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         gs.cursor = (unsigned long long*)(base + off[b].gcursor);
         gs.values_out = base + off[b].gvalues;
         int64_t gblocks = (n + 4095) / 4096;
-        if (gblocks > device_info().cus) gblocks = device_info().cus;
+        if (gblocks > 2 * device_info().cus) gblocks = 2 * device_info().cus;     // two work-groups fit a CU (64 KiB of LDS each)
         if (gblocks > 0) {
             if ((h = launch_group_scatter(gs, (int)gblocks, stream)) != hipSuccess) return hip_err("group scatter", h);
             r->kernel_count++;

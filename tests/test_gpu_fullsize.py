@@ -165,3 +165,24 @@ def test_pagerank_full_size_sampled_vertices_and_rank_conservation(wb):
     assert abs(total - float(new_rank.sum().item())) <= 1e-9 * total
     kept = float(rank[outdeg > 0].sum().item())
     assert abs(total - (graphs.DAMPING * kept + (1.0 - graphs.DAMPING))) <= 1e-9 * total
+
+
+def test_groupbuilder_full_size_on_the_zip_code_column(wb):
+    """groupbuilder over the 1e8-row zip-code column (9e7 pairs, 1e5 groups): the oracle produces
+    the whole result; groups are compared sorted by key, each group's values as a sorted list
+    (both orders are free)."""
+    from oracle import interp
+    n = configs.FULL_ROWS["C5"]
+    cols = configs.make_columns("C5", n, device="cuda")
+    p = Program(["i64"])
+    c = p.col(0)
+    pred = p.bin("gt", c, p.const("i64", 0))
+    key = p.bin("mod", c, p.const("i64", 100_000))
+    p.merge(p.groupbuilder(["i64"], "i64", 100_000), c, keys=[key], pred=pred)
+    res = wb.fused_for(p, cols).check()
+    keys, offsets, values = res.groups(0, sort=True)
+    res.free()
+    wkeys, woff, wvals = interp.run(p, _host(cols))[0]
+    assert np.array_equal(keys[0], wkeys[0]) and np.array_equal(offsets, woff)
+    gid = np.repeat(np.arange(len(woff) - 1), np.diff(woff))
+    assert np.array_equal(values, wvals[np.lexsort((wvals, gid))])
