@@ -51,7 +51,9 @@ typedef enum {
 typedef enum { WELD_BOOL = 0, WELD_I8 = 1, WELD_I32 = 2, WELD_I64 = 3, WELD_F64 = 4 } weld_type_t;
 
 /* Expression operators of the loop body (Sec. 3.2: arithmetic, comparisons, select;
- * exp/log/sqrt/erf are the math operators the Black-Scholes workload of Sec. 7.1 needs).
+ * exp/log/sqrt/erf are the math operators the Black-Scholes workload of Sec. 7.1 needs;
+ * exp and log come from the device math library, erf is evaluated by the library itself:
+ * a piecewise polynomial, within 1e-15 relative of the correctly rounded value).
  * Integers wrap modulo 2^w; integer DIV and MOD truncate toward zero; f64 is IEEE
  * round-to-nearest with one rounding per operator (no contraction). */
 typedef enum {
@@ -168,7 +170,8 @@ typedef struct {
     int32_t dict_spill;         /* merges that miss such an LDS table: -1 = device atomics on the global
                                    table; otherwise they are appended to key-partitioned queues that a
                                    second kernel aggregates in LDS (> 0: entries per queue segment,
-                                   0 = sized so that no merge can overflow a segment)               */
+                                   0 = sized for the case that every row misses; a full segment
+                                   sends its merges to the global table)                            */
 } weld_tuning_t;
 
 typedef struct {
