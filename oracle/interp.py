@@ -75,7 +75,16 @@ def _trunc_div(a, b):
     return (a - r) // b
 
 
-def eval_columns(program, columns, n=None, gather=None, outer=None, inner=None):
+def _probe(table, key_cols):
+    """Position of each probed key struct in a dictionary result `table` = (key columns, value
+    columns), -1 where the key is absent (a hash join's probe, written with a Python dict)."""
+    index = {key: pos for pos, key in enumerate(zip(*[c.tolist() for c in table[0]]))}
+    n = len(key_cols[0]) if key_cols else 0
+    probe = zip(*[c.tolist() for c in key_cols])
+    return np.fromiter((index.get(key, -1) for key in probe), dtype=np.int64, count=n)
+
+
+def eval_columns(program, columns, n=None, gather=None, outer=None, inner=None, dicts=None):
     """Materialise every body expression as a full column (one operator at a time).
 
     gather / outer / inner give meaning to the operators of nested loops: the vectors
@@ -93,13 +102,20 @@ def eval_columns(program, columns, n=None, gather=None, outer=None, inner=None):
             code, t = op[0], op[1]
             dt = NP_TYPE[t]
             a = ([val[j] for j in op[2:]]
-                 if code not in ("col", "const", "index", "lookup", "outer", "inner") else None)
+                 if code not in ("col", "const", "index", "lookup", "outer", "inner", "keyexists", "dictlookup")
+                 else None)
             if code == "col":
                 out = columns[op[2]]
             elif code == "lookup":
                 vec, idx = gather[op[2]], val[op[3]].astype(np.int64)
                 assert idx.size == 0 or (idx.min() >= 0 and idx.max() < len(vec)), "lookup out of range"
                 out = vec[idx]
+            elif code == "keyexists":
+                out = _probe(dicts[op[2]], [val[j] for j in op[3:]]) >= 0
+            elif code == "dictlookup":
+                pos = _probe(dicts[op[2]], [val[j] for j in op[4:]])
+                field = dicts[op[2]][1][op[3]]
+                out = np.where(pos >= 0, field[np.maximum(pos, 0)] if len(field) else dt(0), dt(0)).astype(dt)
             elif code == "outer":
                 out = outer[op[2]]
             elif code == "inner":
@@ -253,7 +269,7 @@ def _vecmerge(spec, init, idx, v):
     return out
 
 
-def run(program, columns, sums="exact", inits=None):
+def run(program, columns, sums="exact", inits=None, dicts=None):
     """Evaluate the loop; returns one result per builder, in builder order.
 
     merger      -> numpy scalar of its type
@@ -263,11 +279,14 @@ def run(program, columns, sums="exact", inits=None):
     vecmerger   -> 1-d numpy array (inits: {builder index: initial vector})
     groupbuilder-> (list of key columns sorted by key, offsets, values)
 
+    dicts: the dictionaries `keyexists` / `dictlookup` probe, each the (key columns, value
+    columns) result of an earlier `run` (a hash join's build side).
+
     sums = "exact": an f64 `add` returns the correctly rounded real sum (any
     merge order is legal, Sec. 3.2, so this is the value every order
     approximates);  sums = "fold": the literal left-to-right f64 fold.
     """
-    val = eval_columns(program, columns)
+    val = eval_columns(program, columns, dicts=dicts)
     n = len(columns[0]) if columns else 0
     return _results(program, val, n, sums, inits)
 

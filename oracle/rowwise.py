@@ -117,7 +117,7 @@ def _typed(x, t):
     return float(x) if t == "f64" else (bool(x) if t == "bool" else int(x))
 
 
-def _body(program, i, elem, gather=None, outer_elem=None, inner_value=None):
+def _body(program, i, elem, gather=None, outer_elem=None, inner_value=None, dicts=None):
     """Every expression of the body for ONE row: index i, `elem` = this row's element of each
     zipped vector.  Nested loops: `gather` are the vectors lookup may read, `outer_elem` the
     current outer element (inner bodies), `inner_value` the inner loop's result (outer bodies)."""
@@ -136,6 +136,11 @@ def _body(program, i, elem, gather=None, outer_elem=None, inner_value=None):
             ix = val[op[3]]
             assert 0 <= ix < len(gather[op[2]]), "lookup out of range"
             val.append(_typed(gather[op[2]][ix], t))
+        elif code == "keyexists":
+            val.append(tuple(val[j] for j in op[3:]) in dicts[op[2]])
+        elif code == "dictlookup":
+            entry = dicts[op[2]].get(tuple(val[j] for j in op[4:]))
+            val.append(_typed(entry[op[3]] if entry is not None else 0, t))
         elif code == "outer":
             val.append(_typed(outer_elem[op[2]], t))
         elif code == "inner":
@@ -163,10 +168,12 @@ def run_nested(nested, outer_columns, inner_columns, gather):
     return run(nested.outer, outer_columns, inner_results=inner_results)
 
 
-def run(program, columns, inits=None, inner_results=None):
+def run(program, columns, inits=None, inner_results=None, dicts=None):
     """columns: list of Python lists (ints / floats).  Returns Python values:
     merger -> number, vecbuilder -> list, dictmerger -> {key tuple: [values]},
-    vecmerger -> list (inits: {builder index: list}), groupbuilder -> {key tuple: list of values}."""
+    vecmerger -> list (inits: {builder index: list}), groupbuilder -> {key tuple: list of values}.
+    dicts: dictionaries probed by keyexists / dictlookup, each {key tuple: [values]} as returned
+    for a dictmerger by an earlier run."""
     n = len(columns[0]) if columns else 0
     state = []
     for b, spec in enumerate(program.builders):
@@ -184,7 +191,7 @@ def run(program, columns, inits=None, inner_results=None):
             state.append({})
     for i in range(n):
         val = _body(program, i, [c[i] for c in columns],
-                    inner_value=None if inner_results is None else inner_results[i])
+                    inner_value=None if inner_results is None else inner_results[i], dicts=dicts)
         for m in program.merges:
             if m["pred"] is not None and not val[m["pred"]]:
                 continue                            # `else b`: builder returned untouched

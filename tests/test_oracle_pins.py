@@ -578,3 +578,62 @@ def test_groupbuilder_relations_to_the_other_builders():
     r.merge(r.groupbuilder(["i64"], "i64", 30_000), r.col(0), keys=[r.index()])
     gk, off, vals = interp.run(r, [code])[0]
     assert np.array_equal(gk[0], np.arange(len(code))) and np.array_equal(off, np.arange(len(code) + 1)) and np.array_equal(vals, code)
+
+
+# ----------------------------------------------------------------------
+# dictionaries as inputs of a later loop: keyexists / dictlookup (a hash join's probe side)
+# ----------------------------------------------------------------------
+def _join_programs():
+    """build: dict[{i32 id} -> {i64 weight, f64 price}] over the build side's rows with id % 3 != 0;
+    probe: rows whose id is in the dictionary contribute price * qty to a sum and are grouped
+    by the looked-up weight."""
+    b = Program(["i32", "i64", "f64"])
+    b.merge(b.dictmerger(["i32"], ["i64", "f64"], "add", 1000), [b.col(1), b.col(2)], keys=[b.col(0)],
+            pred=b.bin("ne", b.bin("mod", b.col(0), b.const("i32", 3)), b.const("i32", 0)))
+    p = Program(["i32", "f64"], dicts=[{"key_types": ["i32"], "val_types": ["i64", "f64"]}])
+    hit = p.keyexists(0, [p.col(0)])
+    w = p.dictlookup(0, 0, [p.col(0)])
+    price = p.dictlookup(0, 1, [p.col(0)])
+    p.merge(p.merger("f64", "add"), p.bin("mul", price, p.col(1)), pred=hit)
+    p.merge(p.dictmerger(["i64"], ["i64"], "add", 64), [p.const("i64", 1)], keys=[w], pred=hit)
+    p.merge(p.vecbuilder("i64"), w)                                     # absent keys look up 0
+    return b, p
+
+
+def test_dictionary_probe_hand_worked_example():
+    b, p = _join_programs()
+    ids = np.array([1, 2, 3, 4, 2], dtype=np.int32)                     # id 3 is filtered out, id 2 occurs twice
+    weight = np.array([10, 20, 30, 40, 5], dtype=np.int64)
+    price = np.array([1.0, 2.0, 3.0, 4.0, 0.5])
+    table = interp.run(b, [ids, weight, price])[0]
+    assert table[0][0].tolist() == [1, 2, 4] and table[1][0].tolist() == [10, 25, 40] and table[1][1].tolist() == [1.0, 2.5, 4.0]
+    probe_ids = np.array([2, 3, 9, 4, 2, 1], dtype=np.int32)
+    qty = np.array([1.0, 1.0, 1.0, 2.0, 3.0, 10.0])
+    total, (gk, gv), looked = interp.run(p, [probe_ids, qty], dicts=[table])
+    assert float(total) == 2.5 * 1 + 4.0 * 2 + 2.5 * 3 + 1.0 * 10
+    assert gk[0].tolist() == [10, 25, 40] and gv[0].tolist() == [1, 2, 1]
+    assert looked.tolist() == [25, 0, 0, 40, 25, 10]
+
+
+def test_dictionary_probe_against_per_row_loop_and_pandas_merge():
+    import pandas as pd
+    rnd = np.random.RandomState(8)
+    b, p = _join_programs()
+    nb, npr = 900, 3000
+    ids = rnd.randint(0, 700, size=nb).astype(np.int32)
+    weight = rnd.randint(0, 20, size=nb).astype(np.int64)
+    price = rnd.randint(1, 9, size=nb).astype(np.float64)
+    table = interp.run(b, [ids, weight, price])[0]
+    table_rows = rowwise.run(b, [ids.tolist(), weight.tolist(), price.tolist()])[0]
+    probe_ids = rnd.randint(0, 800, size=npr).astype(np.int32)
+    qty = rnd.randint(1, 5, size=npr).astype(np.float64)
+    total, (gk, gv), looked = interp.run(p, [probe_ids, qty], dicts=[table])
+    w_total, w_groups, w_looked = rowwise.run(p, [probe_ids.tolist(), qty.tolist()], dicts=[table_rows])
+    assert float(total) == w_total and looked.tolist() == w_looked
+    assert dict(zip(gk[0].tolist(), gv[0].tolist())) == {k[0]: v[0] for k, v in w_groups.items()}
+    # the same join with a library: aggregate the build side, inner-merge, aggregate
+    keep = ids % 3 != 0
+    build = pd.DataFrame({"id": ids[keep], "w": weight[keep], "price": price[keep]}).groupby("id", as_index=False).sum()
+    joined = pd.DataFrame({"id": probe_ids, "qty": qty}).merge(build, on="id", how="inner")
+    assert float(total) == float((joined["price"] * joined["qty"]).sum())
+    assert joined.groupby("w").size().to_dict() == dict(zip(gk[0].tolist(), gv[0].tolist()))

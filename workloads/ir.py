@@ -25,6 +25,10 @@ A `Program` holds
                         the current OUTER element of that vector
              'inner' -> args = ()   outer body of a nested loop: the result of this
                         outer element's inner loop
+             'keyexists' -> args = (dict_index, *key_values)   whether a dictionary that an
+                        earlier loop built (an input of this loop) holds the key struct
+             'dictlookup'-> args = (dict_index, value_field, *key_values)   that field of
+                        the key's value struct (0 if the key is absent)
            operand references are indices of earlier entries.
   builders : list of dicts
              {'kind': 'merger',     'type': T, 'func': f}
@@ -52,9 +56,12 @@ FUNCS = ("add", "mul", "min", "max")
 class Program:
     """Builder for the plain-data loop description (no evaluation here)."""
 
-    def __init__(self, columns, gather=(), outer=(), inner_type=None):
+    def __init__(self, columns, gather=(), outer=(), inner_type=None, dicts=()):
         for t in list(columns) + list(gather) + list(outer):
             assert t in TYPES, t
+        # dictionaries built by earlier loops that this loop may probe:
+        # [{'key_types': [...], 'val_types': [...]}, ...]
+        self.dicts = [dict(d) for d in dicts]
         self.columns = list(columns)
         self.gather = list(gather)        # element types of the vectors `lookup` may read
         self.outer_columns = list(outer)  # an inner body's view of the outer vectors
@@ -101,6 +108,14 @@ class Program:
     def lookup(self, k, idx):
         assert self.type_of(idx) in ("i8", "i32", "i64")
         return self._push(("lookup", self.gather[k], k, idx))
+
+    def keyexists(self, d, keys):
+        assert [self.type_of(k) for k in keys] == self.dicts[d]["key_types"]
+        return self._push(("keyexists", "bool", d) + tuple(keys))
+
+    def dictlookup(self, d, field, keys):
+        assert [self.type_of(k) for k in keys] == self.dicts[d]["key_types"]
+        return self._push(("dictlookup", self.dicts[d]["val_types"][field], d, field) + tuple(keys))
 
     def outer(self, k):
         return self._push(("outer", self.outer_columns[k], k))
