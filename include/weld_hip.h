@@ -218,6 +218,26 @@ typedef struct weld_result weld_result_t; /* opaque (the paper's WeldResult hand
 weld_status_t weld_fused_for(const weld_cols_t* cols, int64_t n, const weld_body_t* body,
                              const weld_builder_t* builder, weld_result_t** out);
 
+/*
+ * Dictionaries built by earlier calls as inputs of a loop: the probe side of a hash join
+ * (Sec. 3.1: dictionaries are the data type joins are implemented with).  The body may use
+ *   WELD_OP_KEYEXISTS : a = index into `dicts`, b (and c) = the key struct's fields; bool
+ *   WELD_OP_DICTLOOKUP: same operands, reserved = index of a value field; the field of that
+ *                       key's value struct, 0 if the key is absent
+ * on dictionaries of one or two key fields.  Each dictionary is the result of a dictmerger of
+ * an earlier weld_fused_for call: that call must have been enqueued on the same stream (or
+ * have finished), its handle must stay alive until this call's weld_result_status() has
+ * returned, and a build that failed (capacity) leaves a partial dictionary.  Fused mode only.
+ */
+enum { WELD_OP_KEYEXISTS = 29, WELD_OP_DICTLOOKUP = 30 };
+typedef struct {
+    weld_result_t* result; /* handle of the call that built the dictionary  */
+    int32_t builder;       /* index of a dictmerger among that call's builders */
+} weld_dict_ref_t;
+#define WELD_MAX_DICT_INPUTS 4
+weld_status_t weld_fused_for_probe(const weld_cols_t* cols, int64_t n, const weld_dict_ref_t* dicts, int32_t ndicts,
+                                   const weld_body_t* body, const weld_builder_t* builder, weld_result_t** out);
+
 /* Evaluation point: waits for the stream, reads back lengths and kernel-side error
  * flags.  WELD_OK, WELD_ERR_CAPACITY or WELD_ERR_DEVICE.  Idempotent. */
 weld_status_t weld_result_status(weld_result_t* r);

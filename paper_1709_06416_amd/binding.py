@@ -29,7 +29,8 @@ TORCH_TYPE = {v: k for k, v in TYPE_TORCH.items()}
 OPCODE = {"col": 0, "const": 1, "index": 2, "neg": 3, "not": 4, "cast": 5, "exp": 6, "log": 7, "sqrt": 8,
           "erf": 9, "add": 10, "sub": 11, "mul": 12, "div": 13, "mod": 14, "min": 15, "max": 16, "lt": 17,
           "le": 18, "gt": 19, "ge": 20, "eq": 21, "ne": 22, "and": 23, "or": 24, "select": 25,
-          "lookup": 26, "outer": 27, "inner": 28}      # the last three: include/weld_nested.h
+          "lookup": 26, "outer": 27, "inner": 28,      # these three: include/weld_nested.h
+          "keyexists": 29, "dictlookup": 30}
 KIND = {"merger": 0, "vecbuilder": 1, "dictmerger": 2, "vecmerger": 3, "groupbuilder": 4}
 FUNC = {"add": 0, "mul": 1, "min": 2, "max": 3}
 MODE = {"fused": 0, "unfused": 1}
@@ -101,6 +102,13 @@ class Groups(C.Structure):
 lib.weld_fused_for.argtypes = [C.POINTER(Cols), C.c_int64, C.POINTER(Body), C.POINTER(Builder),
                                C.POINTER(C.c_void_p)]
 lib.weld_fused_for.restype = C.c_int
+class DictRef(C.Structure):
+    _fields_ = [("result", C.c_void_p), ("builder", C.c_int32)]
+
+
+lib.weld_fused_for_probe.argtypes = [C.POINTER(Cols), C.c_int64, C.POINTER(DictRef), C.c_int32, C.POINTER(Body),
+                                     C.POINTER(Builder), C.POINTER(C.c_void_p)]
+lib.weld_fused_for_probe.restype = C.c_int
 lib.weld_result_status.argtypes = [C.c_void_p]
 lib.weld_result_status.restype = C.c_int
 lib.weld_result_error.argtypes = [C.c_void_p]
@@ -181,8 +189,17 @@ class Marshalled:
                     o.imm.f64 = float(op[2])
                 else:
                     o.imm.i64 = int(op[2])
+            elif op[0] == "dictlookup":                 # (dict, value field, key fields...)
+                o.a, o.reserved = int(op[2]), int(op[3])
+                keys = list(op[4:])
+                if len(keys) > 2:
+                    raise WeldError(ERR_UNSUPPORTED, "probes take dictionaries of one or two key fields")
+                o.b = int(keys[0])
+                o.c = int(keys[1]) if len(keys) > 1 else -1
             else:
                 args = list(op[2:])
+                if op[0] == "keyexists" and len(args) > 3:
+                    raise WeldError(ERR_UNSUPPORTED, "probes take dictionaries of one or two key fields")
                 if len(args) > 0:
                     o.a = int(args[0])
                 if len(args) > 1:
@@ -390,9 +407,11 @@ class Result:
             pass
 
 
-def fused_for(program, columns, mode="fused", stream=None, memory_limit=0, tune=None, n=None, inits=None):
+def fused_for(program, columns, mode="fused", stream=None, memory_limit=0, tune=None, n=None, inits=None, dicts=None):
     """weld_fused_for over torch CUDA tensors; returns a Result (work is only enqueued).
-    inits: {builder index: CUDA tensor} initial vectors of vecmergers."""
+    inits: {builder index: CUDA tensor} initial vectors of vecmergers.
+    dicts: [(Result, builder index), ...] dictionaries of earlier calls that the body probes
+    (weld_fused_for_probe); the Results are kept alive by the returned one."""
     if stream is None:
         stream = torch.cuda.current_stream().cuda_stream
     m = Marshalled(program, mode=mode, stream=stream, memory_limit=memory_limit, tune=tune, inits=inits)
@@ -415,10 +434,17 @@ def fused_for(program, columns, mode="fused", stream=None, memory_limit=0, tune=
         n = rows if rows is not None else 0
     cs = Cols(len(columns), cols)
     out = C.c_void_p()
-    st = lib.weld_fused_for(C.byref(cs), n, C.byref(m.body), C.byref(m.builder), C.byref(out))
+    if dicts:
+        refs = (DictRef * len(dicts))()
+        for k, (res, b) in enumerate(dicts):
+            refs[k].result = res._h
+            refs[k].builder = int(b)
+        st = lib.weld_fused_for_probe(C.byref(cs), n, refs, len(dicts), C.byref(m.body), C.byref(m.builder), C.byref(out))
+    else:
+        st = lib.weld_fused_for(C.byref(cs), n, C.byref(m.body), C.byref(m.builder), C.byref(out))
     if st != OK:
         raise WeldError(st, lib.weld_last_error().decode())
-    return Result(out, program, (m, cols, list(columns), inits))
+    return Result(out, program, (m, cols, list(columns), inits, dicts))
 
 
 def _col_array(tensors, types, what):

@@ -125,7 +125,8 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
     o.f("}\n\n");
     // ---- the body, one statement per IR operator
     o.f("__device__ __forceinline__ void weld_row(const i64 i");
-    if (segmented) o.f(", const i64 row, const KArgs& a, int* errp");
+    if (segmented) o.f(", const i64 row");
+    if (segmented || L.ndicts > 0) o.f(", const KArgs& a, int* errp");
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c]) o.f(", const %s x%d", stype(L.col_type[c]), c);
     o.f(", RowOut& o) {\n");
@@ -187,6 +188,19 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
             case WELD_OP_SELECT: o.f("t%d ? t%d : t%d", q.a, q.b, q.c); break;
             case WELD_OP_LOOKUP: o.f("w_lookup(a.g%d, a.g%d_len, (i64)t%d, errp)", q.a, q.a, q.b); break;
             case WELD_OP_OUTER: o.f("a.o%d[row]", q.a); break;
+            case WELD_OP_KEYEXISTS: case WELD_OP_DICTLOOKUP: {
+                const DictTable& t = L.dict_in[q.a];
+                std::string key = std::string("((u64)(") + utype(t.key_type[0]) + ")t" + std::to_string(q.b) + ")";
+                if (t.nkeys == 2)
+                    key += std::string(" | ((u64)(") + utype(t.key_type[1]) + ")t" + std::to_string(q.c) + " << " +
+                           std::to_string(8 * type_size(t.key_type[0])) + ")";
+                if (q.opcode == WELD_OP_KEYEXISTS)
+                    o.f("w_table_find(a.p%d_keys, a.p%d_hdr, a.p%d_slots, %s) >= 0", q.a, q.a, q.a, key.c_str());
+                else
+                    o.f("w_table_value<%s>(a.p%d_v%d, w_table_find(a.p%d_keys, a.p%d_hdr, a.p%d_slots, %s))", T, q.a, q.reserved,
+                        q.a, q.a, q.a, key.c_str());
+                break;
+            }
         }
         o.f(";\n");
     }
@@ -382,6 +396,15 @@ Generated generate(const Loop& L, const Variant& var) {
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c]) slot(SLOT_COL, c, 0, "c" + std::to_string(c), std::string("const ") + stype(L.col_type[c]) + "* __restrict__");
     slot(SLOT_CTL, -1, 0, "ctl", "u32*");
+    for (int d = 0; d < L.ndicts; ++d) {
+        const std::string P = "p" + std::to_string(d);
+        slot(SLOT_PKEYS, d, 0, P + "_keys", "const u64* __restrict__");
+        slot(SLOT_PHDR, d, 0, P + "_hdr", "const u32* __restrict__");
+        slot(SLOT_PSLOTS, d, 0, P + "_slots", "i64");
+        for (int k = 0; k < L.dict_in[d].nvals; ++k)
+            if (L.dict_val_used[d][k])
+                slot(SLOT_PVAL, d, k, P + "_v" + std::to_string(k), std::string("const ") + acc_ctype(L.dict_in[d].val_type[k]) + "* __restrict__");
+    }
     int ncompact = 0;
     for (size_t b = 0; b < NB; ++b) {
         const weld_builder_spec_t& s = L.builders[b];
@@ -582,6 +605,7 @@ Generated generate(const Loop& L, const Variant& var) {
         // fmt_col is a printf format taking the column number
         std::string c = "weld_row(";
         c += idx;
+        if (L.ndicts > 0) c += ", a, errp";
         for (int k = 0; k < L.ncols; ++k)
             if (L.col_used[k]) {
                 char buf[96];

@@ -324,6 +324,26 @@ __device__ __forceinline__ i64 w_table_slot(u64* keys, u32* hdr, i64 slots, u64 
     return -1;
 }
 
+// Read-only probe of a table that an earlier loop built (the probe side of a hash join):
+// the slot of `kbits`, or -1 if the key is absent.
+__device__ __forceinline__ i64 w_table_find(const u64* __restrict__ keys, const u32* __restrict__ hdr, i64 slots, u64 kbits) {
+    if (kbits == W_EMPTY_KEY) return hdr[1] ? slots : -1;
+    const i64 mask = slots - 1;
+    i64 s = (i64)w_hash_slot(kbits, (u32)slots);
+    for (i64 probe = 0; probe < slots; ++probe) {
+        const u64 cur = keys[s];
+        if (cur == kbits) return s;
+        if (cur == W_EMPTY_KEY) return -1;
+        s = (s + 1) & mask;
+    }
+    return -1;
+}
+// one field of the value struct found there (cells are 8 bytes: i64 or double accumulators)
+template <class T, class A>
+__device__ __forceinline__ T w_table_value(const A* __restrict__ cells, i64 slot) {
+    return slot >= 0 ? (T)cells[slot] : (T)0;
+}
+
 // Work-group private table in LDS: same scheme, at most `max_probe` probes; -1 means
 // "no room here", and the caller sends that merge to the global table instead.
 __device__ __forceinline__ int w_lds_slot(u64* keys, int slots, u64 kbits, int max_probe) {

@@ -179,18 +179,19 @@ Loop expand_groups(const Loop& in, std::vector<GroupLink>* links) {
 }
 
 static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links, size_t user_builders, const ColRef* cols,
-                             int64_t n, const weld_conf_t& conf, weld_result* r, const void* prior_ctl);
+                             int64_t n, const weld_conf_t& conf, weld_result* r, const void* prior_ctl, const DictTable* tables);
 
 Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t& conf, weld_result* r,
-                const void* prior_ctl) {
+                const void* prior_ctl, const DictTable* tables) {
     std::vector<GroupLink> links;
     const Loop X = expand_groups(L, &links);
     if (X.builders.size() > 10) return mk(WELD_ERR_UNSUPPORTED, "too many builders once the groupbuilders are expanded (10 at most)");
-    return run_fused_plain(X, links, L.builders.size(), cols, n, conf, r, prior_ctl);
+    if (L.ndicts > 0 && !tables) return mk(WELD_ERR_INVALID_ARG, "the loop probes dictionaries but none were passed");
+    return run_fused_plain(X, links, L.builders.size(), cols, n, conf, r, prior_ctl, tables);
 }
 
 static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links, size_t user_builders, const ColRef* cols,
-                             int64_t n, const weld_conf_t& conf, weld_result* r, const void* prior_ctl) {
+                             int64_t n, const weld_conf_t& conf, weld_result* r, const void* prior_ctl, const DictTable* tables) {
     hipStream_t stream = (hipStream_t)conf.stream;
     bool aligned = true;
     for (int c = 0; c < L.ncols; ++c)
@@ -321,6 +322,16 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             for (int k = 0; k < s.nvals; ++k) br.val_stride += type_size(s.val_type[k]);
             br.dict.keys.ptr = base + off[b].okeys;
             br.dict.values.ptr = base + off[b].ovals;
+            br.table.keys = base + off[b].keys;
+            br.table.hdr = base + off_ctl + ctl_hdr_off((int)b);
+            br.table.slots = off[b].slots;
+            br.table.nkeys = s.nkeys;
+            br.table.nvals = s.nvals;
+            for (int k = 0; k < s.nkeys; ++k) br.table.key_type[k] = s.key_type[k];
+            for (int k = 0; k < s.nvals; ++k) {
+                br.table.val_type[k] = s.val_type[k];
+                br.table.vals[k] = base + off[b].vals[k];
+            }
         }
     }
 
@@ -345,6 +356,11 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             case SLOT_DLOG: v = (uint64_t)(uintptr_t)(base + off[b].log); break;
             case SLOT_DQCNT: v = (uint64_t)(uintptr_t)(base + off[b].qcnt); break;
             case SLOT_DQCAP: v = (uint64_t)off[b].qcap; break;
+            case SLOT_PKEYS: v = (uint64_t)(uintptr_t)tables[b].keys; break;
+            case SLOT_PHDR: v = (uint64_t)(uintptr_t)tables[b].hdr; break;
+            case SLOT_PSLOTS: v = (uint64_t)tables[b].slots; break;
+            case SLOT_PVAL: v = (uint64_t)(uintptr_t)tables[b].vals[s.field]; break;
+            default: break;
         }
         args.push_back(v);
     }
@@ -651,6 +667,59 @@ weld_status_t weld_fused_for(const weld_cols_t* cols, int64_t n, const weld_body
     for (int c = 0; c < cols->ncols; ++c) { refs[c].data = cols->col[c].data; refs[c].type = cols->col[c].type; }
     e = builder->conf.mode == WELD_MODE_FUSED ? run_fused(L, refs, n, builder->conf, r)
                                               : run_unfused(L, refs, n, builder->conf, r);
+    if (!e.ok()) {
+        set_last_error(e.text);
+        destroy_result(r);
+        return e.status;
+    }
+    *out = r;
+    return WELD_OK;
+}
+
+weld_status_t weld_fused_for_probe(const weld_cols_t* cols, int64_t n, const weld_dict_ref_t* dicts, int32_t ndicts,
+                                   const weld_body_t* body, const weld_builder_t* builder, weld_result_t** out) {
+    if (out) *out = nullptr;
+    if (!cols || !body || !builder || !out) { set_last_error("null argument"); return WELD_ERR_INVALID_ARG; }
+    if (n < 0) { set_last_error("negative row count"); return WELD_ERR_INVALID_ARG; }
+    if (ndicts < 0 || ndicts > WELD_MAX_DICT_INPUTS || (ndicts > 0 && !dicts)) { set_last_error("bad dictionary list"); return WELD_ERR_INVALID_ARG; }
+    if (cols->ncols < 0 || cols->ncols > WELD_MAX_COLS || (cols->ncols > 0 && !cols->col)) {
+        set_last_error("bad column list");
+        return WELD_ERR_INVALID_ARG;
+    }
+    DictTable tables[WELD_MAX_DICT_INPUTS];
+    for (int d = 0; d < ndicts; ++d) {
+        const weld_result* src = dicts[d].result;
+        if (!src || dicts[d].builder < 0 || dicts[d].builder >= (int)src->res.size() ||
+            src->res[dicts[d].builder].kind != WELD_DICTMERGER || !src->res[dicts[d].builder].table.keys) {
+            set_last_error("dictionary input " + std::to_string(d) + " is not the dictmerger result of an earlier call");
+            return WELD_ERR_INVALID_ARG;
+        }
+        tables[d] = src->res[dicts[d].builder].table;
+    }
+    if (builder->conf.mode != WELD_MODE_FUSED) { set_last_error("loops that probe dictionaries run in fused mode only"); return WELD_ERR_UNSUPPORTED; }
+    NestedContext ctx;
+    ctx.ndicts = ndicts;
+    ctx.dict_in = tables;
+    int32_t types[WELD_MAX_COLS];
+    for (int c = 0; c < cols->ncols; ++c) types[c] = cols->col[c].type;
+    Loop L;
+    Error e = validate(types, cols->ncols, body, builder, &L, &ctx);
+    if (!e.ok()) { set_last_error(e.text); return e.status; }
+    for (int c = 0; c < cols->ncols; ++c) {
+        if (n > 0 && L.col_used[c] && !cols->col[c].data) { set_last_error("null column pointer"); return WELD_ERR_INVALID_ARG; }
+        if ((uintptr_t)cols->col[c].data % (uintptr_t)type_size(L.col_type[c])) {
+            set_last_error("column pointer not aligned to its element size");
+            return WELD_ERR_INVALID_ARG;
+        }
+    }
+    weld_result* r = new_result(builder->conf.stream);
+    if (!r) {
+        set_last_error("could not allocate pinned memory / events (no usable HIP device?)");
+        return WELD_ERR_DEVICE;
+    }
+    ColRef refs[WELD_MAX_COLS];
+    for (int c = 0; c < cols->ncols; ++c) { refs[c].data = cols->col[c].data; refs[c].type = cols->col[c].type; }
+    e = run_fused(L, refs, n, builder->conf, r, nullptr, tables);
     if (!e.ok()) {
         set_last_error(e.text);
         destroy_result(r);

@@ -37,6 +37,8 @@ Error validate(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
     L = Loop();
     L.ncols = ncols;
     if (inner_of) {
+        L.ndicts = inner_of->ndicts;
+        for (int d = 0; d < L.ndicts; ++d) L.dict_in[d] = inner_of->dict_in[d];
         L.ngather = inner_of->ngather;
         L.nouter = inner_of->nouter;
         for (int k = 0; k < L.ngather; ++k) L.gather_type[k] = inner_of->gather_type[k];
@@ -121,8 +123,25 @@ Error validate(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
                 if (ty(o.a) != WELD_BOOL || ty(o.b) != o.type || ty(o.c) != o.type)
                     return fail(WELD_ERR_TYPE, "op %d: select(bool, T, T) -> T", i);
                 break;
+            case WELD_OP_KEYEXISTS: case WELD_OP_DICTLOOKUP: {
+                if (o.a < 0 || o.a >= L.ndicts) return fail(WELD_ERR_INVALID_ARG, "op %d: dictionary %d is not an input of this loop", i, o.a);
+                const DictTable& t = L.dict_in[o.a];
+                if (t.nkeys > 2) return fail(WELD_ERR_UNSUPPORTED, "op %d: probes of dictionaries with more than two key fields", i);
+                if (!operand(o.b) || (t.nkeys == 2 && !operand(o.c)) || (t.nkeys == 1 && o.c != -1))
+                    return fail(WELD_ERR_INVALID_ARG, "op %d: one earlier op per key field of the dictionary", i);
+                if (ty(o.b) != t.key_type[0] || (t.nkeys == 2 && ty(o.c) != t.key_type[1]))
+                    return fail(WELD_ERR_TYPE, "op %d: key operands do not have the dictionary's key types", i);
+                if (o.opcode == WELD_OP_KEYEXISTS) {
+                    if (o.type != WELD_BOOL) return fail(WELD_ERR_TYPE, "op %d: keyexists yields bool", i);
+                } else {
+                    if (o.reserved < 0 || o.reserved >= t.nvals) return fail(WELD_ERR_INVALID_ARG, "op %d: value field %d not in the dictionary", i, o.reserved);
+                    if (o.type != t.val_type[o.reserved]) return fail(WELD_ERR_TYPE, "op %d: value field %d has type %d", i, o.reserved, t.val_type[o.reserved]);
+                    L.dict_val_used[o.a][o.reserved] = true;
+                }
+                break;
+            }
             case WELD_OP_LOOKUP:
-                if (!inner_of) return fail(WELD_ERR_UNSUPPORTED, "op %d: lookup is only implemented in the inner body of weld_nested_for", i);
+                if (!inner_of || (inner_of->ngather == 0 && inner_of->nouter == 0)) return fail(WELD_ERR_UNSUPPORTED, "op %d: lookup is only implemented in the inner body of weld_nested_for", i);
                 if (o.a < 0 || o.a >= L.ngather) return fail(WELD_ERR_INVALID_ARG, "op %d: gather vector %d not declared", i, o.a);
                 if (!operand(o.b)) return fail(WELD_ERR_INVALID_ARG, "op %d: operand %d is not an earlier op", i, o.b);
                 if (!type_is_int(ty(o.b))) return fail(WELD_ERR_TYPE, "op %d: lookup index must be an integer", i);
@@ -130,7 +149,7 @@ Error validate(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
                 L.gather_used[o.a] = true;
                 break;
             case WELD_OP_OUTER:
-                if (!inner_of) return fail(WELD_ERR_INVALID_ARG, "op %d: outer-element access outside an inner body", i);
+                if (!inner_of || inner_of->nouter == 0) return fail(WELD_ERR_INVALID_ARG, "op %d: outer-element access outside an inner body", i);
                 if (o.a < 0 || o.a >= L.nouter) return fail(WELD_ERR_INVALID_ARG, "op %d: outer column %d not declared", i, o.a);
                 if (o.type != L.outer_type[o.a]) return fail(WELD_ERR_TYPE, "op %d: outer column %d has type %d", i, o.a, L.outer_type[o.a]);
                 L.outer_used[o.a] = true;

@@ -10,6 +10,18 @@
 
 #include <hip/hip_runtime_api.h>
 
+// The open-addressing table a dictmerger leaves behind (device pointers into the result's
+// block), kept so that a later loop can probe it.
+struct DictTable {
+    const void* keys = nullptr;
+    const void* vals[WELD_MAX_VAL_FIELDS] = {nullptr};
+    const void* hdr = nullptr;
+    int64_t slots = 0;
+    int nkeys = 0, nvals = 0;
+    int key_type[WELD_MAX_KEY_FIELDS] = {0};
+    int val_type[WELD_MAX_VAL_FIELDS] = {0};
+};
+
 struct BuilderResult {
     int kind = 0;
     void* scalar = nullptr;   // merger: device pointer to the scalar
@@ -21,6 +33,7 @@ struct BuilderResult {
     weld_groups_t groups = {{0, nullptr}, {0, nullptr}, {0, nullptr}};   // groupbuilder
     int ctl_index = -1;       // which length word of the control block belongs to this result (-1: its own index)
     int ctl_index2 = -1;      // groupbuilder: the word holding the number of grouped values
+    DictTable table;          // dictmerger
 };
 
 struct weld_result {
@@ -72,6 +85,10 @@ struct Loop {
     int nouter = 0;
     int outer_type[WELD_MAX_COLS] = {0};
     bool outer_used[WELD_MAX_COLS] = {false};
+    // dictionaries of earlier calls that WELD_OP_KEYEXISTS / WELD_OP_DICTLOOKUP probe (types only)
+    int ndicts = 0;
+    DictTable dict_in[WELD_MAX_DICT_INPUTS];
+    bool dict_val_used[WELD_MAX_DICT_INPUTS][WELD_MAX_VAL_FIELDS] = {{false}};
 };
 
 // groupbuilder b of a loop, rewritten into builders the kernels know: a dictmerger that counts
@@ -88,6 +105,8 @@ Loop expand_groups(const Loop& loop, std::vector<GroupLink>* links);
 
 // What the body of an inner loop may refer to besides its own zipped vectors.
 struct NestedContext {
+    int ndicts = 0;                       // (also used alone, for a loop that probes dictionaries)
+    const DictTable* dict_in = nullptr;
     int ngather = 0;
     int gather_type[8] = {0};
     int nouter = 0;
@@ -145,7 +164,9 @@ enum SlotKind {
     SLOT_DKEYS, SLOT_DHDR, SLOT_DSLOTS, SLOT_DVAL,  // dictmerger
     SLOT_DLOG, SLOT_DQCNT, SLOT_DQCAP,              // dictmerger spill queues
     // flattened inner loop of a nested for
-    SLOT_N_OUTER, SLOT_GATHER, SLOT_GATHER_LEN, SLOT_OUTER_COL, SLOT_SEG_START, SLOT_TILE_ROW, SLOT_SUMS
+    SLOT_N_OUTER, SLOT_GATHER, SLOT_GATHER_LEN, SLOT_OUTER_COL, SLOT_SEG_START, SLOT_TILE_ROW, SLOT_SUMS,
+    // dictionaries probed by the body
+    SLOT_PKEYS, SLOT_PHDR, SLOT_PSLOTS, SLOT_PVAL
 };
 struct Slot {
     SlotKind kind;
@@ -195,8 +216,9 @@ struct ColRef {
 // prior_ctl: control block (device) of work already enqueued for the same result handle (the
 // flattened inner loop of a nested for).  When given, the handle's start and kernel events are
 // left to the caller and that block's error word is folded into this loop's.
+// tables: the loop.ndicts dictionaries the body probes.
 Error run_fused(const Loop& loop, const ColRef* cols, int64_t n, const weld_conf_t& conf, weld_result* r,
-                const void* prior_ctl = nullptr);
+                const void* prior_ctl = nullptr, const DictTable* tables = nullptr);
 // A validated nested loop: `inner` holds the inner body with its merger as builder 0, `outer`
 // the outer body in which the inner loop's result is column `outer.ncols - 1`.
 struct NestedLoop {

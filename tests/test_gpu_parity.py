@@ -652,3 +652,71 @@ def test_groupbuilder_capacity_error_and_unfused_mode(wb):
     assert res.status() == wb.ERR_CAPACITY
     res.free()
     _check(wb, _group_on_c5(), cols, label="groups unfused", mode="unfused")
+
+
+# ----------------------------------------------------------------------
+# dictionaries of earlier calls probed by a later loop (hash join: build, then probe)
+# ----------------------------------------------------------------------
+def _join_case(rnd, n_build, n_probe, two_keys):
+    kt = ["i32", "i8"] if two_keys else ["i32"]
+    b = Program(kt + ["i64", "f64"])
+    bk = [b.col(i) for i in range(len(kt))]
+    b.merge(b.dictmerger(kt, ["i64", "f64"], "add", max(64, n_build)), [b.col(len(kt)), b.col(len(kt) + 1)], keys=bk,
+            pred=b.bin("ne", b.bin("mod", b.col(0), b.const("i32", 3)), b.const("i32", 0)))
+    p = Program(kt + ["f64"], dicts=[{"key_types": kt, "val_types": ["i64", "f64"]}])
+    pk = [p.col(i) for i in range(len(kt))]
+    hit = p.keyexists(0, pk)
+    w = p.dictlookup(0, 0, pk)
+    price = p.dictlookup(0, 1, pk)
+    p.merge(p.merger("f64", "add"), p.bin("mul", price, p.col(len(kt))), pred=hit)
+    p.merge(p.dictmerger(["i64"], ["i64"], "add", 4096), [p.const("i64", 1)], keys=[w], pred=hit)
+    p.merge(p.vecbuilder("i64"), w)
+    p.merge(p.vecbuilder("f64"), price, pred=p.un("not", hit))
+    span = max(4, n_build)
+    mk = lambda m: [rnd.randint(-span, span, size=m).astype(np.int32)] + ([rnd.randint(-2, 3, size=m).astype(np.int8)] if two_keys else [])
+    build_cols = mk(n_build) + [rnd.randint(0, 50, size=n_build).astype(np.int64), rnd.randint(1, 9, size=n_build).astype(np.float64)]
+    probe_cols = mk(n_probe) + [rnd.randint(1, 5, size=n_probe).astype(np.float64)]
+    return b, p, build_cols, probe_cols
+
+
+@pytest.mark.parametrize("two_keys", [False, True])
+@pytest.mark.parametrize("n_build,n_probe", [(0, 1000), (1, 1), (5_000, 0), (5_000, 200_003), (150_000, 70_001)])
+def test_probe_of_a_dictionary_built_by_an_earlier_call(wb, n_build, n_probe, two_keys):
+    from oracle import interp
+    from tests import parity
+    rnd = np.random.RandomState(n_build + n_probe)
+    b, p, build_cols, probe_cols = _join_case(rnd, n_build, n_probe, two_keys)
+    table = interp.run(b, build_cols)[0]
+    want = interp.run(p, probe_cols, dicts=[table])
+    built = _run(wb, b, [_dev(c) for c in build_cols])            # not waited for: the probe is enqueued behind it
+    res = _run(wb, p, [_dev(c) for c in probe_cols], dicts=[(built, 0)])
+    try:
+        parity.assert_matches(p, res, want, label="probe %d %d" % (n_build, n_probe))
+        built.check()
+    finally:
+        res.free()
+        built.free()
+
+
+def test_probe_argument_errors(wb):
+    rnd = np.random.RandomState(1)
+    b, p, build_cols, probe_cols = _join_case(rnd, 100, 100, False)
+    built = _run(wb, b, [_dev(c) for c in build_cols]).check()
+    dev = [_dev(c) for c in probe_cols]
+    with pytest.raises(wb.WeldError) as e:                          # probe ops without a dictionary
+        _run(wb, p, dev)
+    assert e.value.status == wb.ERR_INVALID_ARG
+    other = _run(wb, configs.program_c1(), configs.make_columns("C1", 1000, device="cuda")).check()
+    with pytest.raises(wb.WeldError) as e:                          # a merger is not a dictionary
+        _run(wb, p, dev, dicts=[(other, 0)])
+    assert e.value.status == wb.ERR_INVALID_ARG
+    q = Program(["i64", "f64"], dicts=[{"key_types": ["i64"], "val_types": ["i64", "f64"]}])
+    q.merge(q.merger("i64", "add"), q.dictlookup(0, 0, [q.col(0)]))
+    with pytest.raises(wb.WeldError) as e:                          # i64 key against an i32-keyed dictionary
+        _run(wb, q, [_dev(np.zeros(10, np.int64)), _dev(np.zeros(10))], dicts=[(built, 0)])
+    assert e.value.status == wb.ERR_TYPE
+    with pytest.raises(wb.WeldError) as e:
+        _run(wb, p, dev, dicts=[(built, 0)], mode="unfused")
+    assert e.value.status == wb.ERR_UNSUPPORTED
+    other.free()
+    built.free()
