@@ -265,6 +265,31 @@ def main():
                   "groups": ngroups, "call_ms": round(median(ts), 4), "pairs_per_s": npairs / median(ts) * 1e3}
         del gcols
 
+    # ---- hash join shaped like TPC-H Q12: build a dictionary over `orders`, probe it from `lineitem`
+    join = None
+    if not args.no_nested:
+        from workloads import joins
+        no, nl = max(1, int(joins.ORDERS * args.scale)), max(1, int(joins.LINEITEMS * args.scale))
+        orders, lines = joins.make_tables(no, nl, device="cuda")
+        bp, pp = joins.program_build(no), joins.program_probe()
+        bms, pms = [], []
+        for i in range(args.warmup + 5):
+            built = wb.fused_for(bp, orders)
+            r = wb.fused_for(pp, lines, dicts=[(built, 0)]).check()
+            if i >= args.warmup:
+                bms.append(built.elapsed_ms())
+                pms.append(r.elapsed_ms())
+            if i == 0:
+                _, jv = r.dict(0)
+                matched = int(jv[0].sum() + jv[1].sum())
+            r.free()
+            built.free()
+        join = {"workload": "hash join shaped like TPC-H Q12", "orders": no, "lineitems": nl, "matched_lines": matched,
+                "build_ms": round(median(bms), 4), "probe_ms": round(median(pms), 4),
+                "build_rows_per_s": no / median(bms) * 1e3, "probe_rows_per_s": nl / median(pms) * 1e3,
+                "probe_input_GBps": round(14 * nl / median(pms) / 1e6, 1)}
+        del orders, lines
+
     line = {
         "metric": "fused-loop input GB/s (all five configs back to back)", "value": round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -280,6 +305,8 @@ def main():
         line["nested_loop"] = nested
     if groups is not None:
         line["groupbuilder"] = groups
+    if join is not None:
+        line["hash_join"] = join
     print(json.dumps(line))
 
 

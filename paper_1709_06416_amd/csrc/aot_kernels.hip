@@ -101,37 +101,74 @@ __global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, cons
                                                            DictValues vals, DictLayout lay, i64 capacity,
                                                            unsigned char* out_keys, unsigned char* out_vals,
                                                            u64* count, int* err, int* slot_pos) {
-    for (i64 s = (i64)blockIdx.x * 256 + threadIdx.x; s <= slots; s += (i64)gridDim.x * 256) {
-        const u64 kb = s < slots ? keys[s] : kEmptyKey;
-        const bool used = s < slots ? (kb != kEmptyKey) : (hdr[1] != 0);
-        if (!used) continue;
-        const u64 pos = atomicAdd(count, 1ull);
-        if (slot_pos) slot_pos[s] = (i64)pos < capacity ? (int)pos : -1;
-        if ((i64)pos >= capacity) {
-            atomicOr(err, 1);
-            continue;
+    // A work-group takes 2048 slots at a time (thread t: slots base + j * 256 + t), counts its
+    // occupied ones, reserves their output positions with ONE device atomic (a same-address atomic
+    // costs about 12 ns here, so one per entry would dominate large dictionaries) and hands
+    // them out by a prefix sum inside the work-group.
+    __shared__ u32 s_wave[4];
+    __shared__ u64 s_base;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const i64 total = slots + 1;                       // the extra slot holds the key equal to the free marker
+    for (i64 base = (i64)blockIdx.x * 2048; base < total; base += (i64)gridDim.x * 2048) {
+        u64 kb[8];
+        bool used[8];
+        u32 mine = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const i64 s = base + j * 256 + tid;
+            kb[j] = s < slots ? keys[s] : kEmptyKey;
+            used[j] = s < slots ? (kb[j] != kEmptyKey) : (s == slots && hdr[1] != 0);
+            mine += used[j] ? 1u : 0u;
         }
-        unsigned char* ko = out_keys + pos * lay.key_stride;
-        int off = 0;
-        for (int k = 0; k < lay.nkeys; ++k) {
-            const u64 field = kb >> lay.key_shift[k];
-            for (int b = 0; b < lay.key_size[k]; ++b) ko[off + b] = (unsigned char)(field >> (8 * b));
-            off += lay.key_size[k];
+        u32 incl = mine;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const u32 o = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += o;
         }
-        unsigned char* vo = out_vals + pos * lay.val_stride;
-        off = 0;
-        for (int k = 0; k < lay.nvals; ++k) {
-            const u64 bits = vals.p[k][s];
-            for (int b = 0; b < lay.val_size[k]; ++b) vo[off + b] = (unsigned char)(bits >> (8 * b));
-            off += lay.val_size[k];
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        u32 before = 0, all = 0;
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) before += s_wave[w];
+            all += s_wave[w];
         }
+        if (tid == 0) s_base = all ? atomicAdd(count, (u64)all) : 0;
+        __syncthreads();
+        u64 pos = s_base + before + incl - mine;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (!used[j]) continue;
+            const i64 s = base + j * 256 + tid;
+            const u64 at = pos++;
+            if (slot_pos) slot_pos[s] = (i64)at < capacity ? (int)at : -1;
+            if ((i64)at >= capacity) {
+                atomicOr(err, 1);
+                continue;
+            }
+            unsigned char* ko = out_keys + at * lay.key_stride;
+            int off = 0;
+            for (int k = 0; k < lay.nkeys; ++k) {
+                const u64 field = kb[j] >> lay.key_shift[k];
+                for (int b = 0; b < lay.key_size[k]; ++b) ko[off + b] = (unsigned char)(field >> (8 * b));
+                off += lay.key_size[k];
+            }
+            unsigned char* vo = out_vals + at * lay.val_stride;
+            off = 0;
+            for (int k = 0; k < lay.nvals; ++k) {
+                const u64 bits = vals.p[k][s];
+                for (int b = 0; b < lay.val_size[k]; ++b) vo[off + b] = (unsigned char)(bits >> (8 * b));
+                off += lay.val_size[k];
+            }
+        }
+        __syncthreads();                               // s_wave / s_base are reused by the next round
     }
 }
 
 hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots, const DictValues& vals,
                                const DictLayout& lay, int64_t capacity, void* out_keys, void* out_vals,
                                void* count, void* err, int* slot_pos, hipStream_t stream) {
-    int64_t blocks = (slots + 1 + 255) / 256;
+    int64_t blocks = (slots + 1 + 2047) / 2048;
     if (blocks > 2048) blocks = 2048;
     dict_extract_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
         (const u64*)keys, (const u32*)hdr, slots, vals, lay, capacity, (unsigned char*)out_keys,

@@ -123,6 +123,35 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
         o.f("\n");
     }
     o.f("}\n\n");
+    // ---- which predicate guards each value: an op that only feeds merges under one predicate
+    // (computed before it) is only needed on rows where that predicate holds.  Used for the
+    // operators that go to memory at a computed address (lookups, dictionary probes): they are
+    // skipped on the other rows, which never read their result.
+    const int kUnused = -1, kAlways = -2;
+    std::vector<int> need(L.ops.size(), kUnused);
+    auto mark = [&](int x, int g) {
+        if (x < 0) return;
+        if (need[x] == kUnused) need[x] = g;
+        else if (need[x] != g) need[x] = kAlways;
+    };
+    for (const weld_merge_t& g : L.merges) {
+        const int p = g.pred >= 0 ? g.pred : kAlways;
+        for (int k = 0; k < g.nkeys; ++k) mark(g.key[k], p);
+        for (int k = 0; k < g.nvals; ++k) mark(g.val[k], p);
+        if (g.pred >= 0) mark(g.pred, kAlways);
+    }
+    for (int i = (int)L.ops.size() - 1; i >= 0; --i) {
+        const weld_op_t& q = L.ops[i];
+        if (need[i] == kUnused || q.opcode == WELD_OP_COL || q.opcode == WELD_OP_CONST || q.opcode == WELD_OP_INDEX ||
+            q.opcode == WELD_OP_OUTER)
+            continue;
+        const bool dict_op = q.opcode == WELD_OP_KEYEXISTS || q.opcode == WELD_OP_DICTLOOKUP;
+        if (q.opcode != WELD_OP_LOOKUP && !dict_op) mark(q.a, need[i]);      // for those two, a is a vector / dictionary index
+        mark(q.b, need[i]);
+        mark(q.c, need[i]);
+    }
+    auto guarded = [&](size_t i) { return need[i] >= 0 && need[i] < (int)i; };
+
     // ---- the body, one statement per IR operator
     o.f("__device__ __forceinline__ void weld_row(const i64 i");
     if (segmented) o.f(", const i64 row");
@@ -186,7 +215,10 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
             case WELD_OP_AND: o.f("(bool)((int)t%d & (int)t%d)", q.a, q.b); break;
             case WELD_OP_OR: o.f("(bool)((int)t%d | (int)t%d)", q.a, q.b); break;
             case WELD_OP_SELECT: o.f("t%d ? t%d : t%d", q.a, q.b, q.c); break;
-            case WELD_OP_LOOKUP: o.f("w_lookup(a.g%d, a.g%d_len, (i64)t%d, errp)", q.a, q.a, q.b); break;
+            case WELD_OP_LOOKUP:
+                if (guarded(i)) o.f("!t%d ? (%s)0 : ", need[i], T);
+                o.f("w_lookup(a.g%d, a.g%d_len, (i64)t%d, errp)", q.a, q.a, q.b);
+                break;
             case WELD_OP_OUTER: o.f("a.o%d[row]", q.a); break;
             case WELD_OP_KEYEXISTS: case WELD_OP_DICTLOOKUP: {
                 const DictTable& t = L.dict_in[q.a];
@@ -194,6 +226,7 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
                 if (t.nkeys == 2)
                     key += std::string(" | ((u64)(") + utype(t.key_type[1]) + ")t" + std::to_string(q.c) + " << " +
                            std::to_string(8 * type_size(t.key_type[0])) + ")";
+                if (guarded(i)) o.f("!t%d ? (%s)0 : ", need[i], T);
                 if (q.opcode == WELD_OP_KEYEXISTS)
                     o.f("w_table_find(a.p%d_keys, a.p%d_hdr, a.p%d_slots, %s) >= 0", q.a, q.a, q.a, key.c_str());
                 else

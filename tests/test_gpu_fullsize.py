@@ -186,3 +186,32 @@ def test_groupbuilder_full_size_on_the_zip_code_column(wb):
     assert np.array_equal(keys[0], wkeys[0]) and np.array_equal(offsets, woff)
     gid = np.repeat(np.arange(len(woff) - 1), np.diff(woff))
     assert np.array_equal(values, wvals[np.lexsort((wvals, gid))])
+
+
+def test_join_full_size_against_the_oracle_on_the_rows_that_matter(wb):
+    """The Q12-shaped join at the size bench.py runs (1.5e7 orders, 6e7 line items).  The oracle
+    cannot probe 6e7 rows in reasonable time, and need not: rows failing the date / ship-mode
+    predicate merge nothing, and orders that no surviving row names are never looked at.  The
+    test selects both subsets itself (plain torch comparisons, written here), hands the oracle
+    the two small tables, and the results must be identical to the full run's."""
+    from oracle import interp
+    from workloads import joins
+    orders, lines = joins.make_tables(device="cuda")
+    build, probe = joins.program_build(), joins.program_probe()
+    built = wb.fused_for(build, orders)
+    res = wb.fused_for(probe, lines, dicts=[(built, 0)]).check()
+    keys, vals = res.dict(0)
+    res.free()
+    built.check()
+    built.free()
+    okey, mode, commit, receipt, ship = lines
+    keep = ((mode == 2) | (mode == 5)) & (commit < receipt) & (ship < commit) & \
+           (receipt >= joins.YEAR_START) & (receipt < joins.YEAR_END)
+    sub_lines = [c[keep].cpu().numpy() for c in lines]
+    named = torch.isin(orders[0], okey[keep])
+    sub_orders = [c[named].cpu().numpy() for c in orders]
+    table = interp.run(build, sub_orders)[0]
+    wkeys, wvals = interp.run(probe, sub_lines, dicts=[table])[0]
+    assert np.array_equal(keys[0], wkeys[0])
+    assert np.array_equal(vals[0], wvals[0]) and np.array_equal(vals[1], wvals[1])
+    assert int(vals[0].sum() + vals[1].sum()) == int(keep.sum().item())

@@ -720,3 +720,21 @@ def test_probe_argument_errors(wb):
     assert e.value.status == wb.ERR_UNSUPPORTED
     other.free()
     built.free()
+
+
+def test_join_shaped_like_q12(wb):
+    from oracle import interp
+    from tests import parity
+    from workloads import joins
+    orders, lines = joins.make_tables(40_000, 160_001, device="cuda")
+    build, probe = joins.program_build(40_000), joins.program_probe()
+    table = interp.run(build, [c.cpu().numpy() for c in orders])[0]
+    want = interp.run(probe, [c.cpu().numpy() for c in lines], dicts=[table])
+    built = _run(wb, build, orders)
+    res = _run(wb, probe, lines, dicts=[(built, 0)])
+    try:
+        parity.assert_matches(probe, res, want, label="q12")
+        parity.assert_matches(build, built, [table], label="q12 build side")
+    finally:
+        res.free()
+        built.free()
