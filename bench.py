@@ -232,6 +232,7 @@ def main():
             r = wb.nested_for(spmv, [start, end], [src, weight], [rank]).check()
             if i >= args.warmup:
                 sp_ms.append(r.elapsed_ms())
+            sname = r.kernel_name()
             r.free()
         # algorithmic bytes of an iteration: every edge's source once, the contribution vector
         # once, both row offsets, ranks and out-degrees in, new ranks out
@@ -240,7 +241,8 @@ def main():
                   "iteration_ms": round(median(it_ms), 4), "inner_kernel_ms": round(median(inner_ms), 4),
                   "inner_kernel": kname, "edges_per_s": ne / median(it_ms) * 1e3,
                   "algorithmic_GBps": round(alg / median(it_ms) / 1e6, 1), "rank_sum_after_one_iteration": total,
-                  "spmv_ms": round(median(sp_ms), 4), "spmv_edges_per_s": ne / median(sp_ms) * 1e3}
+                  "spmv_ms": round(median(sp_ms), 4), "spmv_edges_per_s": ne / median(sp_ms) * 1e3,
+                  "spmv_inner_kernel": sname}
 
     # ---- groupbuilder: the zip-code column grouped by its key (values = the codes themselves)
     groups = None
@@ -260,9 +262,11 @@ def main():
                 gk, go, gv = r.groups(0, sort=False)
                 npairs, ngroups = int(len(gv)), int(len(gk[0]))
                 assert int(go[-1]) == npairs
+            gname = r.kernel_name()
             r.free()
         groups = {"workload": "groupbuilder over the zip-code column", "rows": rows["C5"], "pairs": npairs,
-                  "groups": ngroups, "call_ms": round(median(ts), 4), "pairs_per_s": npairs / median(ts) * 1e3}
+                  "groups": ngroups, "call_ms": round(median(ts), 4), "pairs_per_s": npairs / median(ts) * 1e3,
+                  "loop_kernel": gname}
         del gcols
 
     # ---- hash join shaped like TPC-H Q12: build a dictionary over `orders`, probe it from `lineitem`
@@ -282,12 +286,13 @@ def main():
             if i == 0:
                 _, jv = r.dict(0)
                 matched = int(jv[0].sum() + jv[1].sum())
+            bname, pname = built.kernel_name(), r.kernel_name()
             r.free()
             built.free()
         join = {"workload": "hash join shaped like TPC-H Q12", "orders": no, "lineitems": nl, "matched_lines": matched,
                 "build_ms": round(median(bms), 4), "probe_ms": round(median(pms), 4),
                 "build_rows_per_s": no / median(bms) * 1e3, "probe_rows_per_s": nl / median(pms) * 1e3,
-                "probe_input_GBps": round(14 * nl / median(pms) / 1e6, 1)}
+                "probe_input_GBps": round(17 * nl / median(pms) / 1e6, 1), "build_kernel": bname, "probe_kernel": pname}
         del orders, lines
 
     line = {

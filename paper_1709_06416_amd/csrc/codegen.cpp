@@ -353,7 +353,14 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
                     while (p2w < w && p2w < 8192) p2w *= 2;
                     var.door_words = p2w;
                 }
-                if (tune.dict_spill >= 0) var.spill = true;
+                // the second kernel aggregates one partition per LDS table: pointless when a
+                // partition's share of the keys cannot fit one (every merge would end as a device
+                // atomic anyway, issued by 256 work-groups instead of the whole grid)
+                int nv = 1;
+                for (size_t b = 0; b < L.builders.size(); ++b)
+                    if (var.backend[b] == BK_DICT_LDS) nv = L.builders[b].nvals;
+                const int64_t part_slots = nv <= 1 ? 8192 : nv <= 3 ? 4096 : nv <= 7 ? 2048 : 1024;
+                if (tune.dict_spill > 0 || (tune.dict_spill == 0 && max_cap <= 256 * part_slots * 3 / 4)) var.spill = true;
             }
         }
     }
