@@ -205,95 +205,104 @@ def main():
     # matrix-vector product over the synthetic power-law graph; not part of `value`
     nested = None
     if not args.no_nested:
-        from workloads import graphs
-        for c in names:
-            cols[c] = None                      # the step's columns are no longer needed
-        torch.cuda.empty_cache()
-        nv = max(1, int(graphs.PAGERANK_VERTICES * args.scale))
-        rowptr, src, weight, outdeg = graphs.make_graph(nv, device="cuda")
-        start, end = rowptr[:-1].contiguous(), rowptr[1:].contiguous()
-        ne = src.numel()
-        rank = torch.full((nv,), 1.0 / nv, dtype=torch.float64, device="cuda")
-        pr, spmv, contrib_prog = graphs.program_pagerank(nv), graphs.program_spmv(), graphs.program_contrib()
-        it_ms, inner_ms, total = [], [], None
-        for i in range(args.warmup + max(5, args.steps // 2)):
-            r1 = wb.fused_for(contrib_prog, [rank, outdeg])
-            contrib = r1.check().vec(0)
-            r2 = wb.nested_for(pr, [start, end], [src], [contrib]).check()
-            if i >= args.warmup:
-                it_ms.append(r1.elapsed_ms() + r2.elapsed_ms())
-                inner_ms.append(r2.kernel_ms())
-            total = float(r2.merger(1))
-            kname = r2.kernel_name()
-            r1.free()
-            r2.free()
-        sp_ms = []
-        for i in range(args.warmup + 5):
-            r = wb.nested_for(spmv, [start, end], [src, weight], [rank]).check()
-            if i >= args.warmup:
-                sp_ms.append(r.elapsed_ms())
-            sname = r.kernel_name()
-            r.free()
-        # algorithmic bytes of an iteration: every edge's source once, the contribution vector
-        # once, both row offsets, ranks and out-degrees in, new ranks out
-        alg = 4 * ne + 8 * nv + 2 * 8 * nv + 8 * nv + 8 * nv + 8 * nv
-        nested = {"workload": "PageRank iteration, synthetic power-law graph", "vertices": nv, "edges": ne,
-                  "iteration_ms": round(median(it_ms), 4), "inner_kernel_ms": round(median(inner_ms), 4),
-                  "inner_kernel": kname, "edges_per_s": ne / median(it_ms) * 1e3,
-                  "algorithmic_GBps": round(alg / median(it_ms) / 1e6, 1), "rank_sum_after_one_iteration": total,
-                  "spmv_ms": round(median(sp_ms), 4), "spmv_edges_per_s": ne / median(sp_ms) * 1e3,
-                  "spmv_inner_kernel": sname}
+        try:
+            from workloads import graphs
+            for c in names:
+                cols[c] = None                      # the step's columns are no longer needed
+            torch.cuda.empty_cache()
+            nv = max(1, int(graphs.PAGERANK_VERTICES * args.scale))
+            rowptr, src, weight, outdeg = graphs.make_graph(nv, device="cuda")
+            start, end = rowptr[:-1].contiguous(), rowptr[1:].contiguous()
+            ne = src.numel()
+            rank = torch.full((nv,), 1.0 / nv, dtype=torch.float64, device="cuda")
+            pr, spmv, contrib_prog = graphs.program_pagerank(nv), graphs.program_spmv(), graphs.program_contrib()
+            it_ms, inner_ms, total = [], [], None
+            for i in range(args.warmup + max(5, args.steps // 2)):
+                r1 = wb.fused_for(contrib_prog, [rank, outdeg])
+                contrib = r1.check().vec(0)
+                r2 = wb.nested_for(pr, [start, end], [src], [contrib]).check()
+                if i >= args.warmup:
+                    it_ms.append(r1.elapsed_ms() + r2.elapsed_ms())
+                    inner_ms.append(r2.kernel_ms())
+                total = float(r2.merger(1))
+                kname = r2.kernel_name()
+                r1.free()
+                r2.free()
+            sp_ms = []
+            for i in range(args.warmup + 5):
+                r = wb.nested_for(spmv, [start, end], [src, weight], [rank]).check()
+                if i >= args.warmup:
+                    sp_ms.append(r.elapsed_ms())
+                sname = r.kernel_name()
+                r.free()
+            # algorithmic bytes of an iteration: every edge's source once, the contribution vector
+            # once, both row offsets, ranks and out-degrees in, new ranks out
+            alg = 4 * ne + 8 * nv + 2 * 8 * nv + 8 * nv + 8 * nv + 8 * nv
+            nested = {"workload": "PageRank iteration, synthetic power-law graph", "vertices": nv, "edges": ne,
+                      "iteration_ms": round(median(it_ms), 4), "inner_kernel_ms": round(median(inner_ms), 4),
+                      "inner_kernel": kname, "edges_per_s": ne / median(it_ms) * 1e3,
+                      "algorithmic_GBps": round(alg / median(it_ms) / 1e6, 1), "rank_sum_after_one_iteration": total,
+                      "spmv_ms": round(median(sp_ms), 4), "spmv_edges_per_s": ne / median(sp_ms) * 1e3,
+                      "spmv_inner_kernel": sname}
+        except Exception as e:      # a leg beyond the step must not take the step's line with it
+            nested = {"error": "%s: %s" % (type(e).__name__, str(e)[:300])}
 
     # ---- groupbuilder: the zip-code column grouped by its key (values = the codes themselves)
     groups = None
     if not args.no_nested and "C5" in names:
-        from workloads.ir import Program
-        gcols = configs.make_columns("C5", rows["C5"], device="cuda")
-        gp = Program(["i64"])
-        c0 = gp.col(0)
-        gp.merge(gp.groupbuilder(["i64"], "i64", 100_000), c0, keys=[gp.bin("mod", c0, gp.const("i64", 100_000))],
-                 pred=gp.bin("gt", c0, gp.const("i64", 0)))
-        ts, npairs, ngroups = [], 0, 0
-        for i in range(args.warmup + 5):
-            r = wb.fused_for(gp, gcols).check()
-            if i >= args.warmup:
-                ts.append(r.elapsed_ms())
-            if i == 0:
-                gk, go, gv = r.groups(0, sort=False)
-                npairs, ngroups = int(len(gv)), int(len(gk[0]))
-                assert int(go[-1]) == npairs
-            gname = r.kernel_name()
-            r.free()
-        groups = {"workload": "groupbuilder over the zip-code column", "rows": rows["C5"], "pairs": npairs,
-                  "groups": ngroups, "call_ms": round(median(ts), 4), "pairs_per_s": npairs / median(ts) * 1e3,
-                  "loop_kernel": gname}
-        del gcols
+        try:
+            from workloads.ir import Program
+            gcols = configs.make_columns("C5", rows["C5"], device="cuda")
+            gp = Program(["i64"])
+            c0 = gp.col(0)
+            gp.merge(gp.groupbuilder(["i64"], "i64", 100_000), c0, keys=[gp.bin("mod", c0, gp.const("i64", 100_000))],
+                     pred=gp.bin("gt", c0, gp.const("i64", 0)))
+            ts, npairs, ngroups = [], 0, 0
+            for i in range(args.warmup + 5):
+                r = wb.fused_for(gp, gcols).check()
+                if i >= args.warmup:
+                    ts.append(r.elapsed_ms())
+                if i == 0:
+                    gk, go, gv = r.groups(0, sort=False)
+                    npairs, ngroups = int(len(gv)), int(len(gk[0]))
+                    assert int(go[-1]) == npairs
+                gname = r.kernel_name()
+                r.free()
+            groups = {"workload": "groupbuilder over the zip-code column", "rows": rows["C5"], "pairs": npairs,
+                      "groups": ngroups, "call_ms": round(median(ts), 4), "pairs_per_s": npairs / median(ts) * 1e3,
+                      "loop_kernel": gname}
+            del gcols
+        except Exception as e:      # a leg beyond the step must not take the step's line with it
+            groups = {"error": "%s: %s" % (type(e).__name__, str(e)[:300])}
 
     # ---- hash join shaped like TPC-H Q12: build a dictionary over `orders`, probe it from `lineitem`
     join = None
     if not args.no_nested:
-        from workloads import joins
-        no, nl = max(1, int(joins.ORDERS * args.scale)), max(1, int(joins.LINEITEMS * args.scale))
-        orders, lines = joins.make_tables(no, nl, device="cuda")
-        bp, pp = joins.program_build(no), joins.program_probe()
-        bms, pms = [], []
-        for i in range(args.warmup + 5):
-            built = wb.fused_for(bp, orders)
-            r = wb.fused_for(pp, lines, dicts=[(built, 0)]).check()
-            if i >= args.warmup:
-                bms.append(built.elapsed_ms())
-                pms.append(r.elapsed_ms())
-            if i == 0:
-                _, jv = r.dict(0)
-                matched = int(jv[0].sum() + jv[1].sum())
-            bname, pname = built.kernel_name(), r.kernel_name()
-            r.free()
-            built.free()
-        join = {"workload": "hash join shaped like TPC-H Q12", "orders": no, "lineitems": nl, "matched_lines": matched,
-                "build_ms": round(median(bms), 4), "probe_ms": round(median(pms), 4),
-                "build_rows_per_s": no / median(bms) * 1e3, "probe_rows_per_s": nl / median(pms) * 1e3,
-                "probe_input_GBps": round(17 * nl / median(pms) / 1e6, 1), "build_kernel": bname, "probe_kernel": pname}
-        del orders, lines
+        try:
+            from workloads import joins
+            no, nl = max(1, int(joins.ORDERS * args.scale)), max(1, int(joins.LINEITEMS * args.scale))
+            orders, lines = joins.make_tables(no, nl, device="cuda")
+            bp, pp = joins.program_build(no), joins.program_probe()
+            bms, pms = [], []
+            for i in range(args.warmup + 5):
+                built = wb.fused_for(bp, orders)
+                r = wb.fused_for(pp, lines, dicts=[(built, 0)]).check()
+                if i >= args.warmup:
+                    bms.append(built.elapsed_ms())
+                    pms.append(r.elapsed_ms())
+                if i == 0:
+                    _, jv = r.dict(0)
+                    matched = int(jv[0].sum() + jv[1].sum())
+                bname, pname = built.kernel_name(), r.kernel_name()
+                r.free()
+                built.free()
+            join = {"workload": "hash join shaped like TPC-H Q12", "orders": no, "lineitems": nl, "matched_lines": matched,
+                    "build_ms": round(median(bms), 4), "probe_ms": round(median(pms), 4),
+                    "build_rows_per_s": no / median(bms) * 1e3, "probe_rows_per_s": nl / median(pms) * 1e3,
+                    "probe_input_GBps": round(17 * nl / median(pms) / 1e6, 1), "build_kernel": bname, "probe_kernel": pname}
+            del orders, lines
+        except Exception as e:
+            join = {"error": "%s: %s" % (type(e).__name__, str(e)[:300])}
 
     line = {
         "metric": "fused-loop input GB/s (all five configs back to back)", "value": round(value, 1), "unit": "GB/s",
