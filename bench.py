@@ -45,7 +45,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the loop shards by "
-                 "contiguous row ranges, see DESIGN.md, but no multi-GPU path is built)" % args.gpus)
+                 "contiguous row ranges with one small exchange per builder, but no multi-GPU path is built)" % args.gpus)
 
     import torch
     from paper_1709_06416_amd import binding as wb

@@ -28,7 +28,8 @@ using namespace weld;
 namespace {
 
 const int kCtlBytes = 256;
-// control words (u32 index): 0 tile ticket, 1 arrived work-groups, 2 error bits,
+// control words (u32 index): 0 tile ticket, 2 error bits (1 capacity, 2 bounded wait gave up,
+// 4 index / lookup out of range, 8 nested ranges not consecutive),
 // byte 16 + 8*b: length / entry count of builder b, byte 96 + 8*b: dictionary header
 inline size_t ctl_count_off(int b) { return 16 + 8 * (size_t)b; }
 inline size_t ctl_hdr_off(int b) { return 96 + 8 * (size_t)b; }

@@ -1,6 +1,6 @@
 """Shared comparison rules for the GPU parity tests (test infrastructure).
 
-Tolerances (stated by the benchmark spec, restated in the design doc):
+Tolerances:
   * integer, count, compaction-order and key-set outputs: bit-exact;
   * f64 merger / dictmerger sums: 1e-9 relative to the correctly rounded sum;
   * f64 min / max: bit-exact (order independent);

@@ -91,7 +91,7 @@ def test_config(wb, name, n):
 def test_config_c2_black_scholes(wb):
     # a deep out-of-the-money price is ~1e-16 while N(d) = 1/2 + 1/2 erf(.) is formed from an
     # O(1) erf value: one ulp of erf is an O(1) relative change of such a price.  Prices live in
-    # [0, 100], so the element bound is 1e-12 * max(|price|, 1.0) (stated in the design doc)
+    # [0, 100], so the element bound is 1e-12 * max(|price|, 1.0)
     cols = configs.make_columns("C2", 300_007, device="cuda")
     _check(wb, configs.program_c2(), cols, map_floor=1.0, label="C2")
 
