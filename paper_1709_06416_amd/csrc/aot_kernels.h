@@ -34,6 +34,21 @@ struct MergerFinish {
 hipError_t launch_merger_finish(const MergerFinish& m, int count, hipStream_t stream);
 
 hipError_t launch_fill64(void* p, int64_t count, uint64_t value, hipStream_t stream);
+// Several fills in one launch (the workspace of a call: control words, scan descriptors, the
+// keys and value columns of a dictionary table ...).
+struct FillList {
+    int n = 0;
+    void* p[16];
+    long long count[16];
+    unsigned long long value[16];
+    bool add(void* ptr, int64_t cnt, uint64_t val) {
+        if (cnt <= 0) return true;
+        if (n == 16) return false;
+        p[n] = ptr; count[n] = cnt; value[n] = val; ++n;
+        return true;
+    }
+};
+hipError_t launch_fill_list(const FillList& f, hipStream_t stream);
 // slot_pos (may be null): receives, for every occupied slot (and the extra slot `slots`), the
 // position its entry was written to.
 hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots, const DictValues& vals,

@@ -28,6 +28,24 @@ hipError_t launch_fill64(void* p, int64_t count, uint64_t value, hipStream_t str
     return hipGetLastError();
 }
 
+__global__ void __launch_bounds__(256) fill_list_kernel(const FillList f) {
+    for (int k = 0; k < f.n; ++k) {
+        u64* const p = (u64*)f.p[k];
+        const u64 v = f.value[k];
+        for (i64 i = (i64)blockIdx.x * 256 + threadIdx.x; i < f.count[k]; i += (i64)gridDim.x * 256) p[i] = v;
+    }
+}
+
+hipError_t launch_fill_list(const FillList& f, hipStream_t stream) {
+    if (f.n == 0) return hipSuccess;
+    long long most = 0;
+    for (int k = 0; k < f.n; ++k) most = f.count[k] > most ? f.count[k] : most;
+    int64_t blocks = (most + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    fill_list_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(f);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- merger result
 // Fixed-order combination of the per-work-group partials of every merger of a call
 // (one work-group per merger).  Thread j folds partials j, j+256, ... in that order,

@@ -11,6 +11,8 @@
 #include <cstdio>
 #include <cmath>
 #include <cstring>
+#include <map>
+#include <memory>
 #include <mutex>
 
 #include "aot_kernels.h"
@@ -117,6 +119,83 @@ struct Layout {
 
 namespace weld {
 
+// ---------------------------------------------------------------------------------------
+// Plans.  Generating a kernel's text (about 150 KB with the prelude) and looking it up in the
+// code-object cache costs the host more than 100 us a call, which shows as idle GPU time
+// whenever the previous kernel is short.  A loop that was planned before - same body, builders,
+// tuning and alignment - takes its variant, argument slots, loaded kernel and occupancy from here.
+namespace {
+
+struct Plan {
+    Variant var;
+    std::vector<Slot> slots;
+    std::string kernel_name;
+    Kernel* kern = nullptr;
+    int per_cu = 0;
+};
+std::mutex g_plan_mu;
+std::map<std::string, std::shared_ptr<Plan>> g_plans;
+
+template <class T> void key_add(std::string& k, const T& v) { k.append(reinterpret_cast<const char*>(&v), sizeof v); }
+
+std::string plan_key(const Loop& L, const weld_tuning_t& tune, bool aligned, int kind, int extra) {
+    std::string k;
+    k.reserve(256 + 32 * L.ops.size());
+    key_add(k, kind);
+    key_add(k, extra);
+    key_add(k, aligned);
+    key_add(k, tune);
+    key_add(k, L.ncols);
+    for (int c = 0; c < L.ncols; ++c) { key_add(k, L.col_type[c]); key_add(k, L.col_used[c]); }
+    for (const weld_op_t& o : L.ops) {
+        key_add(k, o.opcode); key_add(k, o.type); key_add(k, o.a); key_add(k, o.b); key_add(k, o.c);
+        key_add(k, o.reserved); key_add(k, o.imm.i64);
+    }
+    for (weld_builder_spec_t b : L.builders) {
+        b.init = nullptr;                       // data, not shape
+        key_add(k, b.kind); key_add(k, b.func); key_add(k, b.nkeys); key_add(k, b.key_type); key_add(k, b.nvals);
+        key_add(k, b.val_type); key_add(k, b.capacity); key_add(k, b.length);
+    }
+    for (const weld_merge_t& m : L.merges) {
+        key_add(k, m.builder); key_add(k, m.pred); key_add(k, m.nkeys); key_add(k, m.key); key_add(k, m.nvals); key_add(k, m.val);
+    }
+    key_add(k, L.ngather);
+    for (int g = 0; g < L.ngather; ++g) { key_add(k, L.gather_type[g]); key_add(k, L.gather_used[g]); }
+    key_add(k, L.nouter);
+    for (int c = 0; c < L.nouter; ++c) { key_add(k, L.outer_type[c]); key_add(k, L.outer_used[c]); }
+    key_add(k, L.ndicts);
+    for (int d = 0; d < L.ndicts; ++d) {
+        const DictTable& t = L.dict_in[d];
+        key_add(k, t.nkeys); key_add(k, t.key_type); key_add(k, t.nvals); key_add(k, t.val_type); key_add(k, L.dict_val_used[d]);
+    }
+    return k;
+}
+
+// kind 0: fused loop; kind 1: flattened inner loop of a nested for (extra = offset type)
+Error get_plan(const Loop& L, const weld_tuning_t& tune, bool aligned, int kind, int extra, std::shared_ptr<Plan>* out) {
+    const std::string key = plan_key(L, tune, aligned, kind, extra);
+    {
+        std::lock_guard<std::mutex> lk(g_plan_mu);
+        auto it = g_plans.find(key);
+        if (it != g_plans.end()) { *out = it->second; return Error(); }
+    }
+    auto p = std::make_shared<Plan>();
+    p->var = kind == 0 ? choose_variant(L, tune, aligned) : choose_segmented_variant(L, tune, aligned);
+    Generated G = kind == 0 ? generate(L, p->var) : generate_segmented(L, p->var, extra);
+    Error e = jit_get(G.source, G.kernel_name, true, &p->kern);
+    if (!e.ok()) return e;
+    p->slots = G.slots;
+    p->kernel_name = G.kernel_name;
+    p->per_cu = jit_blocks_per_cu(p->kern, p->var.block);
+    if (p->per_cu <= 0 || p->per_cu > 8) p->per_cu = 8;
+    std::lock_guard<std::mutex> lk(g_plan_mu);
+    g_plans[key] = p;
+    *out = p;
+    return Error();
+}
+
+}  // namespace
+
 Loop expand_groups(const Loop& in, std::vector<GroupLink>* links) {
     links->clear();
     bool any = false;
@@ -197,20 +276,19 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     bool aligned = true;
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c] && ((uintptr_t)cols[c].data & 15)) aligned = false;
-    Variant var = choose_variant(L, conf.tune, aligned);
-    Generated G = generate(L, var);
-    Kernel* kern = nullptr;
-    Error e = jit_get(G.source, G.kernel_name, true, &kern);
+    std::shared_ptr<Plan> plan;
+    Error e = get_plan(L, conf.tune, aligned, 0, 0, &plan);
     if (!e.ok()) return e;
-    if (!prior_ctl) r->kernel_name = G.kernel_name;
+    const Variant& var = plan->var;
+    Kernel* kern = plan->kern;
+    if (!prior_ctl) r->kernel_name = plan->kernel_name;
 
     const size_t NB = L.builders.size();
     const int64_t tile = (int64_t)var.block * var.v * var.u;
     const int64_t ntiles = (n + tile - 1) / tile;
     // persistent grid: as many work-groups as are resident at once (registers and LDS
     // of this kernel decide), at most 8 per CU
-    int per_cu = jit_blocks_per_cu(kern, var.block);
-    if (per_cu <= 0 || per_cu > 8) per_cu = 8;
+    const int per_cu = plan->per_cu;
     int64_t grid = conf.tune.grid_blocks > 0 ? conf.tune.grid_blocks : (int64_t)device_info().cus * per_cu;
     if (grid > ntiles) grid = ntiles;
     if (grid < 1) grid = 1;
@@ -338,7 +416,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
 
     // ---- kernel arguments, in the order the generated struct declares them
     std::vector<uint64_t> args;
-    for (const Slot& s : G.slots) {
+    for (const Slot& s : plan->slots) {
         uint64_t v = 0;
         const int b = s.builder;
         switch (s.kind) {
@@ -369,35 +447,46 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     // ---- enqueue
     hipError_t h;
     if (!prior_ctl && (h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
-    if ((h = launch_fill64(base + off_ctl, kCtlBytes / 8, 0, stream)) != hipSuccess) return hip_err("fill", h);
-    r->kernel_count++;
-    for (const GroupLink& g : links) {
-        // pairs of a groupbuilder merged without a predicate: their number is n, known now
-        if (var.backend[g.val_vec] != BK_VEC_DIRECT || L.merge_of[g.val_vec] < 0) continue;
-        if ((h = launch_fill64(base + off_ctl + ctl_count_off(g.val_vec), 1, (uint64_t)n, stream)) != hipSuccess) return hip_err("fill", h);
+    // the workspace of the call is cleared by ONE kernel (a dictionary alone has a key column
+    // and up to eight value columns; a launch each left the GPU idle for microseconds apiece)
+    FillList fills;
+    auto fill = [&](void* p, int64_t count, uint64_t value) -> hipError_t {
+        if (fills.add(p, count, value)) return hipSuccess;
+        const hipError_t he = launch_fill_list(fills, stream);
         r->kernel_count++;
-    }
+        fills = FillList();
+        fills.add(p, count, value);
+        return he;
+    };
+    if ((h = fill(base + off_ctl, kCtlBytes / 8, 0)) != hipSuccess) return hip_err("fill", h);
     for (size_t b = 0; b < NB; ++b) {
         const weld_builder_spec_t& s = L.builders[b];
         if (var.backend[b] == BK_VEC_COMPACT && ntiles > 0) {
-            if ((h = launch_fill64(base + off[b].desc, ntiles, 0, stream)) != hipSuccess) return hip_err("fill", h);
-            r->kernel_count++;
+            if ((h = fill(base + off[b].desc, ntiles, 0)) != hipSuccess) return hip_err("fill", h);
         } else if (s.kind == WELD_VECMERGER) {
             // the result starts as a copy of the caller's vector (or as identities)
-            if (s.init) h = hipMemcpyAsync(base + off[b].out, s.init, 8 * (size_t)s.length, hipMemcpyDeviceToDevice, stream);
-            else h = launch_fill64(base + off[b].out, s.length, ident_bits(s.func, s.val_type[0]), stream);
-            if (h != hipSuccess) return hip_err("vecmerger init", h);
-            r->kernel_count++;
-        } else if (s.kind == WELD_DICTMERGER) {
-            if ((h = launch_fill64(base + off[b].keys, off[b].slots + 1, 0x8000000000000000ull, stream)) != hipSuccess)
-                return hip_err("fill", h);
-            r->kernel_count++;
-            for (int k = 0; k < s.nvals; ++k) {
-                if ((h = launch_fill64(base + off[b].vals[k], off[b].slots + 1, ident_bits(s.func, s.val_type[k]), stream)) != hipSuccess)
-                    return hip_err("fill", h);
+            if (s.init) {
+                h = hipMemcpyAsync(base + off[b].out, s.init, 8 * (size_t)s.length, hipMemcpyDeviceToDevice, stream);
                 r->kernel_count++;
+            } else {
+                h = fill(base + off[b].out, s.length, ident_bits(s.func, s.val_type[0]));
             }
+            if (h != hipSuccess) return hip_err("vecmerger init", h);
+        } else if (s.kind == WELD_DICTMERGER) {
+            if ((h = fill(base + off[b].keys, off[b].slots + 1, 0x8000000000000000ull)) != hipSuccess) return hip_err("fill", h);
+            for (int k = 0; k < s.nvals; ++k)
+                if ((h = fill(base + off[b].vals[k], off[b].slots + 1, ident_bits(s.func, s.val_type[k]))) != hipSuccess)
+                    return hip_err("fill", h);
         }
+    }
+    if ((h = launch_fill_list(fills, stream)) != hipSuccess) return hip_err("fill", h);
+    r->kernel_count++;
+    for (const GroupLink& g : links) {
+        // pairs of a groupbuilder merged without a predicate: their number is n, known now
+        // (after the control words have been cleared)
+        if (var.backend[g.val_vec] != BK_VEC_DIRECT || L.merge_of[g.val_vec] < 0) continue;
+        if ((h = launch_fill64(base + off_ctl + ctl_count_off(g.val_vec), 1, (uint64_t)n, stream)) != hipSuccess) return hip_err("fill", h);
+        r->kernel_count++;
     }
     if (!prior_ctl && (h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream);
@@ -532,17 +621,16 @@ Error run_nested(const NestedLoop& NL, const NestedData& D, const weld_conf_t& c
     bool aligned = true;
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c] && ((uintptr_t)D.inner[c].data & 15)) aligned = false;
-    Variant var = choose_segmented_variant(L, conf.tune, aligned);
-    Generated G = generate_segmented(L, var, NL.offset_type);
-    Kernel* kern = nullptr;
-    Error e = jit_get(G.source, G.kernel_name, true, &kern);
+    std::shared_ptr<Plan> plan;
+    Error e = get_plan(L, conf.tune, aligned, 1, NL.offset_type, &plan);
     if (!e.ok()) return e;
-    r->kernel_name = G.kernel_name;
+    const Variant& var = plan->var;
+    Kernel* kern = plan->kern;
+    r->kernel_name = plan->kernel_name;
 
     const int64_t tile = (int64_t)var.block * var.v * var.u;
     const int64_t ntiles = (D.n_inner + tile - 1) / tile;
-    int per_cu = jit_blocks_per_cu(kern, var.block);
-    if (per_cu <= 0 || per_cu > 8) per_cu = 8;
+    const int per_cu = plan->per_cu;
     int64_t grid = conf.tune.grid_blocks > 0 ? conf.tune.grid_blocks : (int64_t)device_info().cus * per_cu;
     if (grid > ntiles) grid = ntiles;
     if (grid < 1) grid = 1;
@@ -562,7 +650,7 @@ Error run_nested(const NestedLoop& NL, const NestedData& D, const weld_conf_t& c
     const weld_builder_spec_t& ms = L.builders[0];
 
     std::vector<uint64_t> args;
-    for (const Slot& s : G.slots) {
+    for (const Slot& s : plan->slots) {
         uint64_t v = 0;
         switch (s.kind) {
             case SLOT_N: v = (uint64_t)D.n_inner; break;
@@ -582,13 +670,15 @@ Error run_nested(const NestedLoop& NL, const NestedData& D, const weld_conf_t& c
     hipError_t h;
     const int is64 = NL.offset_type == WELD_I64;
     if ((h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
-    if ((h = launch_fill64(base + off_ctl, kCtlBytes / 8, 0, stream)) != hipSuccess) return hip_err("fill", h);
-    if ((h = launch_fill64(base + off_sums, D.n_outer, ident_bits(ms.func, ms.val_type[0]), stream)) != hipSuccess) return hip_err("fill", h);
+    FillList fills;
+    fills.add(base + off_ctl, kCtlBytes / 8, 0);
+    fills.add(base + off_sums, D.n_outer, ident_bits(ms.func, ms.val_type[0]));
+    if ((h = launch_fill_list(fills, stream)) != hipSuccess) return hip_err("fill", h);
     if ((h = launch_segments_check(D.outer[NL.start_col].data, D.outer[NL.end_col].data, is64, D.n_outer, D.n_inner,
                                    base + off_ctl + 8, stream)) != hipSuccess) return hip_err("segments check", h);
     if ((h = launch_tile_rows(D.outer[NL.start_col].data, is64, D.n_outer, tile, ntiles, base + off_tiles, stream)) != hipSuccess)
         return hip_err("tile rows", h);
-    r->kernel_count += 4;
+    r->kernel_count += 3;
     if ((h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     if (ntiles > 0 && D.n_outer > 0) {
         e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream);
