@@ -172,6 +172,16 @@ typedef struct {
                                    second kernel aggregates in LDS (> 0: entries per queue segment,
                                    0 = sized for the case that every row misses; a full segment
                                    sends its merges to the global table)                            */
+    int32_t merge_loop;         /* merges into builders that live in memory (LDS / global hash tables,
+                                   vecmergers) of the rows a lane holds per tile: 1 = one loop over the
+                                   rows (the merge code exists once), -1 = unrolled per row, 0 = library's
+                                   choice                                                            */
+    int32_t dict_defer;         /* LDS hash table in a loop that also compacts: 0 = merges that the first
+                                   probe does not settle are queued per wavefront and handled 64 at a
+                                   time, -1 = every merge walks the whole path where it stands      */
+    int32_t tile_prefetch;      /* loops that compact (tiles handed out in order): 1 = the next tile's
+                                   columns are loaded while the current tile merges and stores, -1 = each
+                                   tile loads when it starts, 0 = library's choice                    */
 } weld_tuning_t;
 
 typedef struct {

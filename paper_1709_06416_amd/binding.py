@@ -75,7 +75,8 @@ class BuilderSpec(C.Structure):
 class Tuning(C.Structure):
     _fields_ = [("block_threads", C.c_int32), ("units_per_thread", C.c_int32), ("grid_blocks", C.c_int32),
                 ("dict_strategy", C.c_int32), ("lds_dict_slots", C.c_int32), ("spin_limit", C.c_int32),
-                ("vecmerger_strategy", C.c_int32), ("lds_filter_words", C.c_int32), ("dict_spill", C.c_int32)]
+                ("vecmerger_strategy", C.c_int32), ("lds_filter_words", C.c_int32), ("dict_spill", C.c_int32),
+                ("merge_loop", C.c_int32), ("dict_defer", C.c_int32), ("tile_prefetch", C.c_int32)]
 
 
 class Conf(C.Structure):
@@ -176,8 +177,10 @@ class Marshalled:
     """C structs of one loop description; keeps the backing arrays alive."""
 
     def __init__(self, program, mode="fused", stream=0, memory_limit=0, tune=None, inits=None):
+        self.program = program
         nops = len(program.ops)
         inits = inits or {}
+        self.inits = inits                               # kept alive with the description
         self.ops = (Op * max(nops, 1))()
         for i, op in enumerate(program.ops):
             o = self.ops[i]
@@ -414,7 +417,13 @@ def fused_for(program, columns, mode="fused", stream=None, memory_limit=0, tune=
     (weld_fused_for_probe); the Results are kept alive by the returned one."""
     if stream is None:
         stream = torch.cuda.current_stream().cuda_stream
-    m = Marshalled(program, mode=mode, stream=stream, memory_limit=memory_limit, tune=tune, inits=inits)
+    if isinstance(program, Marshalled):
+        m, program = program, program.program
+        if inits:
+            raise WeldError(ERR_INVALID_ARG, "a prepared loop carries its initial vectors; pass them to prepare()")
+        m.builder.conf.stream = stream
+    else:
+        m = Marshalled(program, mode=mode, stream=stream, memory_limit=memory_limit, tune=tune, inits=inits)
     if len(columns) != len(program.columns):
         raise WeldError(ERR_INVALID_ARG, "column count mismatch")
     cols = (Col * max(len(columns), 1))()
@@ -445,6 +454,14 @@ def fused_for(program, columns, mode="fused", stream=None, memory_limit=0, tune=
     if st != OK:
         raise WeldError(st, lib.weld_last_error().decode())
     return Result(out, program, (m, cols, list(columns), inits, dicts))
+
+
+def prepare(program, mode="fused", memory_limit=0, tune=None, inits=None):
+    """The C description of a loop, built once: fused_for accepts it in place of the program, so a
+    loop that runs many times is not marshalled again per call.  Later changes to the program
+    are not seen; calls that share one prepared loop must not overlap on different host threads
+    (the stream is written into it per call)."""
+    return Marshalled(program, mode=mode, memory_limit=memory_limit, tune=tune, inits=inits)
 
 
 def _col_array(tensors, types, what):

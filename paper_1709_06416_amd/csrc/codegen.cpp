@@ -15,6 +15,7 @@
 // what the order-preserving vecbuilder ranks rely on.
 #include <cstdarg>
 #include <cstdio>
+#include <algorithm>
 #include <cstring>
 
 #include "weld_internal.h"
@@ -196,14 +197,22 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
                 if (q.type == WELD_F64) o.f("t%d * t%d", q.a, q.b);
                 else o.f("%s", wrap_bin(q.type, "*", q.a, q.b).c_str());
                 break;
-            case WELD_OP_DIV:
-                if (q.type == WELD_F64) o.f("t%d / t%d", q.a, q.b);
-                else o.f("(%s)(t%d / t%d)", T, q.a, q.b);
+            case WELD_OP_DIV: case WELD_OP_MOD: {
+                const bool div = q.opcode == WELD_OP_DIV;
+                const weld_op_t& d = L.ops[q.b];
+                if (q.type == WELD_F64) {
+                    if (div) o.f("t%d / t%d", q.a, q.b);
+                    else o.f("fmod(t%d, t%d)", q.a, q.b);
+                } else if (q.type == WELD_I64 && d.opcode == WELD_OP_CONST && d.imm.i64 >= 2 && d.imm.i64 < (1ll << 31)) {
+                    // 64-bit operand, small constant divisor: 32-bit arithmetic when the wavefront's operands allow
+                    o.f("w_%s_const<%lldll>(t%d, ", div ? "div" : "mod", (long long)d.imm.i64, q.a);
+                    if (guarded(i)) o.f("t%d)", need[i]);
+                    else o.f("true)");
+                } else {
+                    o.f("(%s)(t%d %s t%d)", T, q.a, div ? "/" : "%", q.b);
+                }
                 break;
-            case WELD_OP_MOD:
-                if (q.type == WELD_F64) o.f("fmod(t%d, t%d)", q.a, q.b);
-                else o.f("(%s)(t%d %% t%d)", T, q.a, q.b);
-                break;
+            }
             case WELD_OP_MIN: o.f("(t%d < t%d ? t%d : t%d)", q.b, q.a, q.b, q.a); break;
             case WELD_OP_MAX: o.f("(t%d > t%d ? t%d : t%d)", q.b, q.a, q.b, q.a); break;
             case WELD_OP_LT: o.f("t%d < t%d", q.a, q.b); break;
@@ -267,6 +276,11 @@ std::string pack_key(const weld_builder_spec_t& s, size_t b, const char* row) {
         shift += 8 * type_size(s.key_type[k]);
     }
     return e;
+}
+
+// builders whose merges go to memory at a computed address (as opposed to register accumulators)
+bool merges_in_memory(int backend) {
+    return backend == BK_DICT_LDS || backend == BK_DICT_GLOBAL || backend == BK_VECM_LDS || backend == BK_VECM_GLOBAL;
 }
 
 }  // namespace
@@ -395,9 +409,39 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
         int per_slot = 0;
         for (size_t b = 0; b < L.builders.size(); ++b)
             if (var.backend[b] == BK_DICT_LDS) per_slot += 8 * (1 + L.builders[b].nvals);
-        const int other = (var.ticketed ? 8 * var.block * var.v : 0) + 4 * var.door_words + (var.spill ? 1024 : 0) +
-                          (body_uses(L, WELD_OP_ERF) ? 7680 : 0) + 2048;
+        int other = (var.ticketed ? 8 * var.block * var.v : 0) + 4 * var.door_words + (var.spill ? 1024 : 0) +
+                    (body_uses(L, WELD_OP_ERF) ? 7680 : 0) + 2048;
+        for (size_t b = 0; b < L.builders.size(); ++b) {
+            if (var.backend[b] == BK_VECM_LDS) other += 8 * (var.ranges > 1 ? 8192 : (int)L.builders[b].length);
+            if (var.backend[b] == BK_DICT_REG || var.backend[b] == BK_DICT_LANE) other += 8 * (int)L.builders[b].capacity;
+            if (var.backend[b] == BK_DICT_LANE) other += 8 * (int)L.builders[b].capacity * L.builders[b].nvals * var.block;
+        }
         while (var.lds_slots > 64 && var.lds_slots * per_slot + other > 160 * 1024) var.lds_slots /= 2;
+    }
+    // Merges into hash tables and vecmergers are divergent code (probe, claim, overflow paths).
+    // Unrolled over the rows a lane holds per tile they multiply the kernel text and leave the
+    // compiler short of scalar registers for the execution masks; one loop over the rows, which
+    // indexes the lane's values with the loop counter, keeps that code once.
+    {
+        bool in_memory = false;
+        for (size_t b = 0; b < L.builders.size(); ++b)
+            if (L.merge_of[b] >= 0 && merges_in_memory(var.backend[b])) in_memory = true;
+        const int rows = var.u * var.v;
+        // one LDS dictionary in a compacting loop: its merges beyond the first probe are queued per
+        // wavefront (in the wavefront's part of the staging buffer, free while the tile merges)
+        int nlds = 0, which = -1;
+        for (size_t b = 0; b < L.builders.size(); ++b)
+            if (var.backend[b] == BK_DICT_LDS && L.merge_of[b] >= 0) { ++nlds; which = (int)b; }
+        if (tune.dict_defer >= 0 && nlds == 1 && var.ticketed && rows >= 4 && rows <= 16) {
+            const weld_merge_t& g = L.merges[L.merge_of[which]];
+            int words = 1;
+            for (int k = 0; k < g.nvals; ++k)
+                if (L.ops[g.val[k]].opcode != WELD_OP_CONST) ++words;
+            const int cap = 64 * var.v / words;
+            if (cap >= 64) { var.defer_builder = which; var.defer_cap = cap; }
+        }
+        var.merge_loop = (tune.merge_loop > 0 || var.defer_builder >= 0) && var.ticketed && in_memory && rows >= 4 && rows <= 16;
+        var.prefetch = var.ticketed && (tune.tile_prefetch > 0 || (tune.tile_prefetch == 0 && false));
     }
     return var;
 }
@@ -486,9 +530,73 @@ Generated generate(const Loop& L, const Variant& var) {
 
     // ------------------------------------------------------------ merge statements
     // (everything except vecbuilders, which the tile code handles)
-    o.f("#define WELD_MERGE(o) do { \\\n");
+    // The whole merge of one (key, values) into dictionary b, given `kb` and the value
+    // expressions: LDS table (up to three probes, admission filter), then spill queue, then
+    // the global table.  Lines of a macro body.
+    auto emit_dict_slow = [&](Out& o, size_t b, const std::vector<std::string>& vals) {
+        const weld_builder_spec_t& s = L.builders[b];
+        const int F = s.func;
+        if (var.backend[b] == BK_DICT_LDS) {
+            if (var.door_words > 0)
+                o.f("    const int sl = w_lds_slot_filtered(d%zu_lk, %d, kb, 3, d%zu_door, %d); \\\n", b, var.lds_slots, b, var.door_words);
+            else
+                o.f("    const int sl = w_lds_slot(d%zu_lk, %d, kb, 3); \\\n", b, var.lds_slots);
+            o.f("    if (sl >= 0) { \\\n");
+            for (int k = 0; k < s.nvals; ++k)
+                o.f("      w_atomic<%d>(d%zu_lv%d + sl, %s, 0); \\\n", F, b, k, vals[k].c_str());
+            o.f("    } else { \\\n");
+        } else {
+            o.f("    { \\\n");
+        }
+        const bool spill = var.backend[b] == BK_DICT_LDS && var.spill;
+        if (spill) {
+            o.f("      const i64 ei = w_spill_index(d%zu_qn, a.b%zu_qcap, %d, kb); \\\n", b, b, 1 + s.nvals);
+            o.f("      if (ei >= 0) { \\\n");
+            std::vector<std::string> words;
+            words.push_back("kb");
+            for (int k = 0; k < s.nvals; ++k) words.push_back("w_bits(" + vals[k] + ")");
+            emit_log_stores(o, b, words, " \\");
+            o.f("      } else { \\\n");
+        }
+        o.f("      const i64 g = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, kb, errp); \\\n", b, b, b);
+        o.f("      if (g >= 0) { \\\n");
+        for (int k = 0; k < s.nvals; ++k)
+            o.f("        w_atomic<%d>(a.b%zu_v%d + g, %s, 1); \\\n", F, b, k, vals[k].c_str());
+        if (spill) o.f("      } \\\n");
+        o.f("      } \\\n    } \\\n");
+    };
+    if (var.defer_builder >= 0) {
+        // the queued merges of one wavefront, 64 at a time: entry e is key word dq[e] and value
+        // words dq[cap * w + e]; merged values that are constants are not stored
+        const size_t b = (size_t)var.defer_builder;
+        const weld_builder_spec_t& s = L.builders[b];
+        const weld_merge_t& g = L.merges[L.merge_of[b]];
+        o.f("#define WELD_DRAIN() do { \\\n  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\"); \\\n");
+        o.f("  for (int qb = 0; qb < dq_n; qb += 64) { \\\n    const int e = qb + lane; \\\n    if (e < dq_n) { \\\n    const u64 kb = dq[e]; \\\n");
+        std::vector<std::string> vals;
+        int w = 1;
+        for (int k = 0; k < s.nvals; ++k) {
+            char buf[160];
+            const char* A = acc_ctype(s.val_type[k]);
+            if (L.ops[g.val[k]].opcode == WELD_OP_CONST) {
+                snprintf(buf, sizeof buf, "(%s)(%s)%s", A, ctype(s.val_type[k]), const_expr(L.ops[g.val[k]]).c_str());
+            } else {
+                snprintf(buf, sizeof buf, "w_from_bits<%s>(dq[%d + e])", A, var.defer_cap * w);
+                ++w;
+            }
+            vals.push_back(buf);
+        }
+        emit_dict_slow(o, b, vals);
+        o.f("    } \\\n  } \\\n  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\"); \\\n  dq_n = 0; \\\n} while (0)\n\n");
+    }
+
+    // which: 0 = every builder, 1 = those held in registers, 2 = those held in memory
+    auto emit_merge_macro = [&](const char* name, int which) {
+    o.f("#define %s(o) do { \\\n", name);
     for (size_t b = 0; b < NB; ++b) {
         if (L.merge_of[b] < 0) continue;
+        if (which == 1 && merges_in_memory(var.backend[b])) continue;
+        if (which == 2 && !merges_in_memory(var.backend[b])) continue;
         const weld_builder_spec_t& s = L.builders[b];
         const int F = s.func;
         if (var.backend[b] == BK_MERGER) {
@@ -531,45 +639,49 @@ Generated generate(const Loop& L, const Variant& var) {
                 o.f("      w_atomic<%d>(a.b%zu_out + ix, (%s)(o).v%zu_0, 1); \\\n", F, b, A, b);
             o.f("    } else atomicOr(errp, 4); \\\n  } \\\n");
         } else if (var.backend[b] == BK_DICT_LDS || var.backend[b] == BK_DICT_GLOBAL) {
-            o.f("  if ((o).p%zu) { \\\n", b);
-            o.f("    const u64 kb = %s; \\\n", pack_key(s, b, "(o)").c_str());
-            if (var.backend[b] == BK_DICT_LDS) {
-                if (var.door_words > 0)
-                    o.f("    const int sl = w_lds_slot_filtered(d%zu_lk, %d, kb, 3, d%zu_door, %d); \\\n", b, var.lds_slots, b, var.door_words);
-                else
-                    o.f("    const int sl = w_lds_slot(d%zu_lk, %d, kb, 3); \\\n", b, var.lds_slots);
-                o.f("    if (sl >= 0) { \\\n");
-                for (int k = 0; k < s.nvals; ++k)
-                    o.f("      w_atomic<%d>(d%zu_lv%d + sl, (%s)(o).v%zu_%d, 0); \\\n", F, b, k, acc_ctype(s.val_type[k]), b, k);
-                o.f("    } else { \\\n");
+            std::vector<std::string> vals;
+            for (int k = 0; k < s.nvals; ++k) {
+                char buf[96];
+                snprintf(buf, sizeof buf, "(%s)(o).v%zu_%d", acc_ctype(s.val_type[k]), b, k);
+                vals.push_back(buf);
+            }
+            if (var.defer_builder != (int)b) {
+                o.f("  if ((o).p%zu) { \\\n", b);
+                o.f("    const u64 kb = %s; \\\n", pack_key(s, b, "(o)").c_str());
+                emit_dict_slow(o, b, vals);
+                o.f("  } \\\n");
             } else {
-                o.f("    { \\\n");
-            }
-            const bool spill = var.backend[b] == BK_DICT_LDS && var.spill;
-            if (spill) {
-                o.f("      const i64 ei = w_spill_index(d%zu_qn, a.b%zu_qcap, %d, kb); \\\n", b, b, 1 + s.nvals);
-                o.f("      if (ei >= 0) { \\\n");
-                {
-                    std::vector<std::string> words;
-                    words.push_back("kb");
-                    for (int k = 0; k < s.nvals; ++k) {
-                        char buf[96];
-                        snprintf(buf, sizeof buf, "w_bits((%s)(o).v%zu_%d)", acc_ctype(s.val_type[k]), b, k);
-                        words.push_back(buf);
-                    }
-                    emit_log_stores(o, b, words, " \\");
+                // first probe only; whatever it does not settle is queued for the wavefront to
+                // handle 64 at a time (WELD_DRAIN), instead of every lane walking the long path
+                // of probes, admission filter, claim and overflow whenever one lane has to
+                const weld_merge_t& g = L.merges[L.merge_of[b]];
+                o.f("  { \\\n    const u64 kb = %s; \\\n    bool miss = false; \\\n", pack_key(s, b, "(o)").c_str());
+                o.f("    if ((o).p%zu) { \\\n      miss = true; \\\n      if (kb != W_EMPTY_KEY) { \\\n", b);
+                o.f("        const int s0 = (int)w_hash_slot(kb, %du); \\\n", var.lds_slots);
+                o.f("        if (__hip_atomic_load(d%zu_lk + s0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == kb) { \\\n          miss = false; \\\n", b);
+                for (int k = 0; k < s.nvals; ++k)
+                    o.f("          w_atomic<%d>(d%zu_lv%d + s0, %s, 0); \\\n", F, b, k, vals[k].c_str());
+                o.f("        } \\\n      } \\\n    } \\\n");
+                o.f("    const u64 mb = w_ballot(miss); \\\n    if (mb) { \\\n      const int add = __popcll(mb); \\\n");
+                o.f("      if (dq_n + add > %d) WELD_DRAIN(); \\\n", var.defer_cap);
+                o.f("      if (miss) { \\\n        const int e = dq_n + w_rank_below(mb); \\\n        dq[e] = kb; \\\n");
+                int w = 1;
+                for (int k = 0; k < s.nvals; ++k) {
+                    if (L.ops[g.val[k]].opcode == WELD_OP_CONST) continue;
+                    o.f("        dq[%d + e] = w_bits(%s); \\\n", var.defer_cap * w, vals[k].c_str());
+                    ++w;
                 }
-                o.f("      } else { \\\n");
+                o.f("      } \\\n      dq_n += add; \\\n    } \\\n  } \\\n");
             }
-            o.f("      const i64 g = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, kb, errp); \\\n", b, b, b);
-            o.f("      if (g >= 0) { \\\n");
-            for (int k = 0; k < s.nvals; ++k)
-                o.f("        w_atomic<%d>(a.b%zu_v%d + g, (%s)(o).v%zu_%d, 1); \\\n", F, b, k, acc_ctype(s.val_type[k]), b, k);
-            if (spill) o.f("      } \\\n");
-            o.f("      } \\\n    } \\\n  } \\\n");
         }
     }
     o.f("} while (0)\n\n");
+    };
+    emit_merge_macro("WELD_MERGE", 0);
+    if (var.merge_loop || var.prefetch) {
+        emit_merge_macro("WELD_MERGE_REG", 1);
+        emit_merge_macro("WELD_MERGE_MEM", 2);
+    }
 
     // ------------------------------------------------------------ kernel
     o.f("extern \"C\" __global__ void __launch_bounds__(W_BLOCK) weld_kernel(const KArgs a) {\n");
@@ -585,6 +697,8 @@ Generated generate(const Loop& L, const Variant& var) {
     if (var.ticketed) {
         o.f("  __shared__ i64 s_tile;\n  __shared__ i64 s_cnt[%d][W_WAVES];\n  __shared__ i64 s_pfx[%d];\n", ncompact, ncompact);
         o.f("  __shared__ u64 s_stage[W_WAVES * W_UNIT];\n");
+        if (var.defer_builder >= 0)   // the wavefront's queue of unsettled merges lives in its part of the staging buffer
+            o.f("  u64* const dq = s_stage + wave * W_UNIT;\n  int dq_n = 0;\n");
         lds += 8 + 8 * ncompact * (var.block / 64) + 8 * ncompact + 8 * (var.block / 64) * 64 * var.v;
     }
     // builder state
@@ -701,17 +815,34 @@ Generated generate(const Loop& L, const Variant& var) {
         o.f("  }\n");
     } else {
         // ---------------- ticketed tile order (needed by the look-back scan)
+        // One work-group works on one tile at a time, in phases divided by barriers: load, evaluate,
+        // count, (wait for the tiles before), merge, store.  With `prefetch` the ticket and the loads
+        // of the NEXT tile are issued as soon as this tile's counts are published, so that they are
+        // in flight while this tile merges and stores - a work-group that fills a CU on its own
+        // (large LDS table) has no neighbour to hide its load phase behind.
+        const bool P = var.prefetch;
+        const char* ticket = "(i64)__hip_atomic_fetch_add(a.ctl, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)";
         o.f("  const i64 ntiles = (a.n + W_TILE - 1) / W_TILE;\n");
-        o.f("  for (;;) {\n");
-        o.f("    if (threadIdx.x == 0) s_tile = (i64)__hip_atomic_fetch_add(a.ctl, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n");
-        o.f("    __syncthreads();\n    const i64 t = s_tile;\n    if (t >= ntiles) break;\n");
+        if (P) {
+            o.f("  if (threadIdx.x == 0) s_tile = %s;\n  __syncthreads();\n  i64 t = s_tile;\n  __syncthreads();\n", ticket);
+            o.f("  bool have = false;   // the tile's columns are already in registers\n");
+            for (int c = 0; c < L.ncols; ++c)
+                if (L.col_used[c]) o.f("  wvec<%s, W_V> x%d[W_U] = {};\n", stype(L.col_type[c]), c);
+            o.f("  while (t < ntiles) {\n");
+            o.f("    if (threadIdx.x == 0) s_tile = %s;   // the tile after this one\n", ticket);
+        } else {
+            o.f("  for (;;) {\n");
+            o.f("    if (threadIdx.x == 0) s_tile = %s;\n", ticket);
+            o.f("    __syncthreads();\n    const i64 t = s_tile;\n    if (t >= ntiles) break;\n");
+        }
         o.f("    const i64 r0 = t * W_TILE + (i64)wave * W_WAVE_ROWS + lane * W_V;\n");
         o.f("    const bool full = (t + 1) * W_TILE <= a.n;\n");
         o.f("    RowOut o[W_U][W_V];\n");
         o.f("    if (full) {\n");
-        for (int c = 0; c < L.ncols; ++c)
-            if (L.col_used[c]) o.f("      wvec<%s, W_V> x%d[W_U];\n", stype(L.col_type[c]), c);
-        o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+        if (!P)
+            for (int c = 0; c < L.ncols; ++c)
+                if (L.col_used[c]) o.f("      wvec<%s, W_V> x%d[W_U];\n", stype(L.col_type[c]), c);
+        o.f("      %s_Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n", P ? "if (!have) " : "");
         for (int c = 0; c < L.ncols; ++c)
             if (L.col_used[c]) o.f("        x%d[u] = w_load<%s, W_V>(a.c%d + r0 + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
         o.f("      }\n");
@@ -722,7 +853,64 @@ Generated generate(const Loop& L, const Variant& var) {
         o.f("          const i64 i = r0 + u * W_UNIT + k;\n");
         o.f("          if (i < a.n) { %s } else weld_row_none(o[u][k]);\n        }\n", row_call("i", "a.c%d[i]", "o[u][k]").c_str());
         o.f("    }\n");
-        o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) WELD_MERGE(o[u][k]);\n");
+        Out mm;      // merges that go to memory, when they come after the tile's counts are published
+        if (!var.merge_loop && !P) {
+            o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) WELD_MERGE(o[u][k]);\n");
+        } else if (!var.merge_loop) {
+            o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) WELD_MERGE_REG(o[u][k]);\n");
+            mm.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) WELD_MERGE_MEM(o[u][k]);\n");
+        } else {
+            // register accumulators unrolled as ever; the merges that go to memory in one loop over
+            // the lane's rows: their operands are gathered into vectors indexed by the loop counter
+            // (the compiler turns that into relative register addressing), constants stay literals
+            o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) WELD_MERGE_REG(o[u][k]);\n");
+            mm.f("    {\n");
+            std::vector<std::string> gather, scatter;     // statements filling the vectors / the row of one iteration
+            std::vector<int> seen_op, seen_pred;
+            auto vec_elem = [](int t) { return t == WELD_F64 ? "double" : t == WELD_I64 ? "i64" : "int"; };
+            char buf[256];
+            for (size_t b = 0; b < NB; ++b) {
+                const int m = L.merge_of[b];
+                if (m < 0 || !merges_in_memory(var.backend[b])) continue;
+                const weld_merge_t& g = L.merges[m];
+                if (std::find(seen_pred.begin(), seen_pred.end(), g.pred) == seen_pred.end()) {
+                    seen_pred.push_back(g.pred);
+                    mm.f("      u32 mp%d = 0;\n", g.pred + 1);
+                    snprintf(buf, sizeof buf, "mp%d |= (o[u][k].p%zu ? 1u : 0u) << (u * W_V + k);", g.pred + 1, b);
+                    gather.push_back(buf);
+                }
+                snprintf(buf, sizeof buf, "r.p%zu = (mp%d >> j) & 1u;", b, g.pred + 1);
+                scatter.push_back(buf);
+                for (int f = 0; f < g.nkeys + g.nvals; ++f) {
+                    const bool is_key = f < g.nkeys;
+                    const int fi = is_key ? f : f - g.nkeys;
+                    const int op = is_key ? g.key[fi] : g.val[fi];
+                    const int ft = is_key ? L.builders[b].key_type[fi] : L.builders[b].val_type[fi];
+                    const char* fn = is_key ? "k" : "v";
+                    if (L.ops[op].opcode == WELD_OP_CONST) {
+                        snprintf(buf, sizeof buf, "r.%s%zu_%d = (%s)%s;", fn, b, fi, ctype(ft), const_expr(L.ops[op]).c_str());
+                        scatter.push_back(buf);
+                        continue;
+                    }
+                    if (std::find(seen_op.begin(), seen_op.end(), op) == seen_op.end()) {
+                        seen_op.push_back(op);
+                        mm.f("      typedef %s mt%d_t __attribute__((ext_vector_type(W_U * W_V)));\n      mt%d_t mt%d;\n", vec_elem(L.ops[op].type), op, op, op);
+                        snprintf(buf, sizeof buf, "mt%d[u * W_V + k] = (%s)o[u][k].%s%zu_%d;", op, vec_elem(L.ops[op].type), fn, b, fi);
+                        gather.push_back(buf);
+                    }
+                    snprintf(buf, sizeof buf, "r.%s%zu_%d = (%s)mt%d[j];", fn, b, fi, ctype(ft), op);
+                    scatter.push_back(buf);
+                }
+            }
+            mm.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
+            for (const std::string& g : gather) mm.f("          %s\n", g.c_str());
+            mm.f("        }\n");
+            mm.f("      _Pragma(\"unroll 1\") for (int j = 0; j < W_U * W_V; ++j) {\n        RowOut r;\n");
+            for (const std::string& g : scatter) mm.f("        %s\n", g.c_str());
+            mm.f("        WELD_MERGE_MEM(r);\n      }\n");
+            if (var.defer_builder >= 0) mm.f("      WELD_DRAIN();\n");
+            mm.f("    }\n");
+        }
         // direct vecbuilders inside a ticketed kernel
         for (size_t b = 0; b < NB; ++b)
             if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) {
@@ -743,6 +931,14 @@ Generated generate(const Loop& L, const Variant& var) {
             ++j;
         }
         o.f("    __syncthreads();\n");
+        if (P) {
+            o.f("    const i64 tn = s_tile;\n    const bool fulln = (tn + 1) * W_TILE <= a.n;\n");
+            o.f("    if (fulln) {\n      const i64 rn = tn * W_TILE + (i64)wave * W_WAVE_ROWS + lane * W_V;\n");
+            o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+            for (int c = 0; c < L.ncols; ++c)
+                if (L.col_used[c]) o.f("        x%d[u] = w_load<%s, W_V>(a.c%d + rn + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
+            o.f("      }\n    }\n");
+        }
         o.f("    if (wave == 0) {\n");
         j = 0;
         for (size_t b = 0; b < NB; ++b) {
@@ -752,7 +948,10 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("        if (lane == 0) {\n          s_pfx[%d] = ex;\n          if (t == ntiles - 1) *a.b%zu_len = ex + tot;\n        }\n      }\n", j, b);
             ++j;
         }
-        o.f("    }\n    __syncthreads();\n");
+        o.f("    }\n");
+        // while the first wavefront waits for the tiles before this one, the others merge
+        o.f("%s", mm.s.c_str());
+        o.f("    __syncthreads();\n");
         j = 0;
         for (size_t b = 0; b < NB; ++b) {
             if (var.backend[b] != BK_VEC_COMPACT) continue;
@@ -770,6 +969,7 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("          if (e < uc%zu[u]) __builtin_nontemporal_store(stg[e], a.b%zu_out + base + uo%zu[u] + e);\n        }\n      }\n    }\n", b, b, b);
             ++j;
         }
+        if (P) o.f("    t = tn;\n    have = fulln;\n");
         o.f("  }\n");
     }
 

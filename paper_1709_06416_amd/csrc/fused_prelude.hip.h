@@ -284,6 +284,23 @@ template <int F> __device__ __forceinline__ void w_atomic_i64(i64* p, i64 v, con
 template <int F> __device__ __forceinline__ void w_atomic(double* p, double v, const int agent) { w_atomic_f64<F>(p, v, agent); }
 template <int F> __device__ __forceinline__ void w_atomic(i64* p, i64 v, const int agent) { w_atomic_i64<F>(p, v, agent); }
 
+// ---------------------------------------------------------------- division by a constant
+// x / D and x % D for a 64-bit x and a compile-time D in [2, 2^31): the compiler turns them
+// into a 64 x 64 -> 128-bit multiplication (ten quarter-rate 32-bit multiplications with the
+// correction); when every lane of the wavefront holds 0 <= x < 2^32 - columns of codes, dates
+// and identifiers mostly do - a 32-bit one does.  `live` = the row needs the result at all:
+// the other lanes do not force the long path.
+template <i64 D> __device__ __forceinline__ i64 w_div_const(i64 x, bool live) {
+    if (!live) x = 0;
+    if (w_ballot((u64)x >> 32 != 0) == 0) return (i64)((u32)x / (u32)D);
+    return x / D;
+}
+template <i64 D> __device__ __forceinline__ i64 w_mod_const(i64 x, bool live) {
+    if (!live) x = 0;
+    if (w_ballot((u64)x >> 32 != 0) == 0) return (i64)((u32)x % (u32)D);
+    return x % D;
+}
+
 // ---------------------------------------------------------------- hash tables
 // 32-bit multiplicative (Fibonacci) hash of the folded key: a handful of 32-bit
 // instructions; callers take the HIGH bits (w_hash(k) >> (32 - log2 slots)).
@@ -293,6 +310,16 @@ __device__ __forceinline__ u32 w_hash(u64 k) {
 }
 __device__ __forceinline__ u32 w_hash_slot(u64 k, u32 slots) {   // slots is a power of two >= 2
     return w_hash(k) >> (__builtin_clz(slots) + 1);
+}
+// Second hash (admission filter bits, spill partition), all of whose bits depend on all of
+// w_hash's: given the high bits that pick a table slot, it still takes every value.  One more
+// 32-bit multiplication - these run at a quarter of the rate of other vector instructions,
+// which is what the loops over large dictionaries are bound by.
+__device__ __forceinline__ u32 w_hash2(u64 k) {
+    u32 h = w_hash(k);
+    h ^= h >> 15;
+    h *= 0x2c1b3c6du;
+    return h ^ (h >> 13);
 }
 
 // Global open-addressing table (linear probing, power-of-two slot count, keys packed
@@ -378,7 +405,7 @@ __device__ __forceinline__ int w_lds_slot_filtered(u64* keys, int slots, u64 kbi
         u64 cur = __hip_atomic_load(keys + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         if (cur == kbits) return s;
         if (cur == W_EMPTY_KEY) {
-            const u32 h2 = w_hash(kbits * 0xc2b2ae3d27d4eb4full + 0x165667b19e3779f9ull);
+            const u32 h2 = w_hash2(kbits);
             const u32 bit = 1u << (h2 & 31);
             const u32 seen = __hip_atomic_fetch_or(door + ((h2 >> 5) & (door_words - 1)), bit, __ATOMIC_RELAXED,
                                                    __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -404,10 +431,13 @@ __device__ __forceinline__ int w_lds_slot_filtered(u64* keys, int slots, u64 kbi
 // partition in LDS.
 #define W_SPILL_PARTS 256
 __device__ __forceinline__ i64 w_spill_index(u32* qn, i64 cap, int words, u64 kbits) {
-    const u32 part = w_hash(kbits * 0xc2b2ae3d27d4eb4full + 0x165667b19e3779f9ull) >> 24;
+    const u32 part = w_hash2(kbits) >> 24;
     const u32 pos = __hip_atomic_fetch_add(qn + part, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    if ((i64)pos >= cap) return -1;
-    return (i64)((((u64)blockIdx.x * W_SPILL_PARTS + part) * (u64)cap + pos) * (u64)words);
+    if (pos >= (u32)cap) return -1;
+    // cap < 2^23 (the host sees to it): the entry's index inside the work-group's block of
+    // segments fits 32 bits and takes a 24-bit multiplication; the block's base is scalar
+    const u32 local = __umul24(part, (u32)cap) + pos;
+    return (i64)(((u64)blockIdx.x * W_SPILL_PARTS * (u64)cap + local) * (u64)words);
 }
 // Stores to device memory that say so (a pointer that went through a select or a helper is
 // otherwise stored through with flat instructions, which also count as LDS operations and
@@ -426,6 +456,11 @@ __device__ __forceinline__ u64 w_bits(double v) {
     return b;
 }
 __device__ __forceinline__ u64 w_bits(i64 v) { return (u64)v; }
+template <class T> __device__ __forceinline__ T w_from_bits(u64 b) {
+    T v;
+    __builtin_memcpy(&v, &b, 8);
+    return v;
+}
 
 // Register-slot dictionary for a handful of groups: the work-group keeps the list
 // of keys it has met in LDS (append-only); every lane accumulates each group in

@@ -362,6 +362,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             const double mean = (rows + var.lds_slots) / kSpillParts;
             cap = (int64_t)(mean + 6.0 * std::sqrt(mean) + 16.0);
         }
+        if (cap > (1 << 23) - 1) cap = (1 << 23) - 1;   // the kernel indexes a work-group's segments with 32 bits
         const size_t seg = (size_t)grid * kSpillParts * entry;
         if (conf.memory_limit > 0) {
             const int64_t room = conf.memory_limit - (int64_t)lay.total;

@@ -153,6 +153,11 @@ struct Variant {
     int door_words = 0;   // > 0: admission filter of that many 32-bit words in front of the LDS table
     bool spill = false;   // merges that miss the LDS dictionary are appended to key-partitioned queues
                           // which a second kernel aggregates, instead of device atomics on the global table
+    bool merge_loop = false;    // merges into builders that live in memory run in one loop over the rows a
+                                // lane holds (their code exists once per kernel instead of once per row)
+    int defer_builder = -1;     // LDS dictionary whose merges beyond the first probe are queued per wavefront
+    int defer_cap = 0;          // and handled 64 at a time; entries the queue holds
+    bool prefetch = false;      // ticketed tiles: the next tile's ticket and loads are issued while this one merges and stores
     std::vector<int> backend;   // per builder
 };
 

@@ -374,6 +374,74 @@ def test_other_stream(wb):
         _check(wb, configs.program_c3(), cols, label="side stream")
 
 
+def _mixed_memory_builders():
+    """Compaction + struct-key dictmerger with two value fields + vecmerger, under different predicates."""
+    p = Program(["i8", "i32", "f64", "i64"])
+    k1, k2, x, y = p.col(0), p.col(1), p.col(2), p.col(3)
+    pa = p.bin("gt", x, p.const("f64", 0.0))
+    pb = p.bin("ne", k1, p.const("i8", 1))
+    p.merge(p.vecbuilder("f64"), x, pred=pa)
+    p.merge(p.dictmerger(["i8", "i32"], ["f64", "i64"], "add", 40_000), [x, y], keys=[k1, k2], pred=pb)
+    p.merge(p.vecmerger("i64", "add", 5000), p.const("i64", 2),
+            keys=[p.bin("mod", p.bin("mul", y, y), p.const("i64", 5000))], pred=pa)
+    return p
+
+
+@pytest.mark.parametrize("tune", [None, {"dict_defer": -1}, {"dict_defer": -1, "merge_loop": 1}, {"tile_prefetch": 1},
+                                  {"dict_defer": -1, "tile_prefetch": 1}, {"units_per_thread": 2},
+                                  {"block_threads": 256, "grid_blocks": 3, "tile_prefetch": 1}, {"lds_dict_slots": 256}])
+def test_merge_phase_variants_of_compacting_loops(wb, tune):
+    """Loops that compact and merge into builders held in memory: merges unrolled or as one loop
+    over the lane's rows, LDS-table misses walked in place or queued per wavefront, next tile's
+    loads issued early or not - every variant gives the oracle's result."""
+    for n in (0, 1, 4097, 300_007):
+        _check(wb, configs.program_c5(), configs.make_columns("C5", n, device="cuda"), label="C5 %d %s" % (n, tune), tune=tune)
+    _check(wb, _group_on_c5(), configs.make_columns("C5", 120_001, device="cuda"), label="groups %s" % tune, tune=tune)
+    rnd = np.random.RandomState(5)
+    n = 200_003
+    cols = [_dev(a) for a in (rnd.randint(-2, 3, size=n).astype(np.int8), (rnd.zipf(1.3, size=n) % 30000).astype(np.int32) * 3,
+                              rnd.uniform(-1, 3, size=n), rnd.randint(-1000, 1000, size=n).astype(np.int64))]
+    _check(wb, _mixed_memory_builders(), cols, label="mixed %s" % tune, tune=tune)
+
+
+def test_division_by_a_constant_takes_the_same_value_on_both_paths(wb):
+    """i64 / and % by a small constant use 32-bit arithmetic when a wavefront's operands fit and
+    the 64-bit form otherwise: columns that fit, columns that do not, and mixtures (also with
+    negative values and values only the predicate excludes) agree with the oracle bit for bit."""
+    rnd = np.random.RandomState(11)
+    n = 100_003
+    small = rnd.randint(0, 2**32, size=n, dtype=np.int64)
+    wide = rnd.randint(-2**62, 2**62, size=n, dtype=np.int64)
+    mixed = np.where(rnd.uniform(size=n) < 0.01, wide, small)
+    edge = np.array([0, 1, 2**32 - 1, 2**32, 2**32 + 1, -1, -2**32, 2**63 - 1, -2**63, 99_999, 100_000, 100_001] * 10, dtype=np.int64)
+    for d in (2, 7, 100_000, 2**31 - 1):
+        p = Program(["i64"])
+        x = p.col(0)
+        p.merge(p.vecbuilder("i64"), p.bin("mod", x, p.const("i64", d)))
+        p.merge(p.vecbuilder("i64"), p.bin("div", x, p.const("i64", d)))
+        p.merge(p.vecbuilder("i64"), p.bin("mod", x, p.const("i64", d)), pred=p.bin("gt", x, p.const("i64", 0)))
+        p.merge(p.merger("i64", "add"), p.bin("div", x, p.const("i64", d)), pred=p.bin("lt", x, p.const("i64", 5)))
+        for name, col in (("small", small), ("wide", wide), ("mixed", mixed), ("edge", edge)):
+            _check(wb, p, [_dev(col)], label="div/mod by %d, %s" % (d, name))
+
+
+def test_prepared_loop_runs_repeatedly_on_different_inputs(wb):
+    """A loop description marshalled once (prepare) and run on inputs of different sizes, with
+    a tuning that differs from the default, matches the oracle every time."""
+    from tests import parity
+    for name, tune in (("C4", {"dict_strategy": 2}), ("C5", None), ("C2", None)):
+        prog = configs.PROGRAMS[name]()
+        loop = wb.prepare(prog, tune=tune)
+        for n in (70_001, 0, 5_003, 70_001):
+            cols = configs.make_columns(name, n, device="cuda", seed=n + 1)
+            want = parity.oracle_results(prog, cols, None)
+            res = wb.fused_for(loop, cols)
+            try:
+                parity.assert_matches(prog, res, want, map_floor=1.0 if name == "C2" else 0.0, label="%s prepared %d" % (name, n))
+            finally:
+                res.free()
+
+
 def test_single_library_instance_loaded():
     # the library must bind to the HIP runtime torch already loaded, not a second copy
     libs = set()
