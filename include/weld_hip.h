@@ -179,9 +179,6 @@ typedef struct {
     int32_t dict_defer;         /* LDS hash table in a loop that also compacts: 0 = merges that the first
                                    probe does not settle are queued per wavefront and handled 64 at a
                                    time, -1 = every merge walks the whole path where it stands      */
-    int32_t tile_prefetch;      /* loops that compact (tiles handed out in order): 1 = the next tile's
-                                   columns are loaded while the current tile merges and stores, -1 = each
-                                   tile loads when it starts, 0 = library's choice                    */
 } weld_tuning_t;
 
 typedef struct {

@@ -441,7 +441,6 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
             if (cap >= 64) { var.defer_builder = which; var.defer_cap = cap; }
         }
         var.merge_loop = (tune.merge_loop > 0 || var.defer_builder >= 0) && var.ticketed && in_memory && rows >= 4 && rows <= 16;
-        var.prefetch = var.ticketed && (tune.tile_prefetch > 0 || (tune.tile_prefetch == 0 && false));
     }
     return var;
 }
@@ -678,7 +677,7 @@ Generated generate(const Loop& L, const Variant& var) {
     o.f("} while (0)\n\n");
     };
     emit_merge_macro("WELD_MERGE", 0);
-    if (var.merge_loop || var.prefetch) {
+    if (var.merge_loop) {
         emit_merge_macro("WELD_MERGE_REG", 1);
         emit_merge_macro("WELD_MERGE_MEM", 2);
     }
@@ -815,34 +814,20 @@ Generated generate(const Loop& L, const Variant& var) {
         o.f("  }\n");
     } else {
         // ---------------- ticketed tile order (needed by the look-back scan)
-        // One work-group works on one tile at a time, in phases divided by barriers: load, evaluate,
-        // count, (wait for the tiles before), merge, store.  With `prefetch` the ticket and the loads
-        // of the NEXT tile are issued as soon as this tile's counts are published, so that they are
-        // in flight while this tile merges and stores - a work-group that fills a CU on its own
-        // (large LDS table) has no neighbour to hide its load phase behind.
-        const bool P = var.prefetch;
-        const char* ticket = "(i64)__hip_atomic_fetch_add(a.ctl, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)";
+        // A tile's ticket is drawn when the tile starts, not earlier: tickets order the look-back,
+        // and a tile that waits for one drawn ahead of time waits for a work-group that is still
+        // busy with its previous tile (measured: tickets drawn one tile ahead cost C5 20 %).
         o.f("  const i64 ntiles = (a.n + W_TILE - 1) / W_TILE;\n");
-        if (P) {
-            o.f("  if (threadIdx.x == 0) s_tile = %s;\n  __syncthreads();\n  i64 t = s_tile;\n  __syncthreads();\n", ticket);
-            o.f("  bool have = false;   // the tile's columns are already in registers\n");
-            for (int c = 0; c < L.ncols; ++c)
-                if (L.col_used[c]) o.f("  wvec<%s, W_V> x%d[W_U] = {};\n", stype(L.col_type[c]), c);
-            o.f("  while (t < ntiles) {\n");
-            o.f("    if (threadIdx.x == 0) s_tile = %s;   // the tile after this one\n", ticket);
-        } else {
-            o.f("  for (;;) {\n");
-            o.f("    if (threadIdx.x == 0) s_tile = %s;\n", ticket);
-            o.f("    __syncthreads();\n    const i64 t = s_tile;\n    if (t >= ntiles) break;\n");
-        }
+        o.f("  for (;;) {\n");
+        o.f("    if (threadIdx.x == 0) s_tile = (i64)__hip_atomic_fetch_add(a.ctl, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n");
+        o.f("    __syncthreads();\n    const i64 t = s_tile;\n    if (t >= ntiles) break;\n");
         o.f("    const i64 r0 = t * W_TILE + (i64)wave * W_WAVE_ROWS + lane * W_V;\n");
         o.f("    const bool full = (t + 1) * W_TILE <= a.n;\n");
         o.f("    RowOut o[W_U][W_V];\n");
         o.f("    if (full) {\n");
-        if (!P)
-            for (int c = 0; c < L.ncols; ++c)
-                if (L.col_used[c]) o.f("      wvec<%s, W_V> x%d[W_U];\n", stype(L.col_type[c]), c);
-        o.f("      %s_Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n", P ? "if (!have) " : "");
+        for (int c = 0; c < L.ncols; ++c)
+            if (L.col_used[c]) o.f("      wvec<%s, W_V> x%d[W_U];\n", stype(L.col_type[c]), c);
+        o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
         for (int c = 0; c < L.ncols; ++c)
             if (L.col_used[c]) o.f("        x%d[u] = w_load<%s, W_V>(a.c%d + r0 + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
         o.f("      }\n");
@@ -854,62 +839,85 @@ Generated generate(const Loop& L, const Variant& var) {
         o.f("          if (i < a.n) { %s } else weld_row_none(o[u][k]);\n        }\n", row_call("i", "a.c%d[i]", "o[u][k]").c_str());
         o.f("    }\n");
         Out mm;      // merges that go to memory, when they come after the tile's counts are published
-        if (!var.merge_loop && !P) {
+        Out gather_text;
+        bool gathered = false;
+        std::vector<int> seen_op, seen_pred;
+        // how the later phases name "row (u, k) is selected for builder b" and its value
+        auto sel_expr = [&](size_t b) {
+            char buf[96];
+            if (gathered) snprintf(buf, sizeof buf, "((mp%d >> (u * W_V + k)) & 1u)", L.merges[L.merge_of[b]].pred + 1);
+            else snprintf(buf, sizeof buf, "o[u][k].p%zu", b);
+            return std::string(buf);
+        };
+        auto val_expr = [&](size_t b) {
+            char buf[96];
+            if (gathered) snprintf(buf, sizeof buf, "mt%d[u * W_V + k]", L.merges[L.merge_of[b]].val[0]);
+            else snprintf(buf, sizeof buf, "o[u][k].v%zu_0", b);
+            return std::string(buf);
+        };
+        if (!var.merge_loop) {
             o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) WELD_MERGE(o[u][k]);\n");
-        } else if (!var.merge_loop) {
-            o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) WELD_MERGE_REG(o[u][k]);\n");
-            mm.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) WELD_MERGE_MEM(o[u][k]);\n");
         } else {
             // register accumulators unrolled as ever; the merges that go to memory in one loop over
             // the lane's rows: their operands are gathered into vectors indexed by the loop counter
             // (the compiler turns that into relative register addressing), constants stay literals
             o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) WELD_MERGE_REG(o[u][k]);\n");
-            mm.f("    {\n");
+            // What the rows of the tile leave behind for the later phases - the operands of the
+            // merges that go to memory and the values and predicates of the compacting vecbuilders -
+            // is gathered into vectors (one per IR value) and bit masks (one per predicate) of
+            // tile scope; the row structs die here, and a value used twice is held once.
             std::vector<std::string> gather, scatter;     // statements filling the vectors / the row of one iteration
-            std::vector<int> seen_op, seen_pred;
             auto vec_elem = [](int t) { return t == WELD_F64 ? "double" : t == WELD_I64 ? "i64" : "int"; };
             char buf[256];
+            Out decl;
             for (size_t b = 0; b < NB; ++b) {
                 const int m = L.merge_of[b];
-                if (m < 0 || !merges_in_memory(var.backend[b])) continue;
+                const bool mem = m >= 0 && merges_in_memory(var.backend[b]);
+                if (m < 0 || (!mem && var.backend[b] != BK_VEC_COMPACT)) continue;
                 const weld_merge_t& g = L.merges[m];
                 if (std::find(seen_pred.begin(), seen_pred.end(), g.pred) == seen_pred.end()) {
                     seen_pred.push_back(g.pred);
-                    mm.f("      u32 mp%d = 0;\n", g.pred + 1);
+                    decl.f("    u32 mp%d = 0;\n", g.pred + 1);
                     snprintf(buf, sizeof buf, "mp%d |= (o[u][k].p%zu ? 1u : 0u) << (u * W_V + k);", g.pred + 1, b);
                     gather.push_back(buf);
                 }
-                snprintf(buf, sizeof buf, "r.p%zu = (mp%d >> j) & 1u;", b, g.pred + 1);
-                scatter.push_back(buf);
+                if (mem) {
+                    snprintf(buf, sizeof buf, "r.p%zu = (mp%d >> j) & 1u;", b, g.pred + 1);
+                    scatter.push_back(buf);
+                }
                 for (int f = 0; f < g.nkeys + g.nvals; ++f) {
                     const bool is_key = f < g.nkeys;
                     const int fi = is_key ? f : f - g.nkeys;
                     const int op = is_key ? g.key[fi] : g.val[fi];
                     const int ft = is_key ? L.builders[b].key_type[fi] : L.builders[b].val_type[fi];
                     const char* fn = is_key ? "k" : "v";
-                    if (L.ops[op].opcode == WELD_OP_CONST) {
+                    if (mem && L.ops[op].opcode == WELD_OP_CONST) {
                         snprintf(buf, sizeof buf, "r.%s%zu_%d = (%s)%s;", fn, b, fi, ctype(ft), const_expr(L.ops[op]).c_str());
                         scatter.push_back(buf);
                         continue;
                     }
                     if (std::find(seen_op.begin(), seen_op.end(), op) == seen_op.end()) {
                         seen_op.push_back(op);
-                        mm.f("      typedef %s mt%d_t __attribute__((ext_vector_type(W_U * W_V)));\n      mt%d_t mt%d;\n", vec_elem(L.ops[op].type), op, op, op);
+                        decl.f("    typedef %s mt%d_t __attribute__((ext_vector_type(W_U * W_V)));\n    mt%d_t mt%d;\n", vec_elem(L.ops[op].type), op, op, op);
                         snprintf(buf, sizeof buf, "mt%d[u * W_V + k] = (%s)o[u][k].%s%zu_%d;", op, vec_elem(L.ops[op].type), fn, b, fi);
                         gather.push_back(buf);
                     }
-                    snprintf(buf, sizeof buf, "r.%s%zu_%d = (%s)mt%d[j];", fn, b, fi, ctype(ft), op);
-                    scatter.push_back(buf);
+                    if (mem) {
+                        snprintf(buf, sizeof buf, "r.%s%zu_%d = (%s)mt%d[j];", fn, b, fi, ctype(ft), op);
+                        scatter.push_back(buf);
+                    }
                 }
             }
-            mm.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
-            for (const std::string& g : gather) mm.f("          %s\n", g.c_str());
-            mm.f("        }\n");
-            mm.f("      _Pragma(\"unroll 1\") for (int j = 0; j < W_U * W_V; ++j) {\n        RowOut r;\n");
-            for (const std::string& g : scatter) mm.f("        %s\n", g.c_str());
-            mm.f("        WELD_MERGE_MEM(r);\n      }\n");
-            if (var.defer_builder >= 0) mm.f("      WELD_DRAIN();\n");
-            mm.f("    }\n");
+            gathered = true;
+            // the gather itself comes after the direct vecbuilders below, the last readers of the row structs
+            gather_text.f("%s", decl.s.c_str());
+            gather_text.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
+            for (const std::string& g : gather) gather_text.f("        %s\n", g.c_str());
+            gather_text.f("      }\n");
+            mm.f("    _Pragma(\"unroll 1\") for (int j = 0; j < W_U * W_V; ++j) {\n      RowOut r;\n");
+            for (const std::string& g : scatter) mm.f("      %s\n", g.c_str());
+            mm.f("      WELD_MERGE_MEM(r);\n    }\n");
+            if (var.defer_builder >= 0) mm.f("    WELD_DRAIN();\n");
         }
         // direct vecbuilders inside a ticketed kernel
         for (size_t b = 0; b < NB; ++b)
@@ -917,28 +925,22 @@ Generated generate(const Loop& L, const Variant& var) {
                 o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
                 o.f("        const i64 i = r0 + u * W_UNIT + k;\n        if (i < a.n) a.b%zu_out[i] = o[u][k].v%zu_0;\n      }\n", b, b);
             }
+        o.f("%s", gather_text.s.c_str());
         // ranks of the selected rows inside this wavefront's run, per compacting builder
         int j = 0;
         for (size_t b = 0; b < NB; ++b) {
             if (var.backend[b] != BK_VEC_COMPACT) continue;
-            o.f("    int rk%zu[W_U][W_V];\n    int uo%zu[W_U], uc%zu[W_U];\n    {\n      int wtot = 0;\n", b, b, b);
-            o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n        int below = 0, utot = 0, mine = 0;\n");
-            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
-            o.f("          const u64 bal = w_ballot(o[u][k].p%zu);\n          below += w_rank_below(bal);\n          utot += __popcll(bal);\n        }\n", b);
-            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n          rk%zu[u][k] = below + mine;\n          mine += o[u][k].p%zu ? 1 : 0;\n        }\n", b, b);
+            // per load unit: how many rows the wavefront selected and where its run starts; the rank
+            // of a row inside the run is recomputed when the values are staged (a few instructions,
+            // cheaper than holding sixteen ranks per lane through the merge phase)
+            o.f("    int uo%zu[W_U], uc%zu[W_U];\n    {\n      int wtot = 0;\n", b, b);
+            o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n        int utot = 0;\n");
+            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) utot += __popcll(w_ballot(%s));\n", sel_expr(b).c_str());
             o.f("        uo%zu[u] = wtot;\n        uc%zu[u] = utot;\n        wtot += utot;\n      }\n", b, b);
             o.f("      if (lane == 0) s_cnt[%d][wave] = wtot;\n    }\n", j);
             ++j;
         }
         o.f("    __syncthreads();\n");
-        if (P) {
-            o.f("    const i64 tn = s_tile;\n    const bool fulln = (tn + 1) * W_TILE <= a.n;\n");
-            o.f("    if (fulln) {\n      const i64 rn = tn * W_TILE + (i64)wave * W_WAVE_ROWS + lane * W_V;\n");
-            o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
-            for (int c = 0; c < L.ncols; ++c)
-                if (L.col_used[c]) o.f("        x%d[u] = w_load<%s, W_V>(a.c%d + rn + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
-            o.f("      }\n    }\n");
-        }
         o.f("    if (wave == 0) {\n");
         j = 0;
         for (size_t b = 0; b < NB; ++b) {
@@ -963,13 +965,13 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("      %s* const stg = (%s*)(s_stage + wave * W_UNIT);\n", ST, ST);
             o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
             o.f("        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\");\n");
-            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k)\n          if (o[u][k].p%zu) stg[rk%zu[u][k]] = (%s)o[u][k].v%zu_0;\n", b, b, ST, b);
+            o.f("        int rank = 0;\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) rank += w_rank_below(w_ballot(%s));\n", sel_expr(b).c_str());
+            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k)\n          if (%s) stg[rank++] = (%s)%s;\n", sel_expr(b).c_str(), ST, val_expr(b).c_str());
             o.f("        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\");\n");
             o.f("        _Pragma(\"unroll\") for (int q = 0; q < W_V; ++q) {\n          const int e = q * 64 + lane;\n");
             o.f("          if (e < uc%zu[u]) __builtin_nontemporal_store(stg[e], a.b%zu_out + base + uo%zu[u] + e);\n        }\n      }\n    }\n", b, b, b);
             ++j;
         }
-        if (P) o.f("    t = tn;\n    have = fulln;\n");
         o.f("  }\n");
     }
 

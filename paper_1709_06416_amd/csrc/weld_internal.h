@@ -157,7 +157,6 @@ struct Variant {
                                 // lane holds (their code exists once per kernel instead of once per row)
     int defer_builder = -1;     // LDS dictionary whose merges beyond the first probe are queued per wavefront
     int defer_cap = 0;          // and handled 64 at a time; entries the queue holds
-    bool prefetch = false;      // ticketed tiles: the next tile's ticket and loads are issued while this one merges and stores
     std::vector<int> backend;   // per builder
 };
 

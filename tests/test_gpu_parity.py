@@ -387,13 +387,12 @@ def _mixed_memory_builders():
     return p
 
 
-@pytest.mark.parametrize("tune", [None, {"dict_defer": -1}, {"dict_defer": -1, "merge_loop": 1}, {"tile_prefetch": 1},
-                                  {"dict_defer": -1, "tile_prefetch": 1}, {"units_per_thread": 2},
-                                  {"block_threads": 256, "grid_blocks": 3, "tile_prefetch": 1}, {"lds_dict_slots": 256}])
+@pytest.mark.parametrize("tune", [None, {"dict_defer": -1}, {"dict_defer": -1, "merge_loop": 1}, {"units_per_thread": 2},
+                                  {"units_per_thread": 1}, {"block_threads": 256, "grid_blocks": 3}, {"lds_dict_slots": 256}])
 def test_merge_phase_variants_of_compacting_loops(wb, tune):
     """Loops that compact and merge into builders held in memory: merges unrolled or as one loop
-    over the lane's rows, LDS-table misses walked in place or queued per wavefront, next tile's
-    loads issued early or not - every variant gives the oracle's result."""
+    over the lane's rows, LDS-table misses walked in place or queued per wavefront - every variant
+    gives the oracle's result."""
     for n in (0, 1, 4097, 300_007):
         _check(wb, configs.program_c5(), configs.make_columns("C5", n, device="cuda"), label="C5 %d %s" % (n, tune), tune=tune)
     _check(wb, _group_on_c5(), configs.make_columns("C5", 120_001, device="cuda"), label="groups %s" % tune, tune=tune)
