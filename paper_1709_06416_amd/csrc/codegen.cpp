@@ -154,7 +154,9 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
     auto guarded = [&](size_t i) { return need[i] >= 0 && need[i] < (int)i; };
 
     // ---- the body, one statement per IR operator
-    o.f("__device__ __forceinline__ void weld_row(const i64 i");
+    // W_CONV: every lane of the wavefront makes this call together (full tiles); only then may the
+    // body take decisions for the whole wavefront
+    o.f("template <bool W_CONV> __device__ __forceinline__ void weld_row(const i64 i");
     if (segmented) o.f(", const i64 row");
     if (segmented || L.ndicts > 0) o.f(", const KArgs& a, int* errp");
     for (int c = 0; c < L.ncols; ++c)
@@ -205,7 +207,7 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
                     else o.f("fmod(t%d, t%d)", q.a, q.b);
                 } else if (q.type == WELD_I64 && d.opcode == WELD_OP_CONST && d.imm.i64 >= 2 && d.imm.i64 < (1ll << 31)) {
                     // 64-bit operand, small constant divisor: 32-bit arithmetic when the wavefront's operands allow
-                    o.f("w_%s_const<%lldll>(t%d, ", div ? "div" : "mod", (long long)d.imm.i64, q.a);
+                    o.f("w_%s_const<%lldll, W_CONV>(t%d, ", div ? "div" : "mod", (long long)d.imm.i64, q.a);
                     if (guarded(i)) o.f("t%d)", need[i]);
                     else o.f("true)");
                 } else {
@@ -754,9 +756,9 @@ Generated generate(const Loop& L, const Variant& var) {
     if (need_sync) o.f("  __syncthreads();\n");
 
     // row evaluation call text
-    auto row_call = [&](const char* idx, const char* fmt_col, const char* dst) {
+    auto row_call = [&](const char* idx, const char* fmt_col, const char* dst, bool together) {
         // fmt_col is a printf format taking the column number
-        std::string c = "weld_row(";
+        std::string c = together ? "weld_row<true>(" : "weld_row<false>(";
         c += idx;
         if (L.ndicts > 0) c += ", a, errp";
         for (int k = 0; k < L.ncols; ++k)
@@ -794,7 +796,7 @@ Generated generate(const Loop& L, const Variant& var) {
         for (size_t b = 0; b < NB; ++b)
             if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) o.f("      wvec<%s, W_V> y%zu;\n", stype(L.builders[b].val_type[0]), b);
         o.f("      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
-        o.f("        RowOut o;\n        %s\n", row_call("r0 + u * W_UNIT + k", "x%d[u].e[k]", "o").c_str());
+        o.f("        RowOut o;\n        %s\n", row_call("r0 + u * W_UNIT + k", "x%d[u].e[k]", "o", true).c_str());
         o.f("        WELD_MERGE(o);\n");
         for (size_t b = 0; b < NB; ++b)
             if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) o.f("        y%zu.e[k] = o.v%zu_0;\n", b, b);
@@ -808,7 +810,7 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("  for (i64 i = nfull * W_TILE + (i64)member * W_BLOCK + threadIdx.x; i < a.n; i += (i64)members * W_BLOCK) {\n");
         else
             o.f("  for (i64 i = nfull * W_TILE + (i64)blockIdx.x * W_BLOCK + threadIdx.x; i < a.n; i += (i64)gridDim.x * W_BLOCK) {\n");
-        o.f("    RowOut o;\n    %s\n    WELD_MERGE(o);\n", row_call("i", "a.c%d[i]", "o").c_str());
+        o.f("    RowOut o;\n    %s\n    WELD_MERGE(o);\n", row_call("i", "a.c%d[i]", "o", false).c_str());
         for (size_t b = 0; b < NB; ++b)
             if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) o.f("    a.b%zu_out[i] = o.v%zu_0;\n", b, b);
         o.f("  }\n");
@@ -832,11 +834,11 @@ Generated generate(const Loop& L, const Variant& var) {
             if (L.col_used[c]) o.f("        x%d[u] = w_load<%s, W_V>(a.c%d + r0 + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
         o.f("      }\n");
         o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
-        o.f("          %s\n        }\n", row_call("r0 + u * W_UNIT + k", "x%d[u].e[k]", "o[u][k]").c_str());
+        o.f("          %s\n        }\n", row_call("r0 + u * W_UNIT + k", "x%d[u].e[k]", "o[u][k]", true).c_str());
         o.f("    } else {\n");
         o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
         o.f("          const i64 i = r0 + u * W_UNIT + k;\n");
-        o.f("          if (i < a.n) { %s } else weld_row_none(o[u][k]);\n        }\n", row_call("i", "a.c%d[i]", "o[u][k]").c_str());
+        o.f("          if (i < a.n) { %s } else weld_row_none(o[u][k]);\n        }\n", row_call("i", "a.c%d[i]", "o[u][k]", false).c_str());
         o.f("    }\n");
         Out mm;      // merges that go to memory, when they come after the tile's counts are published
         Out gather_text;
@@ -1180,7 +1182,7 @@ Generated generate_segmented(const Loop& L, const Variant& var, int offset_type)
     o.f("    RowOut o[W_U][W_V];\n");
     o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
     o.f("        const i64 e = base + u * W_UNIT + k;\n");
-    o.f("        if (e < e1) weld_row(e, r0 + rowid[u][k], a, errp%s, o[u][k]); else weld_row_none(o[u][k]);\n      }\n", call_args.c_str());
+    o.f("        if (e < e1) weld_row<false>(e, r0 + rowid[u][k], a, errp%s, o[u][k]); else weld_row_none(o[u][k]);\n      }\n", call_args.c_str());
     // ---- segmented combine: runs of equal outer element in registers, one atomic per run
     o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
     o.f("      %s acc = %s;\n      bool any = false;\n      int cur = rowid[u][0];\n", A, ID.c_str());

@@ -289,15 +289,23 @@ template <int F> __device__ __forceinline__ void w_atomic(i64* p, i64 v, const i
 // into a 64 x 64 -> 128-bit multiplication (ten quarter-rate 32-bit multiplications with the
 // correction); when every lane of the wavefront holds 0 <= x < 2^32 - columns of codes, dates
 // and identifiers mostly do - a 32-bit one does.  `live` = the row needs the result at all:
-// the other lanes do not force the long path.
-template <i64 D> __device__ __forceinline__ i64 w_div_const(i64 x, bool live) {
-    if (!live) x = 0;
-    if (w_ballot((u64)x >> 32 != 0) == 0) return (i64)((u32)x / (u32)D);
+// the other lanes do not force the long path.  CONV = all 64 lanes make the call together;
+// the wavefront-wide decision is only taken then.  In the guarded code of a ragged tile, where
+// lanes past the end sit out, the long form is used: with the ballot-controlled branch nested
+// in that divergent code, merges of LATER statements lost lanes (seen on the GPU; both
+// branches return the same value, so the source gave no reason for it).
+template <i64 D, bool CONV> __device__ __forceinline__ i64 w_div_const(i64 x, bool live) {
+    if (CONV) {
+        if (!live) x = 0;
+        if (w_ballot((u64)x >> 32 != 0) == 0) return (i64)((u32)x / (u32)D);
+    }
     return x / D;
 }
-template <i64 D> __device__ __forceinline__ i64 w_mod_const(i64 x, bool live) {
-    if (!live) x = 0;
-    if (w_ballot((u64)x >> 32 != 0) == 0) return (i64)((u32)x % (u32)D);
+template <i64 D, bool CONV> __device__ __forceinline__ i64 w_mod_const(i64 x, bool live) {
+    if (CONV) {
+        if (!live) x = 0;
+        if (w_ballot((u64)x >> 32 != 0) == 0) return (i64)((u32)x % (u32)D);
+    }
     return x % D;
 }
 
