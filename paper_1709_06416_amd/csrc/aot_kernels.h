@@ -79,10 +79,21 @@ struct GroupScatter {
     const long long* offsets;
     unsigned long long* cursor;
     void* values_out;
+    // two-pass form (many groups): the pairs are first partitioned by ranges of 2^log_bucket groups
+    const unsigned long long* ngroups;     // device
+    int log_bucket;
+    int nbuckets;                          // <= 256
+    unsigned long long* bcursor;           // one per bucket, zero on entry
+    unsigned int* tmp_group;               // group of each partitioned pair
+    unsigned long long* tmp_value;         // its value (bits)
 };
 hipError_t launch_group_offsets(const void* counts, const void* ngroups, int64_t capacity, void* offsets, void* cursor,
                                 hipStream_t stream);
 hipError_t launch_group_scatter(const GroupScatter& g, int blocks, hipStream_t stream);
+// The same in two kernels for dictionaries of many groups: partition the pairs by group range,
+// then place every range's pairs (both read g.ngroups and the offsets on the device).
+hipError_t launch_group_partition(const GroupScatter& g, int blocks, hipStream_t stream);
+hipError_t launch_group_place(const GroupScatter& g, int blocks, hipStream_t stream);
 // Aggregation of the key-partitioned spill queues of a large dictmerger (spill_kernels.hip).
 // The loop kernel's work-group g appends to segment [g][partition] of `log` (cap entries of
 // 1 + nvals 8-byte words each) and stores the segment lengths in qcnt[g * kSpillParts + partition].

@@ -391,6 +391,259 @@ hipError_t launch_group_scatter(const GroupScatter& g, int blocks, hipStream_t s
     return hipGetLastError();
 }
 
+// Many groups: the kernel above pays one device atomic per (tile, group), and with a heavy-tailed
+// key set nearly every pair of a rare group is alone in its tile - C5's zip codes: 5.5e7 atomics
+// for 9e7 pairs, which is what its 2.3 ms were.  Two kernels instead:
+//  * group_partition_kernel partitions the pairs by RANGES of 2^log_bucket consecutive groups (at
+//    most 256 ranges; a range's pairs go to the same index range of the scratch arrays that its
+//    values will occupy in the result, so the group offsets double as range boundaries): one
+//    device atomic per (tile, range);
+//  * group_place_kernel takes a range 8192 pairs at a time and moves every value into its
+//    group's vector, counting per group in a directly indexed LDS array: one device atomic per
+//    (chunk, group), with a few hundred groups per chunk instead of 1e5.
+// The first sorts its 4096 pairs in LDS before it writes, so that consecutive threads store to
+// consecutive addresses (runs of one range): 1.25 -> 1.1 ms; the same in the second kernel, whose
+// runs are shorter, cost more than it saved (0.6 -> 0.8 ms).  Counting a work-group's whole share
+// first, to reserve once per destination, was slower too: the second look-up of every key cost
+// more than the atomics it saved (1.8 against 1.1 ms).
+#define PART_CACHE 2048
+
+// Groups of four pairs per thread: (key bits, live) -> group number or -1.  Which group a key
+// belongs to is a probe of the dictionary's table plus a read of the slot's group number: two
+// random 8- and 4-byte reads that each move a whole cache line to the CU.  The work-group
+// remembers the groups of the keys it has looked up in a directly mapped LDS cache (no eviction:
+// with a heavy-tailed key set the frequent keys get there first and then answer most lookups).
+// An entry is claimed by writing its key; its group number follows, and until then reads of the
+// entry count as misses.
+__device__ __forceinline__ void groups_of_keys(const GroupScatter& a, u64* s_ck, u32* s_cg, const u64 (&kb)[4], const bool (&live)[4],
+                                               int (&gid)[4]) {
+    u32 ce[4];
+    u64 first[4], ck[4];
+    i64 slot[4];
+    bool miss[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        ce[j] = table_hash_slot(kb[j], PART_CACHE);
+        ck[j] = __hip_atomic_load(&s_ck[ce[j]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        gid[j] = -1;
+        miss[j] = live[j];
+        if (live[j] && ck[j] == kb[j] && kb[j] != kEmptyKey) {
+            const u32 g = __hip_atomic_load(&s_cg[ce[j]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (g != ~0u) {
+                gid[j] = (int)g;
+                miss[j] = false;
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        slot[j] = (i64)table_hash_slot(kb[j], (u32)a.slots);
+        first[j] = miss[j] ? a.table_keys[slot[j]] : kEmptyKey;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (!miss[j]) { slot[j] = -1; continue; }
+        if (kb[j] == kEmptyKey) { slot[j] = a.hdr[1] ? a.slots : -1; continue; }
+        if (first[j] == kb[j]) continue;
+        i64 s = slot[j], found = -1;
+        u64 cur = first[j];
+        for (i64 probe = 1; probe < a.slots && cur != kEmptyKey; ++probe) {
+            s = (s + 1) & (a.slots - 1);
+            cur = a.table_keys[s];
+            if (cur == kb[j]) { found = s; break; }
+        }
+        slot[j] = found;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (miss[j]) gid[j] = slot[j] >= 0 ? a.slot_pos[slot[j]] : -1;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (!miss[j] || gid[j] < 0 || kb[j] == kEmptyKey || ck[j] != kEmptyKey) continue;
+        u64 expect = kEmptyKey;
+        if (__hip_atomic_compare_exchange_strong(&s_ck[ce[j]], &expect, kb[j], __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_WORKGROUP))
+            __hip_atomic_store(&s_cg[ce[j]], (u32)gid[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (gid[j] >= 0 && (gid[j] >> a.log_bucket) >= a.nbuckets) gid[j] = -1;     // (capacity error: not extracted)
+}
+
+__global__ void __launch_bounds__(1024) group_partition_kernel(const GroupScatter a) {
+    __shared__ u32 s_cnt[256];        // pairs of the tile per range
+    __shared__ i64 s_cur[256];        // where the tile's pairs of a range go
+    __shared__ u64 s_ck[PART_CACHE];
+    __shared__ u32 s_cg[PART_CACHE];
+    __shared__ u32 s_off[257];
+    __shared__ u32 s_sg[GROUP_TILE];
+    __shared__ u64 s_sv[GROUP_TILE];
+    const int tid = threadIdx.x;
+    const i64 npairs = (i64)*a.npairs;
+    const i64 ntiles = (npairs + GROUP_TILE - 1) / GROUP_TILE;
+    if (tid < 256) s_cnt[tid] = 0;
+    for (int q = tid; q < PART_CACHE; q += 1024) {
+        s_ck[q] = kEmptyKey;
+        s_cg[q] = ~0u;
+    }
+    __syncthreads();
+    for (i64 t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        u32 rank[4];
+        u64 val[4], kb[4];
+        int gid[4];
+        bool live[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const i64 i = t * GROUP_TILE + j * 1024 + tid;
+            live[j] = i < npairs;
+            kb[j] = 0;
+            val[j] = 0;
+            if (live[j]) {
+                for (int k = 0; k < a.nkeys; ++k) kb[j] |= load_bits(a.key[k], i, a.key_size[k]) << a.key_shift[k];
+                val[j] = load_bits(a.value, i, a.value_size);
+            }
+        }
+        groups_of_keys(a, s_ck, s_cg, kb, live, gid);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            rank[j] = 0;
+            if (gid[j] >= 0)
+                rank[j] = __hip_atomic_fetch_add(&s_cnt[gid[j] >> a.log_bucket], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        __syncthreads();
+        if (tid < 64) {
+            // exclusive prefix of the 256 counts: four per lane, then across the wavefront
+            u32 c[4], mine = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { c[k] = s_cnt[tid * 4 + k]; mine += c[k]; }
+            u32 incl = mine;
+            for (int o = 1; o < 64; o <<= 1) {
+                const u32 up = __shfl_up(incl, o, 64);
+                if (tid >= o) incl += up;
+            }
+            u32 run = incl - mine;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { s_off[tid * 4 + k] = run; run += c[k]; }
+            if (tid == 63) s_off[256] = run;
+        } else if (tid - 64 < a.nbuckets && s_cnt[tid - 64] != 0) {
+            // one device atomic per (tile, range); a pair of the range exists, so its first group does
+            const int b = tid - 64;
+            s_cur[b] = a.offsets[(i64)b << a.log_bucket] +
+                       (i64)__hip_atomic_fetch_add(&a.bcursor[b], (u64)s_cnt[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (gid[j] < 0) continue;
+            const u32 p = s_off[gid[j] >> a.log_bucket] + rank[j];
+            s_sg[p] = (u32)gid[j];
+            s_sv[p] = val[j];
+        }
+        __syncthreads();
+        const u32 placed = s_off[256];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const u32 p = j * 1024 + tid;
+            if (p >= placed) continue;
+            const u32 g = s_sg[p];
+            const int b = (int)(g >> a.log_bucket);
+            const i64 dst = s_cur[b] + (i64)(p - s_off[b]);
+            if (dst < 0 || dst >= npairs) continue;     // only after a capacity error (sizes and pairs then disagree)
+            a.tmp_group[dst] = g;
+            a.tmp_value[dst] = s_sv[p];
+        }
+        __syncthreads();
+        if (tid < 256) s_cnt[tid] = 0;
+        __syncthreads();
+    }
+}
+
+#define PLACE_CHUNK 8192
+#define PLACE_MAX_BUCKET 4096
+__global__ void __launch_bounds__(1024) group_place_kernel(const GroupScatter a) {
+    __shared__ i64 s_first[257];                  // chunks before each range
+    __shared__ u32 s_cnt[PLACE_MAX_BUCKET];       // pairs of the chunk per group of the range
+    __shared__ i64 s_base[PLACE_MAX_BUCKET];      // where they go
+    const int tid = threadIdx.x;
+    const i64 npairs = (i64)*a.npairs;
+    i64 G = (i64)*a.ngroups;
+    if (G > a.capacity) G = a.capacity;
+    const i64 B = (i64)1 << a.log_bucket;
+    if (tid == 0) {
+        i64 run = 0;
+        for (int b = 0; b < 256; ++b) {
+            s_first[b] = run;
+            if (b < a.nbuckets) {
+                const i64 lo = (i64)b * B < G ? (i64)b * B : G, hi = (i64)(b + 1) * B < G ? (i64)(b + 1) * B : G;
+                run += (a.offsets[hi] - a.offsets[lo] + PLACE_CHUNK - 1) / PLACE_CHUNK;
+            }
+        }
+        s_first[256] = run;
+    }
+    for (int q = tid; q < PLACE_MAX_BUCKET; q += 1024) s_cnt[q] = 0;
+    __syncthreads();
+    const i64 total = s_first[256];
+    for (i64 w = blockIdx.x; w < total; w += gridDim.x) {
+        int b = 0;                                 // last range with s_first[b] <= w
+        for (int step = 128; step > 0; step >>= 1)
+            if (b + step < 256 && s_first[b + step] <= w) b += step;
+        const i64 lo_g = (i64)b * B < G ? (i64)b * B : G, hi_g = (i64)(b + 1) * B < G ? (i64)(b + 1) * B : G;
+        const i64 start = a.offsets[lo_g] + (w - s_first[b]) * PLACE_CHUNK;
+        const i64 stop = a.offsets[hi_g];
+        u32 rank[8], local[8];
+        u64 val[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const i64 i = start + j * 1024 + tid;
+            local[j] = ~0u;
+            val[j] = 0;
+            if (i < stop) {
+                local[j] = a.tmp_group[i] - (u32)lo_g;
+                val[j] = a.tmp_value[i];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            rank[j] = 0;
+            if (local[j] >= (u32)(hi_g - lo_g)) { local[j] = ~0u; continue; }   // (scratch left unwritten after a capacity error)
+            rank[j] = __hip_atomic_fetch_add(&s_cnt[local[j]], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        __syncthreads();
+        for (int q = tid; q < (int)B; q += 1024) {
+            const u32 c = s_cnt[q];
+            if (c != 0)
+                s_base[q] = a.offsets[lo_g + q] + (i64)__hip_atomic_fetch_add(&a.cursor[lo_g + q], (u64)c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (local[j] == ~0u) continue;
+            // the places of one (chunk, group) are neighbours: L2 merges these stores into lines
+            const i64 dst = s_base[local[j]] + rank[j];
+            if (dst < 0 || dst >= npairs) continue;
+            switch (a.value_size) {
+                case 1: ((unsigned char*)a.values_out)[dst] = (unsigned char)val[j]; break;
+                case 4: ((u32*)a.values_out)[dst] = (u32)val[j]; break;
+                default: ((u64*)a.values_out)[dst] = val[j]; break;
+            }
+        }
+        __syncthreads();
+        for (int q = tid; q < (int)B; q += 1024) s_cnt[q] = 0;
+        __syncthreads();
+    }
+}
+
+hipError_t launch_group_partition(const GroupScatter& g, int blocks, hipStream_t stream) {
+    if (g.nbuckets < 1 || g.nbuckets > 256 || g.log_bucket < 0 || (1ll << g.log_bucket) > PLACE_MAX_BUCKET) return hipErrorInvalidValue;
+    group_partition_kernel<<<dim3((unsigned)blocks), dim3(1024), 0, stream>>>(g);
+    return hipGetLastError();
+}
+hipError_t launch_group_place(const GroupScatter& g, int blocks, hipStream_t stream) {
+    if (g.nbuckets < 1 || g.nbuckets > 256 || g.log_bucket < 0 || (1ll << g.log_bucket) > PLACE_MAX_BUCKET) return hipErrorInvalidValue;
+    group_place_kernel<<<dim3((unsigned)blocks), dim3(1024), 0, stream>>>(g);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- nested loops
 template <class T>
 __global__ void __launch_bounds__(256) segments_check_kernel(const T* start, const T* end, i64 n_outer, i64 n_inner, int* err) {

@@ -302,7 +302,8 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     Layout lay;
     const size_t off_ctl = lay.take(kCtlBytes);
     struct Off { size_t part = 0, res = 0, out = 0, desc = 0, keys = 0, vals[8] = {0}, okeys = 0, ovals = 0, log = 0, qcnt = 0,
-                        slot_pos = 0, goffsets = 0, gcursor = 0, gvalues = 0; int64_t slots = 0, qcap = 0; };
+                        slot_pos = 0, goffsets = 0, gcursor = 0, gvalues = 0, gbcursor = 0, gtmp_group = 0, gtmp_value = 0;
+                        int64_t slots = 0, qcap = 0; int glog = -1; };
     auto link_of = [&](size_t b) -> const GroupLink* {
         for (const GroupLink& g : links)
             if ((size_t)g.dict == b) return &g;
@@ -342,6 +343,20 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
                     off[b].goffsets = lay.take(8 * (size_t)(s.capacity + 1));
                     off[b].gcursor = lay.take(8 * (size_t)s.capacity);
                     off[b].gvalues = lay.take((size_t)n * type_size(L.builders[g->val_vec].val_type[0]));
+                    // many groups: the pairs are partitioned by ranges of 2^glog groups first (at most
+                    // 256 ranges of at most 4096 groups), which takes 12 bytes of scratch per row -
+                    // unless the memory limit has no room for that
+                    if (s.capacity > 1024 && s.capacity <= 256 * 4096) {
+                        int lg = 9;
+                        while (((int64_t)256 << lg) < s.capacity) ++lg;
+                        const size_t need = 12 * (size_t)n + 256 * 8 + 64;
+                        if (conf.memory_limit <= 0 || (int64_t)(lay.total + need) <= conf.memory_limit) {
+                            off[b].glog = lg;
+                            off[b].gbcursor = lay.take(256 * 8);
+                            off[b].gtmp_group = lay.take(4 * (size_t)n);
+                            off[b].gtmp_value = lay.take(8 * (size_t)n);
+                        }
+                    }
                 }
             }
         }
@@ -478,6 +493,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             for (int k = 0; k < s.nvals; ++k)
                 if ((h = fill(base + off[b].vals[k], off[b].slots + 1, ident_bits(s.func, s.val_type[k]))) != hipSuccess)
                     return hip_err("fill", h);
+            if (off[b].glog >= 0 && (h = fill(base + off[b].gbcursor, 256, 0)) != hipSuccess) return hip_err("fill", h);
         }
     }
     if ((h = launch_fill_list(fills, stream)) != hipSuccess) return hip_err("fill", h);
@@ -588,7 +604,17 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         gs.values_out = base + off[b].gvalues;
         int64_t gblocks = (n + 4095) / 4096;
         if (gblocks > 2 * device_info().cus) gblocks = 2 * device_info().cus;     // two work-groups fit a CU (64 KiB of LDS each)
-        if (gblocks > 0) {
+        if (gblocks > 0 && off[b].glog >= 0) {
+            gs.ngroups = (const unsigned long long*)(base + off_ctl + ctl_count_off((int)b));
+            gs.log_bucket = off[b].glog;
+            gs.nbuckets = (int)((s.capacity + ((int64_t)1 << off[b].glog) - 1) >> off[b].glog);
+            gs.bcursor = (unsigned long long*)(base + off[b].gbcursor);
+            gs.tmp_group = (unsigned int*)(base + off[b].gtmp_group);
+            gs.tmp_value = (unsigned long long*)(base + off[b].gtmp_value);
+            if ((h = launch_group_partition(gs, (int)gblocks, stream)) != hipSuccess) return hip_err("group partition", h);
+            if ((h = launch_group_place(gs, 2 * device_info().cus, stream)) != hipSuccess) return hip_err("group place", h);
+            r->kernel_count += 2;
+        } else if (gblocks > 0) {
             if ((h = launch_group_scatter(gs, (int)gblocks, stream)) != hipSuccess) return hip_err("group scatter", h);
             r->kernel_count++;
         }
