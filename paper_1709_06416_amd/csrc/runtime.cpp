@@ -343,22 +343,28 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
                     off[b].goffsets = lay.take(8 * (size_t)(s.capacity + 1));
                     off[b].gcursor = lay.take(8 * (size_t)s.capacity);
                     off[b].gvalues = lay.take((size_t)n * type_size(L.builders[g->val_vec].val_type[0]));
-                    // many groups: the pairs are partitioned by ranges of 2^glog groups first (at most
-                    // 256 ranges of at most 4096 groups), which takes 12 bytes of scratch per row -
-                    // unless the memory limit has no room for that
-                    if (s.capacity > 1024 && s.capacity <= 256 * 4096) {
-                        int lg = 9;
-                        while (((int64_t)256 << lg) < s.capacity) ++lg;
-                        const size_t need = 12 * (size_t)n + 256 * 8 + 64;
-                        if (conf.memory_limit <= 0 || (int64_t)(lay.total + need) <= conf.memory_limit) {
-                            off[b].glog = lg;
-                            off[b].gbcursor = lay.take(256 * 8);
-                            off[b].gtmp_group = lay.take(4 * (size_t)n);
-                            off[b].gtmp_value = lay.take(8 * (size_t)n);
-                        }
-                    }
                 }
             }
+        }
+    }
+    // groupbuilders of many groups: the pairs are partitioned by ranges of 2^glog groups first (at
+    // most 256 ranges of at most 4096 groups), which takes 12 bytes of scratch per row - unless
+    // the memory limit has no room for that next to everything else the loop needs
+    {
+        size_t still_to_come = 0;
+        for (size_t b = 0; b < NB; ++b)
+            if (var.backend[b] == BK_DICT_LDS && var.spill) still_to_come += 4 * (size_t)grid * kSpillParts + 512;
+        for (size_t b = 0; b < NB; ++b) {
+            const weld_builder_spec_t& s = L.builders[b];
+            if (!link_of(b) || s.capacity <= 1024 || s.capacity > 256 * 4096) continue;
+            int lg = 9;
+            while (((int64_t)256 << lg) < s.capacity) ++lg;
+            const size_t need = 12 * (size_t)n + 256 * 8 + 1024;
+            if (conf.memory_limit > 0 && (int64_t)(lay.total + need + still_to_come) > conf.memory_limit) continue;
+            off[b].glog = lg;
+            off[b].gbcursor = lay.take(256 * 8);
+            off[b].gtmp_group = lay.take(4 * (size_t)n);
+            off[b].gtmp_value = lay.take(8 * (size_t)n);
         }
     }
     // spill queues of a large LDS dictionary come last, so that they can shrink to what

@@ -721,6 +721,41 @@ def test_groupbuilder_capacity_error_and_unfused_mode(wb):
     _check(wb, _group_on_c5(), cols, label="groups unfused", mode="unfused")
 
 
+@pytest.mark.parametrize("capacity", [1_024, 1_025, 40_000, 131_073, 1_048_576, 2_000_000])
+@pytest.mark.parametrize("vt", ["i8", "f64"])
+def test_groupbuilder_placement_paths(wb, capacity, vt):
+    """Few groups are placed by one kernel, many by partitioning into ranges of groups first (512
+    to 4096 groups a range by capacity), very many by the one kernel again; keys whose packed
+    bits are the table's marker, capacities one past a power of two, 1- and 8-byte values."""
+    rnd = np.random.RandomState(capacity % 1000 + len(vt))
+    n = 180_001
+    distinct = min(capacity, 900) if capacity < 2_000 else 30_000
+    keys = (rnd.zipf(1.2, size=n) % distinct).astype(np.int64) * 1_000_003 - 77
+    keys[::5000] = -2**63                                   # the marker key
+    vals = rnd.randint(-100, 100, size=n).astype(np.int8) if vt == "i8" else rnd.uniform(-1, 1, size=n)
+    p = Program(["i64", vt])
+    p.merge(p.groupbuilder(["i64"], vt, capacity), p.col(1), keys=[p.col(0)], pred=p.bin("ne", p.col(0), p.const("i64", 5)))
+    _check(wb, p, [_dev(keys), _dev(vals)], label="groups cap %d %s" % (capacity, vt))
+
+
+def test_groupbuilder_without_room_for_the_partition_scratch(wb):
+    """Under a memory limit that leaves no room for 12 bytes of scratch per row the one-kernel
+    placement is used; the result is the same."""
+    cols = configs.make_columns("C5", 300_007, device="cuda")
+    prog = _group_on_c5()
+    from tests import parity
+    want = parity.oracle_results(prog, cols, None)
+    free = wb.fused_for(prog, cols)
+    limited = wb.fused_for(prog, cols, memory_limit=16_500_000)      # the loop itself needs about 15 MB here
+    try:
+        parity.assert_matches(prog, free, want, label="groups, no limit")
+        parity.assert_matches(prog, limited, want, label="groups, limit")
+        assert limited.kernel_count() < free.kernel_count()             # one placement kernel instead of two
+    finally:
+        free.free()
+        limited.free()
+
+
 # ----------------------------------------------------------------------
 # dictionaries of earlier calls probed by a later loop (hash join: build, then probe)
 # ----------------------------------------------------------------------
