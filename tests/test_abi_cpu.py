@@ -106,6 +106,39 @@ def test_generated_source_has_one_statement_per_operator(wb):
     assert "0x3fa999999999999a" in src            # 0.05
 
 
+def test_planner_variants_of_a_compacting_loop_with_a_large_dictionary(wb):
+    """Host logic only: which merge-phase form the generator picks, read off the generated text."""
+    c5 = configs.program_c5()
+    src = wb.generated_source(c5)
+    # merges beyond the first probe queued per wavefront, merges as one loop over the lane's rows
+    assert "#define WELD_DRAIN()" in src and "WELD_MERGE_MEM(r)" in src and '_Pragma("unroll 1")' in src
+    # the merged value is the constant 1: queue entries hold the key only (128 per wavefront)
+    assert "dq_n + add > 128" in src
+    # division by a constant: wavefront-wide shortcut in full tiles only
+    assert "w_mod_const<100000ll, W_CONV>" in src
+    assert "weld_row<true>(r0 + u * W_UNIT + k" in src and "if (i < a.n) { weld_row<false>(i" in src
+    plain = wb.generated_source(c5, tune={"dict_defer": -1})
+    assert "WELD_DRAIN" not in plain and "WELD_MERGE(o[u][k])" in plain
+    rolled = wb.generated_source(c5, tune={"dict_defer": -1, "merge_loop": 1})
+    assert "WELD_DRAIN" not in rolled and "WELD_MERGE_MEM(r)" in rolled
+    # two merged values that are not constants: three words per entry, 42 < 64 entries fit the wavefront's
+    # share of the staging buffer, so nothing is queued
+    p = Program(["i64", "f64", "i64"])
+    pred = p.bin("gt", p.col(1), p.const("f64", 0.0))
+    p.merge(p.vecbuilder("f64"), p.col(1), pred=pred)
+    p.merge(p.dictmerger(["i64"], ["f64", "i64"], "add", 50_000), [p.col(1), p.col(2)], keys=[p.col(0)], pred=pred)
+    assert "WELD_DRAIN" not in wb.generated_source(p)
+    # divisors that are not small positive constants keep the plain operator
+    q = Program(["i64", "i64"])
+    q.merge(p_b := q.vecbuilder("i64"), q.bin("div", q.col(0), q.col(1)))
+    q.merge(q.vecbuilder("i64"), q.bin("mod", q.col(0), q.const("i64", 2**31)))
+    q.merge(q.vecbuilder("i64"), q.bin("mod", q.col(0), q.const("i64", -7)))
+    body = wb.generated_source(q)
+    body = body[body.index("void weld_row("):body.index("#define WELD_MERGE")]
+    assert "w_div_const<" not in body and "w_mod_const<" not in body
+    assert p_b == 0
+
+
 def test_kernels_compile_for_gfx950_without_a_gpu(wb, tmp_path):
     assert wb.lib.weld_set_cache_dir(str(tmp_path).encode()) == wb.OK
     try:
