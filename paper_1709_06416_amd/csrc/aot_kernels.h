@@ -111,8 +111,19 @@ struct SpillMerge {
     long long slots;
     unsigned long long* vals[8];
     int* err;
+    // slice mode (launch_dict_slice_build): `parts` partitions = slices of the global table
+    int parts;
+    unsigned long long* overflow;        // entries (1 + nvals words) that found no room in their slice
+    unsigned int* overflow_count;        // zero on entry
+    long long overflow_cap;
 };
 hipError_t launch_dict_spill_merge(const SpillMerge& a, int nvals, hipStream_t stream);
+// Dictionaries of millions of keys: partition p of the queues holds the keys whose home slot lies in
+// the p-th of `parts` equal slices of the global table (slice = as many slots as an LDS table of this
+// entry size has).  One work-group per slice loads the slice, merges the partition into it in LDS
+// and stores it back; the few entries that probe past the end of their slice are inserted into
+// the global table by a second small kernel afterwards.  a.slots == a.parts * slice slots.
+hipError_t launch_dict_slice_build(const SpillMerge& a, int nvals, hipStream_t stream);
 
 // Nested loops.  is64: the start / end vectors hold 64-bit (else 32-bit) integers.
 // segments_check raises bit 8 of *err unless start[0] == 0, start[i] <= end[i],

@@ -111,40 +111,51 @@ hipError_t launch_merger_finish(const MergerFinish& m, int count, hipStream_t st
 }
 
 // ---------------------------------------------------------------- dictionary result
+// One field of a packed struct: a single store of the field's width where the address is aligned
+// to it (always so for a struct of one field, or of 8-byte fields), byte by byte otherwise.
+__device__ __forceinline__ void store_field(unsigned char* p, u64 bits, int size) {
+    if (size == 8 && ((uintptr_t)p & 7) == 0) *(u64*)p = bits;
+    else if (size == 4 && ((uintptr_t)p & 3) == 0) *(u32*)p = (u32)bits;
+    else
+        for (int b = 0; b < size; ++b) p[b] = (unsigned char)(bits >> (8 * b));
+}
+
 // Walks the open-addressing table and writes every occupied slot as one (key struct,
 // value struct) pair in C packed layout (Sec. 4.2 of the paper).  Entry order is
 // unspecified (the paper's dict is unordered).  Entries beyond `capacity` raise the
 // capacity error instead of being written.
+template <int J>
 __global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, const u32* hdr, i64 slots,
                                                            DictValues vals, DictLayout lay, i64 capacity,
                                                            unsigned char* out_keys, unsigned char* out_vals,
                                                            u64* count, int* err, int* slot_pos) {
-    // A work-group takes 2048 slots at a time (thread t: slots base + j * 256 + t), counts its
-    // occupied ones, reserves their output positions with ONE device atomic (a same-address atomic
-    // costs about 12 ns here, so one per entry would dominate large dictionaries) and hands
-    // them out by a prefix sum inside the work-group.
+    // A work-group takes 256 * J slots at a time, a wavefront 64 * J consecutive ones (load j of lane
+    // l: slot (wave * J + j) * 64 + l).  The occupied slots are counted, their output positions
+    // reserved with ONE device atomic (a same-address atomic costs about 12 ns here, serialised: one
+    // per entry would dominate large dictionaries, and for tables of millions of slots even one per
+    // 2048 slots shows - those take 8192 a round) and handed out in slot order, so that the 64
+    // lanes of a store write neighbouring entries.
     __shared__ u32 s_wave[4];
     __shared__ u64 s_base;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const i64 total = slots + 1;                       // the extra slot holds the key equal to the free marker
-    for (i64 base = (i64)blockIdx.x * 2048; base < total; base += (i64)gridDim.x * 2048) {
-        u64 kb[8];
-        bool used[8];
-        u32 mine = 0;
+    for (i64 base = (i64)blockIdx.x * 256 * J; base < total; base += (i64)gridDim.x * 256 * J) {
+        u64 kb[J];
+        u32 used = 0;                                  // bit j: slot j of this thread is occupied
+        u32 mine = 0;                                  // occupied slots of the wavefront
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const i64 s = base + j * 256 + tid;
-            kb[j] = s < slots ? keys[s] : kEmptyKey;
-            used[j] = s < slots ? (kb[j] != kEmptyKey) : (s == slots && hdr[1] != 0);
-            mine += used[j] ? 1u : 0u;
+        for (int j = 0; j < J; ++j) {                  // all loads first: they are in flight together
+            const i64 s = base + (i64)(wave * J + j) * 64 + lane;
+            kb[j] = s < slots ? __builtin_nontemporal_load(keys + s) : kEmptyKey;
         }
-        u32 incl = mine;
 #pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const u32 o = __shfl_up(incl, off, 64);
-            if (lane >= off) incl += o;
+        for (int j = 0; j < J; ++j) {
+            const i64 s = base + (i64)(wave * J + j) * 64 + lane;
+            const bool u = s < slots ? (kb[j] != kEmptyKey) : (s == slots && hdr[1] != 0);
+            used |= (u ? 1u : 0u) << j;
+            mine += (u32)__popcll(__builtin_amdgcn_ballot_w64(u));
         }
-        if (lane == 63) s_wave[wave] = incl;
+        if (lane == 0) s_wave[wave] = mine;
         __syncthreads();
         u32 before = 0, all = 0;
         for (int w = 0; w < 4; ++w) {
@@ -153,29 +164,46 @@ __global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, cons
         }
         if (tid == 0) s_base = all ? atomicAdd(count, (u64)all) : 0;
         __syncthreads();
-        u64 pos = s_base + before + incl - mine;
+        u64 run = s_base + before;
+        // eight slots per lane at a time: their value cells are loaded side by side before any is
+        // stored (a store through a byte pointer may alias anything, so the compiler keeps every
+        // load behind the store before it: one memory round trip per slot otherwise)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if (!used[j]) continue;
-            const i64 s = base + j * 256 + tid;
-            const u64 at = pos++;
-            if (slot_pos) slot_pos[s] = (i64)at < capacity ? (int)at : -1;
-            if ((i64)at >= capacity) {
-                atomicOr(err, 1);
-                continue;
+        for (int j0 = 0; j0 < J; j0 += 8) {
+            i64 at[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int j = j0 + q;
+                const bool u = (used >> j) & 1u;
+                const u64 bal = __builtin_amdgcn_ballot_w64(u);
+                at[q] = (i64)(run + (u64)__builtin_amdgcn_mbcnt_hi((u32)(bal >> 32), __builtin_amdgcn_mbcnt_lo((u32)bal, 0)));
+                run += (u64)__popcll(bal);
+                if (!u) { at[q] = -1; continue; }
+                const i64 s = base + (i64)(wave * J + j) * 64 + lane;
+                if (slot_pos) slot_pos[s] = at[q] < capacity ? (int)at[q] : -1;
+                if (at[q] >= capacity) {
+                    atomicOr(err, 1);
+                    at[q] = -1;
+                    continue;
+                }
+                unsigned char* ko = out_keys + at[q] * lay.key_stride;
+                int off = 0;
+                for (int k = 0; k < lay.nkeys; ++k) {
+                    store_field(ko + off, kb[j] >> lay.key_shift[k], lay.key_size[k]);
+                    off += lay.key_size[k];
+                }
             }
-            unsigned char* ko = out_keys + at * lay.key_stride;
             int off = 0;
-            for (int k = 0; k < lay.nkeys; ++k) {
-                const u64 field = kb[j] >> lay.key_shift[k];
-                for (int b = 0; b < lay.key_size[k]; ++b) ko[off + b] = (unsigned char)(field >> (8 * b));
-                off += lay.key_size[k];
-            }
-            unsigned char* vo = out_vals + at * lay.val_stride;
-            off = 0;
             for (int k = 0; k < lay.nvals; ++k) {
-                const u64 bits = vals.p[k][s];
-                for (int b = 0; b < lay.val_size[k]; ++b) vo[off + b] = (unsigned char)(bits >> (8 * b));
+                u64 cell[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const i64 s = base + (i64)(wave * J + j0 + q) * 64 + lane;
+                    cell[q] = at[q] >= 0 ? vals.p[k][s] : 0;
+                }
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    if (at[q] >= 0) store_field(out_vals + at[q] * lay.val_stride + off, cell[q], lay.val_size[k]);
                 off += lay.val_size[k];
             }
         }
@@ -186,11 +214,18 @@ __global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, cons
 hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots, const DictValues& vals,
                                const DictLayout& lay, int64_t capacity, void* out_keys, void* out_vals,
                                void* count, void* err, int* slot_pos, hipStream_t stream) {
-    int64_t blocks = (slots + 1 + 2047) / 2048;
+    const bool big = slots >= (1ll << 22);
+    const int64_t round = big ? 8192 : 2048;
+    int64_t blocks = (slots + 1 + round - 1) / round;
     if (blocks > 2048) blocks = 2048;
-    dict_extract_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
-        (const u64*)keys, (const u32*)hdr, slots, vals, lay, capacity, (unsigned char*)out_keys,
-        (unsigned char*)out_vals, (u64*)count, (int*)err, slot_pos);
+    if (big)
+        dict_extract_kernel<32><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
+            (const u64*)keys, (const u32*)hdr, slots, vals, lay, capacity, (unsigned char*)out_keys,
+            (unsigned char*)out_vals, (u64*)count, (int*)err, slot_pos);
+    else
+        dict_extract_kernel<8><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
+            (const u64*)keys, (const u32*)hdr, slots, vals, lay, capacity, (unsigned char*)out_keys,
+            (unsigned char*)out_vals, (u64*)count, (int*)err, slot_pos);
     return hipGetLastError();
 }
 

@@ -369,14 +369,21 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
                     while (p2w < w && p2w < 8192) p2w *= 2;
                     var.door_words = p2w;
                 }
-                // the second kernel aggregates one partition per LDS table: pointless when a
-                // partition's share of the keys cannot fit one (every merge would end as a device
-                // atomic anyway, issued by 256 work-groups instead of the whole grid)
+                // the second kernel aggregates one partition per LDS table, which needs a partition's share
+                // of the keys to fit one; beyond that (below) the partitions become slices of the table
                 int nv = 1;
                 for (size_t b = 0; b < L.builders.size(); ++b)
                     if (var.backend[b] == BK_DICT_LDS) nv = L.builders[b].nvals;
                 const int64_t part_slots = nv <= 1 ? 8192 : nv <= 3 ? 4096 : nv <= 7 ? 2048 : 1024;
-                if (tune.dict_spill > 0 || (tune.dict_spill == 0 && max_cap <= 256 * part_slots * 3 / 4)) var.spill = true;
+                if (tune.dict_spill >= 0 && max_cap <= 256 * part_slots * 3 / 4) {
+                    var.spill = true;
+                } else if (tune.dict_spill >= 0 && dict_table_slots(max_cap) / part_slots <= 4096) {
+                    // more keys than 256 LDS tables hold, but a global table of at most 4096 LDS tables:
+                    // the queues are partitioned by slice of that table, which is then built slice by slice
+                    var.spill = true;
+                    var.spill_slices = true;
+                    var.spill_parts = (int)(dict_table_slots(max_cap) / part_slots);
+                }
             }
         }
     }
@@ -411,7 +418,7 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
         int per_slot = 0;
         for (size_t b = 0; b < L.builders.size(); ++b)
             if (var.backend[b] == BK_DICT_LDS) per_slot += 8 * (1 + L.builders[b].nvals);
-        int other = (var.ticketed ? 8 * var.block * var.v : 0) + 4 * var.door_words + (var.spill ? 1024 : 0) +
+        int other = (var.ticketed ? 8 * var.block * var.v : 0) + 4 * var.door_words + (var.spill ? 4 * var.spill_parts : 0) +
                     (body_uses(L, WELD_OP_ERF) ? 7680 : 0) + 2048;
         for (size_t b = 0; b < L.builders.size(); ++b) {
             if (var.backend[b] == BK_VECM_LDS) other += 8 * (var.ranges > 1 ? 8192 : (int)L.builders[b].length);
@@ -466,6 +473,7 @@ Generated generate(const Loop& L, const Variant& var) {
     const size_t NB = L.builders.size();
     o.f("// generated: fused for-loop kernel, %d columns, %zu builders\n", L.ncols, NB);
     o.f("#define W_BLOCK %d\n#define W_V %d\n#define W_U %d\n#define W_ALIGNED %d\n", var.block, var.v, var.u, var.aligned);
+    if (var.spill_slices) o.f("#define W_SPILL_PARTS %d\n#define W_SPILL_BY_SLOT 1\n", var.spill_parts);
     const bool uses_erf = body_uses(L, WELD_OP_ERF);
     if (uses_erf) o.f("#define W_USE_ERF 1\n");
     o.s += kPreludeSource;
@@ -558,6 +566,8 @@ Generated generate(const Loop& L, const Variant& var) {
             for (int k = 0; k < s.nvals; ++k) words.push_back("w_bits(" + vals[k] + ")");
             emit_log_stores(o, b, words, " \\");
             o.f("      } else { \\\n");
+            // (tells the kernel that builds the table slice by slice that the table is no longer empty)
+            if (var.spill_slices) o.f("      __hip_atomic_store(a.b%zu_hdr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); \\\n", b);
         }
         o.f("      const i64 g = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, kb, errp); \\\n", b, b, b);
         o.f("      if (g >= 0) { \\\n");
@@ -745,7 +755,7 @@ Generated generate(const Loop& L, const Variant& var) {
             }
             if (var.spill) {
                 o.f("  __shared__ u32 d%zu_qn[W_SPILL_PARTS];\n  for (int q = threadIdx.x; q < W_SPILL_PARTS; q += W_BLOCK) d%zu_qn[q] = 0;\n", b, b);
-                lds += 4 * 256;
+                lds += 4 * var.spill_parts;
             }
             o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) {\n    d%zu_lk[q] = W_EMPTY_KEY;\n", var.lds_slots, b);
             for (int k = 0; k < s.nvals; ++k) o.f("    d%zu_lv%d[q] = %s;\n", b, k, ident_expr(s.func, s.val_type[k]).c_str());
@@ -1032,6 +1042,7 @@ Generated generate(const Loop& L, const Variant& var) {
                     emit_log_stores(o, b, words, "");
                 }
                 o.f("        continue;\n      }\n");
+                if (var.spill_slices) o.f("      __hip_atomic_store(a.b%zu_hdr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n", b);
             }
             o.f("      const i64 g = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, kb, errp);\n      if (g >= 0) {\n", b, b, b);
             for (int k = 0; k < s.nvals; ++k) o.f("        w_atomic<%d>(a.b%zu_v%d + g, d%zu_lv%d[q], 1);\n", s.func, b, k, b, k);

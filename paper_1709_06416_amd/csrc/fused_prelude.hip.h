@@ -437,14 +437,27 @@ __device__ __forceinline__ int w_lds_slot_filtered(u64* keys, int slots, u64 kbi
 // the word offset of the entry in the log (key word first), or -1 if the segment is full:
 // the caller then falls back to the global table.  A second kernel aggregates partition by
 // partition in LDS.
+// With W_SPILL_BY_SLOT the partition is instead the slice of the global table that the key's
+// home slot lies in (W_SPILL_PARTS slices, up to 4096): dictionaries of millions of keys, whose
+// table a second kernel then builds slice by slice in LDS.
+#ifndef W_SPILL_PARTS
 #define W_SPILL_PARTS 256
+#endif
 __device__ __forceinline__ i64 w_spill_index(u32* qn, i64 cap, int words, u64 kbits) {
+#ifdef W_SPILL_BY_SLOT
+    const u32 part = w_hash_slot(kbits, W_SPILL_PARTS);
+#else
     const u32 part = w_hash2(kbits) >> 24;
+#endif
     const u32 pos = __hip_atomic_fetch_add(qn + part, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     if (pos >= (u32)cap) return -1;
+#ifdef W_SPILL_BY_SLOT
+    const u64 local = (u64)part * (u64)(u32)cap + pos;
+#else
     // cap < 2^23 (the host sees to it): the entry's index inside the work-group's block of
     // segments fits 32 bits and takes a 24-bit multiplication; the block's base is scalar
-    const u32 local = __umul24(part, (u32)cap) + pos;
+    const u64 local = __umul24(part, (u32)cap) + pos;
+#endif
     return (i64)(((u64)blockIdx.x * W_SPILL_PARTS * (u64)cap + local) * (u64)words);
 }
 // Stores to device memory that say so (a pointer that went through a select or a helper is

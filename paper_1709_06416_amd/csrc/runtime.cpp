@@ -270,6 +270,9 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
     return run_fused_plain(X, links, L.builders.size(), cols, n, conf, r, prior_ctl, tables);
 }
 
+// entries the slice-building kernel may hand on to the global insert (those that probe past the end of their slice)
+static const size_t kOverflowEntries = 1 << 16;
+
 static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links, size_t user_builders, const ColRef* cols,
                              int64_t n, const weld_conf_t& conf, weld_result* r, const void* prior_ctl, const DictTable* tables) {
     hipStream_t stream = (hipStream_t)conf.stream;
@@ -302,7 +305,8 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     Layout lay;
     const size_t off_ctl = lay.take(kCtlBytes);
     struct Off { size_t part = 0, res = 0, out = 0, desc = 0, keys = 0, vals[8] = {0}, okeys = 0, ovals = 0, log = 0, qcnt = 0,
-                        slot_pos = 0, goffsets = 0, gcursor = 0, gvalues = 0, gbcursor = 0, gtmp_group = 0, gtmp_value = 0;
+                        slot_pos = 0, goffsets = 0, gcursor = 0, gvalues = 0, gbcursor = 0, gtmp_group = 0, gtmp_value = 0,
+                        ovf = 0, ovf_count = 0;
                         int64_t slots = 0, qcap = 0; int glog = -1; };
     auto link_of = [&](size_t b) -> const GroupLink* {
         for (const GroupLink& g : links)
@@ -328,8 +332,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
                 off[b].out = lay.take(8 * (size_t)s.length);
                 break;
             default: {
-                int64_t slots = 64;
-                while (slots < 2 * s.capacity) slots *= 2;
+                const int64_t slots = dict_table_slots(s.capacity);
                 off[b].slots = slots;
                 off[b].keys = lay.take(8 * (size_t)(slots + 1));
                 for (int k = 0; k < s.nvals; ++k) off[b].vals[k] = lay.take(8 * (size_t)(slots + 1));
@@ -353,7 +356,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     {
         size_t still_to_come = 0;
         for (size_t b = 0; b < NB; ++b)
-            if (var.backend[b] == BK_DICT_LDS && var.spill) still_to_come += 4 * (size_t)grid * kSpillParts + 512;
+            if (var.backend[b] == BK_DICT_LDS && var.spill) still_to_come += 4 * (size_t)grid * var.spill_parts + 512;
         for (size_t b = 0; b < NB; ++b) {
             const weld_builder_spec_t& s = L.builders[b];
             if (!link_of(b) || s.capacity <= 1024 || s.capacity > 256 * 4096) continue;
@@ -373,18 +376,22 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         if (var.backend[b] != BK_DICT_LDS || !var.spill) continue;
         const weld_builder_spec_t& s = L.builders[b];
         const size_t entry = 8 * (size_t)(1 + s.nvals);
-        off[b].qcnt = lay.take(4 * (size_t)grid * kSpillParts);
+        off[b].qcnt = lay.take(4 * (size_t)grid * var.spill_parts);
+        if (var.spill_slices) {
+            off[b].ovf_count = lay.take(8);
+            off[b].ovf = lay.take(kOverflowEntries * entry);
+        }
         int64_t cap = conf.tune.dict_spill;
         if (cap <= 0) {
             // every row of a work-group may miss: its share of the rows (tickets hand tiles out
             // unevenly: a quarter more), spread over the partitions by a hash (six standard
             // deviations more), plus what the table itself holds when it is flushed
             const double rows = (double)((ntiles + grid - 1) / grid) * (double)tile * (var.ticketed ? 1.25 : 1.0);
-            const double mean = (rows + var.lds_slots) / kSpillParts;
+            const double mean = (rows + var.lds_slots) / var.spill_parts;
             cap = (int64_t)(mean + 6.0 * std::sqrt(mean) + 16.0);
         }
         if (cap > (1 << 23) - 1) cap = (1 << 23) - 1;   // the kernel indexes a work-group's segments with 32 bits
-        const size_t seg = (size_t)grid * kSpillParts * entry;
+        const size_t seg = (size_t)grid * var.spill_parts * entry;
         if (conf.memory_limit > 0) {
             const int64_t room = conf.memory_limit - (int64_t)lay.total;
             const int64_t fit = room > 0 ? (room - 256) / (int64_t)seg : 0;
@@ -500,6 +507,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
                 if ((h = fill(base + off[b].vals[k], off[b].slots + 1, ident_bits(s.func, s.val_type[k]))) != hipSuccess)
                     return hip_err("fill", h);
             if (off[b].glog >= 0 && (h = fill(base + off[b].gbcursor, 256, 0)) != hipSuccess) return hip_err("fill", h);
+            if (var.spill_slices && var.backend[b] == BK_DICT_LDS && (h = fill(base + off[b].ovf_count, 1, 0)) != hipSuccess) return hip_err("fill", h);
         }
     }
     if ((h = launch_fill_list(fills, stream)) != hipSuccess) return hip_err("fill", h);
@@ -536,7 +544,17 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         sm.hdr = (unsigned int*)(base + off_ctl + ctl_hdr_off((int)b));
         sm.slots = off[b].slots;
         sm.err = (int*)(base + off_ctl + 8);
-        if ((h = launch_dict_spill_merge(sm, s.nvals, stream)) != hipSuccess) return hip_err("dict spill merge", h);
+        if (var.spill_slices) {
+            sm.parts = var.spill_parts;
+            sm.overflow = (unsigned long long*)(base + off[b].ovf);
+            sm.overflow_count = (unsigned int*)(base + off[b].ovf_count);
+            sm.overflow_cap = kOverflowEntries;
+            h = launch_dict_slice_build(sm, s.nvals, stream);
+            r->kernel_count++;
+        } else {
+            h = launch_dict_spill_merge(sm, s.nvals, stream);
+        }
+        if (h != hipSuccess) return hip_err("dict spill merge", h);
         r->kernel_count++;
     }
     if (!prior_ctl && (h = hipEventRecord(r->ev3, stream)) != hipSuccess) return hip_err("hipEventRecord", h);

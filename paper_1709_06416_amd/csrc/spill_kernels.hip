@@ -216,6 +216,171 @@ __global__ void __launch_bounds__(1024) dict_spill_merge_kernel(const SpillMerge
     }
 }
 
+// ---------------------------------------------------------------- slices of the global table
+// Dictionaries of millions of keys (the build side of a join): a partition's keys do not fit an
+// LDS table, and every merge would be two device atomics at random addresses (23.7 G/s on this
+// part: 1.3 ms for 1.5e7 keys).  Here the partitions ARE the table: partition p of the queues
+// holds the keys whose home slot lies in slice p of the global table, a slice has as many slots
+// as the LDS table of this entry size, and one work-group per slice loads the slice (it holds
+// what loop kernels inserted directly when a queue segment was full), merges its partition into
+// it with LDS atomics - linear probing as in the global table, but never past the end of the
+// slice - and stores it back with plain coalesced stores.  What would probe past the end of
+// its slice (and the one key equal to the free marker) goes to a short list that a second
+// kernel inserts into the global table the usual way, after every slice is in place.
+template <int NV, int FUNC>
+__global__ void __launch_bounds__(1024) dict_slice_build_kernel(const SpillMerge a) {
+    constexpr int S = SpillTable<NV>::kSlots;
+    constexpr int WORDS = 1 + NV;
+    __shared__ u64 s_keys[S];
+    __shared__ u64 s_vals[NV][S];
+    __shared__ u32 s_off[1025];
+    __shared__ u32 s_wave[16];
+    const int part = blockIdx.x;
+    const int tid = threadIdx.x;
+    const i64 base = (i64)part * S;
+    // hdr[0] != 0: a loop kernel inserted into the global table directly (a queue segment was
+    // full); otherwise the table is still as the fill kernel left it and need not be read
+    const bool fresh = a.hdr[0] == 0;
+    for (int q = tid; q < S; q += 1024) {
+        s_keys[q] = fresh ? W_EMPTY_KEY : a.keys[base + q];
+#pragma unroll
+        for (int k = 0; k < NV; ++k) s_vals[k][q] = fresh ? a.ident[k] : a.vals[k][base + q];
+    }
+    // exclusive prefix of the segment lengths of this partition over the groups (<= 1024)
+    u32 mine = 0;
+    if (tid < a.groups) {
+        mine = a.qcnt[(size_t)tid * a.parts + part];
+        if ((i64)mine > a.cap) mine = (u32)a.cap;
+    }
+    u32 incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const u32 o = __shfl_up(incl, off, 64);
+        if ((tid & 63) >= off) incl += o;
+    }
+    if ((tid & 63) == 63) s_wave[tid >> 6] = incl;
+    __syncthreads();
+    u32 before = 0;
+    for (int w = 0; w < (tid >> 6); ++w) before += s_wave[w];
+    s_off[tid + 1] = before + incl;
+    if (tid == 0) s_off[0] = 0;
+    __syncthreads();
+    const u32 total = s_off[a.groups];
+    // four entries per thread at a time, all loaded before the first is merged
+    for (u32 i0 = (u32)tid; i0 < total; i0 += 4096u) {
+        u64 key[4], w[4][NV];
+        bool live[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const u32 i = i0 + (u32)q * 1024u;
+            live[q] = i < total;
+            key[q] = W_EMPTY_KEY;
+#pragma unroll
+            for (int f = 0; f < NV; ++f) w[q][f] = 0;
+            if (!live[q]) continue;
+            // the segment of entry i (segments of one partition are about equally long: proportional guess, then walk)
+            int lo = (int)(((u64)i * (u64)a.groups) / total);
+            while (s_off[lo] > i) --lo;
+            while (s_off[lo + 1] <= i) ++lo;
+            const u64* e = a.log + (((size_t)lo * a.parts + part) * (size_t)a.cap + (i - s_off[lo])) * WORDS;
+            key[q] = e[0];
+#pragma unroll
+            for (int f = 0; f < NV; ++f) w[q][f] = e[1 + f];
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (!live[q]) continue;
+            int sl = -1;
+            if (key[q] != W_EMPTY_KEY) {
+                i64 s = (i64)w_hash_slot(key[q], (u32)a.slots) - base;      // the key's home slot, inside this slice
+                if (s >= 0 && s < S) {
+#pragma unroll 1
+                    for (; s < S; ++s) {
+                        const u64 cur = __hip_atomic_load(s_keys + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        if (cur == key[q]) { sl = (int)s; break; }
+                        if (cur == W_EMPTY_KEY) {
+                            u64 expect = W_EMPTY_KEY;
+                            if (__hip_atomic_compare_exchange_strong(s_keys + s, &expect, key[q], __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                                     __HIP_MEMORY_SCOPE_WORKGROUP) || expect == key[q]) {
+                                sl = (int)s;
+                                break;
+                            }
+                        }
+                    }
+                }
+            }
+            if (sl >= 0) {
+#pragma unroll
+                for (int f = 0; f < NV; ++f) cell_combine<FUNC>(&s_vals[f][sl], w[q][f], a.is_f64[f], 0);
+            } else {
+                const u32 at = __hip_atomic_fetch_add(a.overflow_count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((i64)at < a.overflow_cap) {
+                    u64* o = a.overflow + (size_t)at * WORDS;
+                    o[0] = key[q];
+#pragma unroll
+                    for (int f = 0; f < NV; ++f) o[1 + f] = w[q][f];
+                } else {
+                    atomicOr(a.err, 1);          // only a table far over its declared capacity gets here: the capacity error
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (int q = tid; q < S; q += 1024) {
+        a.keys[base + q] = s_keys[q];
+#pragma unroll
+        for (int k = 0; k < NV; ++k) a.vals[k][base + q] = s_vals[k][q];
+    }
+}
+
+template <int NV, int FUNC>
+__global__ void __launch_bounds__(256) dict_overflow_insert_kernel(const SpillMerge a) {
+    constexpr int WORDS = 1 + NV;
+    i64 n = (i64)*a.overflow_count;
+    if (n > a.overflow_cap) n = a.overflow_cap;
+    for (i64 i = (i64)blockIdx.x * 256 + threadIdx.x; i < n; i += (i64)gridDim.x * 256) {
+        const u64* e = a.overflow + (size_t)i * WORDS;
+        const i64 g = w_table_slot(a.keys, a.hdr, a.slots, e[0], a.err);
+        if (g >= 0) {
+#pragma unroll
+            for (int f = 0; f < NV; ++f) cell_combine<FUNC>(a.vals[f] + g, e[1 + f], a.is_f64[f], 1);
+        }
+    }
+}
+
+template <int NV, int FUNC>
+static hipError_t launch_slices(const SpillMerge& a, hipStream_t stream) {
+    if (a.slots != (long long)a.parts * SpillTable<NV>::kSlots || a.groups > 1024) return hipErrorInvalidValue;
+    dict_slice_build_kernel<NV, FUNC><<<dim3((unsigned)a.parts), dim3(1024), 0, stream>>>(a);
+    hipError_t h = hipGetLastError();
+    if (h != hipSuccess) return h;
+    dict_overflow_insert_kernel<NV, FUNC><<<dim3(64), dim3(256), 0, stream>>>(a);
+    return hipGetLastError();
+}
+template <int NV>
+static hipError_t launch_slices_nv(const SpillMerge& a, hipStream_t stream) {
+    switch (a.func) {
+        case W_FUNC_ADD: return launch_slices<NV, W_FUNC_ADD>(a, stream);
+        case W_FUNC_MUL: return launch_slices<NV, W_FUNC_MUL>(a, stream);
+        case W_FUNC_MIN: return launch_slices<NV, W_FUNC_MIN>(a, stream);
+        case W_FUNC_MAX: return launch_slices<NV, W_FUNC_MAX>(a, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+hipError_t launch_dict_slice_build(const SpillMerge& a, int nvals, hipStream_t stream) {
+    switch (nvals) {
+        case 1: return launch_slices_nv<1>(a, stream);
+        case 2: return launch_slices_nv<2>(a, stream);
+        case 3: return launch_slices_nv<3>(a, stream);
+        case 4: return launch_slices_nv<4>(a, stream);
+        case 5: return launch_slices_nv<5>(a, stream);
+        case 6: return launch_slices_nv<6>(a, stream);
+        case 7: return launch_slices_nv<7>(a, stream);
+        case 8: return launch_slices_nv<8>(a, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 template <int NV>
 static hipError_t launch_nv(const SpillMerge& a, hipStream_t stream) {
     const dim3 grid(kSpillParts), block(1024);

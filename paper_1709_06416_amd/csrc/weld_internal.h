@@ -141,6 +141,15 @@ enum Backend {
 
 // Compile-time shape of one fused kernel.  Two loops with equal Variant and equal
 // body text share one compiled code object.
+// slots of a dictmerger's global table: the power of two >= twice the declared capacity
+inline int64_t dict_table_slots(int64_t capacity) {
+    int64_t slots = 64;
+    while (slots < 2 * capacity) slots *= 2;
+    return slots;
+}
+// slots of the LDS table that aggregates one partition of the spill queues (128 KiB for keys and values)
+inline int spill_table_slots(int nvals) { return nvals <= 1 ? 8192 : nvals <= 3 ? 4096 : nvals <= 7 ? 2048 : 1024; }
+
 struct Variant {
     int block = 256;      // W_BLOCK
     int v = 2;            // W_V rows per lane per load
@@ -153,6 +162,9 @@ struct Variant {
     int door_words = 0;   // > 0: admission filter of that many 32-bit words in front of the LDS table
     bool spill = false;   // merges that miss the LDS dictionary are appended to key-partitioned queues
                           // which a second kernel aggregates, instead of device atomics on the global table
+    int spill_parts = 256;      // partitions of the spill queues
+    bool spill_slices = false;  // the partitions are slices of the global table (a partition = the keys whose home
+                                // slot lies in one slice) that a second kernel builds in LDS, slice by slice
     bool merge_loop = false;    // merges into builders that live in memory run in one loop over the rows a
                                 // lane holds (their code exists once per kernel instead of once per row)
     int defer_builder = -1;     // LDS dictionary whose merges beyond the first probe are queued per wavefront

@@ -312,6 +312,30 @@ def test_dictmerger_extreme_i64_keys(wb):
     _check(wb, p, [_dev(keys)], label="extreme keys global", tune={"dict_strategy": 3})
 
 
+@pytest.mark.parametrize("tune", [None, {"dict_spill": 2}, {"dict_spill": -1}, {"lds_dict_slots": 1024}])
+@pytest.mark.parametrize("func,vts", [("add", ["i64"]), ("max", ["f64", "i32"]), ("min", ["i8", "i64", "f64", "i64"])])
+def test_dictionary_of_millions_of_keys_built_slice_by_slice(wb, func, vts, tune):
+    """Capacity beyond what 256 LDS tables hold: the queues are partitioned by slice of the global
+    table and the table is built slice by slice (one, two and four value fields: 8192-, 4096- and
+    2048-slot slices); tiny queue segments send most merges down the direct path instead, which the
+    slice kernel then finds in the table; keys repeat, some probe past the end of their slice."""
+    rnd = np.random.RandomState(len(vts) * 7 + len(func))
+    n = 400_003
+    capacity = 2_000_000
+    keys = rnd.randint(0, 150_000, size=n).astype(np.int64) * 2_654_435_761 % (2**40)
+    keys[::1000] = -2**63                                   # the marker key
+    cols = [_dev(keys)]
+    p = Program(["i64"] + vts)
+    vals = []
+    for k, t in enumerate(vts):
+        c = rnd.uniform(-3, 3, size=n) if t == "f64" else rnd.randint(-100, 100, size=n).astype(
+            {"i8": np.int8, "i32": np.int32, "i64": np.int64}[t])
+        cols.append(_dev(c))
+        vals.append(p.col(1 + k))
+    p.merge(p.dictmerger(["i64"], vts, func, capacity), vals, keys=[p.col(0)], pred=p.bin("ne", p.col(0), p.const("i64", 7)))
+    _check(wb, p, cols, label="slices %s %s %s" % (func, vts, tune), tune=tune)
+
+
 def test_dictmerger_capacity_error(wb):
     keys = np.arange(5000, dtype=np.int64)
     p = Program(["i64"])
