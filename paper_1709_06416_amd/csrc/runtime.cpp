@@ -189,6 +189,7 @@ Error get_plan(const Loop& L, const weld_tuning_t& tune, bool aligned, int kind,
     p->per_cu = jit_blocks_per_cu(p->kern, p->var.block);
     if (p->per_cu <= 0 || p->per_cu > 8) p->per_cu = 8;
     std::lock_guard<std::mutex> lk(g_plan_mu);
+    if (g_plans.size() >= 4096) g_plans.clear();      // a program generator gone wild: start over (plans in use stay alive)
     g_plans[key] = p;
     *out = p;
     return Error();
