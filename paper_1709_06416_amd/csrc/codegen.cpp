@@ -237,12 +237,13 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
                 if (t.nkeys == 2)
                     key += std::string(" | ((u64)(") + utype(t.key_type[1]) + ")t" + std::to_string(q.c) + " << " +
                            std::to_string(8 * type_size(t.key_type[0])) + ")";
-                if (guarded(i)) o.f("!t%d ? (%s)0 : ", need[i], T);
+                // rows whose guarding predicate fails still issue the (cached) first load: see w_table_find
+                const std::string live = guarded(i) ? "t" + std::to_string(need[i]) : std::string("true");
                 if (q.opcode == WELD_OP_KEYEXISTS)
-                    o.f("w_table_find(a.p%d_keys, a.p%d_hdr, a.p%d_slots, %s) >= 0", q.a, q.a, q.a, key.c_str());
+                    o.f("w_table_find(a.p%d_keys, a.p%d_hdr, a.p%d_slots, %s, %s) >= 0", q.a, q.a, q.a, key.c_str(), live.c_str());
                 else
-                    o.f("w_table_value<%s>(a.p%d_v%d, w_table_find(a.p%d_keys, a.p%d_hdr, a.p%d_slots, %s))", T, q.a, q.reserved,
-                        q.a, q.a, q.a, key.c_str());
+                    o.f("w_table_value<%s>(a.p%d_v%d, w_table_find(a.p%d_keys, a.p%d_hdr, a.p%d_slots, %s, %s))", T, q.a, q.reserved,
+                        q.a, q.a, q.a, key.c_str(), live.c_str());
                 break;
             }
         }
