@@ -28,6 +28,12 @@ typedef unsigned int u32;
 
 // ---------------------------------------------------------------- column loader
 template <class T, int V> struct wvec { T e[V]; };
+template <int BYTES> struct w_carrier;
+template <> struct w_carrier<1> { typedef unsigned char t; };
+template <> struct w_carrier<2> { typedef unsigned short t; };
+template <> struct w_carrier<4> { typedef unsigned int t; };
+template <> struct w_carrier<8> { typedef unsigned long long t; };
+template <> struct w_carrier<16> { typedef unsigned int t __attribute__((ext_vector_type(4))); };
 
 // One lane reads V consecutive elements with a single wide load (16 bytes when
 // sizeof(T)*V == 16); a wavefront thereby reads one contiguous span.
@@ -35,10 +41,19 @@ template <class T, int V>
 __device__ __forceinline__ wvec<T, V> w_load(const T* __restrict__ p) {
     wvec<T, V> r;
 #if W_ALIGNED
-    typedef T vt __attribute__((ext_vector_type(V)));
-    const vt x = __builtin_nontemporal_load(reinterpret_cast<const vt*>(p));
+    if constexpr (sizeof(T) < 4 && sizeof(T) * V <= 16) {
+        // vectors of one- and two-byte elements go through an integer of their size: as element
+        // vectors they are loaded without the streaming hint, and such loads displace what
+        // earlier kernels wrote from the memory-side cache, write-backs included
+        typedef typename w_carrier<sizeof(T) * V>::t ct;
+        const ct x = __builtin_nontemporal_load(reinterpret_cast<const ct*>(p));
+        __builtin_memcpy(r.e, &x, sizeof(T) * V);
+    } else {
+        typedef T vt __attribute__((ext_vector_type(V)));
+        const vt x = __builtin_nontemporal_load(reinterpret_cast<const vt*>(p));
 #pragma unroll
-    for (int k = 0; k < V; ++k) r.e[k] = x[k];
+        for (int k = 0; k < V; ++k) r.e[k] = x[k];
+    }
 #else
 #pragma unroll
     for (int k = 0; k < V; ++k) r.e[k] = p[k];
@@ -49,11 +64,18 @@ __device__ __forceinline__ wvec<T, V> w_load(const T* __restrict__ p) {
 template <class T, int V>
 __device__ __forceinline__ void w_store(T* __restrict__ p, const wvec<T, V>& v) {
 #if W_ALIGNED
-    typedef T vt __attribute__((ext_vector_type(V)));
-    vt x;
+    if constexpr (sizeof(T) < 4 && sizeof(T) * V <= 16) {
+        typedef typename w_carrier<sizeof(T) * V>::t ct;
+        ct x;
+        __builtin_memcpy(&x, v.e, sizeof(T) * V);
+        __builtin_nontemporal_store(x, reinterpret_cast<ct*>(p));
+    } else {
+        typedef T vt __attribute__((ext_vector_type(V)));
+        vt x;
 #pragma unroll
-    for (int k = 0; k < V; ++k) x[k] = v.e[k];
-    __builtin_nontemporal_store(x, reinterpret_cast<vt*>(p));
+        for (int k = 0; k < V; ++k) x[k] = v.e[k];
+        __builtin_nontemporal_store(x, reinterpret_cast<vt*>(p));
+    }
 #else
 #pragma unroll
     for (int k = 0; k < V; ++k) p[k] = v.e[k];
