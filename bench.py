@@ -63,8 +63,10 @@ def main():
 
     loops = {c: wb.prepare(progs[c], tune=tune) for c in names}                      # marshalled once, like a host program would
 
-    def step(collect=None):
-        handles = [(c, wb.fused_for(loops[c], cols[c])) for c in names]                # enqueue everything
+    def enqueue():
+        return [(c, wb.fused_for(loops[c], cols[c])) for c in names]                  # work is only enqueued
+
+    def drain(handles, collect=None):
         for c, r in handles:
             r.check()
             if collect is not None:
@@ -74,13 +76,25 @@ def main():
                 collect[c]["launches"] = r.kernel_count()
             r.free()
 
-    for _ in range(args.warmup):
-        step()
+    # Steps are pipelined the way a host program that keeps evaluating would run them: the results of
+    # a step are checked and freed while the GPU works on the next one, so the GPU does not idle
+    # while the host wakes up from a wait and enqueues again (measured: 70 us per step).  Every
+    # result of every step is checked and freed inside the timed region.
+    def run(steps, collect=None):
+        pending = None
+        for _ in range(steps):
+            cur = enqueue()
+            if pending is not None:
+                drain(pending, collect)
+            pending = cur
+        if pending is not None:
+            drain(pending, collect)
+
+    run(args.warmup)
     stats = {c: {"call_ms": [], "kernel_ms": []} for c in names}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(stats)
+    run(args.steps, stats)
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     total_in = sum(in_bytes.values())

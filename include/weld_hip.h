@@ -18,7 +18,9 @@
  *     library until weld_result_free(); temporaries go back to its pool when
  *     the result is freed;
  *   - a call only enqueues work on the caller's HIP stream and returns; the
- *     accessors below are the evaluation point and synchronise that stream;
+ *     accessors below are the evaluation point and wait for that call's work
+ *     (for an event recorded after its last operation, not for what was
+ *     enqueued on the stream later: calls can be pipelined);
  *   - every function returns a status; nothing throws across this boundary;
  *     on error from weld_fused_for, *out is NULL.
  *   - all pointers inside the argument structs are HOST pointers to host
@@ -245,7 +247,7 @@ typedef struct {
 weld_status_t weld_fused_for_probe(const weld_cols_t* cols, int64_t n, const weld_dict_ref_t* dicts, int32_t ndicts,
                                    const weld_body_t* body, const weld_builder_t* builder, weld_result_t** out);
 
-/* Evaluation point: waits for the stream, reads back lengths and kernel-side error
+/* Evaluation point: waits for the call's work, reads back lengths and kernel-side error
  * flags.  WELD_OK, WELD_ERR_CAPACITY or WELD_ERR_DEVICE.  Idempotent. */
 weld_status_t weld_result_status(weld_result_t* r);
 

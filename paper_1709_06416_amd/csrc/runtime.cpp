@@ -658,9 +658,12 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         if ((h = launch_or_error(base + off_ctl, prior_ctl, stream)) != hipSuccess) return hip_err("error word", h);
         r->kernel_count++;
     }
-    if ((h = hipEventRecord(r->ev1, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     if ((h = hipMemcpyAsync(r->host_ctl, base + off_ctl, kCtlBytes, hipMemcpyDeviceToHost, stream)) != hipSuccess)
         return hip_err("hipMemcpyAsync", h);
+    // the call's last operation: the evaluation point waits for this event, not for the stream,
+    // so work enqueued after this call keeps the GPU busy while the host looks at the result
+    if ((h = hipEventRecord(r->ev1, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    r->recorded = true;
     return Error();
 }
 
@@ -875,11 +878,11 @@ weld_status_t weld_fused_for_probe(const weld_cols_t* cols, int64_t n, const wel
 weld_status_t weld_result_status(weld_result_t* r) {
     if (!r) return WELD_ERR_INVALID_ARG;
     if (r->synced) return r->status;
-    hipError_t h = hipStreamSynchronize((hipStream_t)r->stream);
+    hipError_t h = r->recorded ? hipEventSynchronize(r->ev1) : hipStreamSynchronize((hipStream_t)r->stream);
     r->synced = true;
     if (h != hipSuccess) {
         r->status = WELD_ERR_DEVICE;
-        r->error = std::string("hipStreamSynchronize: ") + hipGetErrorString(h);
+        r->error = std::string("waiting for the call's work: ") + hipGetErrorString(h);
         return r->status;
     }
     (void)hipEventElapsedTime(&r->ms, r->ev0, r->ev1);

@@ -44,6 +44,7 @@ struct weld_result {
     hipEvent_t ev2 = nullptr, ev3 = nullptr;   // around the main loop kernel alone
     uint32_t* host_ctl = nullptr;  // pinned copy of the control words
     bool synced = false;
+    bool recorded = false;         // ev1 stands after the call's last operation on the stream
     weld_status_t status = WELD_OK;
     std::string error;
     int kernel_count = 0;

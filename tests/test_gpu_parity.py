@@ -465,6 +465,33 @@ def test_prepared_loop_runs_repeatedly_on_different_inputs(wb):
                 res.free()
 
 
+def test_pipelined_calls_are_checked_one_by_one(wb):
+    """Several calls enqueued back to back on one stream; each result is looked at while later
+    calls may still be running (the evaluation point waits for its own call only), freed, and its
+    memory is reused by the next round.  Every result of every round matches the oracle."""
+    from tests import parity
+    names = ("C5", "C1", "C4", "C2", "C3")
+    progs = {c: configs.PROGRAMS[c]() for c in names}
+    loops = {c: wb.prepare(progs[c]) for c in names}
+    sizes = {"C5": 1_200_007, "C1": 50_001, "C4": 2_000_003, "C2": 300_001, "C3": 1_500_001}
+    cols = {c: configs.make_columns(c, sizes[c], device="cuda", seed=5) for c in names}
+    want = {c: parity.oracle_results(progs[c], cols[c], None) for c in names}
+    pending = None
+    for rnd in range(3):
+        cur = [(c, wb.fused_for(loops[c], cols[c])) for c in names]
+        for c, res in (pending or []):
+            try:
+                parity.assert_matches(progs[c], res, want[c], map_floor=1.0 if c == "C2" else 0.0, label="%s pipelined" % c)
+            finally:
+                res.free()
+        pending = cur
+    for c, res in reversed(pending):      # and the last round from its end
+        try:
+            parity.assert_matches(progs[c], res, want[c], map_floor=1.0 if c == "C2" else 0.0, label="%s pipelined, last round" % c)
+        finally:
+            res.free()
+
+
 def test_single_library_instance_loaded():
     # the library must bind to the HIP runtime torch already loaded, not a second copy
     libs = set()
