@@ -91,7 +91,9 @@ std::string const_expr(const weld_op_t& o) {
 // wrapping integer arithmetic through the unsigned type
 std::string wrap_bin(int t, const char* op, int a, int b) {
     char buf[160];
-    if (t == WELD_I8)
+    if (t == WELD_I8 && op[0] == '*')
+        snprintf(buf, sizeof buf, "w_mul_i8(t%d, t%d)", a, b);
+    else if (t == WELD_I8)
         snprintf(buf, sizeof buf, "(signed char)(unsigned char)((u32)(unsigned char)t%d %s (u32)(unsigned char)t%d)", a, op, b);
     else
         snprintf(buf, sizeof buf, "(%s)((%s)t%d %s (%s)t%d)", ctype(t), utype(t), a, op, utype(t), b);

@@ -82,6 +82,18 @@ __device__ __forceinline__ void w_store(T* __restrict__ p, const wvec<T, V>& v) 
 #endif
 }
 
+// ---------------------------------------------------------------- 8-bit products
+// The product of two i8 values wraps to 8 bits; it is formed in a 32-bit register that the
+// optimiser cannot see through.  Written as plain 8-bit arithmetic, the compiler merged the
+// multiply with a following addition into a byte dot product (v_dot4_u32_u8) and got the addend
+// wrong where it was the rounding term of a signed division or remainder: (x * x) % 2 of an i8
+// column came out as 89.
+__device__ __forceinline__ signed char w_mul_i8(signed char a, signed char b) {
+    int r = (int)a * (int)b;
+    asm("" : "+v"(r));
+    return (signed char)r;
+}
+
 // ---------------------------------------------------------------- merge functions
 template <int F> __device__ __forceinline__ double w_combine(double a, double b) {
     if (F == W_FUNC_ADD) return a + b;

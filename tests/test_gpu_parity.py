@@ -448,6 +448,37 @@ def test_division_by_a_constant_takes_the_same_value_on_both_paths(wb):
             _check(wb, p, [_dev(col)], label="div/mod by %d, %s" % (d, name))
 
 
+@pytest.mark.parametrize("t", ["i8", "i32"])
+def test_narrow_integer_arithmetic_over_all_operand_pairs(wb, t):
+    """Products, sums and differences of narrow integers wrap to their width before they are
+    divided, compared or cast: every pair of i8 values (and i32 pairs around the type's limits),
+    bit-exact.  (x * x) % 2 on an i8 column once came back as 89: the compiler had merged the 8-bit
+    product and the remainder's rounding term into a byte dot product.)"""
+    if t == "i8":
+        v = np.arange(-128, 128, dtype=np.int8)
+        a, b = np.repeat(v, 256), np.tile(v, 256)
+    else:
+        rnd = np.random.RandomState(8)
+        edge = np.array([-2**31, -2**31 + 1, -65537, -65536, -46341, -3, -2, -1, 0, 1, 2, 3, 46340, 46341, 65535, 65536,
+                         2**31 - 2, 2**31 - 1], dtype=np.int64)
+        v = np.concatenate([edge, rnd.randint(-2**31, 2**31, size=238)]).astype(np.int32)
+        a, b = np.repeat(v, 256), np.tile(v, 256)
+    for ops in ((("mul", "mod", 2), ("mul", "div", 2), ("mul", "mod", 7)),            # a call has eight builders at most
+                (("mul", "div", -3), ("add", "mod", 2), ("sub", "div", 5)),
+                (("mul", "mod", -2), ("mul", "div", 16), ("add", "div", -2)),
+                (("sub", "mod", 16), ("mul", "mod", 100), ("mul", None, 0))):
+        p = Program([t, t])
+        for first, second, c in ops:
+            x = p.bin(first, p.col(0), p.col(1))
+            if second:
+                x = p.bin(second, x, p.const(t, c))
+            p.merge(p.vecbuilder(t), x)
+            p.merge(p.vecbuilder("i64"), p.un("cast", p.un("neg", x), to="i64"), pred=p.bin("lt", x, p.const(t, 1)))
+        sq = p.bin("mul", p.col(0), p.col(0))
+        p.merge(p.dictmerger([t], ["i64"], "add", 16), [p.const("i64", 1)], keys=[p.bin("mod", sq, p.const(t, 2))])
+        _check(wb, p, [_dev(a), _dev(b)], label="%s arithmetic %s" % (t, ops[0]))
+
+
 def test_prepared_loop_runs_repeatedly_on_different_inputs(wb):
     """A loop description marshalled once (prepare) and run on inputs of different sizes, with
     a tuning that differs from the default, matches the oracle every time."""
@@ -490,6 +521,27 @@ def test_pipelined_calls_are_checked_one_by_one(wb):
             parity.assert_matches(progs[c], res, want[c], map_floor=1.0 if c == "C2" else 0.0, label="%s pipelined, last round" % c)
         finally:
             res.free()
+
+
+_RANDOM_TUNES = (None, None, {"units_per_thread": 1}, {"block_threads": 256, "grid_blocks": 3}, {"lds_dict_slots": 256},
+                 {"dict_defer": -1}, {"merge_loop": 1}, {"dict_strategy": 2}, {"dict_spill": -1})
+
+
+@pytest.mark.parametrize("group", range(16))
+def test_random_programs_match_the_oracle(wb, group):
+    """Differential test: seeded random expression graphs over random column types, merged into
+    random builders under random predicates (workloads/random_programs.py), evaluated by the
+    generated kernel and by the oracle.  Integer results bit-exact, f64 to the usual bounds."""
+    from tests import parity
+    from workloads import random_programs
+    for seed in range(1000 + 10 * group, 1010 + 10 * group):
+        prog, cols, inits = random_programs.make(seed)
+        dev_inits = {b: _dev(v) for b, v in inits.items()}
+        tune = _RANDOM_TUNES[seed % len(_RANDOM_TUNES)]
+        label = "random program, seed %d (%d ops, %s, %d rows, tune %s)" % (
+            seed, len(prog.ops), "+".join(b["kind"] for b in prog.builders), len(cols[0]), tune)
+        print(label, flush=True)
+        _check(wb, prog, [_dev(c) for c in cols], label=label, inits=dev_inits or None, tune=tune)
 
 
 def test_single_library_instance_loaded():

@@ -1,0 +1,208 @@
+"""Seeded random loop bodies and inputs for differential tests (input plumbing only).
+
+`make(seed)` returns (Program, columns as numpy arrays, initial vectors of the vecmergers):
+a random expression graph over one to five zipped columns of random types, merged into one
+to three random builders under random predicates.  Nothing here evaluates a program: the
+CPU oracle and the HIP library each give it meaning on their own, and the tests compare them.
+
+The graphs stay inside what both sides define and what the comparison rules can judge:
+  * no operator whose result depends on a library's last bit (exp, log, erf): a predicate
+    that flips on such a bit changes counts; those operators have tests of their own;
+  * an upper bound on |value| is carried along for every f64 value, and operators that would
+    take it past 1e100 are not generated (no inf - inf);
+  * f64 -> integer casts are clamped into the target's range first; integer divisors are
+    constants of magnitude >= 2; f64 divisors are of the form x*x + 1;
+  * f64 values merged with `add` are squares: a sum of mixed signs can cancel to nothing,
+    and then no relative tolerance is meaningful;
+  * dictionary keys and vecmerger indices are reduced modulo small constants, so capacities
+    and lengths are known.
+"""
+import numpy as np
+
+from workloads.ir import Program
+
+INTS = ("i8", "i32", "i64")
+INT_MAX = {"i8": 127.0, "i32": 2147483647.0, "i64": 9.3e18}
+CLAMP = {"i8": 100.0, "i32": 1.0e9, "i64": 1.0e15}
+SIZES = (1, 63, 4_097, 70_001, 70_001, 300_007, 300_007)
+
+
+class _Gen:
+    def __init__(self, seed):
+        self.rnd = np.random.RandomState(seed)
+        ncols = int(self.rnd.randint(1, 6))
+        self.col_types = [str(self.rnd.choice(["i8", "i32", "i64", "f64"])) for _ in range(ncols)]
+        self.p = Program(self.col_types)
+        self.pool = {"bool": [], "i8": [], "i32": [], "i64": [], "f64": []}
+        self.mag = {}
+        col_mag = {"i8": 128.0, "i32": 2.0e6, "i64": 1.0e12, "f64": 3.0}
+        for k, t in enumerate(self.col_types):
+            self._add(self.p.col(k), col_mag[t])
+        if self.rnd.rand() < 0.4:
+            self._add(self.p.index(), 1.0e6)
+
+    def _add(self, v, mag):
+        t = self.p.type_of(v)
+        self.pool[t].append(v)
+        self.mag[v] = min(mag, INT_MAX[t]) if t in INTS else mag
+        return v
+
+    def pick(self, t):
+        vs = self.pool[t]
+        return vs[int(self.rnd.randint(len(vs)))] if vs else None
+
+    def const(self, t, value):
+        v = self.p.const(t, value)
+        self.mag[v] = abs(float(value))
+        return v
+
+    def some(self, t):
+        """A value of type t: an earlier one, else a constant."""
+        v = self.pick(t)
+        if v is not None and self.rnd.rand() < 0.85:
+            return v
+        if t == "f64":
+            return self.const(t, float(np.round(self.rnd.uniform(-4, 4), 3)))
+        if t == "bool":
+            c = self.const("i64", 0)
+            return self._add(self.p.bin("eq", c, c), 1.0)
+        return self.const(t, int(self.rnd.randint(-100, 101)))
+
+    def square(self, v):
+        return self._add(self.p.bin("mul", v, v), self.mag[v] ** 2)
+
+    def grow(self):
+        rnd, p = self.rnd, self.p
+        kind = rnd.choice(["iarith", "iarith", "idiv", "farith", "farith", "fdiv", "sqrt", "neg", "cmp", "cmp",
+                           "logic", "select", "cast", "cast"])
+        if kind == "iarith":
+            t = str(rnd.choice(INTS))
+            a, b = self.some(t), self.some(t)
+            op = str(rnd.choice(["add", "sub", "mul", "min", "max"]))
+            m = {"add": self.mag[a] + self.mag[b], "sub": self.mag[a] + self.mag[b], "mul": self.mag[a] * self.mag[b]}.get(
+                op, max(self.mag[a], self.mag[b]))
+            self._add(p.bin(op, a, b), m)
+        elif kind == "idiv":
+            t = str(rnd.choice(INTS))
+            a = self.some(t)
+            d = int(rnd.choice([2, 3, 5, 7, 10, 11, 16, 60, 100, 127])) * (-1 if rnd.rand() < 0.25 else 1)
+            op = str(rnd.choice(["div", "mod"]))
+            self._add(p.bin(op, a, self.const(t, d)), self.mag[a] if op == "div" else abs(d))
+        elif kind == "farith":
+            a, b = self.some("f64"), self.some("f64")
+            op = str(rnd.choice(["add", "sub", "mul", "min", "max"]))
+            m = self.mag[a] * self.mag[b] if op == "mul" else self.mag[a] + self.mag[b]
+            if m < 1e100:
+                self._add(p.bin(op, a, b), m)
+        elif kind == "fdiv":
+            a, b = self.some("f64"), self.some("f64")
+            if self.mag[b] ** 2 < 1e100:
+                den = self._add(p.bin("add", self.square(b), self.const("f64", 1.0)), self.mag[b] ** 2 + 1)
+                self._add(p.bin("div", a, den), self.mag[a])
+        elif kind == "sqrt":
+            a = self.some("f64")
+            if self.mag[a] ** 2 < 1e100:
+                self._add(p.un("sqrt", self.square(a)), self.mag[a])
+        elif kind == "neg":
+            t = str(rnd.choice(INTS + ("f64",)))
+            a = self.some(t)
+            self._add(p.un("neg", a), self.mag[a])
+        elif kind == "cmp":
+            t = str(rnd.choice(INTS + ("f64",)))
+            a, b = self.some(t), self.some(t)
+            self._add(p.bin(str(rnd.choice(["lt", "le", "gt", "ge", "eq", "ne"])), a, b), 1.0)
+        elif kind == "logic":
+            a = self.some("bool")
+            if rnd.rand() < 0.3:
+                self._add(p.un("not", a), 1.0)
+            else:
+                self._add(p.bin(str(rnd.choice(["and", "or"])), a, self.some("bool")), 1.0)
+        elif kind == "select":
+            t = str(rnd.choice(INTS + ("f64",)))
+            a, b = self.some(t), self.some(t)
+            self._add(p.select(self.some("bool"), a, b), max(self.mag[a], self.mag[b]))
+        else:
+            src = str(rnd.choice(["bool"] + list(INTS) + ["f64"]))
+            dst = str(rnd.choice([t for t in INTS + ("f64",) if t != src]))
+            a = self.some(src)
+            if src == "f64" and dst in INTS and self.mag[a] >= CLAMP[dst]:
+                lo, hi = self.const("f64", -CLAMP[dst]), self.const("f64", CLAMP[dst])
+                a = self._add(p.bin("min", self._add(p.bin("max", a, lo), CLAMP[dst]), hi), CLAMP[dst])
+            self._add(p.un("cast", a, to=dst), self.mag[a])
+
+    # ---- values fit for merging -------------------------------------
+    def summand(self, t, func):
+        v = self.some(t)
+        if t == "f64" and func == "add":
+            if self.mag[v] ** 2 >= 1e100:
+                v = self.const("f64", 1.5)
+            v = self.square(v)
+        return v
+
+    def reduced(self, v, modulus):
+        """v mod modulus, in (-modulus, modulus)."""
+        t = self.p.type_of(v)
+        return self._add(self.p.bin("mod", v, self.const(t, modulus)), modulus)
+
+    def pred(self):
+        return self.some("bool") if self.rnd.rand() < 0.7 else None
+
+
+def make(seed):
+    g = _Gen(seed)
+    rnd, p = g.rnd, g.p
+    for _ in range(int(rnd.randint(3, 15))):
+        g.grow()
+    inits = {}
+    for _ in range(int(rnd.randint(1, 4))):
+        kind = str(rnd.choice(["merger", "merger", "vecbuilder", "vecbuilder", "dictmerger", "dictmerger", "vecmerger"]))
+        if kind == "merger":
+            t = str(rnd.choice(INTS + ("f64",)))
+            func = str(rnd.choice(["add", "min", "max"] if t == "f64" else ["add", "mul", "min", "max"]))
+            p.merge(p.merger(t, func), g.summand(t, func), pred=g.pred())
+        elif kind == "vecbuilder":
+            t = str(rnd.choice(INTS + ("f64",)))
+            p.merge(p.vecbuilder(t), g.some(t), pred=g.pred())
+        elif kind == "dictmerger":
+            keys, capacity = [], 1
+            nkeys = int(rnd.randint(1, 3))
+            for _k in range(nkeys):
+                t = str(rnd.choice(INTS if nkeys == 1 else ("i8", "i32")))      # a key struct has 64 bits at most
+                modulus = int(rnd.choice([2, 3, 7, 50, 120])) if t == "i8" or len(keys) else int(rnd.choice([3, 40, 900, 20_000]))
+                keys.append(g.reduced(g.some(t), modulus))
+                capacity *= 2 * modulus - 1
+            func = str(rnd.choice(["add", "add", "min", "max", "mul"]))
+            vts = [str(rnd.choice(INTS if func == "mul" else INTS + ("f64",))) for _v in range(int(rnd.randint(1, 4)))]
+            vals = [g.summand(t, func) for t in vts]
+            p.merge(p.dictmerger([p.type_of(k) for k in keys], vts, func, capacity), vals, keys=keys, pred=g.pred())
+        else:
+            t = str(rnd.choice(["i64", "f64"]))
+            func = str(rnd.choice(["add", "min", "max"]))
+            length = int(rnd.choice([1, 17, 1_000, 50_000]))
+            src = g.some(str(rnd.choice(INTS)))
+            if p.type_of(src) != "i64":
+                src = g._add(p.un("cast", src, to="i64"), g.mag[src])
+            r = g.reduced(src, length) if length > 1 else g.const("i64", 0)
+            if length > 1:   # into [0, length)
+                r = g.reduced(g._add(p.bin("add", r, g.const("i64", length)), 2 * length), length)
+            b = p.vecmerger(t, func, length)
+            p.merge(b, [g.summand(t, func)], keys=[r], pred=g.pred())
+            if rnd.rand() < 0.5:
+                inits[b] = (rnd.uniform(0, 2, size=length) if t == "f64" else rnd.randint(-5, 6, size=length)).astype(
+                    np.float64 if t == "f64" else np.int64)
+    n = int(rnd.choice(SIZES))
+    cols = []
+    for t in g.col_types:
+        if t == "f64":
+            cols.append(np.round(rnd.uniform(-3, 3, size=n), 6))
+        elif t == "i8":
+            cols.append(rnd.randint(-128, 128, size=n).astype(np.int8))
+        elif t == "i32":
+            c = rnd.randint(-1_000_000, 1_000_001, size=n).astype(np.int32)
+            c[rnd.rand(n) < 0.01] = np.int32(2147483647)
+            cols.append(c)
+        else:
+            c = rnd.randint(-10 ** 12, 10 ** 12, size=n).astype(np.int64)
+            c[rnd.rand(n) < 0.01] = np.int64(-2 ** 63)
+            cols.append(c)
+    return p, cols, inits
