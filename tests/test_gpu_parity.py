@@ -541,7 +541,10 @@ def test_random_programs_match_the_oracle(wb, group):
         label = "random program, seed %d (%d ops, %s, %d rows, tune %s)" % (
             seed, len(prog.ops), "+".join(b["kind"] for b in prog.builders), len(cols[0]), tune)
         print(label, flush=True)
-        _check(wb, prog, [_dev(c) for c in cols], label=label, inits=dev_inits or None, tune=tune)
+        dev = [_dev(c) for c in cols]
+        if seed % 7 == 3:            # columns that start one element past an aligned address: the scalar-load variant
+            dev = [torch.cat([d[:1], d])[1:] for d in dev]
+        _check(wb, prog, dev, label=label, inits=dev_inits or None, tune=tune)
 
 
 def test_single_library_instance_loaded():

@@ -2,7 +2,8 @@
 
 `make(seed)` returns (Program, columns as numpy arrays, initial vectors of the vecmergers):
 a random expression graph over one to five zipped columns of random types, merged into one
-to three random builders under random predicates.  Nothing here evaluates a program: the
+to three random builders (merger, vecbuilder, dictmerger, vecmerger, groupbuilder) under random
+predicates.  Nothing here evaluates a program: the
 CPU oracle and the HIP library each give it meaning on their own, and the tests compare them.
 
 The graphs stay inside what both sides define and what the comparison rules can judge:
@@ -155,7 +156,10 @@ def make(seed):
         g.grow()
     inits = {}
     for _ in range(int(rnd.randint(1, 4))):
-        kind = str(rnd.choice(["merger", "merger", "vecbuilder", "vecbuilder", "dictmerger", "dictmerger", "vecmerger"]))
+        kind = str(rnd.choice(["merger", "merger", "vecbuilder", "vecbuilder", "dictmerger", "dictmerger", "vecmerger",
+                               "groupbuilder"]))
+        if kind == "groupbuilder" and any(b["kind"] == "groupbuilder" for b in p.builders):
+            kind = "vecbuilder"              # one a program: it stands for three builders inside the library
         if kind == "merger":
             t = str(rnd.choice(INTS + ("f64",)))
             func = str(rnd.choice(["add", "min", "max"] if t == "f64" else ["add", "mul", "min", "max"]))
@@ -175,6 +179,16 @@ def make(seed):
             vts = [str(rnd.choice(INTS if func == "mul" else INTS + ("f64",))) for _v in range(int(rnd.randint(1, 4)))]
             vals = [g.summand(t, func) for t in vts]
             p.merge(p.dictmerger([p.type_of(k) for k in keys], vts, func, capacity), vals, keys=keys, pred=g.pred())
+        elif kind == "groupbuilder":
+            keys, capacity = [], 1
+            nkeys = int(rnd.randint(1, 3))
+            for _k in range(nkeys):
+                t = str(rnd.choice(INTS if nkeys == 1 else ("i8", "i32")))
+                modulus = int(rnd.choice([2, 3, 7, 50, 120])) if t == "i8" or len(keys) else int(rnd.choice([3, 40, 900, 20_000]))
+                keys.append(g.reduced(g.some(t), modulus))
+                capacity *= 2 * modulus - 1
+            t = str(rnd.choice(INTS + ("f64",)))
+            p.merge(p.groupbuilder([p.type_of(k) for k in keys], t, capacity), [g.some(t)], keys=keys, pred=g.pred())
         else:
             t = str(rnd.choice(["i64", "f64"]))
             func = str(rnd.choice(["add", "min", "max"]))
