@@ -547,6 +547,20 @@ def test_random_programs_match_the_oracle(wb, group):
         _check(wb, prog, dev, label=label, inits=dev_inits or None, tune=tune)
 
 
+def test_random_programs_operator_at_a_time(wb):
+    """The same kind of random programs through the operator-at-a-time mode (every intermediate
+    a vector in HBM): it shares the row code generator with the fused loop but none of its
+    tiling, so the two modes check each other through the oracle."""
+    from workloads import random_programs
+    for seed in range(3000, 3012):
+        prog, cols, inits = random_programs.make(seed)
+        dev_inits = {b: _dev(v) for b, v in inits.items()}
+        label = "random program, unfused, seed %d (%d ops, %s, %d rows)" % (
+            seed, len(prog.ops), "+".join(b["kind"] for b in prog.builders), len(cols[0]))
+        print(label, flush=True)
+        _check(wb, prog, [_dev(c) for c in cols], label=label, inits=dev_inits or None, mode="unfused")
+
+
 def test_single_library_instance_loaded():
     # the library must bind to the HIP runtime torch already loaded, not a second copy
     libs = set()
