@@ -228,6 +228,22 @@ weld_status_t weld_fused_for(const weld_cols_t* cols, int64_t n, const weld_body
                              const weld_builder_t* builder, weld_result_t** out);
 
 /*
+ * Launch-shape tuning (beyond the paper: its CPU backend sizes its task grain itself, Sec. 5).
+ * Runs the loop over the given columns a few times for each of several persistent-grid sizes
+ * (the library's own choice first, then 1..16 work-groups per compute unit), times the loop
+ * kernel with HIP events, and returns builder->conf.tune with grid_blocks set to the fastest
+ * in *best (unchanged fields are kept; another grid replaces the library's choice only if it is
+ * more than 2.5 % faster: below that, runs of one grid differ as much).  best_ms / default_ms (may be NULL): loop-kernel milliseconds of the
+ * winner and of the library's choice.  The results of the runs are discarded.  Synchronous;
+ * fused mode only; arguments as for weld_fused_for.  How many work-groups a streaming loop wants
+ * in flight depends on its mix of loads and arithmetic, which the kernel's resource use does not
+ * tell; a host program that runs a loop many times asks once and passes the record on.
+ */
+weld_status_t weld_tune_launch(const weld_cols_t* cols, int64_t n, const weld_body_t* body,
+                               const weld_builder_t* builder, weld_tuning_t* best, float* best_ms,
+                               float* default_ms);
+
+/*
  * Dictionaries built by earlier calls as inputs of a loop: the probe side of a hash join
  * (Sec. 3.1: dictionaries are the data type joins are implemented with).  The body may use
  *   WELD_OP_KEYEXISTS : a = index into `dicts`, b (and c) = the key struct's fields; bool

@@ -130,6 +130,9 @@ lib.weld_result_free.argtypes = [C.c_void_p]
 lib.weld_result_free.restype = None
 lib.weld_precompile.argtypes = [C.POINTER(C.c_int32), C.c_int32, C.POINTER(Body), C.POINTER(Builder)]
 lib.weld_precompile.restype = C.c_int
+lib.weld_tune_launch.argtypes = [C.POINTER(Cols), C.c_int64, C.POINTER(Body), C.POINTER(Builder), C.POINTER(Tuning),
+                                 C.POINTER(C.c_float), C.POINTER(C.c_float)]
+lib.weld_tune_launch.restype = C.c_int
 lib.weld_set_cache_dir.argtypes = [C.c_char_p]
 lib.weld_set_cache_dir.restype = C.c_int
 lib.weld_validate.argtypes = [C.POINTER(C.c_int32), C.c_int32, C.POINTER(Body), C.POINTER(Builder),
@@ -410,20 +413,7 @@ class Result:
             pass
 
 
-def fused_for(program, columns, mode="fused", stream=None, memory_limit=0, tune=None, n=None, inits=None, dicts=None):
-    """weld_fused_for over torch CUDA tensors; returns a Result (work is only enqueued).
-    inits: {builder index: CUDA tensor} initial vectors of vecmergers.
-    dicts: [(Result, builder index), ...] dictionaries of earlier calls that the body probes
-    (weld_fused_for_probe); the Results are kept alive by the returned one."""
-    if stream is None:
-        stream = torch.cuda.current_stream().cuda_stream
-    if isinstance(program, Marshalled):
-        m, program = program, program.program
-        if inits:
-            raise WeldError(ERR_INVALID_ARG, "a prepared loop carries its initial vectors; pass them to prepare()")
-        m.builder.conf.stream = stream
-    else:
-        m = Marshalled(program, mode=mode, stream=stream, memory_limit=memory_limit, tune=tune, inits=inits)
+def _zipped_columns(program, columns):
     if len(columns) != len(program.columns):
         raise WeldError(ERR_INVALID_ARG, "column count mismatch")
     cols = (Col * max(len(columns), 1))()
@@ -439,6 +429,42 @@ def fused_for(program, columns, mode="fused", stream=None, memory_limit=0, tune=
             raise WeldError(ERR_INVALID_ARG, "columns differ in length")
         cols[k].data = t.data_ptr()
         cols[k].type = TYPE_ID[program.columns[k]]
+    return cols, rows
+
+
+def tune_launch(program, columns, tune=None, memory_limit=0, inits=None, stream=None):
+    """weld_tune_launch: times the loop on these columns with several persistent-grid sizes and
+    returns (tuning dict to pass as `tune=`, loop-kernel ms of the winner, ms of the library's own choice)."""
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    m = Marshalled(program, stream=stream, memory_limit=memory_limit, tune=tune, inits=inits)
+    cols, rows = _zipped_columns(program, columns)
+    cs = Cols(len(columns), cols)
+    best = Tuning()
+    best_ms, default_ms = C.c_float(-1.0), C.c_float(-1.0)
+    st = lib.weld_tune_launch(C.byref(cs), rows or 0, C.byref(m.body), C.byref(m.builder), C.byref(best),
+                              C.byref(best_ms), C.byref(default_ms))
+    if st != OK:
+        raise WeldError(st, lib.weld_last_error().decode())
+    out = {name: getattr(best, name) for name, _ in Tuning._fields_ if getattr(best, name) != 0}
+    return out, best_ms.value, default_ms.value
+
+
+def fused_for(program, columns, mode="fused", stream=None, memory_limit=0, tune=None, n=None, inits=None, dicts=None):
+    """weld_fused_for over torch CUDA tensors; returns a Result (work is only enqueued).
+    inits: {builder index: CUDA tensor} initial vectors of vecmergers.
+    dicts: [(Result, builder index), ...] dictionaries of earlier calls that the body probes
+    (weld_fused_for_probe); the Results are kept alive by the returned one."""
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    if isinstance(program, Marshalled):
+        m, program = program, program.program
+        if inits:
+            raise WeldError(ERR_INVALID_ARG, "a prepared loop carries its initial vectors; pass them to prepare()")
+        m.builder.conf.stream = stream
+    else:
+        m = Marshalled(program, mode=mode, stream=stream, memory_limit=memory_limit, tune=tune, inits=inits)
+    cols, rows = _zipped_columns(program, columns)
     if n is None:
         n = rows if rows is not None else 0
     cs = Cols(len(columns), cols)

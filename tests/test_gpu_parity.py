@@ -561,6 +561,28 @@ def test_random_programs_operator_at_a_time(wb):
         _check(wb, prog, [_dev(c) for c in cols], label=label, inits=dev_inits or None, mode="unfused")
 
 
+def test_launch_tuning_returns_a_record_that_gives_the_same_results(wb):
+    """weld_tune_launch times the loop on its own columns over several grid sizes; whatever it
+    returns is a tuning record like any other: the loop run with it matches the oracle, and the
+    times it reports are those of real runs."""
+    from tests import parity
+    for name, n in (("C3", 3_000_001), ("C4", 2_000_003), ("C5", 1_000_003)):
+        prog = configs.PROGRAMS[name]()
+        cols = configs.make_columns(name, n, device="cuda", seed=9)
+        tune, best_ms, default_ms = wb.tune_launch(prog, cols)
+        assert set(tune) <= {"grid_blocks"} and 0 < best_ms <= default_ms, (tune, best_ms, default_ms)
+        want = parity.oracle_results(prog, cols, None)
+        res = wb.fused_for(wb.prepare(prog, tune=tune), cols)
+        try:
+            parity.assert_matches(prog, res, want, label="%s tuned %s" % (name, tune))
+        finally:
+            res.free()
+    p = Program(["f64"])
+    p.merge(p.dictmerger(["i64"], ["i64"], "add", 4), [p.const("i64", 1)], keys=[p.un("cast", p.col(0), to="i64")])
+    with pytest.raises(wb.WeldError):                 # more keys than the declared capacity: the tuner reports the loop's error
+        wb.tune_launch(p, [_dev(np.arange(100, dtype=np.float64))])
+
+
 def test_single_library_instance_loaded():
     # the library must bind to the HIP runtime torch already loaded, not a second copy
     libs = set()
