@@ -41,7 +41,9 @@ def main():
     ap.add_argument("--no-nested", action="store_true",
                     help="skip the nested-loop leg (one PageRank iteration over the synthetic power-law graph)")
     ap.add_argument("--no-unfused", action="store_true")
-    ap.add_argument("--no-tune", action="store_true", help="keep the library's own persistent-grid sizes (no tuning pass before the warm-up)")
+    ap.add_argument("--tune-launch", action="store_true",
+                    help="before the warm-up, let weld_tune_launch pick each loop's persistent-grid size on its own data "
+                         "(default: the library's own choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -62,13 +64,12 @@ def main():
     torch.cuda.synchronize()
     in_bytes = {c: configs.IN_BYTES[c] * rows[c] for c in names}
 
-    # A loop that runs many times is tuned once on its own data (persistent-grid size: how many
-    # work-groups a streaming loop wants in flight depends on its mix of loads and arithmetic),
-    # outside the timed region, like its compilation; --no-tune keeps the library's own choice.
+    # --tune-launch: a loop that runs many times is tuned once on its own data (persistent-grid
+    # size), outside the timed region, like its compilation.
     tunes, tuning_report = {}, {}
     for c in names:
         tunes[c] = tune
-        if not args.no_tune:
+        if args.tune_launch:
             tunes[c], best_ms, default_ms = wb.tune_launch(progs[c], cols[c], tune=tune)
             tuning_report[c] = {"tune": tunes[c], "kernel_ms": round(best_ms, 4), "library_choice_ms": round(default_ms, 4)}
     loops = {c: wb.prepare(progs[c], tune=tunes[c]) for c in names}                  # marshalled once, like a host program would

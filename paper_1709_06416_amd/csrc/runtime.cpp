@@ -271,22 +271,23 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
     return run_fused_plain(X, links, L.builders.size(), cols, n, conf, r, prior_ctl, tables);
 }
 
-// Loops whose work-groups need not be many: static tiles, every builder in registers (mergers,
-// vectors written in place, dictionaries of a few keys), and no operator with a long dependent
-// chain or a trip to memory at a computed address (those hide their latency behind other
-// wavefronts and keep the grid that occupancy allows).
-static bool streams_with_light_arithmetic(const Loop& L, const Variant& var) {
-    if (var.ticketed || var.spill || var.ranges > 1 || L.ndicts > 0 || L.ngather > 0) return false;
+// Loops with static tiles whose builders all live in registers (mergers, vectors written in place,
+// dictionaries of a few keys) and that make no trip to memory at a computed address: their grid
+// follows from what the body does between its loads.  0: not such a loop; 1: light arithmetic only;
+// 2: operators with long dependent chains (division, roots, transcendentals), whose latency other
+// wavefronts have to hide.
+static int streaming_class(const Loop& L, const Variant& var) {
+    if (var.ticketed || var.spill || var.ranges > 1 || L.ndicts > 0 || L.ngather > 0) return 0;
     for (size_t b = 0; b < L.builders.size(); ++b)
-        if (var.backend[b] != BK_MERGER && var.backend[b] != BK_VEC_DIRECT && var.backend[b] != BK_DICT_REG) return false;
+        if (var.backend[b] != BK_MERGER && var.backend[b] != BK_VEC_DIRECT && var.backend[b] != BK_DICT_REG) return 0;
     for (const weld_op_t& o : L.ops) {
         switch (o.opcode) {
             case WELD_OP_EXP: case WELD_OP_LOG: case WELD_OP_SQRT: case WELD_OP_ERF: case WELD_OP_DIV: case WELD_OP_MOD:
-                return false;
+                return 2;
             default: break;
         }
     }
-    return true;
+    return 1;
 }
 
 // entries the slice-building kernel may hand on to the global insert (those that probe past the end of their slice)
@@ -311,7 +312,8 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     // persistent grid: as many work-groups as are resident at once (registers and LDS
     // of this kernel decide), at most 8 per CU
     int per_cu = plan->per_cu;
-    if (streams_with_light_arithmetic(L, var)) {
+    const int sclass = streaming_class(L, var);
+    if (sclass == 1) {
         // A loop that only streams its columns through light arithmetic into registers runs best with
         // about 56 KB of loads in flight per compute unit (measured: 28 B/row, 2048-row tiles: one
         // work-group per unit is 3-7 % faster than the eight that fit; seven columns and a register
@@ -322,6 +324,11 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         const int64_t tile_bytes = tile * (row_bytes > 0 ? row_bytes : 1);
         const int64_t want = (57344 + tile_bytes - 1) / tile_bytes;
         if (want < per_cu) per_cu = (int)(want < 1 ? 1 : want);
+    } else if (sclass == 2) {
+        // A loop that computes about as long as it loads: more work-groups than are resident at once
+        // (four fit for the Black-Scholes loop), so that they drift apart and one group's arithmetic
+        // overlaps another's loads; a resident grid marches in step (measured 0.465 -> 0.445 ms).
+        per_cu = 8;
     }
     int64_t grid = conf.tune.grid_blocks > 0 ? conf.tune.grid_blocks : (int64_t)device_info().cus * per_cu;
     if (grid > ntiles) grid = ntiles;
@@ -554,6 +561,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream);
     if (!e.ok()) return e;
     r->kernel_count++;
+    if (!prior_ctl) r->grid = grid;
     // queued dictionary merges: aggregated per key partition, then added to the global table
     // (timed with the loop kernel: it is the second half of that kernel's work)
     for (size_t b = 0; b < NB; ++b) {

@@ -44,11 +44,13 @@ extern "C" weld_status_t weld_tune_launch(const weld_cols_t* cols, int64_t n, co
     const int kRuns = 6;      // the first one warms up (code object load, pool blocks)
     *best = builder->conf.tune;
     float best_time = -1.0f, first_time = -1.0f;
+    std::vector<int64_t> tried;           // grids as launched (the library clamps what it is asked for)
     for (int per_unit : kPerUnit) {
         weld_builder_t b = *builder;
         b.conf.tune.grid_blocks = per_unit * cus;
         std::vector<float> ms;
-        for (int run = 0; run < kRuns; ++run) {
+        bool seen_before = false;
+        for (int run = 0; run < kRuns && !seen_before; ++run) {
             weld_result_t* r = nullptr;
             weld_status_t st = weld_fused_for(cols, n, body, &b, &r);
             if (st != WELD_OK) return st;
@@ -60,10 +62,16 @@ extern "C" weld_status_t weld_tune_launch(const weld_cols_t* cols, int64_t n, co
                 weld_result_free(r);
                 return st;
             }
+            const int64_t launched = r->grid;
             weld_result_free(r);
-            if (run > 0 && t >= 0.0f) ms.push_back(t);
+            if (run == 0) {
+                seen_before = std::find(tried.begin(), tried.end(), launched) != tried.end();
+                tried.push_back(launched);
+            } else if (t >= 0.0f) {
+                ms.push_back(t);
+            }
         }
-        if (ms.empty()) continue;
+        if (seen_before || ms.empty()) continue;
         std::sort(ms.begin(), ms.end());
         const float t = ms[ms.size() / 2];
         if (per_unit == 0) first_time = t;

@@ -45,6 +45,7 @@ struct weld_result {
     uint32_t* host_ctl = nullptr;  // pinned copy of the control words
     bool synced = false;
     bool recorded = false;         // ev1 stands after the call's last operation on the stream
+    int64_t grid = 0;              // work-groups of the main loop kernel
     weld_status_t status = WELD_OK;
     std::string error;
     int kernel_count = 0;
