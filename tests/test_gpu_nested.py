@@ -200,3 +200,18 @@ def test_validation_errors(wb):
     plain.merge(plain.merger("f64", "add"), plain.lookup(0, plain.col(0)))
     st, text = wb.validate(plain)                                       # lookup outside a nested loop
     assert st == wb.ERR_UNSUPPORTED, text
+
+
+@pytest.mark.parametrize("group", range(5))
+def test_random_nested_programs_match_the_oracle(wb, group):
+    """Differential test: seeded random nested loops (workloads/random_programs.py): random inner
+    bodies over random column types that read the current outer element and look values up in
+    gather vectors, folded per inner range (empty, short and long ranges mixed; i32 or i64
+    offsets), and random outer bodies over the results."""
+    from workloads import random_programs
+    for seed in range(2000 + 8 * group, 2008 + 8 * group):
+        nested, outer, inner, gather = random_programs.make_nested(seed)
+        label = "random nested program, seed %d (%d outer, %d inner rows, %s %s)" % (
+            seed, len(outer[0]), len(inner[0]), nested.inner_type, nested.inner_func)
+        print(label, flush=True)
+        _check(wb, nested, outer, inner, gather, label=label)

@@ -20,25 +20,45 @@ The graphs stay inside what both sides define and what the comparison rules can 
 """
 import numpy as np
 
-from workloads.ir import Program
+from workloads.ir import NestedProgram, Program
 
 INTS = ("i8", "i32", "i64")
 INT_MAX = {"i8": 127.0, "i32": 2147483647.0, "i64": 9.3e18}
 CLAMP = {"i8": 100.0, "i32": 1.0e9, "i64": 1.0e15}
+NP = {"i8": np.int8, "i32": np.int32, "i64": np.int64, "f64": np.float64}
 SIZES = (1, 63, 4_097, 70_001, 70_001, 300_007, 300_007)
 
 
+COL_MAG = {"i8": 128.0, "i32": 2.0e6, "i64": 1.0e12, "f64": 3.0}
+
+
+def random_column(rnd, t, n):
+    if t == "f64":
+        return np.round(rnd.uniform(-3, 3, size=n), 6)
+    if t == "i8":
+        return rnd.randint(-128, 128, size=n).astype(np.int8)
+    if t == "i32":
+        c = rnd.randint(-1_000_000, 1_000_001, size=n).astype(np.int32)
+        c[rnd.rand(n) < 0.01] = np.int32(2147483647)
+        return c
+    c = rnd.randint(-10 ** 12, 10 ** 12, size=n).astype(np.int64)
+    c[rnd.rand(n) < 0.01] = np.int64(-2 ** 63)
+    return c
+
+
 class _Gen:
-    def __init__(self, seed):
-        self.rnd = np.random.RandomState(seed)
-        ncols = int(self.rnd.randint(1, 6))
-        self.col_types = [str(self.rnd.choice(["i8", "i32", "i64", "f64"])) for _ in range(ncols)]
-        self.p = Program(self.col_types)
+    def __init__(self, rnd, program=None, skip_columns=()):
+        self.rnd = rnd
+        if program is None:
+            ncols = int(self.rnd.randint(1, 6))
+            program = Program([str(self.rnd.choice(["i8", "i32", "i64", "f64"])) for _ in range(ncols)])
+        self.col_types = list(program.columns)
+        self.p = program
         self.pool = {"bool": [], "i8": [], "i32": [], "i64": [], "f64": []}
         self.mag = {}
-        col_mag = {"i8": 128.0, "i32": 2.0e6, "i64": 1.0e12, "f64": 3.0}
         for k, t in enumerate(self.col_types):
-            self._add(self.p.col(k), col_mag[t])
+            if k not in skip_columns:
+                self._add(self.p.col(k), COL_MAG[t])
         if self.rnd.rand() < 0.4:
             self._add(self.p.index(), 1.0e6)
 
@@ -150,7 +170,7 @@ class _Gen:
 
 
 def make(seed):
-    g = _Gen(seed)
+    g = _Gen(np.random.RandomState(seed))
     rnd, p = g.rnd, g.p
     for _ in range(int(rnd.randint(3, 15))):
         g.grow()
@@ -205,18 +225,65 @@ def make(seed):
                 inits[b] = (rnd.uniform(0, 2, size=length) if t == "f64" else rnd.randint(-5, 6, size=length)).astype(
                     np.float64 if t == "f64" else np.int64)
     n = int(rnd.choice(SIZES))
-    cols = []
-    for t in g.col_types:
-        if t == "f64":
-            cols.append(np.round(rnd.uniform(-3, 3, size=n), 6))
-        elif t == "i8":
-            cols.append(rnd.randint(-128, 128, size=n).astype(np.int8))
-        elif t == "i32":
-            c = rnd.randint(-1_000_000, 1_000_001, size=n).astype(np.int32)
-            c[rnd.rand(n) < 0.01] = np.int32(2147483647)
-            cols.append(c)
-        else:
-            c = rnd.randint(-10 ** 12, 10 ** 12, size=n).astype(np.int64)
-            c[rnd.rand(n) < 0.01] = np.int64(-2 ** 63)
-            cols.append(c)
+    cols = [random_column(rnd, t, n) for t in g.col_types]
     return p, cols, inits
+
+
+def make_nested(seed):
+    """A random `for` nested in a `for`: (NestedProgram, outer columns, inner columns, gather vectors).
+    Inner ranges are consecutive (a CSR row-pointer array split into its start and end columns),
+    with empty, short and long ranges mixed; the inner body may read the current outer element and
+    look values up in the gather vectors at reduced (in-range) positions."""
+    rnd = np.random.RandomState(seed)
+    n_outer = int(rnd.choice([1, 50, 3_000, 40_000]))
+    inner_type = str(rnd.choice(["i64", "f64"]))
+    inner_func = str(rnd.choice(["add", "min", "max"] if inner_type == "f64" else ["add", "mul", "min", "max"]))
+    never_empty = inner_type == "f64" and inner_func != "add"      # an empty range gives the identity: +-inf
+    lengths = rnd.randint(0, 9, size=n_outer)
+    long_rows = rnd.rand(n_outer) < 0.01
+    lengths[long_rows] = rnd.randint(100, 5_000, size=int(long_rows.sum()))
+    if never_empty:
+        lengths = np.maximum(lengths, 1)
+    offsets_type = str(rnd.choice(["i32", "i64"]))
+    rowptr = np.concatenate([[0], np.cumsum(lengths)]).astype(NP[offsets_type])
+    n_inner = int(rowptr[-1])
+    extra_outer = [str(rnd.choice(["i8", "i32", "i64", "f64"])) for _ in range(int(rnd.randint(0, 3)))]
+    inner_cols = [str(rnd.choice(["i8", "i32", "i64", "f64"])) for _ in range(int(rnd.randint(1, 4)))]
+    gather_types = [str(rnd.choice(["i32", "i64", "f64"])) for _ in range(int(rnd.randint(0, 3)))]
+    gather_len = [int(rnd.choice([1, 7, 1_000, 5_000])) for _ in gather_types]
+    nested = NestedProgram([offsets_type, offsets_type] + extra_outer, 0, 1, inner_cols, gather_types, inner_type, inner_func)
+
+    gi = _Gen(rnd, nested.inner)
+    for k, t in enumerate(extra_outer):
+        gi._add(nested.inner.outer(2 + k), COL_MAG[t])
+    for k, t in enumerate(gather_types):
+        src = gi.some(str(rnd.choice(INTS)))
+        wide = src if nested.inner.type_of(src) == "i64" else gi._add(nested.inner.un("cast", src, to="i64"), gi.mag[src])
+        if gather_len[k] > 1:      # into [0, length): reduced, shifted up by the length, reduced again
+            pos = gi.reduced(gi._add(nested.inner.bin("add", gi.reduced(wide, gather_len[k]), gi.const("i64", gather_len[k])),
+                                     2.0 * gather_len[k]), gather_len[k])
+        else:
+            pos = gi.const("i64", 0)
+        gi._add(nested.inner.lookup(k, pos), COL_MAG[t])
+    for _ in range(int(rnd.randint(2, 9))):
+        gi.grow()
+    v = gi.summand(inner_type, inner_func)
+    nested.inner.merge(0, v, pred=None if never_empty else gi.pred())
+
+    go = _Gen(rnd, nested.outer, skip_columns=())
+    inner_mag = gi.mag[v] * 5_000 if inner_func == "add" else gi.mag[v]
+    go._add(nested.outer.inner(), min(inner_mag, 9.9e99) if inner_type == "f64" else inner_mag)
+    for _ in range(int(rnd.randint(1, 7))):
+        go.grow()
+    for _ in range(int(rnd.randint(1, 3))):
+        if rnd.rand() < 0.5:
+            t = str(rnd.choice(INTS + ("f64",)))
+            func = str(rnd.choice(["add", "min", "max"] if t == "f64" else ["add", "mul", "min", "max"]))
+            nested.outer.merge(nested.outer.merger(t, func), go.summand(t, func), pred=go.pred())
+        else:
+            t = str(rnd.choice(INTS + ("f64",)))
+            nested.outer.merge(nested.outer.vecbuilder(t), go.some(t), pred=go.pred())
+    outer = [rowptr[:-1].copy(), rowptr[1:].copy()] + [random_column(rnd, t, n_outer) for t in extra_outer]
+    inner = [random_column(rnd, t, n_inner) for t in inner_cols]
+    gather = [random_column(rnd, t, m) for t, m in zip(gather_types, gather_len)]
+    return nested, outer, inner, gather
