@@ -272,9 +272,19 @@ def make_nested(seed):
 
     go = _Gen(rnd, nested.outer, skip_columns=())
     inner_mag = gi.mag[v] * 5_000 if inner_func == "add" else gi.mag[v]
-    go._add(nested.outer.inner(), min(inner_mag, 9.9e99) if inner_type == "f64" else inner_mag)
+    inner_value = nested.outer.inner()
+    # an f64 sum depends on the order of its merges in the last bits: it is merged as it is (and
+    # compared with a tolerance), never compared, cast or combined further, where a last bit decides
+    order_dependent = inner_type == "f64" and inner_func == "add"
+    if not order_dependent:
+        go._add(inner_value, min(inner_mag, 9.9e99) if inner_type == "f64" else inner_mag)
     for _ in range(int(rnd.randint(1, 7))):
         go.grow()
+    if order_dependent:
+        if rnd.rand() < 0.5:
+            nested.outer.merge(nested.outer.vecbuilder("f64"), inner_value, pred=go.pred())
+        else:
+            nested.outer.merge(nested.outer.merger("f64", "add"), inner_value, pred=go.pred())
     for _ in range(int(rnd.randint(1, 3))):
         if rnd.rand() < 0.5:
             t = str(rnd.choice(INTS + ("f64",)))
