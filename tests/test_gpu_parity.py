@@ -942,6 +942,33 @@ def test_probe_of_a_dictionary_built_by_an_earlier_call(wb, n_build, n_probe, tw
         built.free()
 
 
+@pytest.mark.parametrize("group", range(5))
+def test_random_joins_match_the_oracle(wb, group):
+    """Differential test of dictionaries as loop inputs: a seeded random build loop (one dictmerger
+    over one or two reduced integer keys, one to three value fields) and a random probe loop that
+    computes key structs, asks whether they exist, looks value fields up and computes on with the
+    answers (workloads/random_programs.py), against the oracle's Python-dict probe."""
+    from oracle import interp
+    from tests import parity
+    from workloads import random_programs
+    for seed in range(4000 + 8 * group, 4008 + 8 * group):
+        b, build_cols, p, probe_cols, inits = random_programs.make_probe(seed)
+        label = "random join, seed %d (%d build rows, %d probe rows, keys %s)" % (
+            seed, len(build_cols[0]), len(probe_cols[0]), b.builders[0]["key_types"])
+        print(label, flush=True)
+        table = interp.run(b, build_cols)[0]
+        want = interp.run(p, probe_cols, dicts=[table], sums="exact", inits=inits)
+        dev_inits = {k: _dev(v) for k, v in inits.items()}
+        built = _run(wb, b, [_dev(c) for c in build_cols])
+        res = _run(wb, p, [_dev(c) for c in probe_cols], dicts=[(built, 0)], inits=dev_inits or None)
+        try:
+            parity.assert_matches(p, res, want, label=label)
+            parity.assert_matches(b, built, [table], label=label + ", build side")
+        finally:
+            res.free()
+            built.free()
+
+
 def test_probe_argument_errors(wb):
     rnd = np.random.RandomState(1)
     b, p, build_cols, probe_cols = _join_case(rnd, 100, 100, False)

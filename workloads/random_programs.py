@@ -169,11 +169,9 @@ class _Gen:
         return self.some("bool") if self.rnd.rand() < 0.7 else None
 
 
-def make(seed):
-    g = _Gen(np.random.RandomState(seed))
+def _add_builders(g):
+    """One to three random builders with their merges; returns the vecmergers' initial vectors."""
     rnd, p = g.rnd, g.p
-    for _ in range(int(rnd.randint(3, 15))):
-        g.grow()
     inits = {}
     for _ in range(int(rnd.randint(1, 4))):
         kind = str(rnd.choice(["merger", "merger", "vecbuilder", "vecbuilder", "dictmerger", "dictmerger", "vecmerger",
@@ -224,9 +222,66 @@ def make(seed):
             if rnd.rand() < 0.5:
                 inits[b] = (rnd.uniform(0, 2, size=length) if t == "f64" else rnd.randint(-5, 6, size=length)).astype(
                     np.float64 if t == "f64" else np.int64)
+    return inits
+
+
+def make(seed):
+    g = _Gen(np.random.RandomState(seed))
+    rnd, p = g.rnd, g.p
+    for _ in range(int(rnd.randint(3, 15))):
+        g.grow()
+    inits = _add_builders(g)
     n = int(rnd.choice(SIZES))
     cols = [random_column(rnd, t, n) for t in g.col_types]
     return p, cols, inits
+
+
+def make_probe(seed):
+    """A random build side and probe side of a hash join: (build Program, build columns, probe Program,
+    probe columns, initial vectors of the probe's vecmergers).  The build loop merges into one
+    dictmerger (builder 0); the probe loop computes key structs of the same types (reduced with a
+    modulus of its own, so some keys are absent), asks whether they exist and looks fields of their
+    values up, and goes on computing with the answers."""
+    rnd = np.random.RandomState(seed)
+    gb = _Gen(rnd)
+    for _ in range(int(rnd.randint(1, 6))):
+        gb.grow()
+    nkeys = int(rnd.randint(1, 3))
+    key_types = [str(rnd.choice(INTS if nkeys == 1 else ("i8", "i32"))) for _ in range(nkeys)]
+    build_mod = [int(rnd.choice([2, 7, 50, 120])) if t == "i8" or k else int(rnd.choice([3, 40, 900, 20_000, 300_000]))
+                 for k, t in enumerate(key_types)]
+    keys = [gb.reduced(gb.some(t), m) for t, m in zip(key_types, build_mod)]
+    capacity = 1
+    for m in build_mod:
+        capacity *= 2 * m - 1
+    # an f64 sum in the dictionary would depend on merge order in its last bits, and the probe side
+    # compares and casts what it looks up
+    func = str(rnd.choice(["add", "min", "max"]))
+    val_types = [str(rnd.choice(INTS if func == "add" else INTS + ("f64",))) for _ in range(int(rnd.randint(1, 4)))]
+    vals = [gb.summand(t, func) for t in val_types]
+    gb.p.merge(gb.p.dictmerger(key_types, val_types, func, capacity), vals, keys=keys, pred=gb.pred())
+    n_build = int(rnd.choice([1, 500, 70_001, 300_007]))
+    build_cols = [random_column(rnd, t, n_build) for t in gb.col_types]
+
+    ncols = int(rnd.randint(1, 5))
+    probe = Program([str(rnd.choice(["i8", "i32", "i64", "f64"])) for _ in range(ncols)],
+                    dicts=[{"key_types": key_types, "val_types": val_types}])
+    gp = _Gen(rnd, probe)
+    for _ in range(int(rnd.randint(0, 4))):
+        gp.grow()
+    for _ in range(int(rnd.randint(1, 3))):
+        pk = [gp.reduced(gp.some(t), min(int(m * rnd.choice([1, 1, 2])), 127 if t == "i8" else 2 ** 30))
+              for t, m in zip(key_types, build_mod)]
+        gp._add(probe.keyexists(0, pk), 1.0)
+        for f in range(len(val_types)):
+            if rnd.rand() < 0.7:
+                gp._add(probe.dictlookup(0, f, pk), INT_MAX[val_types[f]] if val_types[f] in INTS else 1.0e99)
+    for _ in range(int(rnd.randint(1, 8))):
+        gp.grow()
+    inits = _add_builders(gp)
+    n_probe = int(rnd.choice([1, 63, 4_097, 70_001, 300_007]))
+    probe_cols = [random_column(rnd, t, n_probe) for t in gp.col_types]
+    return gb.p, build_cols, probe, probe_cols, inits
 
 
 def make_nested(seed):
