@@ -5,6 +5,7 @@ oracle/interp.py and compares builder by builder under the rules of
 tests/parity.py.  Sizes span several tiles (a tile is 2048 rows by default) and
 a ragged tail.
 """
+import math
 import os
 
 import numpy as np
@@ -778,6 +779,112 @@ def test_lazy_c1_and_c3_match_the_oracle(wb):
     assert abs(float(res.merger(0)) - float(want[0])) <= 1e-9 * abs(float(want[0]))
     assert res.kernel_count() <= 3                        # one fused loop, not one kernel per operator
     res.free()
+
+
+def _trunc_div(a, b):
+    r = np.fmod(a, b)
+    return (a - r) // b
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_lazy_graphs_fuse_into_one_loop_with_numpy_results(wb, seed):
+    """Random expression graphs built through the lazy object API over shared inputs, with filters
+    (also chained) and several roots: reductions, counts and one materialised vector.  Every root
+    is mirrored in NumPy while the graph is built; the roots are evaluated together (one fused
+    loop: at most three kernels) and compared (integers and order-preserving vectors bit-exact, f64
+    sums of non-negative values at 1e-9)."""
+    from paper_1709_06416_amd import lazy
+    rnd = np.random.RandomState(900 + seed)
+    n = int(rnd.choice([1, 4_097, 123_457, 300_007]))
+    pool = {"i64": [], "f64": [], "i32": []}                     # (lazy vector, numpy mirror) of full length
+    for t in ("i64", "f64", "i32")[: int(rnd.randint(1, 4))]:
+        host = {"i64": lambda: rnd.randint(-10 ** 9, 10 ** 9, size=n).astype(np.int64),
+                "f64": lambda: np.round(rnd.uniform(-3, 3, size=n), 6),
+                "i32": lambda: rnd.randint(-30_000, 30_000, size=n).astype(np.int32)}[t]()
+        pool[t].append((lazy.Vec.from_tensor(_dev(host)), host))
+    types = [t for t in pool if pool[t]]
+    masks = []
+    np_t = {"i64": np.int64, "f64": np.float64, "i32": np.int32}
+    with np.errstate(all="ignore"):
+        for _ in range(int(rnd.randint(3, 10))):
+            t = str(rnd.choice(types))
+            (la, ha) = pool[t][int(rnd.randint(len(pool[t])))]
+            other_is_vec = rnd.rand() < 0.5
+            (lb, hb) = pool[t][int(rnd.randint(len(pool[t])))] if other_is_vec else (None, None)
+            c = float(np.round(rnd.uniform(-2, 2), 2)) if t == "f64" else int(rnd.randint(2, 50))
+            op = str(rnd.choice(["add", "sub", "mul", "cmp", "cmp", "neg", "divc", "modc"] if t != "f64" else
+                                ["add", "sub", "mul", "cmp", "cmp", "neg", "sqrt2"]))
+            rhs_l, rhs_h = (lb, hb) if other_is_vec else (c, np_t[t](c))
+            if op == "add":
+                pool[t].append((la + rhs_l, ha + rhs_h))
+            elif op == "sub":
+                pool[t].append((la - rhs_l, ha - rhs_h))
+            elif op == "mul":
+                if t == "f64" and np.max(np.abs(ha), initial=0) * np.max(np.abs(rhs_h), initial=0) > 1e100:
+                    continue
+                pool[t].append((la * rhs_l, ha * rhs_h))
+            elif op == "neg":
+                pool[t].append((-la, -ha))
+            elif op == "divc":
+                pool[t].append((la / c, _trunc_div(ha, np_t[t](c))))
+            elif op == "modc":
+                pool[t].append((la % c, np.fmod(ha, np_t[t](c))))
+            elif op == "sqrt2":
+                pool[t].append(((la * la).sqrt(), np.sqrt(ha * ha)))
+            else:
+                which = str(rnd.choice(["lt", "le", "gt", "ge"]))
+                lm = {"lt": la < rhs_l, "le": la <= rhs_l, "gt": la > rhs_l, "ge": la >= rhs_l}[which]
+                hm = {"lt": ha < rhs_h, "le": ha <= rhs_h, "gt": ha > rhs_h, "ge": ha >= rhs_h}[which]
+                masks.append((lm, hm))
+                if len(masks) >= 2 and rnd.rand() < 0.4:
+                    (l1, h1), (l2, h2) = masks[-1], masks[int(rnd.randint(len(masks) - 1))]
+                    masks.append((l1 & l2, h1 & h2) if rnd.rand() < 0.5 else (l1 | l2, h1 | h2))
+    roots, wants = [], []
+    for _ in range(int(rnd.randint(1, 5))):
+        t = str(rnd.choice(types))
+        lv, hv = pool[t][int(rnd.randint(len(pool[t])))]
+        kind = str(rnd.choice(["sum", "min", "max", "count", "vec"]))
+        if kind == "sum" and t == "f64":
+            lv, hv = lv * lv, hv * hv                          # non-negative: the tolerance is relative to the sum
+        if masks and rnd.rand() < 0.7:
+            lm, hm = masks[int(rnd.randint(len(masks)))]
+            lv, hv = lv[lm], hv[hm]
+            if masks and rnd.rand() < 0.3 and kind != "vec":      # a filter of a filtered vector
+                lm2, hm2 = masks[int(rnd.randint(len(masks)))]
+                lv, hv = lv[lm2[lm]], hv[hm2[hm]]
+        if kind == "sum":
+            roots.append(lv.sum()); wants.append(("sum", t, hv))
+        elif kind == "min":
+            roots.append(lv.min()); wants.append(("min", t, hv))
+        elif kind == "max":
+            roots.append(lv.max()); wants.append(("max", t, hv))
+        elif kind == "count":
+            roots.append(lv.count()); wants.append(("count", "i64", hv))
+        elif not any(w[0] == "vec" for w in wants):
+            roots.append(lv); wants.append(("vec", t, hv))
+    if not roots:
+        lv, hv = pool[types[0]][0]
+        roots.append(lv.count()); wants.append(("count", "i64", hv))
+    res = lazy.evaluate(*roots).check()
+    try:
+        assert res.kernel_count() <= 3, res.kernel_count()          # one fused loop: fill, loop, final combination
+        for i, (kind, t, hv) in enumerate(wants):
+            tag = "seed %d root %d (%s %s)" % (seed, i, kind, t)
+            if kind == "vec":
+                assert np.array_equal(res.vec_host(i), hv), tag
+            elif kind == "count":
+                assert int(res.merger(i)) == len(hv), tag
+            elif kind == "sum":
+                if t == "f64":
+                    want = math.fsum(hv.tolist())
+                    assert abs(float(res.merger(i)) - want) <= 1e-9 * abs(want), (tag, res.merger(i), want)
+                else:
+                    assert int(res.merger(i)) == int(np.add.reduce(hv, dtype=hv.dtype)), tag
+            elif len(hv):
+                want = hv.min() if kind == "min" else hv.max()
+                assert res.merger(i) == want, (tag, res.merger(i), want)
+    finally:
+        res.free()
 
 
 def test_lazy_groupby_and_materialised_vector(wb):
