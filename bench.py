@@ -278,12 +278,8 @@ def main():
     groups = None
     if not args.no_nested and "C5" in names:
         try:
-            from workloads.ir import Program
             gcols = configs.make_columns("C5", rows["C5"], device="cuda")
-            gp = Program(["i64"])
-            c0 = gp.col(0)
-            gp.merge(gp.groupbuilder(["i64"], "i64", 100_000), c0, keys=[gp.bin("mod", c0, gp.const("i64", 100_000))],
-                     pred=gp.bin("gt", c0, gp.const("i64", 0)))
+            gp = configs.program_group_by_zip()
             ts, npairs, ngroups = [], 0, 0
             for i in range(args.warmup + 5):
                 r = wb.fused_for(gp, gcols).check()

@@ -119,6 +119,15 @@ def program_c5(capacity=100_000):
 EXAMPLES = {}
 
 
+def program_group_by_zip(capacity=100_000):
+    """filter code>0; groupbuilder: the codes grouped by code mod 100000 (the C5 column)."""
+    p = Program(["i64"])
+    code = p.col(0)
+    p.merge(p.groupbuilder(["i64"], "i64", capacity), code, keys=[p.bin("mod", code, p.const("i64", 100_000))],
+            pred=p.bin("gt", code, p.const("i64", 0)))
+    return p
+
+
 PROGRAMS = {"C1": program_c1, "C2": program_c2, "C3": program_c3,
             "C4": program_c4, "C5": program_c5}
 
