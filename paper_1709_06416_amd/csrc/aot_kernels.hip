@@ -283,11 +283,14 @@ hipError_t launch_group_offsets(const void* counts, const void* ngroups, int64_t
     return hipGetLastError();
 }
 
+// Element i of a vector that is read once, front to back (the compacted pairs of a groupbuilder):
+// loaded with the streaming hint, so that it does not push the dictionary's table, which every pair
+// looks its key up in, out of the L2.
 __device__ __forceinline__ u64 load_bits(const void* p, i64 i, int size) {
     switch (size) {
-        case 1: return (u64)((const unsigned char*)p)[i];
-        case 4: return (u64)((const u32*)p)[i];
-        default: return ((const u64*)p)[i];
+        case 1: return (u64)__builtin_nontemporal_load((const unsigned char*)p + i);
+        case 4: return (u64)__builtin_nontemporal_load((const u32*)p + i);
+        default: return __builtin_nontemporal_load((const u64*)p + i);
     }
 }
 // same multiplicative hash as the loop kernels' tables (both probe the same table)
@@ -633,8 +636,8 @@ __global__ void __launch_bounds__(1024) group_place_kernel(const GroupScatter a)
             local[j] = ~0u;
             val[j] = 0;
             if (i < stop) {
-                local[j] = a.tmp_group[i] - (u32)lo_g;
-                val[j] = a.tmp_value[i];
+                local[j] = __builtin_nontemporal_load(a.tmp_group + i) - (u32)lo_g;
+                val[j] = __builtin_nontemporal_load(a.tmp_value + i);
             }
         }
 #pragma unroll
