@@ -158,7 +158,11 @@ typedef enum { WELD_MODE_FUSED = 0, WELD_MODE_UNFUSED = 1 } weld_mode_t;
 typedef struct {
     int32_t block_threads;   /* work-group size: 64..1024, multiple of 64            */
     int32_t units_per_thread;/* 128-bit load groups in flight per lane and column    */
-    int32_t grid_blocks;     /* persistent grid size                                 */
+    int32_t grid_blocks;     /* work-groups of the loop kernel; 0: as many as are resident at
+                                once, fewer for loops that only stream columns through light
+                                arithmetic (about 56 KB of loads in flight per compute unit),
+                                eight per unit for register-only loops with division, roots or
+                                transcendentals; weld_tune_launch measures it instead */
     int32_t dict_strategy;   /* 0 auto, 1 register slots, 2 LDS hash table, 3 global only,
                                 4 per-lane LDS slots                                */
     int32_t lds_dict_slots;  /* slots of the per-block LDS hash table (power of two) */
