@@ -184,3 +184,100 @@ def test_i8_products_are_not_merged_into_byte_dot_products(wb, tmp_path):
             assert "v_dot4" not in asm, f
     finally:
         wb.lib.weld_set_cache_dir(os.path.join(ROOT, "paper_1709_06416_amd", "kcache").encode())
+
+
+# ----------------------------------------------------------------------
+# corrupted descriptions
+# ----------------------------------------------------------------------
+def _corrupt(m, rnd):
+    """One random corruption of the marshalled description; returns (label, must_reject)."""
+    p = m.program
+    nops, nm, nb = len(p.ops), len(p.merges), len(p.builders)
+    kind = int(rnd.randint(0, 16))
+    bad_index = int(rnd.choice([nops, nops + 7, 1 << 30, -2, -1000, 2**31 - 1, -2**31]))
+    if kind == 0:      # operand refers forward / out of range
+        cands = [i for i, o in enumerate(p.ops) if o[0] not in ("col", "const", "index")]
+        if not cands: return None
+        i = int(rnd.choice(cands)); which = str(rnd.choice(["a", "b", "c"]))
+        if getattr(m.ops[i], which) < 0 and which != "a": which = "a"
+        setattr(m.ops[i], which, int(rnd.choice([i, i + 1, bad_index])))
+        return "operand %s of op %d" % (which, i), True
+    if kind == 1:
+        i = int(rnd.randint(nops)); m.ops[i].opcode = int(rnd.choice([26, 27, 28, 31, 77, -3, 1000, 2**31 - 1]))
+        return "opcode of op %d" % i, True
+    if kind == 2:
+        i = int(rnd.randint(nops)); m.ops[i].type = int(rnd.choice([5, 6, -1, 99, 2**31 - 1]))
+        return "type of op %d" % i, True
+    if kind == 3:
+        cands = [i for i, o in enumerate(p.ops) if o[0] == "col"]
+        i = int(rnd.choice(cands)); m.ops[i].a = int(rnd.choice([len(p.columns), 64, -1, 1 << 30, -5]))
+        return "column index of op %d" % i, True
+    if kind == 4:
+        i = int(rnd.randint(nm)); m.merges[i].builder = int(rnd.choice([nb, -1, 1 << 30, 8, -2**31]))
+        return "builder of merge %d" % i, True
+    if kind == 5:
+        i = int(rnd.randint(nm)); m.merges[i].pred = int(rnd.choice([nops, 1 << 30, -2, -77]))
+        return "pred of merge %d" % i, True
+    if kind == 6:
+        i = int(rnd.randint(nm)); m.merges[i].nvals = int(rnd.choice([9, -1, 100, 2**31 - 1, 0]))
+        return "nvals of merge %d" % i, True
+    if kind == 7:
+        i = int(rnd.randint(nm)); m.merges[i].nkeys = int(rnd.choice([5, -1, 100, 2**31 - 1]))
+        return "nkeys of merge %d" % i, True
+    if kind == 8:
+        i = int(rnd.randint(nm)); m.merges[i].val[0] = bad_index if bad_index != -1 else -2
+        return "value of merge %d" % i, True
+    if kind == 9:
+        i = int(rnd.randint(nb)); m.specs[i].kind = int(rnd.choice([5, 6, -1, 99, 2**31 - 1]))
+        return "kind of builder %d" % i, True
+    if kind == 10:
+        i = int(rnd.randint(nb)); m.specs[i].func = int(rnd.choice([4, -1, 99]))
+        return "func of builder %d" % i, p.builders[i]["kind"] in ("merger", "dictmerger", "vecmerger")
+    if kind == 11:
+        cands = [i for i, b in enumerate(p.builders) if b["kind"] in ("dictmerger", "groupbuilder")]
+        if not cands: return None
+        i = int(rnd.choice(cands)); which = int(rnd.randint(3))
+        if which == 0: m.specs[i].capacity = int(rnd.choice([0, -1, -2**62]))
+        elif which == 1: m.specs[i].nkeys = int(rnd.choice([0, 5, -1, 2**31 - 1]))
+        else: m.specs[i].key_type[0] = int(rnd.choice([4, 0, 7, -1]))      # f64 / bool / invalid key
+        return "dictionary spec %d of builder %d" % (which, i), True
+    if kind == 12:
+        cands = [i for i, b in enumerate(p.builders) if b["kind"] == "vecmerger"]
+        if not cands: return None
+        i = int(rnd.choice(cands)); m.specs[i].length = int(rnd.choice([0, -1, -2**40]))
+        return "vecmerger length of builder %d" % i, True
+    if kind == 13:
+        m.body.nops = int(rnd.choice([-1, 0, -2**31])); return "nops", True
+    if kind == 14:
+        m.builder.count = int(rnd.choice([0, -1, 9, 1000, 2**31 - 1])); return "builder count", True
+    if kind == 15:
+        if nm < 2: return None
+        m.merges[1].builder = m.merges[0].builder; return "two merges into one builder", True
+    return None
+
+
+def test_validator_rejects_corrupted_descriptions(wb):
+    """Random valid loop descriptions (workloads/random_programs.py) with one field of their C structs
+    overwritten: operand, column, builder and merge indices out of range or referring forward,
+    unknown opcodes / types / kinds / functions, field counts beyond the arrays, non-positive
+    capacities and lengths, negative counts, two merges into one builder.  Every one of them is
+    turned down with a status and a message by weld_validate and by the code generator's entry
+    (which validates first); none is read out of bounds."""
+    import numpy as np
+    from workloads import random_programs
+    tried = 0
+    for seed in range(600):
+        rnd = np.random.RandomState(seed)
+        prog = random_programs.make(int(rnd.randint(1 << 30)))[0]
+        m = wb.Marshalled(prog)
+        c = _corrupt(m, rnd)
+        if c is None:
+            continue
+        label, must_reject = c
+        buf = ctypes.create_string_buffer(512)
+        st = wb.lib.weld_validate(m.col_types, m.ncols, ctypes.byref(m.body), ctypes.byref(m.builder), buf, 512)
+        need = wb.lib.weld_generated_source(m.col_types, m.ncols, ctypes.byref(m.body), ctypes.byref(m.builder), None, 0)
+        if must_reject:
+            assert st != wb.OK and buf.value and need < 0, (seed, label, st, buf.value)
+            tried += 1
+    assert tried > 400
