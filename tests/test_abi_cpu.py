@@ -281,3 +281,48 @@ def test_validator_rejects_corrupted_descriptions(wb):
             assert st != wb.OK and buf.value and need < 0, (seed, label, st, buf.value)
             tried += 1
     assert tried > 400
+
+
+def test_nested_validator_rejects_corrupted_descriptions(wb):
+    """The same for nested loops: range columns, inner type and function, gather vectors, column
+    counts, merge counts, and the operands of `lookup` / `outer` overwritten with values out of range."""
+    import numpy as np
+    from workloads import random_programs as rp
+    C = ctypes
+    tried = 0
+    for seed in range(400):
+        rnd = np.random.RandomState(seed)
+        nested = rp.make_nested(int(rnd.randint(1 << 30)))[0]
+        m = wb.MarshalledNested(nested)
+        s = m.struct
+        kind = int(rnd.randint(0, 12))
+        label = None
+        if kind == 0: s.start_col = int(rnd.choice([-1, len(nested.outer.columns), 99, 2**31 - 1])); label = "start_col"
+        elif kind == 1: s.end_col = int(rnd.choice([-1, len(nested.outer.columns), 99, -2**31])); label = "end_col"
+        elif kind == 2: s.inner_type = int(rnd.choice([0, 1, 2, 5, -1, 99])); label = "inner_type"
+        elif kind == 3: s.inner_func = int(rnd.choice([4, -1, 99])); label = "inner_func"
+        elif kind == 4: s.ngather = int(rnd.choice([-1, 9, 1000, 2**31 - 1])); label = "ngather"
+        elif kind == 5:
+            if not nested.gather: continue
+            m.gcols[0].type = int(rnd.choice([0, 5, -1, 99])); label = "gather type"
+        elif kind == 6:
+            m.ocols[0].type = int(rnd.choice([0, 1, 4, 5, -1])); label = "offset column type"
+        elif kind == 7:
+            cands = [i for i, o in enumerate(nested.inner.ops) if o[0] == "lookup"]
+            if not cands: continue
+            i = int(rnd.choice(cands)); m.mi.ops[i].a = int(rnd.choice([len(nested.gather), -1, 64, 1 << 30])); label = "lookup vector"
+        elif kind == 8:
+            cands = [i for i, o in enumerate(nested.inner.ops) if o[0] == "outer"]
+            if not cands: continue
+            i = int(rnd.choice(cands)); m.mi.ops[i].a = int(rnd.choice([len(nested.outer.columns), -1, 64, 1 << 30])); label = "outer column"
+        elif kind == 9:
+            s.inner.ncols = int(rnd.choice([-1, 0, 65, 2**31 - 1])); label = "inner ncols"
+        elif kind == 10:
+            s.outer.ncols = int(rnd.choice([-1, 0, 1, 65, 2**31 - 1])); label = "outer ncols"
+        elif kind == 11:
+            s.inner_body.nmerges = int(rnd.choice([0, 2, -1, 100])); label = "inner merges"
+        buf = C.create_string_buffer(512)
+        st = wb.lib.weld_nested_validate(C.byref(s), C.byref(m.mo.builder), buf, 512)
+        assert st != wb.OK and buf.value, (seed, label, st)
+        tried += 1
+    assert tried > 250
