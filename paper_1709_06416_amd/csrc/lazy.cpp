@@ -459,6 +459,22 @@ int64_t weld_object_describe(weld_object_t* const* roots, int32_t nroots, char* 
     Fused F;
     Error e = fuse(roots, nroots, &F);
     if (!e.ok()) { weld::set_last_error(e.text); return -1; }
+    {   // what evaluation would turn down is turned down here as well (maps are checked when they are fused)
+        std::vector<int32_t> types(F.f.leaves.size());
+        for (size_t k = 0; k < types.size(); ++k) types[k] = F.f.leaves[k]->type;
+        weld_body_t body;
+        body.nops = (int32_t)F.f.ops.size();
+        body.ops = F.f.ops.data();
+        body.nmerges = (int32_t)F.merges.size();
+        body.merges = F.merges.data();
+        weld_builder_t b;
+        memset(&b, 0, sizeof b);
+        b.count = (int32_t)F.specs.size();
+        b.spec = F.specs.data();
+        weld::Loop checked;
+        e = weld::validate(types.data(), (int32_t)types.size(), &body, &b, &checked);
+        if (!e.ok()) { weld::set_last_error(e.text); return -1; }
+    }
     const std::string s = describe(F);
     if (buf && buflen > 0) snprintf(buf, (size_t)buflen, "%s", s.c_str());
     return (int64_t)s.size() + 1;
