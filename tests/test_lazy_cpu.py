@@ -85,31 +85,31 @@ def test_corrupted_maps_are_turned_down_at_construction_or_when_fused(lz):
     from paper_1709_06416_amd import binding as wb
     lazy, lib = lz, wb.lib
     for seed in range(300):
-    rnd = np.random.RandomState(seed)
-    t = str(rnd.choice(["i64", "f64", "i32"]))
-    deps = [lazy.Vec.from_pointer(0x10000 * (k + 1), t, 1000) for k in range(int(rnd.randint(1, 4)))]
-    nd = len(deps)
-    ops = [("col", t, k, -1, -1, 0) for k in range(nd)] + [("const", t, -1, -1, -1, 3)]
-    for _ in range(int(rnd.randint(1, 5))):
-        a, b = int(rnd.randint(len(ops))), int(rnd.randint(len(ops)))
-        ops.append((str(rnd.choice(["add", "mul", "sub", "min"])), t, a, b, -1, 0))
-    arr = (wb.Op * len(ops))()
-    for i, (code, ty, a, b, c, imm) in enumerate(ops):
-        o = arr[i]; o.opcode, o.type, o.a, o.b, o.c = wb.OPCODE[code], wb.TYPE_ID[ty], a, b, c
-        if code == "const": o.imm.i64 = 3
-    handles = (C.c_void_p * nd)(*[d._h for d in deps])
-    nops, ndeps = len(ops), nd
-    kind = int(rnd.randint(0, 9)); label = None
-    bad = int(rnd.choice([len(ops), 1 << 30, -2, -1000, 2**31 - 1]))
-    if kind == 0: arr[len(ops) - 1].a = int(rnd.choice([len(ops) - 1, bad])); label = "operand"
-    elif kind == 1: arr[int(rnd.randint(len(ops)))].opcode = int(rnd.choice([26, 77, -3, 2**31 - 1])); label = "opcode"
-    elif kind == 2: arr[int(rnd.randint(len(ops)))].type = int(rnd.choice([5, -1, 99])); label = "type"
-    elif kind == 3: arr[0].a = int(rnd.choice([nd, 64, -1, 1 << 30])); label = "dep index"
-    elif kind == 4: nops = int(rnd.choice([0, -1, -2**31])); label = "nops"
-    elif kind == 5: ndeps = int(rnd.choice([0, -1, -5])); label = "ndeps"
-    elif kind == 6: handles[0] = None; label = "null dep"
-    elif kind == 7: arr[len(ops) - 1].type = wb.TYPE_ID["f64" if t != "f64" else "i64"]; label = "result type differs from operands"
-    elif kind == 8: arr[len(ops) - 1].opcode = wb.OPCODE["keyexists"]; label = "probe op in a map"
+        rnd = np.random.RandomState(seed)
+        t = str(rnd.choice(["i64", "f64", "i32"]))
+        deps = [lazy.Vec.from_pointer(0x10000 * (k + 1), t, 1000) for k in range(int(rnd.randint(1, 4)))]
+        nd = len(deps)
+        ops = [("col", t, k, -1, -1, 0) for k in range(nd)] + [("const", t, -1, -1, -1, 3)]
+        for _ in range(int(rnd.randint(1, 5))):
+            a, b = int(rnd.randint(len(ops))), int(rnd.randint(len(ops)))
+            ops.append((str(rnd.choice(["add", "mul", "sub", "min"])), t, a, b, -1, 0))
+        arr = (wb.Op * len(ops))()
+        for i, (code, ty, a, b, c, imm) in enumerate(ops):
+            o = arr[i]; o.opcode, o.type, o.a, o.b, o.c = wb.OPCODE[code], wb.TYPE_ID[ty], a, b, c
+            if code == "const": o.imm.i64 = 3
+        handles = (C.c_void_p * nd)(*[d._h for d in deps])
+        nops, ndeps = len(ops), nd
+        kind = int(rnd.randint(0, 9)); label = None
+        bad = int(rnd.choice([len(ops), 1 << 30, -2, -1000, 2**31 - 1]))
+        if kind == 0: arr[len(ops) - 1].a = int(rnd.choice([len(ops) - 1, bad])); label = "operand"
+        elif kind == 1: arr[int(rnd.randint(len(ops)))].opcode = int(rnd.choice([26, 77, -3, 2**31 - 1])); label = "opcode"
+        elif kind == 2: arr[int(rnd.randint(len(ops)))].type = int(rnd.choice([5, -1, 99])); label = "type"
+        elif kind == 3: arr[0].a = int(rnd.choice([nd, 64, -1, 1 << 30])); label = "dep index"
+        elif kind == 4: nops = int(rnd.choice([0, -1, -2**31])); label = "nops"
+        elif kind == 5: ndeps = int(rnd.choice([0, -1, -5])); label = "ndeps"
+        elif kind == 6: handles[0] = None; label = "null dep"
+        elif kind == 7: arr[len(ops) - 1].type = wb.TYPE_ID["f64" if t != "f64" else "i64"]; label = "result type differs from operands"
+        elif kind == 8: arr[len(ops) - 1].opcode = wb.OPCODE["keyexists"]; label = "probe op in a map"
         out = C.c_void_p()
         st = lib.weld_object_new_map(handles, ndeps, arr, nops, C.byref(out))
         if st == wb.OK:
