@@ -74,8 +74,6 @@ def main():
             tuning_report[c] = {"tune": tunes[c], "kernel_ms": round(best_ms, 4), "library_choice_ms": round(default_ms, 4)}
     loops = {c: wb.prepare(progs[c], tune=tunes[c]) for c in names}                  # marshalled once, like a host program would
 
-    def enqueue():
-        return [(c, wb.fused_for(loops[c], cols[c])) for c in names]                  # work is only enqueued
 
     def drain(handles, collect=None):
         for c, r in handles:
@@ -94,9 +92,15 @@ def main():
     def run(steps, collect=None):
         pending = None
         for _ in range(steps):
-            cur = enqueue()
-            if pending is not None:
-                drain(pending, collect)
+            cur = []
+            for k, c in enumerate(names):
+                cur.append((c, wb.fused_for(loops[c], cols[c])))                       # work is only enqueued
+                if pending is not None and k == (len(names) - 1) // 2:
+                    # the first half of this step is queued: look at the previous step now, so that the
+                    # second half finds that step's blocks back in the pool (a dictionary's spill queues
+                    # written to the addresses of the last step are still in the memory-side cache)
+                    drain(pending, collect)
+                    pending = None
             pending = cur
         if pending is not None:
             drain(pending, collect)
