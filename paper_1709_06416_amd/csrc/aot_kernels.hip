@@ -10,6 +10,7 @@ typedef unsigned long long u64;
 typedef long long i64;
 typedef unsigned int u32;
 typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+typedef i64 i64x2 __attribute__((ext_vector_type(2)));
 
 static const u64 kEmptyKey = 0x8000000000000000ull;
 
@@ -240,16 +241,32 @@ __global__ void __launch_bounds__(1024) group_offsets_kernel(const i64* counts, 
     const int tid = threadIdx.x;
     i64 n = (i64)*ngroups;
     if (n > capacity) n = capacity;
+    const bool aligned16 = (((uintptr_t)counts | (uintptr_t)offsets | (uintptr_t)cursor) & 15) == 0;
     if (tid == 0) s_carry = 0;
     __syncthreads();
     for (i64 base = 0; base < n; base += 8192) {
         i64 c[8];
         i64 mine = 0;
+        const bool whole = base + 8192 <= n && aligned16;      // every thread's eight groups exist
+        if (whole) {
+            // 16-byte loads: a lane's eight sizes are 64 contiguous bytes, lanes are 64 bytes apart, so
+            // every load instruction of a wavefront touches 32 cache lines whatever its width
+            const i64x2* p = (const i64x2*)(counts + base + (i64)tid * 8);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const i64 g = base + (i64)tid * 8 + k;
-            c[k] = g < n ? counts[g] : 0;
-            mine += c[k];
+            for (int q = 0; q < 4; ++q) {
+                const i64x2 v = p[q];
+                c[2 * q] = v.x;
+                c[2 * q + 1] = v.y;
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) mine += c[k];
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const i64 g = base + (i64)tid * 8 + k;
+                c[k] = g < n ? counts[g] : 0;
+                mine += c[k];
+            }
         }
         i64 incl = mine;
         for (int off = 1; off < 64; off <<= 1) {
@@ -260,14 +277,29 @@ __global__ void __launch_bounds__(1024) group_offsets_kernel(const i64* counts, 
         __syncthreads();
         i64 run = s_carry + incl - mine;
         for (int w = 0; w < (tid >> 6); ++w) run += s_wave[w];
+        if (whole) {
+            i64x2* po = (i64x2*)(offsets + base + (i64)tid * 8);
+            i64x2* pc = (i64x2*)(cursor + base + (i64)tid * 8);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const i64 g = base + (i64)tid * 8 + k;
-            if (g < n) {
-                offsets[g] = run;
-                cursor[g] = 0;
+            for (int q = 0; q < 4; ++q) {
+                i64x2 o;
+                o.x = run;
+                o.y = run + c[2 * q];
+                run = o.y + c[2 * q + 1];
+                po[q] = o;
+                const i64x2 zero = {0, 0};
+                pc[q] = zero;
             }
-            run += c[k];
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const i64 g = base + (i64)tid * 8 + k;
+                if (g < n) {
+                    offsets[g] = run;
+                    cursor[g] = 0;
+                }
+                run += c[k];
+            }
         }
         __syncthreads();
         if (tid == 1023) s_carry = run;
