@@ -215,3 +215,39 @@ def test_join_full_size_against_the_oracle_on_the_rows_that_matter(wb):
     assert np.array_equal(keys[0], wkeys[0])
     assert np.array_equal(vals[0], wvals[0]) and np.array_equal(vals[1], wvals[1])
     assert int(vals[0].sum() + vals[1].sum()) == int(keep.sum().item())
+
+
+def test_more_than_two_to_the_31_rows(wb):
+    """Row indices, tile numbers, output offsets and lengths beyond 32 bits: an i8 column of
+    2^31 + 77 rows through a filtered sum, an order-preserving compaction (1.9e9 elements out),
+    a max over the row index and a 227-key dictionary.  The oracle would materialise an i64
+    intermediate of 17 GB per operator; the results are checked against what they are by
+    definition (NumPy on the host copy of the same column): filtered sum, selected
+    subsequence, n - 1, histogram."""
+    n = (1 << 31) + 77
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    col = torch.randint(-128, 128, (n,), dtype=torch.int8, device="cuda", generator=g)
+    host = col.cpu().numpy()
+    p = Program(["i8"])
+    x = p.col(0)
+    pred = p.bin("gt", x, p.const("i8", -100))
+    p.merge(p.merger("i64", "add"), p.un("cast", x, to="i64"), pred=pred)
+    p.merge(p.vecbuilder("i8"), x, pred=pred)
+    p.merge(p.merger("i64", "max"), p.index())
+    p.merge(p.dictmerger(["i8"], ["i64"], "add", 256), [p.const("i64", 1)], keys=[x], pred=pred)
+    res = wb.fused_for(p, [col]).check()
+    try:
+        keep = host > -100
+        assert int(res.merger(0)) == int(host[keep].sum(dtype=np.int64))
+        assert int(res.merger(2)) == n - 1
+        kept = res.vec(1)
+        assert kept.numel() == int(keep.sum())
+        assert torch.equal(kept.cpu(), torch.from_numpy(host[keep]))
+        del kept
+        keys, vals = res.dict(3)
+        counts = np.bincount(host[keep].astype(np.int64) + 128, minlength=256)
+        assert dict(zip(keys[0].tolist(), vals[0].tolist())) == {k - 128: int(c) for k, c in enumerate(counts) if c}
+    finally:
+        res.free()
+        wb.lib.weld_pool_trim()
