@@ -778,22 +778,23 @@ hipError_t launch_or_error(void* dst_ctl, const void* src_ctl, hipStream_t strea
 }
 
 // ---------------------------------------------------------------- probes
-// Pure streaming read with 16-byte loads: the attainable HBM read rate on this machine.
+// Pure streaming read with 16-byte loads, in the shape the loop kernels read their columns in: a
+// work-group takes contiguous 56 KB tiles round-robin and has a whole tile's loads (fourteen per
+// thread) in flight before it uses the first; one work-group per compute unit is what that rate
+// wants.  This is the attainable HBM read rate on the box.
+#define PROBE_LOADS 14
 __global__ void __launch_bounds__(256) probe_read_kernel(const u32x4* p, i64 n16, u64* checksum) {
     u32 a = 0, b = 0, c = 0, d = 0;
-    const i64 stride = (i64)gridDim.x * 256;
-    i64 i = (i64)blockIdx.x * 256 + threadIdx.x;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        const u32x4 v0 = __builtin_nontemporal_load(p + i);
-        const u32x4 v1 = __builtin_nontemporal_load(p + i + stride);
-        const u32x4 v2 = __builtin_nontemporal_load(p + i + 2 * stride);
-        const u32x4 v3 = __builtin_nontemporal_load(p + i + 3 * stride);
-        a += v0.x + v1.x + v2.x + v3.x;
-        b += v0.y + v1.y + v2.y + v3.y;
-        c += v0.z + v1.z + v2.z + v3.z;
-        d += v0.w + v1.w + v2.w + v3.w;
+    const i64 tile = (i64)PROBE_LOADS * 256;
+    const i64 ntiles = n16 / tile;
+    for (i64 t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        u32x4 v[PROBE_LOADS];
+#pragma unroll
+        for (int j = 0; j < PROBE_LOADS; ++j) v[j] = __builtin_nontemporal_load(p + t * tile + j * 256 + threadIdx.x);
+#pragma unroll
+        for (int j = 0; j < PROBE_LOADS; ++j) { a += v[j].x; b += v[j].y; c += v[j].z; d += v[j].w; }
     }
-    for (; i < n16; i += stride) {
+    for (i64 i = ntiles * tile + (i64)blockIdx.x * 256 + threadIdx.x; i < n16; i += (i64)gridDim.x * 256) {
         const u32x4 v = __builtin_nontemporal_load(p + i);
         a += v.x; b += v.y; c += v.z; d += v.w;
     }

@@ -1064,7 +1064,7 @@ const char* weld_last_error(void) { return g_last_error.c_str(); }
 
 weld_status_t weld_probe_read(const void* data, int64_t bytes, void* checksum_dev, void* stream) {
     if (!data || !checksum_dev || bytes < 0 || ((uintptr_t)data & 15)) return WELD_ERR_INVALID_ARG;
-    hipError_t h = launch_probe_read(data, bytes, checksum_dev, device_info().cus * 8, (hipStream_t)stream);
+    hipError_t h = launch_probe_read(data, bytes, checksum_dev, device_info().cus, (hipStream_t)stream);
     return h == hipSuccess ? WELD_OK : WELD_ERR_DEVICE;
 }
 

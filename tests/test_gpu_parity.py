@@ -584,6 +584,21 @@ def test_launch_tuning_returns_a_record_that_gives_the_same_results(wb):
         wb.tune_launch(p, [_dev(np.arange(100, dtype=np.float64))])
 
 
+@pytest.mark.parametrize("words", [4, 4 * 14 * 256 * 3 + 4 * 77, 40_000_004])
+def test_memory_probes_touch_every_byte_once(wb, words):
+    """The read probe's checksum is the sum of the 32-bit words it was given (whole 56 KB tiles and
+    a ragged rest), and the copy probe copies them: the two kernels the bench line's attainable read
+    rate and the scaling of the HBM counters rest on."""
+    rnd = np.random.RandomState(words % 1000)
+    host = rnd.randint(0, 256, size=words).astype(np.int32)        # small: a thread sums its words in 32 bits
+    src = _dev(host)
+    assert int(wb.probe_read(src).item()) == int(host.astype(np.int64).sum())
+    dst = torch.zeros_like(src)
+    wb.probe_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+
+
 def test_single_library_instance_loaded():
     # the library must bind to the HIP runtime torch already loaded, not a second copy
     libs = set()
