@@ -36,7 +36,10 @@ dictionary entries are returned sorted by key (the paper leaves them
 unordered, so callers compare sorted).
 
 Parity pins live in tests/test_oracle_pins.py (paper-printed results, closed
-forms, brute force against oracle/rowwise.py, library routines, exact sums) and, for
+forms, brute force against oracle/rowwise.py, library routines, exact sums), in
+tests/test_oracle_operator_pins.py (every operator of the expression language against
+hand-worked tables, and every expression column of seeded random programs against the
+per-row loop) and, for
 nested loops, tests/test_oracle_nested_pins.py (a hand-worked example, scipy's sparse
 product, the literal nested loops, PageRank fixed points and rank conservation).
 Black-Scholes prices have no printed value in the paper: they are pinned by
