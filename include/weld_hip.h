@@ -267,6 +267,49 @@ typedef struct {
 weld_status_t weld_fused_for_probe(const weld_cols_t* cols, int64_t n, const weld_dict_ref_t* dicts, int32_t ndicts,
                                    const weld_body_t* body, const weld_builder_t* builder, weld_result_t** out);
 
+/*
+ * weld_fused_for_static -- weld_fused_for for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It calls no
+ * hipMalloc, hipFree, hipHostMalloc, event or module routine: the results go to buffers the CALLER
+ * passes, and the workspace (control words, merger partials, scan descriptors, hash tables, spill
+ * queues) is one fixed buffer of WELD_STATIC_SCRATCH_BYTES that the library holds on every GPU it
+ * runs on until the process ends.
+ *
+ *  cols, n, body, builder : as for weld_fused_for.  Fused mode only; merger, vecbuilder,
+ *           dictmerger and vecmerger (a groupbuilder's workspace grows with n: WELD_ERR_UNSUPPORTED).
+ *           conf.memory_limit is ignored: the limit is the fixed buffer.
+ *  outs   : host array, one entry per builder, 16-byte aligned DEVICE buffers owned by the caller:
+ *             merger     data = 8 bytes (the scalar is stored in its own type at offset 0)
+ *             vecbuilder data = room for `capacity` >= n elements (a filter's selectivity is not
+ *                        known in advance; what lies beyond the returned length is unspecified)
+ *             vecmerger  data = room for `capacity` >= length 8-byte cells
+ *             dictmerger data = packed key structs, data2 = packed value structs, room for
+ *                        `capacity` >= the builder's capacity entries each; unordered
+ *  status_dev : DEVICE array of 1 + WELD_MAX_BUILDERS int64 written behind the call's kernels:
+ *           [0] = 0 or error bits (1: more distinct keys than a dictmerger's capacity, 2: a tile gave
+ *           up its bounded wait, 4: vecmerger index out of range); [1 + b] = elements of builder b
+ *           (merger 1, vecbuilder / vecmerger length, dictmerger entries).
+ * The call only enqueues on conf.stream; the caller waits for the stream and reads status_dev.
+ *
+ * Errors: WELD_ERR_NOT_READY when this loop has no loaded kernel yet -- compiling and loading one
+ * allocates, so run the same loop (body, builders, tuning, 16-byte alignment of the columns) once
+ * through weld_fused_for beforehand; WELD_ERR_OOM when the workspace exceeds the fixed buffer (a
+ * dictmerger of more than about 5e5 keys and one value field, or more than about 4e6 tiles of a
+ * filter; spill queues shrink to what is left and full ones fall back to device atomics, so large
+ * dictionaries get slower, not wrong); WELD_ERR_INVALID_ARG for a missing or too small output.
+ * The first call on a device fetches the buffer's address (set-up, once per device; do it outside a
+ * capture).  Every call on a GPU shares that GPU's one buffer: calls on one stream are ordered and
+ * safe, calls that overlap on different streams or host threads RACE -- the caller serialises them.
+ */
+#define WELD_STATIC_SCRATCH_BYTES (32ll << 20)
+typedef struct {
+    void* data;       /* device */
+    void* data2;      /* device; dictmerger values, NULL otherwise */
+    int64_t capacity; /* elements / entries the buffers have room for */
+} weld_out_t;
+weld_status_t weld_fused_for_static(const weld_cols_t* cols, int64_t n, const weld_body_t* body,
+                                    const weld_builder_t* builder, const weld_out_t* outs, int64_t* status_dev);
+
 /* Evaluation point: waits for the call's work, reads back lengths and kernel-side error
  * flags.  WELD_OK, WELD_ERR_CAPACITY or WELD_ERR_DEVICE.  Idempotent. */
 weld_status_t weld_result_status(weld_result_t* r);

@@ -110,6 +110,15 @@ class DictRef(C.Structure):
 lib.weld_fused_for_probe.argtypes = [C.POINTER(Cols), C.c_int64, C.POINTER(DictRef), C.c_int32, C.POINTER(Body),
                                      C.POINTER(Builder), C.POINTER(C.c_void_p)]
 lib.weld_fused_for_probe.restype = C.c_int
+class Out(C.Structure):
+    _fields_ = [("data", C.c_void_p), ("data2", C.c_void_p), ("capacity", C.c_int64)]
+
+
+lib.weld_fused_for_static.argtypes = [C.POINTER(Cols), C.c_int64, C.POINTER(Body), C.POINTER(Builder), C.POINTER(Out),
+                                      C.c_void_p]
+lib.weld_fused_for_static.restype = C.c_int
+STATIC_SCRATCH_BYTES = 32 << 20
+MAX_BUILDERS = 8
 lib.weld_result_status.argtypes = [C.c_void_p]
 lib.weld_result_status.restype = C.c_int
 lib.weld_result_error.argtypes = [C.c_void_p]
@@ -480,6 +489,41 @@ def fused_for(program, columns, mode="fused", stream=None, memory_limit=0, tune=
     if st != OK:
         raise WeldError(st, lib.weld_last_error().decode())
     return Result(out, program, (m, cols, list(columns), inits, dicts))
+
+
+def fused_for_static(program, columns, outs, status, stream=None, tune=None, n=None, inits=None):
+    """weld_fused_for_static: the loop enqueued with the caller's output tensors and no allocation by
+    the library.  outs: per builder a CUDA tensor (merger: one 8-byte element; vecbuilder / vecmerger:
+    room for the elements) or, for a dictmerger, a pair of uint8 CUDA tensors (packed keys, packed
+    values); status: int64 CUDA tensor of 1 + MAX_BUILDERS elements.  Returns nothing: the caller
+    waits for the stream and reads `status` and the outputs."""
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    if isinstance(program, Marshalled):
+        m, program = program, program.program
+        m.builder.conf.stream = stream
+    else:
+        m = Marshalled(program, stream=stream, tune=tune, inits=inits)
+    cols, rows = _zipped_columns(program, columns)
+    if n is None:
+        n = rows if rows is not None else 0
+    cs = Cols(len(columns), cols)
+    if status.dtype != torch.int64 or not status.is_cuda or status.numel() < 1 + MAX_BUILDERS:
+        raise WeldError(ERR_INVALID_ARG, "status must be an int64 CUDA tensor of 1 + MAX_BUILDERS elements")
+    o = (Out * max(len(program.builders), 1))()
+    for b, spec in enumerate(program.builders):
+        t = outs[b]
+        if spec["kind"] == "dictmerger":
+            ksize = sum(np.dtype(TYPE_NP[k]).itemsize for k in spec["key_types"])
+            vsize = sum(np.dtype(TYPE_NP[v]).itemsize for v in spec["val_types"])
+            o[b].data, o[b].data2 = t[0].data_ptr(), t[1].data_ptr()
+            o[b].capacity = min(t[0].numel() * t[0].element_size() // ksize, t[1].numel() * t[1].element_size() // vsize)
+        else:
+            o[b].data = t.data_ptr() if t.numel() else None
+            o[b].capacity = t.numel()
+    st = lib.weld_fused_for_static(C.byref(cs), n, C.byref(m.body), C.byref(m.builder), o, status.data_ptr())
+    if st != OK:
+        raise WeldError(st, lib.weld_last_error().decode())
 
 
 def prepare(program, mode="fused", memory_limit=0, tune=None, inits=None):

@@ -20,7 +20,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HOST_SOURCES = ["validate.cpp", "codegen.cpp", "jit.cpp", "pool.cpp", "runtime.cpp", "unfused.cpp", "lazy.cpp", "nested.cpp", "tuner.cpp"]
-HIP_SOURCES = ["aot_kernels.hip", "spill_kernels.hip"]
+HIP_SOURCES = ["aot_kernels.hip", "spill_kernels.hip", "static_entry.hip"]
 ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 HIPCC = os.path.join(ROCM, "bin", "hipcc")
 

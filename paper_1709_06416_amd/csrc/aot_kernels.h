@@ -137,6 +137,15 @@ hipError_t launch_tile_rows(const void* start, int is64, int64_t n_outer, int64_
                             void* tile_row, hipStream_t stream);
 hipError_t launch_or_error(void* dst_ctl, const void* src_ctl, hipStream_t stream);
 
+// weld_fused_for_static (static_entry.hip): copies the error bits and the builders' lengths from a
+// call's control block to the caller's device array (status[0] = error bits, status[1 + b] = length
+// of builder b: known[b] if that is >= 0, else the count word the kernels left in the block).
+struct StaticLengths {
+    int count;
+    long long known[8];
+};
+hipError_t launch_static_status(const void* ctl, const StaticLengths& lens, int64_t* status_dev, hipStream_t stream);
+
 hipError_t launch_probe_read(const void* data, int64_t bytes, void* checksum, int blocks, hipStream_t stream);
 hipError_t launch_probe_copy(void* dst, const void* src, int64_t bytes, int blocks, hipStream_t stream);
 

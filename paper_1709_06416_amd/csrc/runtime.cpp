@@ -172,13 +172,19 @@ std::string plan_key(const Loop& L, const weld_tuning_t& tune, bool aligned, int
 }
 
 // kind 0: fused loop; kind 1: flattened inner loop of a nested for (extra = offset type)
-Error get_plan(const Loop& L, const weld_tuning_t& tune, bool aligned, int kind, int extra, std::shared_ptr<Plan>* out) {
+// create == false: only a plan that an earlier call made is returned (compiling and loading a kernel
+// allocates device memory, which some callers must not do)
+Error get_plan(const Loop& L, const weld_tuning_t& tune, bool aligned, int kind, int extra, std::shared_ptr<Plan>* out,
+               bool create = true) {
     const std::string key = plan_key(L, tune, aligned, kind, extra);
     {
         std::lock_guard<std::mutex> lk(g_plan_mu);
         auto it = g_plans.find(key);
         if (it != g_plans.end()) { *out = it->second; return Error(); }
     }
+    if (!create)
+        return mk(WELD_ERR_NOT_READY, "this loop has no loaded kernel yet: run it once through weld_fused_for (same body, builders, "
+                                      "tuning and 16-byte alignment of the columns) before the call that must not allocate");
     auto p = std::make_shared<Plan>();
     p->var = kind == 0 ? choose_variant(L, tune, aligned) : choose_segmented_variant(L, tune, aligned);
     Generated G = kind == 0 ? generate(L, p->var) : generate_segmented(L, p->var, extra);
@@ -260,7 +266,8 @@ Loop expand_groups(const Loop& in, std::vector<GroupLink>* links) {
 }
 
 static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links, size_t user_builders, const ColRef* cols,
-                             int64_t n, const weld_conf_t& conf, weld_result* r, const void* prior_ctl, const DictTable* tables);
+                             int64_t n, const weld_conf_t& conf, weld_result* r, const void* prior_ctl, const DictTable* tables,
+                             const StaticTarget* st = nullptr);
 
 Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t& conf, weld_result* r,
                 const void* prior_ctl, const DictTable* tables) {
@@ -269,6 +276,16 @@ Error run_fused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t&
     if (X.builders.size() > 10) return mk(WELD_ERR_UNSUPPORTED, "too many builders once the groupbuilders are expanded (10 at most)");
     if (L.ndicts > 0 && !tables) return mk(WELD_ERR_INVALID_ARG, "the loop probes dictionaries but none were passed");
     return run_fused_plain(X, links, L.builders.size(), cols, n, conf, r, prior_ctl, tables);
+}
+
+Error run_fused_static(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_t& conf, const StaticTarget& st) {
+    for (const weld_builder_spec_t& s : L.builders)
+        if (s.kind == WELD_GROUPBUILDER) return mk(WELD_ERR_UNSUPPORTED, "groupbuilders need workspace in proportion to the rows: not in the call that allocates nothing");
+    if (L.ndicts > 0) return mk(WELD_ERR_UNSUPPORTED, "loops that probe dictionaries run through weld_fused_for_probe only");
+    weld_result r;                       // never handed out: no events, no pinned words, no pool block
+    r.stream = conf.stream;
+    const std::vector<GroupLink> none;
+    return run_fused_plain(L, none, L.builders.size(), cols, n, conf, &r, nullptr, nullptr, &st);
 }
 
 // Loops with static tiles whose builders all live in registers (mergers, vectors written in place,
@@ -294,13 +311,14 @@ static int streaming_class(const Loop& L, const Variant& var) {
 static const size_t kOverflowEntries = 1 << 16;
 
 static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links, size_t user_builders, const ColRef* cols,
-                             int64_t n, const weld_conf_t& conf, weld_result* r, const void* prior_ctl, const DictTable* tables) {
+                             int64_t n, const weld_conf_t& conf, weld_result* r, const void* prior_ctl, const DictTable* tables,
+                             const StaticTarget* st) {
     hipStream_t stream = (hipStream_t)conf.stream;
     bool aligned = true;
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c] && ((uintptr_t)cols[c].data & 15)) aligned = false;
     std::shared_ptr<Plan> plan;
-    Error e = get_plan(L, conf.tune, aligned, 0, 0, &plan);
+    Error e = get_plan(L, conf.tune, aligned, 0, 0, &plan, st == nullptr);
     if (!e.ok()) return e;
     const Variant& var = plan->var;
     Kernel* kern = plan->kern;
@@ -342,6 +360,10 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     // ---- one block: control words, per-builder workspace, results
     Layout lay;
     const size_t off_ctl = lay.take(kCtlBytes);
+    // with a StaticTarget the results go to the caller's buffers and only the workspace is laid out
+    // (in the library's fixed buffer, whose size then plays the part of the memory limit)
+    const int64_t mem_limit = st ? (int64_t)st->scratch_bytes : conf.memory_limit;
+    auto take_out = [&](size_t bytes) -> size_t { return st ? 0 : lay.take(bytes); };
     struct Off { size_t part = 0, res = 0, out = 0, desc = 0, keys = 0, vals[8] = {0}, okeys = 0, ovals = 0, log = 0, qcnt = 0,
                         slot_pos = 0, goffsets = 0, gcursor = 0, gvalues = 0, gbcursor = 0, gtmp_group = 0, gtmp_value = 0,
                         ovf = 0, ovf_count = 0;
@@ -357,17 +379,17 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         switch (var.backend[b]) {
             case BK_MERGER:
                 off[b].part = lay.take(8 * (size_t)grid);
-                off[b].res = lay.take(8);
+                off[b].res = take_out(8);
                 break;
             case BK_VEC_DIRECT:
-                off[b].out = lay.take((size_t)n * type_size(s.val_type[0]));
+                off[b].out = take_out((size_t)n * type_size(s.val_type[0]));
                 break;
             case BK_VEC_COMPACT:
-                off[b].out = lay.take((size_t)n * type_size(s.val_type[0]));
+                off[b].out = take_out((size_t)n * type_size(s.val_type[0]));
                 off[b].desc = lay.take(8 * (size_t)ntiles);
                 break;
             case BK_VECM_REG: case BK_VECM_LDS: case BK_VECM_GLOBAL:
-                off[b].out = lay.take(8 * (size_t)s.length);
+                off[b].out = take_out(8 * (size_t)s.length);
                 break;
             default: {
                 const int64_t slots = dict_table_slots(s.capacity);
@@ -377,8 +399,8 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
                 int ks = 0, vs = 0;
                 for (int k = 0; k < s.nkeys; ++k) ks += type_size(s.key_type[k]);
                 for (int k = 0; k < s.nvals; ++k) vs += type_size(s.val_type[k]);
-                off[b].okeys = lay.take((size_t)s.capacity * ks);
-                off[b].ovals = lay.take((size_t)s.capacity * vs);
+                off[b].okeys = take_out((size_t)s.capacity * ks);
+                off[b].ovals = take_out((size_t)s.capacity * vs);
                 if (const GroupLink* g = link_of(b)) {      // second half of a groupbuilder
                     off[b].slot_pos = lay.take(4 * (size_t)(slots + 1));
                     off[b].goffsets = lay.take(8 * (size_t)(s.capacity + 1));
@@ -401,7 +423,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             int lg = 9;
             while (((int64_t)256 << lg) < s.capacity) ++lg;
             const size_t need = 12 * (size_t)n + 256 * 8 + 1024;
-            if (conf.memory_limit > 0 && (int64_t)(lay.total + need + still_to_come) > conf.memory_limit) continue;
+            if (mem_limit > 0 && (int64_t)(lay.total + need + still_to_come) > mem_limit) continue;
             off[b].glog = lg;
             off[b].gbcursor = lay.take(256 * 8);
             off[b].gtmp_group = lay.take(4 * (size_t)n);
@@ -430,22 +452,41 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         }
         if (cap > (1 << 23) - 1) cap = (1 << 23) - 1;   // the kernel indexes a work-group's segments with 32 bits
         const size_t seg = (size_t)grid * var.spill_parts * entry;
-        if (conf.memory_limit > 0) {
-            const int64_t room = conf.memory_limit - (int64_t)lay.total;
+        if (mem_limit > 0) {
+            const int64_t room = mem_limit - (int64_t)lay.total;
             const int64_t fit = room > 0 ? (room - 256) / (int64_t)seg : 0;
             if (cap > fit) cap = fit > 0 ? fit : 0;
         }
         off[b].qcap = cap;
         off[b].log = lay.take(seg * (size_t)cap);
     }
-    if (conf.memory_limit > 0 && (int64_t)lay.total > conf.memory_limit)
-        return mk(WELD_ERR_OOM, "the loop needs " + std::to_string(lay.total) + " bytes of device memory, limit is " +
-                                    std::to_string(conf.memory_limit));
+    if (mem_limit > 0 && (int64_t)lay.total > mem_limit)
+        return mk(WELD_ERR_OOM, "the loop needs " + std::to_string(lay.total) + " bytes of device memory, " +
+                                    (st ? "the fixed workspace of the call that allocates nothing holds " : "limit is ") +
+                                    std::to_string(mem_limit));
     void* block = nullptr;
-    e = pool_alloc(lay.total, &block);
-    if (!e.ok()) return e;
-    r->blocks.push_back(block);
+    if (st) {
+        block = st->scratch;
+    } else {
+        e = pool_alloc(lay.total, &block);
+        if (!e.ok()) return e;
+        r->blocks.push_back(block);
+    }
     char* base = (char*)block;
+    // where the results go: pieces of the block, or the caller's buffers
+    struct OutPtr { char *res = nullptr, *out = nullptr, *okeys = nullptr, *ovals = nullptr; };
+    std::vector<OutPtr> op(NB);
+    for (size_t b = 0; b < NB; ++b) {
+        if (st) {
+            op[b].res = op[b].out = op[b].okeys = (char*)st->outs[b].data;
+            op[b].ovals = (char*)st->outs[b].data2;
+        } else {
+            op[b].res = base + off[b].res;
+            op[b].out = base + off[b].out;
+            op[b].okeys = base + off[b].okeys;
+            op[b].ovals = base + off[b].ovals;
+        }
+    }
 
     // ---- results
     r->res.assign(NB, BuilderResult());
@@ -455,19 +496,19 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         br.kind = s.kind;
         br.elem_size = type_size(s.val_type[0]);
         if (s.kind == WELD_MERGER) {
-            br.scalar = base + off[b].res;
+            br.scalar = op[b].res;
         } else if (s.kind == WELD_VECMERGER) {
             br.kind = WELD_VECBUILDER;   // read back like any vector
-            br.vec.ptr = base + off[b].out;
+            br.vec.ptr = op[b].out;
             br.known_len = s.length;
         } else if (s.kind == WELD_VECBUILDER) {
-            br.vec.ptr = base + off[b].out;
+            br.vec.ptr = op[b].out;
             br.known_len = (var.backend[b] == BK_VEC_DIRECT) ? (L.merge_of[b] >= 0 ? n : 0) : -1;
         } else {
             for (int k = 0; k < s.nkeys; ++k) br.key_stride += type_size(s.key_type[k]);
             for (int k = 0; k < s.nvals; ++k) br.val_stride += type_size(s.val_type[k]);
-            br.dict.keys.ptr = base + off[b].okeys;
-            br.dict.values.ptr = base + off[b].ovals;
+            br.dict.keys.ptr = op[b].okeys;
+            br.dict.values.ptr = op[b].ovals;
             br.table.keys = base + off[b].keys;
             br.table.hdr = base + off_ctl + ctl_hdr_off((int)b);
             br.table.slots = off[b].slots;
@@ -492,7 +533,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             case SLOT_COL: v = (uint64_t)(uintptr_t)cols[b].data; break;
             case SLOT_CTL: v = (uint64_t)(uintptr_t)(base + off_ctl); break;
             case SLOT_PARTIAL: v = (uint64_t)(uintptr_t)(base + off[b].part); break;
-            case SLOT_OUT: v = (uint64_t)(uintptr_t)(base + off[b].out); break;
+            case SLOT_OUT: v = (uint64_t)(uintptr_t)op[b].out; break;
             case SLOT_DESC: v = (uint64_t)(uintptr_t)(base + off[b].desc); break;
             case SLOT_LEN: v = (uint64_t)(uintptr_t)(base + off_ctl + ctl_count_off(b)); break;
             case SLOT_DKEYS: v = (uint64_t)(uintptr_t)(base + off[b].keys); break;
@@ -513,7 +554,8 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
 
     // ---- enqueue
     hipError_t h;
-    if (!prior_ctl && (h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    const bool timed = !prior_ctl && !st;
+    if (timed && (h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     // the workspace of the call is cleared by ONE kernel (a dictionary alone has a key column
     // and up to eight value columns; a launch each left the GPU idle for microseconds apiece)
     FillList fills;
@@ -533,10 +575,10 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         } else if (s.kind == WELD_VECMERGER) {
             // the result starts as a copy of the caller's vector (or as identities)
             if (s.init) {
-                h = hipMemcpyAsync(base + off[b].out, s.init, 8 * (size_t)s.length, hipMemcpyDeviceToDevice, stream);
+                h = hipMemcpyAsync(op[b].out, s.init, 8 * (size_t)s.length, hipMemcpyDeviceToDevice, stream);
                 r->kernel_count++;
             } else {
-                h = fill(base + off[b].out, s.length, ident_bits(s.func, s.val_type[0]));
+                h = fill(op[b].out, s.length, ident_bits(s.func, s.val_type[0]));
             }
             if (h != hipSuccess) return hip_err("vecmerger init", h);
         } else if (s.kind == WELD_DICTMERGER) {
@@ -557,7 +599,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         if ((h = launch_fill64(base + off_ctl + ctl_count_off(g.val_vec), 1, (uint64_t)n, stream)) != hipSuccess) return hip_err("fill", h);
         r->kernel_count++;
     }
-    if (!prior_ctl && (h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    if (timed && (h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream);
     if (!e.ok()) return e;
     r->kernel_count++;
@@ -596,7 +638,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         if (h != hipSuccess) return hip_err("dict spill merge", h);
         r->kernel_count++;
     }
-    if (!prior_ctl && (h = hipEventRecord(r->ev3, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    if (timed && (h = hipEventRecord(r->ev3, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     MergerFinish mf;
     memset(&mf, 0, sizeof mf);
     for (size_t b = 0; b < NB; ++b) {
@@ -604,7 +646,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         if (s.kind != WELD_MERGER) continue;
         const int k = mf.n++;
         mf.partial[k] = (const unsigned long long*)(base + off[b].part);
-        mf.result[k] = base + off[b].res;
+        mf.result[k] = op[b].res;
         mf.func[k] = s.func;
         mf.is_f64[k] = s.val_type[0] == WELD_F64;
         mf.elem_size[k] = type_size(s.val_type[0]);
@@ -637,13 +679,13 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         }
         const GroupLink* g = link_of(b);
         h = launch_dict_extract(base + off[b].keys, base + off_ctl + ctl_hdr_off((int)b), off[b].slots, dv, dl, s.capacity,
-                                base + off[b].okeys, base + off[b].ovals, base + off_ctl + ctl_count_off((int)b),
+                                op[b].okeys, op[b].ovals, base + off_ctl + ctl_count_off((int)b),
                                 base + off_ctl + 8, g ? (int*)(base + off[b].slot_pos) : nullptr, stream);
         if (h != hipSuccess) return hip_err("dict extract", h);
         r->kernel_count++;
         if (!g) continue;
         // groupbuilder: group sizes -> offsets, then every compacted pair to its group's vector
-        h = launch_group_offsets(base + off[b].ovals, base + off_ctl + ctl_count_off((int)b), s.capacity,
+        h = launch_group_offsets(op[b].ovals, base + off_ctl + ctl_count_off((int)b), s.capacity,
                                  base + off[b].goffsets, base + off[b].gcursor, stream);
         if (h != hipSuccess) return hip_err("group offsets", h);
         GroupScatter gs;
@@ -651,11 +693,11 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         gs.npairs = (const unsigned long long*)(base + off_ctl + ctl_count_off(g->val_vec));
         gs.nkeys = s.nkeys;
         for (int k = 0; k < s.nkeys; ++k) {
-            gs.key[k] = base + off[g->key_vec[k]].out;
+            gs.key[k] = op[g->key_vec[k]].out;
             gs.key_size[k] = dl.key_size[k];
             gs.key_shift[k] = dl.key_shift[k];
         }
-        gs.value = base + off[g->val_vec].out;
+        gs.value = op[g->val_vec].out;
         gs.value_size = type_size(L.builders[g->val_vec].val_type[0]);
         gs.table_keys = (const unsigned long long*)(base + off[b].keys);
         gs.hdr = (const unsigned int*)(base + off_ctl + ctl_hdr_off((int)b));
@@ -684,7 +726,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         r->kernel_count++;
         BuilderResult& br = r->res[b];
         br.kind = WELD_GROUPBUILDER;
-        br.groups.keys.ptr = base + off[b].okeys;
+        br.groups.keys.ptr = op[b].okeys;
         br.groups.offsets.ptr = base + off[b].goffsets;
         br.groups.values.ptr = base + off[b].gvalues;
         br.elem_size = gs.value_size;
@@ -695,6 +737,19 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     if (prior_ctl) {
         if ((h = launch_or_error(base + off_ctl, prior_ctl, stream)) != hipSuccess) return hip_err("error word", h);
         r->kernel_count++;
+    }
+    if (st) {
+        // no handle, no pinned copy: the error bits and the builders' lengths go to the caller's
+        // device array, written by a kernel behind everything else of the call
+        StaticLengths sl;
+        memset(&sl, 0, sizeof sl);
+        sl.count = (int)user_builders;
+        for (size_t b = 0; b < user_builders; ++b) {
+            const BuilderResult& br = r->res[b];
+            sl.known[b] = br.kind == WELD_MERGER ? 1 : br.kind == WELD_VECBUILDER ? br.known_len : -1;
+        }
+        if ((h = launch_static_status(base + off_ctl, sl, st->status_dev, stream)) != hipSuccess) return hip_err("status", h);
+        return Error();
     }
     if ((h = hipMemcpyAsync(r->host_ctl, base + off_ctl, kCtlBytes, hipMemcpyDeviceToHost, stream)) != hipSuccess)
         return hip_err("hipMemcpyAsync", h);

@@ -251,6 +251,17 @@ struct NestedData {
     ColRef gather[8];
     int64_t gather_len[8] = {0};
 };
+// Where a loop's results and workspace go when the caller supplies the outputs and the workspace is
+// the library's fixed device buffer (weld_fused_for_static): no pool block, no events, no pinned copy.
+struct StaticTarget {
+    char* scratch = nullptr;            // device; the call's control words and workspace
+    size_t scratch_bytes = 0;
+    const weld_out_t* outs = nullptr;   // one per builder, checked by the caller of run_fused_static
+    int64_t* status_dev = nullptr;      // device; 1 + WELD_MAX_BUILDERS words
+};
+// runtime.cpp: the fused loop with such a target.  Uses only a plan (compiled, loaded kernel) that an
+// earlier weld_fused_for call made; WELD_ERR_NOT_READY otherwise.
+Error run_fused_static(const Loop& loop, const ColRef* cols, int64_t n, const weld_conf_t& conf, const StaticTarget& st);
 Error run_nested(const NestedLoop& loop, const NestedData& data, const weld_conf_t& conf, weld_result* r);
 weld_result* new_result(void* stream);   // with pinned control words and events; nullptr on failure
 void destroy_result(weld_result* r);
