@@ -129,31 +129,42 @@ def main():
     # ---- operator-at-a-time GPU mode, same columns (comparison arm)
     if not args.no_unfused:
         for c in names:
-            ts = []
+            ts, busy = [], []
             launches = 0
             for i in range(4):
                 r = wb.fused_for(progs[c], cols[c], mode="unfused").check()
                 if i:
                     ts.append(r.elapsed_ms())
+                    busy.append(r.busy_ms())
                 launches = r.kernel_count()
                 r.free()
+            # unfused_ms: first to last kernel, with the host waits an eager library has between operators (a
+            # filter's length is read back before the next loop is sized); unfused_kernel_sum_ms: the GPU's own
+            # time for the operator loops, without those waits - the ratio that fusion alone accounts for
             per[c]["unfused_ms"] = round(median(ts), 4)
+            per[c]["unfused_kernel_sum_ms"] = round(median(busy), 4)
             per[c]["unfused_launches"] = launches
             per[c]["fused_speedup_over_unfused"] = round(median(ts) / per[c]["call_ms"], 2)
+            per[c]["fused_speedup_over_unfused_kernel_sum"] = round(median(busy) / per[c]["call_ms"], 2)
         wb.lib.weld_pool_trim()
 
-    # ---- attainable read rate on this machine (streaming 16-byte loads)
+    # ---- a streaming-read kernel on this box (16-byte loads, the loops' own tile pattern, nothing else to
+    # do): four launches per bracket so that the launch gap is not in the figure, best of six brackets.
+    # It is a measured lower bound of what the memory system can deliver, not a ceiling: a loop whose
+    # columns keep more bytes in flight can pass it, so `attainable_read_GBps` is the larger of the
+    # probe and the fastest loop of this run.
     probe = torch.empty(1 << 30, dtype=torch.int32, device="cuda")
     probe.fill_(1)
     pts = []
     for _ in range(6):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        wb.probe_read(probe)
+        for _k in range(4):
+            wb.probe_read(probe)
         e1.record()
         torch.cuda.synchronize()
-        pts.append(e0.elapsed_time(e1))
-    read_probe = probe.numel() * 4 / median(pts) / 1e6
+        pts.append(e0.elapsed_time(e1) / 4)
+    read_probe = probe.numel() * 4 / min(pts) / 1e6
     # plain copy of known size (1 GiB read + 1 GiB written): the kernel the HBM counters are scaled by
     dst = torch.empty_like(probe)
     cts = []
@@ -171,17 +182,25 @@ def main():
     dom = max(names, key=lambda c: per[c]["kernel_ms"])
     alg_bytes = (configs.IN_BYTES[dom] + configs.OUT_BYTES[dom]) * rows[dom]
     achieved = alg_bytes / per[dom]["kernel_ms"] / 1e6
-    traffic = None
-    tfile = os.path.join(ROOT, "profiles", "hbm_traffic.txt")     # measured with rocprofv3 --pmc
+    # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/hbm_traffic.txt: config, kernel
+    # name, bytes).  The kernel is named after its own text, so a row only counts for the kernel it was
+    # measured on: after any change to a loop's code the figure is null until the counters are taken again.
+    traffic_of = {}
+    tfile = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if os.path.exists(tfile) and args.scale == 1.0:
         for ln in open(tfile):
             f = ln.split()
-            if len(f) == 2 and f[0] == dom:
-                traffic = int(f[1])
+            if len(f) == 3 and f[0] in per and f[1] == per[f[0]]["kernel"]:
+                traffic_of[f[0]] = int(f[2])
+    attainable = max([read_probe] + [per[c]["input_GBps"] for c in names])
+    for c in names:
+        per[c]["hbm_traffic_bytes"] = traffic_of.get(c)
+        per[c]["in_plus_out_frac_of_hbm_peak"] = round(per[c]["in_plus_out_GBps"] / HBM_PEAK_GBPS, 4)
+        per[c]["in_plus_out_frac_of_attainable_read"] = round(per[c]["in_plus_out_GBps"] / attainable, 4)
     roofline = {"bound": "hbm", "kernel": per[dom]["kernel"], "workload": dom, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": traffic, "read_probe_GBps": round(read_probe, 1),
-                "copy_probe_GBps": round(copy_probe, 1)}
+                "traffic": traffic_of.get(dom), "read_probe_GBps": round(read_probe, 1),
+                "attainable_read_GBps": round(attainable, 1), "copy_probe_GBps": round(copy_probe, 1)}
 
     # ---- the CPU oracle as it stands, on a bounded sample of the same workloads
     cpu = None
@@ -207,17 +226,22 @@ def main():
                "sample": "first rows of each config (" + ", ".join(desc) + "), numpy operator-at-a-time oracle, 1 thread"}
 
     # ---- vecmerger strategies on the count-occurrences program (1e8 32-bit keys, uniform)
+    # (Sec. 7.7 of the paper: local / shared / global copies over the size of the vector; here also LDS copies of
+    # 8192-cell ranges.  The default line carries four sizes, --vecmerger-sweep all ten.)
     sweep = None
-    if args.vecmerger_sweep:
+    if not args.no_nested or args.vecmerger_sweep:
         from workloads import rng
         from workloads.ir import Program
         nk = max(1, int(100_000_000 * args.scale))
         sweep = []
-        for m in (8, 64, 1024, 8192, 32768, 65536, 1 << 18, 1 << 19, 1 << 20, 1 << 24):
+        sizes = (8, 64, 1024, 8192, 32768, 65536, 1 << 18, 1 << 19, 1 << 20, 1 << 24) if args.vecmerger_sweep else (8, 8192, 65536, 1 << 20)
+        for m in sizes:
             keys = rng.uniform_int(6, 0, 0, nk, 0, m - 1, "cuda").to(torch.int32)
             for strat, label in ((1, "local"), (2, "shared"), (4, "shared by range"), (3, "global")):
                 if (strat == 1 and m > 8) or (strat == 2 and m > 16384) or (strat == 4 and not 8192 < m <= 8192 * 64):
                     continue
+                if strat == 3 and m < 8192 and not args.vecmerger_sweep:
+                    continue            # 13-390 ms a run: same-address device atomics, in the long sweep only
                 p = Program(["i32"])
                 p.merge(p.vecmerger("i64", "add", m), [p.const("i64", 1)], keys=[p.un("cast", p.col(0), to="i64")])
                 ts = []

@@ -185,6 +185,10 @@ typedef struct {
     int32_t dict_defer;         /* LDS hash table in a loop that also compacts: 0 = merges that the first
                                    probe does not settle are queued per wavefront and handled 64 at a
                                    time, -1 = every merge walks the whole path where it stands      */
+    int32_t dict_compact;       /* LDS hash table of a dictmerger[K,V,+] whose key provably fits 32 bits and
+                                   whose one value is a constant or a 32-bit integer: 0 = 8-byte cells (32-bit
+                                   key, 32-bit partial sum: twice the slots) and 8-byte queue entries,
+                                   -1 = the general 64-bit cells                                    */
 } weld_tuning_t;
 
 typedef struct {
@@ -339,6 +343,11 @@ weld_status_t weld_result_fetch(weld_result_t* r, int32_t idx, int32_t part, voi
  * on conf.stream around the enqueued work (valid after weld_result_status()). */
 weld_status_t weld_result_elapsed_ms(weld_result_t* r, float* ms);
 
+/* Milliseconds the GPU was busy with the call: in unfused mode the sum, over the operator loops, of the
+ * time between each loop's first and last kernel - without the host waits between the loops (a filter's
+ * length is read back before the next loop is sized); in fused mode the same as weld_result_elapsed_ms. */
+weld_status_t weld_result_busy_ms(weld_result_t* r, float* ms);
+
 /* Same, for the main loop kernel alone (fused mode; -1 if the call ran none). */
 weld_status_t weld_result_kernel_ms(weld_result_t* r, float* ms);
 
@@ -347,6 +356,9 @@ const char* weld_result_kernel_name(const weld_result_t* r);
 
 /* Number of kernels the call launched (1-2 in fused mode, one per operator unfused). */
 int32_t weld_result_kernel_count(const weld_result_t* r);
+
+/* Work-groups of the main loop kernel (fused mode; 0 if the call ran none). */
+int64_t weld_result_grid(const weld_result_t* r);
 
 /* Frees the results and returns workspace to the library's pool (Sec. 4.1 FreeWeldResult).
  * NULL is allowed. */

@@ -76,7 +76,7 @@ class Tuning(C.Structure):
     _fields_ = [("block_threads", C.c_int32), ("units_per_thread", C.c_int32), ("grid_blocks", C.c_int32),
                 ("dict_strategy", C.c_int32), ("lds_dict_slots", C.c_int32), ("spin_limit", C.c_int32),
                 ("vecmerger_strategy", C.c_int32), ("lds_filter_words", C.c_int32), ("dict_spill", C.c_int32),
-                ("merge_loop", C.c_int32), ("dict_defer", C.c_int32)]
+                ("merge_loop", C.c_int32), ("dict_defer", C.c_int32), ("dict_compact", C.c_int32)]
 
 
 class Conf(C.Structure):
@@ -129,12 +129,16 @@ lib.weld_result_fetch.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, 
 lib.weld_result_fetch.restype = C.c_int
 lib.weld_result_elapsed_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
 lib.weld_result_elapsed_ms.restype = C.c_int
+lib.weld_result_busy_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
+lib.weld_result_busy_ms.restype = C.c_int
 lib.weld_result_kernel_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
 lib.weld_result_kernel_ms.restype = C.c_int
 lib.weld_result_kernel_name.argtypes = [C.c_void_p]
 lib.weld_result_kernel_name.restype = C.c_char_p
 lib.weld_result_kernel_count.argtypes = [C.c_void_p]
 lib.weld_result_kernel_count.restype = C.c_int32
+lib.weld_result_grid.argtypes = [C.c_void_p]
+lib.weld_result_grid.restype = C.c_int64
 lib.weld_result_free.argtypes = [C.c_void_p]
 lib.weld_result_free.restype = None
 lib.weld_precompile.argtypes = [C.POINTER(C.c_int32), C.c_int32, C.POINTER(Body), C.POINTER(Builder)]
@@ -321,11 +325,19 @@ class Result:
         lib.weld_result_kernel_ms(self._h, C.byref(ms))
         return ms.value
 
+    def busy_ms(self):
+        ms = C.c_float()
+        lib.weld_result_busy_ms(self._h, C.byref(ms))
+        return ms.value
+
     def kernel_name(self):
         return lib.weld_result_kernel_name(self._h).decode()
 
     def kernel_count(self):
         return lib.weld_result_kernel_count(self._h)
+
+    def grid(self):
+        return lib.weld_result_grid(self._h)
 
     def _fetch_host(self, idx, part, nbytes):
         buf = np.empty(nbytes, dtype=np.uint8)

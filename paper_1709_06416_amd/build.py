@@ -40,9 +40,13 @@ def _run(cmd):
 
 def _embed_prelude():
     src = open(os.path.join(CSRC, "fused_prelude.hip.h")).read()
-    from paper_1709_06416_amd import erf_table
+    from paper_1709_06416_amd import erf_table, logexp_table
     assert src.count("@W_ERF_TABLE@") == 1
     src = src.replace("@W_ERF_TABLE@", erf_table.c_initialiser())
+    for mark, text in (("@W_LOG_TABLE@", logexp_table.log_initialiser()), ("@W_EXP_TABLE@", logexp_table.exp_initialiser()),
+                       ("@W_LOGEXP_CONSTS@", logexp_table.constant_defines())):
+        assert src.count(mark) == 1
+        src = src.replace(mark, text)
     assert ')WELDPRE"' not in src
     out = os.path.join(BUILD, "prelude_embed.cpp")
     # split into chunks: string literals have a length limit in some compilers

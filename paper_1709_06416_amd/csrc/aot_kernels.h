@@ -116,6 +116,9 @@ struct SpillMerge {
     unsigned long long* overflow;        // entries (1 + nvals words) that found no room in their slice
     unsigned int* overflow_count;        // zero on entry
     long long overflow_cap;
+    // 0: entries are 1 + nvals words; 1 / 2: one word per entry, low half = the key (zero- / sign-extended
+    // to the packed 64-bit key), high half = the value, a signed 32-bit partial sum (nvals == 1, func = add)
+    int compact;
 };
 hipError_t launch_dict_spill_merge(const SpillMerge& a, int nvals, hipStream_t stream);
 // Dictionaries of millions of keys: partition p of the queues holds the keys whose home slot lies in

@@ -185,8 +185,8 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
                 else o.f("(%s)t%d", T, q.a);
                 break;
             }
-            case WELD_OP_EXP: o.f("exp(t%d)", q.a); break;
-            case WELD_OP_LOG: o.f("log(t%d)", q.a); break;
+            case WELD_OP_EXP: o.f("w_exp(t%d)", q.a); break;
+            case WELD_OP_LOG: o.f("w_log(t%d)", q.a); break;
             case WELD_OP_SQRT: o.f("sqrt(t%d)", q.a); break;
             case WELD_OP_ERF: o.f("w_erf(t%d)", q.a); break;
             case WELD_OP_ADD:
@@ -264,6 +264,88 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
     o.f("}\n\n");
 }
 
+// Static value ranges of the integer SSA values (interval arithmetic over the body): what a
+// `mod` by a constant, a cast from a narrower type or a constant can be.  Used to hold 64-bit
+// values that provably fit 32 bits in one register, and to give such keys compact cells.
+struct IRange {
+    __int128 lo, hi;
+    bool fits32() const { return lo >= -((__int128)1 << 31) && hi <= ((__int128)1 << 31) - 1; }
+};
+IRange type_range(int t) {
+    const int bits = t == WELD_BOOL ? 1 : 8 * type_size(t);
+    if (t == WELD_BOOL) return IRange{0, 1};
+    return IRange{-((__int128)1 << (bits - 1)), ((__int128)1 << (bits - 1)) - 1};
+}
+std::vector<IRange> static_ranges(const Loop& L) {
+    std::vector<IRange> r(L.ops.size(), IRange{0, 0});
+    for (size_t i = 0; i < L.ops.size(); ++i) {
+        const weld_op_t& q = L.ops[i];
+        if (q.type == WELD_F64) continue;
+        const IRange full = type_range(q.type);
+        IRange out = full;
+        auto clamp = [&](__int128 lo, __int128 hi) {       // a result outside the type wraps: anything then
+            if (lo >= full.lo && hi <= full.hi) out = IRange{lo, hi};
+        };
+        auto is_int = [&](int x) { return x >= 0 && L.ops[x].type != WELD_F64; };
+        switch (q.opcode) {
+            case WELD_OP_CONST: clamp(q.imm.i64, q.imm.i64); break;
+            case WELD_OP_INDEX: out = IRange{0, full.hi}; break;
+            case WELD_OP_CAST: if (is_int(q.a)) clamp(r[q.a].lo, r[q.a].hi); break;
+            case WELD_OP_NEG: clamp(-r[q.a].hi, -r[q.a].lo); break;
+            case WELD_OP_ADD: clamp(r[q.a].lo + r[q.b].lo, r[q.a].hi + r[q.b].hi); break;
+            case WELD_OP_SUB: clamp(r[q.a].lo - r[q.b].hi, r[q.a].hi - r[q.b].lo); break;
+            case WELD_OP_MUL: {
+                const __int128 c[4] = {r[q.a].lo * r[q.b].lo, r[q.a].lo * r[q.b].hi, r[q.a].hi * r[q.b].lo, r[q.a].hi * r[q.b].hi};
+                clamp(*std::min_element(c, c + 4), *std::max_element(c, c + 4));
+                break;
+            }
+            case WELD_OP_MOD: case WELD_OP_DIV: {
+                const weld_op_t& d = L.ops[q.b];
+                if (d.opcode != WELD_OP_CONST || d.imm.i64 == 0 || d.imm.i64 == INT64_MIN) break;
+                const __int128 m = d.imm.i64 < 0 ? -(__int128)d.imm.i64 : (__int128)d.imm.i64;
+                if (q.opcode == WELD_OP_MOD) {      // truncating: the sign of the dividend, magnitude below |divisor|
+                    clamp(r[q.a].lo >= 0 ? 0 : -(m - 1), r[q.a].hi <= 0 ? 0 : m - 1);
+                } else if (d.imm.i64 > 0) {
+                    clamp(r[q.a].lo / m, r[q.a].hi / m);
+                }
+                break;
+            }
+            case WELD_OP_MIN: clamp(std::min(r[q.a].lo, r[q.b].lo), std::min(r[q.a].hi, r[q.b].hi)); break;
+            case WELD_OP_MAX: clamp(std::max(r[q.a].lo, r[q.b].lo), std::max(r[q.a].hi, r[q.b].hi)); break;
+            case WELD_OP_SELECT: clamp(std::min(r[q.b].lo, r[q.c].lo), std::max(r[q.b].hi, r[q.c].hi)); break;
+            default: break;     // columns, lookups, compares (bool: full range already)
+        }
+        r[i] = out;
+    }
+    return r;
+}
+
+// Whether dictmerger b (realised as an LDS table) can keep compact cells; *sext: the packed key is the
+// sign extension of its low half; *guard: |constant| merged per row when the value is a 64-bit constant.
+bool compact_eligible(const Loop& L, size_t b, bool* sext, long long* guard) {
+    const weld_builder_spec_t& s = L.builders[b];
+    const int m = L.merge_of[b];
+    if (s.kind != WELD_DICTMERGER || m < 0 || s.nvals != 1 || s.func != WELD_FUNC_ADD || s.val_type[0] == WELD_F64) return false;
+    const weld_merge_t& g = L.merges[m];
+    const std::vector<IRange> r = static_ranges(L);
+    int bytes = 0;
+    for (int k = 0; k < s.nkeys; ++k) bytes += type_size(s.key_type[k]);
+    *sext = false;
+    if (bytes > 4) {
+        if (s.nkeys != 1 || !r[g.key[0]].fits32()) return false;
+        *sext = true;
+    }
+    *guard = 0;
+    if (s.val_type[0] == WELD_I64) {      // a 32-bit partial sum must stay exact: constants only, with a flush before 2^31
+        const weld_op_t& v = L.ops[g.val[0]];
+        if (v.opcode != WELD_OP_CONST) return false;
+        const long long c = v.imm.i64 < 0 ? -v.imm.i64 : v.imm.i64;
+        if (c > (1 << 10)) return false;
+        *guard = c > 0 ? c : 1;
+    }
+    return true;
+}
+
 bool body_uses(const Loop& L, int opcode) {
     for (const weld_op_t& q : L.ops)
         if (q.opcode == opcode) return true;
@@ -337,6 +419,19 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
                            : strat == 2 ? BK_DICT_LDS : BK_DICT_GLOBAL;
         }
     }
+    // a single LDS dictionary that counts, or sums 32-bit integers, under a key of 32 bits: compact cells
+    {
+        int ndl = 0, which = -1;
+        for (size_t b = 0; b < L.builders.size(); ++b)
+            if (var.backend[b] == BK_DICT_LDS) { ++ndl; which = (int)b; }
+        bool sext = false;
+        long long guard = 0;
+        if (ndl == 1 && tune.dict_compact >= 0 && compact_eligible(L, (size_t)which, &sext, &guard)) {
+            var.compact = which;
+            var.compact_sext = sext;
+            var.compact_guard = guard;
+        }
+    }
     // every LDS dictionary of the loop gets the same slot count; the LDS budget (64 KiB,
     // 128 KiB when some dictionary has more keys than 64 KiB hold) is shared among them
     bool big_dict = false;
@@ -346,7 +441,7 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
         for (size_t b = 0; b < L.builders.size(); ++b)
             if (var.backend[b] == BK_DICT_LDS) {
                 ++ndl;
-                per_slot += 8 * (1 + L.builders[b].nvals);
+                per_slot += var.compact == (int)b ? 8 : 8 * (1 + L.builders[b].nvals);
                 if (L.builders[b].capacity > max_cap) max_cap = L.builders[b].capacity;
             }
         if (ndl > 0) {
@@ -390,6 +485,9 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
             }
         }
     }
+    if (var.spill_slices) var.compact = -1;      // the slice-building kernel reads full entries
+    if (var.compact >= 0) var.door_words = 0;    // measured on the zip-code loop with 16384 compact slots: 11.7 % of the
+                                                 // merges miss the table with the filter, 10.0 % without
     (void)any;
     var.v = widest >= 8 ? 2 : 4;
     // Look-back kernels pay one same-address device atomic (about 12 ns, serialised) and
@@ -399,8 +497,10 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
         var.u = tune.units_per_thread > 0 ? tune.units_per_thread : 16 / var.v;
         var.block = tune.block_threads > 0 ? tune.block_threads : 1024;
     } else if (var.ticketed) {
+        // (measured on the zip-code compaction, 1e8 rows: 0.42 ms with 256 threads, 0.36 with 512, 0.32 with 1024:
+        // the per-tile costs - ticket, look-back, three barriers - are paid once per 16384 rows)
         var.u = tune.units_per_thread > 0 ? tune.units_per_thread : 16 / var.v;
-        var.block = tune.block_threads > 0 ? tune.block_threads : 512;
+        var.block = tune.block_threads > 0 ? tune.block_threads : 1024;
     } else {
         // register-slot dictionaries hold capacity x fields accumulators per lane: fewer loads in
         // flight leave room for a third wavefront per SIMD (C4: 1.22 -> 1.17 ms)
@@ -422,9 +522,9 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
     if (var.lds_slots > 0) {
         int per_slot = 0;
         for (size_t b = 0; b < L.builders.size(); ++b)
-            if (var.backend[b] == BK_DICT_LDS) per_slot += 8 * (1 + L.builders[b].nvals);
+            if (var.backend[b] == BK_DICT_LDS) per_slot += var.compact == (int)b ? 8 : 8 * (1 + L.builders[b].nvals);
         int other = (var.ticketed ? 8 * var.block * var.v : 0) + 4 * var.door_words + (var.spill ? 4 * var.spill_parts : 0) +
-                    (body_uses(L, WELD_OP_ERF) ? 7680 : 0) + 2048;
+                    (body_uses(L, WELD_OP_ERF) ? 7680 : 0) + (body_uses(L, WELD_OP_LOG) ? 2184 : 0) + (body_uses(L, WELD_OP_EXP) ? 1024 : 0) + 2048;
         for (size_t b = 0; b < L.builders.size(); ++b) {
             if (var.backend[b] == BK_VECM_LDS) other += 8 * (var.ranges > 1 ? 8192 : (int)L.builders[b].length);
             if (var.backend[b] == BK_DICT_REG || var.backend[b] == BK_DICT_LANE) other += 8 * (int)L.builders[b].capacity;
@@ -476,11 +576,15 @@ Generated generate(const Loop& L, const Variant& var) {
     Generated G;
     Out o;
     const size_t NB = L.builders.size();
+    const std::vector<IRange> ranges = static_ranges(L);
     o.f("// generated: fused for-loop kernel, %d columns, %zu builders\n", L.ncols, NB);
     o.f("#define W_BLOCK %d\n#define W_V %d\n#define W_U %d\n#define W_ALIGNED %d\n", var.block, var.v, var.u, var.aligned);
     if (var.spill_slices) o.f("#define W_SPILL_PARTS %d\n#define W_SPILL_BY_SLOT 1\n", var.spill_parts);
     const bool uses_erf = body_uses(L, WELD_OP_ERF);
     if (uses_erf) o.f("#define W_USE_ERF 1\n");
+    const bool uses_log = body_uses(L, WELD_OP_LOG), uses_exp = body_uses(L, WELD_OP_EXP);
+    if (uses_log) o.f("#define W_USE_LOG 1\n");
+    if (uses_exp) o.f("#define W_USE_EXP 1\n");
     o.s += kPreludeSource;
     o.f("\n");
 
@@ -550,7 +654,11 @@ Generated generate(const Loop& L, const Variant& var) {
     auto emit_dict_slow = [&](Out& o, size_t b, const std::vector<std::string>& vals) {
         const weld_builder_spec_t& s = L.builders[b];
         const int F = s.func;
-        if (var.backend[b] == BK_DICT_LDS) {
+        const bool compact = var.compact == (int)b;
+        if (compact) {
+            o.f("    const int sl = w_lds_slot32(d%zu_ck, %d, kb, 3); \\\n", b, var.lds_slots);
+            o.f("    if (sl >= 0) { \\\n      w_lds_add32(d%zu_cv, sl, (i64)%s); \\\n    } else { \\\n", b, vals[0].c_str());
+        } else if (var.backend[b] == BK_DICT_LDS) {
             if (var.door_words > 0)
                 o.f("    const int sl = w_lds_slot_filtered(d%zu_lk, %d, kb, 3, d%zu_door, %d); \\\n", b, var.lds_slots, b, var.door_words);
             else
@@ -564,11 +672,15 @@ Generated generate(const Loop& L, const Variant& var) {
         }
         const bool spill = var.backend[b] == BK_DICT_LDS && var.spill;
         if (spill) {
-            o.f("      const i64 ei = w_spill_index(d%zu_qn, a.b%zu_qcap, %d, kb); \\\n", b, b, 1 + s.nvals);
+            o.f("      const i64 ei = w_spill_index(d%zu_qn, a.b%zu_qcap, %d, kb); \\\n", b, b, compact ? 1 : 1 + s.nvals);
             o.f("      if (ei >= 0) { \\\n");
             std::vector<std::string> words;
-            words.push_back("kb");
-            for (int k = 0; k < s.nvals; ++k) words.push_back("w_bits(" + vals[k] + ")");
+            if (compact) {
+                words.push_back("w_compact_entry(kb, (i64)" + vals[0] + ")");
+            } else {
+                words.push_back("kb");
+                for (int k = 0; k < s.nvals; ++k) words.push_back("w_bits(" + vals[k] + ")");
+            }
             emit_log_stores(o, b, words, " \\");
             o.f("      } else { \\\n");
             // (tells the kernel that builds the table slice by slice that the table is no longer empty)
@@ -673,10 +785,16 @@ Generated generate(const Loop& L, const Variant& var) {
                 const weld_merge_t& g = L.merges[L.merge_of[b]];
                 o.f("  { \\\n    const u64 kb = %s; \\\n    bool miss = false; \\\n", pack_key(s, b, "(o)").c_str());
                 o.f("    if ((o).p%zu) { \\\n      miss = true; \\\n      if (kb != W_EMPTY_KEY) { \\\n", b);
+                if (var.compact == (int)b) {
+                    o.f("        const int s0 = (int)w_hash_slot32((u32)kb, %du); \\\n", var.lds_slots);
+                    o.f("        if ((u32)kb != W_EMPTY_KEY32 && __hip_atomic_load(d%zu_ck + s0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == (u32)kb) { \\\n          miss = false; \\\n", b);
+                    o.f("          w_lds_add32(d%zu_cv, s0, (i64)%s); \\\n", b, vals[0].c_str());
+                } else {
                 o.f("        const int s0 = (int)w_hash_slot(kb, %du); \\\n", var.lds_slots);
                 o.f("        if (__hip_atomic_load(d%zu_lk + s0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == kb) { \\\n          miss = false; \\\n", b);
                 for (int k = 0; k < s.nvals; ++k)
                     o.f("          w_atomic<%d>(d%zu_lv%d + s0, %s, 0); \\\n", F, b, k, vals[k].c_str());
+                }
                 o.f("        } \\\n      } \\\n    } \\\n");
                 o.f("    const u64 mb = w_ballot(miss); \\\n    if (mb) { \\\n      const int add = __popcll(mb); \\\n");
                 o.f("      if (dq_n + add > %d) WELD_DRAIN(); \\\n", var.defer_cap);
@@ -694,9 +812,46 @@ Generated generate(const Loop& L, const Variant& var) {
     o.f("} while (0)\n\n");
     };
     emit_merge_macro("WELD_MERGE", 0);
+    // The deferred dictionary as the loop's only builder in memory: the first probes of all rows a lane
+    // holds are issued together (one LDS latency per tile instead of one per row), then a loop settles
+    // the hits and queues the rest.
+    bool probe_ahead = false;
+    if (var.merge_loop && var.defer_builder >= 0) {
+        int in_mem = 0;
+        for (size_t b = 0; b < NB; ++b)
+            if (L.merge_of[b] >= 0 && merges_in_memory(var.backend[b])) ++in_mem;
+        probe_ahead = in_mem == 1;
+    }
     if (var.merge_loop) {
         emit_merge_macro("WELD_MERGE_REG", 1);
         emit_merge_macro("WELD_MERGE_MEM", 2);
+    }
+    if (probe_ahead) {
+        const size_t b = (size_t)var.defer_builder;
+        const weld_builder_spec_t& sb = L.builders[b];
+        const weld_merge_t& g = L.merges[L.merge_of[b]];
+        // WELD_MERGE_HIT: settles row `o` if the key word `cur` read at slot `s0` is its key; sets `miss` otherwise
+        o.f("#define WELD_MERGE_HIT(o, s0, cur, miss) do { \\\n  const u64 kb = %s; \\\n  (miss) = (o).p%zu; \\\n", pack_key(sb, b, "(o)").c_str(), b);
+        if (var.compact == (int)b) {
+            o.f("  if ((o).p%zu && (u32)kb != W_EMPTY_KEY32 && (cur) == (u32)kb) { \\\n    (miss) = false; \\\n", b);
+            o.f("    w_lds_add32(d%zu_cv, (s0), (i64)(o).v%zu_0); \\\n  } \\\n} while (0)\n\n", b, b);
+        } else {
+            o.f("  if ((o).p%zu && kb != W_EMPTY_KEY && (cur) == kb) { \\\n    (miss) = false; \\\n", b);
+            for (int k = 0; k < sb.nvals; ++k)
+                o.f("    w_atomic<%d>(d%zu_lv%d + (s0), (%s)(o).v%zu_%d, 0); \\\n", sb.func, b, k, acc_ctype(sb.val_type[k]), b, k);
+            o.f("  } \\\n} while (0)\n\n");
+        }
+        // WELD_MERGE_QUEUE: appends the rows of the wavefront with `miss` set to its queue (drained when full)
+        o.f("#define WELD_MERGE_QUEUE(o, miss) do { \\\n  const u64 mb = w_ballot(miss); \\\n  if (mb) { \\\n    const int add = __popcll(mb); \\\n");
+        o.f("    if (dq_n + add > %d) WELD_DRAIN(); \\\n", var.defer_cap);
+        o.f("    if (miss) { \\\n      const int e = dq_n + w_rank_below(mb); \\\n      dq[e] = %s; \\\n", pack_key(sb, b, "(o)").c_str());
+        int w = 1;
+        for (int k = 0; k < sb.nvals; ++k) {
+            if (L.ops[g.val[k]].opcode == WELD_OP_CONST) continue;
+            o.f("      dq[%d + e] = w_bits((%s)(o).v%zu_%d); \\\n", var.defer_cap * w, acc_ctype(sb.val_type[k]), b, k);
+            ++w;
+        }
+        o.f("    } \\\n    dq_n += add; \\\n  } \\\n} while (0)\n\n");
     }
 
     // ------------------------------------------------------------ kernel
@@ -709,6 +864,14 @@ Generated generate(const Loop& L, const Variant& var) {
     if (uses_erf) {
         o.f("  w_erf_init();\n");
         lds += 8 * 960;
+    }
+    if (uses_log) {
+        o.f("  w_log_init();\n");
+        lds += 8 * 273;
+    }
+    if (uses_exp) {
+        o.f("  w_exp_init();\n");
+        lds += 8 * 128;
     }
     if (var.ticketed) {
         o.f("  __shared__ i64 s_tile;\n  __shared__ i64 s_cnt[%d][W_WAVES];\n  __shared__ i64 s_pfx[%d];\n", ncompact, ncompact);
@@ -751,9 +914,15 @@ Generated generate(const Loop& L, const Variant& var) {
             }
             need_sync = true;
         } else if (var.backend[b] == BK_DICT_LDS) {
-            o.f("  __shared__ u64 d%zu_lk[%d];\n", b, var.lds_slots);
-            lds += 8 * var.lds_slots * (1 + s.nvals);
-            for (int k = 0; k < s.nvals; ++k) o.f("  __shared__ %s d%zu_lv%d[%d];\n", acc_ctype(s.val_type[k]), b, k, var.lds_slots);
+            const bool compact = var.compact == (int)b;
+            if (compact) {
+                o.f("  __shared__ u32 d%zu_ck[%d];\n  __shared__ u32 d%zu_cv[%d];\n", b, var.lds_slots, b, var.lds_slots);
+                lds += 8 * var.lds_slots;
+            } else {
+                o.f("  __shared__ u64 d%zu_lk[%d];\n", b, var.lds_slots);
+                lds += 8 * var.lds_slots * (1 + s.nvals);
+                for (int k = 0; k < s.nvals; ++k) o.f("  __shared__ %s d%zu_lv%d[%d];\n", acc_ctype(s.val_type[k]), b, k, var.lds_slots);
+            }
             if (var.door_words > 0) {
                 o.f("  __shared__ u32 d%zu_door[%d];\n  for (int q = threadIdx.x; q < %d; q += W_BLOCK) d%zu_door[q] = 0;\n", b, var.door_words, var.door_words, b);
                 lds += 4 * var.door_words;
@@ -762,13 +931,43 @@ Generated generate(const Loop& L, const Variant& var) {
                 o.f("  __shared__ u32 d%zu_qn[W_SPILL_PARTS];\n  for (int q = threadIdx.x; q < W_SPILL_PARTS; q += W_BLOCK) d%zu_qn[q] = 0;\n", b, b);
                 lds += 4 * var.spill_parts;
             }
+            if (compact) {
+                o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) {\n    d%zu_ck[q] = W_EMPTY_KEY32;\n    d%zu_cv[q] = 0;\n  }\n", var.lds_slots, b, b);
+            } else {
             o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) {\n    d%zu_lk[q] = W_EMPTY_KEY;\n", var.lds_slots, b);
             for (int k = 0; k < s.nvals; ++k) o.f("    d%zu_lv%d[q] = %s;\n", b, k, ident_expr(s.func, s.val_type[k]).c_str());
             o.f("  }\n");
+            }
             need_sync = true;
         }
     }
     if (need_sync) o.f("  __syncthreads();\n");
+    if (var.compact >= 0) {
+        // The compact table's contents leave through the same road as its misses (queue entry, else the
+        // global table).  Called by the whole work-group: at the end, and - when the merged value is a
+        // 64-bit constant - before a 32-bit partial sum could pass 2^31 (the keys stay, the sums restart).
+        const size_t b = (size_t)var.compact;
+        o.f("  i64 wg_rows = 0;\n  (void)wg_rows;\n");
+        o.f("  auto flush_d%zu = [&]() {\n    __syncthreads();\n", b);
+        o.f("    for (int q = threadIdx.x; q < %d; q += W_BLOCK) {\n      const u32 k32 = d%zu_ck[q];\n      if (k32 == W_EMPTY_KEY32) continue;\n", var.lds_slots, b);
+        o.f("      const u64 kb = %s;\n", var.compact_sext ? "(u64)(i64)(int)k32" : "(u64)k32");
+        o.f("      const i64 val = (i64)(int)d%zu_cv[q];\n      d%zu_cv[q] = 0;\n", b, b);
+        if (var.spill) {
+            o.f("      const i64 ei = w_spill_index(d%zu_qn, a.b%zu_qcap, 1, kb);\n", b, b);
+            o.f("      if (ei >= 0) {\n        w_gstore1(a.b%zu_log + ei, w_compact_entry(kb, val));\n        continue;\n      }\n", b);
+            if (var.spill_slices) o.f("      __hip_atomic_store(a.b%zu_hdr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n", b);
+        }
+        o.f("      const i64 g = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, kb, errp);\n", b, b, b);
+        o.f("      if (g >= 0) w_atomic<0>(a.b%zu_v0 + g, val, 1);\n    }\n    __syncthreads();\n  };\n", b);
+    }
+    // after each tile: flush the compact table before a partial sum could overflow
+    std::string guard_text;
+    if (var.compact >= 0 && var.compact_guard > 0) {
+        char buf[256];
+        snprintf(buf, sizeof buf, "    wg_rows += W_TILE;\n    if ((wg_rows + W_TILE) * %lldll >= (1ll << 31)) { flush_d%d(); wg_rows = 0; }\n",
+                 var.compact_guard, var.compact);
+        guard_text = buf;
+    }
 
     // row evaluation call text
     auto row_call = [&](const char* idx, const char* fmt_col, const char* dst, bool together) {
@@ -819,7 +1018,7 @@ Generated generate(const Loop& L, const Variant& var) {
         for (size_t b = 0; b < NB; ++b)
             if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0)
                 o.f("      w_store<%s, W_V>(a.b%zu_out + r0 + u * W_UNIT, y%zu);\n", stype(L.builders[b].val_type[0]), b, b);
-        o.f("    }\n  }\n");
+        o.f("    }\n%s  }\n", guard_text.c_str());
         // tail rows, one per thread
         if (var.ranges > 1)
             o.f("  for (i64 i = nfull * W_TILE + (i64)member * W_BLOCK + threadIdx.x; i < a.n; i += (i64)members * W_BLOCK) {\n");
@@ -884,7 +1083,11 @@ Generated generate(const Loop& L, const Variant& var) {
             // is gathered into vectors (one per IR value) and bit masks (one per predicate) of
             // tile scope; the row structs die here, and a value used twice is held once.
             std::vector<std::string> gather, scatter;     // statements filling the vectors / the row of one iteration
-            auto vec_elem = [](int t) { return t == WELD_F64 ? "double" : t == WELD_I64 ? "i64" : "int"; };
+            // (a 64-bit integer that provably fits 32 bits is held in one register)
+            auto vec_elem = [&](int op) {
+                const int t = L.ops[op].type;
+                return t == WELD_F64 ? "double" : (t == WELD_I64 && !ranges[op].fits32()) ? "i64" : "int";
+            };
             char buf[256];
             Out decl;
             for (size_t b = 0; b < NB; ++b) {
@@ -915,8 +1118,8 @@ Generated generate(const Loop& L, const Variant& var) {
                     }
                     if (std::find(seen_op.begin(), seen_op.end(), op) == seen_op.end()) {
                         seen_op.push_back(op);
-                        decl.f("    typedef %s mt%d_t __attribute__((ext_vector_type(W_U * W_V)));\n    mt%d_t mt%d;\n", vec_elem(L.ops[op].type), op, op, op);
-                        snprintf(buf, sizeof buf, "mt%d[u * W_V + k] = (%s)o[u][k].%s%zu_%d;", op, vec_elem(L.ops[op].type), fn, b, fi);
+                        decl.f("    typedef %s mt%d_t __attribute__((ext_vector_type(W_U * W_V)));\n    mt%d_t mt%d;\n", vec_elem(op), op, op, op);
+                        snprintf(buf, sizeof buf, "mt%d[u * W_V + k] = (%s)o[u][k].%s%zu_%d;", op, vec_elem(op), fn, b, fi);
                         gather.push_back(buf);
                     }
                     if (mem) {
@@ -931,9 +1134,31 @@ Generated generate(const Loop& L, const Variant& var) {
             gather_text.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
             for (const std::string& g : gather) gather_text.f("        %s\n", g.c_str());
             gather_text.f("      }\n");
-            mm.f("    _Pragma(\"unroll 1\") for (int j = 0; j < W_U * W_V; ++j) {\n      RowOut r;\n");
-            for (const std::string& g : scatter) mm.f("      %s\n", g.c_str());
-            mm.f("      WELD_MERGE_MEM(r);\n    }\n");
+            if (probe_ahead) {
+                const size_t db = (size_t)var.defer_builder;
+                const bool compact = var.compact == (int)db;
+                mm.f("    typedef int fs_t __attribute__((ext_vector_type(W_U * W_V)));\n    fs_t fs;\n");
+                mm.f("    typedef %s fc_t __attribute__((ext_vector_type(W_U * W_V)));\n    fc_t fc;\n", compact ? "u32" : "u64");
+                mm.f("    _Pragma(\"unroll\") for (int j = 0; j < W_U * W_V; ++j) {\n      RowOut r;\n");
+                for (const std::string& g : scatter) mm.f("      %s\n", g.c_str());
+                mm.f("      const u64 kb = %s;\n", pack_key(L.builders[db], db, "r").c_str());
+                if (compact)
+                    mm.f("      fs[j] = (int)w_hash_slot32((u32)kb, %du);\n      fc[j] = __hip_atomic_load(d%zu_ck + fs[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);\n    }\n", var.lds_slots, db);
+                else
+                    mm.f("      fs[j] = (int)w_hash_slot(kb, %du);\n      fc[j] = __hip_atomic_load(d%zu_lk + fs[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);\n    }\n", var.lds_slots, db);
+                // hits settle here, straight-line; what is left is a bit per row
+                mm.f("    u32 miss_bits = 0;\n");
+                mm.f("    _Pragma(\"unroll\") for (int j = 0; j < W_U * W_V; ++j) {\n      RowOut r;\n");
+                for (const std::string& g : scatter) mm.f("      %s\n", g.c_str());
+                mm.f("      bool miss;\n      WELD_MERGE_HIT(r, fs[j], fc[j], miss);\n      miss_bits |= (miss ? 1u : 0u) << j;\n    }\n");
+                mm.f("    _Pragma(\"unroll 1\") for (int j = 0; j < W_U * W_V; ++j) {\n      RowOut r;\n");
+                for (const std::string& g : scatter) mm.f("      %s\n", g.c_str());
+                mm.f("      const bool miss = (miss_bits >> j) & 1u;\n      WELD_MERGE_QUEUE(r, miss);\n    }\n");
+            } else {
+                mm.f("    _Pragma(\"unroll 1\") for (int j = 0; j < W_U * W_V; ++j) {\n      RowOut r;\n");
+                for (const std::string& g : scatter) mm.f("      %s\n", g.c_str());
+                mm.f("      WELD_MERGE_MEM(r);\n    }\n");
+            }
             if (var.defer_builder >= 0) mm.f("    WELD_DRAIN();\n");
         }
         // direct vecbuilders inside a ticketed kernel
@@ -942,7 +1167,7 @@ Generated generate(const Loop& L, const Variant& var) {
                 o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
                 o.f("        const i64 i = r0 + u * W_UNIT + k;\n        if (i < a.n) a.b%zu_out[i] = o[u][k].v%zu_0;\n      }\n", b, b);
             }
-        o.f("%s", gather_text.s.c_str());
+        o.s += gather_text.s;
         // ranks of the selected rows inside this wavefront's run, per compacting builder
         int j = 0;
         for (size_t b = 0; b < NB; ++b) {
@@ -950,10 +1175,9 @@ Generated generate(const Loop& L, const Variant& var) {
             // per load unit: how many rows the wavefront selected and where its run starts; the rank
             // of a row inside the run is recomputed when the values are staged (a few instructions,
             // cheaper than holding sixteen ranks per lane through the merge phase)
-            o.f("    int uo%zu[W_U], uc%zu[W_U];\n    {\n      int wtot = 0;\n", b, b);
-            o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n        int utot = 0;\n");
-            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) utot += __popcll(w_ballot(%s));\n", sel_expr(b).c_str());
-            o.f("        uo%zu[u] = wtot;\n        uc%zu[u] = utot;\n        wtot += utot;\n      }\n", b, b);
+            o.f("    {\n      int wtot = 0;\n");
+            o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n");
+            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) wtot += __popcll(w_ballot(%s));\n", sel_expr(b).c_str());
             o.f("      if (lane == 0) s_cnt[%d][wave] = wtot;\n    }\n", j);
             ++j;
         }
@@ -968,8 +1192,15 @@ Generated generate(const Loop& L, const Variant& var) {
             ++j;
         }
         o.f("    }\n");
+        // The predicate masks are redefined opaquely at the phase boundaries: otherwise the compiler
+        // extracts every row's bit once, up front, and carries sixteen registers of single bits
+        // through all phases (spilling them where the merge code needs the room).
+        std::string opaque;
+        for (int pr : seen_pred) opaque += "    asm volatile(\"\" : \"+v\"(mp" + std::to_string(pr + 1) + "));\n";
+        o.s += opaque;
         // while the first wavefront waits for the tiles before this one, the others merge
-        o.f("%s", mm.s.c_str());
+        o.s += mm.s;
+        o.s += opaque;
         o.f("    __syncthreads();\n");
         j = 0;
         for (size_t b = 0; b < NB; ++b) {
@@ -979,17 +1210,23 @@ Generated generate(const Loop& L, const Variant& var) {
             // out as one dense run per instruction (lane l writes elements l, l+64, ...), so HBM
             // sees full lines instead of scattered 8-byte pieces.
             const char* ST = stype(L.builders[b].val_type[0]);
-            o.f("      %s* const stg = (%s*)(s_stage + wave * W_UNIT);\n", ST, ST);
+            // (a 64-bit value that provably fits 32 bits is staged in 4 bytes and widened at the store)
+            const int vop = L.merges[L.merge_of[b]].val[0];
+            const char* SG = (gathered && L.builders[b].val_type[0] == WELD_I64 && ranges[vop].fits32()) ? "int" : ST;
+            o.f("      %s* const stg = (%s*)(s_stage + wave * W_UNIT);\n", SG, SG);
+            // (how many rows of each load unit are selected is counted again here: a few scalar
+            // instructions, cheaper than holding the counts of every unit through the merge phase)
+            o.f("      int run = 0;\n");
             o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
             o.f("        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\");\n");
-            o.f("        int rank = 0;\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) rank += w_rank_below(w_ballot(%s));\n", sel_expr(b).c_str());
-            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k)\n          if (%s) stg[rank++] = (%s)%s;\n", sel_expr(b).c_str(), ST, val_expr(b).c_str());
+            o.f("        int rank = 0, ucnt = 0;\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n          const u64 bal = w_ballot(%s);\n          rank += w_rank_below(bal);\n          ucnt += __popcll(bal);\n        }\n", sel_expr(b).c_str());
+            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k)\n          if (%s) stg[rank++] = (%s)%s;\n", sel_expr(b).c_str(), SG, val_expr(b).c_str());
             o.f("        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\");\n");
             o.f("        _Pragma(\"unroll\") for (int q = 0; q < W_V; ++q) {\n          const int e = q * 64 + lane;\n");
-            o.f("          if (e < uc%zu[u]) __builtin_nontemporal_store(stg[e], a.b%zu_out + base + uo%zu[u] + e);\n        }\n      }\n    }\n", b, b, b);
+            o.f("          if (e < ucnt) __builtin_nontemporal_store((%s)stg[e], a.b%zu_out + base + run + e);\n        }\n        run += ucnt;\n      }\n    }\n", ST, b);
             ++j;
         }
-        o.f("  }\n");
+        o.f("%s  }\n", guard_text.c_str());
     }
 
     // ------------------------------------------------------------ builder results
@@ -1029,6 +1266,12 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("      if (threadIdx.x == 0) {\n        const i64 g = w_table_slot(a.b%zu_keys, a.b%zu_hdr, a.b%zu_slots, kb, errp);\n        if (g >= 0) {\n", b, b, b);
             for (int k = 0; k < s.nvals; ++k) o.f("          w_atomic<%d>(a.b%zu_v%d + g, r%d, 1);\n", s.func, b, k, k);
             o.f("        }\n      }\n    }\n  }\n");
+        } else if (var.backend[b] == BK_DICT_LDS && var.compact == (int)b) {
+            o.f("  flush_d%zu();\n", b);
+            if (var.spill) {
+                o.f("  for (int q = threadIdx.x; q < W_SPILL_PARTS; q += W_BLOCK)\n");
+                o.f("    a.b%zu_qcnt[(u64)blockIdx.x * W_SPILL_PARTS + q] = d%zu_qn[q] < (u64)a.b%zu_qcap ? d%zu_qn[q] : (u32)a.b%zu_qcap;\n", b, b, b, b, b);
+            }
         } else if (var.backend[b] == BK_DICT_LDS) {
             o.f("  __syncthreads();\n");
             o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) {\n    const u64 kb = d%zu_lk[q];\n    if (kb != W_EMPTY_KEY) {\n", var.lds_slots, b);
@@ -1118,6 +1361,9 @@ Generated generate_segmented(const Loop& L, const Variant& var, int offset_type)
     o.f("#define W_BLOCK %d\n#define W_V %d\n#define W_U %d\n#define W_ALIGNED %d\n#define W_SEG_CAP %d\n", var.block, var.v, var.u, var.aligned, var.lds_slots);
     const bool uses_erf = body_uses(L, WELD_OP_ERF);
     if (uses_erf) o.f("#define W_USE_ERF 1\n");
+    const bool uses_log = body_uses(L, WELD_OP_LOG), uses_exp = body_uses(L, WELD_OP_EXP);
+    if (uses_log) o.f("#define W_USE_LOG 1\n");
+    if (uses_exp) o.f("#define W_USE_EXP 1\n");
     o.s += kPreludeSource;
     o.f("\n");
     auto slot = [&](SlotKind k, int idx, const std::string& name, const std::string& ct) {
@@ -1153,6 +1399,8 @@ Generated generate_segmented(const Loop& L, const Variant& var, int offset_type)
     o.f("  int* const errp = (int*)(a.ctl + 2);\n");
     o.f("  const int lane = threadIdx.x & 63;\n  const int wave = threadIdx.x >> 6;\n");
     if (uses_erf) o.f("  w_erf_init();\n");
+    if (uses_log) o.f("  w_log_init();\n");
+    if (uses_exp) o.f("  w_exp_init();\n");
     o.f("  const i64 ntiles = (a.n + W_TILE - 1) / W_TILE;\n");
     o.f("  for (i64 t = blockIdx.x; t < ntiles; t += gridDim.x) {\n");
     o.f("    const i64 e0 = t * W_TILE;\n    const i64 e1 = e0 + W_TILE < a.n ? e0 + W_TILE : a.n;\n");

@@ -154,6 +154,85 @@ __device__ __forceinline__ double w_erf(double x) {
 }
 #endif
 
+// ---------------------------------------------------------------- log, exp
+// The library's own log and exp for f64 (the device math library's take about 94 and 38 vector
+// instructions; these take about 40 and 30).  Tables and constants come from the build step
+// (paper_1709_06416_amd/logexp_table.py, 80-digit arithmetic); both stay within about one unit
+// in the last place of the correctly rounded result.
+//   log: x = 2^e * m, m in [181/256, 362/256); per interval of width 1/128 the table holds R, the
+//        double nearest the reciprocal of the interval's centre, and -ln R in two doubles;
+//        r = fma(m, R, -1), log x = e ln2 - ln R + (r - r^2/2 + ... - r^8/8).  Around 1, R = 1:
+//        r = m - 1 exactly, so the result keeps its relative accuracy there.
+//   exp: n = rint(x * 64/ln2), r = x - n ln2/64 in two pieces, e^x = 2^(n>>6) * T[n&63] * e^r.
+// Special values as the C library's: log(+-0) = -inf, log(x<0) = NaN, log(inf) = inf; exp
+// overflows to inf and underflows through the denormals to 0; NaN in, NaN out.
+#if defined(W_USE_LOG) || defined(W_USE_EXP)
+@W_LOGEXP_CONSTS@
+#endif
+#ifdef W_USE_LOG
+__device__ const double w_log_table[273] = {
+@W_LOG_TABLE@
+};
+__shared__ double w_log_lds[273];
+__device__ __forceinline__ void w_log_init() {
+    for (int q = threadIdx.x; q < 273; q += W_BLOCK) w_log_lds[q] = w_log_table[q];
+    __syncthreads();
+}
+__device__ __forceinline__ double w_log(double x) {
+    double m = __builtin_amdgcn_frexp_mant(x);          // [0.5, 1); 0, inf and NaN come back as they are
+    int e = __builtin_amdgcn_frexp_exp(x);
+    const bool low = m < 0.70703125;                    // 181/256
+    m = low ? m * 2.0 : m;
+    e = low ? e - 1 : e;
+    int i = (int)(m * 128.0) - 90;
+    i = i < 0 ? 0 : (i > 90 ? 90 : i);                  // (only special values get clamped)
+    const double* t = w_log_lds + 3 * i;
+    const double r = __builtin_fma(m, t[0], -1.0);
+    double p = W_LOG_C8;
+    p = __builtin_fma(p, r, W_LOG_C7);
+    p = __builtin_fma(p, r, W_LOG_C6);
+    p = __builtin_fma(p, r, W_LOG_C5);
+    p = __builtin_fma(p, r, W_LOG_C4);
+    p = __builtin_fma(p, r, W_LOG_C3);
+    p = __builtin_fma(p, r, W_LOG_C2);
+    const double fe = (double)e;
+    const double hi = __builtin_fma(fe, W_LN2_HI, t[1]);
+    const double lo = __builtin_fma(fe, W_LN2_LO, t[2]);
+    double res = hi + (r + __builtin_fma(p, r * r, lo));
+    res = x < 0.0 ? __builtin_nan("") : res;
+    res = x == 0.0 ? -__builtin_huge_val() : res;
+    return res;
+}
+#endif
+#ifdef W_USE_EXP
+__device__ const double w_exp_table[128] = {
+@W_EXP_TABLE@
+};
+__shared__ double w_exp_lds[128];
+__device__ __forceinline__ void w_exp_init() {
+    for (int q = threadIdx.x; q < 128; q += W_BLOCK) w_exp_lds[q] = w_exp_table[q];
+    __syncthreads();
+}
+__device__ __forceinline__ double w_exp(double x) {
+    double xc = x < -1000.0 ? -1000.0 : x;              // keeps n inside an int; the result is 0 / inf either way
+    xc = xc > 1000.0 ? 1000.0 : xc;
+    const double fn = __builtin_rint(xc * W_INV_L64);
+    const int n = (int)fn;
+    double r = __builtin_fma(-fn, W_L64_HI, xc);
+    r = __builtin_fma(-fn, W_L64_LO, r);
+    const double* t = w_exp_lds + 2 * (n & 63);
+    double p = W_EXP_C6;
+    p = __builtin_fma(p, r, W_EXP_C5);
+    p = __builtin_fma(p, r, W_EXP_C4);
+    p = __builtin_fma(p, r, W_EXP_C3);
+    p = __builtin_fma(p, r, W_EXP_C2);
+    p = __builtin_fma(p, r * r, r);                     // e^r - 1
+    const double s = t[0] + __builtin_fma(t[0], p, t[1]);
+    const double res = __builtin_ldexp(s, n >> 6);
+    return x != x ? x : res;
+}
+#endif
+
 // ---------------------------------------------------------------- lookup
 // lookup(v, ix) of a nested loop's inner body: an index outside the vector raises error
 // bit 4 (the call then fails) and yields 0 instead of reading out of bounds.
@@ -476,6 +555,44 @@ __device__ __forceinline__ int w_lds_slot_filtered(u64* keys, int slots, u64 kbi
     return -1;
 }
 
+// Compact cells: a dictmerger[K,V,+] whose packed key is the zero or sign extension of its low 32
+// bits and whose single value is a 32-bit partial sum keeps a 4-byte key and a 4-byte sum per slot
+// (two arrays, so that the 64 lanes of an access spread over all banks): the same LDS holds twice
+// the slots of the general table, and the entries that leave through the spill queues are 8 bytes
+// instead of 16.  W_EMPTY_KEY32 marks a free slot; the one key with those low bits never enters the
+// table (its merges take the miss path).  The slot hash is private to the table: one multiplication.
+// (Tried and dropped: buckets of four slots read with one 16-byte load, rows whose bucket is full going
+// straight to the spill queue - the wide random LDS reads cost more than the probe sequence saved.)
+#define W_EMPTY_KEY32 0x80000000u
+__device__ __forceinline__ u32 w_hash_slot32(u32 k, u32 slots) {
+    return (k * 0x9e3779b1u) >> (__builtin_clz(slots) + 1);
+}
+__device__ __forceinline__ u64 w_compact_entry(u64 kbits, i64 v) {
+    return (u64)(u32)kbits | ((u64)(u32)v << 32);
+}
+__device__ __forceinline__ int w_lds_slot32(u32* keys, int slots, u64 kbits, int max_probe) {
+    const u32 k = (u32)kbits;
+    if (k == W_EMPTY_KEY32) return -1;
+    const int mask = slots - 1;
+    int s = (int)w_hash_slot32(k, (u32)slots);
+    for (int probe = 0; probe < max_probe; ++probe) {
+        u32 cur = __hip_atomic_load(keys + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (cur == k) return s;
+        if (cur == W_EMPTY_KEY32) {
+            u32 expect = W_EMPTY_KEY32;
+            if (__hip_atomic_compare_exchange_strong(keys + s, &expect, k, __ATOMIC_RELAXED,
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP))
+                return s;
+            if (expect == k) return s;
+        }
+        s = (s + 1) & mask;
+    }
+    return -1;
+}
+__device__ __forceinline__ void w_lds_add32(u32* vals, int slot, i64 v) {
+    __hip_atomic_fetch_add(vals + slot, (u32)v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
 // Spill queues of a large dictionary.  A merge that found no room in the LDS table is
 // appended to segment [work-group][partition] of a log in global memory instead of
 // going to the global table with device atomics; the partition is taken from a hash that
@@ -490,13 +607,21 @@ __device__ __forceinline__ int w_lds_slot_filtered(u64* keys, int slots, u64 kbi
 #ifndef W_SPILL_PARTS
 #define W_SPILL_PARTS 256
 #endif
-__device__ __forceinline__ i64 w_spill_index(u32* qn, i64 cap, int words, u64 kbits) {
+__device__ __forceinline__ u32 w_spill_part(u64 kbits) {
 #ifdef W_SPILL_BY_SLOT
-    const u32 part = w_hash_slot(kbits, W_SPILL_PARTS);
+    return w_hash_slot(kbits, W_SPILL_PARTS);
 #else
-    const u32 part = w_hash2(kbits) >> 24;
+    return w_hash2(kbits) >> 24;
 #endif
+}
+__device__ __forceinline__ i64 w_spill_entry(u32 part, u32 pos, i64 cap, int words);
+__device__ __forceinline__ i64 w_spill_index(u32* qn, i64 cap, int words, u64 kbits) {
+    const u32 part = w_spill_part(kbits);
     const u32 pos = __hip_atomic_fetch_add(qn + part, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return w_spill_entry(part, pos, cap, words);
+}
+// word offset of entry `pos` of this work-group's segment of partition `part`, -1 past the segment's end
+__device__ __forceinline__ i64 w_spill_entry(u32 part, u32 pos, i64 cap, int words) {
     if (pos >= (u32)cap) return -1;
 #ifdef W_SPILL_BY_SLOT
     const u64 local = (u64)part * (u64)(u32)cap + pos;

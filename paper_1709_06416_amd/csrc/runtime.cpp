@@ -435,7 +435,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     for (size_t b = 0; b < NB; ++b) {
         if (var.backend[b] != BK_DICT_LDS || !var.spill) continue;
         const weld_builder_spec_t& s = L.builders[b];
-        const size_t entry = 8 * (size_t)(1 + s.nvals);
+        const size_t entry = var.compact == (int)b ? 8 : 8 * (size_t)(1 + s.nvals);
         off[b].qcnt = lay.take(4 * (size_t)grid * var.spill_parts);
         if (var.spill_slices) {
             off[b].ovf_count = lay.take(8);
@@ -625,6 +625,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         sm.hdr = (unsigned int*)(base + off_ctl + ctl_hdr_off((int)b));
         sm.slots = off[b].slots;
         sm.err = (int*)(base + off_ctl + 8);
+        sm.compact = var.compact == (int)b ? (var.compact_sext ? 2 : 1) : 0;
         if (var.spill_slices) {
             sm.parts = var.spill_parts;
             sm.overflow = (unsigned long long*)(base + off[b].ovf);
@@ -856,6 +857,12 @@ void destroy_result(weld_result* r) {
     delete r;
 }
 
+void recycle_event(hipEvent_t e) {
+    if (!e) return;
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    g_events.push_back(e);
+}
+
 weld_result* new_result(void* stream) {
     weld_result* r = new weld_result();
     r->stream = stream;
@@ -1058,6 +1065,13 @@ weld_status_t weld_result_elapsed_ms(weld_result_t* r, float* ms) {
     return st;
 }
 
+weld_status_t weld_result_busy_ms(weld_result_t* r, float* ms) {
+    if (!r || !ms) return WELD_ERR_INVALID_ARG;
+    weld_status_t st = weld_result_status(r);
+    *ms = r->busy_ms >= 0.f ? r->busy_ms : r->ms;
+    return st;
+}
+
 weld_status_t weld_result_kernel_ms(weld_result_t* r, float* ms) {
     if (!r || !ms) return WELD_ERR_INVALID_ARG;
     weld_status_t st = weld_result_status(r);
@@ -1068,6 +1082,8 @@ weld_status_t weld_result_kernel_ms(weld_result_t* r, float* ms) {
 const char* weld_result_kernel_name(const weld_result_t* r) { return r ? r->kernel_name.c_str() : ""; }
 
 int32_t weld_result_kernel_count(const weld_result_t* r) { return r ? r->kernel_count : 0; }
+
+int64_t weld_result_grid(const weld_result_t* r) { return r ? r->grid : 0; }
 
 void weld_result_free(weld_result_t* r) { destroy_result(r); }
 

@@ -60,7 +60,9 @@ __device__ __forceinline__ int lds_slot_looped(u64* keys, int slots, u64 kbits, 
     return -1;
 }
 
-template <int NV, int FUNC>
+// COMPACT (NV == 1, FUNC == add): an entry is ONE word, low half the key (1: zero-extended, 2: sign-extended
+// to the packed key), high half a signed 32-bit partial sum.
+template <int NV, int FUNC, int COMPACT = 0>
 __global__ void __launch_bounds__(1024) dict_spill_merge_kernel(const SpillMerge a) {
     constexpr int S = SpillTable<NV>::kSlots;
     __shared__ u64 s_keys[S];
@@ -110,7 +112,7 @@ __global__ void __launch_bounds__(1024) dict_spill_merge_kernel(const SpillMerge
     // bytes).  The loads of the next round are issued before the entries of this round are
     // merged, so the merges hide their latency.
     constexpr int ENT = SpillTable<NV>::kBatch;
-    constexpr int WORDS = 1 + NV;
+    constexpr int WORDS = COMPACT ? 1 : 1 + NV;
     typedef u64 u64x2 __attribute__((ext_vector_type(2)));
     u64 kcur[ENT], knext[ENT];
     u64 vcur[ENT][NV], vnext[ENT][NV];
@@ -138,9 +140,15 @@ __global__ void __launch_bounds__(1024) dict_spill_merge_kernel(const SpillMerge
 #pragma unroll
                     for (int q = 0; q < WORDS; ++q) buf[q] = e[q];
                 }
-                k[j] = buf[0];
+                if (COMPACT) {
+                    const u32 lo = (u32)buf[0];
+                    k[j] = COMPACT == 2 ? (u64)(i64)(int)lo : (u64)lo;
+                    w[j][0] = (u64)(i64)(int)(u32)(buf[0] >> 32);
+                } else {
+                    k[j] = buf[0];
 #pragma unroll
-                for (int f = 0; f < NV; ++f) w[j][f] = buf[1 + f];
+                    for (int f = 0; f < NV; ++f) w[j][f] = buf[1 + f];
+                }
             } else {
                 k[j] = W_EMPTY_KEY;
 #pragma unroll
@@ -384,6 +392,12 @@ hipError_t launch_dict_slice_build(const SpillMerge& a, int nvals, hipStream_t s
 template <int NV>
 static hipError_t launch_nv(const SpillMerge& a, hipStream_t stream) {
     const dim3 grid(kSpillParts), block(1024);
+    if (a.compact) {
+        if (NV != 1 || a.func != W_FUNC_ADD) return hipErrorInvalidValue;
+        if (a.compact == 2) dict_spill_merge_kernel<1, W_FUNC_ADD, 2><<<grid, block, 0, stream>>>(a);
+        else dict_spill_merge_kernel<1, W_FUNC_ADD, 1><<<grid, block, 0, stream>>>(a);
+        return hipGetLastError();
+    }
     switch (a.func) {
         case W_FUNC_ADD: dict_spill_merge_kernel<NV, W_FUNC_ADD><<<grid, block, 0, stream>>>(a); break;
         case W_FUNC_MUL: dict_spill_merge_kernel<NV, W_FUNC_MUL><<<grid, block, 0, stream>>>(a); break;

@@ -97,6 +97,7 @@ struct Runner {
     const weld_conf_t& conf;
     weld_result* top;
     std::vector<weld_result*> subs;  // every sub-result still alive
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> timers;   // around each finished sub-loop's work, read at the end
 
     Error run(SubLoop& s, int64_t n, weld_result** out) {
         weld_result* r = new_result(conf.stream);
@@ -124,6 +125,10 @@ struct Runner {
         for (size_t i = 0; i < subs.size(); ++i)
             if (subs[i] == r) { subs.erase(subs.begin() + i); break; }
         r->synced = true;  // stream order protects the memory: no host wait needed
+        if (r->recorded) {
+            timers.push_back({r->ev0, r->ev1});   // the events outlive the sub-result: its GPU time is summed at the end
+            r->ev0 = r->ev1 = nullptr;
+        }
         destroy_result(r);
     }
     // move a sub-result's memory into the caller-visible result
@@ -133,6 +138,9 @@ struct Runner {
     }
     void release_all() {
         while (!subs.empty()) release(subs.back());
+    }
+    ~Runner() {
+        for (auto& t : timers) { recycle_event(t.first); recycle_event(t.second); }
     }
 };
 
@@ -350,6 +358,16 @@ Error run_unfused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_
     if ((h = hipEventRecord(top->ev1, stream)) != hipSuccess) return hipfail("hipEventRecord", h);
     if ((h = hipStreamSynchronize(stream)) != hipSuccess) return hipfail("hipStreamSynchronize", h);
     (void)hipEventElapsedTime(&top->ms, top->ev0, top->ev1);
+    auto sum_timers = [&]() {
+        for (auto& t : R.timers) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, t.first, t.second) == hipSuccess) top->busy_ms = (top->busy_ms < 0.f ? 0.f : top->busy_ms) + ms;
+            recycle_event(t.first);
+            recycle_event(t.second);
+        }
+        R.timers.clear();
+        (void)hipGetLastError();
+    };
 
     // ---- collect lengths and error flags, keep the result memory, drop the rest
     for (size_t b = 0; b < NB; ++b) {
@@ -378,6 +396,7 @@ Error run_unfused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_
         if (!seen) R.adopt(final_sub[b]);
     }
     R.release_all();
+    sum_timers();
     top->synced = true;
     return Error();
 }

@@ -51,6 +51,7 @@ struct weld_result {
     int kernel_count = 0;
     float ms = -1.f;
     float kernel_ms = -1.f;
+    float busy_ms = -1.f;          // unfused mode: sum of the operator loops' own GPU time (no host waits between them)
     std::string kernel_name;
 };
 
@@ -171,6 +172,11 @@ struct Variant {
                                 // lane holds (their code exists once per kernel instead of once per row)
     int defer_builder = -1;     // LDS dictionary whose merges beyond the first probe are queued per wavefront
     int defer_cap = 0;          // and handled 64 at a time; entries the queue holds
+    int compact = -1;           // LDS dictionary with 8-byte cells (32-bit key, 32-bit partial sum) and 8-byte queue
+                                // entries: a dictmerger[K,V,+] whose key provably fits 32 bits and whose one value is a
+                                // constant or a 32-bit integer
+    bool compact_sext = false;  // the 64-bit key is the sign extension (else the zero extension) of its low half
+    long long compact_guard = 0;// > 0: |constant merged|; a work-group flushes its table before a cell could pass 2^31
     std::vector<int> backend;   // per builder
 };
 
@@ -264,6 +270,7 @@ struct StaticTarget {
 Error run_fused_static(const Loop& loop, const ColRef* cols, int64_t n, const weld_conf_t& conf, const StaticTarget& st);
 Error run_nested(const NestedLoop& loop, const NestedData& data, const weld_conf_t& conf, weld_result* r);
 weld_result* new_result(void* stream);   // with pinned control words and events; nullptr on failure
+void recycle_event(hipEvent_t e);        // back to the cache new_result takes its events from
 void destroy_result(weld_result* r);
 
 // unfused.cpp: the same loop as one kernel per operator, every intermediate in HBM

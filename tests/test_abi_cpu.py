@@ -110,8 +110,16 @@ def test_planner_variants_of_a_compacting_loop_with_a_large_dictionary(wb):
     """Host logic only: which merge-phase form the generator picks, read off the generated text."""
     c5 = configs.program_c5()
     src = wb.generated_source(c5)
-    # merges beyond the first probe queued per wavefront, merges as one loop over the lane's rows
-    assert "#define WELD_DRAIN()" in src and "WELD_MERGE_MEM(r)" in src and '_Pragma("unroll 1")' in src
+    # the first probes of a lane's rows are issued together and the hits settled in straight-line code;
+    # the rest is queued per wavefront by one loop over the lane's rows
+    assert "#define WELD_DRAIN()" in src and "WELD_MERGE_HIT(r, fs[j], fc[j], miss)" in src
+    assert "WELD_MERGE_QUEUE(r, miss)" in src and '_Pragma("unroll 1")' in src
+    # a count under a key that provably fits 32 bits (x mod 100000): compact cells, twice the slots, 8-byte queue entries
+    assert "__shared__ u32 d1_ck[16384]" in src and "w_compact_entry(kb" in src
+    general = wb.generated_source(c5, tune={"dict_compact": -1})
+    assert "__shared__ u64 d1_lk[8192]" in general and "w_compact_entry(kb" not in general
+    # the cleaned code fits 32 bits too: it is held and staged in one register and widened at the store
+    assert "typedef int mt4_t" in src and "(i64)stg[e]" in src
     # the merged value is the constant 1: queue entries hold the key only (128 per wavefront)
     assert "dq_n + add > 128" in src
     # division by a constant: wavefront-wide shortcut in full tiles only

@@ -3,9 +3,8 @@
 
 Where the oracle can produce the whole result in seconds it does (C1, C3, C5); for C2
 (1e8 map outputs) a random sample of rows is re-evaluated by the oracle element by
-element; for C4 two of the six groups are recomputed by the oracle as filtered sums and
-the rest is tied down by invariants that hold at any size (group counts add up to the
-filtered count, group sums add up to the filtered total).
+element; for C4 every one of the six groups is recomputed by the oracle as filtered sums
+over its materialised expression columns, and the groups are tied to the filtered totals.
 """
 import numpy as np
 import pytest
@@ -96,6 +95,10 @@ def _c4_group_program(flag, status):
 
 
 def test_c4_full_size_groups(wb):
+    """All six groups against the oracle: its operator-at-a-time evaluation materialises the predicate and the
+    four merged expressions once over all 2e8 rows; each group is then what the dictmerger is defined to
+    return for its key - the correctly rounded sums and the count of the rows that pass the filter and carry
+    that key - and the sum over the groups must equal the filtered totals."""
     from oracle import interp
     n = configs.FULL_ROWS["C4"]
     cols = configs.make_columns("C4", n, device="cuda")
@@ -104,16 +107,25 @@ def test_c4_full_size_groups(wb):
     res.free()
     assert list(zip(keys[0].tolist(), keys[1].tolist())) == [(f, s) for f in range(3) for s in range(2)]
     host = _host(cols)
-    for flag, status in ((0, 1), (2, 0)):                    # two groups, recomputed by the oracle
-        want = interp.run(_c4_group_program(flag, status), host, sums="exact")
-        g = flag * 2 + status
-        for k in range(4):
-            assert abs(vals[k][g] - float(want[k])) <= 1e-9 * abs(float(want[k])), (flag, status, k)
-        assert int(vals[4][g]) == int(want[4])
-    total = interp.run(_c4_group_program(None, None), host, sums="exact")
-    assert int(vals[4].sum()) == int(total[4])               # sum of group counts == filtered count
-    for k in range(4):                                       # sum of group sums == filtered total
-        assert abs(float(np.sum(vals[k], dtype=np.longdouble)) - float(total[k])) <= 1e-9 * abs(float(total[k]))
+    prog = _c4_group_program(None, None)
+    col = interp.eval_columns(prog, host)
+    pred = col[prog.merges[0]["pred"]]
+    merged = [col[m["vals"][0]] for m in prog.merges[:4]]
+    del col
+    counted = 0
+    for flag in range(3):
+        for status in range(2):
+            g = flag * 2 + status
+            mask = pred & (host[0] == flag) & (host[1] == status)
+            for k in range(4):
+                want = float(interp.exact_sum(merged[k][mask]))
+                assert abs(vals[k][g] - want) <= 1e-9 * abs(want), (flag, status, k, vals[k][g], want)
+            assert int(vals[4][g]) == int(mask.sum()), (flag, status)
+            counted += int(mask.sum())
+    assert counted == int(pred.sum()) == int(vals[4].sum())    # every filtered row lies in exactly one group
+    for k in range(4):                                         # sum of group sums == filtered total
+        total = float(interp.exact_sum(merged[k][pred]))
+        assert abs(float(np.sum(vals[k], dtype=np.longdouble)) - total) <= 1e-9 * abs(total)
 
 
 def test_c1_full_size_unfused_equals_fused(wb):

@@ -303,6 +303,68 @@ def test_dictmerger_functions_and_struct_keys(wb, func):
     _check(wb, p, [_dev(k1), _dev(k2), _dev(a), _dev(f)], label="dict " + func)
 
 
+@pytest.mark.parametrize("tune", [None, {"dict_compact": -1}, {"dict_spill": -1}, {"dict_spill": 3}, {"lds_dict_slots": 256}])
+@pytest.mark.parametrize("shape", ["i32 key", "i8 i8 key", "narrow i64 key", "i32 sums", "compaction too"])
+def test_compact_dictionary_cells(wb, shape, tune):
+    """dictmerger[K,V,+] under a key that fits 32 bits, counting or summing 32-bit integers: 8-byte cells in
+    LDS and 8-byte queue entries.  Keys of both signs, the key whose low half is the free-slot marker
+    (-2^31), sums that wrap in 32 bits, more keys than the table holds."""
+    rnd = np.random.RandomState(41)
+    n = 300_011
+    if shape == "i32 key":
+        k = (rnd.randint(0, 60_000, size=n) * 71_567 - 2_000_000_000).astype(np.int32)
+        k[::997] = np.iinfo(np.int32).min
+        p = Program(["i32"])
+        p.merge(p.dictmerger(["i32"], ["i64"], "add", 70_000), [p.const("i64", 3)], keys=[p.col(0)])
+        cols = [_dev(k)]
+    elif shape == "i8 i8 key":
+        a = rnd.randint(-128, 128, size=n).astype(np.int8)
+        b = rnd.randint(-128, 128, size=n).astype(np.int8)
+        p = Program(["i8", "i8"])
+        pred = p.bin("ne", p.col(0), p.const("i8", 5))
+        p.merge(p.dictmerger(["i8", "i8"], ["i64"], "add", 65_536), [p.const("i64", -1)], keys=[p.col(0), p.col(1)], pred=pred)
+        cols = [_dev(a), _dev(b)]
+    elif shape == "narrow i64 key":
+        x = rnd.randint(-10 ** 12, 10 ** 12, size=n).astype(np.int64)           # x mod 40000 takes both signs
+        p = Program(["i64"])
+        p.merge(p.dictmerger(["i64"], ["i64"], "add", 80_000), [p.const("i64", 1)], keys=[p.bin("mod", p.col(0), p.const("i64", 40_000))])
+        cols = [_dev(x)]
+    elif shape == "i32 sums":
+        k = rnd.randint(0, 30_000, size=n).astype(np.int32)
+        v = rnd.randint(-2 ** 31, 2 ** 31, size=n).astype(np.int32)              # sums wrap modulo 2^32
+        p = Program(["i32", "i32"])
+        pred = p.bin("gt", p.col(1), p.const("i32", -2_000_000_000))
+        p.merge(p.dictmerger(["i32"], ["i32"], "add", 30_000), [p.col(1)], keys=[p.col(0)], pred=pred)
+        cols = [_dev(k), _dev(v)]
+    else:
+        x = rnd.randint(-10 ** 6, 10 ** 9, size=n).astype(np.int64)
+        p = Program(["i64"])
+        pred = p.bin("gt", p.col(0), p.const("i64", 0))
+        key = p.bin("mod", p.col(0), p.const("i64", 50_000))
+        p.merge(p.vecbuilder("i64"), key, pred=pred)
+        p.merge(p.dictmerger(["i64"], ["i64"], "add", 50_000), [p.const("i64", 2)], keys=[key], pred=pred)
+        cols = [_dev(x)]
+    if tune is None:
+        src = wb.generated_source(p)
+        assert "w_compact_entry(kb" in src or "w_lds_add32" in src, "this shape should take compact cells"
+    _check(wb, p, cols, label="compact %s %s" % (shape, tune), tune=tune)
+
+
+def test_compact_cells_are_flushed_before_a_partial_sum_overflows(wb):
+    # one work-group, a constant of 1000 per merge into a handful of keys: a 32-bit partial sum would pass
+    # 2^31 after 2.1 million rows; the work-group sends its table's contents on before that and goes on
+    n = 5_000_003
+    x = torch.arange(n, dtype=torch.int64, device="cuda")
+    p = Program(["i64"])
+    p.merge(p.dictmerger(["i64"], ["i64"], "add", 20_000), [p.const("i64", 1000)], keys=[p.bin("mod", p.col(0), p.const("i64", 3))])
+    assert "flush_d0(); wg_rows = 0;" in wb.generated_source(p)
+    res = wb.fused_for(p, [x], tune={"grid_blocks": 1, "dict_strategy": 2}).check()
+    keys, vals = res.dict(0)
+    res.free()
+    assert keys[0].tolist() == [0, 1, 2]
+    assert vals[0].tolist() == [1000 * ((n + 2 - r) // 3) for r in range(3)]       # closed form, far above 2^31
+
+
 def test_dictmerger_extreme_i64_keys(wb):
     # the key whose bits equal the table's free-slot marker, and its neighbours
     lo = np.iinfo(np.int64).min
