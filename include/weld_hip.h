@@ -161,7 +161,7 @@ typedef struct {
     int32_t grid_blocks;     /* work-groups of the loop kernel; 0: as many as are resident at
                                 once, fewer for loops that only stream columns through light
                                 arithmetic (about 56 KB of loads in flight per compute unit),
-                                eight per unit for register-only loops with division, roots or
+                                48 per unit for register-only loops with division, roots or
                                 transcendentals; weld_tune_launch measures it instead */
     int32_t dict_strategy;   /* 0 auto, 1 register slots, 2 LDS hash table, 3 global only,
                                 4 per-lane LDS slots                                */
@@ -189,6 +189,8 @@ typedef struct {
                                    whose one value is a constant or a 32-bit integer: 0 = 8-byte cells (32-bit
                                    key, 32-bit partial sum: twice the slots) and 8-byte queue entries,
                                    -1 = the general 64-bit cells                                    */
+    int32_t device_math;        /* exp and log of the body: 0 = the library's own (tables and polynomials, about a
+                                   third of the instructions), -1 = the device math library's          */
 } weld_tuning_t;
 
 typedef struct {
@@ -238,7 +240,7 @@ weld_status_t weld_fused_for(const weld_cols_t* cols, int64_t n, const weld_body
 /*
  * Launch-shape tuning (beyond the paper: its CPU backend sizes its task grain itself, Sec. 5).
  * Runs the loop over the given columns a few times for each of several persistent-grid sizes
- * (the library's own choice first, then 1..16 work-groups per compute unit), times the loop
+ * (the library's own choice first, then 1..64 work-groups per compute unit), times the loop
  * kernel with HIP events, and returns builder->conf.tune with grid_blocks set to the fastest
  * in *best (unchanged fields are kept; another grid replaces the library's choice only if it is
  * more than 2.5 % faster: below that, runs of one grid differ as much).  best_ms / default_ms (may be NULL): loop-kernel milliseconds of the

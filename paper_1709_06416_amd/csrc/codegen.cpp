@@ -185,8 +185,8 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
                 else o.f("(%s)t%d", T, q.a);
                 break;
             }
-            case WELD_OP_EXP: o.f("w_exp(t%d)", q.a); break;
-            case WELD_OP_LOG: o.f("w_log(t%d)", q.a); break;
+            case WELD_OP_EXP: o.f("W_EXP(t%d)", q.a); break;
+            case WELD_OP_LOG: o.f("W_LOG(t%d)", q.a); break;
             case WELD_OP_SQRT: o.f("sqrt(t%d)", q.a); break;
             case WELD_OP_ERF: o.f("w_erf(t%d)", q.a); break;
             case WELD_OP_ADD:
@@ -517,6 +517,7 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
     if (var.block > 1024) var.block = 1024;
     var.block = (var.block / 64) * 64;
     var.aligned = aligned ? 1 : 0;
+    var.own_math = tune.device_math >= 0;
     // the LDS dictionary shares the 160 KiB with the compaction's staging buffer, the admission
     // filter, the spill counters and the erf table: halve it until everything fits
     if (var.lds_slots > 0) {
@@ -582,9 +583,11 @@ Generated generate(const Loop& L, const Variant& var) {
     if (var.spill_slices) o.f("#define W_SPILL_PARTS %d\n#define W_SPILL_BY_SLOT 1\n", var.spill_parts);
     const bool uses_erf = body_uses(L, WELD_OP_ERF);
     if (uses_erf) o.f("#define W_USE_ERF 1\n");
-    const bool uses_log = body_uses(L, WELD_OP_LOG), uses_exp = body_uses(L, WELD_OP_EXP);
-    if (uses_log) o.f("#define W_USE_LOG 1\n");
-    if (uses_exp) o.f("#define W_USE_EXP 1\n");
+    const bool uses_log = var.own_math && body_uses(L, WELD_OP_LOG), uses_exp = var.own_math && body_uses(L, WELD_OP_EXP);
+    if (uses_log) o.f("#define W_USE_LOG 1\n#define W_LOG w_log\n");
+    else o.f("#define W_LOG log\n");
+    if (uses_exp) o.f("#define W_USE_EXP 1\n#define W_EXP w_exp\n");
+    else o.f("#define W_EXP exp\n");
     o.s += kPreludeSource;
     o.f("\n");
 
@@ -1346,6 +1349,7 @@ Variant choose_segmented_variant(const Loop& L, const weld_tuning_t& tune, bool 
     if (var.lds_slots < 64) var.lds_slots = 64;
     if (var.lds_slots > 8192) var.lds_slots = 8192;
     var.aligned = aligned ? 1 : 0;
+    var.own_math = tune.device_math >= 0;
     var.backend.assign(1, BK_MERGER);
     return var;
 }
@@ -1361,9 +1365,11 @@ Generated generate_segmented(const Loop& L, const Variant& var, int offset_type)
     o.f("#define W_BLOCK %d\n#define W_V %d\n#define W_U %d\n#define W_ALIGNED %d\n#define W_SEG_CAP %d\n", var.block, var.v, var.u, var.aligned, var.lds_slots);
     const bool uses_erf = body_uses(L, WELD_OP_ERF);
     if (uses_erf) o.f("#define W_USE_ERF 1\n");
-    const bool uses_log = body_uses(L, WELD_OP_LOG), uses_exp = body_uses(L, WELD_OP_EXP);
-    if (uses_log) o.f("#define W_USE_LOG 1\n");
-    if (uses_exp) o.f("#define W_USE_EXP 1\n");
+    const bool uses_log = var.own_math && body_uses(L, WELD_OP_LOG), uses_exp = var.own_math && body_uses(L, WELD_OP_EXP);
+    if (uses_log) o.f("#define W_USE_LOG 1\n#define W_LOG w_log\n");
+    else o.f("#define W_LOG log\n");
+    if (uses_exp) o.f("#define W_USE_EXP 1\n#define W_EXP w_exp\n");
+    else o.f("#define W_EXP exp\n");
     o.s += kPreludeSource;
     o.f("\n");
     auto slot = [&](SlotKind k, int idx, const std::string& name, const std::string& ct) {

@@ -201,6 +201,7 @@ __device__ __forceinline__ double w_log(double x) {
     double res = hi + (r + __builtin_fma(p, r * r, lo));
     res = x < 0.0 ? __builtin_nan("") : res;
     res = x == 0.0 ? -__builtin_huge_val() : res;
+    res = x == __builtin_huge_val() ? x : res;          // (the polynomial of an infinite r is inf - inf)
     return res;
 }
 #endif

@@ -343,10 +343,12 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         const int64_t want = (57344 + tile_bytes - 1) / tile_bytes;
         if (want < per_cu) per_cu = (int)(want < 1 ? 1 : want);
     } else if (sclass == 2) {
-        // A loop that computes about as long as it loads: more work-groups than are resident at once
+        // A loop that computes about as long as it loads: many more work-groups than are resident at once
         // (four fit for the Black-Scholes loop), so that they drift apart and one group's arithmetic
-        // overlaps another's loads; a resident grid marches in step (measured 0.465 -> 0.445 ms).
-        per_cu = 8;
+        // overlaps another's loads; a resident grid marches in step.  Measured on that loop, 5e7 rows:
+        // 0.465 ms with the 4 per unit that fit, 0.451 with 8, 0.439 with 16, 0.428 with 32, 0.407 with 48,
+        // 0.41 with 64 and with one work-group per tile.
+        per_cu = 48;
     }
     int64_t grid = conf.tune.grid_blocks > 0 ? conf.tune.grid_blocks : (int64_t)device_info().cus * per_cu;
     if (grid > ntiles) grid = ntiles;

@@ -40,7 +40,7 @@ extern "C" weld_status_t weld_tune_launch(const weld_cols_t* cols, int64_t n, co
         return WELD_ERR_DEVICE;
     }
     // work-groups per compute unit; 0 stands for the library's own choice and is tried first
-    static const int kPerUnit[] = {0, 1, 2, 3, 4, 6, 8, 12, 16};
+    static const int kPerUnit[] = {0, 1, 2, 3, 4, 6, 8, 12, 16, 32, 64};
     const int kRuns = 6;      // the first one warms up (code object load, pool blocks)
     *best = builder->conf.tune;
     float best_time = -1.0f, first_time = -1.0f;

@@ -177,6 +177,7 @@ struct Variant {
                                 // constant or a 32-bit integer
     bool compact_sext = false;  // the 64-bit key is the sign extension (else the zero extension) of its low half
     long long compact_guard = 0;// > 0: |constant merged|; a work-group flushes its table before a cell could pass 2^31
+    bool own_math = true;       // exp and log evaluated by the library's own code (else the device math library's)
     std::vector<int> backend;   // per builder
 };
 

@@ -121,6 +121,37 @@ def test_erf_map_against_the_oracle(wb):
     _check(wb, p, [_dev(x)], label="erf map")
 
 
+def test_log_and_exp_maps_against_the_oracle(wb):
+    # the library evaluates log and exp itself (tables + polynomials): maps over wide ranges, the
+    # neighbourhood of 1 where log loses its leading digits, table-interval edges, special values
+    rnd = np.random.RandomState(32)
+    x = np.concatenate([rnd.uniform(0.1, 10.0, 150_000), np.exp(rnd.uniform(-700, 700, 100_000)),
+                        1.0 + rnd.uniform(-1e-2, 1e-2, 20_000), 1.0 + rnd.uniform(-1e-10, 1e-10, 1_000),
+                        np.arange(90, 182) / 128.0, np.nextafter(np.arange(90, 182) / 128.0, 0),
+                        [1.0, 0.5, 2.0, 5e-324, 2.2250738585072014e-308, 1.7976931348623157e308, 0.70703125]])
+    p = Program(["f64"])
+    p.merge(p.vecbuilder("f64"), p.un("log", p.col(0)))
+    _check(wb, p, [_dev(x)], label="log map")                 # strict 1e-12 relative, no floor
+    y = np.concatenate([rnd.uniform(-0.05, 0.0, 100_000), rnd.uniform(-700, 700, 150_000), rnd.uniform(-1, 1, 20_000),
+                        (np.arange(-64, 65) + 0.5) * np.log(2) / 64, [0.0, -0.0, 709.782712893384, -708.0, 1.0, -1.0]])
+    q = Program(["f64"])
+    q.merge(q.vecbuilder("f64"), q.un("exp", q.col(0)))
+    _check(wb, q, [_dev(y)], label="exp map")
+    # special values, as the C library has them
+    sp = np.array([0.0, -0.0, -1.0, np.inf, np.nan, -np.inf, 1.0])
+    res = wb.fused_for(p, [_dev(sp)]).check()
+    got = res.vec_host(0)
+    res.free()
+    assert got[0] == -np.inf and got[1] == -np.inf and np.isnan(got[2]) and got[3] == np.inf and np.isnan(got[4])
+    assert np.isnan(got[5]) and got[6] == 0.0
+    se = np.array([710.0, 1e300, np.inf, -746.0, -1e300, -np.inf, np.nan, -740.0])
+    res = wb.fused_for(q, [_dev(se)]).check()
+    got = res.vec_host(0)
+    res.free()
+    assert np.all(got[:3] == np.inf) and np.all(got[3:6] == 0.0) and np.isnan(got[6])
+    assert abs(got[7] - np.exp(-740.0)) <= 5e-324            # a denormal result: within one denormal step
+
+
 def test_plain_arithmetic_maps_are_bit_exact(wb):
     # +,-,*,/ and sqrt are correctly rounded on both sides and nothing is contracted
     p = Program(["f64", "f64"])
