@@ -87,12 +87,13 @@ def _probe(table, key_cols):
     return np.fromiter((index.get(key, -1) for key in probe), dtype=np.int64, count=n)
 
 
-def eval_columns(program, columns, n=None, gather=None, outer=None, inner=None, dicts=None):
+def eval_columns(program, columns, n=None, gather=None, outer=None, inner=None, dicts=None, index=None):
     """Materialise every body expression as a full column (one operator at a time).
 
     gather / outer / inner give meaning to the operators of nested loops: the vectors
     `lookup` reads, the outer vectors already expanded to one element per row of this
-    (inner) loop, and the column of inner-loop results seen by an outer body.
+    (inner) loop, and the column of inner-loop results seen by an outer body; index: the
+    position of each row's element in the inner vectors (an inner loop over ranges).
     """
     if n is None:
         n = len(columns[0]) if columns else 0
@@ -126,7 +127,7 @@ def eval_columns(program, columns, n=None, gather=None, outer=None, inner=None, 
             elif code == "const":
                 out = np.full(n, op[2], dtype=dt)
             elif code == "index":
-                out = np.arange(n, dtype=np.int64)
+                out = np.arange(n, dtype=np.int64) if index is None else index
             elif code == "neg":
                 out = np.negative(a[0])
             elif code == "not":
@@ -357,9 +358,10 @@ def run_nested(nested, outer_columns, inner_columns, gather, sums="exact"):
     """A `for` nested in a `for` (Sec. 3.2: loops nest arbitrarily; a loop takes an
     optional start and end index per vector), evaluated one operator at a time:
 
-      1. every (outer element i, inner element j in [start[i], end[i])) pair becomes one row:
-         the inner body is evaluated over all pairs, `outer` reading element i of an outer
-         vector and `col` element j of an inner vector;
+      1. every (outer element i, inner element j = start[i], start[i] + stride[i], ... below
+         end[i]) pair becomes one row (stride 1 unless the loop names a stride vector): the
+         inner body is evaluated over all pairs, `outer` reading element i of an outer vector,
+         `col` element j of an inner vector and `index` being j;
       2. the pairs of one outer element are folded with the inner merger's function
          (f64 sums: the correctly rounded real sum when sums == "exact"): one result per
          outer element, the identity for an empty range;
@@ -376,13 +378,18 @@ def run_nested(nested, outer_columns, inner_columns, gather, sums="exact"):
     assert np.all(start <= end) and (n_outer == 0 or start.min() >= 0)
     if n_inner is not None and n_outer:
         assert end.max() <= n_inner
-    length = end - start
+    stride_col = getattr(nested, "stride_col", None)
+    stride = (outer_columns[stride_col].astype(np.int64) if stride_col is not None
+              else np.ones(n_outer, dtype=np.int64))
+    assert np.all(stride >= 1)
+    length = (end - start + stride - 1) // stride                    # elements start, start + stride, ... < end
     seg = np.repeat(np.arange(n_outer, dtype=np.int64), length)      # outer element of each pair
     first = np.cumsum(length) - length                               # pairs before each outer element
-    j = np.arange(int(length.sum()), dtype=np.int64) - np.repeat(first, length) + np.repeat(start, length)
+    step = np.arange(int(length.sum()), dtype=np.int64) - np.repeat(first, length)
+    j = np.repeat(start, length) + step * np.repeat(stride, length)
     prog = nested.inner
     val = eval_columns(prog, [c[j] for c in inner_columns], n=len(j), gather=gather,
-                       outer=[c[seg] for c in outer_columns])
+                       outer=[c[seg] for c in outer_columns], index=j)
     assert len(prog.merges) == 1 and prog.merges[0]["builder"] == 0
     m = prog.merges[0]
     mask = val[m["pred"]] if m["pred"] is not None else np.ones(len(j), dtype=bool)

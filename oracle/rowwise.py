@@ -152,7 +152,8 @@ def _body(program, i, elem, gather=None, outer_elem=None, inner_value=None, dict
 
 def run_nested(nested, outer_columns, inner_columns, gather):
     """The nested loop written out: for every outer element, run its inner `for` over
-    [start, end) with a fresh merger, take result(), then evaluate the outer body and merge.
+    start, start + stride, ... below end with a fresh merger, take result(), then evaluate the
+    outer body and merge.
     Returns the outer builders like `run` (merger -> number, vecbuilder -> list, ...)."""
     n_outer = len(outer_columns[0]) if outer_columns else 0
     inner_results = []
@@ -160,7 +161,10 @@ def run_nested(nested, outer_columns, inner_columns, gather):
         x = [c[i] for c in outer_columns]
         acc = _identity(nested.inner_func, nested.inner_type)        # a new merger per outer element
         m = nested.inner.merges[0]
-        for j in range(int(x[nested.start_col]), int(x[nested.end_col])):
+        stride_col = getattr(nested, "stride_col", None)
+        stride = int(x[stride_col]) if stride_col is not None else 1
+        assert stride >= 1
+        for j in range(int(x[nested.start_col]), int(x[nested.end_col]), stride):
             val = _body(nested.inner, j, [c[j] for c in inner_columns], gather=gather, outer_elem=x)
             if m["pred"] is None or val[m["pred"]]:
                 acc = _combine(nested.inner_func, nested.inner_type, acc, val[m["vals"][0]])

@@ -98,6 +98,71 @@ def test_operator_at_a_time_equals_literal_nested_loops(func, t, with_pred, over
         assert float(got[1]) == pytest.approx(want[1], rel=1e-13) or (np.isinf(got[1]) and np.isinf(want[1]))
 
 
+def _column_program(with_index=False):
+    """for every column j of a row-major matrix: sum of the column (Sec. 3.2: a loop takes a start, an end
+    and a stride per vector, which is how the paper iterates over matrices) - and, with_index, the sum of
+    the positions the inner loop visited."""
+    p = NestedProgram(["i64", "i64", "i64"], 0, 1, ["i64"], [], "i64", "add", stride_col=2, ranges="any")
+    q = p.inner
+    q.merge(0, q.index() if with_index else q.col(0))
+    p.outer.merge(p.outer.vecbuilder("i64"), p.outer.inner())
+    return p
+
+
+def test_strided_ranges_hand_worked_matrix_columns():
+    # the 3 x 4 matrix [[0,1,2,3],[4,5,6,7],[8,9,10,11]] stored row by row; column j is start = j,
+    # end = 12, stride = 4: sums 0+4+8, 1+5+9, 2+6+10, 3+7+11
+    m = list(range(12))
+    start, end, stride = [0, 1, 2, 3], [12, 12, 12, 12], [4, 4, 4, 4]
+    want = [12, 15, 18, 21]
+    p = _column_program()
+    assert interp.run_nested(p, [np.array(c, dtype=np.int64) for c in (start, end, stride)], [np.array(m, dtype=np.int64)], [])[0].tolist() == want
+    assert rowwise.run_nested(p, [start, end, stride], [m], [])[0] == want
+    # ends that are not start + k * stride, ranges that overlap, an empty one, a gap (elements 9..11 unread),
+    # stride larger than the range: elements [1,4,7], [2], [], [0,2,4,6,8], [5]
+    start, end, stride = [1, 2, 6, 0, 5], [8, 3, 6, 9, 7], [3, 7, 2, 2, 100]
+    want = [1 + 4 + 7, 2, 0, 0 + 2 + 4 + 6 + 8, 5]
+    assert interp.run_nested(p, [np.array(c, dtype=np.int64) for c in (start, end, stride)], [np.array(m, dtype=np.int64)], [])[0].tolist() == want
+    assert rowwise.run_nested(p, [start, end, stride], [m], [])[0] == want
+    # `index` in the inner body is the position in the inner vector, not the iteration count
+    pi = _column_program(with_index=True)
+    vals = [100 + v for v in m]
+    assert interp.run_nested(pi, [np.array(c, dtype=np.int64) for c in (start, end, stride)], [np.array(vals, dtype=np.int64)], [])[0].tolist() == want
+    assert rowwise.run_nested(pi, [start, end, stride], [vals], [])[0] == want
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_strided_ranges_operator_at_a_time_equals_literal_loops(seed):
+    rnd = np.random.RandomState(100 + seed)
+    n_outer, n_inner = 31, 200
+    t = "i64" if seed % 2 else "f64"
+    func = ["add", "min", "max", "add"][seed % 4]
+    start = rnd.randint(0, n_inner, size=n_outer)
+    end = np.minimum(n_inner, start + rnd.randint(0 if func == "add" else 1, 60, size=n_outer))
+    stride = rnd.choice([1, 2, 3, 7, 50], size=n_outer)
+    a = rnd.randint(-9, 10, size=n_inner).astype(np.int64) if t == "i64" else np.round(rnd.uniform(-2, 2, size=n_inner), 3)
+    p = NestedProgram(["i64", "i64", "i64"], 0, 1, [t], [], t, func, stride_col=2, ranges="any")
+    q = p.inner
+    v = q.col(0)
+    if t == "i64":
+        v = q.bin("add", v, q.bin("mul", q.index(), q.outer(2)))          # position and outer element both visible
+    q.merge(0, v, pred=q.bin("ne", q.bin("mod", q.index(), q.const("i64", 5)), q.const("i64", 0)) if seed % 3 == 0 else None)
+    p.outer.merge(p.outer.vecbuilder(t), p.outer.inner())
+    outer = [start.astype(np.int64), end.astype(np.int64), stride.astype(np.int64)]
+    got = interp.run_nested(p, outer, [a], [], sums="fold")[0]
+    want = rowwise.run_nested(p, [c.tolist() for c in outer], [a.tolist()], [])[0]
+    if t == "i64":
+        assert got.tolist() == want
+    else:
+        assert np.array_equal(got, np.array(want))          # same fold order on both sides: identical doubles
+    # brute force per range with numpy slicing (a library routine): start:end:stride
+    if seed % 3 != 0 and t == "f64":
+        red = {"add": np.sum, "min": np.min, "max": np.max}[func]
+        for i in range(n_outer):
+            sl = a[start[i]:end[i]:stride[i]]
+            assert (len(sl) == 0 and func == "add" and got[i] == 0.0) or np.isclose(got[i], red(sl), rtol=1e-12)
+
+
 def _pagerank_once(rowptr, src, outdeg, rank):
     contrib = interp.run(graphs.program_contrib(), [rank, outdeg])[0]
     new_rank, total = interp.run_nested(graphs.program_pagerank(len(rank)), [rowptr[:-1], rowptr[1:]], [src], [contrib])

@@ -169,12 +169,22 @@ class NestedProgram:
     `inner` is a Program over the inner vectors with exactly one merger (builder 0) and may
     use `lookup` and `outer`; `outer` is a Program over the outer vectors that may use
     `inner()`; start_col / end_col name the outer columns that hold each outer element's
-    inner range [start, end).  Plain data, no evaluation.
+    inner range [start, end).  stride_col (optional) names the outer column with each range's
+    stride: the inner loop then visits start, start + stride, ... below end (the paper's
+    per-vector start, end and stride: a column of a row-major matrix is start = j,
+    end = rows * cols, stride = cols).  ranges = "csr": the ranges are consecutive with stride 1
+    (end[i] == start[i+1], a CSR row-pointer array); "any": they may overlap, leave gaps and
+    carry strides.  In an inner body `index` is the position of the element in the inner vectors.
+    Plain data, no evaluation.
     """
 
-    def __init__(self, outer_columns, start_col, end_col, inner_columns, gather, inner_type, inner_func):
+    def __init__(self, outer_columns, start_col, end_col, inner_columns, gather, inner_type, inner_func,
+                 stride_col=None, ranges="csr"):
         assert inner_func in FUNCS and inner_type in ("i64", "f64")
         assert outer_columns[start_col] == outer_columns[end_col] and outer_columns[start_col] in ("i32", "i64")
+        assert ranges in ("csr", "any") and (stride_col is None or ranges == "any")
+        assert stride_col is None or outer_columns[stride_col] == outer_columns[start_col]
+        self.stride_col, self.ranges = stride_col, ranges
         self.start_col, self.end_col = start_col, end_col
         self.inner_type, self.inner_func = inner_type, inner_func
         self.inner = Program(inner_columns, gather=gather, outer=outer_columns)
