@@ -19,11 +19,25 @@
  * the inner elements (balanced by inner elements, not by outer elements, so one outer element
  * with a million inner elements costs what a million outer elements with one each cost), with a
  * segmented merger that keeps one cell per outer element; a second, ordinary fused loop over the
- * outer elements evaluates the outer body with the cell as one more value.  This flattening
- * needs the inner ranges to be CONSECUTIVE: start[0] == 0, end[i] == start[i+1],
- * end[n_outer-1] == n_inner (CSR row pointers: pass the pointer array as `start` and the same
- * array shifted by one element as `end`).  Any other ranges make the call fail with
- * WELD_ERR_INVALID_ARG at the evaluation point; strides other than 1 are not implemented.
+ * outer elements evaluates the outer body with the cell as one more value.
+ *
+ * Two kinds of ranges (weld_nested_t.range_kind):
+ *   WELD_RANGES_CSR  the ranges are CONSECUTIVE with stride 1: start[0] == 0, end[i] == start[i+1],
+ *                    end[n_outer-1] == n_inner (CSR row pointers: pass the pointer array as `start`
+ *                    and the same array shifted by one element as `end`).  The flattened loop then
+ *                    streams the inner vectors front to back; nothing waits for the host.  Ranges
+ *                    that are not of this form make the call fail with WELD_ERR_INVALID_ARG at the
+ *                    evaluation point.
+ *   WELD_RANGES_ANY  the loop's start, end and STRIDE per vector (Sec. 3.2: how the IR iterates over
+ *                    a column of a row-major matrix): outer element i visits start[i], start[i] +
+ *                    stride[i], ... below end[i]; ranges may overlap, leave gaps and be empty.  A
+ *                    small kernel turns the ranges into element counts and their prefix sums, the
+ *                    flattened loop runs over those positions and reads inner element
+ *                    start[i] + k * stride[i] for the k-th of them (a gather instead of a stream).
+ *                    Its size is the total count, so the call waits for that kernel before it
+ *                    enqueues the rest; start < 0, end < start, end > n_inner or stride < 1 make it
+ *                    fail with WELD_ERR_INVALID_ARG there and then.
+ * In an inner body WELD_OP_INDEX is the position of the element in the inner vectors.
  */
 #ifndef WELD_NESTED_H
 #define WELD_NESTED_H
@@ -42,6 +56,8 @@ enum {
     WELD_OP_INNER = 28   /* outer body: the result of this outer element's inner loop            */
 };
 
+enum { WELD_RANGES_CSR = 0, WELD_RANGES_ANY = 1 };
+
 typedef struct {
     int64_t n_outer;            /* outer elements, >= 0                                           */
     weld_cols_t outer;          /* zipped outer vectors: device pointers to n_outer elements      */
@@ -57,14 +73,17 @@ typedef struct {
     int32_t inner_type;         /* T of the inner merger: WELD_I64 or WELD_F64                    */
     int32_t inner_func;         /* weld_func_t                                                    */
     weld_body_t outer_body;     /* WELD_OP_COL reads outer column a; merges go to `builders`      */
+    int32_t range_kind;         /* WELD_RANGES_CSR (0) or WELD_RANGES_ANY                         */
+    int32_t stride_col;         /* WELD_RANGES_ANY: outer column (type of start / end) holding each
+                                   range's stride, or -1 for stride 1; ignored for WELD_RANGES_CSR */
 } weld_nested_t;
 
 /* Runs the nested loop above.  `builders` are the OUTER loop's builders (any kind
  * weld_fused_for takes) and carry the configuration; `out` is a handle like weld_fused_for's,
  * with one result per outer builder.  Enqueues on conf.stream and returns; every vector must
  * stay alive and unmodified until weld_result_status() has returned.  Errors found on the
- * device (ranges that are not consecutive, a lookup outside its vector) are reported by
- * weld_result_status() as WELD_ERR_INVALID_ARG.  weld_result_kernel_ms() times the flattened
+ * device (WELD_RANGES_CSR ranges that are not consecutive, a lookup outside its vector) are
+ * reported by weld_result_status() as WELD_ERR_INVALID_ARG.  weld_result_kernel_ms() times the flattened
  * inner loop; weld_result_elapsed_ms() the whole call. */
 weld_status_t weld_nested_for(const weld_nested_t* loop, const weld_builder_t* builders, weld_result_t** out);
 

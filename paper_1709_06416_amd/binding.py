@@ -172,7 +172,7 @@ class Nested(C.Structure):
     _fields_ = [("n_outer", C.c_int64), ("outer", Cols), ("start_col", C.c_int32), ("end_col", C.c_int32),
                 ("n_inner", C.c_int64), ("inner", Cols), ("ngather", C.c_int32), ("gather", C.POINTER(Col)),
                 ("gather_len", C.POINTER(C.c_int64)), ("inner_body", Body), ("inner_type", C.c_int32),
-                ("inner_func", C.c_int32), ("outer_body", Body)]
+                ("inner_func", C.c_int32), ("outer_body", Body), ("range_kind", C.c_int32), ("stride_col", C.c_int32)]
 
 
 lib.weld_nested_for.argtypes = [C.POINTER(Nested), C.POINTER(Builder), C.POINTER(C.c_void_p)]
@@ -593,6 +593,9 @@ class MarshalledNested:
         s.inner_type = TYPE_ID[nested.inner_type]
         s.inner_func = FUNC[nested.inner_func]
         s.outer_body = self.mo.body
+        s.range_kind = 1 if getattr(nested, "ranges", "csr") == "any" else 0
+        stride_col = getattr(nested, "stride_col", None)
+        s.stride_col = -1 if stride_col is None else int(stride_col)
 
 
 def nested_for(nested, outer, inner, gather, stream=None, memory_limit=0, tune=None):

@@ -136,6 +136,11 @@ hipError_t launch_dict_slice_build(const SpillMerge& a, int nvals, hipStream_t s
 // earlier step's control block into a later one's.
 hipError_t launch_segments_check(const void* start, const void* end, int is64, int64_t n_outer, int64_t n_inner,
                                  void* err, hipStream_t stream);
+// ranges_offsets: offsets[i] = number of inner elements the outer elements before i visit (start, start +
+// stride, ... below end; stride null = 1), offsets[n_outer] = *total = all of them; bit 8 of *err for a
+// negative start, end < start, end > n_inner or stride < 1.  One work-group.
+hipError_t launch_ranges_offsets(const void* start, const void* end, const void* stride, int is64, int64_t n_outer,
+                                 int64_t n_inner, void* offsets, void* total, void* err, hipStream_t stream);
 hipError_t launch_tile_rows(const void* start, int is64, int64_t n_outer, int64_t tile, int64_t ntiles,
                             void* tile_row, hipStream_t stream);
 hipError_t launch_or_error(void* dst_ctl, const void* src_ctl, hipStream_t stream);

@@ -740,6 +740,75 @@ hipError_t launch_segments_check(const void* start, const void* end, int is64, i
     return hipGetLastError();
 }
 
+// Ranges with strides, possibly overlapping or with gaps: outer element i visits start[i],
+// start[i] + stride[i], ... below end[i], count[i] = ceil((end - start) / stride) inner elements.
+// offsets[i] = count[0] + ... + count[i-1], offsets[n_outer] = the total, which is also written to
+// *total (8 bytes of the control block, so that one copy brings it to the host with the error
+// word).  One work-group: eight consecutive elements per thread and round, a work-group scan per
+// round.  Raises bit 8 of *err for start < 0, end < start, end > n_inner or stride < 1.
+template <class T>
+__global__ void __launch_bounds__(1024) ranges_offsets_kernel(const T* start, const T* end, const T* stride, i64 n_outer,
+                                                              i64 n_inner, i64* offsets, i64* total, int* err) {
+    __shared__ i64 s_wave[16];
+    __shared__ i64 s_carry;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) s_carry = 0;
+    __syncthreads();
+    bool bad = false;
+    for (i64 base = 0; base < n_outer; base += 8192) {
+        i64 cnt[8];
+        i64 mine = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const i64 r = base + (i64)tid * 8 + k;
+            i64 c = 0;
+            if (r < n_outer) {
+                const i64 s = (i64)start[r], e = (i64)end[r], st = stride ? (i64)stride[r] : 1;
+                if (s < 0 || e < s || e > n_inner || st < 1) bad = true;
+                else c = (e - s + st - 1) / st;
+            }
+            cnt[k] = c;
+            mine += c;
+        }
+        i64 incl = mine;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const i64 o = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += o;
+        }
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        i64 before = s_carry;
+        for (int w = 0; w < wave; ++w) before += s_wave[w];
+        i64 run = before + incl - mine;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const i64 r = base + (i64)tid * 8 + k;
+            if (r < n_outer) offsets[r] = run;
+            run += cnt[k];
+        }
+        __syncthreads();
+        if (tid == 1023) s_carry = run;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        offsets[n_outer] = s_carry;
+        *total = s_carry;
+    }
+    if (bad) atomicOr(err, 8);
+}
+
+hipError_t launch_ranges_offsets(const void* start, const void* end, const void* stride, int is64, int64_t n_outer,
+                                 int64_t n_inner, void* offsets, void* total, void* err, hipStream_t stream) {
+    if (is64)
+        ranges_offsets_kernel<i64><<<dim3(1), dim3(1024), 0, stream>>>((const i64*)start, (const i64*)end, (const i64*)stride, n_outer,
+                                                                      n_inner, (i64*)offsets, (i64*)total, (int*)err);
+    else
+        ranges_offsets_kernel<int><<<dim3(1), dim3(1024), 0, stream>>>((const int*)start, (const int*)end, (const int*)stride, n_outer,
+                                                                      n_inner, (i64*)offsets, (i64*)total, (int*)err);
+    return hipGetLastError();
+}
+
 template <class T>
 __global__ void __launch_bounds__(256) tile_rows_kernel(const T* start, i64 n_outer, i64 tile, i64 ntiles, int* tile_row) {
     const i64 t = (i64)blockIdx.x * 256 + threadIdx.x;

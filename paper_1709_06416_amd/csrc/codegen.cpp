@@ -1354,7 +1354,7 @@ Variant choose_segmented_variant(const Loop& L, const weld_tuning_t& tune, bool 
     return var;
 }
 
-Generated generate_segmented(const Loop& L, const Variant& var, int offset_type) {
+Generated generate_segmented(const Loop& L, const Variant& var, int offset_type, int mapped) {
     Generated G;
     Out o;
     const weld_builder_spec_t& s = L.builders[0];
@@ -1387,7 +1387,9 @@ Generated generate_segmented(const Loop& L, const Variant& var, int offset_type)
         }
     for (int c = 0; c < L.nouter; ++c)
         if (L.outer_used[c]) slot(SLOT_OUTER_COL, c, "o" + std::to_string(c), std::string("const ") + stype(L.outer_type[c]) + "* __restrict__");
-    slot(SLOT_SEG_START, -1, "seg_start", std::string("const ") + ctype(offset_type) + "* __restrict__");
+    slot(SLOT_SEG_START, -1, "seg_start", std::string("const ") + (mapped ? "i64" : ctype(offset_type)) + "* __restrict__");
+    if (mapped) slot(SLOT_MAP_START, -1, "map_start", std::string("const ") + ctype(offset_type) + "* __restrict__");
+    if (mapped == 2) slot(SLOT_MAP_STRIDE, -1, "map_stride", std::string("const ") + ctype(offset_type) + "* __restrict__");
     slot(SLOT_TILE_ROW, -1, "tile_row", "const int* __restrict__");
     slot(SLOT_SUMS, -1, "sums", std::string(A) + "*");
     slot(SLOT_CTL, -1, "ctl", "u32*");
@@ -1422,10 +1424,11 @@ Generated generate_segmented(const Loop& L, const Variant& var, int offset_type)
     o.f("        s_b[k] = (int)rel;\n        if (k < (int)nrows) s_acc[k] = %s;\n      }\n", ID.c_str());
     o.f("      __syncthreads();\n    }\n");
     o.f("    const i64 base = e0 + (i64)wave * W_WAVE_ROWS + lane * W_V;\n");
-    // ---- loads
+    // ---- loads (streamed form; the mapped form gathers them once it knows every position's outer element)
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c]) o.f("    wvec<%s, W_V> x%d[W_U];\n", stype(L.col_type[c]), c);
-    o.f("    if (e0 + W_TILE <= a.n) {\n      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+    if (!mapped) o.f("    if (e0 + W_TILE <= a.n) {\n      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+    if (!mapped) {
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c]) o.f("        x%d[u] = w_load<%s, W_V>(a.c%d + base + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
     o.f("      }\n    } else {\n      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
@@ -1433,6 +1436,7 @@ Generated generate_segmented(const Loop& L, const Variant& var, int offset_type)
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c]) o.f("          x%d[u].e[k] = e < a.n ? a.c%d[e] : (%s)0;\n", c, c, stype(L.col_type[c]));
     o.f("        }\n    }\n");
+    }
     // ---- outer element of every inner element of this lane (relative to r0)
     o.f("    int rowid[W_U][W_V];\n");
     o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
@@ -1452,7 +1456,17 @@ Generated generate_segmented(const Loop& L, const Variant& var, int offset_type)
     o.f("    RowOut o[W_U][W_V];\n");
     o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
     o.f("        const i64 e = base + u * W_UNIT + k;\n");
+    if (mapped) {
+        // position e of outer element `row` is inner element start[row] + (e - boundary[row]) * stride[row]; the
+        // host has checked the ranges (every visited element lies inside the inner vectors) before this kernel runs
+        o.f("        i64 ie = 0;\n        if (e < e1) {\n          const i64 row = r0 + rowid[u][k];\n");
+        o.f("          ie = (i64)a.map_start[row] + (e - a.seg_start[row])%s;\n        }\n", mapped == 2 ? " * (i64)a.map_stride[row]" : "");
+        for (int c = 0; c < L.ncols; ++c)
+            if (L.col_used[c]) o.f("        x%d[u].e[k] = e < e1 ? a.c%d[ie] : (%s)0;\n", c, c, stype(L.col_type[c]));
+        o.f("        if (e < e1) weld_row<false>(ie, r0 + rowid[u][k], a, errp%s, o[u][k]); else weld_row_none(o[u][k]);\n      }\n", call_args.c_str());
+    } else {
     o.f("        if (e < e1) weld_row<false>(e, r0 + rowid[u][k], a, errp%s, o[u][k]); else weld_row_none(o[u][k]);\n      }\n", call_args.c_str());
+    }
     // ---- segmented combine: runs of equal outer element in registers, one atomic per run
     o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
     o.f("      %s acc = %s;\n      bool any = false;\n      int cur = rowid[u][0];\n", A, ID.c_str());

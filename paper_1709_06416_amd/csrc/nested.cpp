@@ -42,6 +42,14 @@ Error build(const weld_nested_t* in, const weld_builder_t* builders, bool need_d
     NL->start_col = in->start_col;
     NL->end_col = in->end_col;
     NL->offset_type = ot;
+    if (in->range_kind != WELD_RANGES_CSR && in->range_kind != WELD_RANGES_ANY) return fail(WELD_ERR_INVALID_ARG, "unknown range kind");
+    NL->any_ranges = in->range_kind == WELD_RANGES_ANY;
+    NL->stride_col = -1;
+    if (NL->any_ranges && in->stride_col != -1) {
+        if (in->stride_col < 0 || in->stride_col >= no) return fail(WELD_ERR_INVALID_ARG, "stride column not among the outer vectors");
+        if (in->outer.col[in->stride_col].type != ot) return fail(WELD_ERR_TYPE, "the stride vector must have the type of start and end");
+        NL->stride_col = in->stride_col;
+    }
 
     // ---- inner body: one merger, may look vectors up and read the current outer element
     NestedContext nc;
@@ -98,7 +106,7 @@ Error build(const weld_nested_t* in, const weld_builder_t* builders, bool need_d
         return Error();
     };
     for (int c = 0; c < no; ++c) {
-        const bool used = NL->outer.col_used[c] || NL->inner.outer_used[c] || c == in->start_col || c == in->end_col;
+        const bool used = NL->outer.col_used[c] || NL->inner.outer_used[c] || c == in->start_col || c == in->end_col || c == NL->stride_col;
         if (!(e = check(in->outer.col[c], in->n_outer, used, "outer vector")).ok()) return e;
         D->outer[c].data = in->outer.col[c].data;
         D->outer[c].type = in->outer.col[c].type;
@@ -138,7 +146,7 @@ weld_status_t weld_nested_precompile(const weld_nested_t* loop, const weld_build
     if (!e.ok()) { set_last_error(e.text); return e.status; }
     for (int aligned = 1; aligned >= 0; --aligned) {
         Variant v1 = choose_segmented_variant(NL.inner, builders->conf.tune, aligned != 0);
-        Generated g1 = generate_segmented(NL.inner, v1, NL.offset_type);
+        Generated g1 = generate_segmented(NL.inner, v1, NL.offset_type, NL.any_ranges ? (NL.stride_col >= 0 ? 2 : 1) : 0);
         Kernel* k = nullptr;
         e = jit_get(g1.source, g1.kernel_name, false, &k);
         if (!e.ok()) { set_last_error(e.text); return e.status; }

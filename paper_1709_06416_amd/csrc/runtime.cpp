@@ -171,7 +171,7 @@ std::string plan_key(const Loop& L, const weld_tuning_t& tune, bool aligned, int
     return k;
 }
 
-// kind 0: fused loop; kind 1: flattened inner loop of a nested for (extra = offset type)
+// kind 0: fused loop; kind 1: flattened inner loop of a nested for (extra = offset type + 16 * how positions map to inner elements)
 // create == false: only a plan that an earlier call made is returned (compiling and loading a kernel
 // allocates device memory, which some callers must not do)
 Error get_plan(const Loop& L, const weld_tuning_t& tune, bool aligned, int kind, int extra, std::shared_ptr<Plan>* out,
@@ -187,7 +187,7 @@ Error get_plan(const Loop& L, const weld_tuning_t& tune, bool aligned, int kind,
                                       "tuning and 16-byte alignment of the columns) before the call that must not allocate");
     auto p = std::make_shared<Plan>();
     p->var = kind == 0 ? choose_variant(L, tune, aligned) : choose_segmented_variant(L, tune, aligned);
-    Generated G = kind == 0 ? generate(L, p->var) : generate_segmented(L, p->var, extra);
+    Generated G = kind == 0 ? generate(L, p->var) : generate_segmented(L, p->var, extra & 15, extra >> 4);
     Error e = jit_get(G.source, G.kernel_name, true, &p->kern);
     if (!e.ok()) return e;
     p->slots = G.slots;
@@ -772,15 +772,57 @@ Error run_nested(const NestedLoop& NL, const NestedData& D, const weld_conf_t& c
     bool aligned = true;
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c] && ((uintptr_t)D.inner[c].data & 15)) aligned = false;
+    const int mapped = NL.any_ranges ? (NL.stride_col >= 0 ? 2 : 1) : 0;
     std::shared_ptr<Plan> plan;
-    Error e = get_plan(L, conf.tune, aligned, 1, NL.offset_type, &plan);
+    Error e = get_plan(L, conf.tune, aligned, 1, NL.offset_type + 16 * mapped, &plan);
     if (!e.ok()) return e;
     const Variant& var = plan->var;
     Kernel* kern = plan->kern;
     r->kernel_name = plan->kernel_name;
-
     const int64_t tile = (int64_t)var.block * var.v * var.u;
-    const int64_t ntiles = (D.n_inner + tile - 1) / tile;
+    const int is64 = NL.offset_type == WELD_I64;
+    const weld_builder_spec_t& ms = L.builders[0];
+    hipError_t h;
+
+    // Ranges with strides, overlaps or gaps: the flattened loop runs over the positions 0 .. total-1, total =
+    // the sum of the ranges' element counts, which a small kernel computes together with their prefix sums
+    // (the boundaries of the outer elements among the positions).  The rest of the call is sized by that
+    // total, so the host waits for it here - and learns whether the ranges are valid before anything
+    // reads through them.
+    int64_t n_flat = D.n_inner;
+    char* pre = nullptr;              // control words of this step, then the prefix sums
+    size_t pre_bytes = 0;
+    if (mapped) {
+        Layout lp;
+        const size_t o_ctl = lp.take(kCtlBytes);
+        const size_t o_off = lp.take(8 * (size_t)(D.n_outer + 1));
+        pre_bytes = lp.total;
+        if (conf.memory_limit > 0 && (int64_t)pre_bytes > conf.memory_limit)
+            return mk(WELD_ERR_OOM, "the ranges' prefix sums need " + std::to_string(pre_bytes) + " bytes of device memory, limit is " +
+                                        std::to_string(conf.memory_limit));
+        void* block = nullptr;
+        e = pool_alloc(pre_bytes, &block);
+        if (!e.ok()) return e;
+        r->blocks.push_back(block);
+        pre = (char*)block;
+        if ((h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+        FillList fl;
+        fl.add(pre + o_ctl, kCtlBytes / 8, 0);
+        if ((h = launch_fill_list(fl, stream)) != hipSuccess) return hip_err("fill", h);
+        h = launch_ranges_offsets(D.outer[NL.start_col].data, D.outer[NL.end_col].data,
+                                  NL.stride_col >= 0 ? D.outer[NL.stride_col].data : nullptr, is64, D.n_outer, D.n_inner,
+                                  pre + o_off, pre + o_ctl + 192, pre + o_ctl + 8, stream);
+        if (h != hipSuccess) return hip_err("ranges offsets", h);
+        r->kernel_count += 2;
+        if ((h = hipMemcpyAsync(r->host_ctl, pre + o_ctl, kCtlBytes, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_err("hipMemcpyAsync", h);
+        if ((h = hipStreamSynchronize(stream)) != hipSuccess) return hip_err("hipStreamSynchronize", h);
+        if (r->host_ctl[2] & 8)
+            return mk(WELD_ERR_INVALID_ARG, "a range of the nested loop is invalid (start < 0, end < start, end > n_inner or stride < 1)");
+        memcpy(&n_flat, (const char*)r->host_ctl + 192, 8);
+        memset(r->host_ctl, 0, kCtlBytes);
+        pre += o_off;                 // from here on: the prefix sums
+    }
+    const int64_t ntiles = (n_flat + tile - 1) / tile;
     const int per_cu = plan->per_cu;
     int64_t grid = conf.tune.grid_blocks > 0 ? conf.tune.grid_blocks : (int64_t)device_info().cus * per_cu;
     if (grid > ntiles) grid = ntiles;
@@ -790,27 +832,29 @@ Error run_nested(const NestedLoop& NL, const NestedData& D, const weld_conf_t& c
     const size_t off_ctl = lay.take(kCtlBytes);
     const size_t off_tiles = lay.take(4 * (size_t)(ntiles + 1));
     const size_t off_sums = lay.take(8 * (size_t)(D.n_outer > 0 ? D.n_outer : 1));
-    if (conf.memory_limit > 0 && (int64_t)lay.total > conf.memory_limit)
-        return mk(WELD_ERR_OOM, "the inner loop needs " + std::to_string(lay.total) + " bytes of device memory, limit is " +
+    if (conf.memory_limit > 0 && (int64_t)(lay.total + pre_bytes) > conf.memory_limit)
+        return mk(WELD_ERR_OOM, "the inner loop needs " + std::to_string(lay.total + pre_bytes) + " bytes of device memory, limit is " +
                                     std::to_string(conf.memory_limit));
     void* block = nullptr;
     e = pool_alloc(lay.total, &block);
     if (!e.ok()) return e;
     r->blocks.push_back(block);
     char* base = (char*)block;
-    const weld_builder_spec_t& ms = L.builders[0];
+    const void* boundaries = mapped ? (const void*)pre : D.outer[NL.start_col].data;
 
     std::vector<uint64_t> args;
     for (const Slot& s : plan->slots) {
         uint64_t v = 0;
         switch (s.kind) {
-            case SLOT_N: v = (uint64_t)D.n_inner; break;
+            case SLOT_N: v = (uint64_t)n_flat; break;
             case SLOT_N_OUTER: v = (uint64_t)D.n_outer; break;
             case SLOT_COL: v = (uint64_t)(uintptr_t)D.inner[s.builder].data; break;
             case SLOT_GATHER: v = (uint64_t)(uintptr_t)D.gather[s.builder].data; break;
             case SLOT_GATHER_LEN: v = (uint64_t)D.gather_len[s.builder]; break;
             case SLOT_OUTER_COL: v = (uint64_t)(uintptr_t)D.outer[s.builder].data; break;
-            case SLOT_SEG_START: v = (uint64_t)(uintptr_t)D.outer[NL.start_col].data; break;
+            case SLOT_SEG_START: v = (uint64_t)(uintptr_t)boundaries; break;
+            case SLOT_MAP_START: v = (uint64_t)(uintptr_t)D.outer[NL.start_col].data; break;
+            case SLOT_MAP_STRIDE: v = (uint64_t)(uintptr_t)D.outer[NL.stride_col].data; break;
             case SLOT_TILE_ROW: v = (uint64_t)(uintptr_t)(base + off_tiles); break;
             case SLOT_SUMS: v = (uint64_t)(uintptr_t)(base + off_sums); break;
             case SLOT_CTL: v = (uint64_t)(uintptr_t)(base + off_ctl); break;
@@ -818,18 +862,20 @@ Error run_nested(const NestedLoop& NL, const NestedData& D, const weld_conf_t& c
         }
         args.push_back(v);
     }
-    hipError_t h;
-    const int is64 = NL.offset_type == WELD_I64;
-    if ((h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    if (!mapped && (h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     FillList fills;
     fills.add(base + off_ctl, kCtlBytes / 8, 0);
     fills.add(base + off_sums, D.n_outer, ident_bits(ms.func, ms.val_type[0]));
     if ((h = launch_fill_list(fills, stream)) != hipSuccess) return hip_err("fill", h);
-    if ((h = launch_segments_check(D.outer[NL.start_col].data, D.outer[NL.end_col].data, is64, D.n_outer, D.n_inner,
-                                   base + off_ctl + 8, stream)) != hipSuccess) return hip_err("segments check", h);
-    if ((h = launch_tile_rows(D.outer[NL.start_col].data, is64, D.n_outer, tile, ntiles, base + off_tiles, stream)) != hipSuccess)
+    r->kernel_count++;
+    if (!mapped) {
+        if ((h = launch_segments_check(D.outer[NL.start_col].data, D.outer[NL.end_col].data, is64, D.n_outer, D.n_inner,
+                                       base + off_ctl + 8, stream)) != hipSuccess) return hip_err("segments check", h);
+        r->kernel_count++;
+    }
+    if ((h = launch_tile_rows(boundaries, mapped ? 1 : is64, D.n_outer, tile, ntiles, base + off_tiles, stream)) != hipSuccess)
         return hip_err("tile rows", h);
-    r->kernel_count += 3;
+    r->kernel_count++;
     if ((h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     if (ntiles > 0 && D.n_outer > 0) {
         e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream);
@@ -845,7 +891,7 @@ Error run_nested(const NestedLoop& NL, const NestedData& D, const weld_conf_t& c
     cols[NL.outer.ncols - 1].type = ms.val_type[0];
     weld_conf_t conf2 = conf;
     if (conf.memory_limit > 0) {
-        conf2.memory_limit = conf.memory_limit - (int64_t)lay.total;
+        conf2.memory_limit = conf.memory_limit - (int64_t)(lay.total + pre_bytes);
         if (conf2.memory_limit <= 0) return mk(WELD_ERR_OOM, "no device memory left for the outer loop under the limit");
     }
     return run_fused(NL.outer, cols, D.n_outer, conf2, r, base + off_ctl);

@@ -190,6 +190,7 @@ enum SlotKind {
     SLOT_DLOG, SLOT_DQCNT, SLOT_DQCAP,              // dictmerger spill queues
     // flattened inner loop of a nested for
     SLOT_N_OUTER, SLOT_GATHER, SLOT_GATHER_LEN, SLOT_OUTER_COL, SLOT_SEG_START, SLOT_TILE_ROW, SLOT_SUMS,
+    SLOT_MAP_START, SLOT_MAP_STRIDE,    // ranges with strides: the caller's start and stride vectors
     // dictionaries probed by the body
     SLOT_PKEYS, SLOT_PHDR, SLOT_PSLOTS, SLOT_PVAL
 };
@@ -215,7 +216,11 @@ Generated generate(const Loop& loop, const Variant& var);
 // offset_type is the type of the outer start/end vectors.  Uses var.block / v / u / aligned and
 // var.lds_slots (range boundaries a tile stages in LDS).
 Variant choose_segmented_variant(const Loop& loop, const weld_tuning_t& tune, bool aligned);
-Generated generate_segmented(const Loop& loop, const Variant& var, int offset_type);
+// mapped: 0 = consecutive ranges (position p of the flattened loop IS inner element p, the inner vectors are
+// streamed); 1 / 2 = ranges with gaps, overlaps and (2) a stride vector: the boundaries are the prefix sums of
+// the ranges' element counts (64-bit), position p of outer element r is inner element
+// start[r] + (p - boundary[r]) * stride[r], and the inner vectors are gathered.
+Generated generate_segmented(const Loop& loop, const Variant& var, int offset_type, int mapped = 0);
 int key_bits(const weld_builder_spec_t& b);
 
 // jit.cpp
@@ -250,6 +255,8 @@ struct NestedLoop {
     Loop inner, outer;
     int start_col = 0, end_col = 0;
     int offset_type = WELD_I64;
+    bool any_ranges = false;    // ranges with strides, overlaps and gaps: positions mapped to inner elements
+    int stride_col = -1;        // any_ranges: outer column with the strides, -1 = all 1
 };
 struct NestedData {
     int64_t n_outer = 0, n_inner = 0;

@@ -176,6 +176,97 @@ def test_ranges_that_are_not_consecutive_are_rejected(wb):
         res.free()
 
 
+def _column_sums(offsets="i64"):
+    p = NestedProgram([offsets] * 3, 0, 1, ["f64"], [], "f64", "add", stride_col=2, ranges="any")
+    p.inner.merge(0, p.inner.col(0))
+    p.outer.merge(p.outer.vecbuilder("f64"), p.outer.inner())
+    p.outer.merge(p.outer.merger("f64", "add"), p.outer.inner())
+    return p
+
+
+def test_strided_ranges_hand_worked_and_matrix_columns(wb):
+    # the 3 x 4 matrix 0..11 stored row by row: column j is start = j, end = 12, stride = 4 (Sec. 3.2: a loop's
+    # start, end and stride per vector); the sums are written out, not computed
+    m = np.arange(12, dtype=np.float64)
+    outer = [np.array(c, dtype=np.int64) for c in ([0, 1, 2, 3], [12, 12, 12, 12], [4, 4, 4, 4])]
+    res = wb.nested_for(_column_sums(), [_dev(c) for c in outer], [_dev(m)], []).check()
+    assert res.vec_host(0).tolist() == [12.0, 15.0, 18.0, 21.0] and float(res.merger(1)) == 66.0
+    res.free()
+    # overlapping, empty, gapped, stride past the end: elements [1,4,7], [2], [], [0,2,4,6,8], [5]
+    outer = [np.array(c, dtype=np.int64) for c in ([1, 2, 6, 0, 5], [8, 3, 6, 9, 7], [3, 7, 2, 2, 100])]
+    res = wb.nested_for(_column_sums(), [_dev(c) for c in outer], [_dev(m)], []).check()
+    assert res.vec_host(0).tolist() == [12.0, 2.0, 0.0, 20.0, 5.0]
+    res.free()
+    # every column of a 700 x 1300 matrix (columns of 700 elements, each a 1300-element stride apart) and
+    # every row (stride 1) in one call, against the oracle and against numpy's own axis sums
+    rows, cols = 700, 1300
+    a = np.random.RandomState(8).uniform(0.5, 1.5, size=(rows, cols))
+    start = np.concatenate([np.arange(cols), np.arange(rows) * cols])
+    end = np.concatenate([np.full(cols, rows * cols), (np.arange(rows) + 1) * cols])
+    stride = np.concatenate([np.full(cols, cols), np.ones(rows, dtype=np.int64)])
+    for offsets in ("i64", "i32"):
+        dt = np.int64 if offsets == "i64" else np.int32
+        outer = [start.astype(dt), end.astype(dt), stride.astype(dt)]
+        _check(wb, _column_sums(offsets), outer, [a.reshape(-1)], [], label="matrix " + offsets)
+        res = wb.nested_for(_column_sums(offsets), [_dev(c) for c in outer], [_dev(a.reshape(-1))], []).check()
+        got = res.vec_host(0)
+        res.free()
+        assert np.allclose(got[:cols], a.sum(axis=0), rtol=1e-12) and np.allclose(got[cols:], a.sum(axis=1), rtol=1e-12)
+
+
+@pytest.mark.parametrize("n_outer,n_inner,span", [(0, 0, 0), (1, 1, 1), (7, 0, 0), (5_000, 300, 40), (3, 500_000, 400_000),
+                                                  (60_000, 100_000, 9), (400_000, 50, 0), (2_000, 70_000, 5_000)])
+def test_any_ranges_shapes(wb, n_outer, n_inner, span):
+    """Ranges drawn independently (overlaps, gaps, empty ranges, one range longer than many tiles, far more
+    outer elements than positions so that a tile holds more boundaries than LDS stages), with and
+    without a stride vector; `index` and the current outer element are visible in the inner body."""
+    rnd = np.random.RandomState(n_outer * 7 + n_inner)
+    for with_stride in (False, True):
+        start = rnd.randint(0, max(n_inner, 1), size=n_outer).astype(np.int64)
+        length = rnd.randint(0, span + 1, size=n_outer)
+        stride = rnd.choice([1, 2, 5, 64, 999], size=n_outer).astype(np.int64)
+        end = np.minimum(n_inner, start + length * (stride if with_stride else 1)).astype(np.int64)
+        start = np.minimum(start, end)
+        scale = rnd.randint(-3, 4, size=n_outer).astype(np.int64)
+        a = rnd.randint(-4, 5, size=n_inner).astype(np.int64)
+        cols = ["i64", "i64", "i64", "i64"] if with_stride else ["i64", "i64", "i64"]
+        p = NestedProgram(cols, 0, 1, ["i64"], [], "i64", "add", stride_col=3 if with_stride else None, ranges="any")
+        q = p.inner
+        v = q.bin("add", q.bin("mul", q.col(0), q.outer(2)), q.bin("mod", q.index(), q.const("i64", 11)))
+        q.merge(0, v, pred=q.bin("ne", q.col(0), q.const("i64", 3)))
+        o = p.outer
+        o.merge(o.vecbuilder("i64"), o.inner())
+        o.merge(o.merger("i64", "max"), o.inner(), pred=o.bin("lt", o.col(0), o.col(1)))
+        outer = [start, end, scale] + ([stride] if with_stride else [])
+        _check(wb, p, outer, [a], [], label="any ranges %d %d stride %s" % (n_outer, n_inner, with_stride))
+
+
+def test_invalid_ranges_fail_the_call(wb):
+    m = _dev(np.arange(100, dtype=np.float64))
+    for bad in (([0, -1], [5, 5], [1, 1]), ([0, 7], [5, 6], [1, 1]), ([0, 1], [5, 101], [1, 1]), ([0, 1], [5, 5], [1, 0])):
+        outer = [_dev(np.array(c, dtype=np.int64)) for c in bad]
+        with pytest.raises(wb.WeldError) as e:
+            wb.nested_for(_column_sums(), outer, [m], [])
+        assert e.value.status == wb.ERR_INVALID_ARG and "range" in str(e.value)
+    q = NestedProgram(["i64", "i64", "i32"], 0, 1, ["f64"], [], "f64", "add", ranges="any")
+    q.stride_col = 2                                                   # a stride vector of another type than start / end
+    q.inner.merge(0, q.inner.col(0))
+    q.outer.merge(q.outer.vecbuilder("f64"), q.outer.inner())
+    st, text = wb.nested_validate(q)
+    assert st == wb.ERR_TYPE, text
+
+
+@pytest.mark.parametrize("group", range(3))
+def test_random_nested_programs_over_any_ranges(wb, group):
+    from workloads import random_programs
+    for seed in range(3000 + 8 * group, 3008 + 8 * group):
+        nested, outer, inner, gather = random_programs.make_nested(seed, any_ranges=True)
+        label = "random nested program over any ranges, seed %d (%d outer, %d inner rows, %s %s, stride %s)" % (
+            seed, len(outer[0]), len(inner[0]), nested.inner_type, nested.inner_func, nested.stride_col)
+        print(label, flush=True)
+        _check(wb, nested, outer, inner, gather, label=label)
+
+
 def test_lookup_outside_its_vector_is_reported(wb):
     rowptr, src, weight, _ = _graph(5_000)
     x = np.ones(4_000)                                                     # shorter than the vertex count

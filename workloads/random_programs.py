@@ -284,11 +284,13 @@ def make_probe(seed):
     return gb.p, build_cols, probe, probe_cols, inits
 
 
-def make_nested(seed):
+def make_nested(seed, any_ranges=False):
     """A random `for` nested in a `for`: (NestedProgram, outer columns, inner columns, gather vectors).
     Inner ranges are consecutive (a CSR row-pointer array split into its start and end columns),
     with empty, short and long ranges mixed; the inner body may read the current outer element and
-    look values up in the gather vectors at reduced (in-range) positions."""
+    look values up in the gather vectors at reduced (in-range) positions.
+    any_ranges: the ranges are drawn independently instead - they overlap, leave gaps, some are
+    empty - and (two times in three) every range carries a stride of its own."""
     rnd = np.random.RandomState(seed)
     n_outer = int(rnd.choice([1, 50, 3_000, 40_000]))
     inner_type = str(rnd.choice(["i64", "f64"]))
@@ -306,11 +308,27 @@ def make_nested(seed):
     inner_cols = [str(rnd.choice(["i8", "i32", "i64", "f64"])) for _ in range(int(rnd.randint(1, 4)))]
     gather_types = [str(rnd.choice(["i32", "i64", "f64"])) for _ in range(int(rnd.randint(0, 3)))]
     gather_len = [int(rnd.choice([1, 7, 1_000, 5_000])) for _ in gather_types]
-    nested = NestedProgram([offsets_type, offsets_type] + extra_outer, 0, 1, inner_cols, gather_types, inner_type, inner_func)
+    with_stride = any_ranges and seed % 3 != 0
+    first_extra = 3 if with_stride else 2
+    nested = NestedProgram([offsets_type] * first_extra + extra_outer, 0, 1, inner_cols, gather_types, inner_type, inner_func,
+                           stride_col=2 if with_stride else None, ranges="any" if any_ranges else "csr")
+    ranges = [rowptr[:-1].copy(), rowptr[1:].copy()]
+    if any_ranges:
+        n_inner = max(n_inner, 1)
+        strides = rnd.choice([1, 1, 2, 3, 17, 1000], size=n_outer) if with_stride else np.ones(n_outer, dtype=np.int64)
+        start = rnd.randint(0, n_inner, size=n_outer)
+        span = lengths * strides                                   # about `lengths` elements each, whatever the stride
+        end = np.minimum(n_inner, start + span)
+        if never_empty:
+            start = np.minimum(start, n_inner - 1)
+            end = np.maximum(end, start + 1)
+        ranges = [start.astype(NP[offsets_type]), end.astype(NP[offsets_type])]
+        if with_stride:
+            ranges.append(strides.astype(NP[offsets_type]))
 
     gi = _Gen(rnd, nested.inner)
     for k, t in enumerate(extra_outer):
-        gi._add(nested.inner.outer(2 + k), COL_MAG[t])
+        gi._add(nested.inner.outer(first_extra + k), COL_MAG[t])
     for k, t in enumerate(gather_types):
         src = gi.some(str(rnd.choice(INTS)))
         wide = src if nested.inner.type_of(src) == "i64" else gi._add(nested.inner.un("cast", src, to="i64"), gi.mag[src])
@@ -348,7 +366,7 @@ def make_nested(seed):
         else:
             t = str(rnd.choice(INTS + ("f64",)))
             nested.outer.merge(nested.outer.vecbuilder(t), go.some(t), pred=go.pred())
-    outer = [rowptr[:-1].copy(), rowptr[1:].copy()] + [random_column(rnd, t, n_outer) for t in extra_outer]
+    outer = ranges + [random_column(rnd, t, n_outer) for t in extra_outer]
     inner = [random_column(rnd, t, n_inner) for t in inner_cols]
     gather = [random_column(rnd, t, m) for t, m in zip(gather_types, gather_len)]
     return nested, outer, inner, gather
