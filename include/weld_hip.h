@@ -54,10 +54,15 @@ typedef enum { WELD_BOOL = 0, WELD_I8 = 1, WELD_I32 = 2, WELD_I64 = 3, WELD_F64 
 
 /* Expression operators of the loop body (Sec. 3.2: arithmetic, comparisons, select;
  * exp/log/sqrt/erf are the math operators the Black-Scholes workload of Sec. 7.1 needs;
- * exp and log come from the device math library, erf is evaluated by the library itself:
- * a piecewise polynomial, within 1e-15 relative of the correctly rounded value).
+ * exp, log and erf are evaluated by the library itself - tables and polynomials, within about
+ * one unit in the last place (1e-15 relative) of the correctly rounded value - unless
+ * weld_tuning_t.device_math asks for the device math library's exp and log).
  * Integers wrap modulo 2^w; integer DIV and MOD truncate toward zero; f64 is IEEE
- * round-to-nearest with one rounding per operator (no contraction). */
+ * round-to-nearest with one rounding per operator (no contraction).
+ * Where the paper is silent the library fixes one behaviour (its tests pin it): an integer x / 0 is 0
+ * and x % 0 is 0; the most negative value over -1 wraps to itself (remainder 0); MIN / MAX of anything
+ * with a NaN is NaN, as operators and as merge functions; a CAST of f64 to an integer truncates toward
+ * zero, NaN gives 0 and values beyond the 64-bit range its nearest end (narrower types then wrap). */
 typedef enum {
     WELD_OP_COL = 0,   /* a = column index: the i-th element of that zipped vector        */
     WELD_OP_CONST = 1, /* imm: i64 bits for integer/bool types, f64 for WELD_F64          */

@@ -30,7 +30,11 @@ What it follows (paper, Sec. 3.2 and Table 1; Sec. 3.3 for the macros):
     runs the outer body over the outer elements with those results as a column.
 
 Readings where the paper is silent: integers wrap modulo 2^w; integer div/mod
-truncate toward zero (C); no implicit promotion (a `cast` op is required); f64
+truncate toward zero (C), a zero divisor gives quotient 0 and remainder 0, the most
+negative value over -1 wraps to itself (remainder 0); min / max (operator and merge
+function) of anything with a NaN is NaN; a cast of f64 to an integer truncates, NaN gives
+0 and values beyond the 64-bit range its nearest end (narrower types then wrap); no
+implicit promotion (a `cast` op is required); f64
 is IEEE round-to-nearest with one rounding per operator and no contraction;
 dictionary entries are returned sorted by key (the paper leaves them
 unordered, so callers compare sorted).
@@ -73,9 +77,34 @@ def identity(func, t):
 
 
 def _trunc_div(a, b):
-    """Integer quotient rounded toward zero, exact in the operand type."""
-    r = np.fmod(a, b)
-    return (a - r) // b
+    """Integer quotient rounded toward zero, exact in the operand type.  Where the paper is
+    silent: a zero divisor gives quotient 0; the most negative value over -1 wraps to itself."""
+    safe = np.where(b == 0, 1, b)
+    r = np.fmod(a, safe)
+    q = np.where(safe == -1, np.negative(a), (a - r) // np.where(safe == -1, 1, safe))   # -a wraps for the most negative a
+    return np.where(b == 0, 0, q).astype(a.dtype)
+
+
+def _trunc_mod(a, b):
+    """Integer remainder with the sign of the dividend (C); 0 for a zero divisor and for -1."""
+    safe = np.where((b == 0) | (b == -1), 1, b)
+    return np.where((b == 0) | (b == -1), 0, np.fmod(a, safe)).astype(a.dtype)
+
+
+def _minmax(code, a, b):
+    """min / max; a NaN operand gives NaN (numpy's minimum / maximum do that for floats)."""
+    return np.minimum(a, b) if code == "min" else np.maximum(a, b)
+
+
+def _f64_to_i64(x):
+    """Truncation toward zero; where the paper is silent: NaN gives 0, values beyond the 64-bit range
+    the nearest end of it."""
+    t = np.trunc(x)
+    inside = (t >= -9.223372036854775808e18) & (t < 9.223372036854775808e18)
+    out = np.where(inside, t, 0.0).astype(np.int64)
+    out = np.where(t >= 9.223372036854775808e18, np.iinfo(np.int64).max, out)
+    out = np.where(t < -9.223372036854775808e18, np.iinfo(np.int64).min, out)
+    return out
 
 
 def _probe(table, key_cols):
@@ -135,7 +164,7 @@ def eval_columns(program, columns, n=None, gather=None, outer=None, inner=None, 
             elif code == "cast":
                 src = a[0]
                 if src.dtype == np.float64 and t in INT_TYPES:
-                    out = np.trunc(src).astype(np.int64).astype(dt)
+                    out = _f64_to_i64(src).astype(dt)
                 else:
                     out = src.astype(dt)
             elif code == "exp":
@@ -155,11 +184,9 @@ def eval_columns(program, columns, n=None, gather=None, outer=None, inner=None, 
             elif code == "div":
                 out = np.divide(a[0], a[1]) if t == "f64" else _trunc_div(a[0], a[1])
             elif code == "mod":
-                out = np.fmod(a[0], a[1])
-            elif code == "min":
-                out = np.minimum(a[0], a[1])
-            elif code == "max":
-                out = np.maximum(a[0], a[1])
+                out = np.fmod(a[0], a[1]) if t == "f64" else _trunc_mod(a[0], a[1])
+            elif code in ("min", "max"):
+                out = _minmax(code, a[0], a[1])
             elif code in _COMPARE:
                 assert a[0].dtype == a[1].dtype, "compare needs equal types"
                 out = _COMPARE[code](a[0], a[1])

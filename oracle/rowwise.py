@@ -25,12 +25,20 @@ def _wrap(x, t):
 
 
 def _tdiv(a, b):
+    if b == 0:
+        return 0                            # reading: a zero divisor gives quotient 0 (and remainder 0)
     q = abs(a) // abs(b)
     return q if (a < 0) == (b < 0) else -q
 
 
 def _tmod(a, b):
+    if b == 0:
+        return 0
     return a - _tdiv(a, b) * b
+
+
+def _isnan(x):
+    return isinstance(x, float) and x != x
 
 
 def _apply(code, t, a):
@@ -57,6 +65,8 @@ def _apply(code, t, a):
         return _wrap(_tdiv(a[0], a[1]), t) if isint else a[0] / a[1]
     if code == "mod":
         return _tmod(a[0], a[1]) if isint else math.fmod(a[0], a[1])
+    if code in ("min", "max") and (_isnan(a[0]) or _isnan(a[1])):
+        return math.nan                     # reading: NaN in, NaN out
     if code == "min":
         return a[0] if a[0] <= a[1] else a[1]
     if code == "max":
@@ -88,6 +98,12 @@ def _cast(x, src, dst):
     if dst == "f64":
         return float(x)
     if src == "f64":
+        if x != x:
+            return 0                        # reading: NaN casts to 0
+        if x >= 9.223372036854775808e18:
+            return _wrap((1 << 63) - 1, dst)   # beyond the 64-bit range: its nearest end, then wrapped to dst
+        if x < -9.223372036854775808e18:
+            return _wrap(-(1 << 63), dst)
         return _wrap(int(x), dst)          # int() truncates toward zero
     return _wrap(int(x), dst)
 
@@ -97,6 +113,8 @@ def _combine(func, t, acc, v):
         return _wrap(acc + v, t) if t in BITS else acc + v
     if func == "mul":
         return _wrap(acc * v, t) if t in BITS else acc * v
+    if _isnan(v) or _isnan(acc):
+        return math.nan
     if func == "min":
         return v if v < acc else acc
     return v if v > acc else acc

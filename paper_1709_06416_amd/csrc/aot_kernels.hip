@@ -52,12 +52,13 @@ hipError_t launch_fill_list(const FillList& f, hipStream_t stream) {
 // (one work-group per merger).  Thread j folds partials j, j+256, ... in that order,
 // then the 256 per-thread values are combined by a fixed butterfly and in wavefront
 // order, so the result is the same on every run.
+// (min / max of anything with a NaN is NaN, as in the loop kernels: `b != b` is never true for integers)
 template <class T> __device__ T combine(int func, T a, T b) {
     switch (func) {
         case 0: return a + b;
         case 1: return a * b;
-        case 2: return b < a ? b : a;
-        default: return b > a ? b : a;
+        case 2: return b != b ? b : (b < a ? b : a);
+        default: return b != b ? b : (b > a ? b : a);
     }
 }
 template <class T> __device__ T block_combine(int func, T v, T ident, T* scratch) {

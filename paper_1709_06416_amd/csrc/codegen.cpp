@@ -181,7 +181,7 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
             case WELD_OP_CAST: {
                 const int st = L.ops[q.a].type;
                 if (q.type == WELD_BOOL) o.f("(t%d != 0)", q.a);
-                else if (st == WELD_F64 && type_is_int(q.type)) o.f("(%s)(i64)t%d", T, q.a);
+                else if (st == WELD_F64 && type_is_int(q.type)) o.f("(%s)w_f64_to_i64(t%d)", T, q.a);
                 else o.f("(%s)t%d", T, q.a);
                 break;
             }
@@ -213,12 +213,18 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
                     if (guarded(i)) o.f("t%d)", need[i]);
                     else o.f("true)");
                 } else {
-                    o.f("(%s)(t%d %s t%d)", T, q.a, div ? "/" : "%", q.b);
+                    o.f("w_%s_int<%s>(t%d, t%d)", div ? "div" : "mod", T, q.a, q.b);
                 }
                 break;
             }
-            case WELD_OP_MIN: o.f("(t%d < t%d ? t%d : t%d)", q.b, q.a, q.b, q.a); break;
-            case WELD_OP_MAX: o.f("(t%d > t%d ? t%d : t%d)", q.b, q.a, q.b, q.a); break;
+            case WELD_OP_MIN:
+                if (q.type == WELD_F64) o.f("w_min_f64(t%d, t%d)", q.a, q.b);
+                else o.f("(t%d < t%d ? t%d : t%d)", q.b, q.a, q.b, q.a);
+                break;
+            case WELD_OP_MAX:
+                if (q.type == WELD_F64) o.f("w_max_f64(t%d, t%d)", q.a, q.b);
+                else o.f("(t%d > t%d ? t%d : t%d)", q.b, q.a, q.b, q.a);
+                break;
             case WELD_OP_LT: o.f("t%d < t%d", q.a, q.b); break;
             case WELD_OP_LE: o.f("t%d <= t%d", q.a, q.b); break;
             case WELD_OP_GT: o.f("t%d > t%d", q.a, q.b); break;

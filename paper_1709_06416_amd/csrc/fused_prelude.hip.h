@@ -94,12 +94,42 @@ __device__ __forceinline__ signed char w_mul_i8(signed char a, signed char b) {
     return (signed char)r;
 }
 
+// ---------------------------------------------------------------- edge values
+// Where the paper is silent, the library fixes (and its tests pin) one behaviour:
+//   min / max of anything with a NaN is NaN (the operator and the merge function alike);
+//   an integer x / 0 is 0 and x % 0 is 0; the most negative value over -1 wraps to itself, remainder 0;
+//   a cast of f64 to an integer truncates, NaN gives 0, values beyond the 64-bit range its nearest end.
+__device__ __forceinline__ double w_min_f64(double a, double b) {
+    const double r = b < a ? b : a;
+    return b != b ? b : r;                  // (a NaN in `a` is already what the compare leaves)
+}
+__device__ __forceinline__ double w_max_f64(double a, double b) {
+    const double r = b > a ? b : a;
+    return b != b ? b : r;
+}
+template <class T> __device__ __forceinline__ T w_div_int(T a, T b) {
+    typedef typename w_carrier<sizeof(T)>::t U;
+    if (b == 0) return 0;
+    if (b == (T)-1) return (T)((U)0 - (U)a);
+    return (T)(a / b);
+}
+template <class T> __device__ __forceinline__ T w_mod_int(T a, T b) {
+    if (b == 0 || b == (T)-1) return 0;
+    return (T)(a % b);
+}
+__device__ __forceinline__ i64 w_f64_to_i64(double x) {
+    if (x != x) return 0;
+    if (x >= 9223372036854775808.0) return 0x7fffffffffffffffll;
+    if (x < -9223372036854775808.0) return (i64)0x8000000000000000ull;
+    return (i64)x;
+}
+
 // ---------------------------------------------------------------- merge functions
 template <int F> __device__ __forceinline__ double w_combine(double a, double b) {
     if (F == W_FUNC_ADD) return a + b;
     if (F == W_FUNC_MUL) return a * b;
-    if (F == W_FUNC_MIN) return b < a ? b : a;
-    return b > a ? b : a;
+    if (F == W_FUNC_MIN) return w_min_f64(a, b);
+    return w_max_f64(a, b);
 }
 // integers wrap: sums and products go through the unsigned type
 template <int F> __device__ __forceinline__ i64 w_combine(i64 a, i64 b) {

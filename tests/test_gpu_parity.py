@@ -573,6 +573,50 @@ def test_narrow_integer_arithmetic_over_all_operand_pairs(wb, t):
         _check(wb, p, [_dev(a), _dev(b)], label="%s arithmetic %s" % (t, ops[0]))
 
 
+def test_edge_values_follow_the_documented_readings(wb):
+    """Where the paper is silent the library fixes one behaviour (include/weld_hip.h) and the oracle follows the
+    same reading: x / 0 = x % 0 = 0, the most negative value over -1 wraps, min / max with a NaN is NaN (operator and
+    merge function), a cast of NaN is 0 and of a value beyond the 64-bit range its nearest end."""
+    for t, np_t in (("i8", np.int8), ("i32", np.int32), ("i64", np.int64)):
+        lo = np.iinfo(np_t).min
+        a = np.array([7, -7, 0, lo, lo, 5, lo, 100] * 300, dtype=np_t)
+        b = np.array([0, 0, 0, -1, 1, -1, 0, 7] * 300, dtype=np_t)
+        p = Program([t, t])
+        p.merge(p.vecbuilder(t), p.bin("div", p.col(0), p.col(1)))
+        p.merge(p.vecbuilder(t), p.bin("mod", p.col(0), p.col(1)))
+        p.merge(p.vecbuilder(t), p.bin("div", p.col(0), p.const(t, -1)))
+        p.merge(p.merger(t, "add"), p.bin("mod", p.col(0), p.const(t, -1)))
+        _check(wb, p, [_dev(a), _dev(b)], label="integer division edges " + t)
+    nan, inf = np.nan, np.inf
+    x = np.array([nan, 1.0, nan, -inf, 2.0, -0.0] * 500)
+    y = np.array([1.0, nan, nan, inf, 3.0, 0.0] * 500)
+    q = Program(["f64", "f64"])
+    q.merge(q.vecbuilder("f64"), q.bin("min", q.col(0), q.col(1)))
+    q.merge(q.vecbuilder("f64"), q.bin("max", q.col(0), q.col(1)))
+    res = wb.fused_for(q, [_dev(x), _dev(y)]).check()
+    mn, mx = res.vec_host(0), res.vec_host(1)
+    res.free()
+    assert np.all(np.isnan(mn.reshape(-1, 6)[:, :3])) and np.all(np.isnan(mx.reshape(-1, 6)[:, :3]))
+    assert np.all(mn.reshape(-1, 6)[:, 3] == -inf) and np.all(mx.reshape(-1, 6)[:, 3] == inf)
+    assert np.all(mn.reshape(-1, 6)[:, 4] == 2.0) and np.all(mx.reshape(-1, 6)[:, 4] == 3.0)
+    for func in ("min", "max"):                                     # one NaN among 70001 merged values
+        v = np.random.RandomState(3).uniform(-5, 5, size=70_001)
+        v[31_337] = nan
+        m = Program(["f64"])
+        m.merge(m.merger("f64", func), m.col(0))
+        m.merge(m.dictmerger(["i64"], ["f64"], func, 4), [m.col(0)], keys=[m.bin("mod", m.index(), m.const("i64", 3))])
+        res = wb.fused_for(m, [_dev(v)]).check()
+        assert np.isnan(float(res.merger(0)))
+        keys, vals = res.dict(1)
+        res.free()
+        assert keys[0].tolist() == [0, 1, 2] and np.isnan(vals[0][31_337 % 3]) and not np.isnan(vals[0][(31_337 + 1) % 3])
+    big = np.array([nan, 1e30, -1e30, 9.3e18, -9.3e18, 9.2e18, inf, -inf, 2.5, -2.5] * 300)
+    c = Program(["f64"])
+    for t in ("i64", "i32", "i8"):
+        c.merge(c.vecbuilder(t), c.un("cast", c.col(0), to=t))
+    _check(wb, c, [_dev(big)], label="casts of NaN and of values beyond the 64-bit range")
+
+
 def test_prepared_loop_runs_repeatedly_on_different_inputs(wb):
     """A loop description marshalled once (prepare) and run on inputs of different sizes, with
     a tuning that differs from the default, matches the oracle every time."""

@@ -158,6 +158,32 @@ def test_integer_div_and_mod_truncate_toward_zero():
         _both([(t, a), (t, b)], lambda p, x, y: p.bin("mod", x, y), [1, -1, 1, -1, 0, 0, 0])
 
 
+def test_edge_values_where_the_paper_is_silent():
+    """The readings both oracle forms (and the kernels) follow: x / 0 = 0 and x % 0 = 0, the most negative
+    value over -1 wraps to itself with remainder 0, min / max with a NaN is NaN, a cast of NaN to an
+    integer is 0 and values beyond the 64-bit range cast to its nearest end (narrower types then wrap)."""
+    lo8, lo32, lo64 = -128, -2 ** 31, -2 ** 63
+    for t, lo in (("i8", lo8), ("i32", lo32), ("i64", lo64)):
+        _both([(t, [7, -7, 0, lo, lo, 5]), (t, [0, 0, 0, -1, 1, -1])], lambda p, x, y: p.bin("div", x, y), [0, 0, 0, lo, lo, -5])
+        _both([(t, [7, -7, 0, lo, lo, 5]), (t, [0, 0, 0, -1, 1, -1])], lambda p, x, y: p.bin("mod", x, y), [0, 0, 0, 0, 0, 0])
+    nan, inf = math.nan, math.inf
+    for op in ("min", "max"):
+        a, b = _map([("f64", [nan, 1.0, nan, -inf]), ("f64", [1.0, nan, nan, inf])], lambda p, x, y, op=op: p.bin(op, x, y))
+        for got in (a, b):
+            assert all(math.isnan(v) for v in got[:3]) and got[3] == (-inf if op == "min" else inf)
+    big = [nan, 1e30, -1e30, 9.3e18, -9.3e18, 9.2e18, inf, -inf]
+    _both([("f64", big)], lambda p, x: p.un("cast", x, to="i64"),
+          [0, 2 ** 63 - 1, lo64, 2 ** 63 - 1, lo64, 9200000000000000000, 2 ** 63 - 1, lo64])
+    _both([("f64", big)], lambda p, x: p.un("cast", x, to="i32"),
+          [0, -1, 0, -1, 0, -1650982912, -1, 0])       # 2^63 - 1 and -2^63 wrapped to 32 bits; 9.2e18 mod 2^32 as a signed value
+    # merge functions: a NaN among the merged values makes a min / max merger NaN
+    for func in ("min", "max"):
+        p = Program(["f64"])
+        p.merge(p.merger("f64", func), p.col(0))
+        vals = [3.0, nan, -2.0, 7.5]
+        assert math.isnan(float(interp.run(p, [np.array(vals)])[0])) and math.isnan(rowwise.run(p, [vals])[0])
+
+
 def test_f64_arithmetic_and_compares():
     x = [0.1, -0.75, 1e16, 3.0]
     y = [0.2, 0.5, 1.0, -2.0]
