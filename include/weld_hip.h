@@ -279,6 +279,26 @@ weld_status_t weld_fused_for_probe(const weld_cols_t* cols, int64_t n, const wel
                                    const weld_body_t* body, const weld_builder_t* builder, weld_result_t** out);
 
 /*
+ * A scalar defined outside the loop as an operand of its body (Sec. 3.2: a loop's function is a
+ * closure over the values in scope; Sec. 4.1: objects depend on other objects' results):
+ *   WELD_OP_SCALAR : a = column index.  That entry of the column list points at ONE element of
+ *                    its type in DEVICE memory, and every row reads that same value.
+ * The typical scalar is the merger result of an earlier call on the same stream
+ * (weld_result_data of that handle): it is read in stream order by the loop's kernel, so no host
+ * copy and no wait lies between the two loops.  A column is read either by WELD_OP_COL or by
+ * WELD_OP_SCALAR, not both; its pointer must be valid even when n is 0; it is accepted by
+ * weld_fused_for (both modes), weld_fused_for_probe and weld_fused_for_static, not in the bodies of
+ * weld_nested_for.
+ */
+enum { WELD_OP_SCALAR = 31 };
+
+/* The DEVICE address of merger result idx, returned WITHOUT waiting for the call's work: what a
+ * later loop on the same stream passes as the column that WELD_OP_SCALAR reads.  The handle must
+ * stay alive until that later call's weld_result_status() has returned.  NULL if idx is not a
+ * merger of this call. */
+const void* weld_result_scalar(const weld_result_t* r, int32_t idx);
+
+/*
  * weld_fused_for_static -- weld_fused_for for callers that cannot allocate device memory: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It calls no
  * hipMalloc, hipFree, hipHostMalloc, event or module routine: the results go to buffers the CALLER

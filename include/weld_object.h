@@ -7,6 +7,13 @@
  * loop to weld_fused_for.  With conf.mode = WELD_MODE_UNFUSED the same program is run one
  * operator at a time instead.
  *
+ * A scalar (a reduce object) may be a dependency of a map (Sec. 4.1: objects depend on other
+ * objects; this is how a library normalises a column by its mean).  A loop cannot read what it is
+ * still reducing, so evaluation then takes STAGES: the scalars that maps read are computed by
+ * earlier fused loops (all scalars of a stage over vectors of one length share one loop; a
+ * reduction written twice is computed once), and the loops that read them take them from device
+ * memory (WELD_OP_SCALAR), in stream order, with no host wait and no host copy in between.
+ *
  *   NewWeldObject(data, type, encoder)  -> weld_object_new_data
  *   NewWeldObject(deps, expr, encoder)  -> weld_object_new_map / _filter / _reduce / _groupby
  *                                          (the macros of Sec. 3.3; encoders are the caller's
@@ -35,9 +42,11 @@ typedef enum { WELD_OBJ_VEC = 0, WELD_OBJ_SCALAR = 1, WELD_OBJ_DICT = 2 } weld_o
  * written, and alive until every evaluation that reaches it has finished. */
 weld_status_t weld_object_new_data(const void* data, int32_t type, int64_t len, weld_object_t** out);
 
-/* map(zip(deps), f): f is an SSA list as in weld_body_t.ops, in which WELD_OP_COL with a = k
- * reads the current element of deps[k] and the LAST op is the value of the new element.
- * All deps must be vectors of the same length that went through the same filters. */
+/* map(zip(deps), f): f is an SSA list as in weld_body_t.ops (operators up to WELD_OP_SELECT), in
+ * which WELD_OP_COL with a = k reads the current element of deps[k] and the LAST op is the value
+ * of the new element.  The vector deps must have the same length and have gone through the same
+ * filters; a dep may also be a scalar (a reduce object), which WELD_OP_COL then reads as the
+ * same value for every element; at least one dep must be a vector. */
 weld_status_t weld_object_new_map(weld_object_t* const* deps, int32_t ndeps, const weld_op_t* ops,
                                   int32_t nops, weld_object_t** out);
 
@@ -57,12 +66,17 @@ int32_t weld_object_elem_type(const weld_object_t* o); /* element / scalar type;
 
 /* Evaluate `nroots` objects together: they must iterate over vectors of one common length.
  * Result i of the handle belongs to roots[i]: a vector root is materialised by a vecbuilder, a
- * scalar root is a merger, a dictionary root a dictmerger.  Returns like weld_fused_for. */
+ * scalar root is a merger, a dictionary root a dictmerger.  Returns like weld_fused_for.
+ * With stages (see above) every loop is enqueued before the call returns; the handle owns the
+ * earlier loops' results, reports the first error among them, counts their kernels and adds
+ * their time to weld_result_elapsed_ms(); weld_result_kernel_ms() and _kernel_name() are those
+ * of the last loop.  A root that an earlier stage has computed is returned from there. */
 weld_status_t weld_object_evaluate(weld_object_t* const* roots, int32_t nroots, const weld_conf_t* conf,
                                    weld_result_t** out);
 
 /* The fused loop that weld_object_evaluate would run, written in the notation of the paper's
- * listings.  Returns the bytes needed including the terminator (negative on error), copies at
+ * listings; with stages, the earlier loops first, each as `let {s0, s1} = <loop>`, then the
+ * roots' loop, in which s0, s1 are parameters beside the zipped vectors.  Returns the bytes needed including the terminator (negative on error), copies at
  * most buflen.  Needs no GPU. */
 int64_t weld_object_describe(weld_object_t* const* roots, int32_t nroots, char* buf, int64_t buflen);
 

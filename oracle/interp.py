@@ -116,6 +116,18 @@ def _probe(table, key_cols):
     return np.fromiter((index.get(key, -1) for key in probe), dtype=np.int64, count=n)
 
 
+def scalar_columns(program):
+    """Entries of the column list that hold one element: scalars defined outside the loop."""
+    return {op[2] for op in program.ops if op[0] == "scalar"}
+
+
+def row_count(program, columns):
+    """Rows of the loop: the length of its zipped vectors (scalars from outside do not count)."""
+    scalars = scalar_columns(program)
+    lengths = [len(c) for k, c in enumerate(columns) if k not in scalars]
+    return lengths[0] if lengths else 0
+
+
 def eval_columns(program, columns, n=None, gather=None, outer=None, inner=None, dicts=None, index=None):
     """Materialise every body expression as a full column (one operator at a time).
 
@@ -124,21 +136,24 @@ def eval_columns(program, columns, n=None, gather=None, outer=None, inner=None, 
     (inner) loop, and the column of inner-loop results seen by an outer body; index: the
     position of each row's element in the inner vectors (an inner loop over ranges).
     """
+    scalars = scalar_columns(program)
     if n is None:
-        n = len(columns[0]) if columns else 0
+        n = row_count(program, columns)
     for k, c in enumerate(columns):
         assert c.dtype == NP_TYPE[program.columns[k]], (k, c.dtype)
-        assert len(c) == n
+        assert len(c) == (1 if k in scalars else n)
     val = []
     with np.errstate(all="ignore"):
         for op in program.ops:
             code, t = op[0], op[1]
             dt = NP_TYPE[t]
             a = ([val[j] for j in op[2:]]
-                 if code not in ("col", "const", "index", "lookup", "outer", "inner", "keyexists", "dictlookup")
+                 if code not in ("col", "scalar", "const", "index", "lookup", "outer", "inner", "keyexists", "dictlookup")
                  else None)
             if code == "col":
                 out = columns[op[2]]
+            elif code == "scalar":                  # a value from outside the loop: the same for every row
+                out = np.full(n, columns[op[2]][0], dtype=dt)
             elif code == "lookup":
                 vec, idx = gather[op[2]], val[op[3]].astype(np.int64)
                 assert idx.size == 0 or (idx.min() >= 0 and idx.max() < len(vec)), "lookup out of range"
@@ -318,7 +333,7 @@ def run(program, columns, sums="exact", inits=None, dicts=None):
     approximates);  sums = "fold": the literal left-to-right f64 fold.
     """
     val = eval_columns(program, columns, dicts=dicts)
-    n = len(columns[0]) if columns else 0
+    n = row_count(program, columns)
     return _results(program, val, n, sums, inits)
 
 

@@ -135,7 +135,7 @@ def _typed(x, t):
     return float(x) if t == "f64" else (bool(x) if t == "bool" else int(x))
 
 
-def _body(program, i, elem, gather=None, outer_elem=None, inner_value=None, dicts=None):
+def _body(program, i, elem, gather=None, outer_elem=None, inner_value=None, dicts=None, scalars=None):
     """Every expression of the body for ONE row: index i, `elem` = this row's element of each
     zipped vector.  Nested loops: `gather` are the vectors lookup may read, `outer_elem` the
     current outer element (inner bodies), `inner_value` the inner loop's result (outer bodies)."""
@@ -144,6 +144,8 @@ def _body(program, i, elem, gather=None, outer_elem=None, inner_value=None, dict
         code, t = op[0], op[1]
         if code == "col":
             val.append(_typed(elem[op[2]], t))
+        elif code == "scalar":
+            val.append(_typed(scalars[op[2]], t))
         elif code == "const":
             val.append(_typed(op[2], t))
         elif code == "index":
@@ -196,7 +198,10 @@ def run(program, columns, inits=None, inner_results=None, dicts=None):
     vecmerger -> list (inits: {builder index: list}), groupbuilder -> {key tuple: list of values}.
     dicts: dictionaries probed by keyexists / dictlookup, each {key tuple: [values]} as returned
     for a dictmerger by an earlier run."""
-    n = len(columns[0]) if columns else 0
+    # entries of the column list read by `scalar` hold one element, defined outside the loop
+    scalars = {op[2]: columns[op[2]][0] for op in program.ops if op[0] == "scalar"}
+    lengths = [len(c) for k, c in enumerate(columns) if k not in scalars]
+    n = lengths[0] if lengths else 0
     state = []
     for b, spec in enumerate(program.builders):
         if spec["kind"] == "merger":
@@ -212,8 +217,8 @@ def run(program, columns, inits=None, inner_results=None, dicts=None):
         else:
             state.append({})
     for i in range(n):
-        val = _body(program, i, [c[i] for c in columns],
-                    inner_value=None if inner_results is None else inner_results[i], dicts=dicts)
+        val = _body(program, i, [None if k in scalars else c[i] for k, c in enumerate(columns)],
+                    inner_value=None if inner_results is None else inner_results[i], dicts=dicts, scalars=scalars)
         for m in program.merges:
             if m["pred"] is not None and not val[m["pred"]]:
                 continue                            # `else b`: builder returned untouched

@@ -30,7 +30,7 @@ OPCODE = {"col": 0, "const": 1, "index": 2, "neg": 3, "not": 4, "cast": 5, "exp"
           "erf": 9, "add": 10, "sub": 11, "mul": 12, "div": 13, "mod": 14, "min": 15, "max": 16, "lt": 17,
           "le": 18, "gt": 19, "ge": 20, "eq": 21, "ne": 22, "and": 23, "or": 24, "select": 25,
           "lookup": 26, "outer": 27, "inner": 28,      # these three: include/weld_nested.h
-          "keyexists": 29, "dictlookup": 30}
+          "keyexists": 29, "dictlookup": 30, "scalar": 31}
 KIND = {"merger": 0, "vecbuilder": 1, "dictmerger": 2, "vecmerger": 3, "groupbuilder": 4}
 FUNC = {"add": 0, "mul": 1, "min": 2, "max": 3}
 MODE = {"fused": 0, "unfused": 1}
@@ -125,6 +125,8 @@ lib.weld_result_error.argtypes = [C.c_void_p]
 lib.weld_result_error.restype = C.c_char_p
 lib.weld_result_data.argtypes = [C.c_void_p, C.c_int32]
 lib.weld_result_data.restype = C.c_void_p
+lib.weld_result_scalar.argtypes = [C.c_void_p, C.c_int32]
+lib.weld_result_scalar.restype = C.c_void_p
 lib.weld_result_fetch.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_int64, C.c_int32]
 lib.weld_result_fetch.restype = C.c_int
 lib.weld_result_elapsed_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
@@ -352,6 +354,13 @@ class Result:
         t = self._program.builders[idx]["type"]
         return self._fetch_host(idx, 0, np.dtype(TYPE_NP[t]).itemsize).view(TYPE_NP[t])[0]
 
+    def scalar_ref(self, idx):
+        """The merger result idx where it lies in device memory, without waiting for it."""
+        p = lib.weld_result_scalar(self._h, idx)
+        if not p:
+            raise WeldError(ERR_INVALID_ARG, "result %d is not a merger" % idx)
+        return DevScalar(p, self._program.builders[idx]["type"], self)
+
     def vec_len(self, idx):
         self.check()
         p = lib.weld_result_data(self._h, idx)
@@ -434,12 +443,33 @@ class Result:
             pass
 
 
+class DevScalar:
+    """One element in device memory that a later loop reads with the `scalar` operator: the merger
+    result of an earlier call (Result.scalar_ref), used in stream order without a host wait."""
+
+    def __init__(self, ptr, dtype, keep=None):
+        self.ptr, self.dtype, self._keep = ptr, dtype, keep
+
+
 def _zipped_columns(program, columns):
     if len(columns) != len(program.columns):
         raise WeldError(ERR_INVALID_ARG, "column count mismatch")
     cols = (Col * max(len(columns), 1))()
     rows = None
+    scalars = {op[2] for op in program.ops if op[0] == "scalar"}
     for k, t in enumerate(columns):
+        if k in scalars:                          # one element: a DevScalar or a one-element CUDA tensor
+            if isinstance(t, DevScalar):
+                ptr, dt = t.ptr, t.dtype
+            else:
+                if not t.is_cuda or t.numel() != 1:
+                    raise WeldError(ERR_INVALID_ARG, "a scalar operand is one element in device memory")
+                ptr, dt = t.data_ptr(), TORCH_TYPE.get(t.dtype)
+            if dt != program.columns[k]:
+                raise WeldError(ERR_TYPE, "scalar %d: has type %s, declared %s" % (k, dt, program.columns[k]))
+            cols[k].data = ptr
+            cols[k].type = TYPE_ID[program.columns[k]]
+            continue
         if not t.is_cuda or not t.is_contiguous():
             raise WeldError(ERR_INVALID_ARG, "columns must be contiguous CUDA tensors")
         if TORCH_TYPE.get(t.dtype) != program.columns[k]:

@@ -146,7 +146,7 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
     for (int i = (int)L.ops.size() - 1; i >= 0; --i) {
         const weld_op_t& q = L.ops[i];
         if (need[i] == kUnused || q.opcode == WELD_OP_COL || q.opcode == WELD_OP_CONST || q.opcode == WELD_OP_INDEX ||
-            q.opcode == WELD_OP_OUTER)
+            q.opcode == WELD_OP_OUTER || q.opcode == WELD_OP_SCALAR)
             continue;
         const bool dict_op = q.opcode == WELD_OP_KEYEXISTS || q.opcode == WELD_OP_DICTLOOKUP;
         if (q.opcode != WELD_OP_LOOKUP && !dict_op) mark(q.a, need[i]);      // for those two, a is a vector / dictionary index
@@ -163,6 +163,8 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
     if (segmented || L.ndicts > 0) o.f(", const KArgs& a, int* errp");
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c]) o.f(", const %s x%d", stype(L.col_type[c]), c);
+    for (int c = 0; c < L.ncols; ++c)
+        if (L.col_scalar[c]) o.f(", const %s sc%d", stype(L.col_type[c]), c);
     o.f(", RowOut& o) {\n");
     for (size_t i = 0; i < L.ops.size(); ++i) {
         const weld_op_t& q = L.ops[i];
@@ -171,6 +173,7 @@ void emit_row_function(Out& o, const Loop& L, bool segmented = false) {
         o.f("  const %s t%d = ", T, id);
         switch (q.opcode) {
             case WELD_OP_COL: o.f("x%d", q.a); break;
+            case WELD_OP_SCALAR: o.f("sc%d", q.a); break;
             case WELD_OP_CONST: o.f("%s", const_expr(q).c_str()); break;
             case WELD_OP_INDEX: o.f("i"); break;
             case WELD_OP_NEG:
@@ -606,6 +609,8 @@ Generated generate(const Loop& L, const Variant& var) {
     slot(SLOT_SPIN, -1, 0, "spin_limit", "i64");
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c]) slot(SLOT_COL, c, 0, "c" + std::to_string(c), std::string("const ") + stype(L.col_type[c]) + "* __restrict__");
+    for (int c = 0; c < L.ncols; ++c)   // scalars from outside the loop: one element each
+        if (L.col_scalar[c]) slot(SLOT_COL, c, 0, "s" + std::to_string(c), std::string("const ") + stype(L.col_type[c]) + "* __restrict__");
     slot(SLOT_CTL, -1, 0, "ctl", "u32*");
     for (int d = 0; d < L.ndicts; ++d) {
         const std::string P = "p" + std::to_string(d);
@@ -867,6 +872,8 @@ Generated generate(const Loop& L, const Variant& var) {
     o.f("extern \"C\" __global__ void __launch_bounds__(W_BLOCK) weld_kernel(const KArgs a) {\n");
     o.f("  __shared__ u64 s_red[W_WAVES];\n");
     o.f("  int* const errp = (int*)(a.ctl + 2);\n");
+    for (int c = 0; c < L.ncols; ++c)
+        if (L.col_scalar[c]) o.f("  const %s sc%d = a.s%d[0];\n", stype(L.col_type[c]), c, c);
     o.f("  const int lane = threadIdx.x & 63;\n  const int wave = threadIdx.x >> 6;\n");
     o.f("  (void)lane; (void)wave; (void)errp;\n");
     int lds = 8 * (var.block / 64) + 4;
@@ -991,6 +998,8 @@ Generated generate(const Loop& L, const Variant& var) {
                 c += ", ";
                 c += buf;
             }
+        for (int k = 0; k < L.ncols; ++k)
+            if (L.col_scalar[k]) c += ", sc" + std::to_string(k);
         c += ", ";
         c += dst;
         c += ");";

@@ -11,9 +11,19 @@
 //   * expressions are hash-consed while lowering, so a sub-computation shared by several
 //     objects - even objects built by different callers - is evaluated once (CSE of Table 3).
 // The fused loop is then submitted through weld_fused_for, fused or operator at a time.
+//
+// A scalar (the result of a reduce) may be an operand of a map (Sec. 4.1: an object depends on
+// other objects; the Pandas / NumPy pipelines of Sec. 4.5 and Sec. 7 normalise by a mean, divide
+// by a sum).  A loop cannot read a value that the same loop is still reducing, so evaluation
+// then runs in STAGES: every scalar that some map reads is computed by an earlier fused loop
+// (all scalars of one stage that iterate over vectors of one length share a loop), and the
+// loops that use it read it from device memory with WELD_OP_SCALAR, in stream order: there is
+// no host wait and no host copy between the stages.
 #include <cstdio>
+#include <algorithm>
 #include <cstring>
 #include <map>
+#include <set>
 #include <string>
 #include <tuple>
 #include <vector>
@@ -63,13 +73,41 @@ struct Virt {
     int value = -1;
     int pred = -1;
     int64_t n = 0;
+    bool scalar = false;   // a reduce result read by a map: the same value for every element
+};
+
+// One input of the fused loop: a caller's vector, or the scalar that an earlier stage computed.
+struct Leaf {
+    const void* data = nullptr;
+    int type = -1;
+    int64_t len = 0;
+    const weld_object* scalar_of = nullptr;
+};
+
+// Scalars that earlier stages have computed (device address) and the name each has in listings.
+struct Scalars {
+    std::map<const weld_object*, const void*> where;
+    std::map<const weld_object*, int> name;
+    std::map<const weld_object*, const weld_object*> same_as;   // a scalar that repeats another one's computation
+    const weld_object* canon(const weld_object* o) const {
+        auto it = same_as.find(o);
+        return it == same_as.end() ? o : it->second;
+    }
+    int id_of(const weld_object* o) {
+        o = canon(o);
+        auto it = name.find(o);
+        if (it != name.end()) return it->second;
+        const int id = (int)name.size();
+        return name[o] = id;
+    }
 };
 
 struct Fuser {
     std::vector<weld_op_t> ops;                 // the fused body, in dependency order
     std::map<std::tuple<int, int, int, int, int, int64_t>, int> cse;
-    std::vector<const weld_object*> leaves;     // column k of the fused loop
+    std::vector<Leaf> leaves;                   // column k of the fused loop
     std::map<const weld_object*, Virt> memo;
+    Scalars* scalars = nullptr;                 // results of earlier stages
 
     int add(weld_op_t o) {
         o.reserved = 0;
@@ -82,9 +120,28 @@ struct Fuser {
     }
     int leaf_column(const weld_object* o) {
         for (size_t k = 0; k < leaves.size(); ++k)
-            if (leaves[k] == o || (leaves[k]->data == o->data && leaves[k]->type == o->type && leaves[k]->len == o->len))
+            if (!leaves[k].scalar_of && leaves[k].data == o->data && leaves[k].type == o->type && leaves[k].len == o->len)
                 return (int)k;
-        leaves.push_back(o);
+        Leaf l;
+        l.data = o->data;
+        l.type = o->type;
+        l.len = o->len;
+        leaves.push_back(l);
+        return (int)leaves.size() - 1;
+    }
+    int scalar_column(const weld_object* o) {
+        if (scalars) o = scalars->canon(o);
+        for (size_t k = 0; k < leaves.size(); ++k)
+            if (leaves[k].scalar_of == o) return (int)k;
+        Leaf l;
+        l.type = o->type;
+        l.len = 1;
+        l.scalar_of = o;
+        if (scalars) {
+            auto it = scalars->where.find(o);
+            if (it != scalars->where.end()) l.data = it->second;
+        }
+        leaves.push_back(l);
         return (int)leaves.size() - 1;
     }
 
@@ -105,17 +162,23 @@ struct Fuser {
             v.n = o->len;
         } else if (o->op == OBJ_MAP) {
             std::vector<Virt> in(o->deps.size());
+            int first = -1;                              // the first dependency that is a vector
             for (size_t k = 0; k < o->deps.size(); ++k) {
                 Error e = lower(o->deps[k], &in[k]);
                 if (!e.ok()) return e;
-                if (k && (in[k].n != in[0].n || in[k].pred != in[0].pred))
+                if (in[k].scalar) continue;
+                if (first < 0) first = (int)k;
+                else if (in[k].n != in[first].n || in[k].pred != in[first].pred)
                     return bad(WELD_ERR_INVALID_ARG, "map over vectors of different length or with different filters");
             }
-            v.n = in.empty() ? 0 : in[0].n;
-            v.pred = in.empty() ? -1 : in[0].pred;
+            if (first < 0 && !in.empty()) return bad(WELD_ERR_INVALID_ARG, "map: at least one dependency must be a vector");
+            v.n = first < 0 ? 0 : in[first].n;
+            v.pred = first < 0 ? -1 : in[first].pred;
             std::vector<int> id(o->ops.size(), -1);
             for (size_t i = 0; i < o->ops.size(); ++i) {
                 weld_op_t q = o->ops[i];
+                if (q.opcode < WELD_OP_COL || q.opcode > WELD_OP_SELECT)
+                    return bad(WELD_ERR_INVALID_ARG, "map: operator " + std::to_string(q.opcode) + " does not belong in a map");
                 if (q.opcode == WELD_OP_COL) {
                     if (q.a < 0 || q.a >= (int)in.size()) return bad(WELD_ERR_INVALID_ARG, "map refers to a dependency it does not have");
                     if (ops[in[q.a].value].type != q.type) return bad(WELD_ERR_TYPE, "map: dependency has a different element type");
@@ -163,8 +226,21 @@ struct Fuser {
                 a.c = -1;
                 v.pred = add(a);
             }
+        } else if (o->op == OBJ_REDUCE) {
+            // a scalar that an earlier stage leaves in device memory: one more input of this loop
+            const int column = scalar_column(o);
+            if (column >= WELD_MAX_COLS) return bad(WELD_ERR_UNSUPPORTED, "more than 16 inputs in one fused loop");
+            weld_op_t c;
+            memset(&c, 0, sizeof c);
+            c.opcode = WELD_OP_SCALAR;
+            c.type = o->type;
+            c.a = column;
+            c.b = c.c = -1;
+            v.value = add(c);
+            v.n = -1;
+            v.scalar = true;
         } else {
-            return bad(WELD_ERR_UNSUPPORTED, "a scalar or dictionary cannot feed another operator without being evaluated first");
+            return bad(WELD_ERR_UNSUPPORTED, "a dictionary cannot feed another operator without being evaluated first");
         }
         memo[o] = v;
         *out = v;
@@ -180,8 +256,9 @@ struct Fused {
     int64_t n = -1;
 };
 
-Error fuse(weld_object* const* roots, int nroots, Fused* F) {
-    if (!roots || nroots < 1 || nroots > WELD_MAX_BUILDERS) return bad(WELD_ERR_INVALID_ARG, "1..8 roots");
+Error fuse(const weld_object* const* roots, int nroots, Scalars* scalars, Fused* F, bool any_count = false) {
+    if (!roots || nroots < 1 || (nroots > WELD_MAX_BUILDERS && !any_count)) return bad(WELD_ERR_INVALID_ARG, "1..8 roots");
+    F->f.scalars = scalars;
     for (int r = 0; r < nroots; ++r) {
         const weld_object* o = roots[r];
         if (!o) return bad(WELD_ERR_INVALID_ARG, "null root");
@@ -250,18 +327,22 @@ const char* fname(int f) {
     return f >= 0 && f <= 3 ? n[f] : "?";
 }
 
-std::string describe(const Fused& F) {
+std::string describe(const Fused& F, Scalars* scalars) {
     const std::vector<weld_op_t>& ops = F.f.ops;
     std::string s = "|";
     char b[256];
+    std::vector<size_t> vecs;                 // the zipped vectors; scalars of earlier stages are parameters only
+    std::vector<int> zip_pos(F.f.leaves.size(), -1);
     for (size_t k = 0; k < F.f.leaves.size(); ++k) {
-        snprintf(b, sizeof b, "%sv%zu: vec[%s]", k ? ", " : "", k, tname(F.f.leaves[k]->type));
+        const Leaf& l = F.f.leaves[k];
+        if (l.scalar_of) snprintf(b, sizeof b, "%ss%d: %s", k ? ", " : "", scalars ? scalars->id_of(l.scalar_of) : (int)k, tname(l.type));
+        else { snprintf(b, sizeof b, "%sv%zu: vec[%s]", k ? ", " : "", k, tname(l.type)); zip_pos[k] = (int)vecs.size(); vecs.push_back(k); }
         s += b;
     }
     s += "|\nresult(for(";
-    if (F.f.leaves.size() != 1) s += "zip(";
-    for (size_t k = 0; k < F.f.leaves.size(); ++k) { snprintf(b, sizeof b, "%sv%zu", k ? ", " : "", k); s += b; }
-    if (F.f.leaves.size() != 1) s += ")";
+    if (vecs.size() != 1) s += "zip(";
+    for (size_t k = 0; k < vecs.size(); ++k) { snprintf(b, sizeof b, "%sv%zu", k ? ", " : "", vecs[k]); s += b; }
+    if (vecs.size() != 1) s += ")";
     s += ", {";
     for (size_t r = 0; r < F.specs.size(); ++r) {
         const weld_builder_spec_t& sp = F.specs[r];
@@ -277,7 +358,8 @@ std::string describe(const Fused& F) {
     auto ref = [&](int id) {
         const weld_op_t& q = ops[id];
         char t[64];
-        if (q.opcode == WELD_OP_COL) snprintf(t, sizeof t, "x.%d", q.a);
+        if (q.opcode == WELD_OP_COL) snprintf(t, sizeof t, "x.%d", zip_pos[q.a]);
+        else if (q.opcode == WELD_OP_SCALAR) snprintf(t, sizeof t, "s%d", scalars ? scalars->id_of(F.f.leaves[q.a].scalar_of) : q.a);
         else if (q.opcode == WELD_OP_INDEX) snprintf(t, sizeof t, "i");
         else if (q.opcode == WELD_OP_CONST) {
             if (q.type == WELD_F64) snprintf(t, sizeof t, "%.17g", q.imm.f64);
@@ -287,7 +369,7 @@ std::string describe(const Fused& F) {
     };
     for (size_t i = 0; i < ops.size(); ++i) {
         const weld_op_t& q = ops[i];
-        if (q.opcode <= WELD_OP_INDEX) continue;
+        if (q.opcode <= WELD_OP_INDEX || q.opcode == WELD_OP_SCALAR) continue;
         std::string e;
         if (q.opcode == WELD_OP_SELECT) e = "select(" + ref(q.a) + ", " + ref(q.b) + ", " + ref(q.c) + ")";
         else if (q.opcode >= WELD_OP_ADD && q.opcode != WELD_OP_MIN && q.opcode != WELD_OP_MAX) e = ref(q.a) + " " + sym[q.opcode] + " " + ref(q.b);
@@ -315,6 +397,194 @@ std::string describe(const Fused& F) {
     }
     s += "}))\n";
     return s;
+}
+
+// ---- staged evaluation -----------------------------------------------------------------------
+
+// The scalars that the vectors below `o` read directly (not those behind another scalar).
+void scalars_below(const weld_object* o, std::set<const weld_object*>* visited, std::vector<const weld_object*>* found) {
+    if (!visited->insert(o).second || o->op == OBJ_DATA) return;
+    for (const weld_object* d : o->deps) {
+        if (d->op == OBJ_REDUCE) {
+            bool known = false;
+            for (const weld_object* f : *found) known = known || f == d;
+            if (!known) found->push_back(d);
+        } else {
+            scalars_below(d, visited, found);
+        }
+    }
+}
+
+// Below a root: a scalar or dictionary root is an operator over vectors, a vector root is its own tree.
+void scalars_of_root(const weld_object* o, std::set<const weld_object*>* visited, std::vector<const weld_object*>* found) {
+    if (is_vec(o)) { scalars_below(o, visited, found); return; }
+    for (const weld_object* d : o->deps) scalars_below(d, visited, found);
+}
+
+// Stage in which scalar s can be computed: one more than the latest scalar its operand reads.
+int stage_of(const weld_object* s, std::map<const weld_object*, int>* memo) {
+    auto it = memo->find(s);
+    if (it != memo->end()) return it->second;
+    std::set<const weld_object*> visited;
+    std::vector<const weld_object*> need;
+    scalars_of_root(s, &visited, &need);
+    int latest = 0;
+    for (const weld_object* t : need) latest = std::max(latest, stage_of(t, memo));
+    return (*memo)[s] = latest + 1;
+}
+
+int64_t length_of(const weld_object* o) {
+    if (o->op == OBJ_DATA) return o->len;
+    if (o->op == OBJ_FILTER || o->op == OBJ_REDUCE) return length_of(o->deps[0]);
+    for (const weld_object* d : o->deps)
+        if (is_vec(d)) return length_of(d);
+    return 0;
+}
+
+Error submit(Fused& F, const weld_conf_t* conf, weld_result_t** out) {
+    std::vector<weld_col_t> cols(F.f.leaves.size());
+    for (size_t k = 0; k < cols.size(); ++k) {
+        cols[k].data = F.f.leaves[k].data;
+        cols[k].type = F.f.leaves[k].type;
+        if (F.f.leaves[k].scalar_of && !cols[k].data) return bad(WELD_ERR_INVALID_ARG, "internal: a scalar was not computed before the loop that reads it");
+    }
+    weld_cols_t cs;
+    cs.ncols = (int32_t)cols.size();
+    cs.col = cols.data();
+    weld_body_t body;
+    body.nops = (int32_t)F.f.ops.size();
+    body.ops = F.f.ops.data();
+    body.nmerges = (int32_t)F.merges.size();
+    body.merges = F.merges.data();
+    weld_builder_t b;
+    memset(&b, 0, sizeof b);
+    b.count = (int32_t)F.specs.size();
+    b.spec = F.specs.data();
+    if (conf) b.conf = *conf;
+    weld_status_t st = weld_fused_for(&cs, F.n < 0 ? 0 : F.n, &body, &b, out);
+    if (st != WELD_OK) return bad(st, weld_last_error());
+    return Error();
+}
+
+// What evaluation would turn down is turned down by a listing as well (maps are checked when fused).
+Error check(Fused& F) {
+    std::vector<int32_t> types(F.f.leaves.size());
+    for (size_t k = 0; k < types.size(); ++k) types[k] = F.f.leaves[k].type;
+    weld_body_t body;
+    body.nops = (int32_t)F.f.ops.size();
+    body.ops = F.f.ops.data();
+    body.nmerges = (int32_t)F.merges.size();
+    body.merges = F.merges.data();
+    weld_builder_t b;
+    memset(&b, 0, sizeof b);
+    b.count = (int32_t)F.specs.size();
+    b.spec = F.specs.data();
+    weld::Loop checked;
+    return weld::validate(types.data(), (int32_t)types.size(), &body, &b, &checked);
+}
+
+// Evaluates (conf, out) or lists (text) the roots: the stages that compute the scalars some map
+// reads, then the loop of the roots themselves.
+Error run_stages(weld_object* const* roots, int nroots, const weld_conf_t* conf, weld_result_t** out, std::string* text) {
+    if (!roots || nroots < 1 || nroots > WELD_MAX_BUILDERS) return bad(WELD_ERR_INVALID_ARG, "1..8 roots");
+    for (int r = 0; r < nroots; ++r)
+        if (!roots[r]) return bad(WELD_ERR_INVALID_ARG, "null root");
+
+    // every scalar that has to exist before the roots' loop, with its stage
+    std::vector<const weld_object*> wanted;
+    {
+        std::set<const weld_object*> visited;
+        for (int r = 0; r < nroots; ++r) scalars_of_root(roots[r], &visited, &wanted);
+        for (size_t k = 0; k < wanted.size(); ++k) {     // and what those read in turn
+            std::set<const weld_object*> v2;
+            scalars_of_root(wanted[k], &v2, &wanted);
+        }
+    }
+    std::map<const weld_object*, int> stage;
+    int last_stage = 0;
+    for (const weld_object* s : wanted) last_stage = std::max(last_stage, stage_of(s, &stage));
+
+    Scalars scalars;
+    std::vector<weld_result_t*> earlier;                 // results of the stages: they own the scalars
+    auto fail = [&](Error e) {
+        for (weld_result_t* r : earlier) weld_result_free(r);
+        return e;
+    };
+    for (int st = 1; st <= last_stage; ++st) {
+        std::map<int64_t, std::vector<const weld_object*>> by_length;
+        for (const weld_object* s : wanted)
+            if (stage[s] == st) by_length[length_of(s)].push_back(s);
+        for (auto& group : by_length) {
+            // two scalars that reduce the same expression under the same filter with the same function
+            // (x.count() written twice) are one computation: the fuser's expression ids tell
+            std::vector<const weld_object*> todo;
+            {
+                Fused all;
+                Error e = fuse(group.second.data(), (int)group.second.size(), &scalars, &all, true);
+                if (!e.ok()) return fail(e);
+                std::map<std::tuple<int, int, int>, const weld_object*> first;
+                for (size_t k = 0; k < group.second.size(); ++k) {
+                    const auto key = std::make_tuple(all.specs[k].func, all.merges[k].val[0], all.merges[k].pred);
+                    auto it = first.find(key);
+                    if (it == first.end()) { first[key] = group.second[k]; todo.push_back(group.second[k]); }
+                    else scalars.same_as[group.second[k]] = it->second;
+                }
+            }
+            for (size_t at = 0; at < todo.size(); at += WELD_MAX_BUILDERS) {
+                const size_t cnt = std::min<size_t>(WELD_MAX_BUILDERS, todo.size() - at);
+                Fused F;
+                Error e = fuse(todo.data() + at, (int)cnt, &scalars, &F);
+                if (!e.ok()) return fail(e);
+                if (text) {
+                    if (!(e = check(F)).ok()) return fail(e);
+                    *text += "let {";
+                    for (size_t k = 0; k < cnt; ++k) *text += (k ? ", s" : "s") + std::to_string(scalars.id_of(todo[at + k]));
+                    *text += "} =\n" + describe(F, &scalars) + "\n";
+                    continue;
+                }
+                weld_result_t* r = nullptr;
+                if (!(e = submit(F, conf, &r)).ok()) return fail(e);
+                earlier.push_back(r);
+                for (size_t k = 0; k < cnt; ++k) scalars.where[todo[at + k]] = weld_result_scalar(r, (int32_t)k);
+            }
+        }
+    }
+
+    // the roots' own loop; a root that an earlier stage has computed is not computed again
+    std::vector<const weld_object*> rest;
+    std::vector<int> slot(nroots, -1);
+    for (int r = 0; r < nroots; ++r) {
+        if (stage.count(roots[r])) continue;
+        slot[r] = (int)rest.size();
+        rest.push_back(roots[r]);
+    }
+    Fused F;
+    Error e = fuse(rest.data(), (int)rest.size(), &scalars, &F);
+    if (!e.ok()) return fail(e);
+    if (text) {
+        if (!(e = check(F)).ok()) return fail(e);
+        *text += describe(F, &scalars);
+        return Error();
+    }
+    weld_result_t* r = nullptr;
+    if (!(e = submit(F, conf, &r)).ok()) return fail(e);
+    if (!earlier.empty()) {
+        std::vector<BuilderResult> res(nroots);
+        for (int k = 0; k < nroots; ++k) {
+            if (slot[k] >= 0) {
+                res[k] = r->res[slot[k]];
+                if (res[k].ctl_index < 0) res[k].ctl_index = slot[k];   // its length word keeps its place
+            } else {
+                res[k].kind = WELD_MERGER;
+                res[k].scalar = const_cast<void*>(scalars.where[scalars.canon(roots[k])]);
+                res[k].elem_size = weld::type_size(roots[k]->type);
+            }
+        }
+        r->res.swap(res);
+        r->earlier = earlier;
+    }
+    *out = r;
+    return Error();
 }
 
 weld_status_t make(int op, weld_object** out, weld_object** created) {
@@ -355,7 +625,10 @@ weld_status_t weld_object_new_map(weld_object_t* const* deps, int32_t ndeps, con
         return WELD_ERR_INVALID_ARG;
     }
     for (int k = 0; k < ndeps; ++k)
-        if (!is_vec(deps[k])) { weld::set_last_error("map: dependencies must be vectors"); return WELD_ERR_TYPE; }
+        if (!is_vec(deps[k]) && !(deps[k] && deps[k]->op == OBJ_REDUCE)) {
+            weld::set_last_error("map: dependencies must be vectors or scalars");
+            return WELD_ERR_TYPE;
+        }
     weld_object* o;
     make(OBJ_MAP, out, &o);
     o->ops.assign(ops, ops + nops);
@@ -434,48 +707,15 @@ weld_status_t weld_object_evaluate(weld_object_t* const* roots, int32_t nroots, 
                                    weld_result_t** out) {
     if (out) *out = nullptr;
     if (!out) return WELD_ERR_INVALID_ARG;
-    Fused F;
-    Error e = fuse(roots, nroots, &F);
+    Error e = run_stages(roots, nroots, conf, out, nullptr);
     if (!e.ok()) { weld::set_last_error(e.text); return e.status; }
-    std::vector<weld_col_t> cols(F.f.leaves.size());
-    for (size_t k = 0; k < cols.size(); ++k) { cols[k].data = F.f.leaves[k]->data; cols[k].type = F.f.leaves[k]->type; }
-    weld_cols_t cs;
-    cs.ncols = (int32_t)cols.size();
-    cs.col = cols.data();
-    weld_body_t body;
-    body.nops = (int32_t)F.f.ops.size();
-    body.ops = F.f.ops.data();
-    body.nmerges = (int32_t)F.merges.size();
-    body.merges = F.merges.data();
-    weld_builder_t b;
-    memset(&b, 0, sizeof b);
-    b.count = (int32_t)F.specs.size();
-    b.spec = F.specs.data();
-    if (conf) b.conf = *conf;
-    return weld_fused_for(&cs, F.n < 0 ? 0 : F.n, &body, &b, out);
+    return WELD_OK;
 }
 
 int64_t weld_object_describe(weld_object_t* const* roots, int32_t nroots, char* buf, int64_t buflen) {
-    Fused F;
-    Error e = fuse(roots, nroots, &F);
+    std::string s;
+    Error e = run_stages(roots, nroots, nullptr, nullptr, &s);
     if (!e.ok()) { weld::set_last_error(e.text); return -1; }
-    {   // what evaluation would turn down is turned down here as well (maps are checked when they are fused)
-        std::vector<int32_t> types(F.f.leaves.size());
-        for (size_t k = 0; k < types.size(); ++k) types[k] = F.f.leaves[k]->type;
-        weld_body_t body;
-        body.nops = (int32_t)F.f.ops.size();
-        body.ops = F.f.ops.data();
-        body.nmerges = (int32_t)F.merges.size();
-        body.merges = F.merges.data();
-        weld_builder_t b;
-        memset(&b, 0, sizeof b);
-        b.count = (int32_t)F.specs.size();
-        b.spec = F.specs.data();
-        weld::Loop checked;
-        e = weld::validate(types.data(), (int32_t)types.size(), &body, &b, &checked);
-        if (!e.ok()) { weld::set_last_error(e.text); return -1; }
-    }
-    const std::string s = describe(F);
     if (buf && buflen > 0) snprintf(buf, (size_t)buflen, "%s", s.c_str());
     return (int64_t)s.size() + 1;
 }

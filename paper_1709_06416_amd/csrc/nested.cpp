@@ -82,6 +82,7 @@ Error build(const weld_nested_t* in, const weld_builder_t* builders, bool need_d
         return fail(WELD_ERR_INVALID_ARG, "bad outer body");
     std::vector<weld_op_t> ops(in->outer_body.ops, in->outer_body.ops + in->outer_body.nops);
     for (size_t i = 0; i < ops.size(); ++i) {
+        if (ops[i].opcode == WELD_OP_SCALAR) return fail(WELD_ERR_UNSUPPORTED, "outer body: scalars from outside the loop are not implemented in nested loops");
         if (ops[i].opcode != WELD_OP_INNER) continue;
         if (ops[i].type != in->inner_type)
             return fail(WELD_ERR_TYPE, "outer body op " + std::to_string(i) + ": the inner loop's result has type " + std::to_string(in->inner_type));

@@ -146,7 +146,7 @@ std::string plan_key(const Loop& L, const weld_tuning_t& tune, bool aligned, int
     key_add(k, aligned);
     key_add(k, tune);
     key_add(k, L.ncols);
-    for (int c = 0; c < L.ncols; ++c) { key_add(k, L.col_type[c]); key_add(k, L.col_used[c]); }
+    for (int c = 0; c < L.ncols; ++c) { key_add(k, L.col_type[c]); key_add(k, L.col_used[c]); key_add(k, L.col_scalar[c]); }
     for (const weld_op_t& o : L.ops) {
         key_add(k, o.opcode); key_add(k, o.type); key_add(k, o.a); key_add(k, o.b); key_add(k, o.c);
         key_add(k, o.reserved); key_add(k, o.imm.i64);
@@ -900,6 +900,7 @@ Error run_nested(const NestedLoop& NL, const NestedData& D, const weld_conf_t& c
 void destroy_result(weld_result* r) {
     if (!r) return;
     if (!r->synced && !r->blocks.empty()) (void)hipStreamSynchronize((hipStream_t)r->stream);
+    for (weld_result* c : r->earlier) destroy_result(c);
     for (void* p : r->blocks) pool_free(p);
     put_back(r);
     delete r;
@@ -946,7 +947,7 @@ weld_status_t weld_fused_for(const weld_cols_t* cols, int64_t n, const weld_body
     Error e = validate(types, cols->ncols, body, builder, &L);
     if (!e.ok()) { set_last_error(e.text); return e.status; }
     for (int c = 0; c < cols->ncols; ++c) {
-        if (n > 0 && L.col_used[c] && !cols->col[c].data) { set_last_error("null column pointer"); return WELD_ERR_INVALID_ARG; }
+        if (((n > 0 && L.col_used[c]) || L.col_scalar[c]) && !cols->col[c].data) { set_last_error("null column pointer"); return WELD_ERR_INVALID_ARG; }
         if ((uintptr_t)cols->col[c].data % (uintptr_t)type_size(L.col_type[c])) {
             set_last_error("column pointer not aligned to its element size");
             return WELD_ERR_INVALID_ARG;
@@ -1000,7 +1001,7 @@ weld_status_t weld_fused_for_probe(const weld_cols_t* cols, int64_t n, const wel
     Error e = validate(types, cols->ncols, body, builder, &L, &ctx);
     if (!e.ok()) { set_last_error(e.text); return e.status; }
     for (int c = 0; c < cols->ncols; ++c) {
-        if (n > 0 && L.col_used[c] && !cols->col[c].data) { set_last_error("null column pointer"); return WELD_ERR_INVALID_ARG; }
+        if (((n > 0 && L.col_used[c]) || L.col_scalar[c]) && !cols->col[c].data) { set_last_error("null column pointer"); return WELD_ERR_INVALID_ARG; }
         if ((uintptr_t)cols->col[c].data % (uintptr_t)type_size(L.col_type[c])) {
             set_last_error("column pointer not aligned to its element size");
             return WELD_ERR_INVALID_ARG;
@@ -1036,6 +1037,12 @@ weld_status_t weld_result_status(weld_result_t* r) {
     (void)hipEventElapsedTime(&r->ms, r->ev0, r->ev1);
     if (hipEventQuery(r->ev3) == hipSuccess) (void)hipEventElapsedTime(&r->kernel_ms, r->ev2, r->ev3);
     (void)hipGetLastError();
+    for (weld_result* c : r->earlier) {   // a staged evaluation fails if one of its stages did; its time is theirs and its own
+        const weld_status_t cs = weld_result_status(c);
+        if (cs != WELD_OK && r->status == WELD_OK) { r->status = cs; r->error = c->error; }
+        if (c->ms > 0.f) r->ms += c->ms;
+        r->kernel_count += c->kernel_count;
+    }
     const uint32_t err = r->host_ctl[2];
     if (err & 8) {
         r->status = WELD_ERR_INVALID_ARG;
@@ -1080,6 +1087,11 @@ const void* weld_result_data(weld_result_t* r, int32_t idx) {
     if (br.kind == WELD_VECBUILDER) return &br.vec;
     if (br.kind == WELD_GROUPBUILDER) return &br.groups;
     return &br.dict;
+}
+
+const void* weld_result_scalar(const weld_result_t* r, int32_t idx) {
+    if (!r || idx < 0 || idx >= (int32_t)r->res.size() || r->res[idx].kind != WELD_MERGER) return nullptr;
+    return r->res[idx].scalar;
 }
 
 weld_status_t weld_result_fetch(weld_result_t* r, int32_t idx, int32_t part, void* dst, int64_t offset,

@@ -98,7 +98,7 @@ extern "C" weld_status_t weld_fused_for_static(const weld_cols_t* cols, int64_t 
     if (!e.ok()) { set_last_error(e.text); return e.status; }
     ColRef refs[WELD_MAX_COLS];
     for (int c = 0; c < cols->ncols; ++c) {
-        if (n > 0 && L.col_used[c] && !cols->col[c].data) { set_last_error("null column pointer"); return WELD_ERR_INVALID_ARG; }
+        if (((n > 0 && L.col_used[c]) || L.col_scalar[c]) && !cols->col[c].data) { set_last_error("null column pointer"); return WELD_ERR_INVALID_ARG; }
         if ((uintptr_t)cols->col[c].data % (uintptr_t)type_size(L.col_type[c])) {
             set_last_error("column pointer not aligned to its element size");
             return WELD_ERR_INVALID_ARG;

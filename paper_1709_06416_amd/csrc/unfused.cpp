@@ -23,6 +23,7 @@ namespace {
 struct Val {
     bool is_const = false;
     bool is_index = false;
+    bool is_scalar = false;        // one element in device memory, defined outside the loop: stays a scalar operand
     weld_op_t cst;
     ColRef col;
     weld_result* owner = nullptr;  // sub-result whose block holds `col` (nullptr: caller's column)
@@ -53,6 +54,20 @@ struct SubLoop {
         if (c.data) col_op[c.data] = id;
         return id;
     }
+    int add_scalar(const ColRef& c) {
+        const int k = L.ncols++;
+        L.col_type[k] = c.type;
+        L.col_scalar[k] = true;
+        cols.push_back(c);
+        weld_op_t o;
+        memset(&o, 0, sizeof o);
+        o.opcode = WELD_OP_SCALAR;
+        o.type = c.type;
+        o.a = k;
+        o.b = o.c = -1;
+        L.ops.push_back(o);
+        return (int)L.ops.size() - 1;
+    }
     int add_raw(const weld_op_t& o) {
         L.ops.push_back(o);
         return (int)L.ops.size() - 1;
@@ -67,6 +82,7 @@ struct SubLoop {
             o.a = o.b = o.c = -1;
             return add_raw(o);
         }
+        if (v.is_scalar) return add_scalar(v.col);
         return add_col(v.col);
     }
     void set_builder(const weld_builder_spec_t& spec, int pred, const std::vector<int>& keys, const std::vector<int>& vals) {
@@ -201,6 +217,11 @@ Error run_unfused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_
             v.is_index = true;
             continue;
         }
+        if (o.opcode == WELD_OP_SCALAR) {
+            v.is_scalar = true;
+            v.col = cols[o.a];
+            continue;
+        }
         if (v.last_use < 0) continue;  // dead code: never read
         SubLoop s;
         const int ar = arity(o.opcode);
@@ -233,13 +254,8 @@ Error run_unfused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_
     // materialised first (np.full / np.arange)
     auto as_column = [&](int id, Val* out) -> Error {
         Val& v = val[id];
-        if (!v.is_const && !v.is_index) {
+        if (!v.is_const && !v.is_index && !v.is_scalar) {   // a column already (also: materialised for an earlier merge)
             *out = v;
-            return Error();
-        }
-        if (v.col.data) {  // already materialised for an earlier merge
-            *out = v;
-            out->is_const = out->is_index = false;
             return Error();
         }
         SubLoop s;
@@ -251,8 +267,8 @@ Error run_unfused(const Loop& L, const ColRef* cols, int64_t n, const weld_conf_
         v.col.data = r->res[0].vec.ptr;
         v.col.type = L.ops[id].type;
         v.owner = r;
+        v.is_const = v.is_index = v.is_scalar = false;   // every expression operator has run: from here on it is a column
         *out = v;
-        out->is_const = out->is_index = false;
         return Error();
     };
 

@@ -70,7 +70,15 @@ Error validate(const int32_t* col_types, int32_t ncols, const weld_body_t* body,
             case WELD_OP_COL:
                 if (o.a < 0 || o.a >= ncols) return fail(WELD_ERR_INVALID_ARG, "op %d: column %d not declared", i, o.a);
                 if (o.type != L.col_type[o.a]) return fail(WELD_ERR_TYPE, "op %d: column %d has type %d", i, o.a, L.col_type[o.a]);
+                if (L.col_scalar[o.a]) return fail(WELD_ERR_INVALID_ARG, "op %d: column %d is read as a scalar elsewhere in the body", i, o.a);
                 L.col_used[o.a] = true;
+                break;
+            case WELD_OP_SCALAR:
+                if (inner_of && inner_of->nouter > 0) return fail(WELD_ERR_UNSUPPORTED, "op %d: scalars from outside the loop are not implemented in nested bodies", i);
+                if (o.a < 0 || o.a >= ncols) return fail(WELD_ERR_INVALID_ARG, "op %d: column %d not declared", i, o.a);
+                if (o.type != L.col_type[o.a]) return fail(WELD_ERR_TYPE, "op %d: column %d has type %d", i, o.a, L.col_type[o.a]);
+                if (L.col_used[o.a]) return fail(WELD_ERR_INVALID_ARG, "op %d: column %d is read as a vector elsewhere in the body", i, o.a);
+                L.col_scalar[o.a] = true;
                 break;
             case WELD_OP_CONST:
                 if (o.type == WELD_BOOL && o.imm.i64 != 0 && o.imm.i64 != 1)

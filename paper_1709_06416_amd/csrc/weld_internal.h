@@ -53,6 +53,7 @@ struct weld_result {
     float kernel_ms = -1.f;
     float busy_ms = -1.f;          // unfused mode: sum of the operator loops' own GPU time (no host waits between them)
     std::string kernel_name;
+    std::vector<weld_result*> earlier;   // staged evaluation: the loops that ran before this one; freed with it
 };
 
 namespace weld {
@@ -76,6 +77,7 @@ struct Loop {
     int ncols = 0;
     int col_type[WELD_MAX_COLS] = {0};
     bool col_used[WELD_MAX_COLS] = {false};
+    bool col_scalar[WELD_MAX_COLS] = {false};   // read by WELD_OP_SCALAR: one element, the same for every row
     std::vector<weld_op_t> ops;
     std::vector<weld_builder_spec_t> builders;
     std::vector<int> merge_of;           // per builder: index into merges, or -1

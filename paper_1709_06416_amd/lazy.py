@@ -91,6 +91,8 @@ class Vec(Obj):
     # ---- elementwise operators: one object per library call
     def _binary(self, code, other, reflect=False):
         rt = "bool" if code in _COMPARE else self.dtype
+        if isinstance(other, (Scalar, ScalarExpr)):
+            return _with_scalars(self, code, other, reflect, rt)
         if isinstance(other, Vec):
             assert other.dtype == self.dtype, "no implicit casts: use .cast()"
             a, b = (1, 0) if reflect else (0, 1)
@@ -152,8 +154,88 @@ class Vec(Obj):
         return ones._reduce("add")
 
 
+class ScalarExpr:
+    """Arithmetic over lazily evaluated scalars and constants (`s.sum() / s.count()`): nothing of
+    its own to evaluate; it becomes part of the map that combines it with a vector, in which every
+    scalar it mentions is a dependency."""
+
+    def __init__(self, dtype, tree):
+        self.dtype, self.tree = dtype, tree          # tree: ("scalar", Scalar) | ("const", v) | (code, dtype, args...)
+
+    @staticmethod
+    def of(x, dtype):
+        if isinstance(x, ScalarExpr):
+            return x
+        if isinstance(x, Scalar):
+            return ScalarExpr(x.dtype, ("scalar", x))
+        return ScalarExpr(dtype, ("const", x))
+
+    def _bin(self, code, other, reflect=False):
+        o = ScalarExpr.of(other, self.dtype)
+        assert o.dtype == self.dtype, "no implicit casts: use .cast()"
+        a, b = (o, self) if reflect else (self, o)
+        return ScalarExpr(self.dtype, (code, self.dtype, a, b))
+
+    def __add__(self, o): return self._bin("add", o)
+    def __radd__(self, o): return self._bin("add", o, True)
+    def __sub__(self, o): return self._bin("sub", o)
+    def __rsub__(self, o): return self._bin("sub", o, True)
+    def __mul__(self, o): return self._bin("mul", o)
+    def __rmul__(self, o): return self._bin("mul", o, True)
+    def __truediv__(self, o): return self._bin("div", o)
+    def __rtruediv__(self, o): return self._bin("div", o, True)
+    def __neg__(self): return ScalarExpr(self.dtype, ("neg", self.dtype, self))
+    def sqrt(self): return ScalarExpr(self.dtype, ("sqrt", self.dtype, self))
+    def cast(self, dtype): return ScalarExpr(dtype, ("cast", dtype, self))
+
+
 class Scalar(Obj):
-    pass
+    """A lazily evaluated scalar (the result of a reduction).  It can be evaluated, and it can be an
+    operand of elementwise operators on vectors (`x - x.sum() / x.count()`): evaluation then runs
+    the loop that computes it first and the loop that reads it afterwards, on the device."""
+
+    def _e(self): return ScalarExpr.of(self, self.dtype)
+    def __add__(self, o): return self._e() + o
+    def __radd__(self, o): return o + self._e()
+    def __sub__(self, o): return self._e() - o
+    def __rsub__(self, o): return o - self._e()
+    def __mul__(self, o): return self._e() * o
+    def __rmul__(self, o): return o * self._e()
+    def __truediv__(self, o): return self._e() / o
+    def __rtruediv__(self, o): return o / self._e()
+    def __neg__(self): return -self._e()
+    def sqrt(self): return self._e().sqrt()
+    def cast(self, dtype): return self._e().cast(dtype)
+
+
+def _with_scalars(vec, code, other, reflect, rt):
+    """`vec <code> expression over scalars` as one map whose dependencies are the vector and every
+    scalar the expression mentions."""
+    expr = ScalarExpr.of(other, vec.dtype)
+    assert expr.dtype == vec.dtype, "no implicit casts: use .cast()"
+    deps, ops = [vec], [("col", vec.dtype, 0, -1, -1, 0)]
+
+    def emit(e):
+        t = e.tree
+        if t[0] == "scalar":
+            for k, d in enumerate(deps):
+                if d is t[1]:
+                    break
+            else:
+                deps.append(t[1])
+                k = len(deps) - 1
+            ops.append(("col", e.dtype, k, -1, -1, 0))
+        elif t[0] == "const":
+            ops.append(("const", e.dtype, -1, -1, -1, t[1]))
+        else:
+            args = [emit(a) for a in t[2:]] + [-1, -1]
+            ops.append((t[0], t[1], args[0], args[1], -1, 0))
+        return len(ops) - 1
+
+    s = emit(expr)
+    a, b = (s, 0) if reflect else (0, s)
+    ops.append((code, rt, a, b, -1, 0))
+    return _map(deps, ops, rt)
 
 
 class Dict(Obj):

@@ -96,6 +96,30 @@ def test_malformed_bodies_are_rejected(wb):
     assert wb.validate(p)[0] == wb.ERR_UNSUPPORTED
 
 
+def test_scalars_from_outside_the_loop_validate_and_reach_the_kernel_as_one_load(wb):
+    p = Program(["f64", "f64", "i64"])
+    x, s, c = p.col(0), p.scalar(1), p.scalar(2)
+    p.merge(p.vecbuilder("f64"), p.bin("sub", x, p.bin("div", s, p.un("cast", c, "f64"))))
+    st, msg = wb.validate(p)
+    assert st == wb.OK, msg
+    src = wb.generated_source(p)
+    assert "const double sc1 = a.s1[0];" in src and "const i64 sc2 = a.s2[0];" in src      # read once per thread, not per row
+    assert "a.c1" not in src and "a.c2" not in src                                       # and never streamed as vectors
+
+    q = Program(["i64"])
+    q.merge(q.merger("i64", "add"), q.bin("add", q.col(0), q.scalar(0)))                 # one entry, both ways
+    st, msg = wb.validate(q)
+    assert st == wb.ERR_INVALID_ARG and "column 0" in msg
+    q = Program(["i64"])
+    q.ops.append(("scalar", "f64", 0))                                                   # declared i64
+    q.merge(q.merger("f64", "add"), 0)
+    assert wb.validate(q)[0] == wb.ERR_TYPE
+    q = Program(["i64"])
+    q.ops.append(("scalar", "i64", 2))                                                   # not in the list
+    q.merge(q.merger("i64", "add"), 0)
+    assert wb.validate(q)[0] == wb.ERR_INVALID_ARG
+
+
 def test_generated_source_has_one_statement_per_operator(wb):
     prog = configs.program_c3()
     src = wb.generated_source(prog)

@@ -1064,6 +1064,139 @@ def test_lazy_groupby_and_materialised_vector(wb):
 
 
 # ----------------------------------------------------------------------
+# scalars defined outside the loop as operands of its body (Sec. 3.2: the loop's function is a
+# closure; Sec. 4.1: objects depend on the results of other objects)
+# ----------------------------------------------------------------------
+def _scalar_program(t):
+    """Every builder kind fed by expressions of a vector element x and an outside scalar s."""
+    p = Program([t, t])
+    x, s = p.col(0), p.scalar(1)
+    p.merge(p.merger(t, "add"), p.bin("mul", x, s))
+    p.merge(p.vecbuilder(t), p.bin("sub", x, s), pred=p.bin("gt", x, s))
+    if t != "f64":
+        key = p.bin("mod", p.bin("add", x, s), p.const(t, 7))
+        p.merge(p.dictmerger([t], [t], "add", 16), [s], keys=[key])
+    p.merge(p.merger(t, "max"), s, pred=p.bin("lt", x, s))         # a scalar merged directly
+    return p
+
+
+@pytest.mark.parametrize("t", ["i32", "i64", "f64"])
+@pytest.mark.parametrize("mode", ["fused", "unfused"])
+def test_scalar_operand_of_a_loop_body(wb, t, mode):
+    from oracle import interp
+    from tests import parity
+    rnd = np.random.RandomState(11)
+    prog = _scalar_program(t)
+    for n in (0, 1, 5000, 70_001):
+        if t == "f64":
+            x, s = rnd.uniform(-50, 50, n), np.array([3.25])
+        else:
+            x, s = rnd.randint(-1000, 1000, n).astype(wb.TYPE_NP[t]), np.array([17], dtype=wb.TYPE_NP[t])
+        want = interp.run(prog, [x, s], sums="exact")
+        res = wb.fused_for(prog, [_dev(x), _dev(s)], mode=mode, n=n)
+        try:
+            parity.assert_matches(prog, res, want, label="%s %s n=%d" % (t, mode, n))
+        finally:
+            res.free()
+
+
+def test_scalar_operands_are_checked_on_the_host(wb):
+    p = Program(["i64", "i64"])
+    x = p.col(0)
+    p.merge(p.merger("i64", "add"), p.bin("add", x, p.scalar(1)))
+    with pytest.raises(wb.WeldError):                              # two elements where one is expected
+        wb.fused_for(p, [_dev(np.arange(4)), _dev(np.arange(2))])
+    with pytest.raises(wb.WeldError) as e:                         # the same entry as vector and as scalar
+        q = Program(["i64"])
+        q.merge(q.merger("i64", "add"), q.bin("add", q.col(0), q.scalar(0)))
+        wb.fused_for(q, [_dev(np.arange(1))])
+    assert "scalar" in str(e.value) or "vector" in str(e.value)
+
+
+def test_a_reduction_feeds_the_next_loop_without_a_host_wait(wb):
+    """sum and count in one loop; the second loop reads both from device memory (x * count - sum:
+    integers, so every stage is exact) while nothing has waited for the first."""
+    from oracle import interp
+    rnd = np.random.RandomState(5)
+    x = rnd.randint(-10_000, 10_000, 300_007).astype(np.int64)
+    first = Program(["i64"])
+    c = first.col(0)
+    first.merge(first.merger("i64", "add"), c)
+    first.merge(first.merger("i64", "add"), first.const("i64", 1))
+    second = Program(["i64", "i64", "i64"])
+    v, total, count = second.col(0), second.scalar(1), second.scalar(2)
+    centred = second.bin("sub", second.bin("mul", v, count), total)
+    second.merge(second.vecbuilder("i64"), centred)
+    second.merge(second.merger("i64", "max"), centred)
+    second.merge(second.vecbuilder("i64"), v, pred=second.bin("gt", centred, second.const("i64", 0)))
+    w1 = interp.run(first, [x])
+    w2 = interp.run(second, [x, np.array([w1[0]]), np.array([w1[1]])])
+    dx = _dev(x)
+    r1 = wb.fused_for(first, [dx])
+    r2 = wb.fused_for(second, [dx, r1.scalar_ref(0), r1.scalar_ref(1)], n=len(x))      # enqueued behind r1, no wait between
+    r2.check()
+    assert np.array_equal(r2.vec_host(0), w2[0]) and int(r2.merger(1)) == int(w2[1])
+    assert np.array_equal(r2.vec_host(2), w2[2])
+    assert int(r1.merger(0)) == int(w1[0]) and int(r1.merger(1)) == int(w1[1])
+    r2.free()
+    r1.free()
+
+
+@pytest.mark.parametrize("mode", ["fused", "unfused"])
+def test_lazy_scalars_feed_later_objects_in_stages(wb, mode):
+    """Standardisation as a library would write it (z = (x - mean) / std): the mean needs a sum and
+    a count, the variance needs the mean, z needs both: three loops, the later ones reading the
+    earlier ones' results on the device.  The oracle runs the same three loops, each fed with the
+    ORACLE's results of the one before."""
+    from oracle import interp
+    from paper_1709_06416_amd import lazy
+    rnd = np.random.RandomState(21)
+    x = rnd.normal(40.0, 12.0, 200_003)
+    lx = lazy.Vec.from_tensor(_dev(x))
+    n = lx.count().cast("f64")
+    total = lx.sum()
+    mean = total / n
+    d = lx - mean
+    var = (d * d).sum() / lx.count().cast("f64")                   # a second count(): folded into the first
+    z = d / var.sqrt()
+    text = lazy.describe(z, total, z.max())
+    assert text.count("for(") == 3 and "let {s0, s1} =" in text and "let {s2} =" in text
+
+    s1 = Program(["f64"])
+    s1.merge(s1.merger("f64", "add"), s1.col(0))
+    s1.merge(s1.merger("i64", "add"), s1.const("i64", 1))
+    w_sum, w_cnt = interp.run(s1, [x], sums="exact")
+
+    def centred(p):
+        v, t, c = p.col(0), p.scalar(1), p.scalar(2)
+        return p.bin("sub", v, p.bin("div", t, p.un("cast", c, "f64")))
+    s2 = Program(["f64", "f64", "i64"])
+    dd = centred(s2)
+    s2.merge(s2.merger("f64", "add"), s2.bin("mul", dd, dd))
+    scal = [np.array([w_sum]), np.array([w_cnt])]
+    w_ss, = interp.run(s2, [x] + scal, sums="exact")
+    s3 = Program(["f64", "f64", "i64", "f64"])
+    dd = centred(s3)
+    std = s3.un("sqrt", s3.bin("div", s3.scalar(3), s3.un("cast", s3.scalar(2), "f64")))
+    zz = s3.bin("div", dd, std)
+    s3.merge(s3.vecbuilder("f64"), zz)
+    s3.merge(s3.merger("f64", "max"), zz)
+    w_z, w_max = interp.run(s3, [x] + scal + [np.array([w_ss])], sums="exact")
+
+    res = lazy.evaluate(z, total, z.max(), mode=mode).check()
+    got = res.vec_host(0)
+    # the scalars are sums, equal to the oracle's to 1e-9 of their value (in practice a few ulp); an
+    # error e in the mean moves every z by e / std: an absolute bound, not one relative to z
+    assert len(got) == len(w_z) and np.all(np.abs(got - w_z) <= 1e-9 * 40.0 / 12.0)
+    assert np.all(np.abs(got - w_z) <= 1e-12)                       # what is actually seen: rounding only
+    assert abs(float(res.merger(1)) - float(w_sum)) <= 1e-9 * abs(float(w_sum))       # a root an earlier stage computed
+    assert abs(float(res.merger(2)) - float(w_max)) <= 1e-9
+    if mode == "fused":
+        assert res.kernel_count() <= 9                              # three loops (each: loop kernel + finish), not one per operator
+    res.free()
+
+
+# ----------------------------------------------------------------------
 # groupbuilder (Table 1): dict[K, vec[V]]
 # ----------------------------------------------------------------------
 def _group_on_c5(capacity=100_000):

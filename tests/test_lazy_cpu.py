@@ -66,6 +66,47 @@ def test_what_cannot_be_fused_is_reported(lz):
         a + _vec(lz, "f64")                            # no implicit casts
 
 
+def test_a_scalar_that_feeds_a_map_is_computed_by_an_earlier_loop(lz):
+    # normalisation as a library writes it: the mean needs sum and count, the centred vector the mean
+    x = _vec(lz, "f64")
+    mean = x.sum() / x.count().cast("f64")
+    d = x - mean
+    text = lz.describe(d)
+    assert text.count("for(") == 2
+    first, second = text.split("\n\n")
+    assert first.startswith("let {s0, s1} =") and "merger[f64,+], merger[i64,+]" in first
+    assert "|v0: vec[f64], s0: f64, s1: i64|" in second and "for(v0," in second      # the scalars are not zipped
+    assert "let t3 = f64(s1);" in second and "s0 / t3" in second and "x.0 - t4" in second
+    # a third stage, a count written twice folded into one, a root that an earlier stage has computed
+    ss = (d * d).sum()
+    var = ss / x.count().cast("f64")
+    z = d / var.sqrt()
+    text = lz.describe(z, ss)
+    assert text.count("for(") == 3 and text.count("merger[i64,+]") == 1
+    assert "let {s2} =" in text and "sqrt(" in text
+    last = text.split("\n\n")[-1]
+    assert "vecbuilder[f64]" in last and "merger" not in last                      # the sum of squares is not computed twice
+
+
+def test_scalar_operands_that_cannot_be_staged_are_reported(lz):
+    from paper_1709_06416_amd import binding as wb
+    a = _vec(lz, "i64")
+    with pytest.raises(AssertionError):
+        a - _vec(lz, "f64").sum()                      # no implicit casts, for scalars either
+    s = a.sum()
+    ops = (wb.Op * 2)()
+    ops[0].opcode, ops[0].type, ops[0].a, ops[0].b, ops[0].c = wb.OPCODE["col"], wb.TYPE_ID["i64"], 0, -1, -1
+    ops[1].opcode, ops[1].type, ops[1].a, ops[1].b, ops[1].c = wb.OPCODE["neg"], wb.TYPE_ID["i64"], 0, -1, -1
+    import ctypes as C
+    out = C.c_void_p()
+    handles = (C.c_void_p * 1)(s._h)
+    assert wb.lib.weld_object_new_map(handles, 1, ops, 2, C.byref(out)) == wb.OK     # a map over scalars alone is built ...
+    roots = (C.c_void_p * 1)(out)
+    assert wb.lib.weld_object_describe(roots, 1, None, 0) < 0                         # ... and turned down when fused
+    assert "vector" in wb.lib.weld_last_error().decode()
+    wb.lib.weld_object_free(out)
+
+
 def test_groupby_becomes_a_dictmerger(lz):
     k1, k2 = _vec(lz, "i8", addr=0x1000), _vec(lz, "i8", addr=0x2000)
     q, p = _vec(lz, "f64", addr=0x3000), _vec(lz, "f64", addr=0x4000)

@@ -43,6 +43,30 @@ def _both(columns, build, expected):
 
 
 # ----------------------------------------------------------------------
+# a scalar defined outside the loop (Sec. 3.2: the loop's function is a closure): every row reads it
+# ----------------------------------------------------------------------
+def test_scalar_from_outside_the_loop_is_read_by_every_row():
+    p = Program(["i64", "i64", "f64"])
+    x, s, f = p.col(0), p.scalar(1), p.scalar(2)
+    p.merge(p.vecbuilder("i64"), p.bin("sub", p.bin("mul", x, s), p.const("i64", 1)))
+    p.merge(p.merger("i64", "add"), s, pred=p.bin("gt", x, s))
+    p.merge(p.vecbuilder("f64"), p.bin("add", p.un("cast", x, "f64"), f))
+    cols = [[1, 5, 2, 9], [3], [0.5]]
+    want = [[2, 14, 5, 26], 6, [1.5, 5.5, 2.5, 9.5]]             # 3x - 1; s counted where x > 3: twice; x + 0.5
+    a = interp.run(p, [np.array(cols[0]), np.array(cols[1]), np.array(cols[2])])
+    b = rowwise.run(p, cols)
+    assert a[0].tolist() == want[0] and int(a[1]) == want[1] and a[2].tolist() == want[2]
+    assert b[0] == want[0] and b[1] == want[1] and b[2] == want[2]
+    # the loop's length is that of its vectors, wherever the scalar stands in the list
+    q = Program(["i64", "i64"])
+    q.merge(q.vecbuilder("i64"), q.bin("add", q.scalar(0), q.col(1)))
+    assert interp.run(q, [np.array([10]), np.array([1, 2, 3])])[0].tolist() == [11, 12, 13]
+    assert rowwise.run(q, [[10], [1, 2, 3]])[0] == [11, 12, 13]
+    assert interp.run(q, [np.array([10]), np.array([], dtype=np.int64)])[0].tolist() == []
+    assert rowwise.run(q, [[10], []])[0] == []
+
+
+# ----------------------------------------------------------------------
 # boolean operators: complete truth tables
 # ----------------------------------------------------------------------
 def _bool_cols():

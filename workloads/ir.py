@@ -81,6 +81,11 @@ class Program:
     def col(self, k):
         return self._push(("col", self.columns[k], k))
 
+    def scalar(self, k):
+        """Entry k of the column list holds ONE element: a scalar defined outside the loop (say an
+        earlier loop's merger result) that every row reads; never also read with col(k)."""
+        return self._push(("scalar", self.columns[k], k))
+
     def const(self, t, value):
         assert t in TYPES
         return self._push(("const", t, value))
