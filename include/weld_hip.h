@@ -196,6 +196,11 @@ typedef struct {
                                    -1 = the general 64-bit cells                                    */
     int32_t device_math;        /* exp and log of the body: 0 = the library's own (tables and polynomials, about a
                                    third of the instructions), -1 = the device math library's          */
+    int32_t tile_pipeline;      /* loops that compact (a vecbuilder under a predicate) and merge into memory:
+                                   1 = the next tile's columns are loaded into registers while this tile is
+                                   merged and stored, -1 = one tile at a time, 0 = library's choice (on when
+                                   those columns, the tile's gathered values and the first probes take a
+                                   lane at most about 80 registers)                                  */
 } weld_tuning_t;
 
 typedef struct {

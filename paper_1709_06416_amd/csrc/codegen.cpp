@@ -566,6 +566,34 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
         }
         var.merge_loop = (tune.merge_loop > 0 || var.defer_builder >= 0) && var.ticketed && in_memory && rows >= 4 && rows <= 16;
     }
+    // Compacting loops that also merge into memory: the next tile's columns are loaded while this tile
+    // is merged and stored (C5, 1e8 rows: loop kernel 0.50 -> 0.46 ms).  Those columns then occupy
+    // registers through the merge phase, next to the tile's gathered values and the slots and keys of
+    // the first probes; where the three together pass about 80 registers a lane the kernel spills and
+    // loses more than it gains (the same column grouped by key: 0.73 -> 0.90 ms), and a loop that only
+    // compacts has no merge phase to hide the loads behind (0.32 -> 0.34 ms): both keep the plain form.
+    if (var.ticketed && var.merge_loop && tune.tile_pipeline >= 0) {
+        const int rows = var.u * var.v;
+        int regs = 0;
+        for (int c = 0; c < L.ncols; ++c)
+            if (L.col_used[c]) regs += (type_size(L.col_type[c]) * rows + 3) / 4;
+        const std::vector<IRange> rg = static_ranges(L);
+        std::vector<int> held;
+        for (size_t b = 0; b < L.builders.size(); ++b) {
+            const int m = L.merge_of[b];
+            if (m < 0 || (!merges_in_memory(var.backend[b]) && var.backend[b] != BK_VEC_COMPACT)) continue;
+            const weld_merge_t& g = L.merges[m];
+            for (int f = 0; f < g.nkeys + g.nvals; ++f) {
+                const int op = f < g.nkeys ? g.key[f] : g.val[f - g.nkeys];
+                if (L.ops[op].opcode == WELD_OP_CONST || std::find(held.begin(), held.end(), op) != held.end()) continue;
+                held.push_back(op);
+                const int t = L.ops[op].type;
+                regs += ((t == WELD_F64 || (t == WELD_I64 && !rg[op].fits32())) ? 2 : 1) * rows;
+            }
+        }
+        if (var.defer_builder >= 0) regs += (var.compact == var.defer_builder ? 2 : 3) * rows;
+        if (tune.tile_pipeline > 0 || regs <= 80) var.pipeline = 1;
+    }
     return var;
 }
 
@@ -890,7 +918,10 @@ Generated generate(const Loop& L, const Variant& var) {
         lds += 8 * 128;
     }
     if (var.ticketed) {
-        o.f("  __shared__ i64 s_tile;\n  __shared__ i64 s_cnt[%d][W_WAVES];\n  __shared__ i64 s_pfx[%d];\n", ncompact, ncompact);
+        if (var.pipeline)   // two tiles overlap: the next tile's number and this tile's counts live side by side
+            o.f("  __shared__ i64 s_tile[2];\n  __shared__ i64 s_cnt[%d][2][W_WAVES];\n  __shared__ i64 s_pfx[%d];\n", ncompact, ncompact);
+        else
+            o.f("  __shared__ i64 s_tile;\n  __shared__ i64 s_cnt[%d][W_WAVES];\n  __shared__ i64 s_pfx[%d];\n", ncompact, ncompact);
         o.f("  __shared__ u64 s_stage[W_WAVES * W_UNIT];\n");
         if (var.defer_builder >= 0)   // the wavefront's queue of unsettled merges lives in its part of the staging buffer
             o.f("  u64* const dq = s_stage + wave * W_UNIT;\n  int dq_n = 0;\n");
@@ -1048,23 +1079,61 @@ Generated generate(const Loop& L, const Variant& var) {
         o.f("  }\n");
     } else {
         // ---------------- ticketed tile order (needed by the look-back scan)
-        // A tile's ticket is drawn when the tile starts, not earlier: tickets order the look-back,
-        // and a tile that waits for one drawn ahead of time waits for a work-group that is still
-        // busy with its previous tile (measured: tickets drawn one tile ahead cost C5 20 %).
+        // Plain form: a tile's ticket is drawn when the tile starts, its columns are loaded, its counts are
+        // published and the sum of its predecessors is collected at once (the look-back), the other
+        // wavefronts merge meanwhile, and after a barrier the selected values are stored.
+        // Pipelined form (var.pipeline): the columns of the NEXT tile are loaded into registers while
+        // this tile is still being merged and stored, so the loads' latency is hidden and the memory
+        // pipe does not idle between a tile's stores and the next tile's loads.  The next tile's ticket
+        // is therefore drawn at the top of the current tile.  A ticket drawn ahead delays the tile's
+        // counts, and the tiles behind it wait for them in their look-back (with the look-back in one
+        // piece, drawing tickets a tile ahead cost C5 20 %); so the look-back is split: a tile publishes
+        // its own counts as soon as they are known and collects the sum of its predecessors after its
+        // merges, when the tiles in front have had time to publish theirs (7 % over collecting at once).
+        // Measured and dropped: loads issued only after the merges (no gain over the plain form), the
+        // wavefront that finishes its merges first collecting the sum (2 % slower), the tile's stores
+        // moved into the next tile so that one barrier per tile is left (2 % slower, more registers),
+        // the descriptors of the look-back requested before the queued merges are drained (3 % slower).
+        const std::string cb = var.pipeline ? "[it & 1]" : "";
+        const char* ticket = "(i64)__hip_atomic_fetch_add(a.ctl, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)";
+        Out prefetch;
+        if (var.pipeline) {
+            prefetch.f("    const i64 tn = s_tile[(it + 1) & 1];\n");
+            prefetch.f("    if ((tn + 1) * W_TILE <= a.n) {\n      const i64 rn = tn * W_TILE + (i64)wave * W_WAVE_ROWS + lane * W_V;\n");
+            prefetch.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+            for (int c = 0; c < L.ncols; ++c)
+                if (L.col_used[c]) prefetch.f("        x%d[u] = w_load<%s, W_V>(a.c%d + rn + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
+            prefetch.f("      }\n    }\n");
+        }
         o.f("  const i64 ntiles = (a.n + W_TILE - 1) / W_TILE;\n");
-        o.f("  for (;;) {\n");
-        o.f("    if (threadIdx.x == 0) s_tile = (i64)__hip_atomic_fetch_add(a.ctl, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n");
-        o.f("    __syncthreads();\n    const i64 t = s_tile;\n    if (t >= ntiles) break;\n");
+        if (var.pipeline) {
+            o.f("  if (threadIdx.x == 0) s_tile[0] = %s;\n  __syncthreads();\n  i64 t = s_tile[0];\n", ticket);
+            for (int c = 0; c < L.ncols; ++c)
+                if (L.col_used[c]) o.f("  wvec<%s, W_V> x%d[W_U];\n", stype(L.col_type[c]), c);
+            o.f("  if ((t + 1) * W_TILE <= a.n) {\n    const i64 rn = t * W_TILE + (i64)wave * W_WAVE_ROWS + lane * W_V;\n");
+            o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+            for (int c = 0; c < L.ncols; ++c)
+                if (L.col_used[c]) o.f("      x%d[u] = w_load<%s, W_V>(a.c%d + rn + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
+            o.f("    }\n  }\n");
+            o.f("  int it = 0;\n  for (; t < ntiles; ++it) {\n");
+            if (var.pipeline) o.f("    i64 tk = 0;\n    if (threadIdx.x == 0) tk = %s;\n", ticket);
+        } else {
+            o.f("  for (;;) {\n");
+            o.f("    if (threadIdx.x == 0) s_tile = %s;\n", ticket);
+            o.f("    __syncthreads();\n    const i64 t = s_tile;\n    if (t >= ntiles) break;\n");
+        }
         o.f("    const i64 r0 = t * W_TILE + (i64)wave * W_WAVE_ROWS + lane * W_V;\n");
         o.f("    const bool full = (t + 1) * W_TILE <= a.n;\n");
         o.f("    RowOut o[W_U][W_V];\n");
         o.f("    if (full) {\n");
-        for (int c = 0; c < L.ncols; ++c)
-            if (L.col_used[c]) o.f("      wvec<%s, W_V> x%d[W_U];\n", stype(L.col_type[c]), c);
-        o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
-        for (int c = 0; c < L.ncols; ++c)
-            if (L.col_used[c]) o.f("        x%d[u] = w_load<%s, W_V>(a.c%d + r0 + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
-        o.f("      }\n");
+        if (!var.pipeline) {
+            for (int c = 0; c < L.ncols; ++c)
+                if (L.col_used[c]) o.f("      wvec<%s, W_V> x%d[W_U];\n", stype(L.col_type[c]), c);
+            o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+            for (int c = 0; c < L.ncols; ++c)
+                if (L.col_used[c]) o.f("        x%d[u] = w_load<%s, W_V>(a.c%d + r0 + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
+            o.f("      }\n");
+        }
         o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
         o.f("          %s\n        }\n", row_call("r0 + u * W_UNIT + k", "x%d[u].e[k]", "o[u][k]", true).c_str());
         o.f("    } else {\n");
@@ -1196,20 +1265,70 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("    {\n      int wtot = 0;\n");
             o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n");
             o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) wtot += __popcll(w_ballot(%s));\n", sel_expr(b).c_str());
-            o.f("      if (lane == 0) s_cnt[%d][wave] = wtot;\n    }\n", j);
+            o.f("      if (lane == 0) s_cnt[%d]%s[wave] = wtot;\n    }\n", j, cb.c_str());
             ++j;
         }
+        if (var.pipeline) o.f("    if (threadIdx.x == 0) s_tile[(it + 1) & 1] = tk;\n");
         o.f("    __syncthreads();\n");
+        if (var.pipeline) o.s += prefetch.s;
         o.f("    if (wave == 0) {\n");
         j = 0;
         for (size_t b = 0; b < NB; ++b) {
             if (var.backend[b] != BK_VEC_COMPACT) continue;
-            o.f("      {\n        i64 tot = 0;\n        _Pragma(\"unroll\") for (int w = 0; w < W_WAVES; ++w) tot += s_cnt[%d][w];\n", j);
-            o.f("        const i64 ex = w_lookback(a.b%zu_desc, t, tot, a.spin_limit, errp);\n", b);
-            o.f("        if (lane == 0) {\n          s_pfx[%d] = ex;\n          if (t == ntiles - 1) *a.b%zu_len = ex + tot;\n        }\n      }\n", j, b);
+            o.f("      {\n        i64 tot = 0;\n        _Pragma(\"unroll\") for (int w = 0; w < W_WAVES; ++w) tot += s_cnt[%d]%s[w];\n", j, cb.c_str());
+            if (var.pipeline) {
+                o.f("        w_lookback_publish(a.b%zu_desc, t, tot);\n      }\n", b);
+            } else {
+                o.f("        const i64 ex = w_lookback(a.b%zu_desc, t, tot, a.spin_limit, errp);\n", b);
+                o.f("        if (lane == 0) {\n          s_pfx[%d] = ex;\n          if (t == ntiles - 1) *a.b%zu_len = ex + tot;\n        }\n      }\n", j, b);
+            }
             ++j;
         }
         o.f("    }\n");
+        // second half of the split look-back for tile `tile`, whose counts are in slot `cslot`
+        auto resolve_text = [&](const char* tile, const std::string& cslot, const std::string& pslot) {
+            Out d;
+            d.f("    if (wave == 0) {\n");
+            int jj = 0;
+            for (size_t b = 0; b < NB; ++b) {
+                if (var.backend[b] != BK_VEC_COMPACT) continue;
+                d.f("      {\n        i64 tot = 0;\n        _Pragma(\"unroll\") for (int w = 0; w < W_WAVES; ++w) tot += s_cnt[%d]%s[w];\n", jj, cslot.c_str());
+                d.f("        const i64 ex = w_lookback_resolve(a.b%zu_desc, %s, tot, a.spin_limit, errp);\n", b, tile);
+                d.f("        if (lane == 0) {\n          s_pfx[%d]%s = ex;\n          if (%s == ntiles - 1) *a.b%zu_len = ex + tot;\n        }\n      }\n", jj, pslot.c_str(), tile, b);
+                ++jj;
+            }
+            d.f("    }\n");
+            return d.s;
+        };
+        // the selected values of a tile go to their places in the output vectors
+        auto staging_text = [&](const std::string& cslot, const std::string& pslot) {
+            Out d;
+            int jj = 0;
+            for (size_t b = 0; b < NB; ++b) {
+                if (var.backend[b] != BK_VEC_COMPACT) continue;
+                d.f("    {\n      i64 base = s_pfx[%d]%s;\n      for (int w = 0; w < wave; ++w) base += s_cnt[%d]%s[w];\n", jj, pslot.c_str(), jj, cslot.c_str());
+                // The selected values of one load unit are packed in LDS at their ranks and written
+                // out as one dense run per instruction (lane l writes elements l, l+64, ...), so HBM
+                // sees full lines instead of scattered 8-byte pieces.
+                const char* ST = stype(L.builders[b].val_type[0]);
+                // (a 64-bit value that provably fits 32 bits is staged in 4 bytes and widened at the store)
+                const int vop = L.merges[L.merge_of[b]].val[0];
+                const char* SG = (gathered && L.builders[b].val_type[0] == WELD_I64 && ranges[vop].fits32()) ? "int" : ST;
+                d.f("      %s* const stg = (%s*)(s_stage + wave * W_UNIT);\n", SG, SG);
+                // (how many rows of each load unit are selected is counted again here: a few scalar
+                // instructions, cheaper than holding the counts of every unit through the merge phase)
+                d.f("      int run = 0;\n");
+                d.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
+                d.f("        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\");\n");
+                d.f("        int rank = 0, ucnt = 0;\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n          const u64 bal = w_ballot(%s);\n          rank += w_rank_below(bal);\n          ucnt += __popcll(bal);\n        }\n", sel_expr(b).c_str());
+                d.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k)\n          if (%s) stg[rank++] = (%s)%s;\n", sel_expr(b).c_str(), SG, val_expr(b).c_str());
+                d.f("        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\");\n");
+                d.f("        _Pragma(\"unroll\") for (int q = 0; q < W_V; ++q) {\n          const int e = q * 64 + lane;\n");
+                d.f("          if (e < ucnt) __builtin_nontemporal_store((%s)stg[e], a.b%zu_out + base + run + e);\n        }\n        run += ucnt;\n      }\n    }\n", ST, b);
+                ++jj;
+            }
+            return d.s;
+        };
         // The predicate masks are redefined opaquely at the phase boundaries: otherwise the compiler
         // extracts every row's bit once, up front, and carries sixteen registers of single bits
         // through all phases (spilling them where the merge code needs the room).
@@ -1219,32 +1338,12 @@ Generated generate(const Loop& L, const Variant& var) {
         // while the first wavefront waits for the tiles before this one, the others merge
         o.s += mm.s;
         o.s += opaque;
+        if (var.pipeline) o.s += resolve_text("t", cb, "");
         o.f("    __syncthreads();\n");
-        j = 0;
-        for (size_t b = 0; b < NB; ++b) {
-            if (var.backend[b] != BK_VEC_COMPACT) continue;
-            o.f("    {\n      i64 base = s_pfx[%d];\n      for (int w = 0; w < wave; ++w) base += s_cnt[%d][w];\n", j, j);
-            // The selected values of one load unit are packed in LDS at their ranks and written
-            // out as one dense run per instruction (lane l writes elements l, l+64, ...), so HBM
-            // sees full lines instead of scattered 8-byte pieces.
-            const char* ST = stype(L.builders[b].val_type[0]);
-            // (a 64-bit value that provably fits 32 bits is staged in 4 bytes and widened at the store)
-            const int vop = L.merges[L.merge_of[b]].val[0];
-            const char* SG = (gathered && L.builders[b].val_type[0] == WELD_I64 && ranges[vop].fits32()) ? "int" : ST;
-            o.f("      %s* const stg = (%s*)(s_stage + wave * W_UNIT);\n", SG, SG);
-            // (how many rows of each load unit are selected is counted again here: a few scalar
-            // instructions, cheaper than holding the counts of every unit through the merge phase)
-            o.f("      int run = 0;\n");
-            o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
-            o.f("        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\");\n");
-            o.f("        int rank = 0, ucnt = 0;\n        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n          const u64 bal = w_ballot(%s);\n          rank += w_rank_below(bal);\n          ucnt += __popcll(bal);\n        }\n", sel_expr(b).c_str());
-            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k)\n          if (%s) stg[rank++] = (%s)%s;\n", sel_expr(b).c_str(), SG, val_expr(b).c_str());
-            o.f("        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\");\n");
-            o.f("        _Pragma(\"unroll\") for (int q = 0; q < W_V; ++q) {\n          const int e = q * 64 + lane;\n");
-            o.f("          if (e < ucnt) __builtin_nontemporal_store((%s)stg[e], a.b%zu_out + base + run + e);\n        }\n        run += ucnt;\n      }\n    }\n", ST, b);
-            ++j;
-        }
-        o.f("%s  }\n", guard_text.c_str());
+        o.s += staging_text(cb, "");
+        o.s += guard_text;
+        if (var.pipeline) o.f("    t = tn;\n");
+        o.f("  }\n");
     }
 
     // ------------------------------------------------------------ builder results

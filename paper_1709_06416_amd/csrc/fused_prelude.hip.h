@@ -380,6 +380,45 @@ __device__ __forceinline__ i64 w_lookback(u64* desc, i64 tile, i64 own, i64 spin
     return excl;
 }
 
+// The same look-back in two steps, for loops that overlap tiles: a tile publishes its own count as
+// soon as it is known and collects the sum of its predecessors later (after its merges), when the
+// tiles in front have had time to publish theirs.  Called by one whole wavefront each.
+__device__ __forceinline__ void w_lookback_publish(u64* desc, i64 tile, i64 own) {
+    if (w_lane() == 0) w_st_agent(desc + tile, (tile == 0 ? W_DESC_PFX : W_DESC_AGG) | (u64)own);
+}
+__device__ __forceinline__ i64 w_lookback_resolve(u64* desc, i64 tile, i64 own, i64 spin_limit, int* err) {
+    const int lane = w_lane();
+    if (tile == 0) return 0;
+    i64 excl = 0;
+    i64 j = tile - 1;
+    i64 spins = 0;
+    bool failed = false;
+    for (;;) {
+        const i64 idx = j - lane;
+        const u64 d = idx >= 0 ? w_ld_agent(desc + idx) : W_DESC_PFX;
+        const u32 state = (u32)(d >> 62);
+        const u64 unpublished = w_ballot(state == 0);
+        const u64 have_prefix = w_ballot(state == 2);
+        const int first = have_prefix ? (int)__builtin_ctzll(have_prefix) : 64;
+        const u64 need = first >= 63 ? ~0ull : ((2ull << first) - 1);
+        if (unpublished & need) {
+            if (++spins > spin_limit) { failed = true; break; }
+            __builtin_amdgcn_s_sleep(2);
+            continue;
+        }
+        const i64 mine = (lane <= first) ? (i64)(d & W_DESC_VAL) : 0;
+        excl += w_wave_reduce<W_FUNC_ADD>(mine);
+        if (first < 64) break;
+        j -= 64;
+    }
+    if (failed) {
+        if (lane == 0) atomicOr(err, 2);
+        excl = 0;
+    }
+    if (lane == 0) w_st_agent(desc + tile, W_DESC_PFX | (u64)(excl + own));
+    return excl;
+}
+
 // ---------------------------------------------------------------- atomics on builders
 template <int F> __device__ __forceinline__ void w_atomic_f64(double* p, double v, const int scope_agent) {
     if (F == W_FUNC_ADD) {

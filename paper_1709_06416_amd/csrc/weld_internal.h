@@ -180,6 +180,7 @@ struct Variant {
     bool compact_sext = false;  // the 64-bit key is the sign extension (else the zero extension) of its low half
     long long compact_guard = 0;// > 0: |constant merged|; a work-group flushes its table before a cell could pass 2^31
     bool own_math = true;       // exp and log evaluated by the library's own code (else the device math library's)
+    int pipeline = 0;          // ticketed loops: 1 = the next tile's columns are loaded while this tile is merged and stored
     std::vector<int> backend;   // per builder
 };
 

@@ -96,6 +96,19 @@ def test_malformed_bodies_are_rejected(wb):
     assert wb.validate(p)[0] == wb.ERR_UNSUPPORTED
 
 
+def test_planner_overlaps_tiles_only_where_the_registers_allow(wb):
+    """Host logic only: which compacting loops load the next tile's columns ahead, read off the generated text."""
+    c5 = wb.generated_source(configs.program_c5())
+    assert "s_tile[2]" in c5 and "w_lookback_publish(" in c5 and "w_lookback_resolve(" in c5
+    assert "s_tile[2]" not in wb.generated_source(configs.program_c5(), tune={"tile_pipeline": -1})
+    grouped = wb.generated_source(configs.program_group_by_zip())      # key, wide value and first probes: too many registers
+    assert "s_tile[2]" not in grouped and "w_lookback(" in grouped
+    assert "s_tile[2]" in wb.generated_source(configs.program_group_by_zip(), tune={"tile_pipeline": 1})
+    p = Program(["i64"])                                                # compaction alone: nothing to hide the loads behind
+    p.merge(p.vecbuilder("i64"), p.col(0), pred=p.bin("gt", p.col(0), p.const("i64", 0)))
+    assert "s_tile[2]" not in wb.generated_source(p)
+
+
 def test_scalars_from_outside_the_loop_validate_and_reach_the_kernel_as_one_load(wb):
     p = Program(["f64", "f64", "i64"])
     x, s, c = p.col(0), p.scalar(1), p.scalar(2)

@@ -1064,6 +1064,45 @@ def test_lazy_groupby_and_materialised_vector(wb):
 
 
 # ----------------------------------------------------------------------
+# compacting loops with the next tile's columns loaded ahead (two tiles of one work-group overlap)
+# ----------------------------------------------------------------------
+def _pipelined_programs():
+    progs = {}
+    p = Program(["i64"])                                          # the C5 shape: the library's own choice is the pipelined form
+    pred = p.bin("gt", p.col(0), p.const("i64", 0))
+    key = p.bin("mod", p.col(0), p.const("i64", 30_000))
+    p.merge(p.vecbuilder("i64"), key, pred=pred)
+    p.merge(p.dictmerger(["i64"], ["i64"], "add", 30_000), [p.const("i64", 1)], keys=[key], pred=pred)
+    progs["filter, vector and count"] = p
+    p = Program(["i32", "f64", "i64"])                            # several columns, two compacted vectors, an f64 dictionary
+    pred = p.bin("lt", p.col(1), p.const("f64", 0.75))
+    p.merge(p.vecbuilder("i32"), p.col(0), pred=pred)
+    p.merge(p.vecbuilder("f64"), p.bin("mul", p.col(1), p.const("f64", 3.0)), pred=pred)
+    p.merge(p.dictmerger(["i64"], ["f64", "i64"], "add", 10_000), [p.col(1), p.const("i64", 1)],
+            keys=[p.bin("mod", p.col(2), p.const("i64", 5_000))], pred=pred)
+    p.merge(p.merger("i64", "max"), p.col(2))
+    progs["three columns, two vectors"] = p
+    p = Program(["i64"])                                          # compaction alone (no merge phase between loads and stores)
+    p.merge(p.vecbuilder("i64"), p.col(0), pred=p.bin("ne", p.bin("mod", p.col(0), p.const("i64", 3)), p.const("i64", 0)))
+    progs["compaction alone"] = p
+    return progs
+
+
+@pytest.mark.parametrize("name", sorted(_pipelined_programs()))
+@pytest.mark.parametrize("n", [0, 1, 16_383, 16_384, 16_385, 1_000_003])
+def test_pipelined_tile_loop_matches_the_oracle(wb, name, n):
+    """Forced on and forced off, on sizes around one tile (16384 rows of a 1024-thread work-group),
+    a ragged last tile and many tiles per work-group; order-preserving vectors are compared element by element."""
+    prog = _pipelined_programs()[name]
+    rnd = np.random.RandomState(n % 1000 + len(name))
+    host = {"i64": rnd.randint(-50_000, 10 ** 9, size=n).astype(np.int64), "i32": rnd.randint(-2 ** 31, 2 ** 31, size=n).astype(np.int32),
+            "f64": rnd.uniform(0, 1, size=n)}
+    cols = [_dev(host[t]) for t in prog.columns]
+    for form in (1, -1):
+        _check(wb, prog, cols, label="%s n=%d tile_pipeline=%d" % (name, n, form), tune={"tile_pipeline": form}, n=n)
+
+
+# ----------------------------------------------------------------------
 # scalars defined outside the loop as operands of its body (Sec. 3.2: the loop's function is a
 # closure; Sec. 4.1: objects depend on the results of other objects)
 # ----------------------------------------------------------------------
