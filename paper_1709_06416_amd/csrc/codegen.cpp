@@ -1093,9 +1093,17 @@ Generated generate(const Loop& L, const Variant& var) {
         // Measured and dropped: loads issued only after the merges (no gain over the plain form), the
         // wavefront that finishes its merges first collecting the sum (2 % slower), the tile's stores
         // moved into the next tile so that one barrier per tile is left (2 % slower, more registers),
-        // the descriptors of the look-back requested before the queued merges are drained (3 % slower).
+        // the descriptors of the look-back requested before the queued merges are drained (3 % slower),
+        // first probes issued in two halves to free registers, and a 24-bit multiplication in the table
+        // hash (both within the noise: the kernel is bound by how little the phases of its one
+        // work-group per compute unit overlap, not by the instructions it issues; two work-groups of
+        // 512 threads with tables of half the size: 0.52 ms against 0.46).
         const std::string cb = var.pipeline ? "[it & 1]" : "";
-        const char* ticket = "(i64)__hip_atomic_fetch_add(a.ctl, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)";
+        // (drawn ahead, the ticket is a wrapping increment rather than an addition: the compiler turns an
+        // addition by some lanes into one by the wavefront's first lane and waits for the result on the
+        // spot, and that wait - with the tile's stores still in flight - would stop the first wavefront)
+        const char* ticket = var.pipeline ? "(i64)__builtin_amdgcn_atomic_inc32(a.ctl, 0xffffffffu, __ATOMIC_RELAXED, \"agent\")"
+                                          : "(i64)__hip_atomic_fetch_add(a.ctl, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)";
         Out prefetch;
         if (var.pipeline) {
             prefetch.f("    const i64 tn = s_tile[(it + 1) & 1];\n");
@@ -1104,6 +1112,18 @@ Generated generate(const Loop& L, const Variant& var) {
             for (int c = 0; c < L.ncols; ++c)
                 if (L.col_used[c]) prefetch.f("        x%d[u] = w_load<%s, W_V>(a.c%d + rn + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
             prefetch.f("      }\n    }\n");
+        }
+        // The loads issued ahead are waited for where nothing else is in flight (before the tile's stores
+        // are issued, by naming their registers in an empty asm statement): the one counter of vector
+        // memory operations cannot tell loads from stores, so a wait for these loads placed where the
+        // next tile first uses them would also wait for this tile's stores to complete.
+        Out landed;
+        if (var.pipeline) {
+            landed.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
+            for (int c = 0; c < L.ncols; ++c)
+                if (L.col_used[c])
+                    landed.f("        asm volatile(\"\" :: \"v\"(%sx%d[u].e[k]));\n", type_size(L.col_type[c]) < 4 ? "(int)" : "", c);
+            landed.f("      }\n");
         }
         o.f("  const i64 ntiles = (a.n + W_TILE - 1) / W_TILE;\n");
         if (var.pipeline) {
@@ -1115,8 +1135,9 @@ Generated generate(const Loop& L, const Variant& var) {
             for (int c = 0; c < L.ncols; ++c)
                 if (L.col_used[c]) o.f("      x%d[u] = w_load<%s, W_V>(a.c%d + rn + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
             o.f("    }\n  }\n");
+            o.s += landed.s;
             o.f("  int it = 0;\n  for (; t < ntiles; ++it) {\n");
-            if (var.pipeline) o.f("    i64 tk = 0;\n    if (threadIdx.x == 0) tk = %s;\n", ticket);
+            if (var.pipeline) o.f("    u32 tk = 0;\n    if (threadIdx.x == 0) tk = (u32)%s;\n", ticket);
         } else {
             o.f("  for (;;) {\n");
             o.f("    if (threadIdx.x == 0) s_tile = %s;\n", ticket);
@@ -1262,13 +1283,18 @@ Generated generate(const Loop& L, const Variant& var) {
             // per load unit: how many rows the wavefront selected and where its run starts; the rank
             // of a row inside the run is recomputed when the values are staged (a few instructions,
             // cheaper than holding sixteen ranks per lane through the merge phase)
-            o.f("    {\n      int wtot = 0;\n");
-            o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n");
-            o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) wtot += __popcll(w_ballot(%s));\n", sel_expr(b).c_str());
+            if (gathered) {
+                // the lane's selected rows are the bits of its mask: one population count and a sum over the wavefront
+                o.f("    {\n      const int wtot = w_wave_sum(__popc(mp%d));\n", L.merges[L.merge_of[b]].pred + 1);
+            } else {
+                o.f("    {\n      int wtot = 0;\n");
+                o.f("      _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u)\n");
+                o.f("        _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) wtot += __popcll(w_ballot(%s));\n", sel_expr(b).c_str());
+            }
             o.f("      if (lane == 0) s_cnt[%d]%s[wave] = wtot;\n    }\n", j, cb.c_str());
             ++j;
         }
-        if (var.pipeline) o.f("    if (threadIdx.x == 0) s_tile[(it + 1) & 1] = tk;\n");
+        if (var.pipeline) o.f("    if (threadIdx.x == 0) s_tile[(it + 1) & 1] = (i64)tk;\n");
         o.f("    __syncthreads();\n");
         if (var.pipeline) o.s += prefetch.s;
         o.f("    if (wave == 0) {\n");
@@ -1340,6 +1366,7 @@ Generated generate(const Loop& L, const Variant& var) {
         o.s += opaque;
         if (var.pipeline) o.s += resolve_text("t", cb, "");
         o.f("    __syncthreads();\n");
+        o.s += landed.s;
         o.s += staging_text(cb, "");
         o.s += guard_text;
         if (var.pipeline) o.f("    t = tn;\n");

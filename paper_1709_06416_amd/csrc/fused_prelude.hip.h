@@ -287,6 +287,18 @@ __device__ __forceinline__ u64 w_ballot(bool p) { return __builtin_amdgcn_ballot
 
 // butterfly reduction over the 64 lanes; every lane ends with the same value, and
 // the combination order is fixed, so the result does not depend on scheduling
+// Sum of an int over the 64 lanes of the wavefront, returned to all of them (data-parallel-primitive
+// adds inside the 16-lane rows, then the rows' last lanes are passed on: no LDS traffic).
+__device__ __forceinline__ int w_wave_sum(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // lane - 1 of the row
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // lane - 2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // lane - 4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // lane - 8: lane 15 of a row holds the row's sum
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, true);   // rows 1 and 3 add lane 15 of the row before
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, true);   // rows 2 and 3 add lane 31
+    return __builtin_amdgcn_readlane(v, 63);
+}
+
 template <int F, class T> __device__ __forceinline__ T w_wave_reduce(T v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v = w_combine<F>(v, __shfl_xor(v, off, 64));
@@ -480,14 +492,14 @@ template <int F> __device__ __forceinline__ void w_atomic(i64* p, i64 v, const i
 template <i64 D, bool CONV> __device__ __forceinline__ i64 w_div_const(i64 x, bool live) {
     if (CONV) {
         if (!live) x = 0;
-        if (w_ballot((u64)x >> 32 != 0) == 0) return (i64)((u32)x / (u32)D);
+        if (__builtin_expect(w_ballot((u64)x >> 32 != 0) == 0, 1)) return (i64)((u32)x / (u32)D);
     }
     return x / D;
 }
 template <i64 D, bool CONV> __device__ __forceinline__ i64 w_mod_const(i64 x, bool live) {
     if (CONV) {
         if (!live) x = 0;
-        if (w_ballot((u64)x >> 32 != 0) == 0) return (i64)((u32)x % (u32)D);
+        if (__builtin_expect(w_ballot((u64)x >> 32 != 0) == 0, 1)) return (i64)((u32)x % (u32)D);
     }
     return x % D;
 }
