@@ -87,8 +87,9 @@ struct GroupScatter {
     unsigned int* tmp_group;               // group of each partitioned pair
     unsigned long long* tmp_value;         // its value (bits)
 };
+// desc: one zeroed 8-byte word per 8192 groups of the capacity; err: the call's error word; max_blocks: work-groups resident at once
 hipError_t launch_group_offsets(const void* counts, const void* ngroups, int64_t capacity, void* offsets, void* cursor,
-                                hipStream_t stream);
+                                void* desc, void* err, int max_blocks, hipStream_t stream);
 hipError_t launch_group_scatter(const GroupScatter& g, int blocks, hipStream_t stream);
 // The same in two kernels for dictionaries of many groups: partition the pairs by group range,
 // then place every range's pairs (both read g.ngroups and the offsets on the device).

@@ -232,20 +232,24 @@ hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots,
 }
 
 // ---------------------------------------------------------------- groupbuilder
-// Exclusive prefix sums of the group sizes by one work-group, 8192 groups a round: a thread
-// loads eight neighbouring sizes, the 1024 partial sums are scanned across the work-group on
-// top of the running total, and the thread writes its eight offsets.
+// Exclusive prefix sums of the group sizes, 8192 groups a round, one round per work-group at a time:
+// a thread loads eight neighbouring sizes, the 1024 partial sums are scanned across the work-group, the
+// round's total is published in `desc` and the sum of the rounds before it collected from there
+// (decoupled look-back: bits 63..62 of a descriptor = 0 nothing yet, 1 the round's own total, 2 the
+// total of all rounds up to it), and the thread writes its eight offsets.  The grid never exceeds
+// what is resident at once, so a round only waits for work-groups that are running; the wait is
+// bounded all the same (error bit 2, the call then reports a device error).
 __global__ void __launch_bounds__(1024) group_offsets_kernel(const i64* counts, const u64* ngroups, i64 capacity,
-                                                             i64* offsets, u64* cursor) {
+                                                             i64* offsets, u64* cursor, u64* desc, int* err) {
     __shared__ i64 s_wave[16];
     __shared__ i64 s_carry;
     const int tid = threadIdx.x;
     i64 n = (i64)*ngroups;
     if (n > capacity) n = capacity;
     const bool aligned16 = (((uintptr_t)counts | (uintptr_t)offsets | (uintptr_t)cursor) & 15) == 0;
-    if (tid == 0) s_carry = 0;
-    __syncthreads();
-    for (i64 base = 0; base < n; base += 8192) {
+    if (n == 0 && blockIdx.x == 0 && tid == 0) offsets[0] = 0;
+    for (i64 round = blockIdx.x; round * 8192 < n; round += gridDim.x) {
+        const i64 base = round * 8192;
         i64 c[8];
         i64 mine = 0;
         const bool whole = base + 8192 <= n && aligned16;      // every thread's eight groups exist
@@ -276,6 +280,49 @@ __global__ void __launch_bounds__(1024) group_offsets_kernel(const i64* counts, 
         }
         if ((tid & 63) == 63) s_wave[tid >> 6] = incl;
         __syncthreads();
+        if (tid < 64) {
+            i64 total = 0;
+#pragma unroll
+            for (int w = 0; w < 16; ++w) total += s_wave[w];
+            // publish, then walk back over the rounds before this one, 64 at a time
+            i64 excl = 0;
+            if (round == 0) {
+                if (tid == 0) __hip_atomic_store(desc, (2ull << 62) | (u64)total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                if (tid == 0) __hip_atomic_store(desc + round, (1ull << 62) | (u64)total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                i64 j = round - 1, spins = 0;
+                bool failed = false;
+                for (;;) {
+                    const i64 idx = j - tid;
+                    const u64 d = idx >= 0 ? __hip_atomic_load(desc + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : (2ull << 62);
+                    const u32 state = (u32)(d >> 62);
+                    const u64 unpublished = __ballot(state == 0);
+                    const u64 have_prefix = __ballot(state == 2);
+                    const int first = have_prefix ? (int)__builtin_ctzll(have_prefix) : 64;
+                    const u64 need = first >= 63 ? ~0ull : ((2ull << first) - 1);
+                    if (unpublished & need) {
+                        if (++spins > (1 << 22)) { failed = true; break; }
+                        __builtin_amdgcn_s_sleep(2);
+                        continue;
+                    }
+                    i64 part = (tid <= first) ? (i64)(d & ((1ull << 62) - 1)) : 0;
+                    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+                    excl += part;
+                    if (first < 64) break;
+                    j -= 64;
+                }
+                if (failed) {
+                    if (tid == 0) atomicOr(err, 2);
+                    excl = 0;
+                }
+                if (tid == 0) __hip_atomic_store(desc + round, (2ull << 62) | (u64)(excl + total), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (tid == 0) {
+                s_carry = excl;
+                if (base + 8192 >= n) offsets[n] = excl + total;     // the last round closes the array
+            }
+        }
+        __syncthreads();
         i64 run = s_carry + incl - mine;
         for (int w = 0; w < (tid >> 6); ++w) run += s_wave[w];
         if (whole) {
@@ -303,16 +350,16 @@ __global__ void __launch_bounds__(1024) group_offsets_kernel(const i64* counts, 
             }
         }
         __syncthreads();
-        if (tid == 1023) s_carry = run;
-        __syncthreads();
     }
-    if (tid == 0) offsets[n] = s_carry;
 }
 
 hipError_t launch_group_offsets(const void* counts, const void* ngroups, int64_t capacity, void* offsets, void* cursor,
-                                hipStream_t stream) {
-    group_offsets_kernel<<<dim3(1), dim3(1024), 0, stream>>>((const i64*)counts, (const u64*)ngroups, capacity,
-                                                             (i64*)offsets, (u64*)cursor);
+                                void* desc, void* err, int max_blocks, hipStream_t stream) {
+    int64_t blocks = (capacity + 8191) / 8192;
+    if (blocks > max_blocks) blocks = max_blocks;
+    if (blocks < 1) blocks = 1;
+    group_offsets_kernel<<<dim3((unsigned)blocks), dim3(1024), 0, stream>>>((const i64*)counts, (const u64*)ngroups, capacity,
+                                                                              (i64*)offsets, (u64*)cursor, (u64*)desc, (int*)err);
     return hipGetLastError();
 }
 
@@ -506,6 +553,8 @@ __device__ __forceinline__ void groups_of_keys(const GroupScatter& a, u64* s_ck,
             }
         }
     }
+    // (requesting the home slot's group number together with its key, to save the second read its wait,
+    // costs more in cache lines moved than it saves: 1.07 -> 1.17 ms)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         slot[j] = (i64)table_hash_slot(kb[j], (u32)a.slots);
@@ -558,6 +607,21 @@ __global__ void __launch_bounds__(1024) group_partition_kernel(const GroupScatte
         s_cg[q] = ~0u;
     }
     __syncthreads();
+    // the pairs of the work-group's next tile are loaded while this tile is ranked, sorted and stored
+    u64 nval[4], nkb[4];
+    auto load_tile = [&](i64 t) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const i64 i = t * GROUP_TILE + j * 1024 + tid;
+            nkb[j] = 0;
+            nval[j] = 0;
+            if (i < npairs) {
+                for (int k = 0; k < a.nkeys; ++k) nkb[j] |= load_bits(a.key[k], i, a.key_size[k]) << a.key_shift[k];
+                nval[j] = load_bits(a.value, i, a.value_size);
+            }
+        }
+    };
+    if ((i64)blockIdx.x < ntiles) load_tile(blockIdx.x);
     for (i64 t = blockIdx.x; t < ntiles; t += gridDim.x) {
         u32 rank[4];
         u64 val[4], kb[4];
@@ -565,15 +629,11 @@ __global__ void __launch_bounds__(1024) group_partition_kernel(const GroupScatte
         bool live[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const i64 i = t * GROUP_TILE + j * 1024 + tid;
-            live[j] = i < npairs;
-            kb[j] = 0;
-            val[j] = 0;
-            if (live[j]) {
-                for (int k = 0; k < a.nkeys; ++k) kb[j] |= load_bits(a.key[k], i, a.key_size[k]) << a.key_shift[k];
-                val[j] = load_bits(a.value, i, a.value_size);
-            }
+            live[j] = t * GROUP_TILE + j * 1024 + tid < npairs;
+            kb[j] = nkb[j];
+            val[j] = nval[j];
         }
+        if (t + gridDim.x < ntiles) load_tile(t + gridDim.x);
         groups_of_keys(a, s_ck, s_cg, kb, live, gid);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -654,25 +714,40 @@ __global__ void __launch_bounds__(1024) group_place_kernel(const GroupScatter a)
     for (int q = tid; q < PLACE_MAX_BUCKET; q += 1024) s_cnt[q] = 0;
     __syncthreads();
     const i64 total = s_first[256];
-    for (i64 w = blockIdx.x; w < total; w += gridDim.x) {
+    // the chunk after this one is loaded while this one is counted and stored
+    u32 ngrp[8];
+    u64 nval[8];
+    i64 n_lo = 0, n_hi = 0;
+    auto load_chunk = [&](i64 w) {
         int b = 0;                                 // last range with s_first[b] <= w
         for (int step = 128; step > 0; step >>= 1)
             if (b + step < 256 && s_first[b + step] <= w) b += step;
-        const i64 lo_g = (i64)b * B < G ? (i64)b * B : G, hi_g = (i64)(b + 1) * B < G ? (i64)(b + 1) * B : G;
-        const i64 start = a.offsets[lo_g] + (w - s_first[b]) * PLACE_CHUNK;
-        const i64 stop = a.offsets[hi_g];
+        n_lo = (i64)b * B < G ? (i64)b * B : G;
+        n_hi = (i64)(b + 1) * B < G ? (i64)(b + 1) * B : G;
+        const i64 start = a.offsets[n_lo] + (w - s_first[b]) * PLACE_CHUNK;
+        const i64 stop = a.offsets[n_hi];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const i64 i = start + j * 1024 + tid;
+            ngrp[j] = ~0u;
+            nval[j] = 0;
+            if (i < stop) {
+                ngrp[j] = __builtin_nontemporal_load(a.tmp_group + i);
+                nval[j] = __builtin_nontemporal_load(a.tmp_value + i);
+            }
+        }
+    };
+    if ((i64)blockIdx.x < total) load_chunk(blockIdx.x);
+    for (i64 w = blockIdx.x; w < total; w += gridDim.x) {
+        const i64 lo_g = n_lo, hi_g = n_hi;
         u32 rank[8], local[8];
         u64 val[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const i64 i = start + j * 1024 + tid;
-            local[j] = ~0u;
-            val[j] = 0;
-            if (i < stop) {
-                local[j] = __builtin_nontemporal_load(a.tmp_group + i) - (u32)lo_g;
-                val[j] = __builtin_nontemporal_load(a.tmp_value + i);
-            }
+            local[j] = ngrp[j] == ~0u ? ~0u : ngrp[j] - (u32)lo_g;
+            val[j] = nval[j];
         }
+        if (w + gridDim.x < total) load_chunk(w + gridDim.x);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             rank[j] = 0;

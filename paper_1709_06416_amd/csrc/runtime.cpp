@@ -367,7 +367,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     const int64_t mem_limit = st ? (int64_t)st->scratch_bytes : conf.memory_limit;
     auto take_out = [&](size_t bytes) -> size_t { return st ? 0 : lay.take(bytes); };
     struct Off { size_t part = 0, res = 0, out = 0, desc = 0, keys = 0, vals[8] = {0}, okeys = 0, ovals = 0, log = 0, qcnt = 0,
-                        slot_pos = 0, goffsets = 0, gcursor = 0, gvalues = 0, gbcursor = 0, gtmp_group = 0, gtmp_value = 0,
+                        slot_pos = 0, goffsets = 0, gcursor = 0, gdesc = 0, gvalues = 0, gbcursor = 0, gtmp_group = 0, gtmp_value = 0,
                         ovf = 0, ovf_count = 0;
                         int64_t slots = 0, qcap = 0; int glog = -1; };
     auto link_of = [&](size_t b) -> const GroupLink* {
@@ -407,6 +407,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
                     off[b].slot_pos = lay.take(4 * (size_t)(slots + 1));
                     off[b].goffsets = lay.take(8 * (size_t)(s.capacity + 1));
                     off[b].gcursor = lay.take(8 * (size_t)s.capacity);
+                    off[b].gdesc = lay.take(8 * (size_t)((s.capacity + 8191) / 8192));
                     off[b].gvalues = lay.take((size_t)n * type_size(L.builders[g->val_vec].val_type[0]));
                 }
             }
@@ -422,7 +423,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         for (size_t b = 0; b < NB; ++b) {
             const weld_builder_spec_t& s = L.builders[b];
             if (!link_of(b) || s.capacity <= 1024 || s.capacity > 256 * 4096) continue;
-            int lg = 9;
+            int lg = 10;     // (1e5 groups: 98 ranges of 1024 give the partition longer runs to write than 196 of 512: 2.42 -> 2.34 ms)
             while (((int64_t)256 << lg) < s.capacity) ++lg;
             const size_t need = 12 * (size_t)n + 256 * 8 + 1024;
             if (mem_limit > 0 && (int64_t)(lay.total + need + still_to_come) > mem_limit) continue;
@@ -589,6 +590,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
                 if ((h = fill(base + off[b].vals[k], off[b].slots + 1, ident_bits(s.func, s.val_type[k]))) != hipSuccess)
                     return hip_err("fill", h);
             if (off[b].glog >= 0 && (h = fill(base + off[b].gbcursor, 256, 0)) != hipSuccess) return hip_err("fill", h);
+            if (link_of(b) && (h = fill(base + off[b].gdesc, (s.capacity + 8191) / 8192, 0)) != hipSuccess) return hip_err("fill", h);
             if (var.spill_slices && var.backend[b] == BK_DICT_LDS && (h = fill(base + off[b].ovf_count, 1, 0)) != hipSuccess) return hip_err("fill", h);
         }
     }
@@ -689,7 +691,8 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         if (!g) continue;
         // groupbuilder: group sizes -> offsets, then every compacted pair to its group's vector
         h = launch_group_offsets(op[b].ovals, base + off_ctl + ctl_count_off((int)b), s.capacity,
-                                 base + off[b].goffsets, base + off[b].gcursor, stream);
+                                 base + off[b].goffsets, base + off[b].gcursor, base + off[b].gdesc, base + off_ctl + 8,
+                                 device_info().cus, stream);
         if (h != hipSuccess) return hip_err("group offsets", h);
         GroupScatter gs;
         memset(&gs, 0, sizeof gs);

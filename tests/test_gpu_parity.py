@@ -1297,7 +1297,7 @@ def test_groupbuilder_capacity_error_and_unfused_mode(wb):
 @pytest.mark.parametrize("capacity", [1_024, 1_025, 40_000, 131_073, 1_048_576, 2_000_000])
 @pytest.mark.parametrize("vt", ["i8", "f64"])
 def test_groupbuilder_placement_paths(wb, capacity, vt):
-    """Few groups are placed by one kernel, many by partitioning into ranges of groups first (512
+    """Few groups are placed by one kernel, many by partitioning into ranges of groups first (1024
     to 4096 groups a range by capacity), very many by the one kernel again; keys whose packed
     bits are the table's marker, capacities one past a power of two, 1- and 8-byte values."""
     rnd = np.random.RandomState(capacity % 1000 + len(vt))
@@ -1309,6 +1309,19 @@ def test_groupbuilder_placement_paths(wb, capacity, vt):
     p = Program(["i64", vt])
     p.merge(p.groupbuilder(["i64"], vt, capacity), p.col(1), keys=[p.col(0)], pred=p.bin("ne", p.col(0), p.const("i64", 5)))
     _check(wb, p, [_dev(keys), _dev(vals)], label="groups cap %d %s" % (capacity, vt))
+
+
+def test_groupbuilder_offsets_over_more_rounds_than_work_groups(wb):
+    """2.2e6 groups: the offsets are scanned 8192 groups a round by at most one work-group per compute
+    unit, so here every work-group takes a second round and looks back at rounds of other work-groups."""
+    n = 2_200_000
+    rnd = np.random.RandomState(12)
+    keys = rnd.permutation(n).astype(np.int64) * 7 - 3
+    keys[:200_000] = keys[200_000:400_000]                    # some groups of two, some keys absent
+    vals = np.arange(n, dtype=np.int64)
+    p = Program(["i64", "i64"])
+    p.merge(p.groupbuilder(["i64"], "i64", n), p.col(1), keys=[p.col(0)])
+    _check(wb, p, [_dev(keys), _dev(vals)], label="groups, 269 rounds of offsets")
 
 
 def test_groupbuilder_without_room_for_the_partition_scratch(wb):
