@@ -250,9 +250,10 @@ def main():
                     if i >= 2:
                         ts.append(r.kernel_ms())
                     total = int(r.vec(0).sum().item()) if i == 0 else nk
+                    kname = r.kernel_name()
                     r.free()
                     assert total == nk
-                sweep.append({"length": m, "strategy": label, "kernel_ms": round(median(ts), 4),
+                sweep.append({"length": m, "strategy": label, "kernel": kname, "kernel_ms": round(median(ts), 4),
                               "keys_per_s": nk / median(ts) * 1e3})
             del keys
 

@@ -120,6 +120,8 @@ struct SpillMerge {
     // 0: entries are 1 + nvals words; 1 / 2: one word per entry, low half = the key (zero- / sign-extended
     // to the packed 64-bit key), high half = the value, a signed 32-bit partial sum (nvals == 1, func = add)
     int compact;
+    long long capacity;            // the dictmerger's declared capacity (sizes the aggregation's LDS tables)
+    int table_slots, split;        // set by launch_dict_spill_merge
 };
 hipError_t launch_dict_spill_merge(const SpillMerge& a, int nvals, hipStream_t stream);
 // Dictionaries of millions of keys: partition p of the queues holds the keys whose home slot lies in

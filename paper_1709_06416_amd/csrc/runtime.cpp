@@ -630,6 +630,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         sm.slots = off[b].slots;
         sm.err = (int*)(base + off_ctl + 8);
         sm.compact = var.compact == (int)b ? (var.compact_sext ? 2 : 1) : 0;
+        sm.capacity = s.capacity;
         if (var.spill_slices) {
             sm.parts = var.spill_parts;
             sm.overflow = (unsigned long long*)(base + off[b].ovf);

@@ -62,14 +62,22 @@ __device__ __forceinline__ int lds_slot_looped(u64* keys, int slots, u64 kbits, 
 
 // COMPACT (NV == 1, FUNC == add): an entry is ONE word, low half the key (1: zero-extended, 2: sign-extended
 // to the packed key), high half a signed 32-bit partial sum.
+// The LDS table has a.table_slots slots (a power of two, sized by the host from the dictionary's
+// capacity: a partition holds about 1/256 of the keys) and lies in dynamic LDS; a.split work-groups
+// share a partition's entries, each with a table of its own, so that a dictionary of few keys per
+// partition has two work-groups per compute unit at work instead of one.
 template <int NV, int FUNC, int COMPACT = 0>
 __global__ void __launch_bounds__(1024) dict_spill_merge_kernel(const SpillMerge a) {
-    constexpr int S = SpillTable<NV>::kSlots;
-    __shared__ u64 s_keys[S];
-    __shared__ u64 s_vals[NV][S];
+    extern __shared__ u64 s_dyn[];
+    const int S = a.table_slots;
+    u64* const s_keys = s_dyn;
+    u64* s_vals[NV];
+#pragma unroll
+    for (int k = 0; k < NV; ++k) s_vals[k] = s_dyn + (size_t)S * (1 + k);
     __shared__ u32 s_off[1025];
     __shared__ u32 s_wave[16];
-    const int part = blockIdx.x;
+    const int part = blockIdx.x / a.split;
+    const int sub = blockIdx.x % a.split;
     const int tid = threadIdx.x;
     for (int q = tid; q < S; q += 1024) {
         s_keys[q] = W_EMPTY_KEY;
@@ -96,6 +104,7 @@ __global__ void __launch_bounds__(1024) dict_spill_merge_kernel(const SpillMerge
     if (tid == 0) s_off[0] = 0;
     __syncthreads();
     const u32 total = s_off[a.groups];
+    const float guess = total ? (float)a.groups / (float)total : 0.f;
 
     // adds one entry to the global table: for what the LDS table cannot take, and for the
     // LDS table's own contents at the end
@@ -123,7 +132,9 @@ __global__ void __launch_bounds__(1024) dict_spill_merge_kernel(const SpillMerge
             if (i < total) {
                 // the segment of entry i: segments of one partition are about equally long, so
                 // start from the proportional guess and walk (s_off[lo] <= i < s_off[lo + 1])
-                int lo = (int)(((u64)i * (u64)a.groups) / total);
+                // (the guess is a float product, not a 64-bit division per entry)
+                int lo = (int)((float)i * guess);
+                lo = lo < 0 ? 0 : (lo >= a.groups ? a.groups - 1 : lo);
                 while (s_off[lo] > i) --lo;
                 while (s_off[lo + 1] <= i) ++lo;
                 const u64* e = a.log + (((size_t)lo * kSpillParts + part) * (size_t)a.cap + (i - s_off[lo])) * WORDS;
@@ -141,9 +152,10 @@ __global__ void __launch_bounds__(1024) dict_spill_merge_kernel(const SpillMerge
                     for (int q = 0; q < WORDS; ++q) buf[q] = e[q];
                 }
                 if (COMPACT) {
-                    const u32 lo = (u32)buf[0];
-                    k[j] = COMPACT == 2 ? (u64)(i64)(int)lo : (u64)lo;
-                    w[j][0] = (u64)(i64)(int)(u32)(buf[0] >> 32);
+                    // the word is taken apart where it is used: arithmetic on it here would make this
+                    // load wait for its data on the spot, one load after the other (76 -> 63 us on C5)
+                    k[j] = buf[0];
+                    w[j][0] = 0;
                 } else {
                     k[j] = buf[0];
 #pragma unroll
@@ -156,14 +168,24 @@ __global__ void __launch_bounds__(1024) dict_spill_merge_kernel(const SpillMerge
             }
         }
     };
-    fetch(0, kcur, vcur);
-    for (u32 i0 = 0; i0 < total; i0 += 1024u * ENT) {
-        fetch(i0 + 1024u * ENT, knext, vnext);
+    const u32 stride = 1024u * ENT * (u32)a.split;      // the partition's rounds are dealt to its work-groups in turn
+    fetch((u32)sub * 1024u * ENT, kcur, vcur);
+    for (u32 i0 = (u32)sub * 1024u * ENT; i0 < total; i0 += stride) {
+        fetch(i0 + stride, knext, vnext);
         // first probe of all entries of the round side by side (one LDS latency instead of
         // one per entry); an entry whose first slot holds another key or nothing goes the
         // whole way (claim the free slot, or probe on)
         int sl[ENT];
         u64 first[ENT];
+        if (COMPACT) {
+#pragma unroll
+            for (int j = 0; j < ENT; ++j) {
+                const u64 word = kcur[j];
+                const u32 lo = (u32)word;
+                kcur[j] = COMPACT == 2 ? (u64)(i64)(int)lo : (u64)lo;
+                vcur[j][0] = (u64)(i64)(int)(u32)(word >> 32);
+            }
+        }
 #pragma unroll
         for (int j = 0; j < ENT; ++j) {
             sl[j] = (int)w_hash_slot(kcur[j], (u32)S);
@@ -274,6 +296,7 @@ __global__ void __launch_bounds__(1024) dict_slice_build_kernel(const SpillMerge
     if (tid == 0) s_off[0] = 0;
     __syncthreads();
     const u32 total = s_off[a.groups];
+    const float guess = total ? (float)a.groups / (float)total : 0.f;
     // four entries per thread at a time, all loaded before the first is merged
     for (u32 i0 = (u32)tid; i0 < total; i0 += 4096u) {
         u64 key[4], w[4][NV];
@@ -287,7 +310,8 @@ __global__ void __launch_bounds__(1024) dict_slice_build_kernel(const SpillMerge
             for (int f = 0; f < NV; ++f) w[q][f] = 0;
             if (!live[q]) continue;
             // the segment of entry i (segments of one partition are about equally long: proportional guess, then walk)
-            int lo = (int)(((u64)i * (u64)a.groups) / total);
+            int lo = (int)((float)i * guess);
+            lo = lo < 0 ? 0 : (lo >= a.groups ? a.groups - 1 : lo);
             while (s_off[lo] > i) --lo;
             while (s_off[lo + 1] <= i) ++lo;
             const u64* e = a.log + (((size_t)lo * a.parts + part) * (size_t)a.cap + (i - s_off[lo])) * WORDS;
@@ -390,22 +414,38 @@ hipError_t launch_dict_slice_build(const SpillMerge& a, int nvals, hipStream_t s
 }
 
 template <int NV>
-static hipError_t launch_nv(const SpillMerge& a, hipStream_t stream) {
-    const dim3 grid(kSpillParts), block(1024);
+static hipError_t launch_nv(const SpillMerge& in, hipStream_t stream) {
+    SpillMerge a = in;
+    // table: four slots per key the partition is expected to hold (capacity / 256), at least 1024, at
+    // most what 128 KiB take; two work-groups per partition where two such tables fit a compute unit
+    // (more work-groups per partition gained nothing: they do not start any sooner)
+    constexpr int kMax = SpillTable<NV>::kSlots;
+    int slots = 1024;
+    while (slots < kMax && (long long)slots * kSpillParts < 4 * a.capacity) slots *= 2;
+    if (slots > kMax) slots = kMax;
+    a.table_slots = slots;
+    a.split = kMax / slots >= 2 ? 2 : 1;
+    const dim3 grid(kSpillParts * a.split), block(1024);
+    const size_t lds = (size_t)slots * 8 * (1 + NV);
+    auto go = [&](void (*kern)(const SpillMerge)) -> hipError_t {
+        if (lds > 65536) {      // more dynamic LDS than a kernel gets without asking
+            const hipError_t he = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (he != hipSuccess) return he;
+        }
+        kern<<<grid, block, lds, stream>>>(a);
+        return hipGetLastError();
+    };
     if (a.compact) {
         if (NV != 1 || a.func != W_FUNC_ADD) return hipErrorInvalidValue;
-        if (a.compact == 2) dict_spill_merge_kernel<1, W_FUNC_ADD, 2><<<grid, block, 0, stream>>>(a);
-        else dict_spill_merge_kernel<1, W_FUNC_ADD, 1><<<grid, block, 0, stream>>>(a);
-        return hipGetLastError();
+        return a.compact == 2 ? go(dict_spill_merge_kernel<1, W_FUNC_ADD, 2>) : go(dict_spill_merge_kernel<1, W_FUNC_ADD, 1>);
     }
     switch (a.func) {
-        case W_FUNC_ADD: dict_spill_merge_kernel<NV, W_FUNC_ADD><<<grid, block, 0, stream>>>(a); break;
-        case W_FUNC_MUL: dict_spill_merge_kernel<NV, W_FUNC_MUL><<<grid, block, 0, stream>>>(a); break;
-        case W_FUNC_MIN: dict_spill_merge_kernel<NV, W_FUNC_MIN><<<grid, block, 0, stream>>>(a); break;
-        case W_FUNC_MAX: dict_spill_merge_kernel<NV, W_FUNC_MAX><<<grid, block, 0, stream>>>(a); break;
+        case W_FUNC_ADD: return go(dict_spill_merge_kernel<NV, W_FUNC_ADD>);
+        case W_FUNC_MUL: return go(dict_spill_merge_kernel<NV, W_FUNC_MUL>);
+        case W_FUNC_MIN: return go(dict_spill_merge_kernel<NV, W_FUNC_MIN>);
+        case W_FUNC_MAX: return go(dict_spill_merge_kernel<NV, W_FUNC_MAX>);
         default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 hipError_t launch_dict_spill_merge(const SpillMerge& a, int nvals, hipStream_t stream) {
