@@ -315,7 +315,7 @@ def main():
                 if i >= args.warmup:
                     ts.append(r.elapsed_ms())
                 if i == 0:
-                    gk, go, gv = r.groups(0, sort=False)
+                    gk, go, gv = r.groups(0)
                     npairs, ngroups = int(len(gv)), int(len(gk[0]))
                     assert int(go[-1]) == npairs
                 gname = r.kernel_name()

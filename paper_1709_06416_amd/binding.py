@@ -382,8 +382,8 @@ class Result:
         t = self._program.builders[idx]["type"]
         return self._fetch_host(idx, 0, n * np.dtype(TYPE_NP[t]).itemsize).view(TYPE_NP[t])
 
-    def dict(self, idx, sort=True):
-        """dictmerger result as (key columns, value columns); sorted by key on request."""
+    def dict(self, idx):
+        """dictmerger result as (key columns, value columns), in the order the library stores them (unspecified)."""
         self.check()
         spec = self._program.builders[idx]
         p = lib.weld_result_data(self._h, idx)
@@ -397,16 +397,12 @@ class Result:
         vals = self._fetch_host(idx, 1, n * vdt.itemsize).view(vdt)
         kcols = [np.ascontiguousarray(keys[name]) for name in kdt.names]
         vcols = [np.ascontiguousarray(vals[name]) for name in vdt.names]
-        if sort and n:
-            order = np.lexsort(tuple(reversed(kcols)))
-            kcols = [k[order] for k in kcols]
-            vcols = [v[order] for v in vcols]
         return kcols, vcols
 
-    def groups(self, idx, sort=True):
+    def groups(self, idx):
         """groupbuilder result as (key columns, offsets, values): the values of group g are
-        values[offsets[g]:offsets[g+1]].  sort=True: groups ordered by key and the values of each
-        group ascending (the library leaves both orders unspecified)."""
+        values[offsets[g]:offsets[g+1]]; the order of the groups and of the values inside a group is
+        the library's (unspecified)."""
         self.check()
         spec = self._program.builders[idx]
         p = lib.weld_result_data(self._h, idx)
@@ -419,16 +415,6 @@ class Result:
         offsets = self._fetch_host(idx, 1, (ng + 1) * 8).view(np.int64)
         values = self._fetch_host(idx, 2, nv * np.dtype(vt).itemsize).view(vt)
         kcols = [np.ascontiguousarray(keys[name]) for name in kdt.names]
-        if sort and ng:
-            sizes = np.diff(offsets)
-            gid = np.repeat(np.arange(ng), sizes)                     # group of every value, storage order
-            rank = np.empty(ng, dtype=np.int64)
-            order = np.lexsort(tuple(reversed(kcols)))
-            rank[order] = np.arange(ng)                                # position of each group once sorted by key
-            by = np.lexsort((values, rank[gid]))                       # by group (sorted), then by value
-            values = values[by]
-            kcols = [k[order] for k in kcols]
-            offsets = np.concatenate([[0], np.cumsum(sizes[order])]).astype(np.int64)
         return kcols, offsets, values
 
     def free(self):

@@ -10,6 +10,8 @@ import numpy as np
 import pytest
 import torch
 
+from tests import parity
+
 from workloads import configs
 from workloads.ir import Program
 
@@ -67,7 +69,7 @@ def test_c5_full_size_compaction_and_counts(wb):
     prog = configs.program_c5()
     res = wb.fused_for(prog, cols).check()
     got_vec = res.vec_host(0)
-    keys, vals = res.dict(1)
+    keys, vals = parity.sorted_dict(res, 1)
     res.free()
     want_vec, (wkeys, wvals) = interp.run(prog, _host(cols))
     assert len(got_vec) == len(want_vec)
@@ -103,7 +105,7 @@ def test_c4_full_size_groups(wb):
     n = configs.FULL_ROWS["C4"]
     cols = configs.make_columns("C4", n, device="cuda")
     res = wb.fused_for(configs.program_c4(), cols).check()
-    keys, vals = res.dict(0)
+    keys, vals = parity.sorted_dict(res, 0)
     res.free()
     assert list(zip(keys[0].tolist(), keys[1].tolist())) == [(f, s) for f in range(3) for s in range(2)]
     host = _host(cols)
@@ -192,7 +194,7 @@ def test_groupbuilder_full_size_on_the_zip_code_column(wb):
     key = p.bin("mod", c, p.const("i64", 100_000))
     p.merge(p.groupbuilder(["i64"], "i64", 100_000), c, keys=[key], pred=pred)
     res = wb.fused_for(p, cols).check()
-    keys, offsets, values = res.groups(0, sort=True)
+    keys, offsets, values = parity.sorted_groups(res, 0)
     res.free()
     wkeys, woff, wvals = interp.run(p, _host(cols))[0]
     assert np.array_equal(keys[0], wkeys[0]) and np.array_equal(offsets, woff)
@@ -212,7 +214,7 @@ def test_join_full_size_against_the_oracle_on_the_rows_that_matter(wb):
     build, probe = joins.program_build(), joins.program_probe()
     built = wb.fused_for(build, orders)
     res = wb.fused_for(probe, lines, dicts=[(built, 0)]).check()
-    keys, vals = res.dict(0)
+    keys, vals = parity.sorted_dict(res, 0)
     res.free()
     built.check()
     built.free()
@@ -257,7 +259,7 @@ def test_more_than_two_to_the_31_rows(wb):
         assert kept.numel() == int(keep.sum())
         assert torch.equal(kept.cpu(), torch.from_numpy(host[keep]))
         del kept
-        keys, vals = res.dict(3)
+        keys, vals = parity.sorted_dict(res, 3)
         counts = np.bincount(host[keep].astype(np.int64) + 128, minlength=256)
         assert dict(zip(keys[0].tolist(), vals[0].tolist())) == {k - 128: int(c) for k, c in enumerate(counts) if c}
     finally:

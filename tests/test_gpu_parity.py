@@ -12,6 +12,8 @@ import numpy as np
 import pytest
 import torch
 
+from tests import parity
+
 from workloads import configs
 from workloads.ir import Program
 
@@ -390,7 +392,7 @@ def test_compact_cells_are_flushed_before_a_partial_sum_overflows(wb):
     p.merge(p.dictmerger(["i64"], ["i64"], "add", 20_000), [p.const("i64", 1000)], keys=[p.bin("mod", p.col(0), p.const("i64", 3))])
     assert "flush_d0(); wg_rows = 0;" in wb.generated_source(p)
     res = wb.fused_for(p, [x], tune={"grid_blocks": 1, "dict_strategy": 2}).check()
-    keys, vals = res.dict(0)
+    keys, vals = parity.sorted_dict(res, 0)
     res.free()
     assert keys[0].tolist() == [0, 1, 2]
     assert vals[0].tolist() == [1000 * ((n + 2 - r) // 3) for r in range(3)]       # closed form, far above 2^31
@@ -607,7 +609,7 @@ def test_edge_values_follow_the_documented_readings(wb):
         m.merge(m.dictmerger(["i64"], ["f64"], func, 4), [m.col(0)], keys=[m.bin("mod", m.index(), m.const("i64", 3))])
         res = wb.fused_for(m, [_dev(v)]).check()
         assert np.isnan(float(res.merger(0)))
-        keys, vals = res.dict(1)
+        keys, vals = parity.sorted_dict(res, 1)
         res.free()
         assert keys[0].tolist() == [0, 1, 2] and np.isnan(vals[0][31_337 % 3]) and not np.isnan(vals[0][(31_337 + 1) % 3])
     big = np.array([nan, 1e30, -1e30, 9.3e18, -9.3e18, 9.2e18, inf, -inf, 2.5, -2.5] * 300)
@@ -780,8 +782,8 @@ def test_fused_equals_unfused_on_the_gpu(wb):
     a = _run(wb, prog, cols).check()
     b = _run(wb, prog, cols, mode="unfused").check()
     assert np.array_equal(a.vec_host(0), b.vec_host(0))
-    ka, va = a.dict(1)
-    kb, vb = b.dict(1)
+    ka, va = parity.sorted_dict(a, 1)
+    kb, vb = parity.sorted_dict(b, 1)
     assert np.array_equal(ka[0], kb[0]) and np.array_equal(va[0], vb[0])
     assert b.kernel_count() > 2 * a.kernel_count()
     a.free()
@@ -887,7 +889,7 @@ def test_vecmerger_agrees_with_dictmerger(wb):
     p.merge(p.dictmerger(["i64"], ["i64"], "add", 100_000), m["vals"], keys=m["keys"], pred=m["pred"])
     res = _run(wb, p, cols).check()
     counts = res.vec_host(0)
-    keys, vals = res.dict(1)
+    keys, vals = parity.sorted_dict(res, 1)
     res.free()
     assert np.array_equal(np.flatnonzero(counts), keys[0])
     assert np.array_equal(counts[keys[0]], vals[0])
@@ -1051,7 +1053,7 @@ def test_lazy_groupby_and_materialised_vector(wb):
     d = lazy.groupby([flag[keep], status[keep]], [qty[keep], price[keep], dp[keep], charge[keep], ones[keep]], "add", 8)
     res = lazy.evaluate(d, charge[keep]).check()
     (wkeys, wvals), = interp.run(configs.program_c4(), [c.cpu().numpy() for c in cols])
-    keys, vals = res.dict(0)
+    keys, vals = parity.sorted_dict(res, 0)
     assert np.array_equal(keys[0], wkeys[0]) and np.array_equal(keys[1], wkeys[1])
     for k in range(4):
         assert np.all(np.abs(vals[k] - wvals[k]) <= 1e-9 * np.abs(wvals[k]))

@@ -10,6 +10,8 @@ import numpy as np
 import pytest
 import torch
 
+from tests import parity
+
 from workloads import configs
 from workloads.ir import Program
 
@@ -77,7 +79,7 @@ def _read_ordinary(prog, res):
         elif spec["kind"] in ("vecbuilder", "vecmerger"):
             got.append(res.vec_host(b))
         else:
-            got.append(res.dict(b, sort=True))
+            got.append(parity.sorted_dict(res, b))
     return got
 
 
