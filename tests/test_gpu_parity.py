@@ -664,7 +664,8 @@ def test_pipelined_calls_are_checked_one_by_one(wb):
 
 
 _RANDOM_TUNES = (None, None, {"units_per_thread": 1}, {"block_threads": 256, "grid_blocks": 3}, {"lds_dict_slots": 256},
-                 {"dict_defer": -1}, {"merge_loop": 1}, {"dict_strategy": 2}, {"dict_spill": -1})
+                 {"dict_defer": -1}, {"merge_loop": 1}, {"dict_strategy": 2}, {"dict_spill": -1}, {"tile_pipeline": 1},
+                 {"tile_pipeline": 1, "units_per_thread": 2})
 
 
 @pytest.mark.parametrize("group", range(16))
