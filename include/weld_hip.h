@@ -201,6 +201,10 @@ typedef struct {
                                    merged and stored, -1 = one tile at a time, 0 = library's choice (on when
                                    those columns, the tile's gathered values and the first probes take a
                                    lane at most about 80 registers)                                  */
+    int32_t single_launch;      /* loops whose builders are all mergers: 0 = one launch per call (the work-group
+                                   that finishes last combines the work-groups' partial results in index order
+                                   and writes the results and the status words itself), -1 = a fill kernel
+                                   before and a combining kernel behind the loop kernel                */
 } weld_tuning_t;
 
 typedef struct {
@@ -309,7 +313,8 @@ const void* weld_result_scalar(const weld_result_t* r, int32_t idx);
  * hipMalloc, hipFree, hipHostMalloc, event or module routine: the results go to buffers the CALLER
  * passes, and the workspace (control words, merger partials, scan descriptors, hash tables, spill
  * queues) is one fixed buffer of WELD_STATIC_SCRATCH_BYTES that the library holds on every GPU it
- * runs on until the process ends.
+ * runs on until the process ends (its first 4 KiB are the arrival words of kernels that finish
+ * their call themselves, see weld_tuning_t.single_launch; they are zero between calls).
  *
  *  cols, n, body, builder : as for weld_fused_for.  Fused mode only; merger, vecbuilder,
  *           dictmerger and vecmerger (a groupbuilder's workspace grows with n: WELD_ERR_UNSUPPORTED).

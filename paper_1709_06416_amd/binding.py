@@ -76,7 +76,8 @@ class Tuning(C.Structure):
     _fields_ = [("block_threads", C.c_int32), ("units_per_thread", C.c_int32), ("grid_blocks", C.c_int32),
                 ("dict_strategy", C.c_int32), ("lds_dict_slots", C.c_int32), ("spin_limit", C.c_int32),
                 ("vecmerger_strategy", C.c_int32), ("lds_filter_words", C.c_int32), ("dict_spill", C.c_int32),
-                ("merge_loop", C.c_int32), ("dict_defer", C.c_int32), ("dict_compact", C.c_int32), ("device_math", C.c_int32), ("tile_pipeline", C.c_int32)]
+                ("merge_loop", C.c_int32), ("dict_defer", C.c_int32), ("dict_compact", C.c_int32), ("device_math", C.c_int32), ("tile_pipeline", C.c_int32),
+                ("single_launch", C.c_int32)]
 
 
 class Conf(C.Structure):

@@ -594,6 +594,17 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
         if (var.defer_builder >= 0) regs += (var.compact == var.defer_builder ? 2 : 3) * rows;
         if (tune.tile_pipeline > 0 || regs <= 80) var.pipeline = 1;
     }
+    // Mergers only: the kernel can finish the call by itself.  Every work-group publishes its partials, then
+    // counts itself in; the one that arrives last combines all partials in index order and writes the
+    // results and the status words, so the call is one launch instead of three (at 1e6 rows the loop kernel
+    // takes 8 us and the two small kernels around it, with the gaps between dependent launches, twice that).
+    // No cache maintenance is involved: partials and counter are device-scope atomics, which are performed
+    // where every XCD sees them, and a wavefront counts itself in only after its own have been acknowledged.
+    if (tune.single_launch >= 0 && !var.ticketed && !L.builders.empty()) {
+        var.single = true;
+        for (int bk : var.backend)
+            if (bk != BK_MERGER) var.single = false;
+    }
     return var;
 }
 
@@ -640,6 +651,7 @@ Generated generate(const Loop& L, const Variant& var) {
     for (int c = 0; c < L.ncols; ++c)   // scalars from outside the loop: one element each
         if (L.col_scalar[c]) slot(SLOT_COL, c, 0, "s" + std::to_string(c), std::string("const ") + stype(L.col_type[c]) + "* __restrict__");
     slot(SLOT_CTL, -1, 0, "ctl", "u32*");
+    if (var.single) slot(SLOT_ARRIVE, -1, 0, "arrive", "u32*");
     for (int d = 0; d < L.ndicts; ++d) {
         const std::string P = "p" + std::to_string(d);
         slot(SLOT_PKEYS, d, 0, P + "_keys", "const u64* __restrict__");
@@ -656,6 +668,7 @@ Generated generate(const Loop& L, const Variant& var) {
         switch (var.backend[b]) {
             case BK_MERGER:
                 slot(SLOT_PARTIAL, (int)b, 0, B + "_part", "u64*");
+                if (var.single) slot(SLOT_RES, (int)b, 0, B + "_res", std::string(stype(s.val_type[0])) + "*");
                 break;
             case BK_VEC_DIRECT:
                 slot(SLOT_OUT, (int)b, 0, B + "_out", std::string(stype(s.val_type[0])) + "* __restrict__");
@@ -899,7 +912,9 @@ Generated generate(const Loop& L, const Variant& var) {
     // ------------------------------------------------------------ kernel
     o.f("extern \"C\" __global__ void __launch_bounds__(W_BLOCK) weld_kernel(const KArgs a) {\n");
     o.f("  __shared__ u64 s_red[W_WAVES];\n");
-    o.f("  int* const errp = (int*)(a.ctl + 2);\n");
+    // (single-launch form: the status words are written once, at the end; until then the error bits
+    // collect beside the arrival counter, in words that are zero between calls)
+    o.f("  int* const errp = (int*)(%s + 2);\n", var.single ? "a.arrive" : "a.ctl");
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_scalar[c]) o.f("  const %s sc%d = a.s%d[0];\n", stype(L.col_type[c]), c, c);
     o.f("  const int lane = threadIdx.x & 63;\n  const int wave = threadIdx.x >> 6;\n");
@@ -1379,7 +1394,7 @@ Generated generate(const Loop& L, const Variant& var) {
         if (var.backend[b] == BK_MERGER) {
             const char* A = acc_ctype(s.val_type[0]);
             o.f("  {\n    const %s tot = w_block_reduce<%d>(m%zu, (%s*)s_red, %s);\n", A, s.func, b, A, ident_expr(s.func, s.val_type[0]).c_str());
-            o.f("    if (threadIdx.x == 0) w_store_partial(a.b%zu_part, tot);\n  }\n", b);
+            o.f("    if (threadIdx.x == 0) %s(a.b%zu_part, tot);\n  }\n", var.single ? "w_publish_partial" : "w_store_partial", b);
         } else if (var.backend[b] == BK_VECM_REG) {
             const char* A = acc_ctype(s.val_type[0]);
             o.f("  _Pragma(\"unroll\") for (int q = 0; q < %d; ++q) {\n", (int)s.length);
@@ -1444,6 +1459,16 @@ Generated generate(const Loop& L, const Variant& var) {
                 o.f("    a.b%zu_qcnt[(u64)blockIdx.x * W_SPILL_PARTS + q] = d%zu_qn[q] < (u64)a.b%zu_qcap ? d%zu_qn[q] : (u32)a.b%zu_qcap;\n", b, b, b, b, b);
             }
         }
+    }
+    if (var.single) {
+        o.f("  if (w_arrive_last(a.arrive)) {\n");
+        for (size_t b = 0; b < NB; ++b) {
+            const weld_builder_spec_t& s = L.builders[b];
+            const char* A = acc_ctype(s.val_type[0]);
+            o.f("    {\n      const %s r = w_fold_partials<%d>(a.b%zu_part, gridDim.x, (%s*)s_red, %s);\n", A, s.func, b, A, ident_expr(s.func, s.val_type[0]).c_str());
+            o.f("      if (threadIdx.x == 0) *a.b%zu_res = (%s)r;\n    }\n", b, stype(s.val_type[0]));
+        }
+        o.f("    w_finish_status(a.ctl, a.arrive);\n  }\n");
     }
     o.f("}\n");
     // the kernel is named after its own text, so that profiles tell loops apart

@@ -342,6 +342,66 @@ template <class T> __device__ __forceinline__ void w_store_partial(u64* partial,
     partial[blockIdx.x] = bits;
 }
 
+// Single-launch form: the loop kernel combines the partials itself.  A partial is exchanged into its
+// slot at device scope (performed once the old value is back), a work-group counts itself in after
+// every one of its wavefronts has had its device-scope writes acknowledged, and the work-group that
+// finds all others counted reads the partials back at device scope: nothing here relies on one
+// XCD's L2 being written back or another's being invalidated.
+template <class T> __device__ __forceinline__ void w_publish_partial(u64* partial, T v) {
+    u64 bits;
+    __builtin_memcpy(&bits, &v, 8);
+    const u64 old = __hip_atomic_exchange(partial + blockIdx.x, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("" ::"v"(old));
+}
+// True in every thread of the work-group that finishes last.  All threads call it.  Additions to one
+// word are performed one after the other (about 15 ns apiece: 7 us for 500 work-groups), so a
+// work-group counts itself in at one of up to 32 leaves (word 16 * (1 + leaf): a cache line each), and
+// only the last one at a leaf - which puts the leaf back to zero - goes on to the root (word 0).
+__device__ __forceinline__ bool w_arrive_last(u32* arrive) {
+    __shared__ u32 s_last;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const u32 leaves = gridDim.x < 32u ? gridDim.x : 32u;
+        const u32 leaf = blockIdx.x % leaves;
+        const u32 members = (gridDim.x - leaf + leaves - 1u) / leaves;
+        u32* const cell = arrive + 16u * (1u + leaf);
+        u32 last = 0;
+        if (__hip_atomic_fetch_add(cell, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == members - 1u) {
+            __hip_atomic_store(cell, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            last = __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == leaves - 1u ? 1u : 0u;
+        }
+        s_last = last;
+    }
+    __syncthreads();
+    return s_last != 0;
+}
+// Thread j folds partials j, j + W_BLOCK, ... in that order, then the work-group's fixed reduction:
+// the result is the same on every run, whichever work-group does it.
+template <int F, class T> __device__ __forceinline__ T w_fold_partials(const u64* partial, u32 count, T* scratch, T ident) {
+    T v = ident;
+    for (u32 i = threadIdx.x; i < count; i += W_BLOCK) {
+        const u64 bits = w_ld_agent(partial + i);
+        T x;
+        __builtin_memcpy(&x, &bits, 8);
+        v = w_combine<F>(v, x);
+    }
+    return w_block_reduce<F>(v, scratch, ident);
+}
+// The call's status words (64 of them; word 2 = the error bits collected in arrive[2]), written whole,
+// and the arrival words back to zero for the next call that uses them.
+__device__ __forceinline__ void w_finish_status(u32* ctl, u32* arrive) {
+    if (threadIdx.x < 64) {
+        const u32 e = __hip_atomic_load(arrive + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ctl[threadIdx.x] = threadIdx.x == 2 ? e : 0u;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __hip_atomic_store(arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(arrive + 2, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 // ---------------------------------------------------------------- vecbuilder scan
 // Decoupled look-back over tile descriptors: bits 63..62 = state, 61..0 = count.
 //   0 = not yet published, 1 = this tile's own count, 2 = inclusive prefix.

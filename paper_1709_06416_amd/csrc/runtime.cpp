@@ -65,6 +65,41 @@ void put_back(weld_result* r) {
     r->ev0 = r->ev1 = r->ev2 = r->ev3 = nullptr;
 }
 
+// Single-launch loop kernels count their work-groups in, and collect their error bits, in a cell of
+// kArriveBytes (a root line and 32 leaf lines) that is zero whenever no such kernel runs (the kernel's last work-group clears it).  Calls on
+// one stream run one after the other and share a cell; kernels on different streams may overlap, so
+// every (device, stream) gets its own.  Cells are never given back: 4 KiB per stream ever used.
+std::mutex g_arrive_mu;
+std::map<std::pair<int, void*>, uint32_t*> g_arrive;
+char* g_arrive_chunk = nullptr;
+int g_arrive_chunk_dev = -1;
+size_t g_arrive_used = 0;
+const size_t kArriveBytes = 64 * 33;
+const size_t kArriveChunk = 65536;
+
+hipError_t arrive_cell(hipStream_t stream, uint32_t** out) {
+    int dev = 0;
+    hipError_t h = hipGetDevice(&dev);
+    if (h != hipSuccess) return h;
+    std::lock_guard<std::mutex> lk(g_arrive_mu);
+    const auto key = std::make_pair(dev, (void*)stream);
+    auto it = g_arrive.find(key);
+    if (it != g_arrive.end()) { *out = it->second; return hipSuccess; }
+    if (!g_arrive_chunk || g_arrive_chunk_dev != dev || g_arrive_used + kArriveBytes > kArriveChunk) {
+        void* p = nullptr;
+        if ((h = hipMalloc(&p, kArriveChunk)) != hipSuccess) return h;
+        if ((h = hipMemset(p, 0, kArriveChunk)) != hipSuccess) return h;
+        if ((h = hipDeviceSynchronize()) != hipSuccess) return h;
+        g_arrive_chunk = (char*)p;
+        g_arrive_chunk_dev = dev;
+        g_arrive_used = 0;
+    }
+    *out = (uint32_t*)(g_arrive_chunk + g_arrive_used);
+    g_arrive_used += kArriveBytes;
+    g_arrive[key] = *out;
+    return hipSuccess;
+}
+
 Error mk(weld_status_t st, const std::string& s) {
     Error e;
     e.status = st;
@@ -318,7 +353,11 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     for (int c = 0; c < L.ncols; ++c)
         if (L.col_used[c] && ((uintptr_t)cols[c].data & 15)) aligned = false;
     std::shared_ptr<Plan> plan;
-    Error e = get_plan(L, conf.tune, aligned, 0, 0, &plan, st == nullptr);
+    // the single-launch form writes the status words whole (it cannot add to an earlier step's), and its
+    // arrival cell belongs to one stream: the per-thread default stream is a different stream in every thread
+    weld_tuning_t tune = conf.tune;
+    if (prior_ctl || stream == hipStreamPerThread) tune.single_launch = -1;
+    Error e = get_plan(L, tune, aligned, 0, 0, &plan, st == nullptr);
     if (!e.ok()) return e;
     const Variant& var = plan->var;
     Kernel* kern = plan->kern;
@@ -525,6 +564,16 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         }
     }
 
+    uint32_t* arrive = nullptr;
+    if (var.single) {
+        if (st) {
+            arrive = st->arrive;
+        } else {
+            const hipError_t ha = arrive_cell(stream, &arrive);
+            if (ha != hipSuccess) return hip_err("arrival cell", ha);
+        }
+    }
+
     // ---- kernel arguments, in the order the generated struct declares them
     std::vector<uint64_t> args;
     for (const Slot& s : plan->slots) {
@@ -534,8 +583,11 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             case SLOT_N: v = (uint64_t)n; break;
             case SLOT_SPIN: v = conf.tune.spin_limit > 0 ? (uint64_t)conf.tune.spin_limit : (uint64_t)1 << 22; break;
             case SLOT_COL: v = (uint64_t)(uintptr_t)cols[b].data; break;
-            case SLOT_CTL: v = (uint64_t)(uintptr_t)(base + off_ctl); break;
+            // (a single-launch kernel only writes the status words, once: straight into the pinned copy)
+            case SLOT_CTL: v = (uint64_t)(uintptr_t)(var.single && !st ? (char*)r->host_ctl : base + off_ctl); break;
             case SLOT_PARTIAL: v = (uint64_t)(uintptr_t)(base + off[b].part); break;
+            case SLOT_ARRIVE: v = (uint64_t)(uintptr_t)arrive; break;
+            case SLOT_RES: v = (uint64_t)(uintptr_t)op[b].res; break;
             case SLOT_OUT: v = (uint64_t)(uintptr_t)op[b].out; break;
             case SLOT_DESC: v = (uint64_t)(uintptr_t)(base + off[b].desc); break;
             case SLOT_LEN: v = (uint64_t)(uintptr_t)(base + off_ctl + ctl_count_off(b)); break;
@@ -570,7 +622,8 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         fills.add(p, count, value);
         return he;
     };
-    if ((h = fill(base + off_ctl, kCtlBytes / 8, 0)) != hipSuccess) return hip_err("fill", h);
+    // (a single-launch kernel writes the control words itself, at its end)
+    if (!var.single && (h = fill(base + off_ctl, kCtlBytes / 8, 0)) != hipSuccess) return hip_err("fill", h);
     for (size_t b = 0; b < NB; ++b) {
         const weld_builder_spec_t& s = L.builders[b];
         if (var.backend[b] == BK_VEC_COMPACT && ntiles > 0) {
@@ -594,8 +647,10 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             if (var.spill_slices && var.backend[b] == BK_DICT_LDS && (h = fill(base + off[b].ovf_count, 1, 0)) != hipSuccess) return hip_err("fill", h);
         }
     }
-    if ((h = launch_fill_list(fills, stream)) != hipSuccess) return hip_err("fill", h);
-    r->kernel_count++;
+    if (fills.n > 0) {
+        if ((h = launch_fill_list(fills, stream)) != hipSuccess) return hip_err("fill", h);
+        r->kernel_count++;
+    }
     for (const GroupLink& g : links) {
         // pairs of a groupbuilder merged without a predicate: their number is n, known now
         // (after the control words have been cleared)
@@ -603,7 +658,10 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         if ((h = launch_fill64(base + off_ctl + ctl_count_off(g.val_vec), 1, (uint64_t)n, stream)) != hipSuccess) return hip_err("fill", h);
         r->kernel_count++;
     }
-    if (timed && (h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    // (a single-launch kernel is all the call enqueues: the events around the call are the events around it,
+    // and two more records would cost the call as much again as the work they bracket)
+    r->lone_kernel = timed && var.single;
+    if (timed && !var.single && (h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream);
     if (!e.ok()) return e;
     r->kernel_count++;
@@ -644,7 +702,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         if (h != hipSuccess) return hip_err("dict spill merge", h);
         r->kernel_count++;
     }
-    if (timed && (h = hipEventRecord(r->ev3, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    if (timed && !var.single && (h = hipEventRecord(r->ev3, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     MergerFinish mf;
     memset(&mf, 0, sizeof mf);
     for (size_t b = 0; b < NB; ++b) {
@@ -658,7 +716,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         mf.elem_size[k] = type_size(s.val_type[0]);
         mf.bits[k] = 8 * type_size(s.val_type[0]);
     }
-    if (mf.n > 0) {
+    if (mf.n > 0 && !var.single) {
         if ((h = launch_merger_finish(mf, (int)grid, stream)) != hipSuccess) return hip_err("merger finish", h);
         r->kernel_count++;
     }
@@ -758,7 +816,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         if ((h = launch_static_status(base + off_ctl, sl, st->status_dev, stream)) != hipSuccess) return hip_err("status", h);
         return Error();
     }
-    if ((h = hipMemcpyAsync(r->host_ctl, base + off_ctl, kCtlBytes, hipMemcpyDeviceToHost, stream)) != hipSuccess)
+    if (!var.single && (h = hipMemcpyAsync(r->host_ctl, base + off_ctl, kCtlBytes, hipMemcpyDeviceToHost, stream)) != hipSuccess)
         return hip_err("hipMemcpyAsync", h);
     // the call's last operation: the evaluation point waits for this event, not for the stream,
     // so work enqueued after this call keeps the GPU busy while the host looks at the result
@@ -1039,7 +1097,8 @@ weld_status_t weld_result_status(weld_result_t* r) {
         return r->status;
     }
     (void)hipEventElapsedTime(&r->ms, r->ev0, r->ev1);
-    if (hipEventQuery(r->ev3) == hipSuccess) (void)hipEventElapsedTime(&r->kernel_ms, r->ev2, r->ev3);
+    if (r->lone_kernel) r->kernel_ms = r->ms;
+    else if (hipEventQuery(r->ev3) == hipSuccess) (void)hipEventElapsedTime(&r->kernel_ms, r->ev2, r->ev3);
     (void)hipGetLastError();
     for (weld_result* c : r->earlier) {   // a staged evaluation fails if one of its stages did; its time is theirs and its own
         const weld_status_t cs = weld_result_status(c);

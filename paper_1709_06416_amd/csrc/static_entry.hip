@@ -131,8 +131,11 @@ extern "C" weld_status_t weld_fused_for_static(const weld_cols_t* cols, int64_t 
     e = static_scratch(&ptr);
     if (!e.ok()) { set_last_error(e.text); return e.status; }
     StaticTarget st;
-    st.scratch = (char*)ptr;
-    st.scratch_bytes = (size_t)WELD_STATIC_SCRATCH_BYTES;
+    // the array's first 4 KiB are never part of a call's workspace: they are zero from the start, and
+    // the kernels that count their work-groups in there leave them zero
+    st.arrive = (uint32_t*)ptr;
+    st.scratch = (char*)ptr + 4096;
+    st.scratch_bytes = (size_t)WELD_STATIC_SCRATCH_BYTES - 4096;
     st.outs = outs;
     st.status_dev = status_dev;
     e = run_fused_static(L, refs, n, builder->conf, st);

@@ -45,6 +45,7 @@ struct weld_result {
     uint32_t* host_ctl = nullptr;  // pinned copy of the control words
     bool synced = false;
     bool recorded = false;         // ev1 stands after the call's last operation on the stream
+    bool lone_kernel = false;      // the call enqueued one kernel and nothing else: ev2 / ev3 not recorded, kernel_ms = ms
     int64_t grid = 0;              // work-groups of the main loop kernel
     weld_status_t status = WELD_OK;
     std::string error;
@@ -181,6 +182,8 @@ struct Variant {
     long long compact_guard = 0;// > 0: |constant merged|; a work-group flushes its table before a cell could pass 2^31
     bool own_math = true;       // exp and log evaluated by the library's own code (else the device math library's)
     int pipeline = 0;          // ticketed loops: 1 = the next tile's columns are loaded while this tile is merged and stored
+    bool single = false;        // mergers only: the last work-group to finish combines the partials and writes results and
+                                // status (no fill kernel before the loop kernel, no combining kernel behind it)
     std::vector<int> backend;   // per builder
 };
 
@@ -188,6 +191,7 @@ struct Variant {
 enum SlotKind {
     SLOT_N = 0, SLOT_SPIN, SLOT_COL, SLOT_CTL,
     SLOT_PARTIAL,                       // merger
+    SLOT_ARRIVE, SLOT_RES,              // single-launch form: arrival counter and error bits; a merger's result
     SLOT_OUT, SLOT_DESC, SLOT_LEN,      // vecbuilder
     SLOT_DKEYS, SLOT_DHDR, SLOT_DSLOTS, SLOT_DVAL,  // dictmerger
     SLOT_DLOG, SLOT_DQCNT, SLOT_DQCAP,              // dictmerger spill queues
@@ -272,6 +276,7 @@ struct NestedData {
 // the library's fixed device buffer (weld_fused_for_static): no pool block, no events, no pinned copy.
 struct StaticTarget {
     char* scratch = nullptr;            // device; the call's control words and workspace
+    uint32_t* arrive = nullptr;         // device; 33 * 64 bytes that are zero between calls (single-launch kernels count in here)
     size_t scratch_bytes = 0;
     const weld_out_t* outs = nullptr;   // one per builder, checked by the caller of run_fused_static
     int64_t* status_dev = nullptr;      // device; 1 + WELD_MAX_BUILDERS words

@@ -96,6 +96,18 @@ def test_malformed_bodies_are_rejected(wb):
     assert wb.validate(p)[0] == wb.ERR_UNSUPPORTED
 
 
+def test_merger_only_loops_finish_in_the_loop_kernel(wb):
+    """The single-launch form: partials exchanged at device scope, one arrival per work-group, the last
+    one folds; loops with any other builder, and the form switched off, keep the separate kernels."""
+    src = wb.generated_source(configs.program_c1())
+    assert "w_arrive_last(a.arrive)" in src and "w_publish_partial(a.b0_part" in src and "*a.b0_res = (double)r" in src
+    assert "(int*)(a.arrive + 2)" in src
+    off = wb.generated_source(configs.program_c1(), tune={"single_launch": -1})
+    assert "w_arrive_last(a.arrive)" not in off and "w_store_partial(a.b0_part" in off and "(int*)(a.ctl + 2)" in off
+    assert "w_arrive_last(a.arrive)" not in wb.generated_source(configs.program_c2())
+    assert "w_arrive_last(a.arrive)" not in wb.generated_source(configs.program_c4())
+
+
 def test_planner_overlaps_tiles_only_where_the_registers_allow(wb):
     """Host logic only: which compacting loops load the next tile's columns ahead, read off the generated text."""
     c5 = wb.generated_source(configs.program_c5())
