@@ -48,7 +48,8 @@ struct FillList {
         return true;
     }
 };
-hipError_t launch_fill_list(const FillList& f, hipStream_t stream);
+// start / stop (may be null): events that take the dispatch's own start / end time (no packet of their own in the queue)
+hipError_t launch_fill_list(const FillList& f, hipStream_t stream, hipEvent_t start = nullptr);
 // slot_pos (may be null): receives, for every occupied slot (and the extra slot `slots`), the
 // position its entry was written to.
 hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots, const DictValues& vals,
@@ -123,13 +124,13 @@ struct SpillMerge {
     long long capacity;            // the dictmerger's declared capacity (sizes the aggregation's LDS tables)
     int table_slots, split;        // set by launch_dict_spill_merge
 };
-hipError_t launch_dict_spill_merge(const SpillMerge& a, int nvals, hipStream_t stream);
+hipError_t launch_dict_spill_merge(const SpillMerge& a, int nvals, hipStream_t stream, hipEvent_t stop = nullptr);
 // Dictionaries of millions of keys: partition p of the queues holds the keys whose home slot lies in
 // the p-th of `parts` equal slices of the global table (slice = as many slots as an LDS table of this
 // entry size has).  One work-group per slice loads the slice, merges the partition into it in LDS
 // and stores it back; the few entries that probe past the end of their slice are inserted into
 // the global table by a second small kernel afterwards.  a.slots == a.parts * slice slots.
-hipError_t launch_dict_slice_build(const SpillMerge& a, int nvals, hipStream_t stream);
+hipError_t launch_dict_slice_build(const SpillMerge& a, int nvals, hipStream_t stream, hipEvent_t stop = nullptr);
 
 // Nested loops.  is64: the start / end vectors hold 64-bit (else 32-bit) integers.
 // segments_check raises bit 8 of *err unless start[0] == 0, start[i] <= end[i],
@@ -147,6 +148,8 @@ hipError_t launch_ranges_offsets(const void* start, const void* end, const void*
 hipError_t launch_tile_rows(const void* start, int is64, int64_t n_outer, int64_t tile, int64_t ntiles,
                             void* tile_row, hipStream_t stream);
 hipError_t launch_or_error(void* dst_ctl, const void* src_ctl, hipStream_t stream);
+// 64 control words to pinned host memory; `done` (may be null) takes the dispatch's end time and is what the host waits for
+hipError_t launch_ctl_to_host(const void* ctl, void* host, hipStream_t stream, hipEvent_t done);
 
 // weld_fused_for_static (static_entry.hip): copies the error bits and the builders' lengths from a
 // call's control block to the caller's device array (status[0] = error bits, status[1 + b] = length

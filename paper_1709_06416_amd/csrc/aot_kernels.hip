@@ -1,6 +1,7 @@
 // Ahead-of-time compiled helper kernels (gfx950): workspace fills, dictionary
 // result extraction, and the two memory probes used for roofline measurements.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include "aot_kernels.h"
 
@@ -37,13 +38,14 @@ __global__ void __launch_bounds__(256) fill_list_kernel(const FillList f) {
     }
 }
 
-hipError_t launch_fill_list(const FillList& f, hipStream_t stream) {
+hipError_t launch_fill_list(const FillList& f, hipStream_t stream, hipEvent_t start) {
     if (f.n == 0) return hipSuccess;
     long long most = 0;
     for (int k = 0; k < f.n; ++k) most = f.count[k] > most ? f.count[k] : most;
     int64_t blocks = (most + 255) / 256;
     if (blocks > 4096) blocks = 4096;
-    fill_list_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(f);
+    if (start) hipExtLaunchKernelGGL(fill_list_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, start, nullptr, 0, f);
+    else fill_list_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(f);
     return hipGetLastError();
 }
 
@@ -919,6 +921,16 @@ __global__ void or_error_kernel(u32* dst_ctl, const u32* src_ctl) {
 
 hipError_t launch_or_error(void* dst_ctl, const void* src_ctl, hipStream_t stream) {
     or_error_kernel<<<dim3(1), dim3(64), 0, stream>>>((u32*)dst_ctl, (const u32*)src_ctl);
+    return hipGetLastError();
+}
+
+// The call's 64 control words to the result handle's pinned host copy, written by a kernel: a
+// device-to-host copy command of 256 bytes takes the copy engine's detour (about 10 us on the
+// stream); `done`, the event the host waits for, is this dispatch's own end.
+__global__ void ctl_to_host_kernel(const u32* ctl, u32* host) { host[threadIdx.x] = ctl[threadIdx.x]; }
+
+hipError_t launch_ctl_to_host(const void* ctl, void* host, hipStream_t stream, hipEvent_t done) {
+    hipExtLaunchKernelGGL(ctl_to_host_kernel, dim3(1), dim3(64), 0, stream, nullptr, done, 0, (const u32*)ctl, (u32*)host);
     return hipGetLastError();
 }
 

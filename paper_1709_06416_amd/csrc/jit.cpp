@@ -7,6 +7,7 @@
 // Compilation needs no GPU, so kernels can be built ahead of time on a build host.
 #include <dlfcn.h>
 #include <hip/hip_runtime_api.h>
+#include <hip/hip_ext.h>
 #include <hip/hiprtc.h>
 #include <sys/stat.h>
 #include <unistd.h>
@@ -166,10 +167,19 @@ int jit_blocks_per_cu(Kernel* k, int block) {
     return nb;
 }
 
-Error jit_launch(Kernel* k, unsigned grid, unsigned block, void* args, size_t args_bytes, void* stream) {
+Error jit_launch(Kernel* k, unsigned grid, unsigned block, void* args, size_t args_bytes, void* stream, void* start_event,
+                 void* stop_event) {
     void* extra[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, args, HIP_LAUNCH_PARAM_BUFFER_SIZE, &args_bytes,
                      HIP_LAUNCH_PARAM_END};
-    hipError_t h = hipModuleLaunchKernel(k->fn, grid, 1, 1, block, 1, 1, 0, (hipStream_t)stream, nullptr, extra);
+    hipError_t h;
+    if (start_event || stop_event) {
+        // the events take the dispatch's own start and end times: no packets of their own in the queue
+        // (an event record is a barrier packet, about 4.5 us during which the queue starts nothing)
+        h = hipExtModuleLaunchKernel(k->fn, grid * block, 1, 1, block, 1, 1, 0, (hipStream_t)stream, nullptr, extra,
+                                     (hipEvent_t)start_event, (hipEvent_t)stop_event, 0);
+    } else {
+        h = hipModuleLaunchKernel(k->fn, grid, 1, 1, block, 1, 1, 0, (hipStream_t)stream, nullptr, extra);
+    }
     if (h != hipSuccess) return err(WELD_ERR_DEVICE, std::string("hipModuleLaunchKernel: ") + hipGetErrorString(h));
     return Error();
 }

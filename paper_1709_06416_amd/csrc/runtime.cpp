@@ -610,13 +610,29 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     // ---- enqueue
     hipError_t h;
     const bool timed = !prior_ctl && !st;
-    if (timed && (h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    // Timing events ride on the dispatches they bracket wherever they can (they take the dispatch's own start
+    // or end time): an event recorded by itself is a barrier packet, about 4.5 us during which the queue
+    // starts nothing, and four of them cost a short call more than its kernels.  The call's start is the
+    // start of its first fill kernel, the loop kernel's events are its own (the end is the end of the last
+    // queue aggregation where there is one), and only the event the host waits for, behind the copy of the
+    // control words, is recorded as before.  A single-launch kernel is all its call enqueues: it carries
+    // the call's two events and there are no others.
+    const bool lone = timed && var.single;
+    bool copies_first = false;              // a vecmerger's initial vector is copied before the first fill kernel runs
+    size_t spill_left = 0;
+    for (size_t b = 0; b < NB; ++b) {
+        if (L.builders[b].kind == WELD_VECMERGER && L.builders[b].init) copies_first = true;
+        if (var.backend[b] == BK_DICT_LDS && var.spill) ++spill_left;
+    }
+    hipEvent_t start_pending = timed && !lone && !copies_first ? r->ev0 : nullptr;
+    if (timed && !lone && copies_first && (h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     // the workspace of the call is cleared by ONE kernel (a dictionary alone has a key column
     // and up to eight value columns; a launch each left the GPU idle for microseconds apiece)
     FillList fills;
     auto fill = [&](void* p, int64_t count, uint64_t value) -> hipError_t {
         if (fills.add(p, count, value)) return hipSuccess;
-        const hipError_t he = launch_fill_list(fills, stream);
+        const hipError_t he = launch_fill_list(fills, stream, start_pending);
+        start_pending = nullptr;
         r->kernel_count++;
         fills = FillList();
         fills.add(p, count, value);
@@ -648,7 +664,8 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         }
     }
     if (fills.n > 0) {
-        if ((h = launch_fill_list(fills, stream)) != hipSuccess) return hip_err("fill", h);
+        if ((h = launch_fill_list(fills, stream, start_pending)) != hipSuccess) return hip_err("fill", h);
+        start_pending = nullptr;
         r->kernel_count++;
     }
     for (const GroupLink& g : links) {
@@ -658,11 +675,9 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         if ((h = launch_fill64(base + off_ctl + ctl_count_off(g.val_vec), 1, (uint64_t)n, stream)) != hipSuccess) return hip_err("fill", h);
         r->kernel_count++;
     }
-    // (a single-launch kernel is all the call enqueues: the events around the call are the events around it,
-    // and two more records would cost the call as much again as the work they bracket)
-    r->lone_kernel = timed && var.single;
-    if (timed && !var.single && (h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
-    e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream);
+    r->lone_kernel = lone;
+    e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream,
+                   lone ? r->ev0 : timed ? r->ev2 : nullptr, lone ? r->ev1 : timed && spill_left == 0 ? r->ev3 : nullptr);
     if (!e.ok()) return e;
     r->kernel_count++;
     if (!prior_ctl) r->grid = grid;
@@ -694,15 +709,15 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             sm.overflow = (unsigned long long*)(base + off[b].ovf);
             sm.overflow_count = (unsigned int*)(base + off[b].ovf_count);
             sm.overflow_cap = kOverflowEntries;
-            h = launch_dict_slice_build(sm, s.nvals, stream);
+            h = launch_dict_slice_build(sm, s.nvals, stream, timed && spill_left == 1 ? r->ev3 : nullptr);
             r->kernel_count++;
         } else {
-            h = launch_dict_spill_merge(sm, s.nvals, stream);
+            h = launch_dict_spill_merge(sm, s.nvals, stream, timed && spill_left == 1 ? r->ev3 : nullptr);
         }
+        --spill_left;
         if (h != hipSuccess) return hip_err("dict spill merge", h);
         r->kernel_count++;
     }
-    if (timed && !var.single && (h = hipEventRecord(r->ev3, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     MergerFinish mf;
     memset(&mf, 0, sizeof mf);
     for (size_t b = 0; b < NB; ++b) {
@@ -816,11 +831,15 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         if ((h = launch_static_status(base + off_ctl, sl, st->status_dev, stream)) != hipSuccess) return hip_err("status", h);
         return Error();
     }
-    if (!var.single && (h = hipMemcpyAsync(r->host_ctl, base + off_ctl, kCtlBytes, hipMemcpyDeviceToHost, stream)) != hipSuccess)
-        return hip_err("hipMemcpyAsync", h);
-    // the call's last operation: the evaluation point waits for this event, not for the stream,
-    // so work enqueued after this call keeps the GPU busy while the host looks at the result
-    if ((h = hipEventRecord(r->ev1, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+    // The call's last operation: a small kernel that writes the control words to the handle's pinned copy and
+    // carries the event the evaluation point waits for (for the event, not for the stream, so work enqueued
+    // after this call keeps the GPU busy while the host looks at the result).  A single-launch kernel has
+    // written the words itself: if it is all the call enqueued it carries the event too.
+    if (!var.single) {
+        if ((h = launch_ctl_to_host(base + off_ctl, r->host_ctl, stream, r->ev1)) != hipSuccess) return hip_err("control words", h);
+    } else if (!lone && (h = hipEventRecord(r->ev1, stream)) != hipSuccess) {
+        return hip_err("hipEventRecord", h);
+    }
     r->recorded = true;
     return Error();
 }
@@ -938,13 +957,15 @@ Error run_nested(const NestedLoop& NL, const NestedData& D, const weld_conf_t& c
     if ((h = launch_tile_rows(boundaries, mapped ? 1 : is64, D.n_outer, tile, ntiles, base + off_tiles, stream)) != hipSuccess)
         return hip_err("tile rows", h);
     r->kernel_count++;
-    if ((h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     if (ntiles > 0 && D.n_outer > 0) {
-        e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream);
+        // (the kernel's events are the dispatch's own start and end: no packets of their own in the queue)
+        e = jit_launch(kern, (unsigned)grid, (unsigned)var.block, args.data(), args.size() * 8, stream, r->ev2, r->ev3);
         if (!e.ok()) return e;
         r->kernel_count++;
+    } else {
+        if ((h = hipEventRecord(r->ev2, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
+        if ((h = hipEventRecord(r->ev3, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     }
-    if ((h = hipEventRecord(r->ev3, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
 
     // the outer loop: the cells are its last column
     ColRef cols[WELD_MAX_COLS];

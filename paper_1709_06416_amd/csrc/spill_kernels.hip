@@ -10,6 +10,7 @@
 // The hash functions and the global-table insert are the ones of the loop kernels: both
 // write the same table.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #define W_BLOCK 1024
 #define W_V 2
@@ -381,40 +382,41 @@ __global__ void __launch_bounds__(256) dict_overflow_insert_kernel(const SpillMe
 }
 
 template <int NV, int FUNC>
-static hipError_t launch_slices(const SpillMerge& a, hipStream_t stream) {
+static hipError_t launch_slices(const SpillMerge& a, hipStream_t stream, hipEvent_t stop) {
     if (a.slots != (long long)a.parts * SpillTable<NV>::kSlots || a.groups > 1024) return hipErrorInvalidValue;
     dict_slice_build_kernel<NV, FUNC><<<dim3((unsigned)a.parts), dim3(1024), 0, stream>>>(a);
     hipError_t h = hipGetLastError();
     if (h != hipSuccess) return h;
-    dict_overflow_insert_kernel<NV, FUNC><<<dim3(64), dim3(256), 0, stream>>>(a);
+    if (stop) hipExtLaunchKernelGGL((dict_overflow_insert_kernel<NV, FUNC>), dim3(64), dim3(256), 0, stream, nullptr, stop, 0, a);
+    else dict_overflow_insert_kernel<NV, FUNC><<<dim3(64), dim3(256), 0, stream>>>(a);
     return hipGetLastError();
 }
 template <int NV>
-static hipError_t launch_slices_nv(const SpillMerge& a, hipStream_t stream) {
+static hipError_t launch_slices_nv(const SpillMerge& a, hipStream_t stream, hipEvent_t stop) {
     switch (a.func) {
-        case W_FUNC_ADD: return launch_slices<NV, W_FUNC_ADD>(a, stream);
-        case W_FUNC_MUL: return launch_slices<NV, W_FUNC_MUL>(a, stream);
-        case W_FUNC_MIN: return launch_slices<NV, W_FUNC_MIN>(a, stream);
-        case W_FUNC_MAX: return launch_slices<NV, W_FUNC_MAX>(a, stream);
+        case W_FUNC_ADD: return launch_slices<NV, W_FUNC_ADD>(a, stream, stop);
+        case W_FUNC_MUL: return launch_slices<NV, W_FUNC_MUL>(a, stream, stop);
+        case W_FUNC_MIN: return launch_slices<NV, W_FUNC_MIN>(a, stream, stop);
+        case W_FUNC_MAX: return launch_slices<NV, W_FUNC_MAX>(a, stream, stop);
         default: return hipErrorInvalidValue;
     }
 }
-hipError_t launch_dict_slice_build(const SpillMerge& a, int nvals, hipStream_t stream) {
+hipError_t launch_dict_slice_build(const SpillMerge& a, int nvals, hipStream_t stream, hipEvent_t stop) {
     switch (nvals) {
-        case 1: return launch_slices_nv<1>(a, stream);
-        case 2: return launch_slices_nv<2>(a, stream);
-        case 3: return launch_slices_nv<3>(a, stream);
-        case 4: return launch_slices_nv<4>(a, stream);
-        case 5: return launch_slices_nv<5>(a, stream);
-        case 6: return launch_slices_nv<6>(a, stream);
-        case 7: return launch_slices_nv<7>(a, stream);
-        case 8: return launch_slices_nv<8>(a, stream);
+        case 1: return launch_slices_nv<1>(a, stream, stop);
+        case 2: return launch_slices_nv<2>(a, stream, stop);
+        case 3: return launch_slices_nv<3>(a, stream, stop);
+        case 4: return launch_slices_nv<4>(a, stream, stop);
+        case 5: return launch_slices_nv<5>(a, stream, stop);
+        case 6: return launch_slices_nv<6>(a, stream, stop);
+        case 7: return launch_slices_nv<7>(a, stream, stop);
+        case 8: return launch_slices_nv<8>(a, stream, stop);
         default: return hipErrorInvalidValue;
     }
 }
 
 template <int NV>
-static hipError_t launch_nv(const SpillMerge& in, hipStream_t stream) {
+static hipError_t launch_nv(const SpillMerge& in, hipStream_t stream, hipEvent_t stop) {
     SpillMerge a = in;
     // table: four slots per key the partition is expected to hold (capacity / 256), at least 1024, at
     // most what 128 KiB take; two work-groups per partition where two such tables fit a compute unit
@@ -432,7 +434,8 @@ static hipError_t launch_nv(const SpillMerge& in, hipStream_t stream) {
             const hipError_t he = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (he != hipSuccess) return he;
         }
-        kern<<<grid, block, lds, stream>>>(a);
+        if (stop) hipExtLaunchKernelGGL(kern, grid, block, lds, stream, nullptr, stop, 0, a);
+        else kern<<<grid, block, lds, stream>>>(a);
         return hipGetLastError();
     };
     if (a.compact) {
@@ -448,16 +451,16 @@ static hipError_t launch_nv(const SpillMerge& in, hipStream_t stream) {
     }
 }
 
-hipError_t launch_dict_spill_merge(const SpillMerge& a, int nvals, hipStream_t stream) {
+hipError_t launch_dict_spill_merge(const SpillMerge& a, int nvals, hipStream_t stream, hipEvent_t stop) {
     switch (nvals) {
-        case 1: return launch_nv<1>(a, stream);
-        case 2: return launch_nv<2>(a, stream);
-        case 3: return launch_nv<3>(a, stream);
-        case 4: return launch_nv<4>(a, stream);
-        case 5: return launch_nv<5>(a, stream);
-        case 6: return launch_nv<6>(a, stream);
-        case 7: return launch_nv<7>(a, stream);
-        case 8: return launch_nv<8>(a, stream);
+        case 1: return launch_nv<1>(a, stream, stop);
+        case 2: return launch_nv<2>(a, stream, stop);
+        case 3: return launch_nv<3>(a, stream, stop);
+        case 4: return launch_nv<4>(a, stream, stop);
+        case 5: return launch_nv<5>(a, stream, stop);
+        case 6: return launch_nv<6>(a, stream, stop);
+        case 7: return launch_nv<7>(a, stream, stop);
+        case 8: return launch_nv<8>(a, stream, stop);
         default: return hipErrorInvalidValue;
     }
 }

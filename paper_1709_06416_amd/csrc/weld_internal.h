@@ -234,7 +234,9 @@ int key_bits(const weld_builder_spec_t& b);
 struct Kernel;  // compiled + loaded
 Error jit_get(const std::string& source, const std::string& kernel_name, bool load_on_device, Kernel** out);
 int jit_blocks_per_cu(Kernel* k, int block);  // resident work-groups per CU, 0 if unknown
-Error jit_launch(Kernel* k, unsigned grid, unsigned block, void* args, size_t args_bytes, void* stream);
+// start_event / stop_event (hipEvent_t or null): take the dispatch's own start and end times
+Error jit_launch(Kernel* k, unsigned grid, unsigned block, void* args, size_t args_bytes, void* stream, void* start_event = nullptr,
+                 void* stop_event = nullptr);
 Error set_cache_dir(const char* path);
 
 // pool.cpp
