@@ -375,10 +375,23 @@ __device__ __forceinline__ u64 load_bits(const void* p, i64 i, int size) {
         default: return __builtin_nontemporal_load((const u64*)p + i);
     }
 }
-// same multiplicative hash as the loop kernels' tables (both probe the same table)
-__device__ __forceinline__ u32 table_hash_slot(u64 k, u32 slots) {
+// the hash of the work-groups' own LDS caches (one multiplication), and the hash of the dictionaries'
+// global tables, the same as the loop kernels' (both probe the same tables: a second multiplication
+// for tables of 2^21 slots and more)
+__device__ __forceinline__ u32 cache_hash_slot(u64 k, u32 slots) {
     const u32 x = (u32)k ^ ((u32)(k >> 32) * 0x85ebca6bu);
     return (x * 0x9e3779b1u) >> (__builtin_clz(slots) + 1);
+}
+__device__ __forceinline__ u32 table_hash_slot(u64 k, u32 slots) {
+    const u32 x = (u32)k ^ ((u32)(k >> 32) * 0x85ebca6bu);
+    u32 h = x * 0x9e3779b1u;
+    if (slots >= (1u << 21)) {
+        asm volatile("");
+        h ^= h >> 15;
+        h *= 0x2c1b3c6du;
+        h ^= h >> 13;
+    }
+    return h >> (__builtin_clz(slots) + 1);
 }
 
 #define GROUP_TILE 4096
@@ -543,7 +556,7 @@ __device__ __forceinline__ void groups_of_keys(const GroupScatter& a, u64* s_ck,
     bool miss[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        ce[j] = table_hash_slot(kb[j], PART_CACHE);
+        ce[j] = cache_hash_slot(kb[j], PART_CACHE);
         ck[j] = __hip_atomic_load(&s_ck[ce[j]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         gid[j] = -1;
         miss[j] = live[j];

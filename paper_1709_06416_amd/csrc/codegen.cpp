@@ -628,7 +628,13 @@ Generated generate(const Loop& L, const Variant& var) {
     const std::vector<IRange> ranges = static_ranges(L);
     o.f("// generated: fused for-loop kernel, %d columns, %zu builders\n", L.ncols, NB);
     o.f("#define W_BLOCK %d\n#define W_V %d\n#define W_U %d\n#define W_ALIGNED %d\n", var.block, var.v, var.u, var.aligned);
-    if (var.spill_slices) o.f("#define W_SPILL_PARTS %d\n#define W_SPILL_BY_SLOT 1\n", var.spill_parts);
+    if (var.spill_slices) {
+        int nv = 1;
+        for (size_t b = 0; b < NB; ++b)
+            if (var.backend[b] == BK_DICT_LDS) nv = L.builders[b].nvals;
+        const int slice_bits = nv <= 1 ? 13 : nv <= 3 ? 12 : nv <= 7 ? 11 : 10;       // slots of a slice: what the LDS holds of this entry size
+        o.f("#define W_SPILL_PARTS %d\n#define W_SPILL_SLICE_BITS %d\n#define W_SPILL_BY_SLOT 1\n", var.spill_parts, slice_bits);
+    }
     const bool uses_erf = body_uses(L, WELD_OP_ERF);
     if (uses_erf) o.f("#define W_USE_ERF 1\n");
     const bool uses_log = var.own_math && body_uses(L, WELD_OP_LOG), uses_exp = var.own_math && body_uses(L, WELD_OP_EXP);

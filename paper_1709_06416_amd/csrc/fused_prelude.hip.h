@@ -584,6 +584,26 @@ __device__ __forceinline__ u32 w_hash2(u64 k) {
     h *= 0x2c1b3c6du;
     return h ^ (h >> 13);
 }
+// Home slot in a GLOBAL table (every dictionary's final table, and the tables other loops probe).
+// Tables of 2^21 slots and more lie beyond every cache, and each step of a probe is a trip to
+// memory: they take the second hash.  Under one multiplication, keys with a stride keep enough
+// structure to stack on few slots - order numbers times four, 4e6 of them in 2^23 slots: 3.3 keys
+// per occupied home slot, and 70 % of all inserts and lookups find another key there first; a random
+// function gives 1.26 and 21 %, and so does the second hash for strides 1 to 1024.  Smaller tables
+// (their probes stay in the L2) and the LDS tables keep the single multiplication: multiplications
+// run at a quarter of the rate, and the kernels that look keys up in such tables are bound by the
+// instructions they issue (groupbuilder's partition step: 1.03 -> 1.26 ms with the second hash).
+// Which hash a table uses follows from its size alone, so everything that probes it agrees.
+__device__ __forceinline__ u32 w_table_hash_slot(u64 k, u32 slots) {   // slots is a power of two >= 2
+    u32 h = w_hash(k);
+    if (slots >= (1u << 21)) {
+        asm volatile("");                  // (keeps the branch: slots is uniform, and both sides computed cost the multiplication)
+        h ^= h >> 15;
+        h *= 0x2c1b3c6du;
+        h ^= h >> 13;
+    }
+    return h >> (__builtin_clz(slots) + 1);
+}
 
 // Global open-addressing table (linear probing, power-of-two slot count, keys packed
 // into 64 bits, W_EMPTY_KEY marks a free slot).  The one key whose packed bits equal
@@ -595,7 +615,7 @@ __device__ __forceinline__ i64 w_table_slot(u64* keys, u32* hdr, i64 slots, u64 
         return slots;
     }
     const i64 mask = slots - 1;
-    i64 s = (i64)w_hash_slot(kbits, (u32)slots);
+    i64 s = (i64)w_table_hash_slot(kbits, (u32)slots);
     for (i64 probe = 0; probe < slots; ++probe) {
         // a key cell changes once, from the marker to its key: a cached copy that already
         // shows the key is final, and a stale marker is resolved by the compare-and-swap
@@ -624,7 +644,7 @@ __device__ __forceinline__ i64 w_table_slot(u64* keys, u32* hdr, i64 slots, u64 
 __device__ __forceinline__ i64 w_table_find(const u64* __restrict__ keys, const u32* __restrict__ hdr, i64 slots, u64 kbits,
                                             bool live) {
     const i64 mask = slots - 1;
-    const i64 home = live ? (i64)w_hash_slot(kbits, (u32)slots) : 0;
+    const i64 home = live ? (i64)w_table_hash_slot(kbits, (u32)slots) : 0;
     const u64 first = keys[home];
     if (!live) return -1;
     if (kbits == W_EMPTY_KEY) return hdr[1] ? slots : -1;
@@ -751,7 +771,8 @@ __device__ __forceinline__ void w_lds_add32(u32* vals, int slot, i64 v) {
 #endif
 __device__ __forceinline__ u32 w_spill_part(u64 kbits) {
 #ifdef W_SPILL_BY_SLOT
-    return w_hash_slot(kbits, W_SPILL_PARTS);
+    // the slice of the table the key's home slot lies in (slices of 2^W_SPILL_SLICE_BITS slots)
+    return w_table_hash_slot(kbits, (u32)W_SPILL_PARTS << W_SPILL_SLICE_BITS) >> W_SPILL_SLICE_BITS;
 #else
     return w_hash2(kbits) >> 24;
 #endif

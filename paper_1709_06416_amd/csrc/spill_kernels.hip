@@ -266,6 +266,8 @@ __global__ void __launch_bounds__(1024) dict_slice_build_kernel(const SpillMerge
     __shared__ u64 s_vals[NV][S];
     __shared__ u32 s_off[1025];
     __shared__ u32 s_wave[16];
+    __shared__ unsigned short s_seg[4096];
+    __shared__ u64 s_spare[128];           // where the merges of entries that are not there go: a key cell and a value cell per lane
     const int part = blockIdx.x;
     const int tid = threadIdx.x;
     const i64 base = (i64)part * S;
@@ -277,7 +279,6 @@ __global__ void __launch_bounds__(1024) dict_slice_build_kernel(const SpillMerge
 #pragma unroll
         for (int k = 0; k < NV; ++k) s_vals[k][q] = fresh ? a.ident[k] : a.vals[k][base + q];
     }
-    // exclusive prefix of the segment lengths of this partition over the groups (<= 1024)
     u32 mine = 0;
     if (tid < a.groups) {
         mine = a.qcnt[(size_t)tid * a.parts + part];
@@ -297,64 +298,85 @@ __global__ void __launch_bounds__(1024) dict_slice_build_kernel(const SpillMerge
     if (tid == 0) s_off[0] = 0;
     __syncthreads();
     const u32 total = s_off[a.groups];
-    const float guess = total ? (float)a.groups / (float)total : 0.f;
-    // four entries per thread at a time, all loaded before the first is merged
-    for (u32 i0 = (u32)tid; i0 < total; i0 += 4096u) {
+    const u32 seg_lo = before + incl - mine, seg_hi = before + incl;        // this thread's segment among the partition's entries
+    // 4096 entries a round, four per thread, all loaded before the first is merged.  Which segment an
+    // entry lies in is written down by the segments' own threads first (a search through the offsets
+    // by every entry - a guess and a walk of some thirty dependent LDS reads, the segments' lengths
+    // being as uneven as they are - took a quarter of the kernel's time and slowed the merges of the
+    // wavefronts that were already past it).
+    for (u32 r0 = 0; r0 < total; r0 += 4096u) {
+        if (r0) __syncthreads();               // the round before has read its segment numbers
+        {
+            const u32 lo = seg_lo > r0 ? seg_lo : r0, hi = seg_hi < r0 + 4096u ? seg_hi : r0 + 4096u;
+            for (u32 i = lo; i < hi; ++i) s_seg[i - r0] = (unsigned short)tid;
+        }
+        __syncthreads();
+        const u32 i0 = r0 + (u32)tid;
         u64 key[4], w[4][NV];
         bool live[4];
+        // Every step below is written without a branch around it (an entry past the end re-reads the last
+        // one and merges into a spare cell): a load or an LDS operation inside a branch is waited for at the
+        // end of that branch, one entry after the other - four dependent round trips where one will do.
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const u32 i = i0 + (u32)q * 1024u;
+            u32 i = i0 + (u32)q * 1024u;
             live[q] = i < total;
-            key[q] = W_EMPTY_KEY;
-#pragma unroll
-            for (int f = 0; f < NV; ++f) w[q][f] = 0;
-            if (!live[q]) continue;
-            // the segment of entry i (segments of one partition are about equally long: proportional guess, then walk)
-            int lo = (int)((float)i * guess);
-            lo = lo < 0 ? 0 : (lo >= a.groups ? a.groups - 1 : lo);
-            while (s_off[lo] > i) --lo;
-            while (s_off[lo + 1] <= i) ++lo;
+            i = live[q] ? i : total - 1u;
+            const int lo = s_seg[i - r0];
             const u64* e = a.log + (((size_t)lo * a.parts + part) * (size_t)a.cap + (i - s_off[lo])) * WORDS;
             key[q] = e[0];
 #pragma unroll
             for (int f = 0; f < NV; ++f) w[q][f] = e[1 + f];
         }
+        // the home slots of all four are claimed at once (most are free: the table ends up half full)
+        int sl[4];
+        u64 seen[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if (!live[q]) continue;
-            int sl = -1;
-            if (key[q] != W_EMPTY_KEY) {
-                i64 s = (i64)w_hash_slot(key[q], (u32)a.slots) - base;      // the key's home slot, inside this slice
-                if (s >= 0 && s < S) {
+            const i64 s = (i64)w_table_hash_slot(key[q], (u32)a.slots) - base;      // the key's home slot, inside this slice
+            const bool ok = live[q] && key[q] != W_EMPTY_KEY && s >= 0 && s < S;
+            sl[q] = ok ? (int)s : -1;
+            seen[q] = W_EMPTY_KEY;
+            __hip_atomic_compare_exchange_strong(ok ? s_keys + s : s_spare + (tid & 63), &seen[q], ok ? key[q] : W_EMPTY_KEY, __ATOMIC_RELAXED,
+                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        // an entry whose home slot holds another key walks on (one in five, most of them one slot further)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (sl[q] < 0 || seen[q] == W_EMPTY_KEY || seen[q] == key[q]) continue;
+            int t = sl[q] + 1;
+            sl[q] = -1;
 #pragma unroll 1
-                    for (; s < S; ++s) {
-                        const u64 cur = __hip_atomic_load(s_keys + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                        if (cur == key[q]) { sl = (int)s; break; }
-                        if (cur == W_EMPTY_KEY) {
-                            u64 expect = W_EMPTY_KEY;
-                            if (__hip_atomic_compare_exchange_strong(s_keys + s, &expect, key[q], __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                                     __HIP_MEMORY_SCOPE_WORKGROUP) || expect == key[q]) {
-                                sl = (int)s;
-                                break;
-                            }
-                        }
+            for (; t < S; ++t) {
+                const u64 cur = __hip_atomic_load(s_keys + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (cur == key[q]) { sl[q] = t; break; }
+                if (cur == W_EMPTY_KEY) {
+                    u64 expect = W_EMPTY_KEY;
+                    if (__hip_atomic_compare_exchange_strong(s_keys + t, &expect, key[q], __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_WORKGROUP) || expect == key[q]) {
+                        sl[q] = t;
+                        break;
                     }
                 }
             }
-            if (sl >= 0) {
+        }
 #pragma unroll
-                for (int f = 0; f < NV; ++f) cell_combine<FUNC>(&s_vals[f][sl], w[q][f], a.is_f64[f], 0);
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int f = 0; f < NV; ++f) cell_combine<FUNC>(sl[q] >= 0 ? &s_vals[f][sl[q]] : s_spare + 64 + (tid & 63), w[q][f], a.is_f64[f], 0);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (!live[q] || sl[q] >= 0) continue;
+            // past the end of the slice, or the key equal to the free marker: to the list
+            const u32 at = __hip_atomic_fetch_add(a.overflow_count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((i64)at < a.overflow_cap) {
+                u64* o = a.overflow + (size_t)at * WORDS;
+                o[0] = key[q];
+#pragma unroll
+                for (int f = 0; f < NV; ++f) o[1 + f] = w[q][f];
             } else {
-                const u32 at = __hip_atomic_fetch_add(a.overflow_count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if ((i64)at < a.overflow_cap) {
-                    u64* o = a.overflow + (size_t)at * WORDS;
-                    o[0] = key[q];
-#pragma unroll
-                    for (int f = 0; f < NV; ++f) o[1 + f] = w[q][f];
-                } else {
-                    atomicOr(a.err, 1);          // only a table far over its declared capacity gets here: the capacity error
-                }
+                atomicOr(a.err, 1);          // only a table far over its declared capacity gets here: the capacity error
             }
         }
     }

@@ -506,6 +506,29 @@ def test_dictionary_of_millions_of_keys_built_slice_by_slice(wb, func, vts, tune
     _check(wb, p, cols, label="slices %s %s %s" % (func, vts, tune), tune=tune)
 
 
+@pytest.mark.parametrize("repeat", [1, 2])
+def test_slices_filled_the_way_a_join_build_fills_them(wb, repeat):
+    """3e6 distinct keys with a stride of four (order numbers), every one once or twice, in a table of 2^23
+    slots: 1024 slices that each merge some 2900 (5900) queue entries - a second round of 4096 for most of
+    them when keys repeat - with the table's second hash (a table this size takes it; under the first,
+    three of these keys share a home slot)."""
+    from oracle import interp
+    from tests import parity
+    from workloads import joins
+    orders, _ = joins.make_tables(3_000_000, 10, device="cuda")
+    if repeat == 2:
+        g = torch.Generator(device="cpu").manual_seed(5)
+        order = torch.randperm(6_000_000, generator=g).cuda()
+        orders = [torch.cat([c, c])[order].contiguous() for c in orders]
+    build = joins.program_build(3_000_000)
+    want = interp.run(build, [c.cpu().numpy() for c in orders])
+    res = _run(wb, build, orders)
+    try:
+        parity.assert_matches(build, res, want, label="dense slices x%d" % repeat)
+    finally:
+        res.free()
+
+
 def test_dictmerger_capacity_error(wb):
     keys = np.arange(5000, dtype=np.int64)
     p = Program(["i64"])
