@@ -589,9 +589,14 @@ __device__ __forceinline__ void groups_of_keys(const GroupScatter& a, u64* s_ck,
         }
         slot[j] = found;
     }
+    // (the four group numbers are read side by side, from slot 0 where none is needed: behind a branch each
+    // read would be waited for before the next is issued)
+    int sp[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) sp[j] = a.slot_pos[miss[j] && slot[j] >= 0 ? slot[j] : 0];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-        if (miss[j]) gid[j] = slot[j] >= 0 ? a.slot_pos[slot[j]] : -1;
+        if (miss[j]) gid[j] = slot[j] >= 0 ? sp[j] : -1;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         if (!miss[j] || gid[j] < 0 || kb[j] == kEmptyKey || ck[j] != kEmptyKey) continue;
@@ -605,6 +610,12 @@ __device__ __forceinline__ void groups_of_keys(const GroupScatter& a, u64* s_ck,
         if (gid[j] >= 0 && (gid[j] >> a.log_bucket) >= a.nbuckets) gid[j] = -1;     // (capacity error: not extracted)
 }
 
+// WIDE: one 8-byte key field and 8-byte values.  Their loads then stand in the code without a branch
+// around them (a pair past the end re-reads the last one and is not used), which is what lets the next
+// tile's loads stay in flight while this tile is ranked, sorted and stored: a load inside a branch -
+// `if (i < npairs)`, or a switch over the field's size - is waited for at the end of that branch, and the
+// eight loads of a thread then took eight memory round trips, one after the other, before anything else ran.
+template <bool WIDE>
 __global__ void __launch_bounds__(1024) group_partition_kernel(const GroupScatter a) {
     __shared__ u32 s_cnt[256];        // pairs of the tile per range
     __shared__ i64 s_cur[256];        // where the tile's pairs of a range go
@@ -628,11 +639,17 @@ __global__ void __launch_bounds__(1024) group_partition_kernel(const GroupScatte
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const i64 i = t * GROUP_TILE + j * 1024 + tid;
-            nkb[j] = 0;
-            nval[j] = 0;
-            if (i < npairs) {
-                for (int k = 0; k < a.nkeys; ++k) nkb[j] |= load_bits(a.key[k], i, a.key_size[k]) << a.key_shift[k];
-                nval[j] = load_bits(a.value, i, a.value_size);
+            if (WIDE) {
+                const i64 ic = i < npairs ? i : npairs - 1;
+                nkb[j] = __builtin_nontemporal_load((const u64*)a.key[0] + ic);
+                nval[j] = __builtin_nontemporal_load((const u64*)a.value + ic);
+            } else {
+                nkb[j] = 0;
+                nval[j] = 0;
+                if (i < npairs) {
+                    for (int k = 0; k < a.nkeys; ++k) nkb[j] |= load_bits(a.key[k], i, a.key_size[k]) << a.key_shift[k];
+                    nval[j] = load_bits(a.value, i, a.value_size);
+                }
             }
         }
     };
@@ -730,8 +747,11 @@ __global__ void __launch_bounds__(1024) group_place_kernel(const GroupScatter a)
     __syncthreads();
     const i64 total = s_first[256];
     // the chunk after this one is loaded while this one is counted and stored
+    // (loads without a branch around them: a pair past the range's end re-reads the range's last one
+    // and is marked in `ndead`, not by a value put in place of the load's, which would wait for the load)
     u32 ngrp[8];
     u64 nval[8];
+    u32 ndead = 0;
     i64 n_lo = 0, n_hi = 0;
     auto load_chunk = [&](i64 w) {
         int b = 0;                                 // last range with s_first[b] <= w
@@ -741,15 +761,14 @@ __global__ void __launch_bounds__(1024) group_place_kernel(const GroupScatter a)
         n_hi = (i64)(b + 1) * B < G ? (i64)(b + 1) * B : G;
         const i64 start = a.offsets[n_lo] + (w - s_first[b]) * PLACE_CHUNK;
         const i64 stop = a.offsets[n_hi];
+        ndead = 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const i64 i = start + j * 1024 + tid;
-            ngrp[j] = ~0u;
-            nval[j] = 0;
-            if (i < stop) {
-                ngrp[j] = __builtin_nontemporal_load(a.tmp_group + i);
-                nval[j] = __builtin_nontemporal_load(a.tmp_value + i);
-            }
+            ndead |= (i < stop ? 0u : 1u) << j;
+            const i64 ic = i < stop ? i : stop - 1;        // (a chunk exists only where its range has pairs: start < stop)
+            ngrp[j] = __builtin_nontemporal_load(a.tmp_group + ic);
+            nval[j] = __builtin_nontemporal_load(a.tmp_value + ic);
         }
     };
     if ((i64)blockIdx.x < total) load_chunk(blockIdx.x);
@@ -759,7 +778,7 @@ __global__ void __launch_bounds__(1024) group_place_kernel(const GroupScatter a)
         u64 val[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            local[j] = ngrp[j] == ~0u ? ~0u : ngrp[j] - (u32)lo_g;
+            local[j] = (ndead >> j) & 1u ? ~0u : ngrp[j] - (u32)lo_g;
             val[j] = nval[j];
         }
         if (w + gridDim.x < total) load_chunk(w + gridDim.x);
@@ -796,7 +815,10 @@ __global__ void __launch_bounds__(1024) group_place_kernel(const GroupScatter a)
 
 hipError_t launch_group_partition(const GroupScatter& g, int blocks, hipStream_t stream) {
     if (g.nbuckets < 1 || g.nbuckets > 256 || g.log_bucket < 0 || (1ll << g.log_bucket) > PLACE_MAX_BUCKET) return hipErrorInvalidValue;
-    group_partition_kernel<<<dim3((unsigned)blocks), dim3(1024), 0, stream>>>(g);
+    if (g.nkeys == 1 && g.key_size[0] == 8 && g.key_shift[0] == 0 && g.value_size == 8)
+        group_partition_kernel<true><<<dim3((unsigned)blocks), dim3(1024), 0, stream>>>(g);
+    else
+        group_partition_kernel<false><<<dim3((unsigned)blocks), dim3(1024), 0, stream>>>(g);
     return hipGetLastError();
 }
 hipError_t launch_group_place(const GroupScatter& g, int blocks, hipStream_t stream) {
