@@ -143,6 +143,7 @@ __global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, cons
     __shared__ u64 s_base;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const i64 total = slots + 1;                       // the extra slot holds the key equal to the free marker
+    const bool marker_key = hdr[1] != 0;               // (read once: the loops below would reload it for every slot)
     for (i64 base = (i64)blockIdx.x * 256 * J; base < total; base += (i64)gridDim.x * 256 * J) {
         u64 kb[J];
         u32 used = 0;                                  // bit j: slot j of this thread is occupied
@@ -155,7 +156,7 @@ __global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, cons
 #pragma unroll
         for (int j = 0; j < J; ++j) {
             const i64 s = base + (i64)(wave * J + j) * 64 + lane;
-            const bool u = s < slots ? (kb[j] != kEmptyKey) : (s == slots && hdr[1] != 0);
+            const bool u = s < slots ? (kb[j] != kEmptyKey) : (s == slots && marker_key);
             used |= (u ? 1u : 0u) << j;
             mine += (u32)__popcll(__builtin_amdgcn_ballot_w64(u));
         }
