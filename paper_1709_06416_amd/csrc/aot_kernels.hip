@@ -726,6 +726,7 @@ __global__ void __launch_bounds__(1024) group_partition_kernel(const GroupScatte
 #define PLACE_MAX_BUCKET 4096
 __global__ void __launch_bounds__(1024) group_place_kernel(const GroupScatter a) {
     __shared__ i64 s_first[257];                  // chunks before each range
+    __shared__ i64 s_begin[257];                  // where each range's pairs begin in the scratch arrays (s_begin[b + 1]: where they end)
     __shared__ u32 s_cnt[PLACE_MAX_BUCKET];       // pairs of the chunk per group of the range
     __shared__ i64 s_base[PLACE_MAX_BUCKET];      // where they go
     const int tid = threadIdx.x;
@@ -733,16 +734,31 @@ __global__ void __launch_bounds__(1024) group_place_kernel(const GroupScatter a)
     i64 G = (i64)*a.ngroups;
     if (G > a.capacity) G = a.capacity;
     const i64 B = (i64)1 << a.log_bucket;
-    if (tid == 0) {
-        i64 run = 0;
-        for (int b = 0; b < 256; ++b) {
-            s_first[b] = run;
-            if (b < a.nbuckets) {
-                const i64 lo = (i64)b * B < G ? (i64)b * B : G, hi = (i64)(b + 1) * B < G ? (i64)(b + 1) * B : G;
-                run += (a.offsets[hi] - a.offsets[lo] + PLACE_CHUNK - 1) / PLACE_CHUNK;
-            }
+    // Where the ranges begin, read by 257 threads at once and kept (one thread reading them one after the
+    // other was a hundred memory round trips in front of every work-group's first chunk, and read again
+    // when a chunk is looked up they were a round trip of their own in front of every chunk's loads).
+    if (tid <= 256) {
+        const i64 b = tid < a.nbuckets ? tid : a.nbuckets;
+        s_begin[tid] = a.offsets[b * B < G ? b * B : G];
+    }
+    __syncthreads();
+    if (tid < 64) {
+        // chunks before each range: exclusive prefix of the ranges' chunk counts, four ranges per lane
+        i64 c[4], mine = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            c[k] = (s_begin[tid * 4 + k + 1] - s_begin[tid * 4 + k] + PLACE_CHUNK - 1) / PLACE_CHUNK;
+            mine += c[k];
         }
-        s_first[256] = run;
+        i64 incl = mine;
+        for (int o = 1; o < 64; o <<= 1) {
+            const i64 up = __shfl_up(incl, o, 64);
+            if (tid >= o) incl += up;
+        }
+        i64 run = incl - mine;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { s_first[tid * 4 + k] = run; run += c[k]; }
+        if (tid == 63) s_first[256] = run;
     }
     for (int q = tid; q < PLACE_MAX_BUCKET; q += 1024) s_cnt[q] = 0;
     __syncthreads();
@@ -760,8 +776,8 @@ __global__ void __launch_bounds__(1024) group_place_kernel(const GroupScatter a)
             if (b + step < 256 && s_first[b + step] <= w) b += step;
         n_lo = (i64)b * B < G ? (i64)b * B : G;
         n_hi = (i64)(b + 1) * B < G ? (i64)(b + 1) * B : G;
-        const i64 start = a.offsets[n_lo] + (w - s_first[b]) * PLACE_CHUNK;
-        const i64 stop = a.offsets[n_hi];
+        const i64 start = s_begin[b] + (w - s_first[b]) * PLACE_CHUNK;
+        const i64 stop = s_begin[b + 1];
         ndead = 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
