@@ -433,7 +433,8 @@ const char* weld_last_error(void);
  * 128-bit loads; used to measure the attainable HBM read rate on the box.
  * Writes a 64-bit checksum to *checksum_dev (device pointer). */
 weld_status_t weld_probe_read(const void* data, int64_t bytes, void* checksum_dev, void* stream);
-/* Plain copy kernel of known size (device to device), used to scale the HBM counters. */
+/* Plain copy kernel of known size (device to device, one 16-byte vector per thread), used to scale the HBM
+ * counters and as the box's ceiling for a stream of as many bytes written as read. */
 weld_status_t weld_probe_copy(void* dst, const void* src, int64_t bytes, void* stream);
 
 const char* weld_version(void);

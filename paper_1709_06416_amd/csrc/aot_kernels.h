@@ -161,6 +161,6 @@ struct StaticLengths {
 hipError_t launch_static_status(const void* ctl, const StaticLengths& lens, int64_t* status_dev, hipStream_t stream);
 
 hipError_t launch_probe_read(const void* data, int64_t bytes, void* checksum, int blocks, hipStream_t stream);
-hipError_t launch_probe_copy(void* dst, const void* src, int64_t bytes, int blocks, hipStream_t stream);
+hipError_t launch_probe_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream);
 
 }  // namespace weld

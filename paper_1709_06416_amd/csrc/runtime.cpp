@@ -1285,7 +1285,7 @@ weld_status_t weld_probe_read(const void* data, int64_t bytes, void* checksum_de
 
 weld_status_t weld_probe_copy(void* dst, const void* src, int64_t bytes, void* stream) {
     if (!dst || !src || bytes < 0 || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return WELD_ERR_INVALID_ARG;
-    hipError_t h = launch_probe_copy(dst, src, bytes, device_info().cus * 8, (hipStream_t)stream);
+    hipError_t h = launch_probe_copy(dst, src, bytes, (hipStream_t)stream);
     return h == hipSuccess ? WELD_OK : WELD_ERR_DEVICE;
 }
 
