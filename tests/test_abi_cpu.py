@@ -108,6 +108,19 @@ def test_merger_only_loops_finish_in_the_loop_kernel(wb):
     assert "w_arrive_last(a.arrive)" not in wb.generated_source(configs.program_c4())
 
 
+def test_tables_choose_their_hash_by_size_and_slices_follow_the_table(wb):
+    """Host logic read off the generated text: a dictionary of millions of keys queues its merges by slice of
+    the global table, and the slice of a key comes from the TABLE's hash of it (which depends on the table's
+    size), not from a hash of its own."""
+    from workloads import joins
+    src = wb.generated_source(joins.program_build(3_000_000))
+    assert "#define W_SPILL_BY_SLOT 1" in src and "#define W_SPILL_SLICE_BITS 13" in src and "#define W_SPILL_PARTS 1024" in src
+    assert "w_table_hash_slot(kbits, (u32)W_SPILL_PARTS << W_SPILL_SLICE_BITS) >> W_SPILL_SLICE_BITS" in src
+    assert "if (slots >= (1u << 21))" in src
+    small = wb.generated_source(configs.program_c5())
+    assert "W_SPILL_BY_SLOT 1" not in small
+
+
 def test_planner_overlaps_tiles_only_where_the_registers_allow(wb):
     """Host logic only: which compacting loops load the next tile's columns ahead, read off the generated text."""
     c5 = wb.generated_source(configs.program_c5())
