@@ -1118,7 +1118,15 @@ Generated generate(const Loop& L, const Variant& var) {
         // first probes issued in two halves to free registers, and a 24-bit multiplication in the table
         // hash (both within the noise: the kernel is bound by how little the phases of its one
         // work-group per compute unit overlap, not by the instructions it issues; two work-groups of
-        // 512 threads with tables of half the size: 0.52 ms against 0.46).
+        // 512 threads with tables of half the size: 0.52 ms against 0.46).  Clock reads around a tile's
+        // phases put a working wavefront's two barrier waits at 2.0 and 4.3 of the tile's 16.4 us (the ticket's
+        // round trip; the first wavefront's look-back, 2.7 us at 0.1 polls per tile), and three forms without
+        // them were built and measured: the ticket drawn behind the second barrier (no change), a first
+        // wavefront that holds no rows and only draws tickets, publishes and looks back (0.468 against 0.438 ms),
+        // the next tile's counts published a tile early from its prefetched columns (0.454).  A wavefront at a
+        // barrier leaves its issue slots and LDS time to the others: the waits are slack, and what the
+        // work-group lacks is memory operations in flight while it merges (a plain copy in this launch shape
+        // moves 6.0 TB/s, this loop 4.4).
         const std::string cb = var.pipeline ? "[it & 1]" : "";
         // (drawn ahead, the ticket is a wrapping increment rather than an addition: the compiler turns an
         // addition by some lanes into one by the wavefront's first lane and waits for the result on the
