@@ -54,7 +54,8 @@ hipError_t launch_fill_list(const FillList& f, hipStream_t stream, hipEvent_t st
 // position its entry was written to.
 hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots, const DictValues& vals,
                                const DictLayout& lay, int64_t capacity, void* out_keys, void* out_vals,
-                               void* count, void* err, int* slot_pos, hipStream_t stream);
+                               void* count, void* err, int* slot_pos, unsigned long long* kp32, unsigned int* kwide,
+                               hipStream_t stream);
 
 // groupbuilder, second half.  The loop kernel has counted the pairs of every key in a
 // dictionary (extracted into `counts`, one int64 per group, *ngroups of them) and compacted
@@ -76,6 +77,10 @@ struct GroupScatter {
     const unsigned int* hdr;
     long long slots;
     const int* slot_pos;
+    // for every slot (and the extra one) low half = low half of its key, high half = its group number, -1 where the
+    // slot is free; *kwide != 0: some key is not the sign extension of its low half (then slot_pos and table_keys serve)
+    const unsigned long long* kp32;
+    const unsigned int* kwide;
     long long capacity;
     const long long* offsets;
     unsigned long long* cursor;

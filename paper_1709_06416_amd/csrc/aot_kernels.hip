@@ -132,7 +132,7 @@ template <int J>
 __global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, const u32* hdr, i64 slots,
                                                            DictValues vals, DictLayout lay, i64 capacity,
                                                            unsigned char* out_keys, unsigned char* out_vals,
-                                                           u64* count, int* err, int* slot_pos) {
+                                                           u64* count, int* err, int* slot_pos, u64* kp32, u32* kwide) {
     // A work-group takes 256 * J slots at a time, a wavefront 64 * J consecutive ones (load j of lane
     // l: slot (wave * J + j) * 64 + l).  The occupied slots are counted, their output positions
     // reserved with ONE device atomic (a same-address atomic costs about 12 ns here, serialised: one
@@ -144,6 +144,7 @@ __global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, cons
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const i64 total = slots + 1;                       // the extra slot holds the key equal to the free marker
     const bool marker_key = hdr[1] != 0;               // (read once: the loops below would reload it for every slot)
+    bool wide = false;
     for (i64 base = (i64)blockIdx.x * 256 * J; base < total; base += (i64)gridDim.x * 256 * J) {
         u64 kb[J];
         u32 used = 0;                                  // bit j: slot j of this thread is occupied
@@ -183,9 +184,20 @@ __global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, cons
                 const u64 bal = __builtin_amdgcn_ballot_w64(u);
                 at[q] = (i64)(run + (u64)__builtin_amdgcn_mbcnt_hi((u32)(bal >> 32), __builtin_amdgcn_mbcnt_lo((u32)bal, 0)));
                 run += (u64)__popcll(bal);
-                if (!u) { at[q] = -1; continue; }
                 const i64 s = base + (i64)(wave * J + j) * 64 + lane;
+                if (!u) {
+                    if (kp32 && s < total) kp32[s] = 0xffffffff00000000ull;     // a free slot
+                    at[q] = -1;
+                    continue;
+                }
                 if (slot_pos) slot_pos[s] = at[q] < capacity ? (int)at[q] : -1;
+                if (kp32) {
+                    // the slot's group number beside the low half of its key: one 8-byte read answers a look-up
+                    // as long as every key is the sign extension of its low half (`wide` says whether)
+                    const u64 kfull = s < slots ? kb[j] : kEmptyKey;
+                    kp32[s] = ((u64)(u32)(at[q] < capacity ? (int)at[q] : -1) << 32) | (u32)kfull;
+                    wide |= (i64)kfull != (i64)(int)(u32)kfull;
+                }
                 if (at[q] >= capacity) {
                     atomicOr(err, 1);
                     at[q] = -1;
@@ -214,11 +226,13 @@ __global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, cons
         }
         __syncthreads();                               // s_wave / s_base are reused by the next round
     }
+    if (kwide && __builtin_amdgcn_ballot_w64(wide) != 0 && lane == 0) atomicOr(kwide, 1u);
 }
 
 hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots, const DictValues& vals,
                                const DictLayout& lay, int64_t capacity, void* out_keys, void* out_vals,
-                               void* count, void* err, int* slot_pos, hipStream_t stream) {
+                               void* count, void* err, int* slot_pos, unsigned long long* kp32, unsigned int* kwide,
+                               hipStream_t stream) {
     const bool big = slots >= (1ll << 22);
     const int64_t round = big ? 8192 : 2048;
     int64_t blocks = (slots + 1 + round - 1) / round;
@@ -226,11 +240,11 @@ hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots,
     if (big)
         dict_extract_kernel<32><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
             (const u64*)keys, (const u32*)hdr, slots, vals, lay, capacity, (unsigned char*)out_keys,
-            (unsigned char*)out_vals, (u64*)count, (int*)err, slot_pos);
+            (unsigned char*)out_vals, (u64*)count, (int*)err, slot_pos, (u64*)kp32, kwide);
     else
         dict_extract_kernel<8><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
             (const u64*)keys, (const u32*)hdr, slots, vals, lay, capacity, (unsigned char*)out_keys,
-            (unsigned char*)out_vals, (u64*)count, (int*)err, slot_pos);
+            (unsigned char*)out_vals, (u64*)count, (int*)err, slot_pos, (u64*)kp32, kwide);
     return hipGetLastError();
 }
 
@@ -549,8 +563,8 @@ hipError_t launch_group_scatter(const GroupScatter& g, int blocks, hipStream_t s
 // with a heavy-tailed key set the frequent keys get there first and then answer most lookups).
 // An entry is claimed by writing its key; its group number follows, and until then reads of the
 // entry count as misses.
-__device__ __forceinline__ void groups_of_keys(const GroupScatter& a, u64* s_ck, u32* s_cg, const u64 (&kb)[4], const bool (&live)[4],
-                                               int (&gid)[4]) {
+__device__ __forceinline__ void groups_of_keys(const GroupScatter& a, bool narrow, u64* s_ck, u32* s_cg, const u64 (&kb)[4],
+                                               const bool (&live)[4], int (&gid)[4]) {
     u32 ce[4];
     u64 first[4], ck[4];
     i64 slot[4];
@@ -569,6 +583,36 @@ __device__ __forceinline__ void groups_of_keys(const GroupScatter& a, u64* s_ck,
             }
         }
     }
+    if (narrow) {
+        // Every key of the dictionary is the sign extension of its low half: the look-up reads ONE 8-byte
+        // word per slot, the low half of the slot's key beside its group number (written at extraction), and a
+        // table of 2^18 slots is 2 MB of such words instead of 2 MB of keys and 1 MB of numbers read one after
+        // the other.  The four first reads of a thread are issued side by side (slot 0 where none is needed).
+        u64 e[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            slot[j] = (i64)table_hash_slot(kb[j], (u32)a.slots);
+            e[j] = a.kp32[miss[j] ? slot[j] : 0];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (!miss[j]) continue;
+            const u32 k32 = (u32)kb[j];
+            int g = -1;
+            if ((i64)kb[j] == (i64)(int)k32) {                   // (a wide key is in no such dictionary)
+                u64 cur = e[j];
+                i64 s = slot[j];
+                for (i64 probe = 0; probe < a.slots; ++probe) {
+                    const int pos = (int)(cur >> 32);
+                    if (pos < 0) break;                          // a free slot (or an entry beyond the capacity): not there
+                    if ((u32)cur == k32) { g = pos; break; }
+                    s = (s + 1) & (a.slots - 1);
+                    cur = a.kp32[s];
+                }
+            }
+            gid[j] = g;
+        }
+    } else {
     // (requesting the home slot's group number together with its key, to save the second read its wait,
     // costs more in cache lines moved than it saves: 1.07 -> 1.17 ms)
 #pragma unroll
@@ -598,6 +642,7 @@ __device__ __forceinline__ void groups_of_keys(const GroupScatter& a, u64* s_ck,
 #pragma unroll
     for (int j = 0; j < 4; ++j)
         if (miss[j]) gid[j] = slot[j] >= 0 ? sp[j] : -1;
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         if (!miss[j] || gid[j] < 0 || kb[j] == kEmptyKey || ck[j] != kEmptyKey) continue;
@@ -628,6 +673,7 @@ __global__ void __launch_bounds__(1024) group_partition_kernel(const GroupScatte
     const int tid = threadIdx.x;
     const i64 npairs = (i64)*a.npairs;
     const i64 ntiles = (npairs + GROUP_TILE - 1) / GROUP_TILE;
+    const bool narrow = a.kp32 && *a.kwide == 0;      // (uniform: every key of the dictionary fits 32 bits)
     if (tid < 256) s_cnt[tid] = 0;
     for (int q = tid; q < PART_CACHE; q += 1024) {
         s_ck[q] = kEmptyKey;
@@ -667,7 +713,7 @@ __global__ void __launch_bounds__(1024) group_partition_kernel(const GroupScatte
             val[j] = nval[j];
         }
         if (t + gridDim.x < ntiles) load_tile(t + gridDim.x);
-        groups_of_keys(a, s_ck, s_cg, kb, live, gid);
+        groups_of_keys(a, narrow, s_ck, s_cg, kb, live, gid);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             rank[j] = 0;

@@ -406,7 +406,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     const int64_t mem_limit = st ? (int64_t)st->scratch_bytes : conf.memory_limit;
     auto take_out = [&](size_t bytes) -> size_t { return st ? 0 : lay.take(bytes); };
     struct Off { size_t part = 0, res = 0, out = 0, desc = 0, keys = 0, vals[8] = {0}, okeys = 0, ovals = 0, log = 0, qcnt = 0,
-                        slot_pos = 0, goffsets = 0, gcursor = 0, gdesc = 0, gvalues = 0, gbcursor = 0, gtmp_group = 0, gtmp_value = 0,
+                        slot_pos = 0, kp32 = 0, kwide = 0, goffsets = 0, gcursor = 0, gdesc = 0, gvalues = 0, gbcursor = 0, gtmp_group = 0, gtmp_value = 0,
                         ovf = 0, ovf_count = 0;
                         int64_t slots = 0, qcap = 0; int glog = -1; };
     auto link_of = [&](size_t b) -> const GroupLink* {
@@ -444,6 +444,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
                 off[b].ovals = take_out((size_t)s.capacity * vs);
                 if (const GroupLink* g = link_of(b)) {      // second half of a groupbuilder
                     off[b].slot_pos = lay.take(4 * (size_t)(slots + 1));
+                    off[b].kwide = lay.take(8);
                     off[b].goffsets = lay.take(8 * (size_t)(s.capacity + 1));
                     off[b].gcursor = lay.take(8 * (size_t)s.capacity);
                     off[b].gdesc = lay.take(8 * (size_t)((s.capacity + 8191) / 8192));
@@ -464,9 +465,11 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             if (!link_of(b) || s.capacity <= 1024 || s.capacity > 256 * 4096) continue;
             int lg = 10;     // (1e5 groups: 98 ranges of 1024 give the partition longer runs to write than 196 of 512: 2.42 -> 2.34 ms)
             while (((int64_t)256 << lg) < s.capacity) ++lg;
-            const size_t need = 12 * (size_t)n + 256 * 8 + 1024;
+            // (and 8 bytes per table slot for the words the partition step looks keys up in)
+            const size_t need = 12 * (size_t)n + 8 * (size_t)(off[b].slots + 1) + 256 * 8 + 1024;
             if (mem_limit > 0 && (int64_t)(lay.total + need + still_to_come) > mem_limit) continue;
             off[b].glog = lg;
+            off[b].kp32 = lay.take(8 * (size_t)(off[b].slots + 1));
             off[b].gbcursor = lay.take(256 * 8);
             off[b].gtmp_group = lay.take(4 * (size_t)n);
             off[b].gtmp_value = lay.take(8 * (size_t)n);
@@ -660,6 +663,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
                     return hip_err("fill", h);
             if (off[b].glog >= 0 && (h = fill(base + off[b].gbcursor, 256, 0)) != hipSuccess) return hip_err("fill", h);
             if (link_of(b) && (h = fill(base + off[b].gdesc, (s.capacity + 8191) / 8192, 0)) != hipSuccess) return hip_err("fill", h);
+            if (link_of(b) && (h = fill(base + off[b].kwide, 1, 0)) != hipSuccess) return hip_err("fill", h);
             if (var.spill_slices && var.backend[b] == BK_DICT_LDS && (h = fill(base + off[b].ovf_count, 1, 0)) != hipSuccess) return hip_err("fill", h);
         }
     }
@@ -759,7 +763,9 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         const GroupLink* g = link_of(b);
         h = launch_dict_extract(base + off[b].keys, base + off_ctl + ctl_hdr_off((int)b), off[b].slots, dv, dl, s.capacity,
                                 op[b].okeys, op[b].ovals, base + off_ctl + ctl_count_off((int)b),
-                                base + off_ctl + 8, g ? (int*)(base + off[b].slot_pos) : nullptr, stream);
+                                base + off_ctl + 8, g ? (int*)(base + off[b].slot_pos) : nullptr,
+                                g && off[b].glog >= 0 ? (unsigned long long*)(base + off[b].kp32) : nullptr,
+                                g ? (unsigned int*)(base + off[b].kwide) : nullptr, stream);
         if (h != hipSuccess) return hip_err("dict extract", h);
         r->kernel_count++;
         if (!g) continue;
@@ -783,6 +789,8 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         gs.hdr = (const unsigned int*)(base + off_ctl + ctl_hdr_off((int)b));
         gs.slots = off[b].slots;
         gs.slot_pos = (const int*)(base + off[b].slot_pos);
+        gs.kp32 = off[b].glog >= 0 ? (const unsigned long long*)(base + off[b].kp32) : nullptr;
+        gs.kwide = (const unsigned int*)(base + off[b].kwide);
         gs.capacity = s.capacity;
         gs.offsets = (const long long*)(base + off[b].goffsets);
         gs.cursor = (unsigned long long*)(base + off[b].gcursor);
