@@ -51,11 +51,12 @@ struct FillList {
 // start / stop (may be null): events that take the dispatch's own start / end time (no packet of their own in the queue)
 hipError_t launch_fill_list(const FillList& f, hipStream_t stream, hipEvent_t start = nullptr);
 // slot_pos (may be null): receives, for every occupied slot (and the extra slot `slots`), the
-// position its entry was written to.
+// position its entry was written to.  skip_if (may be null): the kernel does nothing when *skip_if != 0
+// (the entries were packed by the kernels that built the table).
 hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots, const DictValues& vals,
                                const DictLayout& lay, int64_t capacity, void* out_keys, void* out_vals,
                                void* count, void* err, int* slot_pos, unsigned long long* kp32, unsigned int* kwide,
-                               hipStream_t stream);
+                               const unsigned int* skip_if, hipStream_t stream);
 
 // groupbuilder, second half.  The loop kernel has counted the pairs of every key in a
 // dictionary (extracted into `counts`, one int64 per group, *ngroups of them) and compacted
@@ -128,6 +129,16 @@ struct SpillMerge {
     int compact;
     long long capacity;            // the dictmerger's declared capacity (sizes the aggregation's LDS tables)
     int table_slots, split;        // set by launch_dict_spill_merge
+    // slice mode, pack != 0: a slice that starts from an empty table (no loop kernel inserted directly) also
+    // writes its entries to the result's packed arrays while it has them in LDS, the entries of the list
+    // follow, and *packed (zero on entry) is set: the extraction kernel behind then has nothing to do
+    // (it would read the whole table again: 512 MiB for 2^25 slots)
+    int pack;
+    DictLayout lay;
+    unsigned char* out_keys;
+    unsigned char* out_vals;
+    unsigned long long* out_count; // entries written so far (zero on entry)
+    unsigned int* packed;
 };
 hipError_t launch_dict_spill_merge(const SpillMerge& a, int nvals, hipStream_t stream, hipEvent_t stop = nullptr);
 // Dictionaries of millions of keys: partition p of the queues holds the keys whose home slot lies in

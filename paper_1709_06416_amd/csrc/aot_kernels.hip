@@ -132,7 +132,9 @@ template <int J>
 __global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, const u32* hdr, i64 slots,
                                                            DictValues vals, DictLayout lay, i64 capacity,
                                                            unsigned char* out_keys, unsigned char* out_vals,
-                                                           u64* count, int* err, int* slot_pos, u64* kp32, u32* kwide) {
+                                                           u64* count, int* err, int* slot_pos, u64* kp32, u32* kwide,
+                                                           const u32* skip_if) {
+    if (skip_if && *skip_if != 0) return;
     // A work-group takes 256 * J slots at a time, a wavefront 64 * J consecutive ones (load j of lane
     // l: slot (wave * J + j) * 64 + l).  The occupied slots are counted, their output positions
     // reserved with ONE device atomic (a same-address atomic costs about 12 ns here, serialised: one
@@ -232,7 +234,7 @@ __global__ void __launch_bounds__(256) dict_extract_kernel(const u64* keys, cons
 hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots, const DictValues& vals,
                                const DictLayout& lay, int64_t capacity, void* out_keys, void* out_vals,
                                void* count, void* err, int* slot_pos, unsigned long long* kp32, unsigned int* kwide,
-                               hipStream_t stream) {
+                               const unsigned int* skip_if, hipStream_t stream) {
     const bool big = slots >= (1ll << 22);
     const int64_t round = big ? 8192 : 2048;
     int64_t blocks = (slots + 1 + round - 1) / round;
@@ -240,11 +242,11 @@ hipError_t launch_dict_extract(const void* keys, const void* hdr, int64_t slots,
     if (big)
         dict_extract_kernel<32><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
             (const u64*)keys, (const u32*)hdr, slots, vals, lay, capacity, (unsigned char*)out_keys,
-            (unsigned char*)out_vals, (u64*)count, (int*)err, slot_pos, (u64*)kp32, kwide);
+            (unsigned char*)out_vals, (u64*)count, (int*)err, slot_pos, (u64*)kp32, kwide, skip_if);
     else
         dict_extract_kernel<8><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
             (const u64*)keys, (const u32*)hdr, slots, vals, lay, capacity, (unsigned char*)out_keys,
-            (unsigned char*)out_vals, (u64*)count, (int*)err, slot_pos, (u64*)kp32, kwide);
+            (unsigned char*)out_vals, (u64*)count, (int*)err, slot_pos, (u64*)kp32, kwide, skip_if);
     return hipGetLastError();
 }
 

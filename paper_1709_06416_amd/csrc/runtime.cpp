@@ -342,6 +342,26 @@ static int streaming_class(const Loop& L, const Variant& var) {
     return 1;
 }
 
+// how a dictmerger's entries lie in the packed result arrays (C struct layout without padding, Sec. 4.2)
+static DictLayout packed_layout(const weld_builder_spec_t& s) {
+    DictLayout dl;
+    memset(&dl, 0, sizeof dl);
+    dl.nkeys = s.nkeys;
+    int shift = 0;
+    for (int k = 0; k < s.nkeys; ++k) {
+        dl.key_size[k] = type_size(s.key_type[k]);
+        dl.key_shift[k] = shift;
+        shift += 8 * dl.key_size[k];
+        dl.key_stride += dl.key_size[k];
+    }
+    dl.nvals = s.nvals;
+    for (int k = 0; k < s.nvals; ++k) {
+        dl.val_size[k] = type_size(s.val_type[k]);
+        dl.val_stride += dl.val_size[k];
+    }
+    return dl;
+}
+
 // entries the slice-building kernel may hand on to the global insert (those that probe past the end of their slice)
 static const size_t kOverflowEntries = 1 << 16;
 
@@ -407,7 +427,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     auto take_out = [&](size_t bytes) -> size_t { return st ? 0 : lay.take(bytes); };
     struct Off { size_t part = 0, res = 0, out = 0, desc = 0, keys = 0, vals[8] = {0}, okeys = 0, ovals = 0, log = 0, qcnt = 0,
                         slot_pos = 0, kp32 = 0, kwide = 0, goffsets = 0, gcursor = 0, gdesc = 0, gvalues = 0, gbcursor = 0, gtmp_group = 0, gtmp_value = 0,
-                        ovf = 0, ovf_count = 0;
+                        ovf = 0, ovf_count = 0, packed = 0;
                         int64_t slots = 0, qcap = 0; int glog = -1; };
     auto link_of = [&](size_t b) -> const GroupLink* {
         for (const GroupLink& g : links)
@@ -484,6 +504,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         off[b].qcnt = lay.take(4 * (size_t)grid * var.spill_parts);
         if (var.spill_slices) {
             off[b].ovf_count = lay.take(8);
+            off[b].packed = lay.take(8);
             off[b].ovf = lay.take(kOverflowEntries * entry);
         }
         int64_t cap = conf.tune.dict_spill;
@@ -665,6 +686,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             if (link_of(b) && (h = fill(base + off[b].gdesc, (s.capacity + 8191) / 8192, 0)) != hipSuccess) return hip_err("fill", h);
             if (link_of(b) && (h = fill(base + off[b].kwide, 1, 0)) != hipSuccess) return hip_err("fill", h);
             if (var.spill_slices && var.backend[b] == BK_DICT_LDS && (h = fill(base + off[b].ovf_count, 1, 0)) != hipSuccess) return hip_err("fill", h);
+            if (var.spill_slices && var.backend[b] == BK_DICT_LDS && (h = fill(base + off[b].packed, 1, 0)) != hipSuccess) return hip_err("fill", h);
         }
     }
     if (fills.n > 0) {
@@ -713,8 +735,16 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             sm.overflow = (unsigned long long*)(base + off[b].ovf);
             sm.overflow_count = (unsigned int*)(base + off[b].ovf_count);
             sm.overflow_cap = kOverflowEntries;
+            if (!link_of(b)) {      // (a groupbuilder's dictionary also needs every slot's position: the extraction kernel's work)
+                sm.pack = 1;
+                sm.lay = packed_layout(s);
+                sm.out_keys = (unsigned char*)op[b].okeys;
+                sm.out_vals = (unsigned char*)op[b].ovals;
+                sm.out_count = (unsigned long long*)(base + off_ctl + ctl_count_off((int)b));
+                sm.packed = (unsigned int*)(base + off[b].packed);
+            }
             h = launch_dict_slice_build(sm, s.nvals, stream, timed && spill_left == 1 ? r->ev3 : nullptr);
-            r->kernel_count++;
+            r->kernel_count += sm.pack ? 2 : 1;
         } else {
             h = launch_dict_spill_merge(sm, s.nvals, stream, timed && spill_left == 1 ? r->ev3 : nullptr);
         }
@@ -742,30 +772,17 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     for (size_t b = 0; b < NB; ++b) {
         const weld_builder_spec_t& s = L.builders[b];
         if (s.kind != WELD_DICTMERGER) continue;
-        DictLayout dl;
-        memset(&dl, 0, sizeof dl);
+        const DictLayout dl = packed_layout(s);
         DictValues dv;
         memset(&dv, 0, sizeof dv);
-        dl.nkeys = s.nkeys;
-        int shift = 0;
-        for (int k = 0; k < s.nkeys; ++k) {
-            dl.key_size[k] = type_size(s.key_type[k]);
-            dl.key_shift[k] = shift;
-            shift += 8 * dl.key_size[k];
-            dl.key_stride += dl.key_size[k];
-        }
-        dl.nvals = s.nvals;
-        for (int k = 0; k < s.nvals; ++k) {
-            dl.val_size[k] = type_size(s.val_type[k]);
-            dl.val_stride += dl.val_size[k];
-            dv.p[k] = (const unsigned long long*)(base + off[b].vals[k]);
-        }
+        for (int k = 0; k < s.nvals; ++k) dv.p[k] = (const unsigned long long*)(base + off[b].vals[k]);
         const GroupLink* g = link_of(b);
         h = launch_dict_extract(base + off[b].keys, base + off_ctl + ctl_hdr_off((int)b), off[b].slots, dv, dl, s.capacity,
                                 op[b].okeys, op[b].ovals, base + off_ctl + ctl_count_off((int)b),
                                 base + off_ctl + 8, g ? (int*)(base + off[b].slot_pos) : nullptr,
                                 g && off[b].glog >= 0 ? (unsigned long long*)(base + off[b].kp32) : nullptr,
-                                g ? (unsigned int*)(base + off[b].kwide) : nullptr, stream);
+                                g ? (unsigned int*)(base + off[b].kwide) : nullptr,
+                                var.spill_slices && var.backend[b] == BK_DICT_LDS && !g ? (const unsigned int*)(base + off[b].packed) : nullptr, stream);
         if (h != hipSuccess) return hip_err("dict extract", h);
         r->kernel_count++;
         if (!g) continue;

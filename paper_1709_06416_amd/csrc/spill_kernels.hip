@@ -28,6 +28,32 @@ template <int NV> struct SpillTable {
     static constexpr int kBatch = NV <= 1 ? 4 : NV <= 3 ? 2 : 1;   // entries a thread holds in registers, twice
 };
 
+// One field of a packed key or value struct: a single store of the field's width where the address is
+// aligned to it, byte by byte otherwise.
+__device__ __forceinline__ void pack_field(unsigned char* p, u64 bits, int size) {
+    if (size == 8 && ((uintptr_t)p & 7) == 0) *(u64*)p = bits;
+    else if (size == 4 && ((uintptr_t)p & 3) == 0) *(u32*)p = (u32)bits;
+    else
+        for (int b = 0; b < size; ++b) p[b] = (unsigned char)(bits >> (8 * b));
+}
+// entry `pos` of the packed result arrays
+template <int NV>
+__device__ __forceinline__ void pack_entry(const SpillMerge& a, i64 pos, u64 key, const u64 (&v)[NV]) {
+    unsigned char* ko = a.out_keys + pos * a.lay.key_stride;
+    int off = 0;
+    for (int k = 0; k < a.lay.nkeys; ++k) {
+        pack_field(ko + off, key >> a.lay.key_shift[k], a.lay.key_size[k]);
+        off += a.lay.key_size[k];
+    }
+    unsigned char* vo = a.out_vals + pos * a.lay.val_stride;
+    off = 0;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        pack_field(vo + off, v[k], a.lay.val_size[k]);
+        off += a.lay.val_size[k];
+    }
+}
+
 // One value cell: the bits are an i64 or a double, FUNC is the dictmerger's merge function.
 template <int FUNC> __device__ __forceinline__ void cell_combine(u64* p, u64 bits, int is_f64, const int agent) {
     if (is_f64) {
@@ -386,6 +412,47 @@ __global__ void __launch_bounds__(1024) dict_slice_build_kernel(const SpillMerge
 #pragma unroll
         for (int k = 0; k < NV; ++k) a.vals[k][base + q] = s_vals[k][q];
     }
+    // The result's packed arrays, while the slice is in LDS (a table that no loop kernel inserted into
+    // directly: everything in it came through this kernel).  A thread's slots get neighbouring places, the
+    // slice's places are reserved with one device atomic.
+    if (a.pack && fresh) {
+        u32 cnt = 0;
+        for (int q = tid; q < S; q += 1024) cnt += s_keys[q] != W_EMPTY_KEY ? 1u : 0u;
+        u32 inc = cnt;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const u32 o = __shfl_up(inc, off, 64);
+            if ((tid & 63) >= off) inc += o;
+        }
+        __syncthreads();                       // (s_wave and s_off[0..1] are free again)
+        if ((tid & 63) == 63) s_wave[tid >> 6] = inc;
+        __syncthreads();
+        u32 pre = 0, all = 0;
+        for (int w = 0; w < 16; ++w) {
+            if (w < (tid >> 6)) pre += s_wave[w];
+            all += s_wave[w];
+        }
+        u64* const s_place = reinterpret_cast<u64*>(s_spare);
+        if (tid == 0) {
+            s_place[0] = all ? __hip_atomic_fetch_add(a.out_count, (u64)all, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+            if (blockIdx.x == 0) *a.packed = 1u;
+        }
+        __syncthreads();
+        i64 pos = (i64)s_place[0] + pre + inc - cnt;
+        for (int q = tid; q < S; q += 1024) {
+            const u64 key = s_keys[q];
+            if (key == W_EMPTY_KEY) continue;
+            if (pos < a.capacity) {
+                u64 v[NV];
+#pragma unroll
+                for (int k = 0; k < NV; ++k) v[k] = s_vals[k][q];
+                pack_entry<NV>(a, pos, key, v);
+            } else {
+                atomicOr(a.err, 1);            // more keys than the declared capacity
+            }
+            ++pos;
+        }
+    }
 }
 
 template <int NV, int FUNC>
@@ -393,13 +460,76 @@ __global__ void __launch_bounds__(256) dict_overflow_insert_kernel(const SpillMe
     constexpr int WORDS = 1 + NV;
     i64 n = (i64)*a.overflow_count;
     if (n > a.overflow_cap) n = a.overflow_cap;
+    const bool pack = a.pack && a.hdr[0] == 0;         // the slices packed their entries: the list's keys follow here
     for (i64 i = (i64)blockIdx.x * 256 + threadIdx.x; i < n; i += (i64)gridDim.x * 256) {
-        const u64* e = a.overflow + (size_t)i * WORDS;
-        const i64 g = w_table_slot(a.keys, a.hdr, a.slots, e[0], a.err);
+        u64* e = a.overflow + (size_t)i * WORDS;
+        const u64 key = e[0];
+        u64 w[NV];
+#pragma unroll
+        for (int f = 0; f < NV; ++f) w[f] = e[1 + f];
+        // the key's slot, and whether THIS entry put the key there (one entry per key does: it reserves the
+        // key's place in the packed arrays and writes the key; the value follows when all are merged)
+        i64 g = -1;
+        bool claimed = false;
+        if (key == W_EMPTY_KEY) {
+            claimed = __hip_atomic_exchange(a.hdr + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u;
+            g = a.slots;
+        } else {
+            const i64 mask = a.slots - 1;
+            i64 s = (i64)w_table_hash_slot(key, (u32)a.slots);
+            for (i64 probe = 0; probe < a.slots; ++probe) {
+                const u64 cur = __hip_atomic_load(a.keys + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (cur == key) { g = s; break; }
+                if (cur == W_EMPTY_KEY) {
+                    u64 expect = W_EMPTY_KEY;
+                    if (__hip_atomic_compare_exchange_strong(a.keys + s, &expect, key, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_AGENT)) {
+                        g = s;
+                        claimed = true;
+                        break;
+                    }
+                    if (expect == key) { g = s; break; }
+                }
+                s = (s + 1) & mask;
+            }
+            if (g < 0) atomicOr(a.err, 1);
+        }
         if (g >= 0) {
 #pragma unroll
-            for (int f = 0; f < NV; ++f) cell_combine<FUNC>(a.vals[f] + g, e[1 + f], a.is_f64[f], 1);
+            for (int f = 0; f < NV; ++f) cell_combine<FUNC>(a.vals[f] + g, w[f], a.is_f64[f], 1);
         }
+        if (pack) {
+            // the entry's own words now say where the key's value goes: slot, place (-1: another entry's business)
+            i64 pos = -1;
+            if (claimed) {
+                pos = (i64)__hip_atomic_fetch_add(a.out_count, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (pos >= a.capacity) {
+                    atomicOr(a.err, 1);
+                    pos = -1;
+                }
+            }
+            e[0] = (u64)g;
+            e[1] = (u64)pos;
+        }
+    }
+}
+
+// Behind the kernel above, when the entries are packed by the table's builders: the keys that came through the
+// list get their (now final) values and their key fields.
+template <int NV>
+__global__ void __launch_bounds__(256) dict_overflow_pack_kernel(const SpillMerge a) {
+    constexpr int WORDS = 1 + NV;
+    if (!(a.pack && a.hdr[0] == 0)) return;
+    i64 n = (i64)*a.overflow_count;
+    if (n > a.overflow_cap) n = a.overflow_cap;
+    for (i64 i = (i64)blockIdx.x * 256 + threadIdx.x; i < n; i += (i64)gridDim.x * 256) {
+        const u64* e = a.overflow + (size_t)i * WORDS;
+        const i64 g = (i64)e[0], pos = (i64)e[1];
+        if (g < 0 || pos < 0) continue;
+        u64 v[NV];
+#pragma unroll
+        for (int f = 0; f < NV; ++f) v[f] = a.vals[f][g];
+        pack_entry<NV>(a, pos, g == a.slots ? W_EMPTY_KEY : a.keys[g], v);
     }
 }
 
@@ -409,8 +539,16 @@ static hipError_t launch_slices(const SpillMerge& a, hipStream_t stream, hipEven
     dict_slice_build_kernel<NV, FUNC><<<dim3((unsigned)a.parts), dim3(1024), 0, stream>>>(a);
     hipError_t h = hipGetLastError();
     if (h != hipSuccess) return h;
-    if (stop) hipExtLaunchKernelGGL((dict_overflow_insert_kernel<NV, FUNC>), dim3(64), dim3(256), 0, stream, nullptr, stop, 0, a);
-    else dict_overflow_insert_kernel<NV, FUNC><<<dim3(64), dim3(256), 0, stream>>>(a);
+    if (!a.pack) {
+        if (stop) hipExtLaunchKernelGGL((dict_overflow_insert_kernel<NV, FUNC>), dim3(64), dim3(256), 0, stream, nullptr, stop, 0, a);
+        else dict_overflow_insert_kernel<NV, FUNC><<<dim3(64), dim3(256), 0, stream>>>(a);
+        return hipGetLastError();
+    }
+    dict_overflow_insert_kernel<NV, FUNC><<<dim3(64), dim3(256), 0, stream>>>(a);
+    h = hipGetLastError();
+    if (h != hipSuccess) return h;
+    if (stop) hipExtLaunchKernelGGL(dict_overflow_pack_kernel<NV>, dim3(64), dim3(256), 0, stream, nullptr, stop, 0, a);
+    else dict_overflow_pack_kernel<NV><<<dim3(64), dim3(256), 0, stream>>>(a);
     return hipGetLastError();
 }
 template <int NV>
