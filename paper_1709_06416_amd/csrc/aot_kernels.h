@@ -72,6 +72,7 @@ struct GroupScatter {
     const void* key[4];
     int key_size[4];
     int key_shift[4];
+    int key_sext32;                        // the one key field holds the low half of a 64-bit key (its sign extension is the key)
     const void* value;
     int value_size;
     const unsigned long long* table_keys;

@@ -443,6 +443,7 @@ __global__ void __launch_bounds__(1024) group_scatter_kernel(const GroupScatter 
             val[j] = 0;
             if (live[j]) {
                 for (int k = 0; k < a.nkeys; ++k) kb[j] |= load_bits(a.key[k], i, a.key_size[k]) << a.key_shift[k];
+                if (a.key_sext32) kb[j] = (u64)(i64)(int)(u32)kb[j];
                 val[j] = load_bits(a.value, i, a.value_size);
             }
         }
@@ -663,7 +664,8 @@ __device__ __forceinline__ void groups_of_keys(const GroupScatter& a, bool narro
 // tile's loads stay in flight while this tile is ranked, sorted and stored: a load inside a branch -
 // `if (i < npairs)`, or a switch over the field's size - is waited for at the end of that branch, and the
 // eight loads of a thread then took eight memory round trips, one after the other, before anything else ran.
-template <bool WIDE>
+// WIDE == 4: the same with the key's low half in a 4-byte column.
+template <int WIDE>
 __global__ void __launch_bounds__(1024) group_partition_kernel(const GroupScatter a) {
     __shared__ u32 s_cnt[256];        // pairs of the tile per range
     __shared__ i64 s_cur[256];        // where the tile's pairs of a range go
@@ -690,13 +692,15 @@ __global__ void __launch_bounds__(1024) group_partition_kernel(const GroupScatte
             const i64 i = t * GROUP_TILE + j * 1024 + tid;
             if (WIDE) {
                 const i64 ic = i < npairs ? i : npairs - 1;
-                nkb[j] = __builtin_nontemporal_load((const u64*)a.key[0] + ic);
+                if (WIDE == 4) nkb[j] = (u64)(i64)(int)__builtin_nontemporal_load((const u32*)a.key[0] + ic);
+                else nkb[j] = __builtin_nontemporal_load((const u64*)a.key[0] + ic);
                 nval[j] = __builtin_nontemporal_load((const u64*)a.value + ic);
             } else {
                 nkb[j] = 0;
                 nval[j] = 0;
                 if (i < npairs) {
                     for (int k = 0; k < a.nkeys; ++k) nkb[j] |= load_bits(a.key[k], i, a.key_size[k]) << a.key_shift[k];
+                    if (a.key_sext32) nkb[j] = (u64)(i64)(int)(u32)nkb[j];
                     nval[j] = load_bits(a.value, i, a.value_size);
                 }
             }
@@ -881,9 +885,11 @@ __global__ void __launch_bounds__(1024) group_place_kernel(const GroupScatter a)
 hipError_t launch_group_partition(const GroupScatter& g, int blocks, hipStream_t stream) {
     if (g.nbuckets < 1 || g.nbuckets > 256 || g.log_bucket < 0 || (1ll << g.log_bucket) > PLACE_MAX_BUCKET) return hipErrorInvalidValue;
     if (g.nkeys == 1 && g.key_size[0] == 8 && g.key_shift[0] == 0 && g.value_size == 8)
-        group_partition_kernel<true><<<dim3((unsigned)blocks), dim3(1024), 0, stream>>>(g);
+        group_partition_kernel<8><<<dim3((unsigned)blocks), dim3(1024), 0, stream>>>(g);
+    else if (g.nkeys == 1 && g.key_sext32 && g.key_size[0] == 4 && g.key_shift[0] == 0 && g.value_size == 8)
+        group_partition_kernel<4><<<dim3((unsigned)blocks), dim3(1024), 0, stream>>>(g);
     else
-        group_partition_kernel<false><<<dim3((unsigned)blocks), dim3(1024), 0, stream>>>(g);
+        group_partition_kernel<0><<<dim3((unsigned)blocks), dim3(1024), 0, stream>>>(g);
     return hipGetLastError();
 }
 hipError_t launch_group_place(const GroupScatter& g, int blocks, hipStream_t stream) {

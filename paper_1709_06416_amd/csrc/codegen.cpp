@@ -381,6 +381,11 @@ bool merges_in_memory(int backend) {
 
 }  // namespace
 
+bool value_fits32(const Loop& L, int op) {
+    if (op < 0 || (size_t)op >= L.ops.size() || L.ops[op].type == WELD_F64) return false;
+    return static_ranges(L)[op].fits32();
+}
+
 Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
     Variant var;
     int widest = 1;

@@ -293,6 +293,19 @@ Loop expand_groups(const Loop& in, std::vector<GroupLink>* links) {
             }
             return nb;
         };
+        // A 64-bit key that provably fits 32 bits (say a remainder by a constant) is written as its low half: the
+        // pairs' keys are scratch that is written once and read once, the result's keys come from the dictionary.
+        if (g.nkeys == 1 && g.key_type[0] == WELD_I64 && m >= 0 && value_fits32(in, in.merges[m].key[0])) {
+            weld_op_t c;
+            memset(&c, 0, sizeof c);
+            c.opcode = WELD_OP_CAST;
+            c.type = WELD_I32;
+            c.a = in.merges[m].key[0];
+            c.b = c.c = -1;
+            L.ops.push_back(c);
+            link.key_low_half = true;
+            link.key_vec[0] = add_vec(WELD_I32, (int)L.ops.size() - 1);
+        } else
         for (int k = 0; k < g.nkeys; ++k) link.key_vec[k] = add_vec(g.key_type[k], m >= 0 ? in.merges[m].key[k] : -1);
         link.val_vec = add_vec(g.val_type[0], m >= 0 ? in.merges[m].val[0] : -1);
         links->push_back(link);
@@ -799,6 +812,10 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             gs.key[k] = op[g->key_vec[k]].out;
             gs.key_size[k] = dl.key_size[k];
             gs.key_shift[k] = dl.key_shift[k];
+        }
+        if (g->key_low_half) {
+            gs.key_size[0] = 4;
+            gs.key_sext32 = 1;
         }
         gs.value = op[g->val_vec].out;
         gs.value_size = type_size(L.builders[g->val_vec].val_type[0]);

@@ -104,7 +104,11 @@ struct GroupLink {
     int dict = 0;                  // index of the counting dictmerger (= the groupbuilder's index)
     int key_vec[WELD_MAX_KEY_FIELDS] = {0};
     int val_vec = 0;
+    bool key_low_half = false;     // the one 64-bit key provably fits 32 bits: its vecbuilder holds the low halves
 };
+// Whether integer value `op` of the body provably lies in the 32-bit range (interval arithmetic over the body:
+// a remainder by a constant, a cast from a narrower type, a constant).
+bool value_fits32(const Loop& loop, int op);
 // Returns `loop` with every groupbuilder rewritten that way (links in builder order); a loop
 // without groupbuilders comes back unchanged.
 Loop expand_groups(const Loop& loop, std::vector<GroupLink>* links);

@@ -1412,6 +1412,28 @@ def test_groupbuilder_placement_paths(wb, capacity, vt):
     _check(wb, p, [_dev(keys), _dev(vals)], label="groups cap %d %s" % (capacity, vt))
 
 
+@pytest.mark.parametrize("capacity", [1_024, 40_000])
+@pytest.mark.parametrize("vt", ["i8", "i64"])
+def test_groupbuilder_keys_that_provably_fit_32_bits(wb, capacity, vt):
+    """A 64-bit key that the body bounds (a remainder by a constant, a cast from i32) travels to the placement
+    kernels as its low half: negative keys, -1 and both ends of the range must come back as themselves."""
+    rnd = np.random.RandomState(capacity % 97 + len(vt))
+    n = 170_003
+    x = rnd.randint(-2**40, 2**40, size=n).astype(np.int64)
+    x[:4] = [-499, 499, -1, 0]
+    y = rnd.randint(0, 700, size=n).astype(np.int64) * 6_000_011 - 2**31 + 5      # few distinct values over the whole 32-bit range
+    y[:4] = [-2**31, 2**31 - 1, -1, 0]
+    y = y.astype(np.int32)
+    vals = rnd.randint(-100, 100, size=n).astype(np.int8 if vt == "i8" else np.int64)
+    p = Program(["i64", "i32", vt])
+    p.merge(p.groupbuilder(["i64"], vt, capacity), p.col(2), keys=[p.bin("mod", p.col(0), p.const("i64", 500))])
+    _check(wb, p, [_dev(x), _dev(y), _dev(vals)], label="groups, remainder keys %d %s" % (capacity, vt))
+    q = Program(["i64", "i32", vt])
+    q.merge(q.groupbuilder(["i64"], vt, capacity), q.col(2), keys=[q.un("cast", q.col(1), to="i64")],
+            pred=q.bin("ne", q.col(0), q.const("i64", 7)))
+    _check(wb, q, [_dev(x), _dev(y), _dev(vals)], label="groups, cast keys %d %s" % (capacity, vt))
+
+
 def test_groupbuilder_offsets_over_more_rounds_than_work_groups(wb):
     """2.2e6 groups: the offsets are scanned 8192 groups a round by at most one work-group per compute
     unit, so here every work-group takes a second round and looks back at rounds of other work-groups."""
