@@ -92,7 +92,7 @@ struct GroupScatter {
     int log_bucket;
     int nbuckets;                          // <= 256
     unsigned long long* bcursor;           // one per bucket, zero on entry
-    unsigned int* tmp_group;               // group of each partitioned pair
+    unsigned short* tmp_group;             // group of each partitioned pair, counted from its range's first
     unsigned long long* tmp_value;         // its value (bits)
 };
 // desc: one zeroed 8-byte word per 8192 groups of the capacity; err: the call's error word; max_blocks: work-groups resident at once

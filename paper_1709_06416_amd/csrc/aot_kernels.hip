@@ -765,7 +765,7 @@ __global__ void __launch_bounds__(1024) group_partition_kernel(const GroupScatte
             const int b = (int)(g >> a.log_bucket);
             const i64 dst = s_cur[b] + (i64)(p - s_off[b]);
             if (dst < 0 || dst >= npairs) continue;     // only after a capacity error (sizes and pairs then disagree)
-            a.tmp_group[dst] = g;
+            a.tmp_group[dst] = (unsigned short)(g & (((u32)1 << a.log_bucket) - 1));      // (a range holds at most 4096 groups)
             a.tmp_value[dst] = s_sv[p];
         }
         __syncthreads();
@@ -836,7 +836,7 @@ __global__ void __launch_bounds__(1024) group_place_kernel(const GroupScatter a)
             const i64 i = start + j * 1024 + tid;
             ndead |= (i < stop ? 0u : 1u) << j;
             const i64 ic = i < stop ? i : stop - 1;        // (a chunk exists only where its range has pairs: start < stop)
-            ngrp[j] = __builtin_nontemporal_load(a.tmp_group + ic);
+            ngrp[j] = (u32)__builtin_nontemporal_load(a.tmp_group + ic);
             nval[j] = __builtin_nontemporal_load(a.tmp_value + ic);
         }
     };
@@ -847,7 +847,7 @@ __global__ void __launch_bounds__(1024) group_place_kernel(const GroupScatter a)
         u64 val[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            local[j] = (ndead >> j) & 1u ? ~0u : ngrp[j] - (u32)lo_g;
+            local[j] = (ndead >> j) & 1u ? ~0u : ngrp[j];
             val[j] = nval[j];
         }
         if (w + gridDim.x < total) load_chunk(w + gridDim.x);

@@ -522,6 +522,10 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
         for (size_t b = 0; b < L.builders.size(); ++b)
             if (var.backend[b] == BK_DICT_REG && L.builders[b].capacity * L.builders[b].nvals >= 24) reg_dict = true;
         var.u = tune.units_per_thread > 0 ? tune.units_per_thread : (var.v == 2 ? (reg_dict ? 2 : 4) : 2);
+        // rows that look a key up in a dictionary wait for two dependent reads of random lines: more wavefronts with
+        // fewer rows each hide that better than more loads per lane (the join's probe loop, 6e7 rows: 0.21 -> 0.19 ms when the
+        // table's lines are still in the memory-side cache from the probe before; right after the build 0.26 ms either way)
+        if (tune.units_per_thread <= 0 && (body_uses(L, WELD_OP_DICTLOOKUP) || body_uses(L, WELD_OP_KEYEXISTS))) var.u = 1;
         // ... and 2048-row tiles in 512-thread work-groups, one per compute unit, are 2 % faster for them than
         // 1024-row tiles in two 256-thread work-groups (C4: 1.14 -> 1.11 ms; the same eight wavefronts per unit)
         var.block = tune.block_threads > 0 ? tune.block_threads : (reg_dict ? 512 : 256);

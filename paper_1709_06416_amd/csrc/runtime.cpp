@@ -487,7 +487,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         }
     }
     // groupbuilders of many groups: the pairs are partitioned by ranges of 2^glog groups first (at
-    // most 256 ranges of at most 4096 groups), which takes 12 bytes of scratch per row - unless
+    // most 256 ranges of at most 4096 groups), which takes 10 bytes of scratch per row - unless
     // the memory limit has no room for that next to everything else the loop needs
     {
         size_t still_to_come = 0;
@@ -499,12 +499,12 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             int lg = 10;     // (1e5 groups: 98 ranges of 1024 give the partition longer runs to write than 196 of 512: 2.42 -> 2.34 ms)
             while (((int64_t)256 << lg) < s.capacity) ++lg;
             // (and 8 bytes per table slot for the words the partition step looks keys up in)
-            const size_t need = 12 * (size_t)n + 8 * (size_t)(off[b].slots + 1) + 256 * 8 + 1024;
+            const size_t need = 10 * (size_t)n + 8 * (size_t)(off[b].slots + 1) + 256 * 8 + 1024;
             if (mem_limit > 0 && (int64_t)(lay.total + need + still_to_come) > mem_limit) continue;
             off[b].glog = lg;
             off[b].kp32 = lay.take(8 * (size_t)(off[b].slots + 1));
             off[b].gbcursor = lay.take(256 * 8);
-            off[b].gtmp_group = lay.take(4 * (size_t)n);
+            off[b].gtmp_group = lay.take(2 * (size_t)n);
             off[b].gtmp_value = lay.take(8 * (size_t)n);
         }
     }
@@ -836,7 +836,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
             gs.log_bucket = off[b].glog;
             gs.nbuckets = (int)((s.capacity + ((int64_t)1 << off[b].glog) - 1) >> off[b].glog);
             gs.bcursor = (unsigned long long*)(base + off[b].gbcursor);
-            gs.tmp_group = (unsigned int*)(base + off[b].gtmp_group);
+            gs.tmp_group = (unsigned short*)(base + off[b].gtmp_group);
             gs.tmp_value = (unsigned long long*)(base + off[b].gtmp_value);
             if ((h = launch_group_partition(gs, (int)gblocks, stream)) != hipSuccess) return hip_err("group partition", h);
             if ((h = launch_group_place(gs, 2 * device_info().cus, stream)) != hipSuccess) return hip_err("group place", h);

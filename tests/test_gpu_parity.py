@@ -1448,7 +1448,7 @@ def test_groupbuilder_offsets_over_more_rounds_than_work_groups(wb):
 
 
 def test_groupbuilder_without_room_for_the_partition_scratch(wb):
-    """Under a memory limit that leaves no room for 12 bytes of scratch per row the one-kernel
+    """Under a memory limit that leaves no room for 10 bytes of scratch per row the one-kernel
     placement is used; the result is the same."""
     cols = configs.make_columns("C5", 300_007, device="cuda")
     prog = _group_on_c5()
