@@ -732,22 +732,30 @@ __device__ __forceinline__ u32 w_hash_slot32(u32 k, u32 slots) {
 __device__ __forceinline__ u64 w_compact_entry(u64 kbits, i64 v) {
     return (u64)(u32)kbits | ((u64)(u32)v << 32);
 }
+// The slots of the probe sequence (at most four) are read side by side, one LDS round trip instead of one per step;
+// what was read may be out of date by the time it is looked at, which only matters for a slot read as free, and that
+// one is taken by compare-and-swap, which tells (a slot once occupied keeps its key: nothing is ever deleted).
 __device__ __forceinline__ int w_lds_slot32(u32* keys, int slots, u64 kbits, int max_probe) {
     const u32 k = (u32)kbits;
     if (k == W_EMPTY_KEY32) return -1;
     const int mask = slots - 1;
-    int s = (int)w_hash_slot32(k, (u32)slots);
-    for (int probe = 0; probe < max_probe; ++probe) {
-        u32 cur = __hip_atomic_load(keys + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        if (cur == k) return s;
-        if (cur == W_EMPTY_KEY32) {
+    const int s0 = (int)w_hash_slot32(k, (u32)slots);
+    u32 cur[4];
+#pragma unroll
+    for (int probe = 0; probe < 4; ++probe)
+        cur[probe] = __hip_atomic_load(keys + ((s0 + (probe < max_probe ? probe : 0)) & mask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+#pragma unroll
+    for (int probe = 0; probe < 4; ++probe) {
+        if (probe >= max_probe) break;
+        const int s = (s0 + probe) & mask;
+        if (cur[probe] == k) return s;
+        if (cur[probe] == W_EMPTY_KEY32) {
             u32 expect = W_EMPTY_KEY32;
             if (__hip_atomic_compare_exchange_strong(keys + s, &expect, k, __ATOMIC_RELAXED,
                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP))
                 return s;
             if (expect == k) return s;
         }
-        s = (s + 1) & mask;
     }
     return -1;
 }
