@@ -227,7 +227,8 @@ def main():
 
     # ---- vecmerger strategies on the count-occurrences program (1e8 32-bit keys, uniform)
     # (Sec. 7.7 of the paper: local / shared / global copies over the size of the vector; here also LDS copies of
-    # 8192-cell ranges.  The default line carries four sizes, --vecmerger-sweep all ten.)
+    # 8192-cell ranges, and merges queued by range of cells for a second kernel.  The default line carries four
+    # sizes, --vecmerger-sweep all ten.)
     sweep = None
     if not args.no_nested or args.vecmerger_sweep:
         from workloads import rng
@@ -237,8 +238,8 @@ def main():
         sizes = (8, 64, 1024, 8192, 32768, 65536, 1 << 18, 1 << 19, 1 << 20, 1 << 24) if args.vecmerger_sweep else (8, 8192, 65536, 1 << 20)
         for m in sizes:
             keys = rng.uniform_int(6, 0, 0, nk, 0, m - 1, "cuda").to(torch.int32)
-            for strat, label in ((1, "local"), (2, "shared"), (4, "shared by range"), (3, "global")):
-                if (strat == 1 and m > 8) or (strat == 2 and m > 16384) or (strat == 4 and not 8192 < m <= 8192 * 64):
+            for strat, label in ((1, "local"), (2, "shared"), (4, "shared by range"), (5, "queued by range"), (3, "global")):
+                if (strat == 1 and m > 8) or (strat == 2 and m > 16384) or (strat == 4 and not 8192 < m <= 8192 * 64) or (strat == 5 and m <= 8192):
                     continue
                 if strat == 3 and m < 8192 and not args.vecmerger_sweep:
                     continue            # 13-390 ms a run: same-address device atomics, in the long sweep only

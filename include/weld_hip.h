@@ -175,7 +175,12 @@ typedef struct {
                                 fails with WELD_ERR_DEVICE (the wait is always bounded)  */
     int32_t vecmerger_strategy; /* 0 auto, 1 per-lane register copies (length <= 8), 2 work-group
                                    copy in LDS updated with LDS atomics, 3 global atomics only,
-                                   4 LDS copies of 8192-cell ranges, each range scanning all rows */
+                                   4 LDS copies of 8192-cell ranges, each range scanning all rows,
+                                   5 merges queued by range of cells in device memory (workspace: 4 bytes
+                                   per row where the merged value is a constant, else 16) and merged range by
+                                   range in LDS by a second kernel (lengths from 8193 to 2^26; one vecmerger
+                                   per loop, the others then use 3; a segment that is full sends its merges
+                                   to the result with device atomics), -1 = auto without 5 */
     int32_t lds_filter_words;   /* admission filter in front of an LDS hash table that is smaller than
                                    the key set: 32-bit words of its bitmap (power of two); -1 = none */
     int32_t dict_spill;         /* merges that miss such an LDS table: -1 = device atomics on the global

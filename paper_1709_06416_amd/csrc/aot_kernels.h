@@ -103,6 +103,28 @@ hipError_t launch_group_scatter(const GroupScatter& g, int blocks, hipStream_t s
 // then place every range's pairs (both read g.ngroups and the offsets on the device).
 hipError_t launch_group_partition(const GroupScatter& g, int blocks, hipStream_t stream);
 hipError_t launch_group_place(const GroupScatter& g, int blocks, hipStream_t stream);
+// A vecmerger whose merges the loop kernel queued by range of 2^shift cells (spill_kernels.hip): work-group g of the
+// loop kernel appended to segment [g][range] of `log` (cap entries of entry_bytes: 4 = the cell within its range, the
+// merged value being the constant const_bits; 16 = cell within the range, value bits) and stored the segment lengths
+// in qcnt[g * ranges + range].  One work-group per range merges the range's entries in LDS and combines the cells
+// that were touched into out[range << shift ...] (it owns them: plain loads and stores).
+struct VecmRanges {
+    const void* log;
+    const unsigned int* qcnt;
+    int groups;
+    int ranges;
+    int shift;                 // <= 13
+    long long cap;
+    long long length;
+    int func;                  // weld_func_t
+    int is_f64;
+    unsigned long long ident;
+    int entry_bytes;
+    unsigned long long const_bits;
+    unsigned long long* out;
+};
+hipError_t launch_vecm_ranges(const VecmRanges& v, hipStream_t stream, hipEvent_t stop = nullptr);
+
 // Aggregation of the key-partitioned spill queues of a large dictmerger (spill_kernels.hip).
 // The loop kernel's work-group g appends to segment [g][partition] of `log` (cap entries of
 // 1 + nvals 8-byte words each) and stores the segment lengths in qcnt[g * kSpillParts + partition].

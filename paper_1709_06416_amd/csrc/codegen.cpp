@@ -376,7 +376,8 @@ std::string pack_key(const weld_builder_spec_t& s, size_t b, const char* row) {
 
 // builders whose merges go to memory at a computed address (as opposed to register accumulators)
 bool merges_in_memory(int backend) {
-    return backend == BK_DICT_LDS || backend == BK_DICT_GLOBAL || backend == BK_VECM_LDS || backend == BK_VECM_GLOBAL;
+    return backend == BK_DICT_LDS || backend == BK_DICT_GLOBAL || backend == BK_VECM_LDS || backend == BK_VECM_GLOBAL ||
+           backend == BK_VECM_QUEUE;
 }
 
 }  // namespace
@@ -406,6 +407,8 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
         } else if (s.kind == WELD_VECMERGER) {
             // Sec. 7.7: thread-local copies, work-group copies with atomics, one global copy
             int strat = tune.vecmerger_strategy;
+            const bool queues_allowed = strat >= 0;        // (-1: the library's choice among the strategies without workspace)
+            if (strat < 0) strat = 0;
             if (strat == 1 && s.length > 8) strat = 0;
             if (strat == 2 && s.length > 16384) strat = 0;
             // measured with 1e8 uniform keys: LDS copy 0.09-0.12 ms up to 8192 cells; register copies
@@ -418,10 +421,25 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
             // builder is this vecmerger: everything else would be repeated R times too.
             const bool alone = L.builders.size() == 1;
             if (strat == 4 && (!alone || s.length > 8192 * 64)) strat = 0;
+            // Beyond that a fifth: every merge is appended to a queue by range of cells (segment [work-group][range],
+            // 4 bytes an entry where the merged value is a constant, else 16), and a second kernel merges each
+            // range in LDS and adds it to the result - two streaming passes instead of one device atomic per row.
+            // One such vecmerger per loop; up to 8192 ranges of 8192 cells.
+            const bool can_queue = queues_allowed && var.vq_builder < 0 && m >= 0 && s.length > 8192 && s.length <= (int64_t)8192 * 8192 && tune.dict_spill >= 0;
+            if (strat == 5 && !can_queue) strat = 0;
             if (strat == 0) strat = (s.length <= 8 && s.val_type[0] == WELD_F64) ? 1
-                                  : s.length <= 8192 ? 2 : (alone && s.length <= 8192 * 36) ? 4 : 3;
-            var.backend[b] = strat == 1 ? BK_VECM_REG : (strat == 2 || strat == 4) ? BK_VECM_LDS : BK_VECM_GLOBAL;
+                                  : s.length <= 8192 ? 2 : (alone && s.length <= 8192 * 4) ? 4 : can_queue ? 5 : 3;
+            var.backend[b] = strat == 1 ? BK_VECM_REG : (strat == 2 || strat == 4) ? BK_VECM_LDS : strat == 5 ? BK_VECM_QUEUE : BK_VECM_GLOBAL;
             if (strat == 4) var.ranges = (int)((s.length + 8191) / 8192);
+            if (strat == 5) {
+                var.vq_builder = (int)b;
+                var.vq_shift = 8;
+                // (1e8 uniform keys, 2^20 cells: 0.58 ms with 128 ranges, 0.62 with 256, 0.75 with 512, 0.92 with 1024 - every range is
+                // one more line a work-group keeps open for its 4-byte stores)
+                while (var.vq_shift < 13 && ((s.length + ((int64_t)1 << var.vq_shift) - 1) >> var.vq_shift) > 128) ++var.vq_shift;
+                var.vq_ranges = (int)((s.length + ((int64_t)1 << var.vq_shift) - 1) >> var.vq_shift);
+                var.vq_const = L.ops[L.merges[m].val[0]].opcode == WELD_OP_CONST;
+            }
         } else {
             int strat = tune.dict_strategy;
             const bool few = s.capacity <= 8 && key_bits(s) < 64;
@@ -507,7 +525,7 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
     // Look-back kernels pay one same-address device atomic (about 12 ns, serialised) and
     // three barriers per tile: they take large tiles (8192 rows).  Other kernels keep
     // 8 KiB (4 KiB for V=4) of loads in flight per wavefront and column.
-    if (big_dict) {
+    if (big_dict || var.vq_builder >= 0) {
         var.u = tune.units_per_thread > 0 ? tune.units_per_thread : 16 / var.v;
         var.block = tune.block_threads > 0 ? tune.block_threads : 1024;
     } else if (var.ticketed) {
@@ -697,6 +715,12 @@ Generated generate(const Loop& L, const Variant& var) {
             case BK_VECM_REG: case BK_VECM_LDS: case BK_VECM_GLOBAL:
                 slot(SLOT_OUT, (int)b, 0, B + "_out", std::string(acc_ctype(s.val_type[0])) + "*");
                 break;
+            case BK_VECM_QUEUE:
+                slot(SLOT_OUT, (int)b, 0, B + "_out", std::string(acc_ctype(s.val_type[0])) + "*");
+                slot(SLOT_DLOG, (int)b, 0, B + "_log", "u64*");
+                slot(SLOT_DQCNT, (int)b, 0, B + "_qcnt", "u32*");
+                slot(SLOT_DQCAP, (int)b, 0, B + "_qcap", "i64");
+                break;
             default:
                 slot(SLOT_DKEYS, (int)b, 0, B + "_keys", "u64*");
                 slot(SLOT_DHDR, (int)b, 0, B + "_hdr", "u32*");
@@ -823,6 +847,22 @@ Generated generate(const Loop& L, const Variant& var) {
                 o.f("    } \\\n");
             }
             o.f("  } \\\n");
+        } else if (var.backend[b] == BK_VECM_QUEUE) {
+            // a full segment (skewed indices, or a memory limit that left the queues short) sends the merge to the
+            // result with a device atomic, as the global strategy does with every merge
+            const char* A = acc_ctype(s.val_type[0]);
+            o.f("  if ((o).p%zu) { \\\n    const i64 ix = (o).k%zu_0; \\\n", b, b);
+            o.f("    if ((u64)ix < (u64)%lldll) { \\\n", (long long)s.length);
+            o.f("      const u32 part = (u32)((u64)ix >> %d); \\\n", var.vq_shift);
+            o.f("      const u32 pos = __hip_atomic_fetch_add(v%zu_qn + part, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); \\\n", b);
+            o.f("      if ((i64)pos < a.b%zu_qcap) { \\\n", b);
+            o.f("        const u64 at = ((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap + pos; \\\n", var.vq_ranges, b);
+            if (var.vq_const)
+                o.f("        w_gstore_u32((u32*)a.b%zu_log + at, (u32)ix & %du); \\\n", b, (1u << var.vq_shift) - 1);
+            else
+                o.f("        w_gstore2(a.b%zu_log + 2 * at, (u64)((u32)ix & %du), w_bits((%s)(o).v%zu_0)); \\\n", b, (1u << var.vq_shift) - 1, A, b);
+            o.f("      } else w_atomic<%d>(a.b%zu_out + ix, (%s)(o).v%zu_0, 1); \\\n", F, b, A, b);
+            o.f("    } else atomicOr(errp, 4); \\\n  } \\\n");
         } else if (var.backend[b] == BK_VECM_REG || var.backend[b] == BK_VECM_LDS || var.backend[b] == BK_VECM_GLOBAL) {
             const char* A = acc_ctype(s.val_type[0]);
             o.f("  if ((o).p%zu) { \\\n    const i64 ix = (o).k%zu_0; \\\n", b, b);
@@ -966,6 +1006,11 @@ Generated generate(const Loop& L, const Variant& var) {
         } else if (var.backend[b] == BK_VECM_REG) {
             o.f("  %s v%zu_a[%d];\n", acc_ctype(s.val_type[0]), b, (int)s.length);
             o.f("  _Pragma(\"unroll\") for (int q = 0; q < %d; ++q) v%zu_a[q] = %s;\n", (int)s.length, b, ident_expr(s.func, s.val_type[0]).c_str());
+        } else if (var.backend[b] == BK_VECM_QUEUE) {
+            o.f("  __shared__ u32 v%zu_qn[%d];\n", b, var.vq_ranges);
+            lds += 4 * var.vq_ranges;
+            o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) v%zu_qn[q] = 0;\n", var.vq_ranges, b);
+            need_sync = true;
         } else if (var.backend[b] == BK_VECM_LDS) {
             const int cells = var.ranges > 1 ? 8192 : (int)s.length;
             o.f("  __shared__ %s v%zu_l[%d];\n", acc_ctype(s.val_type[0]), b, cells);
@@ -1423,6 +1468,9 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("  _Pragma(\"unroll\") for (int q = 0; q < %d; ++q) {\n", (int)s.length);
             o.f("    const %s r = w_block_reduce<%d>(v%zu_a[q], (%s*)s_red, %s);\n", A, s.func, b, A, ident_expr(s.func, s.val_type[0]).c_str());
             o.f("    if (threadIdx.x == 0) w_atomic<%d>(a.b%zu_out + q, r, 1);\n  }\n", s.func, b);
+        } else if (var.backend[b] == BK_VECM_QUEUE) {
+            o.f("  __syncthreads();\n  for (int q = threadIdx.x; q < %d; q += W_BLOCK)\n", var.vq_ranges);
+            o.f("    a.b%zu_qcnt[(u64)blockIdx.x * %du + q] = (i64)v%zu_qn[q] < a.b%zu_qcap ? v%zu_qn[q] : (u32)a.b%zu_qcap;\n", b, var.vq_ranges, b, b, b, b);
         } else if (var.backend[b] == BK_VECM_LDS) {
             // cells this work-group never touched still hold the identity: nothing to send
             const char* A = acc_ctype(s.val_type[0]);

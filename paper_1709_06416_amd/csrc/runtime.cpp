@@ -426,6 +426,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     if (grid > ntiles) grid = ntiles;
     if (grid < 1) grid = 1;
     if (var.spill && grid > 1024) grid = 1024;   // the queue aggregation scans one segment per work-group and thread
+    if (var.vq_builder >= 0 && grid > 2 * (int64_t)device_info().cus) grid = 2 * (int64_t)device_info().cus;   // (segments: grid x ranges)
     if (var.ranges > 1) {   // range-partitioned vecmerger: the same number of work-groups for every range
         grid = grid / var.ranges * var.ranges;
         if (grid < var.ranges) grid = var.ranges;
@@ -462,7 +463,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
                 off[b].out = take_out((size_t)n * type_size(s.val_type[0]));
                 off[b].desc = lay.take(8 * (size_t)ntiles);
                 break;
-            case BK_VECM_REG: case BK_VECM_LDS: case BK_VECM_GLOBAL:
+            case BK_VECM_REG: case BK_VECM_LDS: case BK_VECM_GLOBAL: case BK_VECM_QUEUE:
                 off[b].out = take_out(8 * (size_t)s.length);
                 break;
             default: {
@@ -534,6 +535,26 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         if (mem_limit > 0) {
             const int64_t room = mem_limit - (int64_t)lay.total;
             const int64_t fit = room > 0 ? (room - 256) / (int64_t)seg : 0;
+            if (cap > fit) cap = fit > 0 ? fit : 0;
+        }
+        off[b].qcap = cap;
+        off[b].log = lay.take(seg * (size_t)cap);
+    }
+    // queues of a vecmerger whose merges are queued by range of cells: every row of a work-group may merge, spread
+    // over the ranges by its indices (uniform ones: six standard deviations above the mean); a full segment only
+    // sends its merges to the result with device atomics, so a memory limit may shrink them too
+    if (var.vq_builder >= 0) {
+        const size_t b = (size_t)var.vq_builder;
+        const size_t entry = var.vq_const ? 4 : 16;
+        off[b].qcnt = lay.take(4 * (size_t)grid * var.vq_ranges);
+        const double rows = (double)((ntiles + grid - 1) / grid) * (double)tile;
+        const double mean = rows / var.vq_ranges;
+        int64_t cap = (int64_t)(mean + 6.0 * std::sqrt(mean) + 16.0);
+        cap = (cap + 3) / 4 * 4;                        // (segments of 4-byte entries begin at 16-byte addresses)
+        const size_t seg = (size_t)grid * var.vq_ranges * entry;
+        if (mem_limit > 0) {
+            const int64_t room = mem_limit - (int64_t)lay.total;
+            const int64_t fit = room > 0 ? (room - 256) / (int64_t)seg / 4 * 4 : 0;
             if (cap > fit) cap = fit > 0 ? fit : 0;
         }
         off[b].qcap = cap;
@@ -661,6 +682,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         if (L.builders[b].kind == WELD_VECMERGER && L.builders[b].init) copies_first = true;
         if (var.backend[b] == BK_DICT_LDS && var.spill) ++spill_left;
     }
+    if (var.vq_builder >= 0) ++spill_left;        // (the kernel that merges the vecmerger's queues: the last of them is timed)
     hipEvent_t start_pending = timed && !lone && !copies_first ? r->ev0 : nullptr;
     if (timed && !lone && copies_first && (h = hipEventRecord(r->ev0, stream)) != hipSuccess) return hip_err("hipEventRecord", h);
     // the workspace of the call is cleared by ONE kernel (a dictionary alone has a key column
@@ -763,6 +785,32 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         }
         --spill_left;
         if (h != hipSuccess) return hip_err("dict spill merge", h);
+        r->kernel_count++;
+    }
+    if (var.vq_builder >= 0) {
+        const size_t b = (size_t)var.vq_builder;
+        const weld_builder_spec_t& s = L.builders[b];
+        VecmRanges vr;
+        memset(&vr, 0, sizeof vr);
+        vr.log = base + off[b].log;
+        vr.qcnt = (const unsigned int*)(base + off[b].qcnt);
+        vr.groups = (int)grid;
+        vr.ranges = var.vq_ranges;
+        vr.shift = var.vq_shift;
+        vr.cap = off[b].qcap;
+        vr.length = s.length;
+        vr.func = s.func;
+        vr.is_f64 = s.val_type[0] == WELD_F64;
+        vr.ident = ident_bits(s.func, s.val_type[0]);
+        vr.entry_bytes = var.vq_const ? 4 : 16;
+        if (var.vq_const) {
+            const weld_op_t& c = L.ops[L.merges[L.merge_of[b]].val[0]];
+            if (s.val_type[0] == WELD_F64) memcpy(&vr.const_bits, &c.imm.f64, 8);
+            else vr.const_bits = (unsigned long long)c.imm.i64;
+        }
+        vr.out = (unsigned long long*)op[b].out;
+        if ((h = launch_vecm_ranges(vr, stream, timed && spill_left == 1 ? r->ev3 : nullptr)) != hipSuccess) return hip_err("vecmerger ranges", h);
+        --spill_left;
         r->kernel_count++;
     }
     MergerFinish mf;

@@ -611,6 +611,97 @@ static hipError_t launch_nv(const SpillMerge& in, hipStream_t stream, hipEvent_t
     }
 }
 
+// ---------------------------------------------------------------- queued vecmerger
+// One work-group per range of cells.  The range's cells start at the identity in LDS; a wavefront takes the range's
+// segment of one loop work-group at a time (lanes read neighbouring entries) and merges with LDS atomics; at the
+// end every cell that left the identity is combined into the result, which the work-group owns for its range.
+template <int FUNC, int ENTRY>
+__global__ void __launch_bounds__(1024) vecm_ranges_kernel(const VecmRanges a) {
+    __shared__ u64 s_cell[8192];
+    __shared__ u32 s_len[2048];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = blockIdx.x;
+    const int cells = 1 << a.shift;
+    for (int q = tid; q < cells; q += 1024) s_cell[q] = a.ident;
+    // the lengths of the range's segments, read side by side (one memory round trip for all of them)
+    for (int g = tid; g < a.groups; g += 1024) s_len[g] = a.qcnt[(i64)g * a.ranges + r];
+    __syncthreads();
+    for (int g = wave; g < a.groups; g += 16) {
+        const i64 len = (i64)s_len[g] < a.cap ? (i64)s_len[g] : a.cap;
+        const i64 seg = ((i64)g * a.ranges + r) * a.cap;
+        // eight loads of a lane in flight (no branch around a load: an entry past the end re-reads the last one)
+        if (ENTRY == 4) {
+            const u32* e = (const u32*)a.log + seg;
+            for (i64 i0 = 0; i0 < len; i0 += 512) {
+                u32 c[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const i64 i = i0 + k * 64 + lane;
+                    c[k] = __builtin_nontemporal_load(e + (i < len ? i : len - 1));
+                }
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (i0 + k * 64 + lane < len && c[k] < (u32)cells) cell_combine<FUNC>(s_cell + c[k], a.const_bits, a.is_f64, 0);
+            }
+        } else {
+            const u64* e = (const u64*)a.log + 2 * seg;
+            for (i64 i0 = 0; i0 < len; i0 += 512) {
+                u64 c[8], v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const i64 i = i0 + k * 64 + lane;
+                    const i64 ic = i < len ? i : len - 1;
+                    c[k] = __builtin_nontemporal_load(e + 2 * ic);
+                    v[k] = __builtin_nontemporal_load(e + 2 * ic + 1);
+                }
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (i0 + k * 64 + lane < len && c[k] < (u64)cells) cell_combine<FUNC>(s_cell + c[k], v[k], a.is_f64, 0);
+            }
+        }
+    }
+    __syncthreads();
+    const i64 first = (i64)r << a.shift;
+    for (int q = tid; q < cells; q += 1024) {
+        const u64 x = s_cell[q];
+        if (x == a.ident || first + q >= a.length) continue;
+        u64* p = a.out + first + q;
+        if (a.is_f64) {
+            double cur, add;
+            const u64 cb = *p;
+            __builtin_memcpy(&cur, &cb, 8);
+            __builtin_memcpy(&add, &x, 8);
+            const double res = w_combine<FUNC>(cur, add);
+            u64 rb;
+            __builtin_memcpy(&rb, &res, 8);
+            *p = rb;
+        } else {
+            *p = (u64)w_combine<FUNC>((i64)*p, (i64)x);
+        }
+    }
+}
+
+template <int FUNC>
+static hipError_t launch_vecm_func(const VecmRanges& v, hipStream_t stream, hipEvent_t stop) {
+    if (v.entry_bytes == 4)
+        hipExtLaunchKernelGGL((vecm_ranges_kernel<FUNC, 4>), dim3((unsigned)v.ranges), dim3(1024), 0, stream, nullptr, stop, 0, v);
+    else
+        hipExtLaunchKernelGGL((vecm_ranges_kernel<FUNC, 16>), dim3((unsigned)v.ranges), dim3(1024), 0, stream, nullptr, stop, 0, v);
+    return hipGetLastError();
+}
+hipError_t launch_vecm_ranges(const VecmRanges& v, hipStream_t stream, hipEvent_t stop) {
+    if (v.ranges < 1 || v.shift < 0 || v.shift > 13 || v.groups < 1 || v.groups > 2048 || v.cap < 0 ||
+        (v.entry_bytes != 4 && v.entry_bytes != 16) || ((long long)v.ranges << v.shift) < v.length)
+        return hipErrorInvalidValue;
+    switch (v.func) {
+        case 0: return launch_vecm_func<0>(v, stream, stop);
+        case 1: return launch_vecm_func<1>(v, stream, stop);
+        case 2: return launch_vecm_func<2>(v, stream, stop);
+        case 3: return launch_vecm_func<3>(v, stream, stop);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 hipError_t launch_dict_spill_merge(const SpillMerge& a, int nvals, hipStream_t stream, hipEvent_t stop) {
     switch (nvals) {
         case 1: return launch_nv<1>(a, stream, stop);

@@ -146,7 +146,8 @@ enum Backend {
     BK_DICT_LANE = 6,   // <= 8 groups: key list in LDS, per-lane accumulators in LDS ([slot][lane])
     BK_VECM_REG = 7,    // vecmerger, <= 8 cells: per-lane register copies ("local")
     BK_VECM_LDS = 8,    // vecmerger: work-group copy in LDS, LDS atomics ("shared")
-    BK_VECM_GLOBAL = 9  // vecmerger: one global copy, device atomics ("global")
+    BK_VECM_GLOBAL = 9, // vecmerger: one global copy, device atomics ("global")
+    BK_VECM_QUEUE = 10  // vecmerger: merges appended to queues by range of cells, a second kernel merges a range in LDS
 };
 
 // Compile-time shape of one fused kernel.  Two loops with equal Variant and equal
@@ -188,6 +189,10 @@ struct Variant {
     int pipeline = 0;          // ticketed loops: 1 = the next tile's columns are loaded while this tile is merged and stored
     bool single = false;        // mergers only: the last work-group to finish combines the partials and writes results and
                                 // status (no fill kernel before the loop kernel, no combining kernel behind it)
+    int vq_builder = -1;        // vecmerger whose merges are queued by range of 2^vq_shift cells (vq_ranges ranges): segment
+    int vq_shift = 13;          // [work-group][range] of a log in global memory, entries of 4 bytes (the cell within its
+    int vq_ranges = 0;          // range; vq_const: the merged value is a constant the second kernel is told) or 16 bytes
+    bool vq_const = false;      // (cell within the range, value bits)
     std::vector<int> backend;   // per builder
 };
 

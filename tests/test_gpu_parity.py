@@ -926,7 +926,7 @@ def _count_program(length, t="i64", func="add"):
     return p
 
 
-@pytest.mark.parametrize("strategy", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("strategy", [-1, 0, 1, 2, 3, 4, 5])
 @pytest.mark.parametrize("length", [1, 5, 8, 9, 1000, 8192, 8193, 20_000, 300_000])
 def test_vecmerger_counts_occurrences(wb, length, strategy):
     rnd = np.random.RandomState(length)
@@ -973,6 +973,60 @@ def test_vecmerger_index_out_of_range_is_reported(wb):
     for strategy in (1, 2, 3):
         res = _run(wb, _count_program(8), [_dev(keys)], tune={"vecmerger_strategy": strategy})
         assert res.status() == wb.ERR_INVALID_ARG
+        res.free()
+    keys = np.array([0, 1, 2, 70_000, -1, 3], dtype=np.int32)
+    res = _run(wb, _count_program(20_000), [_dev(keys)], tune={"vecmerger_strategy": 5})
+    assert res.status() == wb.ERR_INVALID_ARG
+    res.free()
+
+
+@pytest.mark.parametrize("func", ["add", "mul", "min", "max"])
+@pytest.mark.parametrize("t", ["i64", "f64"])
+def test_vecmerger_queued_by_range_of_cells(wb, func, t):
+    """Vectors beyond what one LDS copy holds: the merges are queued by range of cells and a second kernel merges
+    every range in LDS.  Values from a column (16-byte entries) and constants (4-byte entries), an initial
+    vector, a predicate, a second builder beside it, lengths that end inside a range and inside a tile of ranges,
+    and indices so skewed that segments fill up and the rest of their merges goes to the result directly."""
+    rnd = np.random.RandomState(len(func) + len(t))
+    n = 400_009
+    for m in (8193, 70_001, 2_100_000):
+        idx = rnd.randint(0, m, size=n).astype(np.int64)
+        idx[: n // 3] = idx[0]                                       # one cell takes a third of the merges
+        idx[n // 3: n // 2] = m - 1                                   # the last cell
+        if t == "f64":
+            v = rnd.choice([0.5, 1.0, 2.0, 1.0], size=n) if func == "mul" else rnd.randint(-50, 50, size=n).astype(np.float64)
+            init = rnd.randint(-5, 5, size=m).astype(np.float64)
+        else:
+            v = rnd.choice([1, -1, 1, 1], size=n).astype(np.int64) if func == "mul" else rnd.randint(-50, 50, size=n).astype(np.int64)
+            init = rnd.randint(-5, 5, size=m).astype(np.int64)
+        p = Program(["i64", t])
+        pred = p.bin("ne", p.col(0), p.const("i64", 13))             # cell 13 keeps its initial value
+        p.merge(p.vecmerger(t, func, m), [p.col(1)], keys=[p.col(0)], pred=pred)
+        p.merge(p.merger("i64", "add"), p.const("i64", 1), pred=pred)
+        inits = {0: _dev(init)}
+        _check(wb, p, [_dev(idx), _dev(v)], label="queued vecmerger %s %s %d" % (func, t, m), inits=inits,
+               tune={"vecmerger_strategy": 5})
+        res = _run(wb, p, [_dev(idx), _dev(v)], inits=inits, tune={"vecmerger_strategy": 5}).check()
+        assert res.vec_host(0)[13] == init[13]
+        res.free()
+        c = Program(["i64", t])
+        two = c.const(t, 2) if t == "i64" else c.const(t, -1.0 if func == "mul" else 2.0)    # (a product of 1e5 twos is inf)
+        c.merge(c.vecmerger(t, func, m), [two], keys=[c.col(0)])
+        _check(wb, c, [_dev(idx), _dev(v)], label="queued vecmerger of a constant %s %s %d" % (func, t, m),
+               tune={"vecmerger_strategy": 5})
+
+
+def test_vecmerger_queues_under_a_memory_limit(wb):
+    """A memory limit shrinks the queues' segments (down to nothing): the merges that find no room go to the result
+    with device atomics; the counts are the same."""
+    rnd = np.random.RandomState(5)
+    n, m = 600_011, 100_000
+    keys = rnd.randint(0, m, size=n).astype(np.int32)
+    p = _count_program(m)
+    want = np.bincount(keys, minlength=m)
+    for limit in (0, 4_000_000, 1_000_000):          # room for every entry, for about half of them, for none
+        res = wb.fused_for(p, [_dev(keys)], tune={"vecmerger_strategy": 5}, memory_limit=limit).check()
+        assert np.array_equal(res.vec_host(0), want), limit
         res.free()
 
 
