@@ -156,6 +156,22 @@ def test_static_call_with_global_dictionary_and_vecmerger(wb):
     _two_calls(wb, p, cols, (n, 30_011), inits={1: init}, label="lds dict")
 
 
+def test_static_call_with_a_vecmerger_queued_by_range(wb):
+    # a vecmerger beyond one LDS copy: its queues lie in the fixed workspace (segments of the larger call's grid are
+    # left behind for the smaller one), with a value column and with a constant
+    n = 500_009
+    g = torch.Generator(device="cpu").manual_seed(12)
+    cols = [torch.randint(0, 60_000, (n,), generator=g, dtype=torch.int64).cuda(),
+            torch.randint(-9, 9, (n,), generator=g, dtype=torch.int64).cuda()]
+    init = torch.arange(60_000, dtype=torch.int64, device="cuda")
+    p = Program(["i64", "i64"])
+    p.merge(p.vecmerger("i64", "add", 60_000), [p.col(1)], keys=[p.col(0)], pred=p.bin("ne", p.col(1), p.const("i64", 3)))
+    _two_calls(wb, p, cols, (n, 40_013), inits={0: init}, label="queued vecmerger, values")
+    c = Program(["i64", "i64"])
+    c.merge(c.vecmerger("i64", "max", 60_000), [c.const("i64", 7)], keys=[c.col(0)])
+    _two_calls(wb, c, cols, (n, 40_013), inits={0: init}, label="queued vecmerger, constant")
+
+
 def test_static_call_refuses_what_it_cannot_do(wb):
     status = torch.zeros(1 + wb.MAX_BUILDERS, dtype=torch.int64, device="cuda")
     # a loop that never ran through the ordinary entry point has no loaded kernel
