@@ -426,19 +426,23 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
             // range in LDS and adds it to the result - two streaming passes instead of one device atomic per row.
             // One such vecmerger per loop; up to 8192 ranges of 8192 cells.
             const bool can_queue = queues_allowed && var.vq_builder < 0 && m >= 0 && s.length > 8192 && s.length <= (int64_t)8192 * 8192 && tune.dict_spill >= 0;
+            bool unsorted = false;                 // (6: 5 without sorting a tile's entries in LDS)
+            if (strat == 6) { strat = 5; unsorted = true; }
             if (strat == 5 && !can_queue) strat = 0;
             if (strat == 0) strat = (s.length <= 8 && s.val_type[0] == WELD_F64) ? 1
-                                  : s.length <= 8192 ? 2 : (alone && s.length <= 8192 * 4) ? 4 : can_queue ? 5 : 3;
+                                  : s.length <= 8192 ? 2 : (alone && s.length <= 8192 * 2) ? 4 : can_queue ? 5 : 3;
             var.backend[b] = strat == 1 ? BK_VECM_REG : (strat == 2 || strat == 4) ? BK_VECM_LDS : strat == 5 ? BK_VECM_QUEUE : BK_VECM_GLOBAL;
             if (strat == 4) var.ranges = (int)((s.length + 8191) / 8192);
             if (strat == 5) {
                 var.vq_builder = (int)b;
                 var.vq_shift = 8;
-                // (1e8 uniform keys, 2^20 cells: 0.58 ms with 128 ranges, 0.62 with 256, 0.75 with 512, 0.92 with 1024 - every range is
-                // one more line a work-group keeps open for its 4-byte stores)
-                while (var.vq_shift < 13 && ((s.length + ((int64_t)1 << var.vq_shift) - 1) >> var.vq_shift) > 128) ++var.vq_shift;
+                // (1e8 uniform keys, 2^20 cells, one 4-byte store per row: 0.58 ms with 128 ranges, 0.62 with 256, 0.75 with 512,
+                // 0.92 with 1024 - every range is one more line a work-group keeps open; with a tile's entries sorted in LDS
+                // first 0.35 ms with 128 ranges and 0.32 with 256, which put the second kernel on every compute unit)
+                while (var.vq_shift < 13 && ((s.length + ((int64_t)1 << var.vq_shift) - 1) >> var.vq_shift) > 256) ++var.vq_shift;
                 var.vq_ranges = (int)((s.length + ((int64_t)1 << var.vq_shift) - 1) >> var.vq_shift);
                 var.vq_const = L.ops[L.merges[m].val[0]].opcode == WELD_OP_CONST;
+                var.vq_sorted = !unsorted;         // (if the rest of the loop allows: decided below)
             }
         } else {
             int strat = tune.dict_strategy;
@@ -549,6 +553,11 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
         var.block = tune.block_threads > 0 ? tune.block_threads : (reg_dict ? 512 : 256);
     }
     if (var.u > 16) var.u = 16;
+    // (the sorted form of the queued vecmerger stages a tile's 4-byte entries in LDS: static tiles of at most 16384 rows)
+    var.vq_sorted = var.vq_sorted && var.vq_builder >= 0 && var.vq_const && var.vq_ranges <= 4096 && !var.ticketed && var.ranges == 1 &&
+                    (int64_t)var.block * var.v * var.u <= 16384;
+    for (size_t b = 0; b < L.builders.size(); ++b)      // (the staging array takes 64 KiB: not beside another builder's LDS state)
+        if (var.backend[b] == BK_DICT_LDS || var.backend[b] == BK_DICT_LANE || var.backend[b] == BK_VECM_LDS) var.vq_sorted = false;
     if (var.block < 64) var.block = 64;
     if (var.block > 1024) var.block = 1024;
     var.block = (var.block / 64) * 64;
@@ -561,7 +570,8 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
         for (size_t b = 0; b < L.builders.size(); ++b)
             if (var.backend[b] == BK_DICT_LDS) per_slot += var.compact == (int)b ? 8 : 8 * (1 + L.builders[b].nvals);
         int other = (var.ticketed ? 8 * var.block * var.v : 0) + 4 * var.door_words + (var.spill ? 4 * var.spill_parts : 0) +
-                    (body_uses(L, WELD_OP_ERF) ? 7680 : 0) + (body_uses(L, WELD_OP_LOG) ? 2184 : 0) + (body_uses(L, WELD_OP_EXP) ? 1024 : 0) + 2048;
+                    (body_uses(L, WELD_OP_ERF) ? 7680 : 0) + (body_uses(L, WELD_OP_LOG) ? 2184 : 0) + (body_uses(L, WELD_OP_EXP) ? 1024 : 0) + 2048 +
+                    (var.vq_builder >= 0 ? 4 * var.vq_ranges : 0);
         for (size_t b = 0; b < L.builders.size(); ++b) {
             if (var.backend[b] == BK_VECM_LDS) other += 8 * (var.ranges > 1 ? 8192 : (int)L.builders[b].length);
             if (var.backend[b] == BK_DICT_REG || var.backend[b] == BK_DICT_LANE) other += 8 * (int)L.builders[b].capacity;
@@ -812,14 +822,20 @@ Generated generate(const Loop& L, const Variant& var) {
         o.f("    } \\\n  } \\\n  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, \"wavefront\"); \\\n  dq_n = 0; \\\n} while (0)\n\n");
     }
 
-    // which: 0 = every builder, 1 = those held in registers, 2 = those held in memory
-    auto emit_merge_macro = [&](const char* name, int which) {
-    o.f("#define %s(o) do { \\\n", name);
+    // which: 0 = every builder, 1 = those held in registers, 2 = those held in memory; tile: the merge of the
+    // vecmerger whose tile entries are sorted in LDS only notes its index in `e` (0xffffffff: nothing to merge)
+    auto emit_merge_macro = [&](const char* name, int which, bool tile = false) {
+    o.f(tile ? "#define %s(o, e) do { \\\n" : "#define %s(o) do { \\\n", name);
     for (size_t b = 0; b < NB; ++b) {
         if (L.merge_of[b] < 0) continue;
         if (which == 1 && merges_in_memory(var.backend[b])) continue;
         if (which == 2 && !merges_in_memory(var.backend[b])) continue;
         const weld_builder_spec_t& s = L.builders[b];
+        if (tile && (int)b == var.vq_builder) {
+            o.f("  (e) = 0xffffffffu; \\\n  if ((o).p%zu) { \\\n    const i64 ix = (o).k%zu_0; \\\n", b, b);
+            o.f("    if ((u64)ix < (u64)%lldll) (e) = (u32)ix; else atomicOr(errp, 4); \\\n  } \\\n", (long long)s.length);
+            continue;
+        }
         const int F = s.func;
         if (var.backend[b] == BK_MERGER) {
             o.f("  if ((o).p%zu) m%zu = w_combine<%d>(m%zu, (%s)(o).v%zu_0); \\\n", b, b, F, b, acc_ctype(s.val_type[0]), b);
@@ -922,6 +938,7 @@ Generated generate(const Loop& L, const Variant& var) {
     o.f("} while (0)\n\n");
     };
     emit_merge_macro("WELD_MERGE", 0);
+    if (var.vq_sorted) emit_merge_macro("WELD_MERGE_TILE", 0, true);
     // The deferred dictionary as the loop's only builder in memory: the first probes of all rows a lane
     // holds are issued together (one LDS latency per tile instead of one per row), then a loop settles
     // the hits and queues the rest.
@@ -1010,6 +1027,14 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("  __shared__ u32 v%zu_qn[%d];\n", b, var.vq_ranges);
             lds += 4 * var.vq_ranges;
             o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) v%zu_qn[q] = 0;\n", var.vq_ranges, b);
+            if (var.vq_sorted) {
+                // a tile's entries per range, where each range's run begins in the staging array (and the tile's total),
+                // where it goes in the range's segment, and the entries sorted by range
+                o.f("  __shared__ u32 v%zu_tc[%d];\n  __shared__ u32 v%zu_to[%d];\n  __shared__ u32 v%zu_tb[%d];\n  __shared__ u32 v%zu_st[W_TILE];\n",
+                    b, var.vq_ranges, b, var.vq_ranges + 1, b, var.vq_ranges, b);
+                lds += 12 * var.vq_ranges + 4 + 4 * var.block * var.v * var.u;
+                o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) v%zu_tc[q] = 0;\n", var.vq_ranges, b);
+            }
             need_sync = true;
         } else if (var.backend[b] == BK_VECM_LDS) {
             const int cells = var.ranges > 1 ? 8192 : (int)s.length;
@@ -1130,19 +1155,48 @@ Generated generate(const Loop& L, const Variant& var) {
         for (int c = 0; c < L.ncols; ++c)
             if (L.col_used[c]) o.f("      x%d[u] = w_load<%s, W_V>(a.c%d + r0 + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
         o.f("    }\n");
+        if (var.vq_sorted) o.f("    u32 vq_e[W_U * W_V];\n");
         o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
         for (size_t b = 0; b < NB; ++b)
             if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) o.f("      wvec<%s, W_V> y%zu;\n", stype(L.builders[b].val_type[0]), b);
         o.f("      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
         o.f("        RowOut o;\n        %s\n", row_call("r0 + u * W_UNIT + k", "x%d[u].e[k]", "o", true).c_str());
-        o.f("        WELD_MERGE(o);\n");
+        o.f(var.vq_sorted ? "        WELD_MERGE_TILE(o, vq_e[u * W_V + k]);\n" : "        WELD_MERGE(o);\n");
         for (size_t b = 0; b < NB; ++b)
             if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) o.f("        y%zu.e[k] = o.v%zu_0;\n", b, b);
         o.f("      }\n");
         for (size_t b = 0; b < NB; ++b)
             if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0)
                 o.f("      w_store<%s, W_V>(a.b%zu_out + r0 + u * W_UNIT, y%zu);\n", stype(L.builders[b].val_type[0]), b, b);
-        o.f("    }\n%s  }\n", guard_text.c_str());
+        o.f("    }\n");
+        if (var.vq_sorted) {
+            // The tile's entries, sorted by range in LDS, leave as runs: a range's entries of one tile go to neighbouring
+            // addresses of its segment from neighbouring threads - a few stores of whole lines per (tile, range) instead
+            // of one 4-byte store per row to a line of its own (the loop was bound by the number of stores, not by bytes).
+            // Rank within (tile, range) from an LDS counter; a scan across the work-group turns the counts into where each
+            // range's run begins in the staging array and in the segment; four barriers a tile.
+            const size_t b = (size_t)var.vq_builder;
+            const weld_builder_spec_t& s = L.builders[b];
+            const int R = var.vq_ranges;
+            const std::string cv = std::string("(") + acc_ctype(s.val_type[0]) + ")(" + ctype(s.val_type[0]) + ")" + const_expr(L.ops[L.merges[L.merge_of[b]].val[0]]);
+            o.f("    {\n      u32 rk[W_U * W_V];\n      _Pragma(\"unroll\") for (int j = 0; j < W_U * W_V; ++j) {\n        rk[j] = 0;\n");
+            o.f("        if (vq_e[j] != 0xffffffffu) rk[j] = __hip_atomic_fetch_add(v%zu_tc + (vq_e[j] >> %d), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);\n      }\n", b, var.vq_shift);
+            const int K = (R + var.block - 1) / var.block;          // ranges per thread in the scan of the counts
+            o.f("      __syncthreads();\n      {\n        u32 c[%d], mine = 0;\n", K);
+            o.f("        _Pragma(\"unroll\") for (int k = 0; k < %d; ++k) { const int q = (int)threadIdx.x * %d + k; c[k] = q < %d ? v%zu_tc[q] : 0u; mine += c[k]; }\n", K, K, R, b);
+            o.f("        u32 incl = mine;\n        for (int d = 1; d < 64; d <<= 1) { const u32 up = __shfl_up(incl, d, 64); if (lane >= d) incl += up; }\n");
+            o.f("        if (lane == 63) s_red[wave] = incl;\n        __syncthreads();\n        u32 run = incl - mine;\n");
+            o.f("        for (int w = 0; w < wave; ++w) run += (u32)s_red[w];\n");
+            o.f("        _Pragma(\"unroll\") for (int k = 0; k < %d; ++k) {\n          const int q = (int)threadIdx.x * %d + k;\n", K, K);
+            o.f("          if (q < %d) { v%zu_to[q] = run; v%zu_tb[q] = v%zu_qn[q]; v%zu_qn[q] += c[k]; v%zu_tc[q] = 0; }\n          run += c[k];\n        }\n", R, b, b, b, b, b);
+            o.f("        if (threadIdx.x == W_BLOCK - 1) v%zu_to[%d] = run;\n      }\n      __syncthreads();\n", b, R);
+            o.f("      _Pragma(\"unroll\") for (int j = 0; j < W_U * W_V; ++j)\n        if (vq_e[j] != 0xffffffffu) v%zu_st[v%zu_to[vq_e[j] >> %d] + rk[j]] = vq_e[j];\n      __syncthreads();\n", b, b, var.vq_shift);
+            o.f("      const u32 staged = v%zu_to[%d];\n      for (u32 i = threadIdx.x; i < staged; i += W_BLOCK) {\n        const u32 e = v%zu_st[i];\n        const u32 part = e >> %d;\n", b, R, b, var.vq_shift);
+            o.f("        const u64 pos = (u64)v%zu_tb[part] + (i - v%zu_to[part]);\n", b, b);
+            o.f("        if ((i64)pos < a.b%zu_qcap) w_gstore_u32((u32*)a.b%zu_log + ((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap + pos, e & %du);\n", b, b, R, b, (1u << var.vq_shift) - 1);
+            o.f("        else w_atomic<%d>(a.b%zu_out + e, %s, 1);\n      }\n    }\n", s.func, b, cv.c_str());
+        }
+        o.f("%s  }\n", guard_text.c_str());
         // tail rows, one per thread
         if (var.ranges > 1)
             o.f("  for (i64 i = nfull * W_TILE + (i64)member * W_BLOCK + threadIdx.x; i < a.n; i += (i64)members * W_BLOCK) {\n");

@@ -193,6 +193,7 @@ struct Variant {
     int vq_shift = 13;          // [work-group][range] of a log in global memory, entries of 4 bytes (the cell within its
     int vq_ranges = 0;          // range; vq_const: the merged value is a constant the second kernel is told) or 16 bytes
     bool vq_const = false;      // (cell within the range, value bits)
+    bool vq_sorted = false;     // a tile's entries are sorted by range in LDS and leave as runs (4-byte entries, <= 256 ranges)
     std::vector<int> backend;   // per builder
 };
 

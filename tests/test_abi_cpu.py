@@ -123,9 +123,9 @@ def test_tables_choose_their_hash_by_size_and_slices_follow_the_table(wb):
 
 def test_planner_chooses_the_vecmerger_strategy_by_length(wb):
     """Host logic read off the generated text: an LDS copy up to 8192 cells, LDS copies of ranges (every range
-    scanning all rows) up to 32768 cells for a loop with no other builder, queues by range of cells beyond -
-    at most 128 ranges up to 2^20 cells, ranges of 8192 cells above -, device atomics on request and where
-    the queues are ruled out."""
+    scanning all rows) up to 16384 cells for a loop with no other builder, queues by range of cells beyond -
+    at most 256 ranges up to 2^21 cells, ranges of 8192 cells above; a tile's entries sorted in LDS where they
+    are 4 bytes -, device atomics on request and where the queues are ruled out."""
     def count(length, tune=None, second=False):
         p = Program(["i32"])
         p.merge(p.vecmerger("i64", "add", length), [p.const("i64", 1)], keys=[p.un("cast", p.col(0), to="i64")])
@@ -133,19 +133,27 @@ def test_planner_chooses_the_vecmerger_strategy_by_length(wb):
             p.merge(p.merger("i64", "add"), p.un("cast", p.col(0), to="i64"))
         return wb.generated_source(p, tune=tune)
     assert "__shared__ i64 v0_l[8192]" in count(8192)
-    assert "range_lo" in count(32768) and "v0_qn" not in count(32768)
-    assert "v0_qn[128]" in count(32768, second=True) and "range_lo" not in count(32768, second=True)
+    assert "range_lo" in count(16384) and "v0_qn" not in count(16384)
+    assert "v0_qn[128]" in count(32768) and "v0_qn[64]" in count(16384, second=True) and "range_lo" not in count(16384, second=True)
     src = count(1 << 20)
-    assert "__shared__ u32 v0_qn[128]" in src and "(u64)ix >> 13" in src and "w_gstore_u32((u32*)a.b0_log + at, (u32)ix & 8191u)" in src
-    assert "else w_atomic<0>(a.b0_out + ix" in src                      # a full segment: straight to the result
-    assert "v0_qn[65]" in count(65 * 1024) and "(u64)ix >> 10" in count(65 * 1024)
-    assert "v0_qn[2048]" in count(1 << 24)
+    assert "__shared__ u32 v0_qn[256]" in src and "(u64)ix >> 12" in src and "w_gstore_u32((u32*)a.b0_log + at, (u32)ix & 4095u)" in src
+    assert "else w_atomic<0>(a.b0_out + ix" in src                      # a full segment: straight to the result (rows of the last, partial tile)
+    assert "WELD_MERGE_TILE(o, vq_e[u * W_V + k]);" in src and "__shared__ u32 v0_st[W_TILE];" in src and "u32 c[1], mine = 0;" in src
+    assert "WELD_MERGE_TILE" not in count(1 << 20, tune={"vecmerger_strategy": 6})
+    assert "v0_qn[132]" in count(65 * 1024 + 1024) and "(u64)ix >> 9" in count(65 * 1024 + 1024)
+    big = count(1 << 24)
+    assert "v0_qn[2048]" in big and "WELD_MERGE_TILE" in big and "u32 c[2], mine = 0;" in big
+    assert "v0_qn[8192]" in count(1 << 26) and "WELD_MERGE_TILE" not in count(1 << 26)      # (four arrays of 8192 words and the staging: too much LDS)
+    beside = Program(["i64"])            # (an LDS dictionary beside it leaves no room for the staging array)
+    beside.merge(beside.vecmerger("i64", "add", 100_000), [beside.const("i64", 1)], keys=[beside.bin("mod", beside.col(0), beside.const("i64", 100_000))])
+    beside.merge(beside.dictmerger(["i64"], ["i64"], "add", 100_000), [beside.const("i64", 1)], keys=[beside.col(0)])
+    assert "v0_qn" in wb.generated_source(beside) and "WELD_MERGE_TILE" not in wb.generated_source(beside)
     for tune in ({"vecmerger_strategy": 3}, {"vecmerger_strategy": -1}, {"dict_spill": -1}):
         off = count(1 << 20, tune=tune)
         assert "v0_qn" not in off and "w_atomic<0>(a.b0_out + ix" in off
     valued = Program(["i64", "f64"])
     valued.merge(valued.vecmerger("f64", "max", 100_000), [valued.col(1)], keys=[valued.col(0)])
-    assert "w_gstore2(a.b0_log + 2 * at, (u64)((u32)ix & 1023u), w_bits((double)(o).v0_0))" in wb.generated_source(valued)
+    assert "w_gstore2(a.b0_log + 2 * at, (u64)((u32)ix & 511u), w_bits((double)(o).v0_0))" in wb.generated_source(valued)
 
 
 def test_planner_overlaps_tiles_only_where_the_registers_allow(wb):

@@ -926,7 +926,7 @@ def _count_program(length, t="i64", func="add"):
     return p
 
 
-@pytest.mark.parametrize("strategy", [-1, 0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("strategy", [-1, 0, 1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("length", [1, 5, 8, 9, 1000, 8192, 8193, 20_000, 300_000])
 def test_vecmerger_counts_occurrences(wb, length, strategy):
     rnd = np.random.RandomState(length)
