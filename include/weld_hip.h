@@ -180,9 +180,9 @@ typedef struct {
                                    per row where the merged value is a constant, else 16) and merged range by
                                    range in LDS by a second kernel (lengths from 8193 to 2^26; one vecmerger
                                    per loop, the others then use 3; a segment that is full sends its merges
-                                   to the result with device atomics; where the merged value is a constant
-                                   and the vector has at most 2^25 cells, a tile's entries are sorted by
-                                   range in LDS and stored as runs),
+                                   to the result with device atomics; up to 2^25 cells (2^24 where entries
+                                   carry a value) a tile's entries are sorted by range in LDS and stored as
+                                   runs),
                                    6 = 5 without that sort, -1 = auto without 5 */
     int32_t lds_filter_words;   /* admission filter in front of an LDS hash table that is smaller than
                                    the key set: 32-bit words of its bitmap (power of two); -1 = none */

@@ -554,8 +554,11 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
     }
     if (var.u > 16) var.u = 16;
     // (the sorted form of the queued vecmerger stages a tile's 4-byte entries in LDS: static tiles of at most 16384 rows)
-    var.vq_sorted = var.vq_sorted && var.vq_builder >= 0 && var.vq_const && var.vq_ranges <= 4096 && !var.ticketed && var.ranges == 1 &&
-                    (int64_t)var.block * var.v * var.u <= 16384;
+    // (... and entries with a value, 12 bytes a row in the staging arrays: tiles of 8192 rows, at most 2048 ranges)
+    var.vq_sorted = var.vq_sorted && var.vq_builder >= 0 && var.vq_ranges <= (var.vq_const ? 4096 : 2048) && !var.ticketed && var.ranges == 1;
+    if (var.vq_sorted && !var.vq_const && tune.units_per_thread <= 0)
+        while (var.u > 1 && (int64_t)var.block * var.v * var.u > 8192) var.u /= 2;
+    var.vq_sorted = var.vq_sorted && (int64_t)var.block * var.v * var.u <= (var.vq_const ? 16384 : 8192);
     for (size_t b = 0; b < L.builders.size(); ++b)      // (the staging array takes 64 KiB: not beside another builder's LDS state)
         if (var.backend[b] == BK_DICT_LDS || var.backend[b] == BK_DICT_LANE || var.backend[b] == BK_VECM_LDS) var.vq_sorted = false;
     if (var.block < 64) var.block = 64;
@@ -825,7 +828,7 @@ Generated generate(const Loop& L, const Variant& var) {
     // which: 0 = every builder, 1 = those held in registers, 2 = those held in memory; tile: the merge of the
     // vecmerger whose tile entries are sorted in LDS only notes its index in `e` (0xffffffff: nothing to merge)
     auto emit_merge_macro = [&](const char* name, int which, bool tile = false) {
-    o.f(tile ? "#define %s(o, e) do { \\\n" : "#define %s(o) do { \\\n", name);
+    o.f(tile ? "#define %s(o, e, vb) do { \\\n" : "#define %s(o) do { \\\n", name);
     for (size_t b = 0; b < NB; ++b) {
         if (L.merge_of[b] < 0) continue;
         if (which == 1 && merges_in_memory(var.backend[b])) continue;
@@ -833,7 +836,11 @@ Generated generate(const Loop& L, const Variant& var) {
         const weld_builder_spec_t& s = L.builders[b];
         if (tile && (int)b == var.vq_builder) {
             o.f("  (e) = 0xffffffffu; \\\n  if ((o).p%zu) { \\\n    const i64 ix = (o).k%zu_0; \\\n", b, b);
-            o.f("    if ((u64)ix < (u64)%lldll) (e) = (u32)ix; else atomicOr(errp, 4); \\\n  } \\\n", (long long)s.length);
+            if (var.vq_const)
+                o.f("    if ((u64)ix < (u64)%lldll) (e) = (u32)ix; else atomicOr(errp, 4); \\\n  } \\\n", (long long)s.length);
+            else
+                o.f("    if ((u64)ix < (u64)%lldll) { (e) = (u32)ix; (vb) = w_bits((%s)(o).v%zu_0); } else atomicOr(errp, 4); \\\n  } \\\n",
+                    (long long)s.length, acc_ctype(s.val_type[0]), b);
             continue;
         }
         const int F = s.func;
@@ -1033,6 +1040,10 @@ Generated generate(const Loop& L, const Variant& var) {
                 o.f("  __shared__ u32 v%zu_tc[%d];\n  __shared__ u32 v%zu_to[%d];\n  __shared__ u32 v%zu_tb[%d];\n  __shared__ u32 v%zu_st[W_TILE];\n",
                     b, var.vq_ranges, b, var.vq_ranges + 1, b, var.vq_ranges, b);
                 lds += 12 * var.vq_ranges + 4 + 4 * var.block * var.v * var.u;
+                if (!var.vq_const) {
+                    o.f("  __shared__ u64 v%zu_sv[W_TILE];\n", b);
+                    lds += 8 * var.block * var.v * var.u;
+                }
                 o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) v%zu_tc[q] = 0;\n", var.vq_ranges, b);
             }
             need_sync = true;
@@ -1155,13 +1166,13 @@ Generated generate(const Loop& L, const Variant& var) {
         for (int c = 0; c < L.ncols; ++c)
             if (L.col_used[c]) o.f("      x%d[u] = w_load<%s, W_V>(a.c%d + r0 + u * W_UNIT);\n", c, stype(L.col_type[c]), c);
         o.f("    }\n");
-        if (var.vq_sorted) o.f("    u32 vq_e[W_U * W_V];\n");
+        if (var.vq_sorted) o.f("    u32 vq_e[W_U * W_V];\n    u64 vq_v[W_U * W_V];\n    (void)vq_v;\n");
         o.f("    _Pragma(\"unroll\") for (int u = 0; u < W_U; ++u) {\n");
         for (size_t b = 0; b < NB; ++b)
             if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) o.f("      wvec<%s, W_V> y%zu;\n", stype(L.builders[b].val_type[0]), b);
         o.f("      _Pragma(\"unroll\") for (int k = 0; k < W_V; ++k) {\n");
         o.f("        RowOut o;\n        %s\n", row_call("r0 + u * W_UNIT + k", "x%d[u].e[k]", "o", true).c_str());
-        o.f(var.vq_sorted ? "        WELD_MERGE_TILE(o, vq_e[u * W_V + k]);\n" : "        WELD_MERGE(o);\n");
+        o.f(var.vq_sorted ? "        WELD_MERGE_TILE(o, vq_e[u * W_V + k], vq_v[u * W_V + k]);\n" : "        WELD_MERGE(o);\n");
         for (size_t b = 0; b < NB; ++b)
             if (var.backend[b] == BK_VEC_DIRECT && L.merge_of[b] >= 0) o.f("        y%zu.e[k] = o.v%zu_0;\n", b, b);
         o.f("      }\n");
@@ -1178,7 +1189,8 @@ Generated generate(const Loop& L, const Variant& var) {
             const size_t b = (size_t)var.vq_builder;
             const weld_builder_spec_t& s = L.builders[b];
             const int R = var.vq_ranges;
-            const std::string cv = std::string("(") + acc_ctype(s.val_type[0]) + ")(" + ctype(s.val_type[0]) + ")" + const_expr(L.ops[L.merges[L.merge_of[b]].val[0]]);
+            const std::string cv = !var.vq_const ? std::string() :
+                std::string("(") + acc_ctype(s.val_type[0]) + ")(" + ctype(s.val_type[0]) + ")" + const_expr(L.ops[L.merges[L.merge_of[b]].val[0]]);
             o.f("    {\n      u32 rk[W_U * W_V];\n      _Pragma(\"unroll\") for (int j = 0; j < W_U * W_V; ++j) {\n        rk[j] = 0;\n");
             o.f("        if (vq_e[j] != 0xffffffffu) rk[j] = __hip_atomic_fetch_add(v%zu_tc + (vq_e[j] >> %d), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);\n      }\n", b, var.vq_shift);
             const int K = (R + var.block - 1) / var.block;          // ranges per thread in the scan of the counts
@@ -1190,11 +1202,19 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("        _Pragma(\"unroll\") for (int k = 0; k < %d; ++k) {\n          const int q = (int)threadIdx.x * %d + k;\n", K, K);
             o.f("          if (q < %d) { v%zu_to[q] = run; v%zu_tb[q] = v%zu_qn[q]; v%zu_qn[q] += c[k]; v%zu_tc[q] = 0; }\n          run += c[k];\n        }\n", R, b, b, b, b, b);
             o.f("        if (threadIdx.x == W_BLOCK - 1) v%zu_to[%d] = run;\n      }\n      __syncthreads();\n", b, R);
-            o.f("      _Pragma(\"unroll\") for (int j = 0; j < W_U * W_V; ++j)\n        if (vq_e[j] != 0xffffffffu) v%zu_st[v%zu_to[vq_e[j] >> %d] + rk[j]] = vq_e[j];\n      __syncthreads();\n", b, b, var.vq_shift);
+            if (var.vq_const)
+                o.f("      _Pragma(\"unroll\") for (int j = 0; j < W_U * W_V; ++j)\n        if (vq_e[j] != 0xffffffffu) v%zu_st[v%zu_to[vq_e[j] >> %d] + rk[j]] = vq_e[j];\n      __syncthreads();\n", b, b, var.vq_shift);
+            else
+                o.f("      _Pragma(\"unroll\") for (int j = 0; j < W_U * W_V; ++j)\n        if (vq_e[j] != 0xffffffffu) {\n          const u32 at = v%zu_to[vq_e[j] >> %d] + rk[j];\n          v%zu_st[at] = vq_e[j];\n          v%zu_sv[at] = vq_v[j];\n        }\n      __syncthreads();\n", b, var.vq_shift, b, b);
             o.f("      const u32 staged = v%zu_to[%d];\n      for (u32 i = threadIdx.x; i < staged; i += W_BLOCK) {\n        const u32 e = v%zu_st[i];\n        const u32 part = e >> %d;\n", b, R, b, var.vq_shift);
             o.f("        const u64 pos = (u64)v%zu_tb[part] + (i - v%zu_to[part]);\n", b, b);
-            o.f("        if ((i64)pos < a.b%zu_qcap) w_gstore_u32((u32*)a.b%zu_log + ((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap + pos, e & %du);\n", b, b, R, b, (1u << var.vq_shift) - 1);
-            o.f("        else w_atomic<%d>(a.b%zu_out + e, %s, 1);\n      }\n    }\n", s.func, b, cv.c_str());
+            if (var.vq_const) {
+                o.f("        if ((i64)pos < a.b%zu_qcap) w_gstore_u32((u32*)a.b%zu_log + ((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap + pos, e & %du);\n", b, b, R, b, (1u << var.vq_shift) - 1);
+                o.f("        else w_atomic<%d>(a.b%zu_out + e, %s, 1);\n      }\n    }\n", s.func, b, cv.c_str());
+            } else {
+                o.f("        if ((i64)pos < a.b%zu_qcap) w_gstore2(a.b%zu_log + 2 * (((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap + pos), (u64)(e & %du), v%zu_sv[i]);\n", b, b, R, b, (1u << var.vq_shift) - 1, b);
+                o.f("        else w_atomic<%d>(a.b%zu_out + e, w_from_bits<%s>(v%zu_sv[i]), 1);\n      }\n    }\n", s.func, b, acc_ctype(s.val_type[0]), b);
+            }
         }
         o.f("%s  }\n", guard_text.c_str());
         // tail rows, one per thread

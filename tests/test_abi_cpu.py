@@ -138,7 +138,7 @@ def test_planner_chooses_the_vecmerger_strategy_by_length(wb):
     src = count(1 << 20)
     assert "__shared__ u32 v0_qn[256]" in src and "(u64)ix >> 12" in src and "w_gstore_u32((u32*)a.b0_log + at, (u32)ix & 4095u)" in src
     assert "else w_atomic<0>(a.b0_out + ix" in src                      # a full segment: straight to the result (rows of the last, partial tile)
-    assert "WELD_MERGE_TILE(o, vq_e[u * W_V + k]);" in src and "__shared__ u32 v0_st[W_TILE];" in src and "u32 c[1], mine = 0;" in src
+    assert "WELD_MERGE_TILE(o, vq_e[u * W_V + k], vq_v[u * W_V + k]);" in src and "__shared__ u32 v0_st[W_TILE];" in src and "u32 c[1], mine = 0;" in src
     assert "WELD_MERGE_TILE" not in count(1 << 20, tune={"vecmerger_strategy": 6})
     assert "v0_qn[132]" in count(65 * 1024 + 1024) and "(u64)ix >> 9" in count(65 * 1024 + 1024)
     big = count(1 << 24)
@@ -153,7 +153,9 @@ def test_planner_chooses_the_vecmerger_strategy_by_length(wb):
         assert "v0_qn" not in off and "w_atomic<0>(a.b0_out + ix" in off
     valued = Program(["i64", "f64"])
     valued.merge(valued.vecmerger("f64", "max", 100_000), [valued.col(1)], keys=[valued.col(0)])
-    assert "w_gstore2(a.b0_log + 2 * at, (u64)((u32)ix & 511u), w_bits((double)(o).v0_0))" in wb.generated_source(valued)
+    vsrc = wb.generated_source(valued)          # (entries with a value: 16 bytes, sorted in tiles of 8192 rows)
+    assert "w_gstore2(a.b0_log + 2 * at, (u64)((u32)ix & 511u), w_bits((double)(o).v0_0))" in vsrc
+    assert "__shared__ u64 v0_sv[W_TILE];" in vsrc and "#define W_U 4" in vsrc and "#define W_V 2" in vsrc
 
 
 def test_planner_overlaps_tiles_only_where_the_registers_allow(wb):
