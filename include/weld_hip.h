@@ -176,7 +176,7 @@ typedef struct {
     int32_t vecmerger_strategy; /* 0 auto, 1 per-lane register copies (length <= 8), 2 work-group
                                    copy in LDS updated with LDS atomics, 3 global atomics only,
                                    4 LDS copies of 8192-cell ranges, each range scanning all rows,
-                                   5 merges queued by range of cells in device memory (workspace: 4 bytes
+                                   5 merges queued by range of cells in device memory (workspace: 2 bytes
                                    per row where the merged value is a constant, else 16) and merged range by
                                    range in LDS by a second kernel (lengths from 8193 to 2^26; one vecmerger
                                    per loop, the others then use 3; a segment that is full sends its merges

@@ -422,7 +422,7 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
             const bool alone = L.builders.size() == 1;
             if (strat == 4 && (!alone || s.length > 8192 * 64)) strat = 0;
             // Beyond that a fifth: every merge is appended to a queue by range of cells (segment [work-group][range],
-            // 4 bytes an entry where the merged value is a constant, else 16), and a second kernel merges each
+            // 2 bytes an entry where the merged value is a constant, else 16), and a second kernel merges each
             // range in LDS and adds it to the result - two streaming passes instead of one device atomic per row.
             // One such vecmerger per loop; up to 8192 ranges of 8192 cells.
             const bool can_queue = queues_allowed && var.vq_builder < 0 && m >= 0 && s.length > 8192 && s.length <= (int64_t)8192 * 8192 && tune.dict_spill >= 0;
@@ -436,7 +436,7 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
             if (strat == 5) {
                 var.vq_builder = (int)b;
                 var.vq_shift = 8;
-                // (1e8 uniform keys, 2^20 cells, one 4-byte store per row: 0.58 ms with 128 ranges, 0.62 with 256, 0.75 with 512,
+                // (1e8 uniform keys, 2^20 cells, one store per row (then of 4 bytes): 0.58 ms with 128 ranges, 0.62 with 256, 0.75 with 512,
                 // 0.92 with 1024 - every range is one more line a work-group keeps open; with a tile's entries sorted in LDS
                 // first 0.35 ms with 128 ranges and 0.32 with 256, which put the second kernel on every compute unit)
                 while (var.vq_shift < 13 && ((s.length + ((int64_t)1 << var.vq_shift) - 1) >> var.vq_shift) > 256) ++var.vq_shift;
@@ -553,7 +553,7 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
         var.block = tune.block_threads > 0 ? tune.block_threads : (reg_dict ? 512 : 256);
     }
     if (var.u > 16) var.u = 16;
-    // (the sorted form of the queued vecmerger stages a tile's 4-byte entries in LDS: static tiles of at most 16384 rows)
+    // (the sorted form of the queued vecmerger stages a tile's indices in LDS, 4 bytes each: static tiles of at most 16384 rows)
     // (... and entries with a value, 12 bytes a row in the staging arrays: tiles of 8192 rows, at most 2048 ranges)
     var.vq_sorted = var.vq_sorted && var.vq_builder >= 0 && var.vq_ranges <= (var.vq_const ? 4096 : 2048) && !var.ticketed && var.ranges == 1;
     if (var.vq_sorted && !var.vq_const && tune.units_per_thread <= 0)
@@ -881,7 +881,7 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("      if ((i64)pos < a.b%zu_qcap) { \\\n", b);
             o.f("        const u64 at = ((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap + pos; \\\n", var.vq_ranges, b);
             if (var.vq_const)
-                o.f("        w_gstore_u32((u32*)a.b%zu_log + at, (u32)ix & %du); \\\n", b, (1u << var.vq_shift) - 1);
+                o.f("        w_gstore_u16((unsigned short*)a.b%zu_log + at, (unsigned short)((u32)ix & %du)); \\\n", b, (1u << var.vq_shift) - 1);
             else
                 o.f("        w_gstore2(a.b%zu_log + 2 * at, (u64)((u32)ix & %du), w_bits((%s)(o).v%zu_0)); \\\n", b, (1u << var.vq_shift) - 1, A, b);
             o.f("      } else w_atomic<%d>(a.b%zu_out + ix, (%s)(o).v%zu_0, 1); \\\n", F, b, A, b);
@@ -1183,7 +1183,7 @@ Generated generate(const Loop& L, const Variant& var) {
         if (var.vq_sorted) {
             // The tile's entries, sorted by range in LDS, leave as runs: a range's entries of one tile go to neighbouring
             // addresses of its segment from neighbouring threads - a few stores of whole lines per (tile, range) instead
-            // of one 4-byte store per row to a line of its own (the loop was bound by the number of stores, not by bytes).
+            // of one small store per row to a line of its own (the loop was bound by the number of stores, not by bytes).
             // Rank within (tile, range) from an LDS counter; a scan across the work-group turns the counts into where each
             // range's run begins in the staging array and in the segment; four barriers a tile.
             const size_t b = (size_t)var.vq_builder;
@@ -1209,7 +1209,7 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("      const u32 staged = v%zu_to[%d];\n      for (u32 i = threadIdx.x; i < staged; i += W_BLOCK) {\n        const u32 e = v%zu_st[i];\n        const u32 part = e >> %d;\n", b, R, b, var.vq_shift);
             o.f("        const u64 pos = (u64)v%zu_tb[part] + (i - v%zu_to[part]);\n", b, b);
             if (var.vq_const) {
-                o.f("        if ((i64)pos < a.b%zu_qcap) w_gstore_u32((u32*)a.b%zu_log + ((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap + pos, e & %du);\n", b, b, R, b, (1u << var.vq_shift) - 1);
+                o.f("        if ((i64)pos < a.b%zu_qcap) w_gstore_u16((unsigned short*)a.b%zu_log + ((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap + pos, (unsigned short)(e & %du));\n", b, b, R, b, (1u << var.vq_shift) - 1);
                 o.f("        else w_atomic<%d>(a.b%zu_out + e, %s, 1);\n      }\n    }\n", s.func, b, cv.c_str());
             } else {
                 o.f("        if ((i64)pos < a.b%zu_qcap) w_gstore2(a.b%zu_log + 2 * (((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap + pos), (u64)(e & %du), v%zu_sv[i]);\n", b, b, R, b, (1u << var.vq_shift) - 1, b);

@@ -810,8 +810,8 @@ typedef u64 w_u64x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void w_gstore1(u64* p, u64 x) {
     *(__attribute__((address_space(1))) u64*)p = x;
 }
-__device__ __forceinline__ void w_gstore_u32(u32* p, u32 x) {
-    *(__attribute__((address_space(1))) u32*)p = x;
+__device__ __forceinline__ void w_gstore_u16(unsigned short* p, unsigned short x) {
+    *(__attribute__((address_space(1))) unsigned short*)p = x;
 }
 __device__ __forceinline__ void w_gstore2(u64* p, u64 x, u64 y) {   // p is 16-byte aligned
     const w_u64x2 v = {x, y};

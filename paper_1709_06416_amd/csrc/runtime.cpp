@@ -545,16 +545,16 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     // sends its merges to the result with device atomics, so a memory limit may shrink them too
     if (var.vq_builder >= 0) {
         const size_t b = (size_t)var.vq_builder;
-        const size_t entry = var.vq_const ? 4 : 16;
+        const size_t entry = var.vq_const ? 2 : 16;
         off[b].qcnt = lay.take(4 * (size_t)grid * var.vq_ranges);
         const double rows = (double)((ntiles + grid - 1) / grid) * (double)tile;
         const double mean = rows / var.vq_ranges;
         int64_t cap = (int64_t)(mean + 6.0 * std::sqrt(mean) + 16.0);
-        cap = (cap + 3) / 4 * 4;                        // (segments of 4-byte entries begin at 16-byte addresses)
+        cap = (cap + 7) / 8 * 8;                        // (segments of 2-byte entries begin at 16-byte addresses)
         const size_t seg = (size_t)grid * var.vq_ranges * entry;
         if (mem_limit > 0) {
             const int64_t room = mem_limit - (int64_t)lay.total;
-            const int64_t fit = room > 0 ? (room - 256) / (int64_t)seg / 4 * 4 : 0;
+            const int64_t fit = room > 0 ? (room - 256) / (int64_t)seg / 8 * 8 : 0;
             if (cap > fit) cap = fit > 0 ? fit : 0;
         }
         off[b].qcap = cap;
@@ -802,7 +802,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         vr.func = s.func;
         vr.is_f64 = s.val_type[0] == WELD_F64;
         vr.ident = ident_bits(s.func, s.val_type[0]);
-        vr.entry_bytes = var.vq_const ? 4 : 16;
+        vr.entry_bytes = var.vq_const ? 2 : 16;
         if (var.vq_const) {
             const weld_op_t& c = L.ops[L.merges[L.merge_of[b]].val[0]];
             if (s.val_type[0] == WELD_F64) memcpy(&vr.const_bits, &c.imm.f64, 8);

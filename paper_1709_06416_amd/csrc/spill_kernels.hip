@@ -630,14 +630,14 @@ __global__ void __launch_bounds__(1024) vecm_ranges_kernel(const VecmRanges a) {
         const i64 len = (i64)s_len[g] < a.cap ? (i64)s_len[g] : a.cap;
         const i64 seg = ((i64)g * a.ranges + r) * a.cap;
         // eight loads of a lane in flight (no branch around a load: an entry past the end re-reads the last one)
-        if (ENTRY == 4) {
-            const u32* e = (const u32*)a.log + seg;
+        if (ENTRY == 2) {
+            const unsigned short* e = (const unsigned short*)a.log + seg;
             for (i64 i0 = 0; i0 < len; i0 += 512) {
                 u32 c[8];
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
                     const i64 i = i0 + k * 64 + lane;
-                    c[k] = __builtin_nontemporal_load(e + (i < len ? i : len - 1));
+                    c[k] = (u32)__builtin_nontemporal_load(e + (i < len ? i : len - 1));
                 }
 #pragma unroll
                 for (int k = 0; k < 8; ++k)
@@ -683,15 +683,15 @@ __global__ void __launch_bounds__(1024) vecm_ranges_kernel(const VecmRanges a) {
 
 template <int FUNC>
 static hipError_t launch_vecm_func(const VecmRanges& v, hipStream_t stream, hipEvent_t stop) {
-    if (v.entry_bytes == 4)
-        hipExtLaunchKernelGGL((vecm_ranges_kernel<FUNC, 4>), dim3((unsigned)v.ranges), dim3(1024), 0, stream, nullptr, stop, 0, v);
+    if (v.entry_bytes == 2)
+        hipExtLaunchKernelGGL((vecm_ranges_kernel<FUNC, 2>), dim3((unsigned)v.ranges), dim3(1024), 0, stream, nullptr, stop, 0, v);
     else
         hipExtLaunchKernelGGL((vecm_ranges_kernel<FUNC, 16>), dim3((unsigned)v.ranges), dim3(1024), 0, stream, nullptr, stop, 0, v);
     return hipGetLastError();
 }
 hipError_t launch_vecm_ranges(const VecmRanges& v, hipStream_t stream, hipEvent_t stop) {
     if (v.ranges < 1 || v.shift < 0 || v.shift > 13 || v.groups < 1 || v.groups > 2048 || v.cap < 0 ||
-        (v.entry_bytes != 4 && v.entry_bytes != 16) || ((long long)v.ranges << v.shift) < v.length)
+        (v.entry_bytes != 2 && v.entry_bytes != 16) || ((long long)v.ranges << v.shift) < v.length)
         return hipErrorInvalidValue;
     switch (v.func) {
         case 0: return launch_vecm_func<0>(v, stream, stop);

@@ -125,7 +125,7 @@ def test_planner_chooses_the_vecmerger_strategy_by_length(wb):
     """Host logic read off the generated text: an LDS copy up to 8192 cells, LDS copies of ranges (every range
     scanning all rows) up to 16384 cells for a loop with no other builder, queues by range of cells beyond -
     at most 256 ranges up to 2^21 cells, ranges of 8192 cells above; a tile's entries sorted in LDS where they
-    are 4 bytes -, device atomics on request and where the queues are ruled out."""
+    are 2 bytes or tiles are small -, device atomics on request and where the queues are ruled out."""
     def count(length, tune=None, second=False):
         p = Program(["i32"])
         p.merge(p.vecmerger("i64", "add", length), [p.const("i64", 1)], keys=[p.un("cast", p.col(0), to="i64")])
@@ -136,7 +136,7 @@ def test_planner_chooses_the_vecmerger_strategy_by_length(wb):
     assert "range_lo" in count(16384) and "v0_qn" not in count(16384)
     assert "v0_qn[128]" in count(32768) and "v0_qn[64]" in count(16384, second=True) and "range_lo" not in count(16384, second=True)
     src = count(1 << 20)
-    assert "__shared__ u32 v0_qn[256]" in src and "(u64)ix >> 12" in src and "w_gstore_u32((u32*)a.b0_log + at, (u32)ix & 4095u)" in src
+    assert "__shared__ u32 v0_qn[256]" in src and "(u64)ix >> 12" in src and "w_gstore_u16((unsigned short*)a.b0_log + at, (unsigned short)((u32)ix & 4095u))" in src
     assert "else w_atomic<0>(a.b0_out + ix" in src                      # a full segment: straight to the result (rows of the last, partial tile)
     assert "WELD_MERGE_TILE(o, vq_e[u * W_V + k], vq_v[u * W_V + k]);" in src and "__shared__ u32 v0_st[W_TILE];" in src and "u32 c[1], mine = 0;" in src
     assert "WELD_MERGE_TILE" not in count(1 << 20, tune={"vecmerger_strategy": 6})
