@@ -556,6 +556,7 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
     // (the sorted form of the queued vecmerger stages a tile's indices in LDS, 4 bytes each: static tiles of at most 16384 rows)
     // (... and entries with a value, 12 bytes a row in the staging arrays: tiles of 8192 rows, at most 2048 ranges)
     var.vq_sorted = var.vq_sorted && var.vq_builder >= 0 && var.vq_ranges <= (var.vq_const ? 4096 : 2048) && !var.ticketed && var.ranges == 1;
+    // (LDS at the limits: staging 64 or 96 KiB, four arrays of 4 bytes a range, 12 KiB for merges that find their segment full)
     if (var.vq_sorted && !var.vq_const && tune.units_per_thread <= 0)
         while (var.u > 1 && (int64_t)var.block * var.v * var.u > 8192) var.u /= 2;
     var.vq_sorted = var.vq_sorted && (int64_t)var.block * var.v * var.u <= (var.vq_const ? 16384 : 8192);
@@ -574,7 +575,7 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
             if (var.backend[b] == BK_DICT_LDS) per_slot += var.compact == (int)b ? 8 : 8 * (1 + L.builders[b].nvals);
         int other = (var.ticketed ? 8 * var.block * var.v : 0) + 4 * var.door_words + (var.spill ? 4 * var.spill_parts : 0) +
                     (body_uses(L, WELD_OP_ERF) ? 7680 : 0) + (body_uses(L, WELD_OP_LOG) ? 2184 : 0) + (body_uses(L, WELD_OP_EXP) ? 1024 : 0) + 2048 +
-                    (var.vq_builder >= 0 ? 4 * var.vq_ranges : 0);
+                    (var.vq_builder >= 0 ? 4 * var.vq_ranges + 12 * 1024 : 0);
         for (size_t b = 0; b < L.builders.size(); ++b) {
             if (var.backend[b] == BK_VECM_LDS) other += 8 * (var.ranges > 1 ? 8192 : (int)L.builders[b].length);
             if (var.backend[b] == BK_DICT_REG || var.backend[b] == BK_DICT_LANE) other += 8 * (int)L.builders[b].capacity;
@@ -884,7 +885,7 @@ Generated generate(const Loop& L, const Variant& var) {
                 o.f("        w_gstore_u16((unsigned short*)a.b%zu_log + at, (unsigned short)((u32)ix & %du)); \\\n", b, (1u << var.vq_shift) - 1);
             else
                 o.f("        w_gstore2(a.b%zu_log + 2 * at, (u64)((u32)ix & %du), w_bits((%s)(o).v%zu_0)); \\\n", b, (1u << var.vq_shift) - 1, A, b);
-            o.f("      } else w_atomic<%d>(a.b%zu_out + ix, (%s)(o).v%zu_0, 1); \\\n", F, b, A, b);
+            o.f("      } else w_vecm_overflow<%d>(v%zu_ot, v%zu_ov, (u32)ix, (%s)(o).v%zu_0, a.b%zu_out); \\\n", F, b, b, A, b, b);
             o.f("    } else atomicOr(errp, 4); \\\n  } \\\n");
         } else if (var.backend[b] == BK_VECM_REG || var.backend[b] == BK_VECM_LDS || var.backend[b] == BK_VECM_GLOBAL) {
             const char* A = acc_ctype(s.val_type[0]);
@@ -1034,6 +1035,10 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("  __shared__ u32 v%zu_qn[%d];\n", b, var.vq_ranges);
             lds += 4 * var.vq_ranges;
             o.f("  for (int q = threadIdx.x; q < %d; q += W_BLOCK) v%zu_qn[q] = 0;\n", var.vq_ranges, b);
+            // merges that find their segment full are combined here before they go to the result (w_vecm_overflow)
+            o.f("  __shared__ u32 v%zu_ot[W_VQ_OVERFLOW];\n  __shared__ %s v%zu_ov[W_VQ_OVERFLOW];\n", b, acc_ctype(s.val_type[0]), b);
+            o.f("  for (int q = threadIdx.x; q < W_VQ_OVERFLOW; q += W_BLOCK) { v%zu_ot[q] = W_VQ_NONE; v%zu_ov[q] = %s; }\n", b, b, ident_expr(s.func, s.val_type[0]).c_str());
+            lds += 12 * 1024;
             if (var.vq_sorted) {
                 // a tile's entries per range, where each range's run begins in the staging array (and the tile's total),
                 // where it goes in the range's segment, and the entries sorted by range
@@ -1210,10 +1215,10 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("        const u64 pos = (u64)v%zu_tb[part] + (i - v%zu_to[part]);\n", b, b);
             if (var.vq_const) {
                 o.f("        if ((i64)pos < a.b%zu_qcap) w_gstore_u16((unsigned short*)a.b%zu_log + ((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap + pos, (unsigned short)(e & %du));\n", b, b, R, b, (1u << var.vq_shift) - 1);
-                o.f("        else w_atomic<%d>(a.b%zu_out + e, %s, 1);\n      }\n    }\n", s.func, b, cv.c_str());
+                o.f("        else w_vecm_overflow<%d>(v%zu_ot, v%zu_ov, e, %s, a.b%zu_out);\n      }\n    }\n", s.func, b, b, cv.c_str(), b);
             } else {
                 o.f("        if ((i64)pos < a.b%zu_qcap) w_gstore2(a.b%zu_log + 2 * (((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap + pos), (u64)(e & %du), v%zu_sv[i]);\n", b, b, R, b, (1u << var.vq_shift) - 1, b);
-                o.f("        else w_atomic<%d>(a.b%zu_out + e, w_from_bits<%s>(v%zu_sv[i]), 1);\n      }\n    }\n", s.func, b, acc_ctype(s.val_type[0]), b);
+                o.f("        else w_vecm_overflow<%d>(v%zu_ot, v%zu_ov, e, w_from_bits<%s>(v%zu_sv[i]), a.b%zu_out);\n      }\n    }\n", s.func, b, b, acc_ctype(s.val_type[0]), b, b);
             }
         }
         o.f("%s  }\n", guard_text.c_str());
@@ -1545,6 +1550,7 @@ Generated generate(const Loop& L, const Variant& var) {
         } else if (var.backend[b] == BK_VECM_QUEUE) {
             o.f("  __syncthreads();\n  for (int q = threadIdx.x; q < %d; q += W_BLOCK)\n", var.vq_ranges);
             o.f("    a.b%zu_qcnt[(u64)blockIdx.x * %du + q] = (i64)v%zu_qn[q] < a.b%zu_qcap ? v%zu_qn[q] : (u32)a.b%zu_qcap;\n", b, var.vq_ranges, b, b, b, b);
+            o.f("  for (int q = threadIdx.x; q < W_VQ_OVERFLOW; q += W_BLOCK)\n    if (v%zu_ot[q] != W_VQ_NONE) w_atomic<%d>(a.b%zu_out + v%zu_ot[q], v%zu_ov[q], 1);\n", b, s.func, b, b, b);
         } else if (var.backend[b] == BK_VECM_LDS) {
             // cells this work-group never touched still hold the identity: nothing to send
             const char* A = acc_ctype(s.val_type[0]);

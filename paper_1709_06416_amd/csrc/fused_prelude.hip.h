@@ -539,6 +539,35 @@ template <int F> __device__ __forceinline__ void w_atomic_i64(i64* p, i64 v, con
 template <int F> __device__ __forceinline__ void w_atomic(double* p, double v, const int agent) { w_atomic_f64<F>(p, v, agent); }
 template <int F> __device__ __forceinline__ void w_atomic(i64* p, i64 v, const int agent) { w_atomic_i64<F>(p, v, agent); }
 
+// A merge of a queued vecmerger that found its segment full (skewed indices: a hot cell fills its range's segment
+// many times over).  Straight to the result it would be one device atomic per merge on the hot cell's address,
+// about 12 ns each and serialised; instead the work-group combines such merges in a small directly mapped LDS
+// table (tag = the cell's index, W_VQ_NONE where free; the values start at the identity) and sends every
+// occupied entry to the result once, at its end.  An index that finds four entries in a row taken by others goes
+// straight to the result (with one entry to try, a cell with 2 % of all merges lost its entry to a neighbour of
+// its range in one work-group in nine, and those work-groups' device atomics on its address tripled the time).
+#define W_VQ_OVERFLOW 1024
+#define W_VQ_NONE 0xffffffffu
+template <int F, class T>
+__device__ __forceinline__ void w_vecm_overflow(u32* tags, T* vals, u32 ix, T v, T* out) {
+    const u32 home = (ix * 0x9e3779b1u) >> 22;
+#pragma unroll 1
+    for (u32 probe = 0; probe < 4; ++probe) {
+        const u32 h = (home + probe) & (W_VQ_OVERFLOW - 1);
+        u32 cur = __hip_atomic_load(tags + h, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (cur == W_VQ_NONE) {
+            u32 expect = W_VQ_NONE;
+            cur = __hip_atomic_compare_exchange_strong(tags + h, &expect, ix, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_WORKGROUP) ? ix : expect;
+        }
+        if (cur == ix) {
+            w_atomic<F>(vals + h, v, 0);
+            return;
+        }
+    }
+    w_atomic<F>(out + ix, v, 1);
+}
+
 // ---------------------------------------------------------------- division by a constant
 // x / D and x % D for a 64-bit x and a compile-time D in [2, 2^31): the compiler turns them
 // into a 64 x 64 -> 128-bit multiplication (ten quarter-rate 32-bit multiplications with the
