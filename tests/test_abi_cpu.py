@@ -137,7 +137,9 @@ def test_planner_chooses_the_vecmerger_strategy_by_length(wb):
     assert "v0_qn[128]" in count(32768) and "v0_qn[64]" in count(16384, second=True) and "range_lo" not in count(16384, second=True)
     src = count(1 << 20)
     assert "__shared__ u32 v0_qn[256]" in src and "(u64)ix >> 12" in src and "w_gstore_u16((unsigned short*)a.b0_log + at, (unsigned short)((u32)ix & 4095u))" in src
-    assert "else w_atomic<0>(a.b0_out + ix" in src                      # a full segment: straight to the result (rows of the last, partial tile)
+    # a full segment: combined in the work-group's LDS table, which goes to the result at the end
+    assert "else w_vecm_overflow<0>(v0_ot, v0_ov, (u32)ix, (i64)(o).v0_0, a.b0_out)" in src
+    assert "if (v0_ot[q] != W_VQ_NONE) w_atomic<0>(a.b0_out + v0_ot[q], v0_ov[q], 1);" in src
     assert "WELD_MERGE_TILE(o, vq_e[u * W_V + k], vq_v[u * W_V + k]);" in src and "__shared__ u32 v0_st[W_TILE];" in src and "u32 c[1], mine = 0;" in src
     assert "WELD_MERGE_TILE" not in count(1 << 20, tune={"vecmerger_strategy": 6})
     assert "v0_qn[132]" in count(65 * 1024 + 1024) and "(u64)ix >> 9" in count(65 * 1024 + 1024)
