@@ -1016,6 +1016,22 @@ def test_vecmerger_queued_by_range_of_cells(wb, func, t):
                tune={"vecmerger_strategy": 5})
 
 
+@pytest.mark.parametrize("n", [0, 1, 63, 5_000, 16_384, 16_385])
+def test_vecmerger_queued_with_few_rows(wb, n):
+    """No row at all, fewer rows than one tile (every merge then takes the one-row-per-thread path behind the tiles),
+    exactly one tile, one tile and a row."""
+    rnd = np.random.RandomState(n + 1)
+    m = 100_000
+    keys = rnd.randint(0, m, size=n).astype(np.int64)
+    init = rnd.randint(-5, 5, size=m).astype(np.int64)
+    p = Program(["i64"])
+    p.merge(p.vecmerger("i64", "add", m), [p.const("i64", 3)], keys=[p.col(0)])
+    _check(wb, p, [_dev(keys)], label="queued vecmerger, %d rows" % n, inits={0: _dev(init)}, tune={"vecmerger_strategy": 5})
+    v = Program(["i64"])
+    v.merge(v.vecmerger("i64", "min", m), [v.col(0)], keys=[v.col(0)])
+    _check(wb, v, [_dev(keys)], label="queued vecmerger with values, %d rows" % n, inits={0: _dev(init)}, tune={"vecmerger_strategy": 5})
+
+
 def test_vecmerger_queues_under_a_memory_limit(wb):
     """A memory limit shrinks the queues' segments (down to nothing): the merges that find no room go to the result
     with device atomics; the counts are the same."""
