@@ -177,7 +177,7 @@ typedef struct {
                                    copy in LDS updated with LDS atomics, 3 global atomics only,
                                    4 LDS copies of 8192-cell ranges, each range scanning all rows,
                                    5 merges queued by range of cells in device memory (workspace: 2 bytes
-                                   per row where the merged value is a constant, else 16) and merged range by
+                                   per row where the merged value is a constant, else 10) and merged range by
                                    range in LDS by a second kernel (lengths from 8193 to 2^26; one vecmerger
                                    per loop, the others then use 3; a segment that is full sends its merges
                                    to the result with device atomics; up to 2^25 cells (2^24 where entries

@@ -104,8 +104,9 @@ hipError_t launch_group_scatter(const GroupScatter& g, int blocks, hipStream_t s
 hipError_t launch_group_partition(const GroupScatter& g, int blocks, hipStream_t stream);
 hipError_t launch_group_place(const GroupScatter& g, int blocks, hipStream_t stream);
 // A vecmerger whose merges the loop kernel queued by range of 2^shift cells (spill_kernels.hip): work-group g of the
-// loop kernel appended to segment [g][range] of `log` (cap entries of entry_bytes: 2 = the cell within its range, the
-// merged value being the constant const_bits; 16 = cell within the range, value bits) and stored the segment lengths
+// loop kernel appended to segment [g][range] of `log` (cap entries, a multiple of 8, of entry_bytes: 2 = the cell within
+// its range, the merged value being the constant const_bits; 10 = a segment is cap values of 8 bytes followed by cap
+// cells of 2 bytes) and stored the segment lengths
 // in qcnt[g * ranges + range].  One work-group per range merges the range's entries in LDS and combines the cells
 // that were touched into out[range << shift ...] (it owns them: plain loads and stores).
 struct VecmRanges {

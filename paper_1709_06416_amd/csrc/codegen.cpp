@@ -422,7 +422,7 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
             const bool alone = L.builders.size() == 1;
             if (strat == 4 && (!alone || s.length > 8192 * 64)) strat = 0;
             // Beyond that a fifth: every merge is appended to a queue by range of cells (segment [work-group][range],
-            // 2 bytes an entry where the merged value is a constant, else 16), and a second kernel merges each
+            // 2 bytes an entry where the merged value is a constant, else 10), and a second kernel merges each
             // range in LDS and adds it to the result - two streaming passes instead of one device atomic per row.
             // One such vecmerger per loop; up to 8192 ranges of 8192 cells.
             const bool can_queue = queues_allowed && var.vq_builder < 0 && m >= 0 && s.length > 8192 && s.length <= (int64_t)8192 * 8192 && tune.dict_spill >= 0;
@@ -881,10 +881,14 @@ Generated generate(const Loop& L, const Variant& var) {
             o.f("      const u32 pos = __hip_atomic_fetch_add(v%zu_qn + part, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); \\\n", b);
             o.f("      if ((i64)pos < a.b%zu_qcap) { \\\n", b);
             o.f("        const u64 at = ((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap + pos; \\\n", var.vq_ranges, b);
-            if (var.vq_const)
+            if (var.vq_const) {
                 o.f("        w_gstore_u16((unsigned short*)a.b%zu_log + at, (unsigned short)((u32)ix & %du)); \\\n", b, (1u << var.vq_shift) - 1);
-            else
-                o.f("        w_gstore2(a.b%zu_log + 2 * at, (u64)((u32)ix & %du), w_bits((%s)(o).v%zu_0)); \\\n", b, (1u << var.vq_shift) - 1, A, b);
+            } else {
+                // (a segment of entries with values: its values, 8 bytes each, then its cells within the range, 2 bytes each)
+                o.f("        char* const sg = (char*)a.b%zu_log + (at - pos) * 10; \\\n", b);
+                o.f("        w_gstore1((u64*)sg + pos, w_bits((%s)(o).v%zu_0)); \\\n", A, b);
+                o.f("        w_gstore_u16((unsigned short*)(sg + 8 * a.b%zu_qcap) + pos, (unsigned short)((u32)ix & %du)); \\\n", b, (1u << var.vq_shift) - 1);
+            }
             o.f("      } else w_vecm_overflow<%d>(v%zu_ot, v%zu_ov, (u32)ix, (%s)(o).v%zu_0, a.b%zu_out); \\\n", F, b, b, A, b, b);
             o.f("    } else atomicOr(errp, 4); \\\n  } \\\n");
         } else if (var.backend[b] == BK_VECM_REG || var.backend[b] == BK_VECM_LDS || var.backend[b] == BK_VECM_GLOBAL) {
@@ -1217,7 +1221,8 @@ Generated generate(const Loop& L, const Variant& var) {
                 o.f("        if ((i64)pos < a.b%zu_qcap) w_gstore_u16((unsigned short*)a.b%zu_log + ((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap + pos, (unsigned short)(e & %du));\n", b, b, R, b, (1u << var.vq_shift) - 1);
                 o.f("        else w_vecm_overflow<%d>(v%zu_ot, v%zu_ov, e, %s, a.b%zu_out);\n      }\n    }\n", s.func, b, b, cv.c_str(), b);
             } else {
-                o.f("        if ((i64)pos < a.b%zu_qcap) w_gstore2(a.b%zu_log + 2 * (((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap + pos), (u64)(e & %du), v%zu_sv[i]);\n", b, b, R, b, (1u << var.vq_shift) - 1, b);
+                o.f("        if ((i64)pos < a.b%zu_qcap) {\n          char* const sg = (char*)a.b%zu_log + ((u64)blockIdx.x * %du + part) * (u64)a.b%zu_qcap * 10;\n", b, b, R, b);
+                o.f("          w_gstore1((u64*)sg + pos, v%zu_sv[i]);\n          w_gstore_u16((unsigned short*)(sg + 8 * a.b%zu_qcap) + pos, (unsigned short)(e & %du));\n        }\n", b, b, (1u << var.vq_shift) - 1);
                 o.f("        else w_vecm_overflow<%d>(v%zu_ot, v%zu_ov, e, w_from_bits<%s>(v%zu_sv[i]), a.b%zu_out);\n      }\n    }\n", s.func, b, b, acc_ctype(s.val_type[0]), b, b);
             }
         }

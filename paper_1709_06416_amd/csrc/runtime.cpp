@@ -545,7 +545,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
     // sends its merges to the result with device atomics, so a memory limit may shrink them too
     if (var.vq_builder >= 0) {
         const size_t b = (size_t)var.vq_builder;
-        const size_t entry = var.vq_const ? 2 : 16;
+        const size_t entry = var.vq_const ? 2 : 10;
         off[b].qcnt = lay.take(4 * (size_t)grid * var.vq_ranges);
         const double rows = (double)((ntiles + grid - 1) / grid) * (double)tile;
         const double mean = rows / var.vq_ranges;
@@ -802,7 +802,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         vr.func = s.func;
         vr.is_f64 = s.val_type[0] == WELD_F64;
         vr.ident = ident_bits(s.func, s.val_type[0]);
-        vr.entry_bytes = var.vq_const ? 2 : 16;
+        vr.entry_bytes = var.vq_const ? 2 : 10;
         if (var.vq_const) {
             const weld_op_t& c = L.ops[L.merges[L.merge_of[b]].val[0]];
             if (s.val_type[0] == WELD_F64) memcpy(&vr.const_bits, &c.imm.f64, 8);

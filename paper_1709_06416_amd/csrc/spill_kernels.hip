@@ -644,15 +644,18 @@ __global__ void __launch_bounds__(1024) vecm_ranges_kernel(const VecmRanges a) {
                     if (i0 + k * 64 + lane < len && c[k] < (u32)cells) cell_combine<FUNC>(s_cell + c[k], a.const_bits, a.is_f64, 0);
             }
         } else {
-            const u64* e = (const u64*)a.log + 2 * seg;
+            // (a segment's values, 8 bytes each, then its cells, 2 bytes each: cap is a multiple of 8)
+            const char* sg = (const char*)a.log + seg * 10;
+            const u64* ev = (const u64*)sg;
+            const unsigned short* ec = (const unsigned short*)(sg + 8 * a.cap);
             for (i64 i0 = 0; i0 < len; i0 += 512) {
                 u64 c[8], v[8];
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
                     const i64 i = i0 + k * 64 + lane;
                     const i64 ic = i < len ? i : len - 1;
-                    c[k] = __builtin_nontemporal_load(e + 2 * ic);
-                    v[k] = __builtin_nontemporal_load(e + 2 * ic + 1);
+                    c[k] = (u64)__builtin_nontemporal_load(ec + ic);
+                    v[k] = __builtin_nontemporal_load(ev + ic);
                 }
 #pragma unroll
                 for (int k = 0; k < 8; ++k)
@@ -686,12 +689,12 @@ static hipError_t launch_vecm_func(const VecmRanges& v, hipStream_t stream, hipE
     if (v.entry_bytes == 2)
         hipExtLaunchKernelGGL((vecm_ranges_kernel<FUNC, 2>), dim3((unsigned)v.ranges), dim3(1024), 0, stream, nullptr, stop, 0, v);
     else
-        hipExtLaunchKernelGGL((vecm_ranges_kernel<FUNC, 16>), dim3((unsigned)v.ranges), dim3(1024), 0, stream, nullptr, stop, 0, v);
+        hipExtLaunchKernelGGL((vecm_ranges_kernel<FUNC, 10>), dim3((unsigned)v.ranges), dim3(1024), 0, stream, nullptr, stop, 0, v);
     return hipGetLastError();
 }
 hipError_t launch_vecm_ranges(const VecmRanges& v, hipStream_t stream, hipEvent_t stop) {
     if (v.ranges < 1 || v.shift < 0 || v.shift > 13 || v.groups < 1 || v.groups > 2048 || v.cap < 0 ||
-        (v.entry_bytes != 2 && v.entry_bytes != 16) || ((long long)v.ranges << v.shift) < v.length)
+        (v.entry_bytes != 2 && v.entry_bytes != 10) || (v.cap & 7) || ((long long)v.ranges << v.shift) < v.length)
         return hipErrorInvalidValue;
     switch (v.func) {
         case 0: return launch_vecm_func<0>(v, stream, stop);

@@ -191,8 +191,8 @@ struct Variant {
                                 // status (no fill kernel before the loop kernel, no combining kernel behind it)
     int vq_builder = -1;        // vecmerger whose merges are queued by range of 2^vq_shift cells (vq_ranges ranges): segment
     int vq_shift = 13;          // [work-group][range] of a log in global memory, entries of 2 bytes (the cell within its
-    int vq_ranges = 0;          // range; vq_const: the merged value is a constant the second kernel is told) or 16 bytes
-    bool vq_const = false;      // (cell within the range, value bits)
+    int vq_ranges = 0;          // range; vq_const: the merged value is a constant the second kernel is told) or 10 bytes
+    bool vq_const = false;      // (a segment's values, 8 bytes each, then its cells within the range, 2 bytes each)
     bool vq_sorted = false;     // a tile's entries are sorted by range in LDS and leave as runs
     std::vector<int> backend;   // per builder
 };

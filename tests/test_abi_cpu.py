@@ -141,7 +141,8 @@ def test_planner_chooses_the_vecmerger_strategy_by_length(wb):
     assert "else w_vecm_overflow<0>(v0_ot, v0_ov, (u32)ix, (i64)(o).v0_0, a.b0_out)" in src
     assert "if (v0_ot[q] != W_VQ_NONE) w_atomic<0>(a.b0_out + v0_ot[q], v0_ov[q], 1);" in src
     assert "WELD_MERGE_TILE(o, vq_e[u * W_V + k], vq_v[u * W_V + k]);" in src and "__shared__ u32 v0_st[W_TILE];" in src and "u32 c[1], mine = 0;" in src
-    assert "WELD_MERGE_TILE" not in count(1 << 20, tune={"vecmerger_strategy": 6})
+    unsorted = count(1 << 20, tune={"vecmerger_strategy": 6})
+    assert "WELD_MERGE_TILE" not in unsorted and "w_gstore_u16((unsigned short*)a.b0_log + at" in unsorted and "sg" not in unsorted
     assert "v0_qn[132]" in count(65 * 1024 + 1024) and "(u64)ix >> 9" in count(65 * 1024 + 1024)
     big = count(1 << 24)
     assert "v0_qn[2048]" in big and "WELD_MERGE_TILE" in big and "u32 c[2], mine = 0;" in big
@@ -155,8 +156,9 @@ def test_planner_chooses_the_vecmerger_strategy_by_length(wb):
         assert "v0_qn" not in off and "w_atomic<0>(a.b0_out + ix" in off
     valued = Program(["i64", "f64"])
     valued.merge(valued.vecmerger("f64", "max", 100_000), [valued.col(1)], keys=[valued.col(0)])
-    vsrc = wb.generated_source(valued)          # (entries with a value: 16 bytes, sorted in tiles of 8192 rows)
-    assert "w_gstore2(a.b0_log + 2 * at, (u64)((u32)ix & 511u), w_bits((double)(o).v0_0))" in vsrc
+    vsrc = wb.generated_source(valued)          # (entries with a value: 8 + 2 bytes in two arrays per segment, sorted in tiles of 8192 rows)
+    assert "w_gstore1((u64*)sg + pos, w_bits((double)(o).v0_0));" in vsrc
+    assert "w_gstore_u16((unsigned short*)(sg + 8 * a.b0_qcap) + pos, (unsigned short)((u32)ix & 511u));" in vsrc
     assert "__shared__ u64 v0_sv[W_TILE];" in vsrc and "#define W_U 4" in vsrc and "#define W_V 2" in vsrc
 
 

@@ -984,7 +984,7 @@ def test_vecmerger_index_out_of_range_is_reported(wb):
 @pytest.mark.parametrize("t", ["i64", "f64"])
 def test_vecmerger_queued_by_range_of_cells(wb, func, t):
     """Vectors beyond what one LDS copy holds: the merges are queued by range of cells and a second kernel merges
-    every range in LDS.  Values from a column (16-byte entries) and constants (2-byte entries), an initial
+    every range in LDS.  Values from a column (10-byte entries) and constants (2-byte entries), an initial
     vector, a predicate, a second builder beside it, lengths that end inside a range and inside a tile of ranges,
     and indices so skewed that segments fill up and the rest of their merges goes to the result directly."""
     rnd = np.random.RandomState(len(func) + len(t))
