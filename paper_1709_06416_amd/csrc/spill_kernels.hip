@@ -639,9 +639,34 @@ __global__ void __launch_bounds__(1024) vecm_ranges_kernel(const VecmRanges a) {
                     const i64 i = i0 + k * 64 + lane;
                     c[k] = (u32)__builtin_nontemporal_load(e + (i < len ? i : len - 1));
                 }
+                if (len < a.cap || !((FUNC == 0 && !a.is_f64) || FUNC == 2 || FUNC == 3)) {
 #pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    if (i0 + k * 64 + lane < len && c[k] < (u32)cells) cell_combine<FUNC>(s_cell + c[k], a.const_bits, a.is_f64, 0);
+                    for (int k = 0; k < 8; ++k)
+                        if (i0 + k * 64 + lane < len && c[k] < (u32)cells) cell_combine<FUNC>(s_cell + c[k], a.const_bits, a.is_f64, 0);
+                    continue;
+                }
+                // A segment that is full: a hot cell.  Most lanes of a load then hold the same cell, and 64 LDS atomics
+                // on one address run one after the other; the lanes that hold the first valid lane's cell merge as one
+                // where that gives the same bits (integer sums: the constant times their number; minima and maxima:
+                // the constant once).  Segments with room keep the plain form: the ballots cost a quarter of the
+                // kernel's time on uniform indices.
+                const bool as_one = true;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const bool valid = i0 + k * 64 + lane < len && c[k] < (u32)cells;
+                    const u64 vm = __builtin_amdgcn_ballot_w64(valid);
+                    if (vm == 0) continue;
+                    const int leader = (int)__builtin_ctzll(vm);
+                    const u32 lead = (u32)__shfl((int)c[k], leader, 64);
+                    const bool same = as_one && valid && c[k] == lead;
+                    const u64 sm = __builtin_amdgcn_ballot_w64(same);
+                    if (same) {
+                        if (lane == leader)
+                            cell_combine<FUNC>(s_cell + lead, FUNC == 0 ? a.const_bits * (u64)__popcll(sm) : a.const_bits, a.is_f64, 0);
+                    } else if (valid) {
+                        cell_combine<FUNC>(s_cell + c[k], a.const_bits, a.is_f64, 0);
+                    }
+                }
             }
         } else {
             // (a segment's values, 8 bytes each, then its cells, 2 bytes each: cap is a multiple of 8)
