@@ -1443,10 +1443,30 @@ Generated generate(const Loop& L, const Variant& var) {
                 o.f("        const i64 i = r0 + u * W_UNIT + k;\n        if (i < a.n) a.b%zu_out[i] = o[u][k].v%zu_0;\n      }\n", b, b);
             }
         o.s += gather_text.s;
+        // Compacting builders under the same predicate select the same rows (the columns of a filtered table, the
+        // keys and values of a groupbuilder): the first of them counts, publishes and looks back for all, the others
+        // take its counts and its prefix.  cj[b]: the slot of s_cnt / s_pfx builder b reads.
+        std::vector<int> cj(NB, -1);
+        std::vector<bool> leads(NB, false);
+        {
+            int slot_no = 0;
+            for (size_t b = 0; b < NB; ++b) {
+                if (var.backend[b] != BK_VEC_COMPACT) continue;
+                for (size_t q = 0; q < b; ++q)
+                    if (var.backend[q] == BK_VEC_COMPACT && leads[q] && L.merges[L.merge_of[q]].pred == L.merges[L.merge_of[b]].pred) { cj[b] = cj[q]; break; }
+                if (cj[b] < 0) { cj[b] = slot_no; leads[b] = true; }
+                ++slot_no;
+            }
+        }
+        auto followers_len = [&](Out& d, size_t b, const char* indent, const char* cond) {
+            for (size_t q = b + 1; q < NB; ++q)
+                if (var.backend[q] == BK_VEC_COMPACT && !leads[q] && cj[q] == cj[b]) d.f("%s  if (%s) *a.b%zu_len = ex + tot;\n", indent, cond, q);
+        };
         // ranks of the selected rows inside this wavefront's run, per compacting builder
         int j = 0;
         for (size_t b = 0; b < NB; ++b) {
             if (var.backend[b] != BK_VEC_COMPACT) continue;
+            if (!leads[b]) { ++j; continue; }
             // per load unit: how many rows the wavefront selected and where its run starts; the rank
             // of a row inside the run is recomputed when the values are staged (a few instructions,
             // cheaper than holding sixteen ranks per lane through the merge phase)
@@ -1468,12 +1488,15 @@ Generated generate(const Loop& L, const Variant& var) {
         j = 0;
         for (size_t b = 0; b < NB; ++b) {
             if (var.backend[b] != BK_VEC_COMPACT) continue;
+            if (!leads[b]) { ++j; continue; }
             o.f("      {\n        i64 tot = 0;\n        _Pragma(\"unroll\") for (int w = 0; w < W_WAVES; ++w) tot += s_cnt[%d]%s[w];\n", j, cb.c_str());
             if (var.pipeline) {
                 o.f("        w_lookback_publish(a.b%zu_desc, t, tot);\n      }\n", b);
             } else {
                 o.f("        const i64 ex = w_lookback(a.b%zu_desc, t, tot, a.spin_limit, errp);\n", b);
-                o.f("        if (lane == 0) {\n          s_pfx[%d] = ex;\n          if (t == ntiles - 1) *a.b%zu_len = ex + tot;\n        }\n      }\n", j, b);
+                o.f("        if (lane == 0) {\n          s_pfx[%d] = ex;\n          if (t == ntiles - 1) *a.b%zu_len = ex + tot;\n", j, b);
+                followers_len(o, b, "        ", "t == ntiles - 1");
+                o.f("        }\n      }\n");
             }
             ++j;
         }
@@ -1485,9 +1508,13 @@ Generated generate(const Loop& L, const Variant& var) {
             int jj = 0;
             for (size_t b = 0; b < NB; ++b) {
                 if (var.backend[b] != BK_VEC_COMPACT) continue;
+                if (!leads[b]) { ++jj; continue; }
                 d.f("      {\n        i64 tot = 0;\n        _Pragma(\"unroll\") for (int w = 0; w < W_WAVES; ++w) tot += s_cnt[%d]%s[w];\n", jj, cslot.c_str());
                 d.f("        const i64 ex = w_lookback_resolve(a.b%zu_desc, %s, tot, a.spin_limit, errp);\n", b, tile);
-                d.f("        if (lane == 0) {\n          s_pfx[%d]%s = ex;\n          if (%s == ntiles - 1) *a.b%zu_len = ex + tot;\n        }\n      }\n", jj, pslot.c_str(), tile, b);
+                d.f("        if (lane == 0) {\n          s_pfx[%d]%s = ex;\n          if (%s == ntiles - 1) *a.b%zu_len = ex + tot;\n", jj, pslot.c_str(), tile, b);
+                const std::string last = std::string(tile) + " == ntiles - 1";
+                followers_len(d, b, "        ", last.c_str());
+                d.f("        }\n      }\n");
                 ++jj;
             }
             d.f("    }\n");
@@ -1499,7 +1526,7 @@ Generated generate(const Loop& L, const Variant& var) {
             int jj = 0;
             for (size_t b = 0; b < NB; ++b) {
                 if (var.backend[b] != BK_VEC_COMPACT) continue;
-                d.f("    {\n      i64 base = s_pfx[%d]%s;\n      for (int w = 0; w < wave; ++w) base += s_cnt[%d]%s[w];\n", jj, pslot.c_str(), jj, cslot.c_str());
+                d.f("    {\n      i64 base = s_pfx[%d]%s;\n      for (int w = 0; w < wave; ++w) base += s_cnt[%d]%s[w];\n", cj[b], pslot.c_str(), cj[b], cslot.c_str());
                 // The selected values of one load unit are packed in LDS at their ranks and written
                 // out as one dense run per instruction (lane l writes elements l, l+64, ...), so HBM
                 // sees full lines instead of scattered 8-byte pieces.

@@ -162,6 +162,23 @@ def test_planner_chooses_the_vecmerger_strategy_by_length(wb):
     assert "__shared__ u64 v0_sv[W_TILE];" in vsrc and "#define W_U 4" in vsrc and "#define W_V 2" in vsrc
 
 
+def test_vecbuilders_under_one_predicate_share_the_look_back(wb):
+    """Four compacting vecbuilders, three of them under the same predicate: two look-backs a tile, the first builder
+    of a predicate writes the lengths of all, each builder stores at the prefix of its predicate's first."""
+    p = Program(["i64", "f64", "i32"])
+    pred = p.bin("gt", p.col(0), p.const("i64", 0))
+    p.merge(p.vecbuilder("i64"), p.col(0), pred=pred)
+    p.merge(p.vecbuilder("f64"), p.col(1), pred=pred)
+    p.merge(p.vecbuilder("i32"), p.col(2), pred=p.bin("lt", p.col(2), p.const("i32", 5)))
+    p.merge(p.vecbuilder("i32"), p.col(2), pred=pred)
+    src = wb.generated_source(p)
+    body = src[src.index('extern "C" __global__'):]
+    assert body.count("w_lookback(") == 2 and "w_lookback(a.b0_desc" in body and "w_lookback(a.b2_desc" in body
+    for b in (0, 1, 2, 3):
+        assert body.count("*a.b%d_len = ex + tot;" % b) == 1
+    assert body.count("i64 base = s_pfx[0];") == 3 and body.count("i64 base = s_pfx[2];") == 1
+
+
 def test_planner_overlaps_tiles_only_where_the_registers_allow(wb):
     """Host logic only: which compacting loops load the next tile's columns ahead, read off the generated text."""
     c5 = wb.generated_source(configs.program_c5())
