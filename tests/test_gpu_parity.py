@@ -218,6 +218,31 @@ def test_two_compactions_with_different_predicates(wb):
     _check(wb, p, cols, label="two compactions")
 
 
+@pytest.mark.parametrize("n", [0, 1, 16_383, 50_003, 700_001])
+@pytest.mark.parametrize("with_dict", [False, True])
+def test_filtered_table_columns_share_their_predicate(wb, n, with_dict):
+    """The columns of a filtered table: several vecbuilders under ONE predicate (one count and one look-back per
+    tile serves them all), one under another predicate in between, with and without an LDS dictionary in the loop
+    (the overlapped tile loop).  Every vector has its own length word."""
+    cols = configs.make_columns("C3", n, device="cuda")
+    p = Program(["i32", "f64", "f64", "f64"])
+    day, disc, qty, price = p.col(0), p.col(1), p.col(2), p.col(3)
+    keep = p.bin("and", p.bin("lt", day, p.const("i32", 1200)), p.bin("ge", qty, p.const("f64", 10.0)))
+    other = p.bin("ge", disc, p.const("f64", 0.05))
+    p.merge(p.vecbuilder("i32"), day, pred=keep)
+    p.merge(p.vecbuilder("f64"), p.bin("mul", price, disc), pred=keep)
+    p.merge(p.vecbuilder("f64"), qty, pred=other)
+    p.merge(p.vecbuilder("i64"), p.index(), pred=keep)
+    if with_dict:
+        p.merge(p.dictmerger(["i64"], ["i64"], "add", 50_000), [p.const("i64", 1)],
+                keys=[p.bin("mod", p.un("cast", p.bin("mul", price, p.const("f64", 7.0)), to="i64"), p.const("i64", 40_000))], pred=keep)
+    res = _run(wb, p, cols).check()
+    lens = [len(res.vec_host(b)) for b in (0, 1, 2, 3)]
+    res.free()
+    assert lens[0] == lens[1] == lens[3]
+    _check(wb, p, cols, label="filtered table, %d rows" % n)
+
+
 # ----------------------------------------------------------------------
 # mergers
 # ----------------------------------------------------------------------
