@@ -718,6 +718,8 @@ __global__ void __launch_bounds__(1024) group_partition_kernel(const GroupScatte
             kb[j] = nkb[j];
             val[j] = nval[j];
         }
+        // (the next tile's loads before this tile's look-ups, although the look-ups' answers then queue behind them:
+        // with the look-ups first the kernel took 0.85 ms instead of 0.75)
         if (t + gridDim.x < ntiles) load_tile(t + gridDim.x);
         groups_of_keys(a, narrow, s_ck, s_cg, kb, live, gid);
 #pragma unroll
