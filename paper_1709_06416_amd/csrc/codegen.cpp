@@ -414,11 +414,12 @@ Variant choose_variant(const Loop& L, const weld_tuning_t& tune, bool aligned) {
             // measured with 1e8 uniform keys: LDS copy 0.09-0.12 ms up to 8192 cells; register copies
             // 0.24 ms at 8 cells (kept for f64, whose LDS atomics serialise on few addresses);
             // global copy 4.2 ms (23.7 G atomics/s) for large vectors, 13-390 ms below 1024 cells
-            // Between 8192 cells and about 3e5 a fourth strategy wins on this part: the cells are
-            // split into 8192-cell ranges, each owned by a group of work-groups that scans ALL rows
-            // and merges only its range in LDS.  Reading the keys R times at 6+ TB/s (0.09 ms a pass)
-            // beats one pass of global atomics (4.2 ms) up to R ~ 40.  Only for loops whose single
-            // builder is this vecmerger: everything else would be repeated R times too.
+            // A fourth strategy: the cells are split into 8192-cell ranges, each owned by a group of
+            // work-groups that scans ALL rows and merges only its range in LDS.  Reading the keys R times
+            // at 6+ TB/s (0.09 ms a pass) beats one pass of global atomics (4.2 ms) up to R ~ 40, but the
+            // queues of the fifth strategy below only for two ranges (16384 cells: 0.24 ms against 0.44;
+            // 32768 cells: 0.43 against 0.36).  Only for loops whose single builder is this vecmerger:
+            // everything else would be repeated R times too.
             const bool alone = L.builders.size() == 1;
             if (strat == 4 && (!alone || s.length > 8192 * 64)) strat = 0;
             // Beyond that a fifth: every merge is appended to a queue by range of cells (segment [work-group][range],
