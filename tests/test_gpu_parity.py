@@ -1057,6 +1057,25 @@ def test_vecmerger_queued_with_few_rows(wb, n):
     _check(wb, v, [_dev(keys)], label="queued vecmerger with values, %d rows" % n, inits={0: _dev(init)}, tune={"vecmerger_strategy": 5})
 
 
+def test_two_large_vecmergers_in_one_loop(wb):
+    """One vecmerger per loop is queued by range, the other merges with device atomics; a merger and a filtered
+    vector share the loop."""
+    rnd = np.random.RandomState(77)
+    n = 300_017
+    a = rnd.randint(0, 50_000, size=n).astype(np.int64)
+    b = rnd.randint(0, 90_000, size=n).astype(np.int64)
+    w = rnd.randint(-9, 9, size=n).astype(np.int64)
+    p = Program(["i64", "i64", "i64"])
+    pred = p.bin("ne", p.col(2), p.const("i64", 0))
+    p.merge(p.vecmerger("i64", "add", 50_000), [p.col(2)], keys=[p.col(0)], pred=pred)
+    p.merge(p.vecmerger("i64", "max", 90_000), [p.col(2)], keys=[p.col(1)])
+    p.merge(p.merger("i64", "add"), p.col(2))
+    p.merge(p.vecbuilder("i64"), p.col(1), pred=pred)
+    _check(wb, p, [_dev(a), _dev(b), _dev(w)], label="two large vecmergers")
+    src = wb.generated_source(p)
+    assert "v0_qn" in src and "v1_qn" not in src and "w_atomic<3>(a.b1_out + ix" in src
+
+
 def test_vecmerger_queues_under_a_memory_limit(wb):
     """A memory limit shrinks the queues' segments (down to nothing): the merges that find no room go to the result
     with device atomics; the counts are the same."""
