@@ -121,6 +121,7 @@ struct VecmRanges {
     int is_f64;
     unsigned long long ident;
     int entry_bytes;
+    int long_segments;         // 2-byte entries: segments of about a thousand entries and more are expected (read with 16-byte loads)
     unsigned long long const_bits;
     unsigned long long* out;
 };

@@ -803,6 +803,7 @@ static Error run_fused_plain(const Loop& L, const std::vector<GroupLink>& links,
         vr.is_f64 = s.val_type[0] == WELD_F64;
         vr.ident = ident_bits(s.func, s.val_type[0]);
         vr.entry_bytes = var.vq_const ? 2 : 10;
+        vr.long_segments = (double)n / ((double)grid * var.vq_ranges) >= 1024.0 ? 1 : 0;
         if (var.vq_const) {
             const weld_op_t& c = L.ops[L.merges[L.merge_of[b]].val[0]];
             if (s.val_type[0] == WELD_F64) memcpy(&vr.const_bits, &c.imm.f64, 8);
